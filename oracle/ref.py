@@ -1,0 +1,179 @@
+"""ctypes front end of the CPU oracle (``hbfp_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+``cpu_baseline`` leg of the benchmark.  Nothing here is used by the GPU library
+and nothing here uses it.
+
+All arrays are plain numpy, host memory, in the *source* orientation of the
+paper's notation: a tensor ``a`` with mantissas ``m_i`` and one exponent per
+block (Eq. (1), Sec. 4), a product ``C = A B`` with ``A`` of shape [M, K] and
+``B`` of shape [K, N] (Eq. (2), Sec. 4).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hbfp_oracle.c")
+_LIB = os.path.join(_HERE, "libhbfp_oracle.so")
+
+RNE = 0
+STOCHASTIC = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, i32, u64 = ctypes.c_int64, ctypes.c_int, ctypes.c_uint64
+        p = ctypes.c_void_p
+        lib.hbfp_ref_hash32.restype = ctypes.c_uint32
+        lib.hbfp_ref_hash32.argtypes = [u64, u64]
+        lib.hbfp_ref_num_threads.restype = i32
+        lib.hbfp_ref_encode.argtypes = [p, i64, i64, i64, i64, i64, i32, i32, u64, p, p]
+        lib.hbfp_ref_decode.argtypes = [p, p, i64, i64, i64, i64, i32, p, i64]
+        lib.hbfp_ref_block_dots.argtypes = [p, p, i64, i64, i64, i64, p]
+        lib.hbfp_ref_gemm.argtypes = [p, i64, p, i64, i64, i64, i64, p]
+        lib.hbfp_ref_gemm_rows.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
+        lib.hbfp_ref_scale_accumulate.argtypes = [p, p, p, i64, i64, i64, i32, i32, p]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_L().hbfp_ref_num_threads())
+
+
+def hash32(seed: int, idx: int) -> int:
+    return int(_L().hbfp_ref_hash32(ctypes.c_uint64(seed), ctypes.c_uint64(idx)))
+
+
+@dataclass
+class BFP:
+    """A BFP tensor in source orientation: ``value = mant * 2**(exps - 125 - m)``."""
+
+    mant: np.ndarray  # int32 [rows, cols]
+    exps: np.ndarray  # uint8 [ceil(rows/br), ceil(cols/bc)]
+    m: int
+    br: int
+    bc: int
+
+    def unit_exponents(self) -> np.ndarray:
+        """Exponent of one mantissa unit, per element, int32 [rows, cols]."""
+        rows, cols = self.mant.shape
+        e = self.exps.astype(np.int32) - 125 - self.m
+        return np.repeat(np.repeat(e, self.br, axis=0)[:rows], self.bc, axis=1)[:, :cols]
+
+
+def _blk(n: int, b: int) -> int:
+    return n if (b <= 0 or b > n) else b
+
+
+def encode(x: np.ndarray, br: int, bc: int, m: int, rounding: int = RNE, seed: int = 0) -> BFP:
+    """FP32 [rows, cols] -> BFP with br x bc exponent blocks (0 = whole extent)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.ndim == 2
+    rows, cols = x.shape
+    br, bc = _blk(rows, br), _blk(cols, bc)
+    nbr, nbc = -(-rows // br), -(-cols // bc)
+    mant = np.empty((rows, cols), dtype=np.int32)
+    exps = np.empty((nbr, nbc), dtype=np.uint8)
+    rc = _L().hbfp_ref_encode(_ptr(x), rows, cols, cols, br, bc, m, rounding,
+                              ctypes.c_uint64(seed), _ptr(mant), _ptr(exps))
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_encode: {rc}")
+    return BFP(mant, exps, m, br, bc)
+
+
+def decode(t: BFP) -> np.ndarray:
+    rows, cols = t.mant.shape
+    out = np.empty((rows, cols), dtype=np.float32)
+    rc = _L().hbfp_ref_decode(_ptr(np.ascontiguousarray(t.mant)), _ptr(np.ascontiguousarray(t.exps)),
+                              rows, cols, t.br, t.bc, t.m, _ptr(out), cols)
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_decode: {rc}")
+    return out
+
+
+def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:
+    """Integer block partials P[i, j, b] of Eq. (2); mA [M, K], mB [K, N]."""
+    mA = np.ascontiguousarray(mA, dtype=np.int32)
+    mB = np.ascontiguousarray(mB, dtype=np.int32)
+    M, K = mA.shape
+    K2, N = mB.shape
+    assert K == K2
+    kb = _blk(K, kb)
+    nb = -(-K // kb)
+    P = np.empty((M, N, nb), dtype=np.int32)
+    rc = _L().hbfp_ref_block_dots(_ptr(mA), _ptr(mB), M, N, K, kb, _ptr(P))
+    if rc == -2:
+        raise OverflowError("a block partial does not fit int32")
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_block_dots: {rc}")
+    return P
+
+
+def gemm(A: np.ndarray, B: np.ndarray, rows=None) -> np.ndarray:
+    """FP64 product of FP32 operands, by definition; optionally only some rows of A."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    if rows is None:
+        C = np.empty((M, N), dtype=np.float64)
+        rc = _L().hbfp_ref_gemm(_ptr(A), K, _ptr(B), N, M, N, K, _ptr(C))
+    else:
+        sel = np.ascontiguousarray(rows, dtype=np.int64)
+        C = np.empty((sel.size, N), dtype=np.float64)
+        rc = _L().hbfp_ref_gemm_rows(_ptr(A), K, _ptr(B), N, M, N, K, _ptr(sel), sel.size, _ptr(C))
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_gemm: {rc}")
+    return C
+
+
+def scale_accumulate(P: np.ndarray, eA: np.ndarray, eB: np.ndarray, mA: int, mB: int) -> np.ndarray:
+    """C[i,j] = sum_b P[i,j,b] * 2^(unit exponent of A block + of B block), in FP64."""
+    P = np.ascontiguousarray(P, dtype=np.int32)
+    M, N, nb = P.shape
+    eA = np.ascontiguousarray(eA, dtype=np.uint8)
+    eB = np.ascontiguousarray(eB, dtype=np.uint8)
+    assert eA.shape == (M, nb) and eB.shape == (nb, N)
+    C = np.empty((M, N), dtype=np.float64)
+    rc = _L().hbfp_ref_scale_accumulate(_ptr(P), _ptr(eA), _ptr(eB), M, N, nb, mA, mB, _ptr(C))
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_scale_accumulate: {rc}")
+    return C
+
+
+def bfp_gemm(A: np.ndarray, B: np.ndarray, fmt_a: dict, fmt_b: dict, rows=None):
+    """The whole path by its definition: quantise A [M,K] and B [K,N], multiply in FP64.
+
+    ``fmt_a`` / ``fmt_b``: dicts with keys br, bc, m and optionally rounding, seed;
+    the block shapes are in each operand's own orientation.  Returns (C64, BFP(A), BFP(B)).
+    """
+    ta = encode(A, fmt_a["br"], fmt_a["bc"], fmt_a["m"], fmt_a.get("rounding", RNE), fmt_a.get("seed", 0))
+    tb = encode(B, fmt_b["br"], fmt_b["bc"], fmt_b["m"], fmt_b.get("rounding", RNE), fmt_b.get("seed", 0))
+    return gemm(decode(ta), decode(tb), rows=rows), ta, tb

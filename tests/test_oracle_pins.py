@@ -1,0 +1,378 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+Hand-worked examples (tests/golden), closed forms, invariants, special cases that
+reduce to library routines (numpy/torch casts, np.rint, integer matmul) and brute
+force on tiny inputs.  None of these needs a GPU.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+
+
+def _read_rows(path):
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield [p.strip() for p in line.split(";")]
+
+
+# ---------------------------------------------------------------- hand-worked examples
+def test_golden_rne_examples(golden_dir):
+    n = 0
+    for m, vals, e, mant in _read_rows(os.path.join(golden_dir, "encode_rne_examples.txt")):
+        m, e = int(m), int(e)
+        x = np.array([[float(v) for v in vals.split()]], dtype=np.float32)
+        want = np.array([int(v) for v in mant.split()], dtype=np.int32)
+        t = ref.encode(x, 1, 0, m)
+        assert t.exps.shape == (1, 1)
+        assert int(t.exps[0, 0]) - 125 - m == e, (vals, t.exps)
+        np.testing.assert_array_equal(t.mant[0], want, err_msg=vals)
+        np.testing.assert_array_equal(ref.decode(t)[0], want.astype(np.float64) * 2.0 ** e)
+        n += 1
+    assert n >= 8
+
+
+def test_golden_dot_examples(golden_dir):
+    for a, b, ea, eb, idot, val in _read_rows(os.path.join(golden_dir, "dot_examples.txt")):
+        a = np.array([[float(v) for v in a.split()]], dtype=np.float32)          # [1, K]
+        b = np.array([[float(v)] for v in b.split()], dtype=np.float32)          # [K, 1]
+        ta, tb = ref.encode(a, 1, 0, 8), ref.encode(b, 0, 1, 8)
+        assert int(ta.exps[0, 0]) - 133 == int(ea) and int(tb.exps[0, 0]) - 133 == int(eb)
+        P = ref.block_dots(ta.mant, tb.mant, 0)
+        assert P.shape == (1, 1, 1) and int(P[0, 0, 0]) == int(idot)
+        C = ref.gemm(ref.decode(ta), ref.decode(tb))
+        assert C[0, 0] == float(val)
+        C2 = ref.scale_accumulate(P, ta.exps, tb.exps, 8, 8)
+        assert C2[0, 0] == float(val)
+
+
+# ---------------------------------------------------------------- an independent formulation
+def _encode_rne_float64(x, br, bc, m):
+    """Same quantiser written with frexp / rint in FP64 instead of integer bit
+    operations (x / unit is exact in FP64, np.rint rounds half to even)."""
+    rows, cols = x.shape
+    br = rows if br <= 0 or br > rows else br
+    bc = cols if bc <= 0 or bc > cols else bc
+    mant = np.zeros((rows, cols), dtype=np.int64)
+    unit_exp = np.zeros((-(-rows // br), -(-cols // bc)), dtype=np.int64)
+    for i, r0 in enumerate(range(0, rows, br)):
+        for j, c0 in enumerate(range(0, cols, bc)):
+            blk = x[r0:r0 + br, c0:c0 + bc].astype(np.float64)
+            amax = np.abs(blk).max()
+            _, ex = np.frexp(amax)                       # amax = f * 2^ex, f in [0.5, 1)
+            emax = max(int(ex) - 1, -126)                # exponent of the leading bit (subnormals pinned)
+            e = emax - (m - 2)
+            q = np.rint(blk / 2.0 ** e)
+            if np.abs(q).max() >= 2 ** (m - 1):
+                e += 1
+                q = np.rint(blk / 2.0 ** e)
+            mant[r0:r0 + br, c0:c0 + bc] = q.astype(np.int64)
+            unit_exp[i, j] = e
+    return mant, unit_exp
+
+
+@pytest.mark.parametrize("m", [2, 4, 8, 9, 12, 16])
+@pytest.mark.parametrize("shape,br,bc", [((7, 96), 1, 32), ((50, 70), 24, 24), ((64, 5), 32, 1),
+                                         ((3, 100), 1, 0), ((33, 33), 0, 0), ((1, 1000), 1, 64)])
+def test_rne_matches_float64_formulation(m, shape, br, bc):
+    rng = np.random.default_rng(m * 1000 + shape[0])
+    x = (rng.standard_normal(shape) * np.exp2(rng.integers(-30, 30, size=shape))).astype(np.float32)
+    x[rng.random(shape) < 0.05] = 0.0
+    t = ref.encode(x, br, bc, m)
+    mant, ue = _encode_rne_float64(x, br, bc, m)
+    np.testing.assert_array_equal(t.mant, mant)
+    np.testing.assert_array_equal(t.exps.astype(np.int64) - 125 - m, ue)
+
+
+def test_rne_near_power_of_two_maxima_and_ties():
+    # maxima just below a power of two force the exponent raise; exact ties test half-to-even
+    for m in (4, 8, 12, 16):
+        top = np.float32(2.0)
+        vals = [np.nextafter(top, np.float32(0)), top * (1 - 2.0 ** -(m - 1)), top * (1 - 2.0 ** -m),
+                top * (1 - 2.0 ** -(m + 1)), 1.0, 2.0 ** -(m - 2) * 0.5, 2.0 ** -(m - 2) * 1.5, 2.0 ** -(m - 2) * 2.5]
+        for v in vals[:4]:
+            x = np.array([[v] + vals[4:]], dtype=np.float32)
+            t = ref.encode(x, 1, 0, m)
+            mant, ue = _encode_rne_float64(x, 1, 0, m)
+            np.testing.assert_array_equal(t.mant, mant)
+            assert int(t.exps[0, 0]) - 125 - m == int(ue[0, 0])
+            assert np.abs(t.mant).max() <= 2 ** (m - 1) - 1
+
+
+# ---------------------------------------------------------------- invariants
+def _lsb(t):
+    return np.exp2(t.unit_exponents().astype(np.float64))
+
+
+@pytest.mark.parametrize("m", [4, 8, 12, 16])
+@pytest.mark.parametrize("rounding", [ref.RNE, ref.STOCHASTIC])
+def test_power_of_two_blocks_are_exact(m, rounding):
+    rng = np.random.default_rng(7 + m)
+    rows, cols, B = 16, 128, 32
+    kmax = rng.integers(-100, 100, size=(rows, cols // B, 1))
+    k = kmax - rng.integers(0, m - 1, size=(rows, cols // B, B))      # within the m-1 magnitude bits
+    k[:, :, 0] = kmax[:, :, 0]
+    sign = rng.choice([-1.0, 1.0], size=k.shape)
+    x = (sign * np.exp2(k.astype(np.float64))).reshape(rows, cols).astype(np.float32)
+    t = ref.encode(x, 1, B, m, rounding, seed=99)
+    np.testing.assert_array_equal(ref.decode(t), x)
+    # the block maximum sits on the top magnitude bit
+    assert (np.abs(t.mant).reshape(rows, cols // B, B).max(axis=2) == 2 ** (m - 2)).all()
+
+
+@pytest.mark.parametrize("m", [4, 8, 12, 16])
+def test_rne_error_at_most_half_unit_and_normalised(m):
+    x = (np.random.default_rng(m).standard_normal((64, 256)) * 3).astype(np.float32)
+    t = ref.encode(x, 1, 32, m)
+    err = np.abs(ref.decode(t).astype(np.float64) - x.astype(np.float64))
+    assert (err <= 0.5 * _lsb(t)).all()
+    top = np.abs(t.mant).reshape(64, 8, 32).max(axis=2)
+    assert (top >= 2 ** (m - 2)).all() and (top <= 2 ** (m - 1) - 1).all()
+
+
+@pytest.mark.parametrize("m", [4, 8, 12])
+def test_sr_error_below_one_unit_unbiased_and_floor_or_ceil(m):
+    rng = np.random.default_rng(100 + m)
+    x = (rng.standard_normal((256, 1024)) * np.exp2(rng.integers(-3, 3, size=(256, 1024)))).astype(np.float32)
+    t = ref.encode(x, 1, 32, m, ref.STOCHASTIC, seed=1234)
+    lsb = _lsb(t)
+    exact = x.astype(np.float64) / lsb
+    q = t.mant.astype(np.float64)
+    mag, qm = np.abs(exact), np.abs(q)
+    assert ((qm == np.floor(mag)) | (qm == np.ceil(mag))).all()          # only the two neighbours
+    assert (np.abs(q - exact) < 1.0).all()
+    assert (np.sign(q) * np.sign(exact) >= 0).all()
+    d = (q - exact).ravel()                                              # error in units
+    n = d.size
+    assert abs(d.mean()) < 4.0 * d.std() / np.sqrt(n)                    # unbiased
+    assert np.abs(t.mant).max() <= 2 ** (m - 1) - 1
+
+
+def test_sr_round_up_frequency_equals_fraction():
+    # a block [64.0, f, f, ...] with m=8 has unit 1, so element f in (0,1) must round up with probability f
+    for f in (0.125, 0.3, 0.5, 0.9):
+        n = 1 << 16
+        x = np.full((n // 32, 32), f, dtype=np.float32)
+        x[:, 0] = 64.0
+        t = ref.encode(x, 1, 32, 8, ref.STOCHASTIC, seed=42)
+        assert (t.exps == 133).all()
+        ups = t.mant[:, 1:].ravel()
+        assert set(np.unique(ups)) <= {0, 1}
+        p = ups.mean()
+        fx = float(np.float32(f))
+        assert abs(p - fx) < 4.0 * np.sqrt(fx * (1 - fx) / ups.size)
+
+
+def test_sr_depends_on_seed_and_logical_index_only():
+    x = np.random.default_rng(5).standard_normal((32, 64)).astype(np.float32)
+    a = ref.encode(x, 1, 32, 8, ref.STOCHASTIC, seed=1)
+    b = ref.encode(x, 1, 32, 8, ref.STOCHASTIC, seed=1)
+    c = ref.encode(x, 1, 32, 8, ref.STOCHASTIC, seed=2)
+    np.testing.assert_array_equal(a.mant, b.mant)
+    assert (a.mant != c.mant).mean() > 0.2
+    np.testing.assert_array_equal(a.exps, c.exps)
+    # block shape does not change the random draw of an element: with a common exponent the mantissas agree
+    y = np.ones((4, 64), dtype=np.float32) * 0.3
+    y[:, ::8] = 1.0
+    d = ref.encode(y, 1, 8, 8, ref.STOCHASTIC, seed=3)
+    e = ref.encode(y, 4, 64, 8, ref.STOCHASTIC, seed=3)
+    np.testing.assert_array_equal(d.mant, e.mant)
+
+
+def test_hash_statistics():
+    idx = np.arange(1 << 16, dtype=np.uint64)
+    h = np.array([ref.hash32(77, int(i)) for i in idx], dtype=np.uint64)
+    top = (h >> np.uint64(24)).astype(np.int64)
+    counts = np.bincount(top, minlength=256)
+    expected = idx.size / 256.0
+    chi2 = ((counts - expected) ** 2 / expected).sum()
+    assert chi2 < 255 + 5 * np.sqrt(2 * 255)                              # uniform top byte
+    low = (h & np.uint64(0xFF)).astype(np.int64)
+    chi2l = ((np.bincount(low, minlength=256) - expected) ** 2 / expected).sum()
+    assert chi2l < 255 + 5 * np.sqrt(2 * 255)
+    h2 = np.array([ref.hash32(78, int(i)) for i in idx[:4096]], dtype=np.uint64)
+    diff = np.array([bin(int(a ^ b)).count("1") for a, b in zip(h[:4096], h2)])
+    assert abs(diff.mean() - 16.0) < 0.5                                  # other seed: half the bits flip
+    hs = np.array([ref.hash32(77, int(i) + (1 << 32)) for i in idx[:4096]], dtype=np.uint64)
+    assert (hs != h[:4096]).mean() > 0.99                                  # the high index word matters
+    # serial correlation of consecutive outputs
+    u = h.astype(np.float64) / 2 ** 32
+    r = np.corrcoef(u[:-1], u[1:])[0, 1]
+    assert abs(r) < 4.0 / np.sqrt(u.size)
+
+
+@pytest.mark.parametrize("m", [8, 12])
+def test_equivariances(m):
+    rng = np.random.default_rng(31 + m)
+    x = rng.standard_normal((16, 96)).astype(np.float32)
+    t = ref.encode(x, 1, 24, m)
+    for k in (-40, -3, 5, 60):
+        tk = ref.encode((x.astype(np.float64) * 2.0 ** k).astype(np.float32), 1, 24, m)
+        np.testing.assert_array_equal(tk.mant, t.mant)
+        np.testing.assert_array_equal(tk.exps.astype(int), t.exps.astype(int) + k)
+    tn = ref.encode(-x, 1, 24, m)
+    np.testing.assert_array_equal(tn.mant, -t.mant)
+    np.testing.assert_array_equal(tn.exps, t.exps)
+    ts = ref.encode(x, 1, 24, m, ref.STOCHASTIC, seed=8)
+    tsn = ref.encode(-x, 1, 24, m, ref.STOCHASTIC, seed=8)
+    np.testing.assert_array_equal(tsn.mant, -ts.mant)
+    # idempotence: a decoded BFP tensor encodes to itself
+    t2 = ref.encode(ref.decode(t), 1, 24, m)
+    np.testing.assert_array_equal(t2.mant, t.mant)
+    np.testing.assert_array_equal(t2.exps, t.exps)
+
+
+def test_block_of_one_is_a_float_cast():
+    rng = np.random.default_rng(2)
+    x = (rng.standard_normal(20000) * np.exp2(rng.integers(-13, 15, size=20000))).astype(np.float32)
+    x = x[(np.abs(x) >= 2.0 ** -14) & (np.abs(x) < 65000.0)].reshape(1, -1)
+    # 12-bit mantissa incl. sign = 11 significant bits = IEEE half precision
+    got = ref.decode(ref.encode(x, 1, 1, 12))
+    np.testing.assert_array_equal(got, x.astype(np.float16).astype(np.float32))
+    # 9 bits incl. sign = 8 significant bits = bfloat16
+    y = (rng.standard_normal(20000) * np.exp2(rng.integers(-100, 100, size=20000))).astype(np.float32).reshape(1, -1)
+    got = ref.decode(ref.encode(y, 1, 1, 9))
+    want = torch.from_numpy(y).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(got, want)
+
+
+def test_zero_subnormal_and_signed_zero():
+    x = np.zeros((2, 32), dtype=np.float32)
+    x[1, 3] = -0.0
+    t = ref.encode(x, 1, 32, 8)
+    assert (t.mant == 0).all() and (t.exps == 1).all()
+    tiny = np.float32(2.0 ** -149)
+    for m in (8, 16):
+        unit = 2.0 ** (1 - 125 - m)                                       # smallest unit a block can have
+        k = np.arange(-20, 21, dtype=np.float64)
+        y = (k * unit).astype(np.float32).reshape(1, -1)                   # subnormal-range multiples of the unit
+        assert np.abs(y).max() < 2.0 ** -126
+        t = ref.encode(y, 1, 0, m)
+        assert int(t.exps[0, 0]) == 1
+        np.testing.assert_array_equal(t.mant[0], k.astype(np.int32))
+        np.testing.assert_array_equal(ref.decode(t), y)
+    z = np.array([[tiny, -tiny, 0.0, 3 * tiny]], dtype=np.float32)
+    t = ref.encode(z, 1, 0, 16)
+    np.testing.assert_array_equal(t.mant[0], [0, 0, 0, 0])               # far below one unit (2^-140)
+
+
+def test_two_d_tiles_and_ragged_edges_share_one_exponent():
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal((50, 70)) * np.exp2(rng.integers(-8, 8, size=(50, 70)))).astype(np.float32)
+    t = ref.encode(x, 24, 24, 8)
+    assert t.exps.shape == (3, 3)
+    for i in range(3):
+        for j in range(3):
+            blk = x[24 * i:24 * i + 24, 24 * j:24 * j + 24]
+            amax = np.abs(blk).max()
+            _, ex = np.frexp(amax)
+            eb = int(ex) - 1 + 127
+            assert int(t.exps[i, j]) in (eb, eb + 1)
+            sub = ref.encode(np.ascontiguousarray(blk), 0, 0, 8)
+            np.testing.assert_array_equal(sub.mant, t.mant[24 * i:24 * i + 24, 24 * j:24 * j + 24])
+            assert int(sub.exps[0, 0]) == int(t.exps[i, j])
+
+
+# ---------------------------------------------------------------- integer dot products
+def test_block_dots_brute_force():
+    rng = np.random.default_rng(3)
+    M, N, K, kb = 4, 5, 70, 32
+    mA = rng.integers(-127, 128, size=(M, K)).astype(np.int32)
+    mB = rng.integers(-127, 128, size=(K, N)).astype(np.int32)
+    P = ref.block_dots(mA, mB, kb)
+    assert P.shape == (M, N, 3)
+    for i in range(M):
+        for j in range(N):
+            for b in range(3):
+                s = 0
+                for k in range(b * kb, min(K, (b + 1) * kb)):
+                    s += int(mA[i, k]) * int(mB[k, j])
+                assert int(P[i, j, b]) == s
+    # extreme block: every mantissa +-127, 32 per block -> 32 * 127^2 = 516128
+    a = np.full((2, 64), 127, dtype=np.int32)
+    b = np.full((64, 2), -127, dtype=np.int32)
+    P = ref.block_dots(a, b, 32)
+    assert (P == -516128).all()
+    # library routine: integer matmul over the whole K
+    P = ref.block_dots(mA, mB, 0)
+    np.testing.assert_array_equal(P[:, :, 0], mA.astype(np.int64) @ mB.astype(np.int64))
+
+
+def test_block_dots_reports_accumulator_overflow():
+    a = np.full((1, 40000), 2047, dtype=np.int32)
+    b = np.full((40000, 1), 2047, dtype=np.int32)
+    with pytest.raises(OverflowError):
+        ref.block_dots(a, b, 0)
+    assert ref.block_dots(a, b, 512).max() == 512 * 2047 * 2047           # 12-bit mantissas, blocks of 512 fit
+
+
+def test_limb_identity_for_12_bit_mantissas_exhaustive():
+    # every 12-bit pair: v = 64 h + l with h in [-32, 31], l in [0, 63]; the four limb
+    # products recombine to the exact product (the identity a limb-split GEMM relies on)
+    v = np.arange(-2047, 2048, dtype=np.int64)
+    h, l = v >> 6, v & 63
+    assert h.min() >= -32 and h.max() <= 31 and l.min() >= 0 and l.max() <= 63
+    prod = np.multiply.outer(v, v)
+    rec = (np.multiply.outer(h, h) << 12) + ((np.multiply.outer(h, l) + np.multiply.outer(l, h)) << 6) \
+        + np.multiply.outer(l, l)
+    np.testing.assert_array_equal(prod, rec)
+
+
+# ---------------------------------------------------------------- GEMM
+def test_gemm_is_the_fp64_product():
+    rng = np.random.default_rng(17)
+    A = rng.standard_normal((37, 129)).astype(np.float32)
+    B = rng.standard_normal((129, 41)).astype(np.float32)
+    C = ref.gemm(A, B)
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    np.testing.assert_allclose(C, want, rtol=0, atol=1e-12 * np.abs(want).max() * 129)
+    sel = np.array([5, 0, 36, 5])
+    np.testing.assert_array_equal(ref.gemm(A, B, rows=sel), C[sel])
+    # a transposed operand must not pass
+    Bt = rng.standard_normal((129, 129)).astype(np.float32)
+    A2 = rng.standard_normal((129, 129)).astype(np.float32)
+    assert np.abs(ref.gemm(A2, Bt) - A2.astype(np.float64) @ Bt.T.astype(np.float64)).max() > 1.0
+
+
+def test_gemm_power_of_two_inputs_is_exact_fp32_gemm():
+    rng = np.random.default_rng(23)
+    M, K, N = 16, 64, 24
+    A = (rng.choice([-1.0, 1.0], size=(M, K)) * np.exp2(rng.integers(-3, 3, size=(M, K)))).astype(np.float32)
+    B = (rng.choice([-1.0, 1.0], size=(K, N)) * np.exp2(rng.integers(-3, 3, size=(K, N)))).astype(np.float32)
+    C, ta, tb = ref.bfp_gemm(A, B, dict(br=1, bc=32, m=8), dict(br=32, bc=1, m=8))
+    np.testing.assert_array_equal(ref.decode(ta), A)
+    np.testing.assert_array_equal(C, A.astype(np.float64) @ B.astype(np.float64))   # small integers * 2^-6: exact
+
+
+def test_gemm_whole_k_blocks_is_scaled_integer_gemm():
+    # Sec. 4: one exponent per row of A and per column of B suffices
+    rng = np.random.default_rng(29)
+    M, K, N = 9, 200, 7
+    A = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-10, 10, size=(M, 1)))).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * np.exp2(rng.integers(-10, 10, size=(1, N)))).astype(np.float32)
+    C, ta, tb = ref.bfp_gemm(A, B, dict(br=1, bc=0, m=8), dict(br=0, bc=1, m=8))
+    assert ta.exps.shape == (M, 1) and tb.exps.shape == (1, N)
+    I = ta.mant.astype(np.int64) @ tb.mant.astype(np.int64)
+    e = (ta.exps.astype(np.int64) - 133) + (tb.exps.astype(np.int64) - 133)
+    np.testing.assert_array_equal(C, I.astype(np.float64) * np.exp2(e.astype(np.float64)))
+
+
+@pytest.mark.parametrize("m,kb", [(8, 32), (8, 24), (12, 64)])
+def test_block_partials_scaled_and_summed_equal_the_definition(m, kb):
+    rng = np.random.default_rng(m + kb)
+    M, K, N = 12, 200, 10
+    A = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-6, 6, size=(M, K)))).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * np.exp2(rng.integers(-6, 6, size=(K, N)))).astype(np.float32)
+    C, ta, tb = ref.bfp_gemm(A, B, dict(br=1, bc=kb, m=m), dict(br=kb, bc=1, m=m))
+    P = ref.block_dots(ta.mant, tb.mant, kb)
+    C2 = ref.scale_accumulate(P, ta.exps, tb.exps, m, m)
+    np.testing.assert_allclose(C2, C, rtol=1e-13, atol=1e-13 * np.abs(C).max())
+    # and the quantised product is close to the FP32 one, as the format promises (8+ bit mantissas)
+    exact = A.astype(np.float64) @ B.astype(np.float64)
+    rel = np.linalg.norm(C - exact) / np.linalg.norm(exact)
+    assert rel < 2.0 ** -(m - 3)
