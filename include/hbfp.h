@@ -1,0 +1,206 @@
+/*
+ * hbfp.h - C ABI of the MI355X (gfx950) block-floating-point library.
+ *
+ * The library implements the dot-product path of Hybrid Block Floating Point
+ * (arXiv 1804.01526): FP32 tensors are converted to BFP right before a dot
+ * product, the product runs on fixed-point mantissas, and the result returns to
+ * FP32 (Sec. 4.1).  Everything else in the paper stays in floating point and is
+ * not part of this library.
+ *
+ * Conventions
+ *   - Every pointer named `src`, `dst`, `C`, `P`, `workspace`, and the `mant`
+ *     and `exps` members of an hbfp_tensor are DEVICE pointers.  Format and
+ *     tensor descriptors are HOST structs, read during the call.
+ *   - The caller owns every buffer.  No entry point allocates or frees device
+ *     memory; sizes come from the pure host functions (hbfp_plan, hbfp_*_workspace).
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls are
+ *     asynchronous with respect to the host and ordered on that stream.
+ *   - Every function returns an int status: HBFP_OK or a negative HBFP_ERR_*.
+ *     Arguments are validated before any work is queued; on an error nothing
+ *     has been launched (HBFP_ERR_LAUNCH excepted: the runtime refused a launch).
+ *   - Results are deterministic: the same inputs and seed give the same bytes.
+ *
+ * The BFP tensor (Eq. (1), Sec. 4:  a_i = m_i * 2^e)
+ *   - Mantissas are two's complement integers of `mant_bits` bits, the sign
+ *     included, in the symmetric range +-(2^(mant_bits-1) - 1).
+ *   - A block of elements shares one exponent, stored as one byte Eb in 1..255:
+ *     the IEEE-754 biased exponent of the block's largest magnitude (Sec. 4.1,
+ *     Sec. 5.3: "exponent of the largest value"), raised by one when rounding
+ *     that largest value would reach 2^(mant_bits-1).  One mantissa unit is worth
+ *     2^(Eb - 125 - mant_bits); an all-zero or subnormal-only block has Eb = 1.
+ *   - Rounding acts on the magnitude, then the sign is applied: round to
+ *     nearest even, or stochastic rounding (Sec. 5.3) with the counter hash below.
+ *   - Inputs must be finite.  NaN/Inf are not trapped; their blocks hold
+ *     unspecified mantissas.
+ *
+ * Stored ("operand") layout.  A tensor is always encoded FOR a dot product, i.e.
+ * with a contraction axis (the k of Eq. (2)).  The other axis indexes operand
+ * rows.  With R operand rows and K contraction elements:
+ *     kblock      elements of one exponent block along k
+ *     kblock_pad  stored length of a block: 32 if kblock <= 32, 64 if <= 64,
+ *                 otherwise kblock rounded up to a multiple of 128
+ *     nblk        ceil(K / kblock)           (the last block may be short)
+ *     kpad        nblk * kblock_pad rounded up to a multiple of 128
+ *     mant        [R][kpad]  int8 (mant_bits <= 8) or int16; element k of block b
+ *                 of row r sits at r*kpad + b*kblock_pad + k; all padding is 0
+ *     exp_ld      nblk rounded up to a multiple of 4
+ *     exps        [R][exp_ld] uint8; exps[r][b] is the exponent byte of the block
+ *                 holding (r, b).  With 2-D blocks several rows repeat the same
+ *                 byte.  Bytes b >= nblk are written as 1.
+ * k is contiguous for both operands of a product, whatever the source layout,
+ * so one GEMM kernel serves the forward, data-gradient and weight-gradient shapes.
+ *
+ * Stochastic rounding (Sec. 5.3 uses a xorshift generator).  Here the random word
+ * of an element is a counter hash, so that any launch geometry draws the same
+ * bits.  With idx = r*cols + c the element's logical position in the source
+ * matrix (independent of ld), lo/hi the 32-bit halves of idx and s0/s1 those of
+ * the seed, all arithmetic modulo 2^32:
+ *     x = lo ^ s0;  x ^= x << 13;  x ^= x >> 17;  x ^= x << 5;   x += hi ^ s1;
+ *     x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16;
+ * An element whose significand must be shifted right by sh bits to align with
+ * the block exponent adds the top sh bits of x below the kept bits before
+ * truncating (sh > 32: the element becomes 0).
+ */
+#ifndef HBFP_H
+#define HBFP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    HBFP_OK = 0,
+    HBFP_ERR_ARG = -1,       /* null pointer, non-positive size, ld too small, bad flag */
+    HBFP_ERR_FORMAT = -2,    /* unsupported mantissa width, block shape or rounding mode */
+    HBFP_ERR_LAYOUT = -3,    /* descriptor does not match hbfp_plan, or operands do not fit each other */
+    HBFP_ERR_RANGE = -4,     /* a block dot product could overflow the int32 accumulator */
+    HBFP_ERR_LAUNCH = -5,    /* the HIP runtime reported an error (no device, bad launch) */
+    HBFP_ERR_WORKSPACE = -6  /* workspace missing, too small or misaligned (256 bytes) */
+};
+
+enum { HBFP_RNE = 0, HBFP_STOCHASTIC = 1 };
+
+/* How a source matrix [rows][cols] is cut into exponent blocks. */
+typedef struct hbfp_format {
+    int32_t mant_bits;   /* 2..16, sign included */
+    int32_t rounding;    /* HBFP_RNE or HBFP_STOCHASTIC */
+    int64_t block_rows;  /* block extent along the source rows; 0 = all rows */
+    int64_t block_cols;  /* block extent along the source columns; 0 = all columns */
+    uint64_t seed;       /* stochastic rounding only */
+} hbfp_format;
+
+/* An encoded operand.  hbfp_plan fills everything but the two pointers. */
+typedef struct hbfp_tensor {
+    void *mant;            /* device, mant_bytes, 16-byte aligned */
+    uint8_t *exps;         /* device, exp_bytes, 4-byte aligned */
+    int64_t rows;          /* R: operand rows (extent of the non-contraction axis) */
+    int64_t kdim;          /* K: contraction extent */
+    int64_t kblock;        /* exponent block length along k */
+    int64_t kblock_pad;
+    int64_t nblk;
+    int64_t kpad;
+    int64_t exp_ld;
+    int64_t rblock;        /* operand rows that share one exponent (block extent across k) */
+    int64_t src_rows, src_cols; /* shape of the source matrix */
+    int32_t contract_axis; /* 0: k runs down the source rows, 1: along the source columns */
+    int32_t mant_bits;
+    int32_t rounding;
+    int32_t reserved;
+    uint64_t seed;
+    uint64_t mant_bytes, exp_bytes;
+} hbfp_tensor;
+
+/* Library version and a short text for a status code (host, never NULL). */
+int hbfp_version(void);
+const char *hbfp_status_string(int status);
+
+/*
+ * hbfp_plan (host only): geometry and byte sizes of the operand that encoding a
+ * source matrix [rows][cols] along `contract_axis` produces (layout above).
+ * Sets out->mant = out->exps = NULL.
+ * Errors: HBFP_ERR_ARG (null, sizes <= 0, axis not 0/1), HBFP_ERR_FORMAT
+ * (mant_bits outside 2..16, negative block extents, unknown rounding).
+ */
+int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_axis, hbfp_tensor *out);
+
+/*
+ * hbfp_encode_workspace (host only): bytes of scratch hbfp_encode needs for this
+ * plan (0 for 1-D blocks of at most 64 elements along k; otherwise 4 bytes per
+ * exponent block, rounded up to 256).
+ */
+int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes);
+
+/*
+ * hbfp_encode: FP32 -> BFP (Sec. 4.1 "convert tensors to BFP before every dot
+ * product, using the exponent of the largest tensor value"; Sec. 5.3 FP-to-BFP
+ * unit: detect the maximum exponent, normalise the mantissas).
+ *   src   device FP32 source matrix, element (r, c) at src[r*ld + c], ld >= cols
+ *   out   descriptor from hbfp_plan for the same (fmt, rows, cols, contract_axis),
+ *         with mant/exps set by the caller; fully overwritten, padding included
+ *   workspace  device scratch of hbfp_encode_workspace bytes (may be NULL when 0)
+ * Errors: HBFP_ERR_ARG, HBFP_ERR_FORMAT, HBFP_ERR_LAYOUT (descriptor differs from the
+ * plan), HBFP_ERR_WORKSPACE, HBFP_ERR_LAUNCH.
+ */
+int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int contract_axis,
+                const hbfp_format *fmt, hbfp_tensor *out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hbfp_decode: BFP -> FP32, Eq. (1): dst[r*ld + c] = mant * 2^(Eb - 125 - mant_bits),
+ * written in the SOURCE orientation [src_rows][src_cols] of the tensor.  Exact,
+ * subnormal results included.
+ */
+int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
+
+/*
+ * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation
+ * (Sec. 4, tiled matrix multiplication):
+ *     C[i][j] = beta*C[i][j] + sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k]*mB[j][k]
+ * The inner sum is exact integer arithmetic (int8 matrix cores, int32
+ * accumulators); the outer sum is FP32.  A has M = A->rows operand rows, B has
+ * N = B->rows; both must have the same kdim, kblock and mantissa class (both
+ * <= 8 bits, or both 9..12 bits, which run as two int8 limbs per mantissa).
+ *   C     device FP32 [M][ldc], ldc >= N
+ *   beta  0 (overwrite; C is not read) or 1 (accumulate)
+ *   workspace  hbfp_gemm_workspace bytes (0 for mantissas of at most 8 bits)
+ * Domain: block exponent bytes up to 254 (magnitudes below 2^127).
+ * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (kdim/kblock mismatch), HBFP_ERR_FORMAT
+ * (mantissa classes differ or exceed 12 bits), HBFP_ERR_RANGE (kblock * max|mA| *
+ * max|mB| >= 2^31), HBFP_ERR_WORKSPACE, HBFP_ERR_LAUNCH.
+ */
+int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes);
+int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
+              void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hbfp_gemm_partials: the fixed-point half of Eq. (2) alone, for checking:
+ *     P[(i*N + j)*nblk + b] = sum_{k in block b} mA[i][k] * mB[j][k]     (int32, exact)
+ * computed by the same matrix-core path as hbfp_gemm.  Same operand rules.
+ */
+int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
+                       void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hbfp_gemm_f32: convert-multiply-convert in one call (Sec. 4.1), BLAS style,
+ * row-major:  C[M][N] = op(A) * op(B),  op(A) is M x K, op(B) is K x N.
+ *   transA = 0: A is [M][lda];  1: A is [K][lda] (used as its transpose)
+ *   transB = 0: B is [K][ldb];  1: B is [N][ldb]
+ * (0,0) is the forward product, (0,1) the data gradient dX = dY * W^T,
+ * (1,0) the weight gradient dW = X^T * dY.  fa/fb give each operand's exponent
+ * blocks in the orientation the matrix is stored in; both must cut the
+ * contraction axis into blocks of the same length.
+ * workspace: hbfp_gemm_f32_workspace bytes (holds both encoded operands).
+ */
+int hbfp_gemm_f32_workspace(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            const hbfp_format *fa, const hbfp_format *fb, size_t *bytes);
+int hbfp_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                  const float *A, int64_t lda, const float *B, int64_t ldb, float *C, int64_t ldc,
+                  const hbfp_format *fa, const hbfp_format *fb,
+                  void *workspace, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBFP_H */

@@ -1,0 +1,327 @@
+// Host side of the C ABI: geometry, argument validation, dispatch.
+// Every check runs before anything is queued on the GPU, so the error paths
+// behave the same on a machine without a GPU.
+#include <string.h>
+
+#include "hbfp_internal.h"
+
+using namespace hbfp;
+
+namespace {
+
+int check_format(const hbfp_format *f) {
+    if (!f) return HBFP_ERR_ARG;
+    if (f->mant_bits < 2 || f->mant_bits > 16) return HBFP_ERR_FORMAT;
+    if (f->rounding != HBFP_RNE && f->rounding != HBFP_STOCHASTIC) return HBFP_ERR_FORMAT;
+    if (f->block_rows < 0 || f->block_cols < 0) return HBFP_ERR_FORMAT;
+    return HBFP_OK;
+}
+
+bool same_plan(const hbfp_tensor &a, const hbfp_tensor &b) {
+    return a.rows == b.rows && a.kdim == b.kdim && a.kblock == b.kblock && a.kblock_pad == b.kblock_pad &&
+           a.nblk == b.nblk && a.kpad == b.kpad && a.exp_ld == b.exp_ld && a.rblock == b.rblock &&
+           a.src_rows == b.src_rows && a.src_cols == b.src_cols && a.contract_axis == b.contract_axis &&
+           a.mant_bits == b.mant_bits && a.rounding == b.rounding && a.seed == b.seed &&
+           a.mant_bytes == b.mant_bytes && a.exp_bytes == b.exp_bytes;
+}
+
+EncodeGeom geom_of(const hbfp_tensor &t, int64_t ld) {
+    EncodeGeom g;
+    g.src_rows = t.src_rows;
+    g.src_cols = t.src_cols;
+    g.ld = ld;
+    g.axis = t.contract_axis;
+    if (t.contract_axis == 1) {
+        g.br = t.rblock;
+        g.bc = t.kblock;
+    } else {
+        g.br = t.kblock;
+        g.bc = t.rblock;
+    }
+    g.nbr = ceil_div(g.src_rows, g.br);
+    g.nbc = ceil_div(g.src_cols, g.bc);
+    g.R = t.rows;
+    g.K = t.kdim;
+    g.kblock = t.kblock;
+    g.kbp = t.kblock_pad;
+    g.nblk = t.nblk;
+    g.kpad = t.kpad;
+    g.exp_ld = t.exp_ld;
+    g.rblock = t.rblock;
+    g.m = t.mant_bits;
+    g.rounding = t.rounding;
+    g.seed_lo = (uint32_t)t.seed;
+    g.seed_hi = (uint32_t)(t.seed >> 32);
+    return g;
+}
+
+// A descriptor is usable if it is exactly what hbfp_plan produces for its own key fields.
+int check_tensor(const hbfp_tensor *t, bool need_ptrs) {
+    if (!t) return HBFP_ERR_ARG;
+    if (need_ptrs && (!t->mant || !t->exps)) return HBFP_ERR_ARG;
+    if (t->src_rows <= 0 || t->src_cols <= 0 || (t->contract_axis != 0 && t->contract_axis != 1)) return HBFP_ERR_LAYOUT;
+    hbfp_format f;
+    f.mant_bits = t->mant_bits;
+    f.rounding = t->rounding;
+    f.seed = t->seed;
+    if (t->contract_axis == 1) {
+        f.block_rows = t->rblock;
+        f.block_cols = t->kblock;
+    } else {
+        f.block_rows = t->kblock;
+        f.block_cols = t->rblock;
+    }
+    hbfp_tensor p;
+    int rc = hbfp_plan(&f, t->src_rows, t->src_cols, t->contract_axis, &p);
+    if (rc != HBFP_OK) return HBFP_ERR_LAYOUT;
+    if (!same_plan(p, *t)) return HBFP_ERR_LAYOUT;
+    if (need_ptrs && (((uintptr_t)t->mant & 15) || ((uintptr_t)t->exps & 3))) return HBFP_ERR_ARG;
+    return HBFP_OK;
+}
+
+bool needs_tile_pass(const hbfp_tensor &t) {
+    if (t.rblock != 1) return true;
+    return t.contract_axis == 1 ? t.kblock > 128 : t.kblock > 64;
+}
+
+int check_pair(const hbfp_tensor *A, const hbfp_tensor *B) {
+    int rc = check_tensor(A, true);
+    if (rc != HBFP_OK) return rc;
+    rc = check_tensor(B, true);
+    if (rc != HBFP_OK) return rc;
+    if (A->kdim != B->kdim || A->kblock != B->kblock) return HBFP_ERR_LAYOUT;
+    const bool a8 = A->mant_bits <= 8, b8 = B->mant_bits <= 8;
+    if (a8 != b8) return HBFP_ERR_FORMAT;
+    if (A->mant_bits > 12 || B->mant_bits > 12) return HBFP_ERR_FORMAT;
+    const int64_t qa = ((int64_t)1 << (A->mant_bits - 1)) - 1, qb = ((int64_t)1 << (B->mant_bits - 1)) - 1;
+    // kblock * qa * qb must stay below 2^31 (int32 accumulators never overflow, Sec. 5.3)
+    const int64_t lim = ((int64_t)1 << 31) - 1;
+    if (A->kblock > lim / (qa * qb)) return HBFP_ERR_RANGE;
+    return HBFP_OK;
+}
+
+GemmArgs gemm_args(const hbfp_tensor *A, const hbfp_tensor *B) {
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = A->mant;
+    g.mantB = B->mant;
+    g.expA = A->exps;
+    g.expB = B->exps;
+    g.M = A->rows;
+    g.N = B->rows;
+    g.kpad = A->kpad;
+    g.expA_ld = A->exp_ld;
+    g.expB_ld = B->exp_ld;
+    g.nblk = A->nblk;
+    g.kbp = A->kblock_pad;
+    g.mA = A->mant_bits;
+    g.mB = B->mant_bits;
+    return g;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+int hbfp_version(void) { return 100; }
+
+const char *hbfp_status_string(int status) {
+    switch (status) {
+        case HBFP_OK: return "ok";
+        case HBFP_ERR_ARG: return "bad argument";
+        case HBFP_ERR_FORMAT: return "unsupported format";
+        case HBFP_ERR_LAYOUT: return "operand layout mismatch";
+        case HBFP_ERR_RANGE: return "int32 accumulator bound exceeded";
+        case HBFP_ERR_LAUNCH: return "HIP runtime error";
+        case HBFP_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+        default: return "unknown status";
+    }
+}
+
+int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_axis, hbfp_tensor *out) {
+    if (!fmt || !out || rows <= 0 || cols <= 0 || (contract_axis != 0 && contract_axis != 1)) return HBFP_ERR_ARG;
+    int rc = check_format(fmt);
+    if (rc != HBFP_OK) return rc;
+    const int64_t br = (fmt->block_rows == 0 || fmt->block_rows > rows) ? rows : fmt->block_rows;
+    const int64_t bc = (fmt->block_cols == 0 || fmt->block_cols > cols) ? cols : fmt->block_cols;
+    memset(out, 0, sizeof *out);
+    out->src_rows = rows;
+    out->src_cols = cols;
+    out->contract_axis = contract_axis;
+    out->mant_bits = fmt->mant_bits;
+    out->rounding = fmt->rounding;
+    out->seed = fmt->rounding == HBFP_STOCHASTIC ? fmt->seed : 0;
+    if (contract_axis == 1) {
+        out->rows = rows;
+        out->kdim = cols;
+        out->kblock = bc;
+        out->rblock = br;
+    } else {
+        out->rows = cols;
+        out->kdim = rows;
+        out->kblock = br;
+        out->rblock = bc;
+    }
+    out->kblock_pad = out->kblock <= 32 ? 32 : out->kblock <= 64 ? 64 : round_up(out->kblock, 128);
+    out->nblk = ceil_div(out->kdim, out->kblock);
+    out->kpad = round_up(out->nblk * out->kblock_pad, 128);
+    out->exp_ld = round_up(out->nblk, 4);
+    out->mant_bytes = (uint64_t)out->rows * (uint64_t)out->kpad * (fmt->mant_bits <= 8 ? 1u : 2u);
+    out->exp_bytes = (uint64_t)out->rows * (uint64_t)out->exp_ld;
+    return HBFP_OK;
+}
+
+int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes) {
+    if (!plan || !bytes) return HBFP_ERR_ARG;
+    int rc = check_tensor(plan, false);
+    if (rc != HBFP_OK) return rc;
+    if (!needs_tile_pass(*plan)) {
+        *bytes = 0;
+        return HBFP_OK;
+    }
+    const int64_t ntile = ceil_div(plan->rows, plan->rblock) * plan->nblk;
+    *bytes = align256((size_t)ntile * 4);
+    return HBFP_OK;
+}
+
+int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int contract_axis,
+                const hbfp_format *fmt, hbfp_tensor *out, void *workspace, size_t ws_bytes, void *stream) {
+    if (!src || !fmt || !out || rows <= 0 || cols <= 0 || ld < cols) return HBFP_ERR_ARG;
+    hbfp_tensor p;
+    int rc = hbfp_plan(fmt, rows, cols, contract_axis, &p);
+    if (rc != HBFP_OK) return rc;
+    if (!same_plan(p, *out)) return HBFP_ERR_LAYOUT;
+    if (!out->mant || !out->exps) return HBFP_ERR_ARG;
+    if (((uintptr_t)out->mant & 15) || ((uintptr_t)out->exps & 3) || ((uintptr_t)src & 3)) return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_encode_workspace(&p, &need);
+    if (need) {
+        if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    }
+    const EncodeGeom g = geom_of(*out, ld);
+    hipStream_t s = (hipStream_t)stream;
+    if (need) return launch_encode_generic(src, g, out->mant, out->exps, (uint32_t *)workspace, s);
+    if (contract_axis == 1) return launch_encode_row_fused(src, g, out->mant, out->exps, s);
+    return launch_encode_col_fused(src, g, out->mant, out->exps, s);
+}
+
+int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
+    if (!dst) return HBFP_ERR_ARG;
+    int rc = check_tensor(t, true);
+    if (rc != HBFP_OK) return rc;
+    if (ld < t->src_cols || ((uintptr_t)dst & 3)) return HBFP_ERR_ARG;
+    return launch_decode(t, dst, ld, (hipStream_t)stream);
+}
+
+int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    int rc = check_tensor(A, false);
+    if (rc != HBFP_OK) return rc;
+    rc = check_tensor(B, false);
+    if (rc != HBFP_OK) return rc;
+    *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
+                                                     : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad);
+    return HBFP_OK;
+}
+
+static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int32_t *P,
+                    void *workspace, size_t ws_bytes, void *stream) {
+    int rc = check_pair(A, B);
+    if (rc != HBFP_OK) return rc;
+    size_t need = 0;
+    hbfp_gemm_workspace(A, B, &need);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    GemmArgs g = gemm_args(A, B);
+    g.C = C;
+    g.ldc = ldc;
+    g.beta = beta;
+    g.P = P;
+    if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
+    return launch_gemm_i8(g, workspace, (hipStream_t)stream);
+}
+
+int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
+              void *workspace, size_t ws_bytes, void *stream) {
+    if (!A || !B || !C) return HBFP_ERR_ARG;
+    if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
+    if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
+    return run_gemm(A, B, C, ldc, beta, nullptr, workspace, ws_bytes, stream);
+}
+
+int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
+                       void *workspace, size_t ws_bytes, void *stream) {
+    if (!A || !B || !P || ((uintptr_t)P & 3)) return HBFP_ERR_ARG;
+    return run_gemm(A, B, nullptr, 0, 0.0f, P, workspace, ws_bytes, stream);
+}
+
+// Layout of the hbfp_gemm_f32 workspace: [A mant][A exps][B mant][B exps][encode scratch][gemm scratch]
+struct F32Plan {
+    hbfp_tensor ta, tb;
+    size_t off_am, off_ae, off_bm, off_be, off_enc, off_gemm, total;
+};
+
+static int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                    const hbfp_format *fa, const hbfp_format *fb, F32Plan *p) {
+    if (!fa || !fb || M <= 0 || N <= 0 || K <= 0) return HBFP_ERR_ARG;
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return HBFP_ERR_ARG;
+    int rc = transA ? hbfp_plan(fa, K, M, 0, &p->ta) : hbfp_plan(fa, M, K, 1, &p->ta);
+    if (rc != HBFP_OK) return rc;
+    rc = transB ? hbfp_plan(fb, N, K, 1, &p->tb) : hbfp_plan(fb, K, N, 0, &p->tb);
+    if (rc != HBFP_OK) return rc;
+    if (p->ta.kblock != p->tb.kblock) return HBFP_ERR_LAYOUT;
+    size_t ea = 0, eb = 0, gw = 0;
+    hbfp_encode_workspace(&p->ta, &ea);
+    hbfp_encode_workspace(&p->tb, &eb);
+    rc = hbfp_gemm_workspace(&p->ta, &p->tb, &gw);
+    if (rc != HBFP_OK) return rc;
+    size_t o = 0;
+    p->off_am = o; o += align256(p->ta.mant_bytes);
+    p->off_ae = o; o += align256(p->ta.exp_bytes);
+    p->off_bm = o; o += align256(p->tb.mant_bytes);
+    p->off_be = o; o += align256(p->tb.exp_bytes);
+    p->off_enc = o; o += align256(ea > eb ? ea : eb);
+    p->off_gemm = o; o += align256(gw);
+    p->total = o;
+    return HBFP_OK;
+}
+
+int hbfp_gemm_f32_workspace(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                            const hbfp_format *fa, const hbfp_format *fb, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    F32Plan p;
+    int rc = plan_f32(transA, transB, M, N, K, fa, fb, &p);
+    if (rc != HBFP_OK) return rc;
+    *bytes = p.total;
+    return HBFP_OK;
+}
+
+int hbfp_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                  const float *A, int64_t lda, const float *B, int64_t ldb, float *C, int64_t ldc,
+                  const hbfp_format *fa, const hbfp_format *fb,
+                  void *workspace, size_t ws_bytes, void *stream) {
+    if (!A || !B || !C) return HBFP_ERR_ARG;
+    F32Plan p;
+    int rc = plan_f32(transA, transB, M, N, K, fa, fb, &p);
+    if (rc != HBFP_OK) return rc;
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return HBFP_ERR_ARG;
+    if (!workspace || ws_bytes < p.total || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    char *w = (char *)workspace;
+    p.ta.mant = w + p.off_am;
+    p.ta.exps = (uint8_t *)(w + p.off_ae);
+    p.tb.mant = w + p.off_bm;
+    p.tb.exps = (uint8_t *)(w + p.off_be);
+    rc = check_pair(&p.ta, &p.tb);  // mantissa classes and accumulator bound, before any launch
+    if (rc != HBFP_OK) return rc;
+    const size_t enc_bytes = p.off_gemm - p.off_enc, gemm_bytes = p.total - p.off_gemm;
+    rc = transA ? hbfp_encode(A, K, M, lda, 0, fa, &p.ta, w + p.off_enc, enc_bytes, stream)
+                : hbfp_encode(A, M, K, lda, 1, fa, &p.ta, w + p.off_enc, enc_bytes, stream);
+    if (rc != HBFP_OK) return rc;
+    rc = transB ? hbfp_encode(B, N, K, ldb, 1, fb, &p.tb, w + p.off_enc, enc_bytes, stream)
+                : hbfp_encode(B, K, N, ldb, 0, fb, &p.tb, w + p.off_enc, enc_bytes, stream);
+    if (rc != HBFP_OK) return rc;
+    return hbfp_gemm(&p.ta, &p.tb, C, ldc, 0.0f, w + p.off_gemm, gemm_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,136 @@
+// BFP -> FP32, Eq. (1) of Sec. 4: value = mantissa * 2^(Eb - 125 - mant_bits).
+// int -> float of a mantissa of at most 16 bits is exact and so is the power-of-two
+// scaling (ldexp, subnormal results included), so decode is exact.
+#include "hbfp_internal.h"
+
+namespace hbfp {
+namespace {
+
+constexpr int kThreads = 256;
+
+struct DecParams {
+    const uint8_t *mant;
+    const uint8_t *exps;
+    float *dst;
+    int64_t ld, src_rows, src_cols, R, K, kblock, kbp, nblk, kpad, exp_ld;
+    int32_t axis, m;
+    int32_t chunks, lpr_log2, nseg, vec_ok, gp_log2;
+};
+
+// row path: k is contiguous in the destination; each lane turns 8 stored mantissas into 8 floats
+template <bool WIDE>
+__global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
+    const int t = threadIdx.x;
+    const int lpr = 1 << p.lpr_log2;
+    const int64_t row = (int64_t)blockIdx.x * (kThreads >> p.lpr_log2) + (t >> p.lpr_log2);
+    if (row >= p.R) return;
+    const int lr = t & (lpr - 1);
+    for (int seg = blockIdx.y; seg < p.nseg; seg += gridDim.y) {
+        const int cl = seg * lpr + lr;
+        if (cl >= p.chunks) continue;
+        const int blk = cl >> p.gp_log2, j = cl & ((1 << p.gp_log2) - 1);
+        if (blk >= p.nblk) continue;
+        const int64_t k0 = (int64_t)blk * p.kblock;
+        const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
+        const int64_t left = blen - 8 * j;
+        if (left <= 0) continue;
+        const int cnt = left >= 8 ? 8 : (int)left;
+        int q[8];
+        if (!WIDE) {
+            const uint2 d = *reinterpret_cast<const uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                q[e] = (int)(int8_t)(d.x >> (8 * e));
+                q[4 + e] = (int)(int8_t)(d.y >> (8 * e));
+            }
+        } else {
+            const uint4 d = *reinterpret_cast<const uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2);
+            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                q[2 * e] = (int)(int16_t)(w[e] & 0xffffu);
+                q[2 * e + 1] = (int)(int16_t)(w[e] >> 16);
+            }
+        }
+        const int ue = (int)p.exps[row * p.exp_ld + blk] - 125 - p.m;
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = __builtin_amdgcn_ldexpf((float)q[e], ue);
+        float *o = p.dst + row * p.ld + k0 + 8 * j;
+        if (cnt == 8 && p.vec_ok) {
+            *reinterpret_cast<float4 *>(o) = make_float4(f[0], f[1], f[2], f[3]);
+            *reinterpret_cast<float4 *>(o + 4) = make_float4(f[4], f[5], f[6], f[7]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (e < cnt) o[e] = f[e];
+        }
+    }
+}
+
+// any orientation: one thread per destination element
+template <bool WIDE>
+__global__ __launch_bounds__(kThreads) void dec_any_kernel(const DecParams p) {
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= p.src_cols) return;
+    for (int64_t r = blockIdx.y; r < p.src_rows; r += gridDim.y) {
+        const int64_t ro = p.axis == 1 ? r : c, k = p.axis == 1 ? c : r;
+        const int64_t blk = k / p.kblock, kk = k % p.kblock;
+        const int64_t off = ro * p.kpad + blk * p.kbp + kk;
+        const int q = WIDE ? (int)reinterpret_cast<const int16_t *>(p.mant)[off]
+                           : (int)reinterpret_cast<const int8_t *>(p.mant)[off];
+        const int ue = (int)p.exps[ro * p.exp_ld + blk] - 125 - p.m;
+        p.dst[r * p.ld + c] = __builtin_amdgcn_ldexpf((float)q, ue);
+    }
+}
+
+}  // namespace
+
+int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s) {
+    DecParams p;
+    p.mant = (const uint8_t *)t->mant;
+    p.exps = t->exps;
+    p.dst = dst;
+    p.ld = ld;
+    p.src_rows = t->src_rows;
+    p.src_cols = t->src_cols;
+    p.R = t->rows;
+    p.K = t->kdim;
+    p.kblock = t->kblock;
+    p.kbp = t->kblock_pad;
+    p.nblk = t->nblk;
+    p.kpad = t->kpad;
+    p.exp_ld = t->exp_ld;
+    p.axis = t->contract_axis;
+    p.m = t->mant_bits;
+    p.chunks = p.lpr_log2 = p.nseg = p.vec_ok = p.gp_log2 = 0;
+    const bool wide = t->mant_bits > 8;
+    const bool row_path = t->contract_axis == 1 && t->kblock_pad <= 128 && t->kpad / 8 <= 0x7fffffff &&
+                          t->nblk <= 0x7fffffff;
+    if (row_path) {
+        p.chunks = (int32_t)(t->kpad / 8);
+        int l2 = 0;
+        while (((int64_t)1 << l2) < p.chunks) ++l2;
+        l2 = l2 < 4 ? 4 : (l2 > 8 ? 8 : l2);
+        p.lpr_log2 = l2;
+        p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
+        p.gp_log2 = t->kblock_pad == 32 ? 2 : t->kblock_pad == 64 ? 3 : 4;
+        p.vec_ok = (((uintptr_t)dst & 15) == 0 && (ld % 4) == 0 && (t->kblock % 4) == 0) ? 1 : 0;
+        const int64_t gx = ceil_div(t->rows, (int64_t)(kThreads >> l2));
+        int64_t gy = p.nseg > 65535 ? 65535 : p.nseg;
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        if (wide) hipLaunchKernelGGL((dec_row_kernel<true>), grid, dim3(kThreads), 0, s, p);
+        else hipLaunchKernelGGL((dec_row_kernel<false>), grid, dim3(kThreads), 0, s, p);
+    } else {
+        const int64_t gx = ceil_div(t->src_cols, kThreads);
+        int64_t gy = t->src_rows > 65535 ? 65535 : t->src_rows;
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        if (wide) hipLaunchKernelGGL((dec_any_kernel<true>), grid, dim3(kThreads), 0, s, p);
+        else hipLaunchKernelGGL((dec_any_kernel<false>), grid, dim3(kThreads), 0, s, p);
+    }
+    return launch_status();
+}
+
+}  // namespace hbfp

@@ -1,0 +1,453 @@
+// FP32 -> BFP conversion kernels for gfx950 (Sec. 4.1: convert before every dot
+// product with the exponent of the largest value; Sec. 5.3: FP-to-BFP unit).
+//
+// Three paths, all writing the operand layout described in the public header:
+//   row   1-D blocks along contiguous source columns (k contiguous in the source):
+//         each lane owns 8 consecutive elements, a block is 4/8/16 neighbouring
+//         lanes, the block maximum is a DPP reduction, one pass over HBM.
+//   col   1-D blocks down the source rows (k strided in the source): each lane owns
+//         one operand row and a whole block in registers, the k-contiguous output is
+//         transposed through LDS so that global stores are full 128-byte lines.
+//   tile  everything else (2-D tiles, very long blocks): a max pass into a small
+//         per-tile array, then a quantise pass.
+#include "bfp_device.h"
+#include "hbfp_internal.h"
+
+namespace hbfp {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// max over groups of GP neighbouring lanes (GP = 4, 8, 16), result in every lane of the group
+template <int GP>
+__device__ __forceinline__ uint32_t group_max(uint32_t v) {
+    v = max(v, dpp_u32<0xB1>(v));                 // quad_perm [1,0,3,2]
+    v = max(v, dpp_u32<0x4E>(v));                 // quad_perm [2,3,0,1]
+    if (GP >= 8) v = max(v, dpp_u32<0x141>(v));   // row_half_mirror: the other quad of the 8
+    if (GP >= 16) v = max(v, dpp_u32<0x140>(v));  // row_mirror: the other half of the 16
+    return v;
+}
+
+__device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
+    return (uint32_t)(a & 0xff) | ((uint32_t)(b & 0xff) << 8) | ((uint32_t)(c & 0xff) << 16) | ((uint32_t)d << 24);
+}
+__device__ __forceinline__ uint32_t pack2_i16(int a, int b) {
+    return (uint32_t)(a & 0xffff) | ((uint32_t)b << 16);
+}
+
+// ------------------------------------------------------------------------------------------
+// row path
+struct RowParams {
+    const float *src;
+    uint8_t *mant;
+    uint8_t *exps;
+    int64_t ld, R, K, kpad, exp_ld, src_cols;
+    int32_t kblock, nblk, nb_stored, m;
+    int32_t lpr_log2;   // lanes of one row handled by a workgroup per segment = 1 << lpr_log2 (16..256)
+    int32_t chunks;     // 8-element chunks per stored row = kpad / 8
+    int32_t nseg;       // segments per row = ceil(chunks / lanes-per-row)
+    int32_t vec_ok;     // 16-byte vector loads are aligned
+    uint32_t s0, s1;
+};
+
+template <int GP, bool WIDE, int ROUND, int U>
+__global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
+    const int t = threadIdx.x;
+    const int lpr = 1 << p.lpr_log2;
+    const int64_t row = (int64_t)blockIdx.x * (kThreads >> p.lpr_log2) + (t >> p.lpr_log2);
+    const int lr = t & (lpr - 1);
+    const bool row_ok = row < p.R;
+    const float *srow = p.src + (row_ok ? row : 0) * p.ld;
+
+    for (int seg0 = blockIdx.y * U; seg0 < p.nseg; seg0 += gridDim.y * U) {
+        float v[U][8];
+        int n[U], cl[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            cl[u] = (seg0 + u) * lpr + lr;
+            const int blk = cl[u] / GP, j = cl[u] % GP;
+            int cnt = 0;
+            if (row_ok && cl[u] < p.chunks && blk < p.nblk) {
+                const int64_t k0 = (int64_t)blk * p.kblock;
+                const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
+                const int64_t left = blen - 8 * j;
+                cnt = left <= 0 ? 0 : (left >= 8 ? 8 : (int)left);
+            }
+            n[u] = cnt;
+            const float *s = srow + (int64_t)blk * p.kblock + 8 * j;
+            if (cnt == 8 && p.vec_ok) {
+                const float4 a = *reinterpret_cast<const float4 *>(s);
+                const float4 b = *reinterpret_cast<const float4 *>(s + 4);
+                v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w;
+                v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = (e < cnt) ? s[e] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int blk = cl[u] / GP, j = cl[u] % GP;
+            uint32_t amax = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
+            amax = group_max<GP>(amax);
+            const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
+            int q[8];
+            const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t idx = idx0 + e;
+                q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+                if (ROUND && e >= n[u]) q[e] = 0;
+            }
+            if (row_ok && cl[u] < p.chunks) {
+                if (!WIDE) {
+                    uint2 o;
+                    o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+                    o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                    *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl[u] * 8) = o;
+                } else {
+                    uint4 o;
+                    o.x = pack2_i16(q[0], q[1]);
+                    o.y = pack2_i16(q[2], q[3]);
+                    o.z = pack2_i16(q[4], q[5]);
+                    o.w = pack2_i16(q[6], q[7]);
+                    *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl[u] * 8) * 2) = o;
+                }
+                if (j == 0) {
+                    uint8_t *e = p.exps + row * p.exp_ld;
+                    e[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+                    if (blk == p.nb_stored - 1)
+                        for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) e[b] = 1;
+                }
+            }
+        }
+    }
+}
+
+template <int GP, bool WIDE, int ROUND>
+void launch_row_t(const RowParams &p, dim3 grid, hipStream_t s) {
+    hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 4>), grid, dim3(kThreads), 0, s, p);
+}
+
+template <int GP>
+void launch_row_g(const RowParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) launch_row_t<GP, false, 0>(p, grid, s);
+    else if (!wide) launch_row_t<GP, false, 1>(p, grid, s);
+    else if (rounding == 0) launch_row_t<GP, true, 0>(p, grid, s);
+    else launch_row_t<GP, true, 1>(p, grid, s);
+}
+
+// ------------------------------------------------------------------------------------------
+// col path
+struct ColParams {
+    const float *src;
+    uint8_t *mant;
+    uint8_t *exps;
+    int64_t ld, R, K, kpad, exp_ld, src_cols;
+    int32_t kblock, nblk, nb_stored, m;
+    uint32_t s0, s1;
+};
+
+constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
+constexpr int kColStride = 528;     // padded LDS row stride: 16-byte writes of 16 lanes hit 16 bank groups
+
+template <int KBP, bool WIDE, int ROUND>
+__global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
+    constexpr int ESZ = WIDE ? 2 : 1;
+    constexpr int NBT = kColRowBytes / (KBP * ESZ);  // exponent blocks per tile row: 16, 8, 8 or 4
+    __shared__ __attribute__((aligned(16))) uint8_t tile[64 * kColStride];
+    __shared__ __attribute__((aligned(4))) uint8_t etile[64 * NBT];
+
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t blk0 = (int64_t)blockIdx.y * NBT;
+    const bool r_ok = r < p.R;
+
+    for (int bi = wave; bi < NBT; bi += 4) {
+        const int64_t blk = blk0 + bi;
+        int blen = 0;
+        if (blk < p.nblk) {
+            const int64_t left = p.K - blk * p.kblock;
+            blen = left < p.kblock ? (int)left : p.kblock;
+        }
+        const float *s = p.src + blk * p.kblock * p.ld + (r_ok ? r : 0);
+        float v[KBP];
+#pragma unroll
+        for (int kk = 0; kk < KBP; ++kk) v[kk] = (kk < blen && r_ok) ? s[(int64_t)kk * p.ld] : 0.0f;
+        uint32_t amax = 0;
+#pragma unroll
+        for (int kk = 0; kk < KBP; ++kk) amax = max(amax, __float_as_uint(v[kk]) & 0x7fffffffu);
+        const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
+        etile[lane * NBT + bi] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+        uint8_t *out = tile + lane * kColStride + bi * KBP * ESZ;
+#pragma unroll
+        for (int kk = 0; kk < KBP; kk += 8) {
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t idx = (uint64_t)(blk * p.kblock + kk + e) * (uint64_t)p.src_cols + (uint64_t)r;
+                q[e] = quantise<ROUND>(v[kk + e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+                if (ROUND && kk + e >= blen) q[e] = 0;
+            }
+            if (!WIDE) {
+                uint2 o;
+                o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+                o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                *reinterpret_cast<uint2 *>(out + kk) = o;
+            } else {
+                uint4 o;
+                o.x = pack2_i16(q[0], q[1]);
+                o.y = pack2_i16(q[2], q[3]);
+                o.z = pack2_i16(q[4], q[5]);
+                o.w = pack2_i16(q[6], q[7]);
+                *reinterpret_cast<uint4 *>(out + kk * 2) = o;
+            }
+        }
+    }
+    __syncthreads();
+
+    // stored blocks of this tile that exist in the operand row
+    const int64_t left_blocks = p.nb_stored - blk0;
+    const int valid_bytes = (int)((left_blocks < NBT ? left_blocks : NBT) * KBP * ESZ);
+    const int piece = t & 31;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int rl = pass * 8 + (t >> 5);
+        const int64_t rr = (int64_t)blockIdx.x * 64 + rl;
+        if (rr < p.R && piece * 16 < valid_bytes) {
+            const uint4 d = *reinterpret_cast<const uint4 *>(tile + rl * kColStride + piece * 16);
+            *reinterpret_cast<uint4 *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16) = d;
+        }
+    }
+    if (t < 64 && r_ok) {
+#pragma unroll
+        for (int w = 0; w < NBT / 4; ++w) {
+            const int64_t b = blk0 + 4 * w;
+            if (b < p.exp_ld)
+                *reinterpret_cast<uint32_t *>(p.exps + r * p.exp_ld + b) =
+                    *reinterpret_cast<const uint32_t *>(etile + t * NBT + 4 * w);
+        }
+    }
+}
+
+template <int KBP>
+void launch_col_k(const ColParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 0>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 1>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, true, 0>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_col_kernel<KBP, true, 1>), grid, dim3(kThreads), 0, s, p);
+}
+
+// ------------------------------------------------------------------------------------------
+// tile path: any block shape
+struct TileParams {
+    const float *src;
+    uint8_t *mant;
+    uint8_t *exps;
+    uint32_t *tile_amax;   // [nbr][nbc] largest magnitude bit pattern per exponent block
+    int64_t ld, src_rows, src_cols, br, bc, nbr, nbc;
+    int64_t R, K, kblock, kbp, nblk, kpad, exp_ld, nb_stored;
+    int32_t axis, m;
+    uint32_t s0, s1;
+};
+
+__global__ __launch_bounds__(kThreads) void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) p[i] = v;
+}
+
+// one workgroup per (source row, 1024-column span); the max over unsigned bit patterns is
+// order independent, so the atomics leave a deterministic result
+__global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p) {
+    for (int64_t r = blockIdx.y; r < p.src_rows; r += gridDim.y) {
+        const int64_t tr = r / p.br;
+        const float *s = p.src + r * p.ld;
+        const int64_t c0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+        uint32_t a[4];
+        int64_t tc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t c = c0 + e;
+            a[e] = c < p.src_cols ? (__float_as_uint(s[c]) & 0x7fffffffu) : 0u;
+            tc[e] = (c < p.src_cols ? c : p.src_cols - 1) / p.bc;
+        }
+        if (c0 < p.src_cols) {
+            // merge neighbours that fall into the same block before touching memory
+            uint32_t run = a[0];
+#pragma unroll
+            for (int e = 1; e < 4; ++e) {
+                if (tc[e] == tc[e - 1]) {
+                    run = max(run, a[e]);
+                } else {
+                    if (run) atomicMax(p.tile_amax + tr * p.nbc + tc[e - 1], run);
+                    run = a[e];
+                }
+            }
+            if (run) atomicMax(p.tile_amax + tr * p.nbc + tc[3], run);
+        }
+    }
+}
+
+template <bool WIDE, int ROUND>
+__global__ __launch_bounds__(kThreads) void tile_quant_kernel(const TileParams p) {
+    const int64_t kp = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // stored position along k
+    if (kp >= p.kpad) return;
+    const int64_t blk = kp / p.kbp, kk = kp % p.kbp;
+    for (int64_t r = blockIdx.y; r < p.R; r += gridDim.y) {
+        int q = 0;
+        uint32_t Eb = 1;
+        if (blk < p.nblk) {
+            const int64_t kfirst = blk * p.kblock;
+            const int64_t sr0 = p.axis == 1 ? r : kfirst, sc0 = p.axis == 1 ? kfirst : r;
+            const uint32_t amax = p.tile_amax[(sr0 / p.br) * p.nbc + (sc0 / p.bc)];
+            Eb = block_exponent<ROUND>(amax, p.m);
+            const int64_t k = kfirst + kk;
+            if (kk < p.kblock && k < p.K) {
+                const int64_t sr = p.axis == 1 ? r : k, sc = p.axis == 1 ? k : r;
+                const float x = p.src[sr * p.ld + sc];
+                const uint64_t idx = (uint64_t)sr * (uint64_t)p.src_cols + (uint64_t)sc;
+                q = quantise<ROUND>(x, Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+            }
+        }
+        if (!WIDE) reinterpret_cast<int8_t *>(p.mant)[r * p.kpad + kp] = (int8_t)q;
+        else reinterpret_cast<int16_t *>(p.mant)[r * p.kpad + kp] = (int16_t)q;
+        if (kk == 0) p.exps[r * p.exp_ld + blk] = (uint8_t)Eb;
+        if (kp == 0)
+            for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) p.exps[r * p.exp_ld + b] = 1;
+    }
+}
+
+int ilog2_ceil(int64_t x) {
+    int l = 0;
+    while (((int64_t)1 << l) < x) ++l;
+    return l;
+}
+
+}  // namespace
+
+int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s) {
+    RowParams p;
+    p.src = src;
+    p.mant = (uint8_t *)mant;
+    p.exps = exps;
+    p.ld = g.ld;
+    p.R = g.R;
+    p.K = g.K;
+    p.kpad = g.kpad;
+    p.exp_ld = g.exp_ld;
+    p.src_cols = g.src_cols;
+    p.kblock = (int32_t)g.kblock;
+    p.nblk = (int32_t)g.nblk;
+    p.nb_stored = (int32_t)(g.kpad / g.kbp);
+    p.m = g.m;
+    if (g.kpad / 8 > 0x7fffffff || g.nblk > 0x7fffffff) return HBFP_ERR_ARG;
+    p.chunks = (int32_t)(g.kpad / 8);
+    int l2 = ilog2_ceil(p.chunks);
+    l2 = l2 < 4 ? 4 : (l2 > 8 ? 8 : l2);
+    p.lpr_log2 = l2;
+    p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
+    p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
+    p.s0 = g.seed_lo;
+    p.s1 = g.seed_hi;
+    const int64_t rows_per_wg = kThreads >> l2;
+    const int64_t gx = ceil_div(g.R, rows_per_wg);
+    int64_t gy = ceil_div(p.nseg, 4);
+    if (gy > 65535) gy = 65535;
+    if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+    const dim3 grid((unsigned)gx, (unsigned)gy);
+    const bool wide = g.m > 8;
+    if (g.kbp == 32) launch_row_g<4>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 64) launch_row_g<8>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 128) launch_row_g<16>(p, grid, wide, g.rounding, s);
+    else return HBFP_ERR_FORMAT;
+    return launch_status();
+}
+
+int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s) {
+    ColParams p;
+    p.src = src;
+    p.mant = (uint8_t *)mant;
+    p.exps = exps;
+    p.ld = g.ld;
+    p.R = g.R;
+    p.K = g.K;
+    p.kpad = g.kpad;
+    p.exp_ld = g.exp_ld;
+    p.src_cols = g.src_cols;
+    p.kblock = (int32_t)g.kblock;
+    if (g.nblk > 0x7fffffff) return HBFP_ERR_ARG;
+    p.nblk = (int32_t)g.nblk;
+    p.nb_stored = (int32_t)(g.kpad / g.kbp);
+    p.m = g.m;
+    p.s0 = g.seed_lo;
+    p.s1 = g.seed_hi;
+    const bool wide = g.m > 8;
+    const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
+    // cover every stored block and every exponent byte up to exp_ld
+    const int64_t nb_cover = p.nb_stored > g.exp_ld ? p.nb_stored : g.exp_ld;
+    const int64_t gx = ceil_div(g.R, 64), gy = ceil_div(nb_cover, nbt);
+    if (gx > 0x7fffffff || gy > 65535) return HBFP_ERR_ARG;
+    const dim3 grid((unsigned)gx, (unsigned)gy);
+    if (g.kbp == 32) launch_col_k<32>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 64) launch_col_k<64>(p, grid, wide, g.rounding, s);
+    else return HBFP_ERR_FORMAT;
+    return launch_status();
+}
+
+int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
+                          uint32_t *tile_amax, hipStream_t s) {
+    TileParams p;
+    p.src = src;
+    p.mant = (uint8_t *)mant;
+    p.exps = exps;
+    p.tile_amax = tile_amax;
+    p.ld = g.ld;
+    p.src_rows = g.src_rows;
+    p.src_cols = g.src_cols;
+    p.br = g.br;
+    p.bc = g.bc;
+    p.nbr = g.nbr;
+    p.nbc = g.nbc;
+    p.R = g.R;
+    p.K = g.K;
+    p.kblock = g.kblock;
+    p.kbp = g.kbp;
+    p.nblk = g.nblk;
+    p.kpad = g.kpad;
+    p.exp_ld = g.exp_ld;
+    p.nb_stored = g.kpad / g.kbp;
+    p.axis = g.axis;
+    p.m = g.m;
+    p.s0 = g.seed_lo;
+    p.s1 = g.seed_hi;
+    const int64_t ntile = g.nbr * g.nbc;
+    int64_t fb = ceil_div(ntile, kThreads);
+    if (fb > 4096) fb = 4096;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)fb), dim3(kThreads), 0, s, tile_amax, ntile, 0u);
+    {
+        const int64_t gx = ceil_div(g.src_cols, kThreads * 4);
+        int64_t gy = g.src_rows > 65535 ? 65535 : g.src_rows;
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        hipLaunchKernelGGL(tile_amax_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p);
+    }
+    {
+        const int64_t gx = ceil_div(g.kpad, kThreads);
+        int64_t gy = g.R > 65535 ? 65535 : g.R;
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        const bool wide = g.m > 8;
+        if (!wide && g.rounding == 0) hipLaunchKernelGGL((tile_quant_kernel<false, 0>), grid, dim3(kThreads), 0, s, p);
+        else if (!wide) hipLaunchKernelGGL((tile_quant_kernel<false, 1>), grid, dim3(kThreads), 0, s, p);
+        else if (g.rounding == 0) hipLaunchKernelGGL((tile_quant_kernel<true, 0>), grid, dim3(kThreads), 0, s, p);
+        else hipLaunchKernelGGL((tile_quant_kernel<true, 1>), grid, dim3(kThreads), 0, s, p);
+    }
+    return launch_status();
+}
+
+}  // namespace hbfp

@@ -1,0 +1,55 @@
+// Internal declarations shared by the host API and the kernel launchers.
+// Nothing here is part of the public ABI (see include/hbfp.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "hbfp.h"
+
+namespace hbfp {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? HBFP_OK : HBFP_ERR_LAUNCH; }
+
+// Geometry of one encode/decode call in terms of the SOURCE matrix.
+struct EncodeGeom {
+    int64_t src_rows, src_cols, ld;   // source matrix
+    int64_t br, bc;                   // exponent block extents in the source (already clamped to the matrix)
+    int64_t nbr, nbc;                 // blocks along source rows / cols
+    int32_t axis;                     // contraction axis in the source
+    // operand side
+    int64_t R, K, kblock, kbp, nblk, kpad, exp_ld, rblock;
+    int32_t m, rounding;
+    uint32_t seed_lo, seed_hi;
+};
+
+// encode.hip
+int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
+int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
+int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
+                          uint32_t *tile_amax, hipStream_t s);
+
+// decode.hip
+int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s);
+
+// gemm.hip
+struct GemmArgs {
+    const void *mantA, *mantB;        // int8 [rows][kpad] (or limb planes)
+    const uint8_t *expA, *expB;       // [rows][exp_ld]
+    int64_t M, N, kpad, expA_ld, expB_ld, nblk, kbp;
+    int32_t mA, mB;                   // mantissa bits
+    float *C;
+    int64_t ldc;
+    float beta;
+    int32_t *P;                       // non-null: dump block partials instead of C
+};
+int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
+size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp);
+int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
+size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
+
+}  // namespace hbfp

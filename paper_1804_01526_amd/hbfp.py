@@ -1,0 +1,217 @@
+"""Thin ctypes binding of ``libhbfp.so``: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory (``tensor.data_ptr()``) and the HIP stream; every
+step of the path runs in the library's kernels.  There is no CPU fallback: if the
+library has not been built, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhbfp.so")
+
+OK, ERR_ARG, ERR_FORMAT, ERR_LAYOUT, ERR_RANGE, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
+RNE, STOCHASTIC = 0, 1
+
+
+class HbfpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class Format(ctypes.Structure):
+    """hbfp_format: how a source matrix is cut into exponent blocks."""
+    _fields_ = [("mant_bits", ctypes.c_int32), ("rounding", ctypes.c_int32),
+                ("block_rows", ctypes.c_int64), ("block_cols", ctypes.c_int64), ("seed", ctypes.c_uint64)]
+
+
+class TensorDesc(ctypes.Structure):
+    """hbfp_tensor: an encoded operand (layout in include/hbfp.h)."""
+    _fields_ = [("mant", ctypes.c_void_p), ("exps", ctypes.c_void_p),
+                ("rows", ctypes.c_int64), ("kdim", ctypes.c_int64), ("kblock", ctypes.c_int64),
+                ("kblock_pad", ctypes.c_int64), ("nblk", ctypes.c_int64), ("kpad", ctypes.c_int64),
+                ("exp_ld", ctypes.c_int64), ("rblock", ctypes.c_int64),
+                ("src_rows", ctypes.c_int64), ("src_cols", ctypes.c_int64),
+                ("contract_axis", ctypes.c_int32), ("mant_bits", ctypes.c_int32),
+                ("rounding", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("seed", ctypes.c_uint64), ("mant_bytes", ctypes.c_uint64), ("exp_bytes", ctypes.c_uint64)]
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    F, T = ctypes.POINTER(Format), ctypes.POINTER(TensorDesc)
+    lib.hbfp_version.restype = i32
+    lib.hbfp_status_string.restype = ctypes.c_char_p
+    lib.hbfp_status_string.argtypes = [i32]
+    lib.hbfp_plan.argtypes = [F, i64, i64, i32, T]
+    lib.hbfp_encode_workspace.argtypes = [T, ctypes.POINTER(sz)]
+    lib.hbfp_encode.argtypes = [vp, i64, i64, i64, i32, F, T, vp, sz, vp]
+    lib.hbfp_decode.argtypes = [T, vp, i64, vp]
+    lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
+    lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
+    lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
+    lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
+    for name in ("hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+                 "hbfp_gemm", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace", "hbfp_gemm_f32"):
+        getattr(lib, name).restype = i32
+    return lib
+
+
+_lib = _load()
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def version() -> int:
+    return int(_lib.hbfp_version())
+
+
+def status_string(status: int) -> str:
+    return _lib.hbfp_status_string(status).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise HbfpError(rc, where)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def make_format(mant_bits: int, block_rows: int, block_cols: int, rounding: int = RNE, seed: int = 0) -> Format:
+    return Format(mant_bits, rounding, block_rows, block_cols, seed)
+
+
+# ---------------------------------------------------------------------------- C ABI, one to one
+def plan(fmt: Format, rows: int, cols: int, contract_axis: int) -> TensorDesc:
+    d = TensorDesc()
+    _check(_lib.hbfp_plan(ctypes.byref(fmt), rows, cols, contract_axis, ctypes.byref(d)), "hbfp_plan")
+    return d
+
+
+def encode_workspace(desc: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_workspace(ctypes.byref(desc), ctypes.byref(n)), "hbfp_encode_workspace")
+    return int(n.value)
+
+
+def gemm_workspace(a: TensorDesc, b: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_workspace(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)), "hbfp_gemm_workspace")
+    return int(n.value)
+
+
+def gemm_f32_workspace(trans_a: int, trans_b: int, M: int, N: int, K: int, fa: Format, fb: Format) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_f32_workspace(trans_a, trans_b, M, N, K, ctypes.byref(fa), ctypes.byref(fb),
+                                        ctypes.byref(n)), "hbfp_gemm_f32_workspace")
+    return int(n.value)
+
+
+@dataclass
+class BfpTensor:
+    """An encoded operand: the descriptor plus the torch buffers that back its two pointers."""
+    desc: TensorDesc
+    mant: torch.Tensor   # int8 / int16 [rows, kpad]
+    exps: torch.Tensor   # uint8 [rows, exp_ld]
+
+
+def alloc(fmt: Format, rows: int, cols: int, contract_axis: int, device="cuda") -> BfpTensor:
+    d = plan(fmt, rows, cols, contract_axis)
+    dt = torch.int8 if d.mant_bits <= 8 else torch.int16
+    mant = torch.empty((d.rows, d.kpad), dtype=dt, device=device)
+    exps = torch.empty((d.rows, d.exp_ld), dtype=torch.uint8, device=device)
+    d.mant, d.exps = mant.data_ptr(), exps.data_ptr()
+    return BfpTensor(d, mant, exps)
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return workspace
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def encode(src: torch.Tensor, contract_axis: int, fmt: Format, out: Optional[BfpTensor] = None,
+           workspace: Optional[torch.Tensor] = None, stream=None) -> BfpTensor:
+    """hbfp_encode on a 2-D FP32 device tensor (row stride = its leading dimension)."""
+    assert src.is_cuda and src.dtype == torch.float32 and src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(src.stride(0), cols)
+    if out is None:
+        out = alloc(fmt, rows, cols, contract_axis, src.device)
+    workspace = _workspace(encode_workspace(out.desc), src.device, workspace)
+    _check(_lib.hbfp_encode(_dev_ptr(src), rows, cols, ld, contract_axis, ctypes.byref(fmt), ctypes.byref(out.desc),
+                            _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                            _stream_ptr(stream)), "hbfp_encode")
+    return out
+
+
+def decode(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((t.desc.src_rows, t.desc.src_cols), dtype=torch.float32, device=t.mant.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
+    _check(_lib.hbfp_decode(ctypes.byref(t.desc), _dev_ptr(out), out.stride(0), _stream_ptr(stream)), "hbfp_decode")
+    return out
+
+
+def gemm(a: BfpTensor, b: BfpTensor, out: Optional[torch.Tensor] = None, beta: float = 0.0,
+         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """C[M,N] (+)= A . B^T over k (both operands k-contiguous)."""
+    if out is None:
+        out = torch.empty((a.desc.rows, b.desc.rows), dtype=torch.float32, device=a.mant.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
+    workspace = _workspace(gemm_workspace(a.desc, b.desc), out.device, workspace)
+    _check(_lib.hbfp_gemm(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(out), out.stride(0), beta,
+                          _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                          _stream_ptr(stream)), "hbfp_gemm")
+    return out
+
+
+def gemm_partials(a: BfpTensor, b: BfpTensor, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    P = torch.empty((a.desc.rows, b.desc.rows, a.desc.nblk), dtype=torch.int32, device=a.mant.device)
+    workspace = _workspace(gemm_workspace(a.desc, b.desc), P.device, workspace)
+    _check(_lib.hbfp_gemm_partials(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(P), _dev_ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
+           "hbfp_gemm_partials")
+    return P
+
+
+def gemm_f32(trans_a: int, trans_b: int, A: torch.Tensor, B: torch.Tensor, fa: Format, fb: Format,
+             out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """C = op(A) op(B): encode both operands along the contraction axis, then the BFP product."""
+    assert A.is_cuda and B.is_cuda and A.dtype == B.dtype == torch.float32
+    assert A.stride(1) == 1 and B.stride(1) == 1
+    M, K = (A.shape[1], A.shape[0]) if trans_a else A.shape
+    N = B.shape[0] if trans_b else B.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    workspace = _workspace(gemm_f32_workspace(trans_a, trans_b, M, N, K, fa, fb), A.device, workspace)
+    _check(_lib.hbfp_gemm_f32(trans_a, trans_b, M, N, K, _dev_ptr(A), A.stride(0), _dev_ptr(B), B.stride(0),
+                              _dev_ptr(out), out.stride(0), ctypes.byref(fa), ctypes.byref(fb),
+                              _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                              _stream_ptr(stream)), "hbfp_gemm_f32")
+    return out
