@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the BFP hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of config 4 (dense layer,
+M = K = N = 4096, 8-bit mantissas, 1 x 24 activation/gradient blocks, 24 x 24 weight
+tiles): for each of the forward, data-gradient and weight-gradient products, both
+operands are converted FP32 -> BFP and multiplied (int8 matrix cores per exponent
+block, FP32 scale-and-accumulate).  Inputs are resident in HBM before the timed
+region.  One JSON line is printed; `value` is effective TOP/s (2*M*N*K per product,
+padding not counted) including every conversion.
+
+The same line carries: the roofline of the dominant kernel (the GEMM) and of the
+encode kernel on config 2 (64M log-normal values, blocks of 32), both timed with HIP
+events on the launch stream, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, published
+HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the config 2 / 3 / 5 side measurements")
+    return ap.parse_args()
+
+
+class Timer:
+    """Accumulates HIP-event time of bracketed regions on the current stream."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}
+
+    def region(self, name):
+        t = self.torch
+        a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        self.pairs.setdefault(name, []).append((a, b))
+        return a, b
+
+    def total_ms(self, name):
+        return sum(a.elapsed_time(b) for a, b in self.pairs.get(name, []))
+
+    def count(self, name):
+        return len(self.pairs.get(name, []))
+
+
+def _linear_layer(torch, hbfp, synth):
+    """Buffers and the step function of config 4.  Nothing is allocated inside step()."""
+    M = K = N = 4096
+    Xh, Wh, dYh = synth.c4_linear(M, K, N)
+    X, W, dY = (torch.from_numpy(a).cuda() for a in (Xh, Wh, dYh))
+    f_act_row = hbfp.make_format(8, 1, 24)     # 1 x 24 blocks along a row-contiguous contraction axis
+    f_act_col = hbfp.make_format(8, 24, 1)     # the same tensors contracted down their rows (weight gradient)
+    f_w = hbfp.make_format(8, 24, 24)          # 24 x 24 weight tiles, either orientation
+
+    ops = {
+        # name: (source, contraction axis, format)
+        "x_fwd": (X, 1, f_act_row), "w_fwd": (W, 0, f_w),
+        "dy_dgrad": (dY, 1, f_act_row), "w_dgrad": (W, 1, f_w),
+        "x_wgrad": (X, 0, f_act_col), "dy_wgrad": (dY, 0, f_act_col),
+    }
+    enc = {k: hbfp.alloc(f, s.shape[0], s.shape[1], ax) for k, (s, ax, f) in ops.items()}
+    ws_enc = {k: torch.empty(max(hbfp.encode_workspace(enc[k].desc), 256), dtype=torch.uint8, device="cuda") for k in ops}
+    prods = [("x_fwd", "w_fwd"), ("dy_dgrad", "w_dgrad"), ("x_wgrad", "dy_wgrad")]
+    outs = [torch.empty((enc[a].desc.rows, enc[b].desc.rows), dtype=torch.float32, device="cuda") for a, b in prods]
+    ws_gemm = [torch.empty(max(hbfp.gemm_workspace(enc[a].desc, enc[b].desc), 256), dtype=torch.uint8, device="cuda")
+               for a, b in prods]
+
+    def step(timer=None):
+        for k, (s, ax, f) in ops.items():
+            if timer:
+                a, b = timer.region("encode_w" if k.startswith("w_") else "encode_act")
+                a.record()
+            hbfp.encode(s, ax, f, out=enc[k], workspace=ws_enc[k])
+            if timer:
+                b.record()
+        for i, (pa, pb) in enumerate(prods):
+            if timer:
+                a, b = timer.region("gemm")
+                a.record()
+            hbfp.gemm(enc[pa], enc[pb], out=outs[i], workspace=ws_gemm[i])
+            if timer:
+                b.record()
+
+    flops_per_product = 2.0 * M * N * K
+    return step, 3 * flops_per_product, flops_per_product, dict(M=M, N=N, K=K)
+
+
+def _encode_config2(torch, hbfp, synth, reps=20):
+    """Config 2: 64M log-normal values, blocks of 32; four rotating inputs (1 GiB) defeat the last-level cache."""
+    n = 1 << 26
+    x0 = torch.from_numpy(synth.c2_lognormal(n)).cuda().reshape(1, n)
+    srcs = [x0] + [x0.roll(1 + i, dims=1).contiguous() for i in range(3)]
+    res = {}
+    for m, rounding, tag in ((8, 0, "m8_rne"), (8, 1, "m8_sr"), (12, 0, "m12_rne"), (12, 1, "m12_sr")):
+        fmt = hbfp.make_format(m, 1, 32, rounding, 1234)
+        outs = [hbfp.alloc(fmt, 1, n, 1) for _ in range(4)]
+        for i in range(4):
+            hbfp.encode(srcs[i], 1, fmt, out=outs[i])
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for r in range(reps):
+            ev[r][0].record()
+            hbfp.encode(srcs[r % 4], 1, fmt, out=outs[r % 4])
+            ev[r][1].record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)[reps // 2]
+        bytes_alg = n * (4 + (1 if m <= 8 else 2)) + n // 32
+        res[f"encode_{tag}"] = {"ms": round(ms, 4), "GBps": round(bytes_alg / ms / 1e6, 1), "bytes": bytes_alg}
+        if rounding == 0:
+            dst = [torch.empty((1, n), dtype=torch.float32, device="cuda") for _ in range(4)]
+            for i in range(4):
+                hbfp.decode(outs[i], out=dst[i])
+            torch.cuda.synchronize()
+            for r in range(reps):
+                ev[r][0].record()
+                hbfp.decode(outs[r % 4], out=dst[r % 4])
+                ev[r][1].record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[reps // 2]
+            res[f"decode_m{m}"] = {"ms": round(ms, 4), "GBps": round(bytes_alg / ms / 1e6, 1), "bytes": bytes_alg}
+            del dst
+        del outs
+    return res
+
+
+def _time_call(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sorted(a.elapsed_time(b) for a, b in ev)[reps // 2]
+
+
+def _gemm_side_configs(torch, hbfp, synth, reps=10):
+    """Config 3 (conv lowered to GEMM; forward, dgrad, wgrad), kernel-only and including encodes."""
+    res = {}
+    Xh, Wh, dYh = synth.c3_conv_as_gemm()
+    X, W, dY = (torch.from_numpy(a).cuda() for a in (Xh, Wh, dYh))
+    row, col = hbfp.make_format(8, 1, 32), hbfp.make_format(8, 32, 1)
+    passes = {
+        "c3_fwd": ((X, 1, row), (W, 0, col)),
+        "c3_dgrad": ((dY, 1, row), (W, 1, row)),
+        "c3_wgrad": ((X, 0, col), (dY, 0, col)),
+    }
+    for name, ((sa, axa, fa), (sb, axb, fb)) in passes.items():
+        ta, tb = hbfp.alloc(fa, sa.shape[0], sa.shape[1], axa), hbfp.alloc(fb, sb.shape[0], sb.shape[1], axb)
+        out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")
+        hbfp.encode(sa, axa, fa, out=ta)
+        hbfp.encode(sb, axb, fb, out=tb)
+        flops = 2.0 * ta.desc.rows * tb.desc.rows * ta.desc.kdim
+        ms_k = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws), reps)
+        ms_ea = _time_call(torch, lambda: hbfp.encode(sa, axa, fa, out=ta), reps)
+        ms_eb = _time_call(torch, lambda: hbfp.encode(sb, axb, fb, out=tb), reps)
+        res[name] = {"gemm_ms": round(ms_k, 4), "encode_a_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+                     "TOPS_kernel": round(flops / ms_k / 1e9, 1),
+                     "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
+        del ta, tb, out, ws
+    return res
+
+
+def _cpu_baseline(synth):
+    """The oracle as it stands on the host cores, on a bounded sample of config 4's forward product."""
+    import numpy as np
+    from oracle import ref
+    M = K = N = 4096
+    rows = 192
+    Xh, Wh, _ = synth.c4_linear(M, K, N)
+    sel = np.arange(rows, dtype=np.int64)
+    t0 = time.perf_counter()
+    ta = ref.encode(Xh[:rows], 1, 24, 8)
+    tb = ref.encode(Wh, 24, 24, 8)
+    C = ref.gemm(ref.decode(ta), ref.decode(tb), rows=sel)
+    dt = time.perf_counter() - t0
+    assert C.shape == (rows, N)
+    return {"value": round(2.0 * rows * N * K / dt / 1e12, 5), "unit": "TOP/s", "cores": ref.num_threads(),
+            "kind": "oracle",
+            "sample": f"config 4 forward product, {rows} of {M} rows of X: encode those rows and all of W, "
+                      f"FP64 product of the dequantised operands; {dt:.1f} s"}
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU; --gpus {args.gpus} is not supported (this build has no multi-GPU path)",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    from paper_1804_01526_amd import hbfp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    step, flops_step, flops_product, shape = _linear_layer(torch, hbfp, synth)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timer = Timer(torch)
+    t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_begin.record()
+    for _ in range(args.steps):
+        step(timer)
+    t_end.record()
+    torch.cuda.synchronize()
+    ms_step = t_begin.elapsed_time(t_end) / args.steps
+    tops = flops_step / ms_step / 1e9
+
+    gemm_ms = timer.total_ms("gemm") / timer.count("gemm")
+    gemm_tops = flops_product / gemm_ms / 1e9
+    enc_act_ms = timer.total_ms("encode_act") / args.steps
+    enc_w_ms = timer.total_ms("encode_w") / args.steps
+    gemm_step_ms = timer.total_ms("gemm") / args.steps
+
+    out = {
+        "metric": "BFP8 GEMM effective TOPS incl. encode (% int8 MFMA peak); encode GB/s",
+        "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 mantissas x int32 block sums, FP32 accumulate", "data": "synthetic",
+        "config": {"workload": "config 4: dense layer M=K=N=4096, BFP8, 1x24 activation blocks, 24x24 weight tiles, "
+                               "forward + data gradient + weight gradient, all six operand encodes included", **shape},
+        "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
+        "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_activations_x4": round(enc_act_ms, 4),
+                                  "encode_weights_x2": round(enc_w_ms, 4)},
+        "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
+        "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
+                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(gemm_ms, 4),
+                     "note": "effective int8 ops 2*M*N*K per launch; blocks of 24 are padded to 32 inside the kernel"},
+    }
+    if not args.no_extra:
+        extra = _encode_config2(torch, hbfp, synth)
+        e = extra["encode_m8_rne"]
+        out["encode_GBps"] = e["GBps"]
+        out["roofline_encode"] = {"bound": "hbm", "kernel": "enc_row_kernel (config 2, m=8, RNE)", "achieved": e["GBps"],
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(e["GBps"] / HBM_PEAK_GBPS, 4),
+                                  "traffic": None, "avg_launch_ms": e["ms"]}
+        extra.update(_gemm_side_configs(torch, hbfp, synth))
+        out["extra"] = extra
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(synth)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
