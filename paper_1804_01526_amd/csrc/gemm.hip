@@ -361,8 +361,4 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     return rc;
 }
 
-size_t gemm_limb_workspace(const hbfp_tensor *, const hbfp_tensor *) { return 256; }
-
-int launch_gemm_limb(const GemmArgs &, void *, hipStream_t) { return HBFP_ERR_FORMAT; }
-
 }  // namespace hbfp

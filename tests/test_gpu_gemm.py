@@ -179,3 +179,32 @@ def test_config4_linear_layer_sampled(hb):
     _run(hb, X, W, (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)                        # forward
     _run(hb, dY, np.ascontiguousarray(W.T), (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)  # dgrad
     _run(hb, np.ascontiguousarray(X.T), dY, (1, 24, 8, 0, 0), (24, 1, 8, 0, 0), partials=False, rows=rows)   # wgrad
+
+
+@pytest.mark.parametrize("M,N,K,B,m,rounding", [
+    (100, 150, 640, 64, 12, 1), (64, 128, 256, 64, 12, 0), (130, 70, 1000, 32, 12, 0), (65, 129, 520, 24, 10, 1),
+    (96, 96, 1024, 256, 12, 0), (70, 200, 1152, 0, 9, 0), (1, 1, 64, 64, 12, 0), (200, 100, 1000, 512, 12, 1),
+])
+def test_gemm_wide_mantissas_as_two_limbs(hb, M, N, K, B, m, rounding):
+    """9..12-bit mantissas run as two int8 limbs; block sums reach 64 * 2047^2 = 2.7e8 > 2^24."""
+    A, Bm = _rand((M, K), M + 2 * K), _rand((K, N), N + 3 * K)
+    _run(hb, A, Bm, (1, B, m, rounding, 5), (B, 1, m, rounding, 6))
+
+
+def test_gemm_wide_mantissas_extreme_values(hb):
+    M, N, K = 64, 128, 512
+    A = np.full((M, K), 2047.0, dtype=np.float32)
+    B = np.full((K, N), -2047.0, dtype=np.float32)
+    B[::2] *= -1
+    A[:, ::3] *= -1
+    _run(hb, A, B, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0))
+    _run(hb, A, np.abs(B), (1, 512, 12, 0, 0), (512, 1, 12, 0, 0))      # 512 * 2047^2 = 2.15e9 - the int32 limit
+
+
+def test_config5_wide_range_bfp12_sampled(hb):
+    """Config 5 at full size: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20."""
+    import synth
+    A, B = synth.c5_wide_range()
+    rows = np.random.default_rng(6).choice(8192, size=16, replace=False)
+    rows.sort()
+    _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows)
