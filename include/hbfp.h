@@ -128,8 +128,9 @@ int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_a
 
 /*
  * hbfp_encode_workspace (host only): bytes of scratch hbfp_encode needs for this
- * plan (0 for 1-D blocks of at most 64 elements along k; otherwise 4 bytes per
- * exponent block, rounded up to 256).
+ * plan: 0 for blocks of at most 64 elements along k and at most 64 across it (128 and
+ * 1024 when k is the contiguous source axis); otherwise 4 bytes per exponent block,
+ * rounded up to 256.
  */
 int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes);
 
@@ -164,7 +165,9 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  * <= 8 bits, or both 9..12 bits, which run as two int8 limbs per mantissa).
  *   C     device FP32 [M][ldc], ldc >= N
  *   beta  0 (overwrite; C is not read) or 1 (accumulate)
- *   workspace  hbfp_gemm_workspace bytes (0 for mantissas of at most 8 bits)
+ *   workspace  hbfp_gemm_workspace bytes: 0 for mantissas of at most 8 bits unless the
+ *              shape is split along k (few output tiles, long k: one FP32 slice of C per
+ *              split); two int8 limb planes per operand for wider mantissas
  * Domain: block exponent bytes up to 254 (magnitudes below 2^127).
  * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (kdim/kblock mismatch), HBFP_ERR_FORMAT
  * (mantissa classes differ or exceed 12 bits), HBFP_ERR_RANGE (kblock * max|mA| *

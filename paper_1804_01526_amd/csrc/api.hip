@@ -79,9 +79,10 @@ int check_tensor(const hbfp_tensor *t, bool need_ptrs) {
     return HBFP_OK;
 }
 
+// Block shapes the single-pass kernels cover; everything else takes the max pass + quantise pass.
 bool needs_tile_pass(const hbfp_tensor &t) {
-    if (t.rblock != 1) return true;
-    return t.contract_axis == 1 ? t.kblock > 128 : t.kblock > 64;
+    if (t.contract_axis == 1) return t.kblock > 128 || t.rblock > 1024;
+    return t.kblock > 64 || t.rblock > 64;
 }
 
 int check_pair(const hbfp_tensor *A, const hbfp_tensor *B) {

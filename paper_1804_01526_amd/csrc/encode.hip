@@ -131,6 +131,95 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     }
 }
 
+// 2-D tiles whose k axis is contiguous in the source: a workgroup owns the rblock source rows of one
+// row of tiles and 256 chunk lanes of them.  Pass 1 takes the maximum down the rows in each lane and
+// across the lanes of a block; pass 2 reads the same (cache-resident) rows again and quantises.
+template <int GP, bool WIDE, int ROUND>
+__global__ __launch_bounds__(kThreads) void enc_row_tiled_kernel(const RowParams p, int rblock) {
+    const int t = threadIdx.x;
+    const int64_t rfirst = (int64_t)blockIdx.x * rblock;
+    int64_t rlast = rfirst + rblock;
+    rlast = rlast < p.R ? rlast : p.R;
+    for (int seg = blockIdx.y; seg < p.nseg; seg += gridDim.y) {
+        const int cl = seg * kThreads + t;
+        const bool lane_ok = cl < p.chunks;
+        const int blk = cl / GP, j = cl % GP;
+        int cnt = 0;
+        if (lane_ok && blk < p.nblk) {
+            const int64_t k0 = (int64_t)blk * p.kblock;
+            const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
+            const int64_t left = blen - 8 * j;
+            cnt = left <= 0 ? 0 : (left >= 8 ? 8 : (int)left);
+        }
+        const int64_t col = (int64_t)blk * p.kblock + 8 * j;
+        uint32_t amax = 0;
+        for (int64_t row = rfirst; row < rlast; ++row) {
+            const float *s = p.src + row * p.ld + col;
+            if (cnt == 8 && p.vec_ok) {
+                const float4 a = *reinterpret_cast<const float4 *>(s);
+                const float4 b = *reinterpret_cast<const float4 *>(s + 4);
+                amax = max(amax, max(max(__float_as_uint(a.x) & 0x7fffffffu, __float_as_uint(a.y) & 0x7fffffffu),
+                                     max(__float_as_uint(a.z) & 0x7fffffffu, __float_as_uint(a.w) & 0x7fffffffu)));
+                amax = max(amax, max(max(__float_as_uint(b.x) & 0x7fffffffu, __float_as_uint(b.y) & 0x7fffffffu),
+                                     max(__float_as_uint(b.z) & 0x7fffffffu, __float_as_uint(b.w) & 0x7fffffffu)));
+            } else {
+                for (int e = 0; e < cnt; ++e) amax = max(amax, __float_as_uint(s[e]) & 0x7fffffffu);
+            }
+        }
+        amax = group_max<GP>(amax);
+        const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
+        for (int64_t row = rfirst; row < rlast; ++row) {
+            const float *s = p.src + row * p.ld + col;
+            float v[8];
+            if (cnt == 8 && p.vec_ok) {
+                const float4 a = *reinterpret_cast<const float4 *>(s);
+                const float4 b = *reinterpret_cast<const float4 *>(s + 4);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+                v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = (e < cnt) ? s[e] : 0.0f;
+            }
+            int q[8];
+            const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)col;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t idx = idx0 + e;
+                q[e] = quantise<ROUND>(v[e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+            }
+            if (lane_ok) {
+                if (!WIDE) {
+                    uint2 o;
+                    o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+                    o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                    *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8) = o;
+                } else {
+                    uint4 o;
+                    o.x = pack2_i16(q[0], q[1]);
+                    o.y = pack2_i16(q[2], q[3]);
+                    o.z = pack2_i16(q[4], q[5]);
+                    o.w = pack2_i16(q[6], q[7]);
+                    *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2) = o;
+                }
+                if (j == 0) {
+                    uint8_t *e = p.exps + row * p.exp_ld;
+                    e[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+                    if (blk == p.nb_stored - 1)
+                        for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) e[b] = 1;
+                }
+            }
+        }
+    }
+}
+
+template <int GP>
+void launch_row_tiled_g(const RowParams &p, int rblock, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_row_tiled_kernel<GP, false, 0>), grid, dim3(kThreads), 0, s, p, rblock);
+    else if (!wide) hipLaunchKernelGGL((enc_row_tiled_kernel<GP, false, 1>), grid, dim3(kThreads), 0, s, p, rblock);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_row_tiled_kernel<GP, true, 0>), grid, dim3(kThreads), 0, s, p, rblock);
+    else hipLaunchKernelGGL((enc_row_tiled_kernel<GP, true, 1>), grid, dim3(kThreads), 0, s, p, rblock);
+}
+
 template <int GP, bool WIDE, int ROUND>
 void launch_row_t(const RowParams &p, dim3 grid, hipStream_t s) {
     hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 4>), grid, dim3(kThreads), 0, s, p);
@@ -152,6 +241,8 @@ struct ColParams {
     uint8_t *exps;
     int64_t ld, R, K, kpad, exp_ld, src_cols;
     int32_t kblock, nblk, nb_stored, m;
+    int32_t rblock;     // operand rows (lanes) sharing one exponent: 1 for 1-D blocks, up to 64 for 2-D tiles
+    int32_t lanes;      // lanes of a wave that carry operand rows: the largest multiple of rblock <= 64
     uint32_t s0, s1;
 };
 
@@ -164,11 +255,13 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     constexpr int NBT = kColRowBytes / (KBP * ESZ);  // exponent blocks per tile row: 16, 8, 8 or 4
     __shared__ __attribute__((aligned(16))) uint8_t tile[64 * kColStride];
     __shared__ __attribute__((aligned(4))) uint8_t etile[64 * NBT];
+    __shared__ uint32_t lane_amax[4][64];
 
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t r = (int64_t)blockIdx.x * p.lanes + lane;
     const int64_t blk0 = (int64_t)blockIdx.y * NBT;
-    const bool r_ok = r < p.R;
+    const bool r_ok = lane < p.lanes && r < p.R;
+    const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
 
     for (int bi = wave; bi < NBT; bi += 4) {
         const int64_t blk = blk0 + bi;
@@ -184,6 +277,13 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
         uint32_t amax = 0;
 #pragma unroll
         for (int kk = 0; kk < KBP; ++kk) amax = max(amax, __float_as_uint(v[kk]) & 0x7fffffffu);
+        if (p.rblock > 1) {
+            // 2-D tile: the maximum also runs over the rblock neighbouring operand rows (lanes of this wave)
+            lane_amax[wave][lane] = amax;
+            __builtin_amdgcn_wave_barrier();
+            for (int i = 0; i < p.rblock; ++i) amax = max(amax, lane_amax[wave][(group0 + i) & 63]);
+            __builtin_amdgcn_wave_barrier();
+        }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
         etile[lane * NBT + bi] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
         uint8_t *out = tile + lane * kColStride + bi * KBP * ESZ;
@@ -220,8 +320,8 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 #pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
         const int rl = pass * 8 + (t >> 5);
-        const int64_t rr = (int64_t)blockIdx.x * 64 + rl;
-        if (rr < p.R && piece * 16 < valid_bytes) {
+        const int64_t rr = (int64_t)blockIdx.x * p.lanes + rl;
+        if (rl < p.lanes && rr < p.R && piece * 16 < valid_bytes) {
             const uint4 d = *reinterpret_cast<const uint4 *>(tile + rl * kColStride + piece * 16);
             *reinterpret_cast<uint4 *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16) = d;
         }
@@ -355,6 +455,19 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
+    if (g.rblock > 1) {
+        p.nseg = (int32_t)ceil_div(p.chunks, kThreads);
+        const int64_t gx = ceil_div(g.R, g.rblock);
+        const int64_t gy = p.nseg > 65535 ? 65535 : p.nseg;
+        if (gx > 0x7fffffff || g.rblock > 0x7fffffff) return HBFP_ERR_ARG;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        const bool wide = g.m > 8;
+        if (g.kbp == 32) launch_row_tiled_g<4>(p, (int)g.rblock, grid, wide, g.rounding, s);
+        else if (g.kbp == 64) launch_row_tiled_g<8>(p, (int)g.rblock, grid, wide, g.rounding, s);
+        else if (g.kbp == 128) launch_row_tiled_g<16>(p, (int)g.rblock, grid, wide, g.rounding, s);
+        else return HBFP_ERR_FORMAT;
+        return launch_status();
+    }
     const int64_t rows_per_wg = kThreads >> l2;
     const int64_t gx = ceil_div(g.R, rows_per_wg);
     int64_t gy = ceil_div(p.nseg, 4);
@@ -387,11 +500,14 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.m = g.m;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
+    if (g.rblock < 1 || g.rblock > 64) return HBFP_ERR_FORMAT;
+    p.rblock = (int32_t)g.rblock;
+    p.lanes = (int32_t)((64 / g.rblock) * g.rblock);
     const bool wide = g.m > 8;
     const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
     // cover every stored block and every exponent byte up to exp_ld
     const int64_t nb_cover = p.nb_stored > g.exp_ld ? p.nb_stored : g.exp_ld;
-    const int64_t gx = ceil_div(g.R, 64), gy = ceil_div(nb_cover, nbt);
+    const int64_t gx = ceil_div(g.R, p.lanes), gy = ceil_div(nb_cover, nbt);
     if (gx > 0x7fffffff || gy > 65535) return HBFP_ERR_ARG;
     const dim3 grid((unsigned)gx, (unsigned)gy);
     if (g.kbp == 32) launch_col_k<32>(p, grid, wide, g.rounding, s);

@@ -74,9 +74,12 @@ def test_encode_workspace_sizes():
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 32, 1), 256, 64, 0)) == 0
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 1, 128), 64, 256, 1)) == 0
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 128, 1), 256, 64, 0)) > 0
-    n = hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 24, 24), 100, 100, 0))
-    assert n >= 5 * 5 * 4 and n % 256 == 0
-    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 100, 100, 1)) == 256
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 24, 24), 100, 100, 0)) == 0
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 24, 24), 100, 100, 1)) == 0
+    n = hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 96, 96), 500, 500, 0))
+    assert n >= 6 * 6 * 4 and n % 256 == 0
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 100, 100, 1)) == 0
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 2000, 2000, 1)) == 256
 
 
 def _raw():
@@ -106,7 +109,7 @@ def test_entry_points_validate_before_launching():
     assert lib.hbfp_encode(fake, 64, 256, 256, 1, byref(fmt), byref(d), None, 0, None) == hbfp.ERR_ARG
     d.mant = 0x10000
     # tile path without workspace
-    f2 = hbfp.make_format(8, 24, 24)
+    f2 = hbfp.make_format(8, 96, 96)
     d2 = hbfp.plan(f2, 100, 100, 0)
     d2.mant, d2.exps = 0x10000, 0x20000
     assert lib.hbfp_encode(fake, 100, 100, 100, 0, byref(f2), byref(d2), None, 0, None) == hbfp.ERR_WORKSPACE

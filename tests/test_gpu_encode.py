@@ -72,7 +72,8 @@ TILE_CASES = [
     (100, 100, 0, 24, 24, 8, 0), (100, 100, 1, 24, 24, 8, 0), (130, 70, 0, 24, 24, 8, 1), (70, 130, 1, 64, 64, 12, 1),
     (50, 3000, 1, 1, 0, 8, 0), (3000, 50, 0, 0, 1, 8, 0), (64, 64, 1, 0, 0, 8, 0), (200, 300, 0, 0, 0, 12, 1),
     (129, 1030, 1, 1, 200, 8, 0), (1030, 129, 0, 200, 1, 8, 1), (33, 65, 1, 2, 32, 8, 0), (65, 33, 0, 32, 2, 8, 0),
-    (48, 4100, 1, 24, 24, 8, 0),
+    (48, 4100, 1, 24, 24, 8, 0), (4100, 48, 0, 24, 24, 8, 1), (300, 200, 0, 100, 100, 8, 0), (200, 300, 1, 100, 100, 8, 1),
+    (150, 150, 0, 64, 64, 12, 0), (130, 2100, 1, 1100, 128, 8, 0), (64, 200, 0, 16, 3, 8, 0), (200, 64, 1, 3, 16, 8, 1),
 ]
 
 
