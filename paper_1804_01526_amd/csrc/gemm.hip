@@ -90,6 +90,23 @@ __device__ __forceinline__ void store_stage(const StageRegs &r, uint8_t *base, c
     }
 }
 
+// Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  XCD x gets
+// a contiguous eighth of the tiles, walked in bands of 8 tile rows column by column, so that the 64
+// tiles an XCD works on at any time are an 8 x 8 patch: 8 row panels and 8 column panels of the current
+// k range stay in that XCD's L2 and each is used 8 times.  Returns false for the padding workgroups.
+__device__ __forceinline__ bool tile_of_workgroup(int wg, int tiles_m, int tiles_n, int &tm, int &tn) {
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = (ntiles + 7) >> 3;
+    const int t = (wg & 7) * per_xcd + (wg >> 3);
+    if ((wg >> 3) >= per_xcd || t >= ntiles) return false;
+    const int band = t / (8 * tiles_n);
+    const int rows_in_band = tiles_m - band * 8 < 8 ? tiles_m - band * 8 : 8;
+    const int r = t - band * 8 * tiles_n;
+    tn = r / rows_in_band;
+    tm = band * 8 + r % rows_in_band;
+    return true;
+}
+
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (blocks span whole stages)
 template <int SPB, bool DUMP>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p) {
@@ -99,8 +116,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    const int tile = blockIdx.x;
-    const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
     const int split = blockIdx.y;
     const int st_begin = split * p.stages_per_split;
@@ -266,6 +283,223 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
             }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Blocks of at most 32 elements (one matrix instruction per exponent block): the hot case, where the
+// FP32 scale-and-accumulate, not the matrix core, sets the pace.  Same tiling as above, but laid out so
+// that nothing except the two vector instructions per output and block lands on the vector ALU:
+//   - LDS holds a stage as [k-step][row][32 bytes], so every fragment address is a per-thread base
+//     plus an immediate; the two 16-byte halves of a row swap on every eighth row, which spreads 16
+//     consecutive rows over all LDS banks;
+//   - global loads use a scalar base that advances by 128 bytes per stage and a per-thread 32-bit
+//     offset that never changes;
+//   - the k-step loop is unrolled and each matrix instruction is issued one scaling block ahead of
+//     the instructions that consume it.
+__device__ __forceinline__ void scale_accumulate(float (&acc)[16], const v16i &d, const v16i &cin, float sb) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const float x = __int_as_float(d[v]) - __int_as_float(cin[v]);   // exact: P * 2^(Ea - 150)
+        acc[v] = fmaf(x, sb, acc[v]);
+    }
+    // pin the results here: without it the compiler sinks all of a stage's scaling below the matrix
+    // instructions and spills every block sum on the way
+#pragma unroll
+    for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[v]));
+}
+
+__device__ __forceinline__ v16i read_cin(const uint8_t *w) {
+    v16i c;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const v4i c4 = *reinterpret_cast<const v4i *>(w + g * 32);
+        c[4 * g + 0] = c4[0];
+        c[4 * g + 1] = c4[1];
+        c[4 * g + 2] = c4[2];
+        c[4 * g + 3] = c4[3];
+    }
+    return c;
+}
+
+// One k-step of one operand tile in LDS: 128 rows x 32 bytes, plus 64 bytes so that the four k-steps a
+// staging thread group writes land on different banks.  LDS has 64 banks of 4 bytes: a 16-byte access is
+// conflict free when every 16 consecutive lanes cover 256 different bytes modulo 256, hence the two halves
+// of a row swap on every eighth row.
+constexpr int kStepBytes = 128 * 32 + 64;
+constexpr int kTileBytes = 4 * kStepBytes;                 // one operand tile of one stage
+constexpr int kB32StageBytes = 2 * kTileBytes + 2 * kWordBytes;
+constexpr int kB32LdsBytes = 2 * kB32StageBytes;
+
+__global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    // wave w owns rows 32 w .. 32 w + 31 of the tile and all 128 columns (1 x 4 matrix tiles): the row
+    // constants of a k-step are read from LDS once per four matrix instructions
+    const int t = threadIdx.x, lane = t & 63, wm = t >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+    const int split = blockIdx.y;
+    const int st_begin = split * p.stages_per_split;
+    int st_end = st_begin + p.stages_per_split;
+    if (st_end > p.nstage) st_end = p.nstage;
+
+    // staging roles: thread t moves 16-byte chunk (t & 7) of rows (t >> 3) + 32 i, i = 0..3, of A and of B
+    const int srow = t >> 3, schunk = t & 7;
+    uint32_t voffA[4], voffB[4];
+    int ldsoff[4];
+    const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = srow + 32 * i;
+        const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
+        const int rb = r < rows_b ? r : rows_b - 1;
+        voffA[i] = (uint32_t)ra * (uint32_t)p.kpad + schunk * 16;
+        voffB[i] = (uint32_t)rb * (uint32_t)p.kpad + schunk * 16;
+        ldsoff[i] = (schunk >> 1) * kStepBytes + r * 32 + (((schunk & 1) ^ ((r >> 3) & 1)) * 16);
+    }
+    const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
+    const bool exp_is_a = t < 128;
+    const int erow = t & 127;
+    const uint8_t *gE;
+    {
+        int64_t r = (exp_is_a ? row0 : col0) + erow;
+        const int64_t lim = exp_is_a ? p.M : p.N;
+        r = r < lim ? r : lim - 1;
+        gE = exp_is_a ? p.eA + r * p.eA_ld : p.eB + r * p.eB_ld;
+    }
+    const int word_off = 2 * kTileBytes + (exp_is_a ? 0 : kWordBytes) + erow * 4;
+
+    // per-thread LDS bases of the fragments (k-step s and column tile ni add immediates)
+    const int r_a = wm * 32 + l32;
+    const int fragA = r_a * 32 + ((lh ^ ((r_a >> 3) & 1)) * 16);
+    const int fragB = kTileBytes + l32 * 32 + ((lh ^ ((l32 >> 3) & 1)) * 16);   // + ni * 1024: (32 ni) >> 3 is even
+    const int offW = 2 * kTileBytes + (wm * 32 + 4 * lh) * 4;
+    const int offS = 2 * kTileBytes + kWordBytes + l32 * 4;
+
+    float acc[4][16];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
+
+    v4i ga[4], gb[4];
+    uint32_t gexp = 0;
+
+#define HBFP_LOAD_STAGE(st)                                                                   \
+    {                                                                                         \
+        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
+            ga[i] = *reinterpret_cast<const v4i *>(sa + voffA[i]);                            \
+            gb[i] = *reinterpret_cast<const v4i *>(sbp + voffB[i]);                           \
+        }                                                                                     \
+        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                            \
+    }
+#define HBFP_STORE_STAGE(base)                                                                \
+    {                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
+            *reinterpret_cast<v4i *>((base) + ldsoff[i]) = ga[i];                             \
+            *reinterpret_cast<v4i *>((base) + kTileBytes + ldsoff[i]) = gb[i];                \
+        }                                                                                     \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                       \
+            uint32_t e = (gexp >> (8 * s)) & 0xffu;                                           \
+            e = e > 254u ? 254u : e;                                                          \
+            uint32_t word = e << 23;                                                          \
+            if (exp_is_a) word |= 0x400000u;                                                  \
+            *reinterpret_cast<uint32_t *>((base) + word_off + s * 512) = word;                \
+        }                                                                                     \
+    }
+
+    // Software pipeline of one stage (4 k-steps) - everything that has latency is requested a step or more
+    // before it is needed, and there is one barrier per stage:
+    //   step 0, step 1            each step fetches the next step's operands from LDS before its last two
+    //                             scaling blocks (the fragment registers are free by then)
+    //   store stage st+1 -> LDS   from registers loaded during the previous stage; then request stage st+2
+    //                             from global memory into the same registers
+    //   step 2, wait, barrier     every LDS access of this wave is complete, so the other buffer may be read
+    //   step 3                    fetches step 0 of stage st+1 from the other buffer
+    // The store is safe without a barrier of its own: a wave that is past the previous stage's barrier has
+    // seen every wave finish its reads of the buffer being overwritten.
+    v4i a, b[4];
+    v16i cin[2];
+    float sb[2][4];
+#define HBFP_READ_STEP(base, s, set)                                                                    \
+    {                                                                                                   \
+        a = *reinterpret_cast<const v4i *>((base) + fragA + (s) * kStepBytes);                          \
+        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
+            b[ni] = *reinterpret_cast<const v4i *>((base) + fragB + (s) * kStepBytes + ni * 1024);      \
+        cin[set] = read_cin((base) + offW + ((s) * 128) * 4);                                           \
+        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
+            sb[set][ni] = *reinterpret_cast<const float *>((base) + offS + ((s) * 128 + ni * 32) * 4);  \
+    }
+#define HBFP_STEP(cur, NEXT_READ)                                                                       \
+    {                                                                                                   \
+        v16i d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin[cur], 0, 0, 0);                    \
+        v16i d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin[cur], 0, 0, 0);                    \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        scale_accumulate(acc[0], d0, cin[cur], sb[cur][0]);                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[2], cin[cur], 0, 0, 0);                         \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        scale_accumulate(acc[1], d1, cin[cur], sb[cur][1]);                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[3], cin[cur], 0, 0, 0);                         \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        NEXT_READ;                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        scale_accumulate(acc[2], d0, cin[cur], sb[cur][2]);                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        scale_accumulate(acc[3], d1, cin[cur], sb[cur][3]);                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+
+    if (st_begin < st_end) {
+        HBFP_LOAD_STAGE(st_begin);
+        HBFP_STORE_STAGE(lds);
+        if (st_begin + 1 < st_end) HBFP_LOAD_STAGE(st_begin + 1);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (st_begin < st_end) HBFP_READ_STEP(lds, 0, 0);
+
+    for (int st = st_begin; st < st_end; ++st) {
+        const bool more = st + 1 < st_end;
+        const uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
+        uint8_t *other = lds + (((st - st_begin) & 1) ^ 1) * kB32StageBytes;
+
+        HBFP_STEP(0, HBFP_READ_STEP(base, 1, 1));
+        HBFP_STEP(1, HBFP_READ_STEP(base, 2, 0));
+        if (more) {
+            HBFP_STORE_STAGE(other);
+            if (st + 2 < st_end) HBFP_LOAD_STAGE(st + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        HBFP_STEP(0, HBFP_READ_STEP(base, 3, 1));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        HBFP_STEP(1, if (more) HBFP_READ_STEP(other, 0, 0));
+    }
+#undef HBFP_READ_STEP
+#undef HBFP_STEP
+#undef HBFP_LOAD_STAGE
+#undef HBFP_STORE_STAGE
+
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t i = row0 + wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+            const int64_t j = col0 + ni * 32 + l32;
+            if (i < p.M && j < p.N) {
+                const float val = acc[ni][v] * p.final_scale;
+                if (p.splits > 1) p.partial[((int64_t)split * p.M + i) * p.N + j] = val;
+                else if (p.beta) p.C[i * p.ldc + j] += val;
+                else p.C[i * p.ldc + j] = val;
+            }
+        }
+}
+
 // fixed-order sum over the split-K slices: deterministic, no float atomics
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *partial, float *C, int64_t M, int64_t N,
                                                                   int64_t ldc, int splits, int beta) {
@@ -331,7 +565,7 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.nstage = (int32_t)(a.kpad / BK);
     p.spb = (int32_t)(a.kbp / 32);
     const int64_t tm = ceil_div(a.M, BM), tn = ceil_div(a.N, BN);
-    if (tm * tn > 0x7fffffff || a.kpad / BK > 0x7fffffff) return HBFP_ERR_ARG;
+    if (tm * tn > 0x7ffffff0 || a.kpad / BK > 0x7fffffff) return HBFP_ERR_ARG;
     p.tiles_m = (int32_t)tm;
     p.tiles_n = (int32_t)tn;
     p.beta = a.beta != 0.0f;
@@ -343,12 +577,24 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
         p.stages_per_split = (int32_t)(ceil_div(units, p.splits) * stages_per_block);
         p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
     }
-    const dim3 grid((unsigned)(tm * tn), (unsigned)p.splits);
+    const dim3 grid((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
     int rc;
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        rc = p.spb == 1 ? launch_t<1, false>(p, grid, s) : p.spb == 2 ? launch_t<2, false>(p, grid, s) : launch_t<0, false>(p, grid, s);
+        if (p.spb == 1 && (uint64_t)127 * (uint64_t)a.kpad + 128 < ((uint64_t)1 << 32)) {
+            static bool configured = false;
+            if (!configured) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_b32_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kB32LdsBytes) != hipSuccess)
+                    return HBFP_ERR_LAUNCH;
+                configured = true;
+            }
+            hipLaunchKernelGGL(gemm_i8_b32_kernel, grid, dim3(kThreads), kB32LdsBytes, s, p);
+            rc = launch_status();
+        } else {
+            rc = p.spb == 1 ? launch_t<1, false>(p, grid, s) : p.spb == 2 ? launch_t<2, false>(p, grid, s) : launch_t<0, false>(p, grid, s);
+        }
     }
     if (rc != HBFP_OK) return rc;
     if (!a.P && p.splits > 1) {
