@@ -28,6 +28,13 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, published
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/bench_default_hbm_traffic_counters.txt),
+# scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
+#   config 4 GEMM launch: 115674 KiB x 2.0 + 65536 KiB = 304.0 MB   (algorithmic 113.6 MB: panels re-read across XCD L2s)
+#   config 2 encode m=8 RNE launch: 131287 KiB x 2.0 + 67588 KiB = 338.1 MB   (algorithmic 337.6 MB)
+TRAFFIC_GEMM_C4_BYTES = 304.0e6
+TRAFFIC_ENCODE_C2_M8_BYTES = 338.1e6
+
 
 def _parse():
     ap = argparse.ArgumentParser()
@@ -272,9 +279,10 @@ def main():
                                   "encode_weights_x2": round(enc_w_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
         "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": round(gemm_tops, 2),
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_b32_kernel", "achieved": round(gemm_tops, 2),
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(gemm_ms, 4),
+                     "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
+                     "algorithmic_bytes": 113.6e6, "avg_launch_ms": round(gemm_ms, 4),
                      "note": "effective int8 ops 2*M*N*K per launch; blocks of 24 are padded to 32 inside the kernel"},
     }
     if not args.no_extra:
@@ -283,7 +291,8 @@ def main():
         out["encode_GBps"] = e["GBps"]
         out["roofline_encode"] = {"bound": "hbm", "kernel": "enc_row_kernel (config 2, m=8, RNE)", "achieved": e["GBps"],
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(e["GBps"] / HBM_PEAK_GBPS, 4),
-                                  "traffic": None, "avg_launch_ms": e["ms"]}
+                                  "traffic": TRAFFIC_ENCODE_C2_M8_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
+                                  "algorithmic_bytes": e["bytes"], "avg_launch_ms": e["ms"]}
         extra.update(_gemm_side_configs(torch, hbfp, synth))
         out["extra"] = extra
     if not args.no_cpu_baseline:
