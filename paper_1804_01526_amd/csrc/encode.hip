@@ -48,7 +48,7 @@ struct RowParams {
     uint8_t *exps;
     int64_t ld, R, K, kpad, exp_ld, src_cols;
     int32_t kblock, nblk, nb_stored, m;
-    int32_t lpr_log2;   // lanes of one row handled by a workgroup per segment = 1 << lpr_log2 (16..256)
+    int32_t lpr_log2;   // log2 of the chunks per row when that is a power of two, else -1
     int32_t chunks;     // 8-element chunks per stored row = kpad / 8
     int32_t nseg;       // segments per row = ceil(chunks / lanes-per-row)
     int32_t vec_ok;     // 16-byte vector loads are aligned
@@ -57,75 +57,88 @@ struct RowParams {
 
 template <int GP, bool WIDE, int ROUND, int U>
 __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
-    const int t = threadIdx.x;
-    const int lpr = 1 << p.lpr_log2;
-    const int64_t row = (int64_t)blockIdx.x * (kThreads >> p.lpr_log2) + (t >> p.lpr_log2);
-    const int lr = t & (lpr - 1);
-    const bool row_ok = row < p.R;
-    const float *srow = p.src + (row_ok ? row : 0) * p.ld;
+    // The (row, chunk) pairs of the whole operand form one flat index space: a workgroup takes U * 256
+    // consecutive chunks.  A row holds a multiple of 16 chunks, so the 4/8/16 lanes of a block never
+    // straddle rows; rows need not be a power of two long.
+    const uint64_t total = (uint64_t)p.R * (uint64_t)p.chunks;
+    const uint64_t g0 = (uint64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
 
-    for (int seg0 = blockIdx.y * U; seg0 < p.nseg; seg0 += gridDim.y * U) {
-        float v[U][8];
-        int n[U], cl[U];
+    float v[U][8];
+    int n[U], cl[U];
+    int64_t rows[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            cl[u] = (seg0 + u) * lpr + lr;
-            const int blk = cl[u] / GP, j = cl[u] % GP;
-            int cnt = 0;
-            if (row_ok && cl[u] < p.chunks && blk < p.nblk) {
-                const int64_t k0 = (int64_t)blk * p.kblock;
-                const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
-                const int64_t left = blen - 8 * j;
-                cnt = left <= 0 ? 0 : (left >= 8 ? 8 : (int)left);
-            }
-            n[u] = cnt;
-            const float *s = srow + (int64_t)blk * p.kblock + 8 * j;
-            if (cnt == 8 && p.vec_ok) {
-                const float4 a = *reinterpret_cast<const float4 *>(s);
-                const float4 b = *reinterpret_cast<const float4 *>(s + 4);
-                v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w;
-                v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[u][e] = (e < cnt) ? s[e] : 0.0f;
-            }
+    for (int u = 0; u < U; ++u) {
+        const uint64_t g = g0 + (uint64_t)u * kThreads;
+        const bool in = g < total;
+        int64_t row;
+        if (p.lpr_log2 >= 0) {                       // chunks per row is a power of two
+            row = (int64_t)(g >> p.lpr_log2);
+            cl[u] = (int)(g & (uint64_t)(p.chunks - 1));
+        } else if (total <= 0xffffffffull) {
+            const uint32_t q = (uint32_t)g / (uint32_t)p.chunks;
+            row = q;
+            cl[u] = (int)((uint32_t)g - q * (uint32_t)p.chunks);
+        } else {
+            row = (int64_t)(g / (uint64_t)p.chunks);
+            cl[u] = (int)(g - (uint64_t)row * (uint64_t)p.chunks);
         }
+        rows[u] = in ? row : -1;
+        const int blk = cl[u] / GP, j = cl[u] % GP;
+        int cnt = 0;
+        if (in && blk < p.nblk) {
+            const int64_t k0 = (int64_t)blk * p.kblock;
+            const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
+            const int64_t left = blen - 8 * j;
+            cnt = left <= 0 ? 0 : (left >= 8 ? 8 : (int)left);
+        }
+        n[u] = cnt;
+        const float *s = p.src + (in ? row : 0) * p.ld + (int64_t)blk * p.kblock + 8 * j;
+        if (cnt == 8 && p.vec_ok) {
+            const float4 a = *reinterpret_cast<const float4 *>(s);
+            const float4 b = *reinterpret_cast<const float4 *>(s + 4);
+            v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w;
+            v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
+        } else {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int blk = cl[u] / GP, j = cl[u] % GP;
-            uint32_t amax = 0;
+            for (int e = 0; e < 8; ++e) v[u][e] = (e < cnt) ? s[e] : 0.0f;
+        }
+    }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
-            amax = group_max<GP>(amax);
-            const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
-            int q[8];
-            const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+    for (int u = 0; u < U; ++u) {
+        const int blk = cl[u] / GP, j = cl[u] % GP;
+        const int64_t row = rows[u];
+        uint32_t amax = 0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint64_t idx = idx0 + e;
-                q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
-                if (ROUND && e >= n[u]) q[e] = 0;
+        for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
+        amax = group_max<GP>(amax);
+        const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
+        int q[8];
+        const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t idx = idx0 + e;
+            q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+            if (ROUND && e >= n[u]) q[e] = 0;
+        }
+        if (row >= 0) {
+            if (!WIDE) {
+                uint2 o;
+                o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+                o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl[u] * 8) = o;
+            } else {
+                uint4 o;
+                o.x = pack2_i16(q[0], q[1]);
+                o.y = pack2_i16(q[2], q[3]);
+                o.z = pack2_i16(q[4], q[5]);
+                o.w = pack2_i16(q[6], q[7]);
+                *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl[u] * 8) * 2) = o;
             }
-            if (row_ok && cl[u] < p.chunks) {
-                if (!WIDE) {
-                    uint2 o;
-                    o.x = pack4_i8(q[0], q[1], q[2], q[3]);
-                    o.y = pack4_i8(q[4], q[5], q[6], q[7]);
-                    *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl[u] * 8) = o;
-                } else {
-                    uint4 o;
-                    o.x = pack2_i16(q[0], q[1]);
-                    o.y = pack2_i16(q[2], q[3]);
-                    o.z = pack2_i16(q[4], q[5]);
-                    o.w = pack2_i16(q[6], q[7]);
-                    *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl[u] * 8) * 2) = o;
-                }
-                if (j == 0) {
-                    uint8_t *e = p.exps + row * p.exp_ld;
-                    e[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
-                    if (blk == p.nb_stored - 1)
-                        for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) e[b] = 1;
-                }
+            if (j == 0) {
+                uint8_t *e = p.exps + row * p.exp_ld;
+                e[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+                if (blk == p.nb_stored - 1)
+                    for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) e[b] = 1;
             }
         }
     }
@@ -448,10 +461,9 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.m = g.m;
     if (g.kpad / 8 > 0x7fffffff || g.nblk > 0x7fffffff) return HBFP_ERR_ARG;
     p.chunks = (int32_t)(g.kpad / 8);
-    int l2 = ilog2_ceil(p.chunks);
-    l2 = l2 < 4 ? 4 : (l2 > 8 ? 8 : l2);
-    p.lpr_log2 = l2;
-    p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
+    const int l2 = ilog2_ceil(p.chunks);
+    p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
+    p.nseg = 0;
     p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
@@ -468,12 +480,9 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
         else return HBFP_ERR_FORMAT;
         return launch_status();
     }
-    const int64_t rows_per_wg = kThreads >> l2;
-    const int64_t gx = ceil_div(g.R, rows_per_wg);
-    int64_t gy = ceil_div(p.nseg, 4);
-    if (gy > 65535) gy = 65535;
+    const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
     if (gx > 0x7fffffff) return HBFP_ERR_ARG;
-    const dim3 grid((unsigned)gx, (unsigned)gy);
+    const dim3 grid((unsigned)gx);
     const bool wide = g.m > 8;
     if (g.kbp == 32) launch_row_g<4>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 64) launch_row_g<8>(p, grid, wide, g.rounding, s);
