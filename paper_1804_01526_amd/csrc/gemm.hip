@@ -344,20 +344,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     int st_end = st_begin + p.stages_per_split;
     if (st_end > p.nstage) st_end = p.nstage;
 
-    // staging roles: thread t moves 16-byte chunk (t & 7) of rows (t >> 3) + 32 i, i = 0..3, of A and of B
-    const int srow = t >> 3, schunk = t & 7;
-    uint32_t voffA[4], voffB[4];
-    int ldsoff[4];
+    // Staging: mantissas go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+    // consecutive lanes fill consecutive LDS bytes).  Wave w moves rows 32 w .. 32 w + 31 of A and of B, one
+    // k-step plane (32 rows x 32 bytes = 1 KB) per instruction: lane l fills 16-byte slot l & 1 of row l >> 1
+    // and therefore fetches the half of the row that the swapped layout keeps in that slot.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wm);
+    const int drow = wm * 32 + (lane >> 1);
+    const int dhalf = (lane & 1) ^ ((drow >> 3) & 1);
     const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = srow + 32 * i;
-        const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
-        const int rb = r < rows_b ? r : rows_b - 1;
-        voffA[i] = (uint32_t)ra * (uint32_t)p.kpad + schunk * 16;
-        voffB[i] = (uint32_t)rb * (uint32_t)p.kpad + schunk * 16;
-        ldsoff[i] = (schunk >> 1) * kStepBytes + r * 32 + (((schunk & 1) ^ ((r >> 3) & 1)) * 16);
-    }
+    // rows past the edge re-read the last row; their results are never stored
+    const uint32_t dmaA = (uint32_t)(drow < rows_a ? drow : rows_a - 1) * (uint32_t)p.kpad + dhalf * 16;
+    const uint32_t dmaB = (uint32_t)(drow < rows_b ? drow : rows_b - 1) * (uint32_t)p.kpad + dhalf * 16;
     const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
     const bool exp_is_a = t < 128;
     const int erow = t & 127;
@@ -383,24 +380,24 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
 
-    v4i ga[4], gb[4];
     uint32_t gexp = 0;
+    typedef __attribute__((address_space(1))) const void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
 
-#define HBFP_LOAD_STAGE(st)                                                                   \
-    {                                                                                         \
-        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;    \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
-            ga[i] = *reinterpret_cast<const v4i *>(sa + voffA[i]);                            \
-            gb[i] = *reinterpret_cast<const v4i *>(sbp + voffB[i]);                           \
-        }                                                                                     \
-        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                            \
+    // request stage st: this thread's exponent bytes into a register, the mantissa planes into LDS buffer `buf`
+#define HBFP_REQUEST_STAGE(st, buf)                                                                       \
+    {                                                                                                     \
+        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                                        \
+        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;                \
+        uint8_t *la = (buf) + wave_u * 1024;                                                              \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                   \
+            __builtin_amdgcn_global_load_lds((gptr_t)(sa + s * 32 + dmaA), (lptr_t)(la + s * kStepBytes), 16, 0, 0); \
+            __builtin_amdgcn_global_load_lds((gptr_t)(sbp + s * 32 + dmaB), (lptr_t)(la + kTileBytes + s * kStepBytes), 16, 0, 0); \
+        }                                                                                                 \
     }
-#define HBFP_STORE_STAGE(base)                                                                \
+    // exponent bytes -> the 32-bit words the matrix core (A side) and the FMA (B side) use
+#define HBFP_STORE_WORDS(base)                                                                \
     {                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
-            *reinterpret_cast<v4i *>((base) + ldsoff[i]) = ga[i];                             \
-            *reinterpret_cast<v4i *>((base) + kTileBytes + ldsoff[i]) = gb[i];                \
-        }                                                                                     \
         _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                       \
             uint32_t e = (gexp >> (8 * s)) & 0xffu;                                           \
             e = e > 254u ? 254u : e;                                                          \
@@ -414,12 +411,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     // before it is needed, and there is one barrier per stage:
     //   step 0, step 1            each step fetches the next step's operands from LDS before its last two
     //                             scaling blocks (the fragment registers are free by then)
-    //   store stage st+1 -> LDS   from registers loaded during the previous stage; then request stage st+2
-    //                             from global memory into the same registers
-    //   step 2, wait, barrier     every LDS access of this wave is complete, so the other buffer may be read
+    //   words of stage st+1       exponent bytes (requested a stage ago) -> LDS words of the other buffer
+    //   step 2, wait, barrier     this wave's LDS accesses and its global->LDS loads of stage st+1 are complete
+    //   request stage st+2        into the buffer this stage used: nobody reads it any more
     //   step 3                    fetches step 0 of stage st+1 from the other buffer
-    // The store is safe without a barrier of its own: a wave that is past the previous stage's barrier has
-    // seen every wave finish its reads of the buffer being overwritten.
     v4i a, b[4];
     v16i cin[2];
     float sb[2][4];
@@ -454,36 +449,35 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     }
 
     if (st_begin < st_end) {
-        HBFP_LOAD_STAGE(st_begin);
-        HBFP_STORE_STAGE(lds);
-        if (st_begin + 1 < st_end) HBFP_LOAD_STAGE(st_begin + 1);
+        HBFP_REQUEST_STAGE(st_begin, lds);
+        HBFP_STORE_WORDS(lds);
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (st_begin + 1 < st_end) HBFP_REQUEST_STAGE(st_begin + 1, lds + kB32StageBytes);
     if (st_begin < st_end) HBFP_READ_STEP(lds, 0, 0);
 
     for (int st = st_begin; st < st_end; ++st) {
         const bool more = st + 1 < st_end;
-        const uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
+        uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
         uint8_t *other = lds + (((st - st_begin) & 1) ^ 1) * kB32StageBytes;
 
         HBFP_STEP(0, HBFP_READ_STEP(base, 1, 1));
         HBFP_STEP(1, HBFP_READ_STEP(base, 2, 0));
-        if (more) {
-            HBFP_STORE_STAGE(other);
-            if (st + 2 < st_end) HBFP_LOAD_STAGE(st + 2);
-        }
+        if (more) HBFP_STORE_WORDS(other);
         __builtin_amdgcn_sched_barrier(0);
         HBFP_STEP(0, HBFP_READ_STEP(base, 3, 1));
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        if (st + 2 < st_end) HBFP_REQUEST_STAGE(st + 2, base);
         HBFP_STEP(1, if (more) HBFP_READ_STEP(other, 0, 0));
     }
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
-#undef HBFP_LOAD_STAGE
-#undef HBFP_STORE_STAGE
+#undef HBFP_REQUEST_STAGE
+#undef HBFP_STORE_WORDS
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni)
