@@ -25,6 +25,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128, BK = 128;            // tile of C, bytes of k per stage
@@ -293,30 +295,38 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
 //   - global loads use a scalar base that advances by 128 bytes per stage and a per-thread 32-bit
 //     offset that never changes;
 //   - the k-step loop is unrolled and each matrix instruction is issued one scaling block ahead of
-//     the instructions that consume it.
+//     the instructions that consume it;
+//   - the C input of a k-step (the row constant 1.5 * 2^(Ea - 127), the same in all 32 columns) is not
+//     read from LDS, where it would be 16 registers per wave and step and the largest LDS consumer of
+//     the kernel: one bf16 matrix instruction spreads one register of row constants over the 32 x 32
+//     output layout (the constant has a 2-bit significand, so bf16 holds it exactly, and the second
+//     operand is a single one per column).
 __device__ __forceinline__ void scale_accumulate(float (&acc)[16], const v16i &d, const v16i &cin, float sb) {
+    // All 16 subtractions first, then all 16 multiply-adds: one wave issues a vector instruction every
+    // 5 clocks when the next one does not need the previous result and every 7 when it does, and with
+    // two waves per SIMD that issue rate, not the ALU, is what a block costs.
+    float x[16];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const float x = __int_as_float(d[v]) - __int_as_float(cin[v]);   // exact: P * 2^(Ea - 150)
-        acc[v] = fmaf(x, sb, acc[v]);
-    }
+    for (int v = 0; v < 16; ++v) x[v] = __int_as_float(d[v]) - __int_as_float(cin[v]);   // exact: P * 2^(Ea - 150)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x[v]));
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = fmaf(x[v], sb, acc[v]);
     // pin the results here: without it the compiler sinks all of a stage's scaling below the matrix
     // instructions and spills every block sum on the way
 #pragma unroll
     for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[v]));
 }
 
-__device__ __forceinline__ v16i read_cin(const uint8_t *w) {
-    v16i c;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const v4i c4 = *reinterpret_cast<const v4i *>(w + g * 32);
-        c[4 * g + 0] = c4[0];
-        c[4 * g + 1] = c4[1];
-        c[4 * g + 2] = c4[2];
-        c[4 * g + 3] = c4[3];
-    }
-    return c;
+// rowc holds, in its low half, the bf16 pattern of 1.5 * 2^(Ea - 127) of row (lane % 32); every other
+// 16-bit element of the first operand meets a zero of one_hot (a bf16 one at k = 0 of lanes 0..31) and
+// only has to be finite.  The product is exact, so the result is the FP32 constant in every column.
+__device__ __forceinline__ v16i row_constants(uint32_t rowc, const v4i &one_hot) {
+    v4i a4 = {(int)rowc, 0, 0, 0};
+    const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const v16f c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a4), __builtin_bit_cast(v8bf, one_hot),
+                                                           zero, 0, 0, 0);
+    return __builtin_bit_cast(v16i, c);
 }
 
 // One k-step of one operand tile in LDS: 128 rows x 32 bytes, plus 64 bytes so that the four k-steps a
@@ -344,17 +354,20 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     int st_end = st_begin + p.stages_per_split;
     if (st_end > p.nstage) st_end = p.nstage;
 
-    // Staging: mantissas go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
-    // consecutive lanes fill consecutive LDS bytes).  Wave w moves rows 32 w .. 32 w + 31 of A and of B, one
-    // k-step plane (32 rows x 32 bytes = 1 KB) per instruction: lane l fills 16-byte slot l & 1 of row l >> 1
-    // and therefore fetches the half of the row that the swapped layout keeps in that slot.
-    const int wave_u = __builtin_amdgcn_readfirstlane(wm);
-    const int drow = wm * 32 + (lane >> 1);
-    const int dhalf = (lane & 1) ^ ((drow >> 3) & 1);
+    // staging roles: thread t moves 16-byte chunk (t & 7) of rows (t >> 3) + 32 i, i = 0..3, of A and of B
+    const int srow = t >> 3, schunk = t & 7;
+    uint32_t voffA[4], voffB[4];
+    int ldsoff[4];
     const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
-    // rows past the edge re-read the last row; their results are never stored
-    const uint32_t dmaA = (uint32_t)(drow < rows_a ? drow : rows_a - 1) * (uint32_t)p.kpad + dhalf * 16;
-    const uint32_t dmaB = (uint32_t)(drow < rows_b ? drow : rows_b - 1) * (uint32_t)p.kpad + dhalf * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = srow + 32 * i;
+        const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
+        const int rb = r < rows_b ? r : rows_b - 1;
+        voffA[i] = (uint32_t)ra * (uint32_t)p.kpad + schunk * 16;
+        voffB[i] = (uint32_t)rb * (uint32_t)p.kpad + schunk * 16;
+        ldsoff[i] = (schunk >> 1) * kStepBytes + r * 32 + (((schunk & 1) ^ ((r >> 3) & 1)) * 16);
+    }
     const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
     const bool exp_is_a = t < 128;
     const int erow = t & 127;
@@ -371,8 +384,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     const int r_a = wm * 32 + l32;
     const int fragA = r_a * 32 + ((lh ^ ((r_a >> 3) & 1)) * 16);
     const int fragB = kTileBytes + l32 * 32 + ((lh ^ ((l32 >> 3) & 1)) * 16);   // + ni * 1024: (32 ni) >> 3 is even
-    const int offW = 2 * kTileBytes + (wm * 32 + 4 * lh) * 4;
+    const int offW = 2 * kTileBytes + (wm * 32 + l32) * 4;
     const int offS = 2 * kTileBytes + kWordBytes + l32 * 4;
+    const v4i one_hot = {lh ? 0 : 0x3F80, 0, 0, 0};
 
     float acc[4][16];
 #pragma unroll
@@ -380,29 +394,28 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
 
+    v4i ga[4], gb[4];
     uint32_t gexp = 0;
-    typedef __attribute__((address_space(1))) const void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
 
-    // request stage st: this thread's exponent bytes into a register, the mantissa planes into LDS buffer `buf`
-#define HBFP_REQUEST_STAGE(st, buf)                                                                       \
-    {                                                                                                     \
-        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                                        \
-        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;                \
-        uint8_t *la = (buf) + wave_u * 1024;                                                              \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                   \
-            __builtin_amdgcn_global_load_lds((gptr_t)(sa + s * 32 + dmaA), (lptr_t)(la + s * kStepBytes), 16, 0, 0); \
-            __builtin_amdgcn_global_load_lds((gptr_t)(sbp + s * 32 + dmaB), (lptr_t)(la + kTileBytes + s * kStepBytes), 16, 0, 0); \
-        }                                                                                                 \
-    }
-    // exponent bytes -> the 32-bit words the matrix core (A side) and the FMA (B side) use
-#define HBFP_STORE_WORDS(base)                                                                \
+#define HBFP_LOAD_STAGE(st)                                                                   \
     {                                                                                         \
+        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
+            ga[i] = *reinterpret_cast<const v4i *>(sa + voffA[i]);                            \
+            gb[i] = *reinterpret_cast<const v4i *>(sbp + voffB[i]);                           \
+        }                                                                                     \
+        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                            \
+    }
+#define HBFP_STORE_STAGE(base)                                                                \
+    {                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
+            *reinterpret_cast<v4i *>((base) + ldsoff[i]) = ga[i];                             \
+            *reinterpret_cast<v4i *>((base) + kTileBytes + ldsoff[i]) = gb[i];                \
+        }                                                                                     \
         _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                       \
             uint32_t e = (gexp >> (8 * s)) & 0xffu;                                           \
             e = e > 254u ? 254u : e;                                                          \
-            uint32_t word = e << 23;                                                          \
-            if (exp_is_a) word |= 0x400000u;                                                  \
+            const uint32_t word = exp_is_a ? ((e << 7) | 0x40u) : (e << 23);                  \
             *reinterpret_cast<uint32_t *>((base) + word_off + s * 512) = word;                \
         }                                                                                     \
     }
@@ -411,22 +424,27 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
     // before it is needed, and there is one barrier per stage:
     //   step 0, step 1            each step fetches the next step's operands from LDS before its last two
     //                             scaling blocks (the fragment registers are free by then)
-    //   words of stage st+1       exponent bytes (requested a stage ago) -> LDS words of the other buffer
-    //   step 2, wait, barrier     this wave's LDS accesses and its global->LDS loads of stage st+1 are complete
-    //   request stage st+2        into the buffer this stage used: nobody reads it any more
+    //   store stage st+1 -> LDS   from registers loaded during the previous stage; then request stage st+2
+    //                             from global memory into the same registers
+    //   step 2, wait, barrier     every LDS access of this wave is complete, so the other buffer may be read
     //   step 3                    fetches step 0 of stage st+1 from the other buffer
+    // The store is safe without a barrier of its own: a wave that is past the previous stage's barrier has
+    // seen every wave finish its reads of the buffer being overwritten.
     v4i a, b[4];
     v16i cin[2];
+    uint32_t rowc = 0;
     float sb[2][4];
 #define HBFP_READ_STEP(base, s, set)                                                                    \
     {                                                                                                   \
+        rowc = *reinterpret_cast<const uint32_t *>((base) + offW + ((s) * 128) * 4);                    \
         a = *reinterpret_cast<const v4i *>((base) + fragA + (s) * kStepBytes);                          \
         _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
             b[ni] = *reinterpret_cast<const v4i *>((base) + fragB + (s) * kStepBytes + ni * 1024);      \
-        cin[set] = read_cin((base) + offW + ((s) * 128) * 4);                                           \
         _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
             sb[set][ni] = *reinterpret_cast<const float *>((base) + offS + ((s) * 128 + ni * 32) * 4);  \
     }
+    // the row constants of the next step are spread out between the last two scaling blocks of this one:
+    // their LDS word was requested a scaling block earlier, and the matrix core is idle by then
 #define HBFP_STEP(cur, NEXT_READ)                                                                       \
     {                                                                                                   \
         v16i d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin[cur], 0, 0, 0);                    \
@@ -444,40 +462,44 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
         __builtin_amdgcn_sched_barrier(0);                                                              \
         scale_accumulate(acc[2], d0, cin[cur], sb[cur][2]);                                             \
         __builtin_amdgcn_sched_barrier(0);                                                              \
+        cin[(cur) ^ 1] = row_constants(rowc, one_hot);                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
         scale_accumulate(acc[3], d1, cin[cur], sb[cur][3]);                                             \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
 
     if (st_begin < st_end) {
-        HBFP_REQUEST_STAGE(st_begin, lds);
-        HBFP_STORE_WORDS(lds);
+        HBFP_LOAD_STAGE(st_begin);
+        HBFP_STORE_STAGE(lds);
+        if (st_begin + 1 < st_end) HBFP_LOAD_STAGE(st_begin + 1);
     }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    if (st_begin + 1 < st_end) HBFP_REQUEST_STAGE(st_begin + 1, lds + kB32StageBytes);
     if (st_begin < st_end) HBFP_READ_STEP(lds, 0, 0);
+    cin[0] = row_constants(rowc, one_hot);
 
     for (int st = st_begin; st < st_end; ++st) {
         const bool more = st + 1 < st_end;
-        uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
+        const uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
         uint8_t *other = lds + (((st - st_begin) & 1) ^ 1) * kB32StageBytes;
 
         HBFP_STEP(0, HBFP_READ_STEP(base, 1, 1));
         HBFP_STEP(1, HBFP_READ_STEP(base, 2, 0));
-        if (more) HBFP_STORE_WORDS(other);
+        if (more) {
+            HBFP_STORE_STAGE(other);
+            if (st + 2 < st_end) HBFP_LOAD_STAGE(st + 2);
+        }
         __builtin_amdgcn_sched_barrier(0);
         HBFP_STEP(0, HBFP_READ_STEP(base, 3, 1));
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (st + 2 < st_end) HBFP_REQUEST_STAGE(st + 2, base);
         HBFP_STEP(1, if (more) HBFP_READ_STEP(other, 0, 0));
     }
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
-#undef HBFP_REQUEST_STAGE
-#undef HBFP_STORE_WORDS
+#undef HBFP_LOAD_STAGE
+#undef HBFP_STORE_STAGE
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni)
@@ -485,6 +507,232 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmPara
         for (int v = 0; v < 16; ++v) {
             const int64_t i = row0 + wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
             const int64_t j = col0 + ni * 32 + l32;
+            if (i < p.M && j < p.N) {
+                const float val = acc[ni][v] * p.final_scale;
+                if (p.splits > 1) p.partial[((int64_t)split * p.M + i) * p.N + j] = val;
+                else if (p.beta) p.C[i * p.ldc + j] += val;
+                else p.C[i * p.ldc + j] = val;
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Blocks of at most 32 elements, second generation.  Measured on this chip, one wave issues at most one
+// vector instruction every 5 clocks while a SIMD retires one every 2.4, and a wave that stages operands
+// (global loads, LDS stores, the waits between them) issues nothing else meanwhile.  So this kernel
+//   - runs 4 waves per SIMD: workgroups of 8 waves, a wave owns 32 x 64 of the 128 x 128 tile and stays
+//     within 128 registers;
+//   - moves operands global -> LDS with the asynchronous copy instruction (no registers, no LDS stores,
+//     no wait in the wave), three copies per wave and stage, issued between the scaling blocks;
+//   - stages 64 bytes of k at a time through a ring of four LDS buffers, so a copy has three stages of
+//     compute to land;
+//   - takes the scale words (row constants as bf16, column scales as FP32) from arrays a small kernel
+//     derives from the exponent bytes beforehand, stored [block][row] so that a copy reads them
+//     contiguously.
+// LDS tile of one operand and stage: [128 rows][64 bytes]; the four 16-byte chunks of a row are XORed
+// with (row >> 2) & 3, which makes both the copy (16 rows x 64 bytes per wave) and the fragment reads
+// (16 consecutive rows, one chunk) cover all 64 banks.
+constexpr int kW8Threads = 512;
+constexpr int kHalfK = 64;                                  // bytes of k per stage
+constexpr int kHalfTile = 128 * kHalfK;                     // 8 KB: one operand
+constexpr int kHalfWords = 2 * 128 * 4;                     // 1 KB: two blocks x 128 rows
+constexpr int kHalfStage = 2 * kHalfTile + 2 * kHalfWords;  // 18 KB
+constexpr int kW8Ring = 4;
+constexpr int kW8LdsBytes = kW8Ring * kHalfStage;           // 72 KB: two workgroups per CU
+
+__device__ __forceinline__ void async_copy16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void async_copy4(const void *gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+// as row_constants above, with the 8-deep bf16 instruction (two registers per operand)
+__device__ __forceinline__ v16i row_constants8(uint32_t rowc, const v2i &one_hot) {
+    const v2i a2 = {(int)rowc, 0};
+    const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const v16f c = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, a2), __builtin_bit_cast(v4s, one_hot), zero, 0, 0, 0);
+    return __builtin_bit_cast(v16i, c);
+}
+
+// exponent bytes [rows][ld] -> scale words [slots][rows_pad]; rows past the end get the smallest scale
+__global__ __launch_bounds__(256) void scale_words_t_kernel(const uint8_t *exps, int64_t ld, int64_t rows, int64_t rows_pad,
+                                                             int slots, int is_a, uint32_t *words) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= rows_pad) return;
+    const int s0 = blockIdx.y * 16;
+#pragma unroll 4
+    for (int s = s0; s < s0 + 16 && s < slots; ++s) {
+        uint32_t e = row < rows ? exps[row * ld + s] : 1u;
+        e = e > 254u ? 254u : e;
+        words[(int64_t)s * rows_pad + row] = is_a ? ((e << 7) | 0x40u) : (e << 23);
+    }
+}
+
+struct W8Params {
+    GemmParams g;
+    const uint32_t *wA, *wB;     // scale words [kpad / 32][rows_pad]
+    int64_t mpad, npad;
+};
+
+__global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const GemmParams &p = q.g;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave & 3, wn = wave >> 2;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+    const int split = blockIdx.y;
+    const int st_begin = 2 * split * p.stages_per_split;                         // in 64-byte stages
+    int st_end = st_begin + 2 * p.stages_per_split;
+    if (st_end > 2 * p.nstage) st_end = 2 * p.nstage;
+    const int nst = st_end - st_begin;
+
+    // ---- copy roles.  Mantissas: wave w moves rows 16 w .. 16 w + 15 of A and of B, lane -> (row, LDS chunk).
+    // Words: waves 0..3 move the row words of A, waves 4..7 the column words of B, 64 rows of one block each.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint32_t voffA, voffB, voffW;
+    {
+        const int r = 16 * wave + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((r >> 2) & 3);
+        const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
+        const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
+        const int rb = r < rows_b ? r : rows_b - 1;
+        voffA = (uint32_t)ra * (uint32_t)p.kpad + chunk * 16;
+        voffB = (uint32_t)rb * (uint32_t)p.kpad + chunk * 16;
+        voffW = lane * 4;
+    }
+    const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
+    const int wc = wave_u & 3;                                                   // word copy: block wc >> 1, rows 64 (wc & 1) ..
+    const uint32_t *wordsrc = wave_u < 4 ? q.wA + row0 + 64 * (wc & 1) : q.wB + col0 + 64 * (wc & 1);
+    const int64_t wordpitch = wave_u < 4 ? q.mpad : q.npad;
+    const uint32_t ldsM = wave_u * 1024;
+    const uint32_t ldsW = 2 * kHalfTile + (wave_u < 4 ? 0 : kHalfWords) + (wc >> 1) * 512 + (wc & 1) * 256;
+
+#define HBFP_COPY_STAGE(st, ring)                                                                       \
+    {                                                                                                   \
+        const uint32_t lb = (ring) * kHalfStage;                                                        \
+        async_copy16(tileA + (int64_t)(st) * kHalfK, voffA, lb + ldsM);                                 \
+        async_copy16(tileB + (int64_t)(st) * kHalfK, voffB, lb + kHalfTile + ldsM);                     \
+        async_copy4(wordsrc + (2 * (int64_t)(st) + (wc >> 1)) * wordpitch, voffW, lb + ldsW);           \
+    }
+#define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+
+    // ---- fragment addresses in ring buffer 0 (k-step 1 flips the 32-byte half of the row)
+    const int r_a = wm * 32 + l32, r_b = wn * 64 + l32;            // second column tile: + 32 rows = + 2048 bytes
+    const int fragA0 = r_a * 64 + (((2 * 0 + lh) ^ ((r_a >> 2) & 3)) * 16);
+    const int fragB0 = kHalfTile + r_b * 64 + (((2 * 0 + lh) ^ ((r_b >> 2) & 3)) * 16);
+    const int fragA1 = fragA0 ^ 32, fragB1 = ((fragB0 - kHalfTile) ^ 32) + kHalfTile;
+    const int offW = 2 * kHalfTile + r_a * 4;                      // + 512 for k-step 1
+    const int offS = 2 * kHalfTile + kHalfWords + r_b * 4;         // + 512 for k-step 1, + 128 for the second column tile
+    const v2i one_hot = {lh ? 0 : 0x3F80, 0};
+
+    float acc[2][16];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
+
+    v4i a, b[2];
+    v16i cin;
+    uint32_t rowc = 0;
+    float sb[2][2];
+#define HBFP_READ_STEP(ring, s, set)                                                                          \
+    {                                                                                                         \
+        const uint8_t *base_ = lds + (ring) * kHalfStage;                                                     \
+        rowc = *reinterpret_cast<const uint32_t *>(base_ + offW + (s) * 512);                                 \
+        a = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragA1 : fragA0));                                  \
+        b[0] = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragB1 : fragB0));                               \
+        b[1] = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragB1 : fragB0) + 2048);                        \
+        sb[set][0] = *reinterpret_cast<const float *>(base_ + offS + (s) * 512);                              \
+        sb[set][1] = *reinterpret_cast<const float *>(base_ + offS + (s) * 512 + 128);                        \
+    }
+    // One k-step: both matrix instructions, then whatever has to happen between issue and use (MIDDLE:
+    // the stage hand-over and the next step's LDS reads), then 32 subtractions, the next step's row
+    // constants on the matrix core, and 32 multiply-adds that cover its latency.
+#define HBFP_STEP(cur, MIDDLE)                                                                          \
+    {                                                                                                   \
+        v16i d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin, 0, 0, 0);                         \
+        v16i d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin, 0, 0, 0);                         \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        MIDDLE;                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        float x0[16], x1[16];                                                                           \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) x0[v] = __int_as_float(d0[v]) - __int_as_float(cin[v]); \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) x1[v] = __int_as_float(d1[v]) - __int_as_float(cin[v]); \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x0[v]));                  \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));                  \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        cin = row_constants8(rowc, one_hot);                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[0][v] = fmaf(x0[v], sb[cur][0], acc[0][v]);  \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[1][v] = fmaf(x1[v], sb[cur][1], acc[1][v]);  \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[0][v]));              \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[1][v]));              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    }
+    // Stage st lives in ring buffer (st - st_begin) & 3.  The hand-over sits in k-step 1 right after its
+    // matrix instructions are issued: by then this wave has consumed every LDS read of the stage, so
+    // after the barrier the buffer is free for stage st + 4, and stage st + 1 has landed for everyone
+    // (copies complete in issue order: all but the newest two groups of three).
+#define HBFP_STAGE(ring)                                                                                \
+    {                                                                                                   \
+        HBFP_STEP(0, HBFP_READ_STEP(ring, 1, 1));                                                       \
+        HBFP_STEP(1, {                                                                                  \
+            const int rem = st_end - 1 - st;                                                            \
+            if (rem > 0) {                                                                              \
+                if (rem >= 3) HBFP_WAIT_COPIES(6); else if (rem == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0); \
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                      \
+                __builtin_amdgcn_s_barrier();                                                           \
+                asm volatile("" ::: "memory");                                                          \
+                if (rem >= 4) HBFP_COPY_STAGE(st + 4, ring);                                            \
+                HBFP_READ_STEP(((ring) + 1) & 3, 0, 0);                                                 \
+            }                                                                                           \
+        });                                                                                             \
+    }
+
+    if (nst > 0) {
+        HBFP_COPY_STAGE(st_begin, 0);
+        if (nst > 1) HBFP_COPY_STAGE(st_begin + 1, 1);
+        if (nst > 2) HBFP_COPY_STAGE(st_begin + 2, 2);
+        if (nst > 3) HBFP_COPY_STAGE(st_begin + 3, 3);
+        if (nst > 3) HBFP_WAIT_COPIES(9); else if (nst == 3) HBFP_WAIT_COPIES(6); else if (nst == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0);
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (nst > 0) {
+        HBFP_READ_STEP(0, 0, 0);
+        cin = row_constants8(rowc, one_hot);
+    }
+    for (int st = st_begin; st < st_end;) {
+        HBFP_STAGE(0);
+        if (++st >= st_end) break;
+        HBFP_STAGE(1);
+        if (++st >= st_end) break;
+        HBFP_STAGE(2);
+        if (++st >= st_end) break;
+        HBFP_STAGE(3);
+        ++st;
+    }
+#undef HBFP_READ_STEP
+#undef HBFP_STEP
+#undef HBFP_STAGE
+#undef HBFP_COPY_STAGE
+#undef HBFP_WAIT_COPIES
+
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t i = row0 + wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+            const int64_t j = col0 + wn * 64 + ni * 32 + l32;
             if (i < p.M && j < p.N) {
                 const float val = acc[ni][v] * p.final_scale;
                 if (p.splits > 1) p.partial[((int64_t)split * p.M + i) * p.N + j] = val;
@@ -533,11 +781,20 @@ static int choose_splits(int64_t M, int64_t N, int64_t nstage, int64_t stages_pe
     return s < 1 ? 1 : (int)s;
 }
 
+// the asynchronous-copy kernel addresses an operand tile with 32-bit offsets
+static bool use_w8(int64_t kpad, int64_t kbp) { return kbp == 32 && (uint64_t)127 * (uint64_t)kpad + 128 < ((uint64_t)1 << 32); }
+static size_t split_bytes(int64_t M, int64_t N, int splits) {
+    return splits <= 1 ? 0 : ((size_t)splits * (size_t)M * (size_t)N * 4 + 255) & ~(size_t)255;
+}
+static size_t word_bytes(int64_t rows, int64_t kpad) { return (size_t)(kpad / 32) * (size_t)(ceil_div(rows, 128) * 128) * 4; }
+
+// workspace: [split-K slices][row words of A][column words of B]
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp) {
     const int64_t nstage = kpad / BK, spb = kbp / 32;
     const int splits = choose_splits(M, N, nstage, spb >= 4 ? spb / 4 : 1);
-    if (splits <= 1) return 0;
-    return ((size_t)splits * (size_t)M * (size_t)N * 4 + 255) & ~(size_t)255;
+    size_t n = split_bytes(M, N, splits);
+    if (use_w8(kpad, kbp)) n += word_bytes(M, kpad) + word_bytes(N, kpad);
+    return n;
 }
 
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
@@ -576,15 +833,28 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        if (p.spb == 1 && (uint64_t)127 * (uint64_t)a.kpad + 128 < ((uint64_t)1 << 32)) {
+        if (use_w8(a.kpad, a.kbp)) {
             static bool configured = false;
             if (!configured) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_b32_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kB32LdsBytes) != hipSuccess)
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_w8_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kW8LdsBytes) != hipSuccess)
                     return HBFP_ERR_LAUNCH;
                 configured = true;
             }
-            hipLaunchKernelGGL(gemm_i8_b32_kernel, grid, dim3(kThreads), kB32LdsBytes, s, p);
+            if (!workspace) return HBFP_ERR_WORKSPACE;
+            W8Params q;
+            q.g = p;
+            q.mpad = ceil_div(a.M, 128) * 128;
+            q.npad = ceil_div(a.N, 128) * 128;
+            uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
+            q.wA = (const uint32_t *)w;
+            q.wB = (const uint32_t *)(w + word_bytes(a.M, a.kpad));
+            const int slots = (int)(a.kpad / 32);
+            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(q.mpad / 256 + 1), (unsigned)ceil_div(slots, 16)), dim3(256), 0, s,
+                               a.expA, a.expA_ld, a.M, q.mpad, slots, 1, const_cast<uint32_t *>(q.wA));
+            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(q.npad / 256 + 1), (unsigned)ceil_div(slots, 16)), dim3(256), 0, s,
+                               a.expB, a.expB_ld, a.N, q.npad, slots, 0, const_cast<uint32_t *>(q.wB));
+            hipLaunchKernelGGL(gemm_i8_w8_kernel, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             rc = launch_status();
         } else {
             rc = p.spb == 1 ? launch_t<1, false>(p, grid, s) : p.spb == 2 ? launch_t<2, false>(p, grid, s) : launch_t<0, false>(p, grid, s);
