@@ -26,7 +26,6 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128, BK = 128;            // tile of C, bytes of k per stage
@@ -287,248 +286,27 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
 
 // ------------------------------------------------------------------------------------------------
 // Blocks of at most 32 elements (one matrix instruction per exponent block): the hot case, where the
-// FP32 scale-and-accumulate, not the matrix core, sets the pace.  Same tiling as above, but laid out so
-// that nothing except the two vector instructions per output and block lands on the vector ALU:
-//   - LDS holds a stage as [k-step][row][32 bytes], so every fragment address is a per-thread base
-//     plus an immediate; the two 16-byte halves of a row swap on every eighth row, which spreads 16
-//     consecutive rows over all LDS banks;
-//   - global loads use a scalar base that advances by 128 bytes per stage and a per-thread 32-bit
-//     offset that never changes;
-//   - the k-step loop is unrolled and each matrix instruction is issued one scaling block ahead of
-//     the instructions that consume it;
-//   - the C input of a k-step (the row constant 1.5 * 2^(Ea - 127), the same in all 32 columns) is not
-//     read from LDS, where it would be 16 registers per wave and step and the largest LDS consumer of
-//     the kernel: one bf16 matrix instruction spreads one register of row constants over the 32 x 32
-//     output layout (the constant has a 2-bit significand, so bf16 holds it exactly, and the second
-//     operand is a single one per column).
-__device__ __forceinline__ void scale_accumulate(float (&acc)[16], const v16i &d, const v16i &cin, float sb) {
-    // All 16 subtractions first, then all 16 multiply-adds: one wave issues a vector instruction every
-    // 5 clocks when the next one does not need the previous result and every 7 when it does, and with
-    // two waves per SIMD that issue rate, not the ALU, is what a block costs.
-    float x[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) x[v] = __int_as_float(d[v]) - __int_as_float(cin[v]);   // exact: P * 2^(Ea - 150)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x[v]));
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = fmaf(x[v], sb, acc[v]);
-    // pin the results here: without it the compiler sinks all of a stage's scaling below the matrix
-    // instructions and spills every block sum on the way
-#pragma unroll
-    for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[v]));
-}
-
-// rowc holds, in its low half, the bf16 pattern of 1.5 * 2^(Ea - 127) of row (lane % 32); every other
-// 16-bit element of the first operand meets a zero of one_hot (a bf16 one at k = 0 of lanes 0..31) and
-// only has to be finite.  The product is exact, so the result is the FP32 constant in every column.
-__device__ __forceinline__ v16i row_constants(uint32_t rowc, const v4i &one_hot) {
-    v4i a4 = {(int)rowc, 0, 0, 0};
-    const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const v16f c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a4), __builtin_bit_cast(v8bf, one_hot),
-                                                           zero, 0, 0, 0);
-    return __builtin_bit_cast(v16i, c);
-}
-
-// One k-step of one operand tile in LDS: 128 rows x 32 bytes, plus 64 bytes so that the four k-steps a
-// staging thread group writes land on different banks.  LDS has 64 banks of 4 bytes: a 16-byte access is
-// conflict free when every 16 consecutive lanes cover 256 different bytes modulo 256, hence the two halves
-// of a row swap on every eighth row.
-constexpr int kStepBytes = 128 * 32 + 64;
-constexpr int kTileBytes = 4 * kStepBytes;                 // one operand tile of one stage
-constexpr int kB32StageBytes = 2 * kTileBytes + 2 * kWordBytes;
-constexpr int kB32LdsBytes = 2 * kB32StageBytes;
-
-__global__ __launch_bounds__(kThreads, 2) void gemm_i8_b32_kernel(const GemmParams p) {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-
-    // wave w owns rows 32 w .. 32 w + 31 of the tile and all 128 columns (1 x 4 matrix tiles): the row
-    // constants of a k-step are read from LDS once per four matrix instructions
-    const int t = threadIdx.x, lane = t & 63, wm = t >> 6;
-    const int l32 = lane & 31, lh = lane >> 5;
-
-    int tm, tn;
-    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
-    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-    const int split = blockIdx.y;
-    const int st_begin = split * p.stages_per_split;
-    int st_end = st_begin + p.stages_per_split;
-    if (st_end > p.nstage) st_end = p.nstage;
-
-    // staging roles: thread t moves 16-byte chunk (t & 7) of rows (t >> 3) + 32 i, i = 0..3, of A and of B
-    const int srow = t >> 3, schunk = t & 7;
-    uint32_t voffA[4], voffB[4];
-    int ldsoff[4];
-    const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = srow + 32 * i;
-        const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
-        const int rb = r < rows_b ? r : rows_b - 1;
-        voffA[i] = (uint32_t)ra * (uint32_t)p.kpad + schunk * 16;
-        voffB[i] = (uint32_t)rb * (uint32_t)p.kpad + schunk * 16;
-        ldsoff[i] = (schunk >> 1) * kStepBytes + r * 32 + (((schunk & 1) ^ ((r >> 3) & 1)) * 16);
-    }
-    const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
-    const bool exp_is_a = t < 128;
-    const int erow = t & 127;
-    const uint8_t *gE;
-    {
-        int64_t r = (exp_is_a ? row0 : col0) + erow;
-        const int64_t lim = exp_is_a ? p.M : p.N;
-        r = r < lim ? r : lim - 1;
-        gE = exp_is_a ? p.eA + r * p.eA_ld : p.eB + r * p.eB_ld;
-    }
-    const int word_off = 2 * kTileBytes + (exp_is_a ? 0 : kWordBytes) + erow * 4;
-
-    // per-thread LDS bases of the fragments (k-step s and column tile ni add immediates)
-    const int r_a = wm * 32 + l32;
-    const int fragA = r_a * 32 + ((lh ^ ((r_a >> 3) & 1)) * 16);
-    const int fragB = kTileBytes + l32 * 32 + ((lh ^ ((l32 >> 3) & 1)) * 16);   // + ni * 1024: (32 ni) >> 3 is even
-    const int offW = 2 * kTileBytes + (wm * 32 + l32) * 4;
-    const int offS = 2 * kTileBytes + kWordBytes + l32 * 4;
-    const v4i one_hot = {lh ? 0 : 0x3F80, 0, 0, 0};
-
-    float acc[4][16];
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
-
-    v4i ga[4], gb[4];
-    uint32_t gexp = 0;
-
-#define HBFP_LOAD_STAGE(st)                                                                   \
-    {                                                                                         \
-        const uint8_t *sa = tileA + (int64_t)(st) * BK, *sbp = tileB + (int64_t)(st) * BK;    \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
-            ga[i] = *reinterpret_cast<const v4i *>(sa + voffA[i]);                            \
-            gb[i] = *reinterpret_cast<const v4i *>(sbp + voffB[i]);                           \
-        }                                                                                     \
-        gexp = *reinterpret_cast<const uint32_t *>(gE + (st) * 4);                            \
-    }
-#define HBFP_STORE_STAGE(base)                                                                \
-    {                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                       \
-            *reinterpret_cast<v4i *>((base) + ldsoff[i]) = ga[i];                             \
-            *reinterpret_cast<v4i *>((base) + kTileBytes + ldsoff[i]) = gb[i];                \
-        }                                                                                     \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                       \
-            uint32_t e = (gexp >> (8 * s)) & 0xffu;                                           \
-            e = e > 254u ? 254u : e;                                                          \
-            const uint32_t word = exp_is_a ? ((e << 7) | 0x40u) : (e << 23);                  \
-            *reinterpret_cast<uint32_t *>((base) + word_off + s * 512) = word;                \
-        }                                                                                     \
-    }
-
-    // Software pipeline of one stage (4 k-steps) - everything that has latency is requested a step or more
-    // before it is needed, and there is one barrier per stage:
-    //   step 0, step 1            each step fetches the next step's operands from LDS before its last two
-    //                             scaling blocks (the fragment registers are free by then)
-    //   store stage st+1 -> LDS   from registers loaded during the previous stage; then request stage st+2
-    //                             from global memory into the same registers
-    //   step 2, wait, barrier     every LDS access of this wave is complete, so the other buffer may be read
-    //   step 3                    fetches step 0 of stage st+1 from the other buffer
-    // The store is safe without a barrier of its own: a wave that is past the previous stage's barrier has
-    // seen every wave finish its reads of the buffer being overwritten.
-    v4i a, b[4];
-    v16i cin[2];
-    uint32_t rowc = 0;
-    float sb[2][4];
-#define HBFP_READ_STEP(base, s, set)                                                                    \
-    {                                                                                                   \
-        rowc = *reinterpret_cast<const uint32_t *>((base) + offW + ((s) * 128) * 4);                    \
-        a = *reinterpret_cast<const v4i *>((base) + fragA + (s) * kStepBytes);                          \
-        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
-            b[ni] = *reinterpret_cast<const v4i *>((base) + fragB + (s) * kStepBytes + ni * 1024);      \
-        _Pragma("unroll") for (int ni = 0; ni < 4; ++ni)                                                \
-            sb[set][ni] = *reinterpret_cast<const float *>((base) + offS + ((s) * 128 + ni * 32) * 4);  \
-    }
-    // the row constants of the next step are spread out between the last two scaling blocks of this one:
-    // their LDS word was requested a scaling block earlier, and the matrix core is idle by then
-#define HBFP_STEP(cur, NEXT_READ)                                                                       \
-    {                                                                                                   \
-        v16i d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin[cur], 0, 0, 0);                    \
-        v16i d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin[cur], 0, 0, 0);                    \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        scale_accumulate(acc[0], d0, cin[cur], sb[cur][0]);                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[2], cin[cur], 0, 0, 0);                         \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        scale_accumulate(acc[1], d1, cin[cur], sb[cur][1]);                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[3], cin[cur], 0, 0, 0);                         \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        NEXT_READ;                                                                                      \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        scale_accumulate(acc[2], d0, cin[cur], sb[cur][2]);                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        cin[(cur) ^ 1] = row_constants(rowc, one_hot);                                                  \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        scale_accumulate(acc[3], d1, cin[cur], sb[cur][3]);                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-    }
-
-    if (st_begin < st_end) {
-        HBFP_LOAD_STAGE(st_begin);
-        HBFP_STORE_STAGE(lds);
-        if (st_begin + 1 < st_end) HBFP_LOAD_STAGE(st_begin + 1);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    if (st_begin < st_end) HBFP_READ_STEP(lds, 0, 0);
-    cin[0] = row_constants(rowc, one_hot);
-
-    for (int st = st_begin; st < st_end; ++st) {
-        const bool more = st + 1 < st_end;
-        const uint8_t *base = lds + ((st - st_begin) & 1) * kB32StageBytes;
-        uint8_t *other = lds + (((st - st_begin) & 1) ^ 1) * kB32StageBytes;
-
-        HBFP_STEP(0, HBFP_READ_STEP(base, 1, 1));
-        HBFP_STEP(1, HBFP_READ_STEP(base, 2, 0));
-        if (more) {
-            HBFP_STORE_STAGE(other);
-            if (st + 2 < st_end) HBFP_LOAD_STAGE(st + 2);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        HBFP_STEP(0, HBFP_READ_STEP(base, 3, 1));
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        HBFP_STEP(1, if (more) HBFP_READ_STEP(other, 0, 0));
-    }
-#undef HBFP_READ_STEP
-#undef HBFP_STEP
-#undef HBFP_LOAD_STAGE
-#undef HBFP_STORE_STAGE
-
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t i = row0 + wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-            const int64_t j = col0 + ni * 32 + l32;
-            if (i < p.M && j < p.N) {
-                const float val = acc[ni][v] * p.final_scale;
-                if (p.splits > 1) p.partial[((int64_t)split * p.M + i) * p.N + j] = val;
-                else if (p.beta) p.C[i * p.ldc + j] += val;
-                else p.C[i * p.ldc + j] = val;
-            }
-        }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Blocks of at most 32 elements, second generation.  Measured on this chip, one wave issues at most one
-// vector instruction every 5 clocks while a SIMD retires one every 2.4, and a wave that stages operands
-// (global loads, LDS stores, the waits between them) issues nothing else meanwhile.  So this kernel
+// FP32 scale-and-accumulate, not the matrix core, sets the pace: 64 vector instructions per wave and
+// k-step against two matrix instructions.  Measured on this chip, one wave issues at most one vector
+// instruction every 5 clocks whatever else it does, a SIMD with four such waves retires close to one per
+// clock, and a wave that stages operands itself (global loads, LDS stores, the waits between them)
+// issues nothing else meanwhile.  So this kernel
 //   - runs 4 waves per SIMD: workgroups of 8 waves, a wave owns 32 x 64 of the 128 x 128 tile and stays
-//     within 128 registers;
+//     within 128 registers; it relies on the other waves, not on software pipelining, to cover the
+//     latency of its matrix instructions and LDS reads;
 //   - moves operands global -> LDS with the asynchronous copy instruction (no registers, no LDS stores,
-//     no wait in the wave), three copies per wave and stage, issued between the scaling blocks;
+//     no wait in the wave), three copies per wave and stage, issued right after the stage hand-over;
 //   - stages 64 bytes of k at a time through a ring of four LDS buffers, so a copy has three stages of
 //     compute to land;
+//   - does not read the C input of a k-step (the row constant 1.5 * 2^(Ea - 127), the same in all 32
+//     columns) from LDS, where it would be 16 registers per wave and step: one bf16 matrix instruction
+//     spreads one register of row constants over the 32 x 32 output layout (the constant has a 2-bit
+//     significand, so bf16 holds it exactly, and the second operand is a single one per column);
 //   - takes the scale words (row constants as bf16, column scales as FP32) from arrays a small kernel
 //     derives from the exponent bytes beforehand, stored [block][row] so that a copy reads them
-//     contiguously.
+//     contiguously;
+//   - does all 32 subtractions of a k-step before its 32 multiply-adds: a wave issues back-to-back
+//     dependent vector instructions every 7 clocks instead of 5.
 // LDS tile of one operand and stage: [128 rows][64 bytes]; the four 16-byte chunks of a row are XORed
 // with (row >> 2) & 3, which makes both the copy (16 rows x 64 bytes per wave) and the fragment reads
 // (16 consecutive rows, one chunk) cover all 64 banks.
@@ -550,25 +328,37 @@ __device__ __forceinline__ void async_copy4(const void *gbase, uint32_t voff, ui
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 
-// as row_constants above, with the 8-deep bf16 instruction (two registers per operand)
-__device__ __forceinline__ v16i row_constants8(uint32_t rowc, const v2i &one_hot) {
+// rowc holds, in its low half, the bf16 pattern of 1.5 * 2^(Ea - 127) of row (lane % 32); every other
+// 16-bit element of the first operand meets a zero of one_hot (a bf16 one at k = 0 of lanes 0..31) and
+// only has to be finite.  The product is exact, so the result is the FP32 constant in every column.
+__device__ __forceinline__ v16i row_constants(uint32_t rowc, const v2i &one_hot) {
     const v2i a2 = {(int)rowc, 0};
     const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const v16f c = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, a2), __builtin_bit_cast(v4s, one_hot), zero, 0, 0, 0);
     return __builtin_bit_cast(v16i, c);
 }
 
-// exponent bytes [rows][ld] -> scale words [slots][rows_pad]; rows past the end get the smallest scale
-__global__ __launch_bounds__(256) void scale_words_t_kernel(const uint8_t *exps, int64_t ld, int64_t rows, int64_t rows_pad,
-                                                             int slots, int is_a, uint32_t *words) {
-    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (row >= rows_pad) return;
-    const int s0 = blockIdx.y * 16;
-#pragma unroll 4
-    for (int s = s0; s < s0 + 16 && s < slots; ++s) {
-        uint32_t e = row < rows ? exps[row * ld + s] : 1u;
+// exponent bytes [rows][ld] -> scale words [slots][rows_pad] for both operands in one launch (blockIdx.z
+// picks the operand); rows past the end get the smallest scale.  A thread turns four consecutive blocks
+// of one row (one 32-bit load: ld and slots are multiples of 4) into four words; consecutive lanes take
+// consecutive rows, so the stores are contiguous.
+struct WordParams {
+    const uint8_t *exps[2];
+    uint32_t *words[2];
+    int64_t ld[2], rows[2], rows_pad[2];
+    int slots, row_blocks;
+};
+__global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
+    const int z = blockIdx.z;
+    const int64_t row = (int64_t)(blockIdx.x % w.row_blocks) * 256 + threadIdx.x;
+    if (row >= w.rows_pad[z]) return;
+    const int s0 = (blockIdx.x / w.row_blocks) * 4;
+    const uint32_t e4 = row < w.rows[z] ? *reinterpret_cast<const uint32_t *>(w.exps[z] + row * w.ld[z] + s0) : 0x01010101u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t e = (e4 >> (8 * i)) & 0xffu;
         e = e > 254u ? 254u : e;
-        words[(int64_t)s * rows_pad + row] = is_a ? ((e << 7) | 0x40u) : (e << 23);
+        w.words[z][(int64_t)(s0 + i) * w.rows_pad[z] + row] = z == 0 ? ((e << 7) | 0x40u) : (e << 23);
     }
 }
 
@@ -670,7 +460,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x0[v]));                  \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));                  \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        cin = row_constants8(rowc, one_hot);                                                            \
+        cin = row_constants(rowc, one_hot);                                                            \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[0][v] = fmaf(x0[v], sb[cur][0], acc[0][v]);  \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[1][v] = fmaf(x1[v], sb[cur][1], acc[1][v]);  \
@@ -709,7 +499,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     asm volatile("" ::: "memory");
     if (nst > 0) {
         HBFP_READ_STEP(0, 0, 0);
-        cin = row_constants8(rowc, one_hot);
+        cin = row_constants(rowc, one_hot);
     }
     for (int st = st_begin; st < st_end;) {
         HBFP_STAGE(0);
@@ -849,11 +639,17 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
             uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
             q.wA = (const uint32_t *)w;
             q.wB = (const uint32_t *)(w + word_bytes(a.M, a.kpad));
-            const int slots = (int)(a.kpad / 32);
-            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(q.mpad / 256 + 1), (unsigned)ceil_div(slots, 16)), dim3(256), 0, s,
-                               a.expA, a.expA_ld, a.M, q.mpad, slots, 1, const_cast<uint32_t *>(q.wA));
-            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(q.npad / 256 + 1), (unsigned)ceil_div(slots, 16)), dim3(256), 0, s,
-                               a.expB, a.expB_ld, a.N, q.npad, slots, 0, const_cast<uint32_t *>(q.wB));
+            WordParams wp;
+            wp.exps[0] = a.expA; wp.exps[1] = a.expB;
+            wp.words[0] = const_cast<uint32_t *>(q.wA); wp.words[1] = const_cast<uint32_t *>(q.wB);
+            wp.ld[0] = a.expA_ld; wp.ld[1] = a.expB_ld;
+            wp.rows[0] = a.M; wp.rows[1] = a.N;
+            wp.rows_pad[0] = q.mpad; wp.rows_pad[1] = q.npad;
+            wp.slots = (int)(a.kpad / 32);
+            const int64_t maxpad = q.mpad > q.npad ? q.mpad : q.npad;
+            wp.row_blocks = (int)ceil_div(maxpad, 256);
+            if ((int64_t)wp.row_blocks * (wp.slots / 4) > 0x7fffffff) return HBFP_ERR_ARG;
+            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(wp.row_blocks * (wp.slots / 4)), 1, 2), dim3(256), 0, s, wp);
             hipLaunchKernelGGL(gemm_i8_w8_kernel, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             rc = launch_status();
         } else {
