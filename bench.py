@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X FP32 vector peak, published (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/bench_default_hbm_traffic_counters.txt),
@@ -42,6 +43,7 @@ def _parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph instead of 12 separate launches")
     ap.add_argument("--no-extra", action="store_true", help="skip the config 2 / 3 / 5 side measurements")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run can scale FETCH_SIZE/WRITE_SIZE")
@@ -107,7 +109,7 @@ def _linear_layer(torch, hbfp, synth):
                 b.record()
 
     flops_per_product = 2.0 * M * N * K
-    return step, 3 * flops_per_product, flops_per_product, dict(M=M, N=N, K=K)
+    return step, 3 * flops_per_product, flops_per_product, dict(M=M, N=N, K=K), outs
 
 
 def _encode_config2(torch, hbfp, synth, reps=20):
@@ -239,22 +241,50 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    step, flops_step, flops_product, shape = _linear_layer(torch, hbfp, synth)
+    step, flops_step, flops_product, shape, outs = _linear_layer(torch, hbfp, synth)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    timer = Timer(torch)
+    run_step = step
+    if args.graph:
+        # one HIP graph of the 12 launches of a step (no memset nodes: the library clears nothing with
+        # hipMemsetAsync on this path); replayed outputs are checked against the eager ones below
+        eager = [o.clone() for o in outs]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+        for _ in range(2):
+            for o in outs:
+                o.zero_()
+            run_step()
+            torch.cuda.synchronize()
+            assert all(torch.equal(o, e) for o, e in zip(outs, eager)), "graph replay differs from the eager step"
     t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     t_begin.record()
     for _ in range(args.steps):
-        step(timer)
+        run_step()
     t_end.record()
+    torch.cuda.synchronize()
+    # the same steps again with HIP events around every call, for the per-kernel figures
+    timer = Timer(torch)
+    for _ in range(args.steps):
+        step(timer)
     torch.cuda.synchronize()
     ms_step = t_begin.elapsed_time(t_end) / args.steps
     tops = flops_step / ms_step / 1e9
 
     gemm_ms = timer.total_ms("gemm") / timer.count("gemm")
     gemm_tops = flops_product / gemm_ms / 1e9
+    nblk = -(-shape["K"] // 24)
+    alu_flop = 3.0 * shape["M"] * shape["N"] * nblk
+    alu_tflops = alu_flop / (gemm_ms * 1e-3) / 1e12
     enc_act_ms = timer.total_ms("encode_act") / args.steps
     enc_w_ms = timer.total_ms("encode_w") / args.steps
     gemm_step_ms = timer.total_ms("gemm") / args.steps
@@ -279,11 +309,21 @@ def main():
                                   "encode_weights_x2": round(enc_w_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
         "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_b32_kernel", "achieved": round(gemm_tops, 2),
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+        # Blocks of 24 (padded to 32) mean one matrix instruction (65536 int8 ops) per 32 x 32 outputs and block,
+        # against 2 FP32 vector instructions (a subtraction and a multiply-add: 3 flop) per output and block for
+        # the scaling: the vector ALU, not the matrix core, bounds this kernel, so that is the roofline stated;
+        # the matrix-core fraction is given beside it.
+        "roofline": {"bound": "alu", "kernel": "gemm_i8_w8_kernel", "achieved": round(alu_tflops, 2),
+                     "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(alu_tflops / FP32_VECTOR_PEAK_TFLOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
                      "algorithmic_bytes": 113.6e6, "avg_launch_ms": round(gemm_ms, 4),
-                     "note": "effective int8 ops 2*M*N*K per launch; blocks of 24 are padded to 32 inside the kernel"},
+                     "algorithmic_flop_per_launch": alu_flop,
+                     "issue_slot_frac": round(2.0 * shape["M"] * shape["N"] * nblk / (gemm_ms * 1e-3) / (FP32_VECTOR_PEAK_TFLOPS * 0.5e12), 4),
+                     "int8_TOPS": round(gemm_tops, 2), "int8_matrix_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "note": "3 flop (v_sub_f32 + v_fmac_f32) per output element and exponent block, 171 blocks of 24 along K; "
+                             "issue_slot_frac counts the 2 instructions against the peak instruction rate (a subtraction fills a "
+                             "slot but is 1 flop); avg_launch_ms is the HIP-event time of one product call = this kernel plus a "
+                             "5 us kernel that expands exponent bytes to scale words"},
     }
     if not args.no_extra:
         extra = _encode_config2(torch, hbfp, synth)
