@@ -18,14 +18,11 @@
 //   2. one subtraction removes the constant (exact), one FMA multiplies by the column
 //      scale 2^(Eb - 127) and accumulates.
 // The remaining constant 2^(27 - mA - mB) is applied once when C is stored.
-#include "hbfp_internal.h"
+#include "gemm_common.h"
 
 namespace hbfp {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128, BK = 128;            // tile of C, bytes of k per stage
@@ -89,23 +86,6 @@ __device__ __forceinline__ void store_stage(const StageRegs &r, uint8_t *base, c
         if (exp_is_a) word = DUMP ? 0u : (word | 0x400000u);    // A side: the float 1.5 * 2^(E - 127)
         w[s * 128 + erow] = word;
     }
-}
-
-// Workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  XCD x gets
-// a contiguous eighth of the tiles, walked in bands of 8 tile rows column by column, so that the 64
-// tiles an XCD works on at any time are an 8 x 8 patch: 8 row panels and 8 column panels of the current
-// k range stay in that XCD's L2 and each is used 8 times.  Returns false for the padding workgroups.
-__device__ __forceinline__ bool tile_of_workgroup(int wg, int tiles_m, int tiles_n, int &tm, int &tn) {
-    const int ntiles = tiles_m * tiles_n;
-    const int per_xcd = (ntiles + 7) >> 3;
-    const int t = (wg & 7) * per_xcd + (wg >> 3);
-    if ((wg >> 3) >= per_xcd || t >= ntiles) return false;
-    const int band = t / (8 * tiles_n);
-    const int rows_in_band = tiles_m - band * 8 < 8 ? tiles_m - band * 8 : 8;
-    const int r = t - band * 8 * tiles_n;
-    tn = r / rows_in_band;
-    tm = band * 8 + r % rows_in_band;
-    return true;
 }
 
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (blocks span whole stages)
@@ -317,50 +297,6 @@ constexpr int kHalfWords = 2 * 128 * 4;                     // 1 KB: two blocks 
 constexpr int kHalfStage = 2 * kHalfTile + 2 * kHalfWords;  // 18 KB
 constexpr int kW8Ring = 4;
 constexpr int kW8LdsBytes = kW8Ring * kHalfStage;           // 72 KB: two workgroups per CU
-
-__device__ __forceinline__ void async_copy16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
-}
-__device__ __forceinline__ void async_copy4(const void *gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
-}
-
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-
-// rowc holds, in its low half, the bf16 pattern of 1.5 * 2^(Ea - 127) of row (lane % 32); every other
-// 16-bit element of the first operand meets a zero of one_hot (a bf16 one at k = 0 of lanes 0..31) and
-// only has to be finite.  The product is exact, so the result is the FP32 constant in every column.
-__device__ __forceinline__ v16i row_constants(uint32_t rowc, const v2i &one_hot) {
-    const v2i a2 = {(int)rowc, 0};
-    const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const v16f c = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(v4s, a2), __builtin_bit_cast(v4s, one_hot), zero, 0, 0, 0);
-    return __builtin_bit_cast(v16i, c);
-}
-
-// exponent bytes [rows][ld] -> scale words [slots][rows_pad] for both operands in one launch (blockIdx.z
-// picks the operand); rows past the end get the smallest scale.  A thread turns four consecutive blocks
-// of one row (one 32-bit load: ld and slots are multiples of 4) into four words; consecutive lanes take
-// consecutive rows, so the stores are contiguous.
-struct WordParams {
-    const uint8_t *exps[2];
-    uint32_t *words[2];
-    int64_t ld[2], rows[2], rows_pad[2];
-    int slots, row_blocks;
-};
-__global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
-    const int z = blockIdx.z;
-    const int64_t row = (int64_t)(blockIdx.x % w.row_blocks) * 256 + threadIdx.x;
-    if (row >= w.rows_pad[z]) return;
-    const int s0 = (blockIdx.x / w.row_blocks) * 4;
-    const uint32_t e4 = row < w.rows[z] ? *reinterpret_cast<const uint32_t *>(w.exps[z] + row * w.ld[z] + s0) : 0x01010101u;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t e = (e4 >> (8 * i)) & 0xffu;
-        e = e > 254u ? 254u : e;
-        w.words[z][(int64_t)(s0 + i) * w.rows_pad[z] + row] = z == 0 ? ((e << 7) | 0x40u) : (e << 23);
-    }
-}
 
 struct W8Params {
     GemmParams g;
@@ -576,14 +512,13 @@ static bool use_w8(int64_t kpad, int64_t kbp) { return kbp == 32 && (uint64_t)12
 static size_t split_bytes(int64_t M, int64_t N, int splits) {
     return splits <= 1 ? 0 : ((size_t)splits * (size_t)M * (size_t)N * 4 + 255) & ~(size_t)255;
 }
-static size_t word_bytes(int64_t rows, int64_t kpad) { return (size_t)(kpad / 32) * (size_t)(ceil_div(rows, 128) * 128) * 4; }
 
 // workspace: [split-K slices][row words of A][column words of B]
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp) {
     const int64_t nstage = kpad / BK, spb = kbp / 32;
     const int splits = choose_splits(M, N, nstage, spb >= 4 ? spb / 4 : 1);
     size_t n = split_bytes(M, N, splits);
-    if (use_w8(kpad, kbp)) n += word_bytes(M, kpad) + word_bytes(N, kpad);
+    if (use_w8(kpad, kbp)) n += word_bytes(M, kpad / 32) + word_bytes(N, kpad / 32);
     return n;
 }
 
@@ -638,18 +573,10 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
             q.npad = ceil_div(a.N, 128) * 128;
             uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
             q.wA = (const uint32_t *)w;
-            q.wB = (const uint32_t *)(w + word_bytes(a.M, a.kpad));
-            WordParams wp;
-            wp.exps[0] = a.expA; wp.exps[1] = a.expB;
-            wp.words[0] = const_cast<uint32_t *>(q.wA); wp.words[1] = const_cast<uint32_t *>(q.wB);
-            wp.ld[0] = a.expA_ld; wp.ld[1] = a.expB_ld;
-            wp.rows[0] = a.M; wp.rows[1] = a.N;
-            wp.rows_pad[0] = q.mpad; wp.rows_pad[1] = q.npad;
-            wp.slots = (int)(a.kpad / 32);
-            const int64_t maxpad = q.mpad > q.npad ? q.mpad : q.npad;
-            wp.row_blocks = (int)ceil_div(maxpad, 256);
-            if ((int64_t)wp.row_blocks * (wp.slots / 4) > 0x7fffffff) return HBFP_ERR_ARG;
-            hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(wp.row_blocks * (wp.slots / 4)), 1, 2), dim3(256), 0, s, wp);
+            q.wB = (const uint32_t *)(w + word_bytes(a.M, a.kpad / 32));
+            rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)(a.kpad / 32), 0x40u,
+                                    const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), s);
+            if (rc != HBFP_OK) return rc;
             hipLaunchKernelGGL(gemm_i8_w8_kernel, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             rc = launch_status();
         } else {

@@ -10,13 +10,10 @@
 //
 // A workgroup of 4 waves owns 64 x 128 of C, a wave 32 x 64 (1 x 2 tiles of
 // v_mfma_i32_32x32x32_i8); a stage is 64 bytes of k of both limb planes of both operands.
-#include "hbfp_internal.h"
+#include "gemm_common.h"
 
 namespace hbfp {
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 64, BN = 128, BK = 64;
@@ -254,6 +251,186 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_limb_kernel(const LimbParams
         }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Blocks of 64 (the 12-bit configuration): same organisation as the 8-bit kernel for short blocks -
+// 8 waves per workgroup at 4 waves per SIMD, asynchronous global -> LDS copies through a ring of LDS
+// buffers, one barrier per stage, row scales spread over the output layout by one bf16 matrix
+// instruction per block.  A workgroup owns 64 x 128 of C, a wave 32 x 32; a stage is one exponent block
+// (64 bytes of k of the four limb planes, 24 KB, plus one scale word per operand row), three stages
+// live in LDS.  Per wave and block: 8 matrix instructions, then 5 vector instructions per output.
+constexpr int kLwThreads = 512;
+constexpr int kLwAH = 0, kLwAL = 4096, kLwBH = 8192, kLwBL = 16384;   // [rows][64 bytes], 16-byte chunks XORed with (row >> 2) & 3
+constexpr int kLwWA = 24576, kLwWB = 24832;                            // 64 row words, 128 column words
+constexpr int kLwStage = 25344;
+constexpr int kLwRing = 3;
+constexpr int kLwLdsBytes = kLwRing * kLwStage;                        // 74.25 KB: two workgroups per CU
+
+struct LimbW8Params {
+    LimbParams g;
+    const uint32_t *wA, *wB;     // scale words [block][rows rounded up to 128]: 2^(E - 127) as bf16 / as FP32
+    int64_t mpad, npad;
+    int32_t tiles_m;
+};
+
+__global__ __launch_bounds__(kLwThreads, 4) void gemm_limb_w8_kernel(const LimbW8Params q) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const LimbParams &p = q.g;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x, q.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+    const int nst = p.nstage;
+
+    // ---- copy roles, four per wave and stage: 16 rows of one A plane (wave >> 2 picks the plane), the
+    // same 16 rows of both B planes, and 64 scale words (waves 0, 3, 6: A rows; 1, 4, 7 and 2, 5: the two
+    // halves of the B rows; duplicates write the same words)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint32_t voffA, voffB;
+    {
+        const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
+        const int ra_ = 16 * (wave & 3) + (lane >> 2), rb_ = 16 * wave + (lane >> 2);
+        const int ra = ra_ < rows_a ? ra_ : rows_a - 1;   // rows past the edge re-read the last row; never stored
+        const int rb = rb_ < rows_b ? rb_ : rows_b - 1;
+        voffA = (uint32_t)ra * (uint32_t)p.kpad + (((lane & 3) ^ ((ra_ >> 2) & 3)) * 16);
+        voffB = (uint32_t)rb * (uint32_t)p.kpad + (((lane & 3) ^ ((rb_ >> 2) & 3)) * 16);
+    }
+    const uint32_t voffW = lane * 4;
+    const uint8_t *planeA = (wave_u >> 2 ? p.AL : p.AH) + row0 * p.kpad;
+    const uint8_t *planeBH = p.BH + col0 * p.kpad, *planeBL = p.BL + col0 * p.kpad;
+    const int wsel = wave_u % 3;
+    const uint32_t *wordsrc = wsel == 0 ? q.wA + row0 : q.wB + col0 + 64 * (wsel - 1);
+    const int64_t wordpitch = wsel == 0 ? q.mpad : q.npad;
+    const uint32_t ldsA = (wave_u >> 2 ? kLwAL : kLwAH) + (wave_u & 3) * 1024;
+    const uint32_t ldsB = wave_u * 1024;
+    const uint32_t ldsW = wsel == 0 ? kLwWA : kLwWB + 256 * (wsel - 1);
+
+#define HBFP_COPY_STAGE(st, ring)                                                                       \
+    {                                                                                                   \
+        const uint32_t lb = (ring) * kLwStage;                                                          \
+        async_copy16(planeA + (int64_t)(st) * BK, voffA, lb + ldsA);                                    \
+        async_copy16(planeBH + (int64_t)(st) * BK, voffB, lb + kLwBH + ldsB);                           \
+        async_copy16(planeBL + (int64_t)(st) * BK, voffB, lb + kLwBL + ldsB);                           \
+        async_copy4(wordsrc + (int64_t)(st) * wordpitch, voffW, lb + ldsW);                             \
+    }
+#define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+
+    // ---- fragment addresses in ring buffer 0; k-step 1 flips the 32-byte half of the row
+    const int r_a = wm * 32 + l32, r_b = wn * 32 + l32;
+    const int fragA = r_a * 64 + ((lh ^ ((r_a >> 2) & 3)) * 16);
+    const int fragB = kLwBH + r_b * 64 + ((lh ^ ((r_b >> 2) & 3)) * 16);
+    const int offW = kLwWA + r_a * 4, offS = kLwWB + r_b * 4;
+    const v2i one_hot = {lh ? 0 : 0x3F80, 0};
+
+    float acc[16];
+    v16i hh, mid, ll;
+    v16i zero;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        acc[v] = 0.0f;
+        zero[v] = 0;
+    }
+    v4i aH, aL, bH, bL;
+    uint32_t rowc = 0;
+    float sb = 0.0f;
+#define HBFP_READ_FRAGS(ring, s)                                                                        \
+    {                                                                                                   \
+        const uint8_t *base_ = lds + (ring) * kLwStage;                                                 \
+        aH = *reinterpret_cast<const v4i *>(base_ + (fragA ^ ((s) * 32)));                              \
+        aL = *reinterpret_cast<const v4i *>(base_ + (fragA ^ ((s) * 32)) + kLwAL);                      \
+        bH = *reinterpret_cast<const v4i *>(base_ + (fragB ^ ((s) * 32)));                              \
+        bL = *reinterpret_cast<const v4i *>(base_ + (fragB ^ ((s) * 32)) + (kLwBL - kLwBH));            \
+    }
+#define HBFP_READ_WORDS(ring)                                                                           \
+    {                                                                                                   \
+        const uint8_t *base_ = lds + (ring) * kLwStage;                                                 \
+        rowc = *reinterpret_cast<const uint32_t *>(base_ + offW);                                       \
+        sb = *reinterpret_cast<const float *>(base_ + offS);                                            \
+    }
+    // One stage = one exponent block.  The hand-over sits right after the block's last matrix
+    // instructions: every LDS read of the stage is consumed by then, so after the barrier its buffer
+    // takes stage st + 3, and stage st + 1 has landed for everyone (copies complete in issue order: all
+    // but the newest group of four).  The recombination and scaling of the block then cover the latency
+    // of the next stage's first fragments.
+#define HBFP_STAGE(ring)                                                                                \
+    {                                                                                                   \
+        hh = __builtin_amdgcn_mfma_i32_32x32x32_i8(aH, bH, zero, 0, 0, 0);                              \
+        mid = __builtin_amdgcn_mfma_i32_32x32x32_i8(aH, bL, zero, 0, 0, 0);                             \
+        ll = __builtin_amdgcn_mfma_i32_32x32x32_i8(aL, bL, zero, 0, 0, 0);                              \
+        mid = __builtin_amdgcn_mfma_i32_32x32x32_i8(aL, bH, mid, 0, 0, 0);                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        HBFP_READ_FRAGS(ring, 1);                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        hh = __builtin_amdgcn_mfma_i32_32x32x32_i8(aH, bH, hh, 0, 0, 0);                                \
+        mid = __builtin_amdgcn_mfma_i32_32x32x32_i8(aH, bL, mid, 0, 0, 0);                              \
+        ll = __builtin_amdgcn_mfma_i32_32x32x32_i8(aL, bL, ll, 0, 0, 0);                                \
+        mid = __builtin_amdgcn_mfma_i32_32x32x32_i8(aL, bH, mid, 0, 0, 0);                              \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        const int rem = nst - 1 - st;                                                                   \
+        if (rem > 0) {                                                                                  \
+            if (rem >= 2) HBFP_WAIT_COPIES(4); else HBFP_WAIT_COPIES(0);                                \
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                          \
+            __builtin_amdgcn_s_barrier();                                                               \
+            asm volatile("" ::: "memory");                                                              \
+            if (rem >= 3) HBFP_COPY_STAGE(st + 3, ring);                                                \
+            HBFP_READ_FRAGS(((ring) + 1) % 3, 0);                                                       \
+        }                                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        const v16i sa = row_constants(rowc, one_hot);                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        int P[16];                                                                                      \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) P[v] = (((hh[v] << 6) + mid[v]) << 6) + ll[v];   \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(P[v]));                   \
+        float x[16];                                                                                    \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) x[v] = (float)P[v];                              \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) x[v] *= __int_as_float(sa[v]);                   \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[v] = fmaf(x[v], sb, acc[v]);                 \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[v]));                 \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        if (rem > 0) HBFP_READ_WORDS(((ring) + 1) % 3);                                                 \
+    }
+
+    if (nst > 0) {
+        HBFP_COPY_STAGE(0, 0);
+        if (nst > 1) HBFP_COPY_STAGE(1, 1);
+        if (nst > 2) HBFP_COPY_STAGE(2, 2);
+        if (nst > 2) HBFP_WAIT_COPIES(8); else if (nst == 2) HBFP_WAIT_COPIES(4); else HBFP_WAIT_COPIES(0);
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (nst > 0) {
+        HBFP_READ_FRAGS(0, 0);
+        HBFP_READ_WORDS(0);
+    }
+    for (int st = 0; st < nst;) {
+        HBFP_STAGE(0);
+        if (++st >= nst) break;
+        HBFP_STAGE(1);
+        if (++st >= nst) break;
+        HBFP_STAGE(2);
+        ++st;
+    }
+#undef HBFP_STAGE
+#undef HBFP_READ_WORDS
+#undef HBFP_READ_FRAGS
+#undef HBFP_COPY_STAGE
+#undef HBFP_WAIT_COPIES
+
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int64_t i = row0 + wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        const int64_t j = col0 + wn * 32 + l32;
+        if (i < p.M && j < p.N) {
+            const float val = acc[v] * p.final_scale;
+            if (p.beta) p.C[i * p.ldc + j] += val;
+            else p.C[i * p.ldc + j] = val;
+        }
+    }
+}
+
 template <int SPB, bool DUMP>
 int launch_t(const LimbParams &p, dim3 grid, hipStream_t s) {
     hipLaunchKernelGGL((gemm_limb_kernel<SPB, DUMP>), grid, dim3(kThreads), 0, s, p);
@@ -264,9 +441,11 @@ size_t plane_bytes(int64_t rows, int64_t kpad) { return ((size_t)rows * (size_t)
 
 }  // namespace
 
-// workspace: [A hi][A lo][B hi][B lo] int8 planes
+// workspace: [A hi][A lo][B hi][B lo] int8 planes, [A row words][B column words] (blocks of 64 only)
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B) {
-    return 2 * plane_bytes(A->rows, A->kpad) + 2 * plane_bytes(B->rows, B->kpad);
+    size_t n = 2 * plane_bytes(A->rows, A->kpad) + 2 * plane_bytes(B->rows, B->kpad);
+    if (A->kblock_pad == 64) n += word_bytes(A->rows, A->exp_ld) + word_bytes(B->rows, B->exp_ld);
+    return n;
 }
 
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
@@ -308,6 +487,28 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.beta = a.beta != 0.0f;
     p.final_scale = ldexpf(1.0f, 4 - a.mA - a.mB);
     const dim3 grid((unsigned)(tm * tn));
+    if (!a.P && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
+        static bool configured = false;
+        if (!configured) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_limb_w8_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLwLdsBytes) != hipSuccess)
+                return HBFP_ERR_LAUNCH;
+            configured = true;
+        }
+        LimbW8Params q;
+        q.g = p;
+        q.mpad = ceil_div(a.M, 128) * 128;
+        q.npad = ceil_div(a.N, 128) * 128;
+        q.tiles_m = (int32_t)tm;
+        uint8_t *ww = w + 2 * pa + 2 * pb;
+        q.wA = (const uint32_t *)ww;
+        q.wB = (const uint32_t *)(ww + word_bytes(a.M, a.expA_ld));
+        const int rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0u,
+                                          const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), s);
+        if (rc != HBFP_OK) return rc;
+        hipLaunchKernelGGL(gemm_limb_w8_kernel, dim3((unsigned)(ceil_div(tm * tn, 8) * 8)), dim3(kLwThreads), kLwLdsBytes, s, q);
+        return launch_status();
+    }
     if (a.P) return p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     return p.spb == 1 ? launch_t<1, false>(p, grid, s) : p.spb == 2 ? launch_t<2, false>(p, grid, s) : launch_t<0, false>(p, grid, s);
 }
