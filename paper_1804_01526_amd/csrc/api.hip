@@ -223,7 +223,7 @@ int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *byte
     rc = check_tensor(B, false);
     if (rc != HBFP_OK) return rc;
     *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
-                                                     : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad);
+                                                     : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld);
     return HBFP_OK;
 }
 

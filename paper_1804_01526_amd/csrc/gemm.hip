@@ -304,6 +304,10 @@ struct W8Params {
     int64_t mpad, npad;
 };
 
+// SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (a block is spb / 2 whole stages).  A block
+// that spans several k-steps chains its matrix instructions through the C input and is scaled once, at its
+// last k-step; the longer the block, the closer the kernel gets to the matrix core's own pace.
+template <int SPB>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const GemmParams &p = q.g;
@@ -341,13 +345,15 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     const int64_t wordpitch = wave_u < 4 ? q.mpad : q.npad;
     const uint32_t ldsM = wave_u * 1024;
     const uint32_t ldsW = 2 * kHalfTile + (wave_u < 4 ? 0 : kHalfWords) + (wc >> 1) * 512 + (wc & 1) * 256;
+    const int spb64 = SPB == 0 ? p.spb / 2 : 1;                                  // stages per block when blocks span stages
 
 #define HBFP_COPY_STAGE(st, ring)                                                                       \
     {                                                                                                   \
         const uint32_t lb = (ring) * kHalfStage;                                                        \
         async_copy16(tileA + (int64_t)(st) * kHalfK, voffA, lb + ldsM);                                 \
         async_copy16(tileB + (int64_t)(st) * kHalfK, voffB, lb + kHalfTile + ldsM);                     \
-        async_copy4(wordsrc + (2 * (int64_t)(st) + (wc >> 1)) * wordpitch, voffW, lb + ldsW);           \
+        const int64_t blk_ = SPB == 1 ? 2 * (int64_t)(st) + (wc >> 1) : SPB == 2 ? (int64_t)(st) : (int64_t)(st) / spb64; \
+        async_copy4(wordsrc + blk_ * wordpitch, voffW, lb + ldsW);                                      \
     }
 #define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 
@@ -367,41 +373,53 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
 
     v4i a, b[2];
-    v16i cin;
+    v16i cin, d0, d1;
     uint32_t rowc = 0;
     float sb[2][2];
-#define HBFP_READ_STEP(ring, s, set)                                                                          \
+#define HBFP_READ_STEP(ring, s_, set)                                                                         \
     {                                                                                                         \
+        constexpr int s = SPB == 1 ? (s_) : 0;           /* slot of the words */                              \
         const uint8_t *base_ = lds + (ring) * kHalfStage;                                                     \
         rowc = *reinterpret_cast<const uint32_t *>(base_ + offW + (s) * 512);                                 \
-        a = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragA1 : fragA0));                                  \
-        b[0] = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragB1 : fragB0));                               \
-        b[1] = *reinterpret_cast<const v4i *>(base_ + ((s) ? fragB1 : fragB0) + 2048);                        \
+        a = *reinterpret_cast<const v4i *>(base_ + ((s_) ? fragA1 : fragA0));                                 \
+        b[0] = *reinterpret_cast<const v4i *>(base_ + ((s_) ? fragB1 : fragB0));                              \
+        b[1] = *reinterpret_cast<const v4i *>(base_ + ((s_) ? fragB1 : fragB0) + 2048);                       \
         sb[set][0] = *reinterpret_cast<const float *>(base_ + offS + (s) * 512);                              \
         sb[set][1] = *reinterpret_cast<const float *>(base_ + offS + (s) * 512 + 128);                        \
     }
     // One k-step: both matrix instructions, then whatever has to happen between issue and use (MIDDLE:
     // the stage hand-over and the next step's LDS reads), then 32 subtractions, the next step's row
     // constants on the matrix core, and 32 multiply-adds that cover its latency.
-#define HBFP_STEP(cur, MIDDLE)                                                                          \
+#define HBFP_STEP(cur, FIRST, LAST, MIDDLE)                                                             \
     {                                                                                                   \
-        v16i d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin, 0, 0, 0);                         \
-        v16i d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin, 0, 0, 0);                         \
+        if (FIRST) {                                                                                    \
+            d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin, 0, 0, 0);                          \
+            d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin, 0, 0, 0);                          \
+        } else {                                                                                        \
+            d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], d0, 0, 0, 0);                           \
+            d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], d1, 0, 0, 0);                           \
+        }                                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         MIDDLE;                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        float x0[16], x1[16];                                                                           \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) x0[v] = __int_as_float(d0[v]) - __int_as_float(cin[v]); \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) x1[v] = __int_as_float(d1[v]) - __int_as_float(cin[v]); \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x0[v]));                  \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));                  \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        cin = row_constants(rowc, one_hot);                                                            \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[0][v] = fmaf(x0[v], sb[cur][0], acc[0][v]);  \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[1][v] = fmaf(x1[v], sb[cur][1], acc[1][v]);  \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[0][v]));              \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[1][v]));              \
+        if (LAST) {                                                                                     \
+            float x0[16], x1[16];                                                                       \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) x0[v] = __int_as_float(d0[v]) - __int_as_float(cin[v]); \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) x1[v] = __int_as_float(d1[v]) - __int_as_float(cin[v]); \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x0[v]));              \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));              \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
+            cin = row_constants(rowc, one_hot);                                                         \
+            if (SPB == 0) {               /* long blocks always chain: the next block starts from its constants */ \
+                d0 = row_constants(rowc, one_hot);                                                      \
+                d1 = row_constants(rowc, one_hot);                                                      \
+            }                                                                                           \
+            __builtin_amdgcn_sched_barrier(0);                                                          \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[0][v] = fmaf(x0[v], sb[cur][0], acc[0][v]); \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[1][v] = fmaf(x1[v], sb[cur][1], acc[1][v]); \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[0][v]));          \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(acc[1][v]));          \
+        }                                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
     // Stage st lives in ring buffer (st - st_begin) & 3.  The hand-over sits in k-step 1 right after its
@@ -410,8 +428,10 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     // (copies complete in issue order: all but the newest two groups of three).
 #define HBFP_STAGE(ring)                                                                                \
     {                                                                                                   \
-        HBFP_STEP(0, HBFP_READ_STEP(ring, 1, 1));                                                       \
-        HBFP_STEP(1, {                                                                                  \
+        const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                             \
+        pos = pos == spb64 - 1 ? 0 : pos + 1;                                                           \
+        HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                     \
+        HBFP_STEP(1, SPB == 1, last1, {                                                                 \
             const int rem = st_end - 1 - st;                                                            \
             if (rem > 0) {                                                                              \
                 if (rem >= 3) HBFP_WAIT_COPIES(6); else if (rem == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0); \
@@ -436,7 +456,12 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     if (nst > 0) {
         HBFP_READ_STEP(0, 0, 0);
         cin = row_constants(rowc, one_hot);
+        if (SPB == 0) {
+            d0 = row_constants(rowc, one_hot);
+            d1 = row_constants(rowc, one_hot);
+        }
     }
+    int pos = 0;                           // stage within its exponent block (splits start on block boundaries)
     for (int st = st_begin; st < st_end;) {
         HBFP_STAGE(0);
         if (++st >= st_end) break;
@@ -508,17 +533,17 @@ static int choose_splits(int64_t M, int64_t N, int64_t nstage, int64_t stages_pe
 }
 
 // the asynchronous-copy kernel addresses an operand tile with 32-bit offsets
-static bool use_w8(int64_t kpad, int64_t kbp) { return kbp == 32 && (uint64_t)127 * (uint64_t)kpad + 128 < ((uint64_t)1 << 32); }
+static bool use_w8(int64_t kpad) { return (uint64_t)127 * (uint64_t)kpad + 128 < ((uint64_t)1 << 32); }
 static size_t split_bytes(int64_t M, int64_t N, int splits) {
     return splits <= 1 ? 0 : ((size_t)splits * (size_t)M * (size_t)N * 4 + 255) & ~(size_t)255;
 }
 
 // workspace: [split-K slices][row words of A][column words of B]
-size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp) {
+size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld) {
     const int64_t nstage = kpad / BK, spb = kbp / 32;
     const int splits = choose_splits(M, N, nstage, spb >= 4 ? spb / 4 : 1);
     size_t n = split_bytes(M, N, splits);
-    if (use_w8(kpad, kbp)) n += word_bytes(M, kpad / 32) + word_bytes(N, kpad / 32);
+    if (use_w8(kpad)) n += word_bytes(M, exp_ld) + word_bytes(N, exp_ld);
     return n;
 }
 
@@ -558,12 +583,12 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        if (use_w8(a.kpad, a.kbp)) {
+        if (use_w8(a.kpad)) {
             static bool configured = false;
             if (!configured) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_w8_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kW8LdsBytes) != hipSuccess)
-                    return HBFP_ERR_LAUNCH;
+                for (const void *f : {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),
+                                      reinterpret_cast<const void *>(&gemm_i8_w8_kernel<0>)})
+                    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kW8LdsBytes) != hipSuccess) return HBFP_ERR_LAUNCH;
                 configured = true;
             }
             if (!workspace) return HBFP_ERR_WORKSPACE;
@@ -573,11 +598,13 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
             q.npad = ceil_div(a.N, 128) * 128;
             uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
             q.wA = (const uint32_t *)w;
-            q.wB = (const uint32_t *)(w + word_bytes(a.M, a.kpad / 32));
-            rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)(a.kpad / 32), 0x40u,
+            q.wB = (const uint32_t *)(w + word_bytes(a.M, a.expA_ld));
+            rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0x40u,
                                     const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), s);
             if (rc != HBFP_OK) return rc;
-            hipLaunchKernelGGL(gemm_i8_w8_kernel, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+            if (p.spb == 1) hipLaunchKernelGGL(gemm_i8_w8_kernel<1>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+            else if (p.spb == 2) hipLaunchKernelGGL(gemm_i8_w8_kernel<2>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+            else hipLaunchKernelGGL(gemm_i8_w8_kernel<0>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             rc = launch_status();
         } else {
             rc = p.spb == 1 ? launch_t<1, false>(p, grid, s) : p.spb == 2 ? launch_t<2, false>(p, grid, s) : launch_t<0, false>(p, grid, s);

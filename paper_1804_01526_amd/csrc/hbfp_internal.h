@@ -48,7 +48,7 @@ struct GemmArgs {
     int32_t *P;                       // non-null: dump block partials instead of C
 };
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
-size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp);
+size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld);
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
 
