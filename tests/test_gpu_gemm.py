@@ -139,6 +139,27 @@ def test_gemm_split_k_and_beta(hb):
     assert torch.equal(c1, c2)                                     # deterministic reduction order
 
 
+@pytest.mark.parametrize("K", [64, 128, 192, 256, 320, 576])
+@pytest.mark.parametrize("B,m", [(32, 8), (64, 8), (64, 12)])
+def test_gemm_few_stages(hb, K, B, m):
+    """One to nine 64-byte stages of k: every start-up and drain path of the LDS ring, with ragged tile edges."""
+    _run(hb, _rand((70, K), K + m), _rand((K, 150), K + B), (1, B, m, 0, 0), (B, 1, m, 0, 0))
+
+
+@pytest.mark.parametrize("B,m", [(64, 8), (256, 8), (1024, 8)])
+def test_gemm_split_k_long_blocks(hb, B, m):
+    """Few tiles and a long contraction with blocks that span one or more stages: split-K starts on block boundaries."""
+    A, Bm = _rand((100, 16384), 31 + B, 2), _rand((16384, 90), 32 + B, 2)
+    _run(hb, A, Bm, (1, B, m, 0, 0), (B, 1, m, 0, 0), partials=False)
+    _run(hb, A, Bm, (1, B, m, 0, 0), (B, 1, m, 0, 0), partials=False, beta=1.0)
+
+
+def test_gemm_wide_mantissas_many_tiles_ragged(hb):
+    """12-bit mantissas, blocks of 64: 3 x 3 tiles of 64 x 128 with ragged last row and column of tiles."""
+    _run(hb, _rand((150, 704), 41), _rand((704, 300), 42), (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False)
+    _run(hb, _rand((150, 704), 43), _rand((704, 300), 44), (1, 64, 12, 1, 3), (64, 1, 12, 1, 4), partials=False, beta=1.0)
+
+
 @pytest.mark.parametrize("trans_a,trans_b", [(0, 0), (0, 1), (1, 0), (1, 1)])
 def test_gemm_f32_transposes(hb, trans_a, trans_b):
     """Forward (N,N), data gradient (N,T) and weight gradient (T,N) shapes in one call each."""
