@@ -15,6 +15,9 @@
  *   - Sec. 4 (tiled matmul) / Sec. 4.2 "Tiling": per-tile fixed-point results
  *     are accumulated in floating point.
  *   - Sec. 5.3: stochastic rounding during mantissa truncation.
+ *   - Sec. 4.2 "Wide weight storage" / Sec. 5.1 (optimizer shell): weights live in
+ *     BFP with wide mantissas; an update is computed in FP32 and converted to a
+ *     wide and a narrow BFP tensor.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - "m-bit mantissa" counts the sign: two's complement, symmetric range
@@ -37,6 +40,7 @@
 #include <stdint.h>
 #include <string.h>
 #include <math.h>
+#include <stdlib.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -264,4 +268,39 @@ int hbfp_ref_scale_accumulate(const int32_t *P, const uint8_t *eA, const uint8_t
             C[i * N + j] = s;
         }
     return 0;
+}
+
+/*
+ * One update of weights stored with wide mantissas (Sec. 4.2 "Wide weight storage";
+ * Sec. 5.1: the update is done in FP32, then the weights are converted to two BFP
+ * formats, wide for later updates and narrow for the forward/backward products).
+ * Steps, in the paper's order:
+ *   1. w  = mant * 2^(Eb - 125 - m_wide)                      Eq. (1), exact in FP32
+ *   2. w' = alpha * delta + w in FP32                          the FP32 update
+ *   3. wide' = encode(w', m_wide), narrow' = encode(w', m_narrow), same br x bc blocks
+ * Reading where the paper is silent: step 2 is one fused multiply-add (a single
+ * FP32 rounding); both conversions start from w' (as the optimizer shell of Sec. 5.1
+ * does), so the narrow mantissas are the wide ones rounded, not truncated.
+ * w_new (optional, [rows][cols]) receives w'.
+ */
+int hbfp_ref_weight_update(const int32_t *wide_mant, const uint8_t *wide_exps, int64_t rows, int64_t cols,
+                           int64_t br, int64_t bc, int m_wide, int rounding_wide, uint64_t seed_wide,
+                           const float *delta, int64_t ld, float alpha,
+                           int m_narrow, int rounding_narrow, uint64_t seed_narrow,
+                           int32_t *wide_mant_out, uint8_t *wide_exps_out,
+                           int32_t *narrow_mant, uint8_t *narrow_exps, float *w_new) {
+    if (!wide_mant || !wide_exps || !delta || !wide_mant_out || !wide_exps_out || rows <= 0 || cols <= 0 || ld < cols)
+        return -1;
+    float *w = w_new ? w_new : (float *)malloc((size_t)rows * (size_t)cols * sizeof(float));
+    if (!w) return -1;
+    int rc = hbfp_ref_decode(wide_mant, wide_exps, rows, cols, br, bc, m_wide, w, cols);
+    if (rc == 0) {
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) w[r * cols + c] = fmaf(alpha, delta[r * ld + c], w[r * cols + c]);
+        rc = hbfp_ref_encode(w, rows, cols, cols, br, bc, m_wide, rounding_wide, seed_wide, wide_mant_out, wide_exps_out);
+    }
+    if (rc == 0 && narrow_mant && narrow_exps)
+        rc = hbfp_ref_encode(w, rows, cols, cols, br, bc, m_narrow, rounding_narrow, seed_narrow, narrow_mant, narrow_exps);
+    if (!w_new) free(w);
+    return rc;
 }

@@ -54,6 +54,8 @@ def _L():
         lib.hbfp_ref_gemm.argtypes = [p, i64, p, i64, i64, i64, i64, p]
         lib.hbfp_ref_gemm_rows.argtypes = [p, i64, p, i64, i64, i64, i64, p, i64, p]
         lib.hbfp_ref_scale_accumulate.argtypes = [p, p, p, i64, i64, i64, i32, i32, p]
+        lib.hbfp_ref_weight_update.argtypes = [p, p, i64, i64, i64, i64, i32, i32, u64, p, i64, ctypes.c_float,
+                                               i32, i32, u64, p, p, p, p, p]
         _lib = lib
     return _lib
 
@@ -177,3 +179,28 @@ def bfp_gemm(A: np.ndarray, B: np.ndarray, fmt_a: dict, fmt_b: dict, rows=None):
     ta = encode(A, fmt_a["br"], fmt_a["bc"], fmt_a["m"], fmt_a.get("rounding", RNE), fmt_a.get("seed", 0))
     tb = encode(B, fmt_b["br"], fmt_b["bc"], fmt_b["m"], fmt_b.get("rounding", RNE), fmt_b.get("seed", 0))
     return gemm(decode(ta), decode(tb), rows=rows), ta, tb
+
+
+def weight_update(wide: BFP, delta: np.ndarray, alpha: float, m_narrow: int, rounding_wide: int = RNE, seed_wide: int = 0,
+                  rounding_narrow: int = RNE, seed_narrow: int = 0):
+    """One FP32 update step on weights stored with wide mantissas (Sec. 4.2, Sec. 5.1).
+
+    Returns (wide', narrow', w') with w' = fma(alpha, delta, value(wide)) in FP32 and both
+    BFP tensors converted from w' with the block shape of ``wide``.
+    """
+    delta = np.ascontiguousarray(delta, dtype=np.float32)
+    rows, cols = wide.mant.shape
+    assert delta.shape == (rows, cols)
+    wm = np.empty((rows, cols), dtype=np.int32)
+    we = np.empty_like(wide.exps)
+    nm = np.empty((rows, cols), dtype=np.int32)
+    ne = np.empty_like(wide.exps)
+    w = np.empty((rows, cols), dtype=np.float32)
+    rc = _L().hbfp_ref_weight_update(_ptr(np.ascontiguousarray(wide.mant)), _ptr(np.ascontiguousarray(wide.exps)),
+                                     rows, cols, wide.br, wide.bc, wide.m, rounding_wide, ctypes.c_uint64(seed_wide),
+                                     _ptr(delta), cols, ctypes.c_float(alpha), m_narrow, rounding_narrow,
+                                     ctypes.c_uint64(seed_narrow), _ptr(wm), _ptr(we), _ptr(nm), _ptr(ne), _ptr(w))
+    if rc != 0:
+        raise ValueError(f"hbfp_ref_weight_update: {rc}")
+    return BFP(wm, we, wide.m, wide.br, wide.bc), BFP(nm, ne, m_narrow, wide.br, wide.bc), w
+

@@ -376,3 +376,82 @@ def test_block_partials_scaled_and_summed_equal_the_definition(m, kb):
     exact = A.astype(np.float64) @ B.astype(np.float64)
     rel = np.linalg.norm(C - exact) / np.linalg.norm(exact)
     assert rel < 2.0 ** -(m - 3)
+
+
+# ---------------------------------------------------------------- wide weight storage (Sec. 4.2, Sec. 5.1)
+def _bfp_block(mant, unit_exp, m):
+    mant = np.array([mant], dtype=np.int32)
+    return ref.BFP(mant, np.array([[unit_exp + 125 + m]], dtype=np.uint8), m, 1, mant.shape[1])
+
+
+def test_golden_weight_update_examples(golden_dir):
+    n = 0
+    for row in _read_rows(os.path.join(golden_dir, "weight_update_examples.txt")):
+        mw, mn, wm, ew, delta, alpha, ew2, wm2, en2, nm2 = row
+        mw, mn, ew, ew2, en2 = int(mw), int(mn), int(ew), int(ew2), int(en2)
+        wide = _bfp_block([int(v) for v in wm.split()], ew, mw)
+        d = np.array([[float(v) for v in delta.split()]], dtype=np.float32)
+        w2, n2, _ = ref.weight_update(wide, d, float(alpha), mn)
+        assert int(w2.exps[0, 0]) - 125 - mw == ew2 and int(n2.exps[0, 0]) - 125 - mn == en2, row
+        np.testing.assert_array_equal(w2.mant[0], [int(v) for v in wm2.split()], err_msg=str(row))
+        np.testing.assert_array_equal(n2.mant[0], [int(v) for v in nm2.split()], err_msg=str(row))
+        n += 1
+    assert n >= 5
+
+
+def _round_to_f32(x):
+    """Exact rational -> nearest FP32 (ties to even), by integer arithmetic."""
+    from fractions import Fraction
+    if x == 0:
+        return np.float32(0.0)
+    sign, ax = (-1 if x < 0 else 1), abs(x)
+    e = ax.numerator.bit_length() - ax.denominator.bit_length()
+    if Fraction(2) ** e > ax:
+        e -= 1
+    e = max(e, -126)
+    q = ax / Fraction(2) ** (e - 23)
+    fl = q.numerator // q.denominator
+    rem = q - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (fl & 1)):
+        fl += 1
+    return np.float32(sign * float(fl) * 2.0 ** (e - 23))
+
+
+def test_weight_update_step_is_one_fp32_rounding_of_the_exact_sum():
+    """w' must equal alpha*delta + w computed exactly (rationals) and rounded once to FP32."""
+    from fractions import Fraction
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((6, 40)) * np.exp2(rng.integers(-6, 7, size=(6, 40)))).astype(np.float32)
+    wide = ref.encode(x, 3, 8, 16)
+    delta = (rng.standard_normal((6, 40)) * np.exp2(rng.integers(-12, 3, size=(6, 40)))).astype(np.float32)
+    alpha = np.float32(-0.0123)
+    _, _, w = ref.weight_update(wide, delta, float(alpha), 8)
+    unit = wide.unit_exponents()
+    for r in range(6):
+        for c in range(40):
+            exact = Fraction(float(alpha)) * Fraction(float(delta[r, c])) + Fraction(int(wide.mant[r, c])) * Fraction(2) ** int(unit[r, c])
+            assert w[r, c] == _round_to_f32(exact), (r, c)
+
+
+@pytest.mark.parametrize("br,bc,mn", [(1, 32, 8), (24, 24, 8), (16, 5, 12), (0, 0, 8)])
+def test_weight_update_properties(br, bc, mn):
+    rng = np.random.default_rng(5 + br + bc)
+    x = (rng.standard_normal((70, 100)) * 0.02).astype(np.float32)
+    wide = ref.encode(x, br, bc, 16)
+    # a zero step changes nothing: a BFP tensor is a fixed point of its own conversion
+    w0, n0, w = ref.weight_update(wide, np.ones_like(x), 0.0, mn)
+    np.testing.assert_array_equal(w0.mant, wide.mant)
+    np.testing.assert_array_equal(w0.exps, wide.exps)
+    np.testing.assert_array_equal(w, wide.mant.astype(np.float64) * np.exp2(wide.unit_exponents().astype(np.float64)))
+    # a real step: both copies are within half a unit of the FP32 result, and where they share the
+    # exponent the narrow mantissas are the wide ones rounded to the top mn bits
+    delta = rng.standard_normal(x.shape).astype(np.float32)
+    w1, n1, w = ref.weight_update(wide, delta, -0.001, mn)
+    for t in (w1, n1):
+        u = np.exp2(t.unit_exponents().astype(np.float64))
+        assert np.all(np.abs(t.mant * u - w.astype(np.float64)) <= 0.5 * u)
+        assert np.abs(t.mant).max() <= 2 ** (t.m - 1) - 1
+    same = np.repeat(np.repeat(w1.exps == n1.exps, w1.br, axis=0)[:70], w1.bc, axis=1)[:, :100]
+    assert same.mean() > 0.9
+    assert np.all(np.abs(n1.mant.astype(np.int64) * 2 ** (16 - mn) - w1.mant)[same] <= 2 ** (15 - mn))
+
