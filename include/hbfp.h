@@ -203,6 +203,35 @@ int hbfp_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
                   const hbfp_format *fa, const hbfp_format *fb,
                   void *workspace, size_t ws_bytes, void *stream);
 
+/*
+ * hbfp_weight_update: one step on weights kept in BFP with wide mantissas
+ * (Sec. 4.2 "Wide weight storage"; Sec. 5.1, the optimizer shell: the update is
+ * computed in FP32 and the result is converted to two BFP formats, the wide one
+ * for later updates and the narrow one for the forward and backward products).
+ *   w   = value of `wide` (Eq. (1); exact in FP32 for mantissas of up to 16 bits)
+ *   w'  = fma(alpha, delta, w)            FP32, one rounding, element by element
+ *   wide     <- encode(w') in wide's own format, layout and rounding (in place)
+ *   narrow_a <- encode(w') in narrow_a's format and layout   (may be NULL)
+ *   narrow_b <- encode(w') in narrow_b's format and layout   (may be NULL)
+ * delta: device FP32 [src_rows][ld], the same orientation as the matrix the
+ * tensors were planned for (e.g. alpha = -learning rate, delta = gradient).
+ * wide, narrow_a, narrow_b: descriptors from hbfp_plan with both device buffers
+ * set, all of the same source shape; any orientation, block shape, mantissa width
+ * and rounding each (typically wide = 16 bits, narrow_a/narrow_b = the forward and
+ * the transposed operand of 8 or 12 bits).  wide must hold an encoded tensor; the
+ * narrow tensors are outputs only.  Every output is what hbfp_encode would give for
+ * the FP32 matrix w', bit for bit; w' itself is left in the first
+ * src_rows*src_cols floats of the workspace.
+ * workspace: hbfp_weight_update_workspace bytes, 256-byte aligned.
+ * Errors: HBFP_ERR_ARG (null/misaligned pointer, ld < src_cols), HBFP_ERR_LAYOUT
+ * (descriptors of different source shapes or inconsistent), HBFP_ERR_WORKSPACE.
+ */
+int hbfp_weight_update_workspace(const hbfp_tensor *wide, const hbfp_tensor *narrow_a, const hbfp_tensor *narrow_b,
+                                 size_t *bytes);
+int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, float alpha,
+                       const hbfp_tensor *narrow_a, const hbfp_tensor *narrow_b,
+                       void *workspace, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

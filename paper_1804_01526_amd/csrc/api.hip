@@ -187,6 +187,14 @@ int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes) {
     return HBFP_OK;
 }
 
+// src [src_rows][ld] -> the buffers of t, in t's own layout and format
+static int encode_planned(const float *src, int64_t ld, const hbfp_tensor *t, bool tile_pass, void *workspace, hipStream_t s) {
+    const EncodeGeom g = geom_of(*t, ld);
+    if (tile_pass) return launch_encode_generic(src, g, t->mant, t->exps, (uint32_t *)workspace, s);
+    if (t->contract_axis == 1) return launch_encode_row_fused(src, g, t->mant, t->exps, s);
+    return launch_encode_col_fused(src, g, t->mant, t->exps, s);
+}
+
 int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int contract_axis,
                 const hbfp_format *fmt, hbfp_tensor *out, void *workspace, size_t ws_bytes, void *stream) {
     if (!src || !fmt || !out || rows <= 0 || cols <= 0 || ld < cols) return HBFP_ERR_ARG;
@@ -201,11 +209,7 @@ int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int co
     if (need) {
         if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     }
-    const EncodeGeom g = geom_of(*out, ld);
-    hipStream_t s = (hipStream_t)stream;
-    if (need) return launch_encode_generic(src, g, out->mant, out->exps, (uint32_t *)workspace, s);
-    if (contract_axis == 1) return launch_encode_row_fused(src, g, out->mant, out->exps, s);
-    return launch_encode_col_fused(src, g, out->mant, out->exps, s);
+    return encode_planned(src, ld, out, need != 0, workspace, (hipStream_t)stream);
 }
 
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
@@ -214,6 +218,57 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
     if (rc != HBFP_OK) return rc;
     if (ld < t->src_cols || ((uintptr_t)dst & 3)) return HBFP_ERR_ARG;
     return launch_decode(t, dst, ld, (hipStream_t)stream);
+}
+
+// hbfp_weight_update workspace: [FP32 weights after the step, src_rows x src_cols][scratch of the largest re-encode]
+static int weight_update_plan(const hbfp_tensor *wide, const hbfp_tensor *na, const hbfp_tensor *nb, size_t *tmp_bytes,
+                              size_t *total) {
+    int rc = check_tensor(wide, true);
+    if (rc != HBFP_OK) return rc;
+    size_t scratch = 0;
+    for (const hbfp_tensor *t : {wide, na, nb}) {
+        if (!t) continue;
+        rc = check_tensor(t, true);
+        if (rc != HBFP_OK) return rc;
+        if (t->src_rows != wide->src_rows || t->src_cols != wide->src_cols) return HBFP_ERR_LAYOUT;
+        if (((uintptr_t)t->mant & 15) || ((uintptr_t)t->exps & 3)) return HBFP_ERR_ARG;
+        size_t n = 0;
+        hbfp_encode_workspace(t, &n);
+        scratch = n > scratch ? n : scratch;
+    }
+    *tmp_bytes = align256((size_t)wide->src_rows * (size_t)wide->src_cols * 4);
+    *total = *tmp_bytes + scratch;
+    return HBFP_OK;
+}
+
+int hbfp_weight_update_workspace(const hbfp_tensor *wide, const hbfp_tensor *narrow_a, const hbfp_tensor *narrow_b,
+                                 size_t *bytes) {
+    if (!wide || !bytes) return HBFP_ERR_ARG;
+    size_t tmp = 0;
+    return weight_update_plan(wide, narrow_a, narrow_b, &tmp, bytes);
+}
+
+int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, float alpha,
+                       const hbfp_tensor *narrow_a, const hbfp_tensor *narrow_b,
+                       void *workspace, size_t ws_bytes, void *stream) {
+    if (!wide || !delta || ((uintptr_t)delta & 3)) return HBFP_ERR_ARG;
+    size_t tmp_bytes = 0, total = 0;
+    int rc = weight_update_plan(wide, narrow_a, narrow_b, &tmp_bytes, &total);
+    if (rc != HBFP_OK) return rc;
+    if (ld < wide->src_cols) return HBFP_ERR_ARG;
+    if (!workspace || ws_bytes < total || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    float *w = (float *)workspace;
+    void *scratch = (char *)workspace + tmp_bytes;
+    const int64_t ldw = wide->src_cols;
+    rc = launch_decode_axpy(wide, w, ldw, delta, ld, alpha, s);          // w = fma(alpha, delta, stored weight)
+    if (rc != HBFP_OK) return rc;
+    for (const hbfp_tensor *t : {wide, narrow_a, narrow_b}) {             // the wide copy first: it is the one read above
+        if (!t) continue;
+        rc = encode_planned(w, ldw, t, needs_tile_pass(*t), scratch, s);
+        if (rc != HBFP_OK) return rc;
+    }
+    return HBFP_OK;
 }
 
 int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {

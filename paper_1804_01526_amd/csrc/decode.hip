@@ -1,6 +1,8 @@
 // BFP -> FP32, Eq. (1) of Sec. 4: value = mantissa * 2^(Eb - 125 - mant_bits).
 // int -> float of a mantissa of at most 16 bits is exact and so is the power-of-two
 // scaling (ldexp, subnormal results included), so decode is exact.
+// With AXPY the decoded value is the stored weight of an update step (Sec. 4.2 "Wide weight
+// storage"): dst = fma(alpha, delta, value), one FP32 rounding.
 #include "hbfp_internal.h"
 
 namespace hbfp {
@@ -12,13 +14,16 @@ struct DecParams {
     const uint8_t *mant;
     const uint8_t *exps;
     float *dst;
+    const float *delta;          // AXPY only: FP32 [src_rows][ldd]
+    int64_t ldd;
+    float alpha;
     int64_t ld, src_rows, src_cols, R, K, kblock, kbp, nblk, kpad, exp_ld;
     int32_t axis, m;
     int32_t chunks, lpr_log2, nseg, vec_ok, gp_log2;
 };
 
 // row path: k is contiguous in the destination; each lane turns 8 stored mantissas into 8 floats
-template <bool WIDE>
+template <bool WIDE, bool AXPY>
 __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
     const int t = threadIdx.x;
     const int lpr = 1 << p.lpr_log2;
@@ -57,6 +62,19 @@ __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] = __builtin_amdgcn_ldexpf((float)q[e], ue);
         float *o = p.dst + row * p.ld + k0 + 8 * j;
+        if (AXPY) {
+            const float *g = p.delta + row * p.ldd + k0 + 8 * j;
+            if (cnt == 8 && p.vec_ok) {
+                const float4 g0 = *reinterpret_cast<const float4 *>(g), g1 = *reinterpret_cast<const float4 *>(g + 4);
+                const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = fmaf(p.alpha, gv[e], f[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e < cnt) f[e] = fmaf(p.alpha, g[e], f[e]);
+            }
+        }
         if (cnt == 8 && p.vec_ok) {
             *reinterpret_cast<float4 *>(o) = make_float4(f[0], f[1], f[2], f[3]);
             *reinterpret_cast<float4 *>(o + 4) = make_float4(f[4], f[5], f[6], f[7]);
@@ -69,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
 }
 
 // any orientation: one thread per destination element
-template <bool WIDE>
+template <bool WIDE, bool AXPY>
 __global__ __launch_bounds__(kThreads) void dec_any_kernel(const DecParams p) {
     const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (c >= p.src_cols) return;
@@ -80,14 +98,21 @@ __global__ __launch_bounds__(kThreads) void dec_any_kernel(const DecParams p) {
         const int q = WIDE ? (int)reinterpret_cast<const int16_t *>(p.mant)[off]
                            : (int)reinterpret_cast<const int8_t *>(p.mant)[off];
         const int ue = (int)p.exps[ro * p.exp_ld + blk] - 125 - p.m;
-        p.dst[r * p.ld + c] = __builtin_amdgcn_ldexpf((float)q, ue);
+        float f = __builtin_amdgcn_ldexpf((float)q, ue);
+        if (AXPY) f = fmaf(p.alpha, p.delta[r * p.ldd + c], f);
+        p.dst[r * p.ld + c] = f;
     }
 }
 
 }  // namespace
 
-int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s) {
+int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float *delta, int64_t ldd, float alpha,
+                       hipStream_t s) {
     DecParams p;
+    p.delta = delta;
+    p.ldd = ldd;
+    p.alpha = alpha;
+    const bool axpy = delta != nullptr;
     p.mant = (const uint8_t *)t->mant;
     p.exps = t->exps;
     p.dst = dst;
@@ -116,21 +141,36 @@ int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s) {
         p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
         p.gp_log2 = t->kblock_pad == 32 ? 2 : t->kblock_pad == 64 ? 3 : 4;
         p.vec_ok = (((uintptr_t)dst & 15) == 0 && (ld % 4) == 0 && (t->kblock % 4) == 0) ? 1 : 0;
+        if (axpy && (((uintptr_t)delta & 15) != 0 || (ldd % 4) != 0)) p.vec_ok = 0;
         const int64_t gx = ceil_div(t->rows, (int64_t)(kThreads >> l2));
         int64_t gy = p.nseg > 65535 ? 65535 : p.nseg;
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
         const dim3 grid((unsigned)gx, (unsigned)gy);
-        if (wide) hipLaunchKernelGGL((dec_row_kernel<true>), grid, dim3(kThreads), 0, s, p);
-        else hipLaunchKernelGGL((dec_row_kernel<false>), grid, dim3(kThreads), 0, s, p);
+        if (axpy) {
+            if (wide) hipLaunchKernelGGL((dec_row_kernel<true, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_row_kernel<false, true>), grid, dim3(kThreads), 0, s, p);
+        } else {
+            if (wide) hipLaunchKernelGGL((dec_row_kernel<true, false>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_row_kernel<false, false>), grid, dim3(kThreads), 0, s, p);
+        }
     } else {
         const int64_t gx = ceil_div(t->src_cols, kThreads);
         int64_t gy = t->src_rows > 65535 ? 65535 : t->src_rows;
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
         const dim3 grid((unsigned)gx, (unsigned)gy);
-        if (wide) hipLaunchKernelGGL((dec_any_kernel<true>), grid, dim3(kThreads), 0, s, p);
-        else hipLaunchKernelGGL((dec_any_kernel<false>), grid, dim3(kThreads), 0, s, p);
+        if (axpy) {
+            if (wide) hipLaunchKernelGGL((dec_any_kernel<true, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_any_kernel<false, true>), grid, dim3(kThreads), 0, s, p);
+        } else {
+            if (wide) hipLaunchKernelGGL((dec_any_kernel<true, false>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_any_kernel<false, false>), grid, dim3(kThreads), 0, s, p);
+        }
     }
     return launch_status();
+}
+
+int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s) {
+    return launch_decode_axpy(t, dst, ld, nullptr, 0, 0.0f, s);
 }
 
 }  // namespace hbfp

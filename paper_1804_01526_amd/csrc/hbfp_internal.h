@@ -35,6 +35,9 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
 
 // decode.hip
 int launch_decode(const hbfp_tensor *t, float *dst, int64_t ld, hipStream_t s);
+// dst = fma(alpha, delta, decode(t)); delta == nullptr: plain decode
+int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float *delta, int64_t ldd, float alpha,
+                       hipStream_t s);
 
 // gemm.hip
 struct GemmArgs {

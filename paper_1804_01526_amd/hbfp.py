@@ -64,7 +64,9 @@ def _load():
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
-    for name in ("hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
+    lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
+    for name in ("hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace", "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
@@ -215,3 +217,28 @@ def gemm_f32(trans_a: int, trans_b: int, A: torch.Tensor, B: torch.Tensor, fa: F
                               _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                               _stream_ptr(stream)), "hbfp_gemm_f32")
     return out
+
+
+def _desc_ref(t: Optional[BfpTensor]):
+    return None if t is None else ctypes.byref(t.desc)
+
+
+def weight_update_workspace(wide: BfpTensor, narrow_a: Optional[BfpTensor] = None,
+                            narrow_b: Optional[BfpTensor] = None) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_weight_update_workspace(ctypes.byref(wide.desc), _desc_ref(narrow_a), _desc_ref(narrow_b),
+                                             ctypes.byref(n)), "hbfp_weight_update_workspace")
+    return int(n.value)
+
+
+def weight_update(wide: BfpTensor, delta: torch.Tensor, alpha: float, narrow_a: Optional[BfpTensor] = None,
+                  narrow_b: Optional[BfpTensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_weight_update: wide <- encode(fma(alpha, delta, value(wide))), and the same FP32 result into the narrow tensors."""
+    assert delta.is_cuda and delta.dtype == torch.float32 and delta.dim() == 2 and delta.stride(1) == 1
+    workspace = _workspace(weight_update_workspace(wide, narrow_a, narrow_b), delta.device, workspace)
+    _check(_lib.hbfp_weight_update(ctypes.byref(wide.desc), _dev_ptr(delta), delta.stride(0), alpha,
+                                   _desc_ref(narrow_a), _desc_ref(narrow_b), _dev_ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
+           "hbfp_weight_update")
+    return workspace
+

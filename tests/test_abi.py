@@ -174,3 +174,30 @@ def test_gemm_f32_validation():
     # weight-gradient shape: both operands are blocked down their rows
     fx, fdy = hbfp.make_format(8, 32, 1), hbfp.make_format(8, 32, 1)
     assert hbfp.gemm_f32_workspace(1, 0, 128, 64, 4096, fx, fdy) > 0
+
+
+def test_weight_update_validation():
+    lib = hbfp._lib
+    byref = ctypes.byref
+    fake = ctypes.c_void_p(0x1000)
+
+    def planned(rows, cols, axis, m, br=24, bc=24):
+        d = hbfp.plan(hbfp.make_format(m, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    wide, n0, n1 = planned(100, 200, 1, 16), planned(100, 200, 0, 8), planned(100, 200, 1, 8)
+    n = ctypes.c_size_t(0)
+    assert lib.hbfp_weight_update_workspace(byref(wide), byref(n0), byref(n1), byref(n)) == hbfp.OK
+    assert n.value >= 100 * 200 * 4 and n.value % 256 == 0
+    assert lib.hbfp_weight_update_workspace(byref(wide), None, None, byref(n)) == hbfp.OK
+    assert lib.hbfp_weight_update_workspace(None, None, None, byref(n)) == hbfp.ERR_ARG
+    other = planned(100, 201, 1, 8)
+    assert lib.hbfp_weight_update_workspace(byref(wide), byref(other), None, byref(n)) == hbfp.ERR_LAYOUT
+    ws = 1 << 20
+    assert lib.hbfp_weight_update(byref(wide), None, 200, 1.0, None, None, fake, ws, None) == hbfp.ERR_ARG
+    assert lib.hbfp_weight_update(byref(wide), fake, 199, 1.0, None, None, fake, ws, None) == hbfp.ERR_ARG
+    assert lib.hbfp_weight_update(byref(wide), fake, 200, 1.0, byref(n0), byref(n1), None, 0, None) == hbfp.ERR_WORKSPACE
+    assert lib.hbfp_weight_update(byref(wide), fake, 200, 1.0, byref(n0), byref(n1), fake, 1024, None) == hbfp.ERR_WORKSPACE
+    nobuf = hbfp.plan(hbfp.make_format(8, 24, 24), 100, 200, 0)
+    assert lib.hbfp_weight_update(byref(wide), fake, 200, 1.0, byref(nobuf), None, fake, ws, None) != hbfp.OK
