@@ -162,6 +162,24 @@ def _time_call(torch, fn, reps):
     return sorted(a.elapsed_time(b) for a, b in ev)[reps // 2]
 
 
+def _weight_update_config4(torch, hbfp, synth, reps=10):
+    """Config 4's weights (4096 x 4096, 24 x 24 tiles) kept with 16-bit mantissas: one FP32 update step
+    re-encoded into the wide copy and the two 8-bit operand layouts (forward, data gradient)."""
+    _, Wh, dYh = synth.c4_linear()
+    W, G = torch.from_numpy(Wh).cuda(), torch.from_numpy(dYh).cuda()
+    f_wide, f_nar = hbfp.make_format(16, 24, 24), hbfp.make_format(8, 24, 24)
+    wide = hbfp.encode(W, 1, f_wide)
+    na, nb = hbfp.alloc(f_nar, 4096, 4096, 0), hbfp.alloc(f_nar, 4096, 4096, 1)
+    ws = torch.empty(hbfp.weight_update_workspace(wide, na, nb), dtype=torch.uint8, device="cuda")
+    ms = _time_call(torch, lambda: hbfp.weight_update(wide, G, -1e-3, na, nb, workspace=ws), reps)
+    n = 4096 * 4096
+    nblocks = 171 * 171
+    alg = n * (2 + 4 + 2 + 1 + 1) + 4 * nblocks          # read wide + step, write wide + two narrow copies; one exponent per tile
+    return {"weight_update_c4": {"ms": round(ms, 4), "GBps": round(alg / ms / 1e6, 1), "bytes": alg,
+                                 "note": "first version: fused decode+step into FP32 scratch, then three encode launches "
+                                         "(28 B/element of traffic against 10 B/element algorithmic)"}}
+
+
 def _gemm_side_configs(torch, hbfp, synth, reps=10):
     """Config 3 (conv lowered to GEMM; forward, dgrad, wgrad), kernel-only and including encodes."""
     res = {}
@@ -334,6 +352,7 @@ def main():
                                   "traffic": TRAFFIC_ENCODE_C2_M8_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
                                   "algorithmic_bytes": e["bytes"], "avg_launch_ms": e["ms"]}
         extra.update(_gemm_side_configs(torch, hbfp, synth))
+        extra.update(_weight_update_config4(torch, hbfp, synth))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)
