@@ -176,8 +176,7 @@ def _weight_update_config4(torch, hbfp, synth, reps=10):
     nblocks = 171 * 171
     alg = n * (2 + 4 + 2 + 1 + 1) + 4 * nblocks          # read wide + step, write wide + two narrow copies; one exponent per tile
     return {"weight_update_c4": {"ms": round(ms, 4), "GBps": round(alg / ms / 1e6, 1), "bytes": alg,
-                                 "note": "first version: fused decode+step into FP32 scratch, then three encode launches "
-                                         "(28 B/element of traffic against 10 B/element algorithmic)"}}
+                                 "note": "one kernel: tiles of the updated weights stay in registers; 10 B/element algorithmic"}}
 
 
 def _gemm_side_configs(torch, hbfp, synth, reps=10):

@@ -220,8 +220,9 @@ int hbfp_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
  * and rounding each (typically wide = 16 bits, narrow_a/narrow_b = the forward and
  * the transposed operand of 8 or 12 bits).  wide must hold an encoded tensor; the
  * narrow tensors are outputs only.  Every output is what hbfp_encode would give for
- * the FP32 matrix w', bit for bit; w' itself is left in the first
- * src_rows*src_cols floats of the workspace.
+ * the FP32 matrix w', bit for bit.  The workspace contents afterwards are unspecified
+ * (when all tensors share a 2-D tile shape of at most 32 x 32, as the paper's 24 x 24,
+ * w' only ever exists in registers).
  * workspace: hbfp_weight_update_workspace bytes, 256-byte aligned.
  * Errors: HBFP_ERR_ARG (null/misaligned pointer, ld < src_cols), HBFP_ERR_LAYOUT
  * (descriptors of different source shapes or inconsistent), HBFP_ERR_WORKSPACE.

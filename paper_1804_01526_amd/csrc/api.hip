@@ -189,6 +189,7 @@ int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes) {
 
 // src [src_rows][ld] -> the buffers of t, in t's own layout and format
 static int encode_planned(const float *src, int64_t ld, const hbfp_tensor *t, bool tile_pass, void *workspace, hipStream_t s) {
+    if (t->rblock > 1 && tile_path_ok(&t, 1, nullptr, src, ld)) return launch_tile_encode(src, ld, 1.0f, nullptr, &t, 1, s);
     const EncodeGeom g = geom_of(*t, ld);
     if (tile_pass) return launch_encode_generic(src, g, t->mant, t->exps, (uint32_t *)workspace, s);
     if (t->contract_axis == 1) return launch_encode_row_fused(src, g, t->mant, t->exps, s);
@@ -258,6 +259,13 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
     if (ld < wide->src_cols) return HBFP_ERR_ARG;
     if (!workspace || ws_bytes < total || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    {   // all copies share a tile shape of at most 32 x 32: one kernel, the updated weights never leave the registers
+        const hbfp_tensor *outs[3] = {wide, nullptr, nullptr};
+        int n = 1;
+        if (narrow_a) outs[n++] = narrow_a;
+        if (narrow_b) outs[n++] = narrow_b;
+        if (wide->rblock > 1 && tile_path_ok(outs, n, wide, delta, ld)) return launch_tile_encode(delta, ld, alpha, wide, outs, n, s);
+    }
     float *w = (float *)workspace;
     void *scratch = (char *)workspace + tmp_bytes;
     const int64_t ldw = wide->src_cols;

@@ -50,6 +50,11 @@ struct GemmArgs {
     float beta;
     int32_t *P;                       // non-null: dump block partials instead of C
 };
+// 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
+// up to three outputs of the same tile shape in any orientation
+bool tile_path_ok(const hbfp_tensor *const *outs, int n, const hbfp_tensor *wide_in, const float *src, int64_t ld);
+int launch_tile_encode(const float *src, int64_t ld, float alpha, const hbfp_tensor *wide_in, const hbfp_tensor *const *outs,
+                       int n, hipStream_t s);
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld);
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);

@@ -82,6 +82,30 @@ def test_encode_tiles_and_long_blocks(hb, rows, cols, axis, br, bc, m, rounding)
     _check(hb, _data((rows, cols), rows + 13 * cols), axis, br, bc, m, rounding, seed=0xABCD)
 
 
+REGISTER_TILE_CASES = [
+    # tiles of at most 32 x 32 with column counts and tile widths that are multiples of 4: the register-tile kernel
+    # rows, cols, br, bc, m, rounding
+    (100, 100, 24, 24, 8, 0), (130, 72, 24, 24, 8, 1), (97, 1060, 32, 32, 8, 0), (33, 44, 3, 8, 8, 0), (64, 64, 8, 4, 8, 1),
+    (260, 200, 17, 20, 12, 0), (50, 96, 24, 12, 16, 0), (75, 132, 32, 28, 16, 1), (1, 8, 24, 24, 8, 0), (500, 36, 9, 32, 12, 1),
+]
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("rows,cols,br,bc,m,rounding", REGISTER_TILE_CASES)
+def test_encode_small_tiles_both_orientations(hb, rows, cols, br, bc, m, rounding, axis):
+    _check(hb, _data((rows, cols), rows + 17 * cols + axis), axis, br, bc, m, rounding, seed=0x5EED + br)
+
+
+def test_encode_small_tiles_from_misaligned_source(hb):
+    """Leading dimensions and starts that rule out 16-byte loads take the other tile path; same bytes."""
+    big = _data((60, 1100), 6)
+    g = torch.from_numpy(big).cuda()
+    for c0, cols in ((0, 1000), (4, 1024), (3, 1000), (0, 998)):
+        view = g[:, c0:c0 + cols]
+        for axis in (0, 1):
+            _check(hb, big[:, c0:c0 + cols].copy(), axis, 24, 24, 8, 0, src=view)
+
+
 def test_encode_from_strided_source(hb):
     big = _data((70, 1100), 5)
     g = torch.from_numpy(big).cuda()
