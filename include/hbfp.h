@@ -204,6 +204,26 @@ int hbfp_gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
                   void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_encode_multi: convert one FP32 matrix into up to three operand tensors in
+ * one call.  A tensor that takes part in the forward and in a backward product is
+ * contracted along a different axis in each (Sec. 5.1: the inputs of both passes are
+ * converted), so it is needed in two layouts, possibly with different exponent
+ * blocks (e.g. 1 x 24 along its rows and 24 x 1 down its columns).
+ * src: device FP32 [src_rows][ld].  outs[i]: descriptors from hbfp_plan for the same
+ * source shape with both device buffers set; each output is what hbfp_encode gives
+ * for its own axis and format, bit for bit.  When all outputs are cut into the same
+ * 2-D tiles of at most 32 x 32 (width a multiple of 4, equal rounding mode) the
+ * source is read once; otherwise the outputs are produced one after the other (for
+ * 1-D blocks the separate row and column kernels are faster than a shared read).
+ * workspace: hbfp_encode_multi_workspace bytes (0 for the one-pass case).
+ * Errors: HBFP_ERR_ARG (n outside 1..3, null/misaligned pointers, ld < src_cols),
+ * HBFP_ERR_LAYOUT (different source shapes, inconsistent descriptor), HBFP_ERR_WORKSPACE.
+ */
+int hbfp_encode_multi_workspace(int n, const hbfp_tensor *const *outs, size_t *bytes);
+int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs,
+                      void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_weight_update: one step on weights kept in BFP with wide mantissas
  * (Sec. 4.2 "Wide weight storage"; Sec. 5.1, the optimizer shell: the update is
  * computed in FP32 and the result is converted to two BFP formats, the wide one

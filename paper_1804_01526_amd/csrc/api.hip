@@ -213,6 +213,43 @@ int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int co
     return encode_planned(src, ld, out, need != 0, workspace, (hipStream_t)stream);
 }
 
+static int encode_multi_check(int n, const hbfp_tensor *const *outs, size_t *scratch) {
+    if (n < 1 || n > 3 || !outs) return HBFP_ERR_ARG;
+    *scratch = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!outs[i]) return HBFP_ERR_ARG;
+        int rc = check_tensor(outs[i], true);
+        if (rc != HBFP_OK) return rc;
+        if (outs[i]->src_rows != outs[0]->src_rows || outs[i]->src_cols != outs[0]->src_cols) return HBFP_ERR_LAYOUT;
+        if (((uintptr_t)outs[i]->mant & 15) || ((uintptr_t)outs[i]->exps & 3)) return HBFP_ERR_ARG;
+        size_t b = 0;
+        hbfp_encode_workspace(outs[i], &b);
+        *scratch = b > *scratch ? b : *scratch;
+    }
+    return HBFP_OK;
+}
+
+int hbfp_encode_multi_workspace(int n, const hbfp_tensor *const *outs, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    return encode_multi_check(n, outs, bytes);
+}
+
+int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs,
+                      void *workspace, size_t ws_bytes, void *stream) {
+    size_t need = 0;
+    int rc = encode_multi_check(n, outs, &need);
+    if (rc != HBFP_OK) return rc;
+    if (!src || ((uintptr_t)src & 3) || ld < outs[0]->src_cols) return HBFP_ERR_ARG;
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (n > 1 && tile_path_ok(outs, n, nullptr, src, ld)) return launch_tile_encode(src, ld, 1.0f, nullptr, outs, n, s);
+    for (int i = 0; i < n; ++i) {
+        rc = encode_planned(src, ld, outs[i], needs_tile_pass(*outs[i]), workspace, s);
+        if (rc != HBFP_OK) return rc;
+    }
+    return HBFP_OK;
+}
+
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
     if (!dst) return HBFP_ERR_ARG;
     int rc = check_tensor(t, true);

@@ -64,9 +64,11 @@ def _load():
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
+    lib.hbfp_encode_multi_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(sz)]
+    lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace", "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
@@ -241,4 +243,29 @@ def weight_update(wide: BfpTensor, delta: torch.Tensor, alpha: float, narrow_a: 
                                    0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
            "hbfp_weight_update")
     return workspace
+
+
+def _desc_array(outs):
+    arr = (ctypes.POINTER(TensorDesc) * len(outs))()
+    for i, t in enumerate(outs):
+        arr[i] = ctypes.pointer(t.desc)
+    return arr
+
+
+def encode_multi_workspace(outs) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_multi_workspace(len(outs), _desc_array(outs), ctypes.byref(n)), "hbfp_encode_multi_workspace")
+    return int(n.value)
+
+
+def encode_multi(src: torch.Tensor, outs, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_encode_multi: one FP32 matrix into up to three planned operand tensors (see ``alloc``)."""
+    assert src.is_cuda and src.dtype == torch.float32 and src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(src.stride(0), cols)
+    arr = _desc_array(outs)
+    workspace = _workspace(encode_multi_workspace(outs), src.device, workspace)
+    _check(_lib.hbfp_encode_multi(_dev_ptr(src), ld, len(outs), arr, _dev_ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_multi")
+    return outs
 

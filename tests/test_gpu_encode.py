@@ -168,3 +168,35 @@ def test_config2_full_size_bit_exact(hb, m, rounding):
     assert np.array_equal(got_m, want.mant.reshape(-1).astype(got_m.dtype))
     assert np.array_equal(bt.exps.cpu().numpy().reshape(-1), want.exps.reshape(-1))
     assert np.array_equal(back.cpu().numpy(), ref.decode(want))
+
+
+MULTI_CASES = [
+    # rows, cols, [(axis, br, bc, m)], rounding
+    (100, 120, [(1, 1, 24, 8), (0, 24, 1, 8)], 0),                       # an activation: along its rows and down its columns
+    (4100, 48, [(1, 1, 24, 8), (0, 24, 1, 8)], 1),
+    (130, 264, [(0, 24, 24, 8), (1, 24, 24, 8)], 0),                     # a weight matrix: both orientations of its tiles
+    (96, 96, [(1, 24, 24, 16), (0, 24, 24, 8), (1, 24, 24, 8)], 0),      # wide copy + two narrow copies
+    (70, 200, [(1, 1, 32, 12), (0, 16, 1, 8), (1, 16, 32, 8)], 1),       # rows, columns and whole tiles of a 16 x 32 tile
+    (64, 100, [(1, 1, 24, 8), (0, 24, 1, 8)], 0),                        # 100 columns: not a whole number of blocks
+    (50, 90, [(1, 1, 24, 8), (0, 24, 1, 8)], 0),                         # 90 columns: not a multiple of 4 -> one launch per output
+    (80, 128, [(1, 1, 64, 8), (0, 64, 1, 8)], 0),                        # blocks longer than 32 -> one launch per output
+]
+
+
+@pytest.mark.parametrize("rows,cols,outs,rounding", MULTI_CASES)
+def test_encode_multi_matches_single_encodes(hb, rows, cols, outs, rounding):
+    x = _data((rows, cols), rows * 5 + cols)
+    print(f"[case] shape={x.shape} outs={outs} rounding={rounding}", flush=True)
+    g = torch.from_numpy(x).cuda()
+    fmts = [hb.make_format(m, br, bc, rounding, 100 + i) for i, (axis, br, bc, m) in enumerate(outs)]
+    tensors = [hb.alloc(f, rows, cols, axis) for f, (axis, _, _, _) in zip(fmts, outs)]
+    for t in tensors:                                  # poison the outputs: padding must be rewritten too
+        t.mant.fill_(0x55)
+        t.exps.fill_(0x55)
+    hb.encode_multi(g, tensors)
+    torch.cuda.synchronize()
+    for i, (t, (axis, br, bc, m)) in enumerate(zip(tensors, outs)):
+        want = ref.encode(x, br, bc, m, rounding, 100 + i)
+        mant, exps = unpack(t)
+        np.testing.assert_array_equal(exps, want.exps)
+        np.testing.assert_array_equal(mant, want.mant)
