@@ -201,3 +201,29 @@ def test_weight_update_validation():
     assert lib.hbfp_weight_update(byref(wide), fake, 200, 1.0, byref(n0), byref(n1), fake, 1024, None) == hbfp.ERR_WORKSPACE
     nobuf = hbfp.plan(hbfp.make_format(8, 24, 24), 100, 200, 0)
     assert lib.hbfp_weight_update(byref(wide), fake, 200, 1.0, byref(nobuf), None, fake, ws, None) != hbfp.OK
+
+
+def test_encode_multi_validation():
+    lib = hbfp._lib
+    T = ctypes.POINTER(hbfp.TensorDesc)
+    fake = ctypes.c_void_p(0x1000)
+
+    def planned(rows, cols, axis, br, bc):
+        d = hbfp.plan(hbfp.make_format(8, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    a, b, c = planned(96, 200, 1, 1, 24), planned(96, 200, 0, 24, 1), planned(96, 204, 0, 24, 1)
+    n = ctypes.c_size_t(7)
+    arr = (T * 2)(ctypes.pointer(a), ctypes.pointer(b))
+    assert lib.hbfp_encode_multi_workspace(2, arr, ctypes.byref(n)) == hbfp.OK and n.value == 0
+    assert lib.hbfp_encode_multi_workspace(0, arr, ctypes.byref(n)) == hbfp.ERR_ARG
+    assert lib.hbfp_encode_multi_workspace(4, arr, ctypes.byref(n)) == hbfp.ERR_ARG
+    bad = (T * 2)(ctypes.pointer(a), ctypes.pointer(c))
+    assert lib.hbfp_encode_multi_workspace(2, bad, ctypes.byref(n)) == hbfp.ERR_LAYOUT
+    assert lib.hbfp_encode_multi(None, 200, 2, arr, None, 0, None) == hbfp.ERR_ARG
+    assert lib.hbfp_encode_multi(fake, 100, 2, arr, None, 0, None) == hbfp.ERR_ARG       # ld < src_cols
+    big = planned(96, 200, 1, 96, 200)                                                    # one block for the matrix: needs scratch
+    arr2 = (T * 2)(ctypes.pointer(a), ctypes.pointer(big))
+    assert lib.hbfp_encode_multi_workspace(2, arr2, ctypes.byref(n)) == hbfp.OK and n.value > 0
+    assert lib.hbfp_encode_multi(fake, 200, 2, arr2, None, 0, None) == hbfp.ERR_WORKSPACE
