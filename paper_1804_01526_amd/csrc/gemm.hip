@@ -399,6 +399,8 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], d0, 0, 0, 0);                           \
             d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], d1, 0, 0, 0);                           \
         }                                                                                               \
+        /* both results live at once: the second matrix instruction runs while the first is scaled */   \
+        asm volatile("" ::"v"(d0), "v"(d1));                                                            \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         MIDDLE;                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                              \
