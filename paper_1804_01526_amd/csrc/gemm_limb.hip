@@ -380,6 +380,7 @@ __global__ __launch_bounds__(kLwThreads, 4) void gemm_limb_w8_kernel(const LimbW
         }                                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         const v16i sa = row_constants(rowc, one_hot);                                                   \
+        asm volatile("" ::"v"(sa));   /* issued here: the recombination below covers its latency */     \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         int P[16];                                                                                      \
         _Pragma("unroll") for (int v = 0; v < 16; ++v) P[v] = (((hh[v] << 6) + mid[v]) << 6) + ll[v];   \
