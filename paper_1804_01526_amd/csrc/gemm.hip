@@ -347,13 +347,23 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     const uint32_t ldsW = 2 * kHalfTile + (wave_u < 4 ? 0 : kHalfWords) + (wc >> 1) * 512 + (wc & 1) * 256;
     const int spb64 = SPB == 0 ? p.spb / 2 : 1;                                  // stages per block when blocks span stages
 
-#define HBFP_COPY_STAGE(st, ring)                                                                       \
+    // stages are requested in order, so the three source pointers of this wave just advance
+    const uint8_t *nextA = tileA + (int64_t)st_begin * kHalfK, *nextB = tileB + (int64_t)st_begin * kHalfK;
+    int st_req = st_begin;                                                       // next stage to request
+    const uint32_t *nextW = wordsrc + (SPB == 1 ? 2 * (int64_t)st_begin + (wc >> 1) : SPB == 2 ? (int64_t)st_begin : (int64_t)st_begin / spb64) * wordpitch;
+    const int64_t stepW = (SPB == 1 ? 2 : 1) * wordpitch;                        // words per stage (long blocks: per block)
+    int req_pos = 0;                                                             // SPB == 0: stage within its block
+#define HBFP_COPY_NEXT(ring)                                                                            \
     {                                                                                                   \
         const uint32_t lb = (ring) * kHalfStage;                                                        \
-        async_copy16(tileA + (int64_t)(st) * kHalfK, voffA, lb + ldsM);                                 \
-        async_copy16(tileB + (int64_t)(st) * kHalfK, voffB, lb + kHalfTile + ldsM);                     \
-        const int64_t blk_ = SPB == 1 ? 2 * (int64_t)(st) + (wc >> 1) : SPB == 2 ? (int64_t)(st) : (int64_t)(st) / spb64; \
-        async_copy4(wordsrc + blk_ * wordpitch, voffW, lb + ldsW);                                      \
+        async_copy16(nextA, voffA, lb + ldsM);                                                          \
+        async_copy16(nextB, voffB, lb + kHalfTile + ldsM);                                              \
+        async_copy4(nextW, voffW, lb + ldsW);                                                           \
+        nextA += kHalfK;                                                                                \
+        nextB += kHalfK;                                                                                \
+        ++st_req;                                                                                       \
+        if (SPB != 0) nextW += stepW;                                                                   \
+        else if (++req_pos == spb64) { req_pos = 0; nextW += stepW; }                                   \
     }
 #define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 
@@ -440,17 +450,17 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                      \
                 __builtin_amdgcn_s_barrier();                                                           \
                 asm volatile("" ::: "memory");                                                          \
-                if (rem >= 4) HBFP_COPY_STAGE(st + 4, ring);                                            \
+                if (rem >= 4) HBFP_COPY_NEXT(ring);                                            \
                 HBFP_READ_STEP(((ring) + 1) & 3, 0, 0);                                                 \
             }                                                                                           \
         });                                                                                             \
     }
 
     if (nst > 0) {
-        HBFP_COPY_STAGE(st_begin, 0);
-        if (nst > 1) HBFP_COPY_STAGE(st_begin + 1, 1);
-        if (nst > 2) HBFP_COPY_STAGE(st_begin + 2, 2);
-        if (nst > 3) HBFP_COPY_STAGE(st_begin + 3, 3);
+        HBFP_COPY_NEXT(0);
+        if (nst > 1) HBFP_COPY_NEXT(1);
+        if (nst > 2) HBFP_COPY_NEXT(2);
+        if (nst > 3) HBFP_COPY_NEXT(3);
         if (nst > 3) HBFP_WAIT_COPIES(9); else if (nst == 3) HBFP_WAIT_COPIES(6); else if (nst == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0);
     }
     __builtin_amdgcn_s_barrier();
@@ -477,7 +487,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
 #undef HBFP_STAGE
-#undef HBFP_COPY_STAGE
+#undef HBFP_COPY_NEXT
 #undef HBFP_WAIT_COPIES
 
 #pragma unroll
