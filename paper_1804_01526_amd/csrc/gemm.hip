@@ -3,14 +3,17 @@
 //     C[i][j] = sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k] * mB[j][k]
 //
 // Both operands are stored with k contiguous (public header), so this is an "NT"
-// product.  A workgroup of 4 waves owns a 128 x 128 tile of C; a wave owns 64 x 64 as
-// 2 x 2 tiles of v_mfma_i32_32x32x32_i8.  A stage is 128 bytes of k for all 256
-// operand rows of the tile, staged through LDS (double buffered).
+// product over 128 x 128 tiles of C.  Two kernels:
+//   gemm_i8_w8_kernel   the product itself, every block length: 8 waves per workgroup, asynchronous
+//                       global -> LDS copies through a ring of LDS buffers (described where it starts);
+//   gemm_i8_kernel      4 waves, 2 x 2 matrix tiles per wave, operands staged through registers: kept for
+//                       the dump of the integer block sums (hbfp_gemm_partials) and for operands too
+//                       long for 32-bit tile offsets.
 //
 // The per-block scaling is the expensive part on this chip (one FP32 operation per 2*B
 // integer operations is cheap next to 8-bit multipliers in the paper's accelerator,
-// Sec. 4.2; here the matrix core retires 2048 integer operations per clock and SIMD while the
-// vector ALU retires 16 lanes).  It is kept to two vector instructions per output and block:
+// Sec. 4.2; here one matrix instruction covers 32 x 32 outputs of a block in 32 clocks while
+// scaling them takes 32 vector instructions).  It is kept to two vector instructions per output and block:
 //   1. the matrix core starts from a constant C input whose int32 bit pattern is the
 //      float 1.5 * 2^(Ea - 127): adding the integer block sum P (|P| < 2^22) to those
 //      bits gives the float (1.5 * 2^23 + P) * 2^(Ea - 150), so the int->float
