@@ -8,8 +8,11 @@
 // P is recombined exactly in int32, converted to FP32 (round to nearest even above 2^24),
 // scaled by the row and the column exponent and accumulated in FP32.
 //
-// A workgroup of 4 waves owns 64 x 128 of C, a wave 32 x 64 (1 x 2 tiles of
-// v_mfma_i32_32x32x32_i8); a stage is 64 bytes of k of both limb planes of both operands.
+// Two kernels over 64 x 128 tiles of C, a stage being 64 bytes of k of both limb planes of both
+// operands: gemm_limb_w8_kernel for blocks of 64 (8 waves, asynchronous copies; described where it
+// starts) and gemm_limb_kernel for every other block length and for the dump of the integer block
+// sums (4 waves, a wave owns 32 x 64 as 1 x 2 tiles of v_mfma_i32_32x32x32_i8, operands staged
+// through registers).
 #include "gemm_common.h"
 
 namespace hbfp {
