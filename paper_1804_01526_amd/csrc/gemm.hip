@@ -278,9 +278,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
 //     within 128 registers; it relies on the other waves, not on software pipelining, to cover the
 //     latency of its matrix instructions and LDS reads;
 //   - moves operands global -> LDS with the asynchronous copy instruction (no registers, no LDS stores,
-//     no wait in the wave), three copies per wave and stage, issued right after the stage hand-over;
-//   - stages 64 bytes of k at a time through a ring of four LDS buffers, so a copy has three stages of
-//     compute to land;
+//     no wait in the wave), three copies per wave and stage, issued right after a hand-over;
+//   - stages 64 bytes of k at a time through a ring of four LDS buffers, handed over two at a time, so a
+//     copy has two stages of compute to land and there is one barrier per four k-steps;
 //   - does not read the C input of a k-step (the row constant 1.5 * 2^(Ea - 127), the same in all 32
 //     columns) from LDS, where it would be 16 registers per wave and step: one bf16 matrix instruction
 //     spreads one register of row constants over the 32 x 32 output layout (the constant has a 2-bit
@@ -437,34 +437,43 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         }                                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
     }
-    // Stage st lives in ring buffer (st - st_begin) & 3.  The hand-over sits in k-step 1 right after its
-    // matrix instructions are issued: by then this wave has consumed every LDS read of the stage, so
-    // after the barrier the buffer is free for stage st + 4, and stage st + 1 has landed for everyone
-    // (copies complete in issue order: all but the newest two groups of three).
-#define HBFP_STAGE(ring)                                                                                \
+    // Stages come in pairs (a stage is 64 bytes of k, the stored k extent and every split-K range are
+    // multiples of 128); the pair starting at stage st lives in ring buffers {0, 1} or {2, 3}.  There is one
+    // hand-over per pair, in its last k-step right after the matrix instructions are issued: by then this
+    // wave has consumed every LDS read of the pair, so after the barrier both buffers are free for the pair
+    // after next, and the next pair - requested a pair earlier - has landed for everyone.  One barrier per
+    // four k-steps instead of two was worth 5 % although a copy now has two stages instead of three to land.
+#define HBFP_PAIR(ring)                                                                                 \
     {                                                                                                   \
-        const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                             \
-        pos = pos == spb64 - 1 ? 0 : pos + 1;                                                           \
-        HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                     \
-        HBFP_STEP(1, SPB == 1, last1, {                                                                 \
-            const int rem = st_end - 1 - st;                                                            \
-            if (rem > 0) {                                                                              \
-                if (rem >= 3) HBFP_WAIT_COPIES(6); else if (rem == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0); \
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                      \
-                __builtin_amdgcn_s_barrier();                                                           \
-                asm volatile("" ::: "memory");                                                          \
-                if (rem >= 4) HBFP_COPY_NEXT(ring);                                            \
-                HBFP_READ_STEP(((ring) + 1) & 3, 0, 0);                                                 \
-            }                                                                                           \
-        });                                                                                             \
+        {                                                                                               \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                         \
+            pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
+            HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                 \
+            HBFP_STEP(1, SPB == 1, last1, HBFP_READ_STEP((ring) + 1, 0, 0));                            \
+        }                                                                                               \
+        {                                                                                               \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                         \
+            pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
+            HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP((ring) + 1, 1, 1));                           \
+            HBFP_STEP(1, SPB == 1, last1, {                                                             \
+                const int rem = st_end - 2 - st;                 /* stages after this pair */           \
+                if (rem > 0) {                                                                          \
+                    HBFP_WAIT_COPIES(0);                                                                \
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                  \
+                    __builtin_amdgcn_s_barrier();                                                       \
+                    asm volatile("" ::: "memory");                                                      \
+                    if (rem >= 4) { HBFP_COPY_NEXT(ring); HBFP_COPY_NEXT((ring) + 1); }                 \
+                    HBFP_READ_STEP(((ring) + 2) & 3, 0, 0);                                             \
+                }                                                                                       \
+            });                                                                                         \
+        }                                                                                               \
     }
 
     if (nst > 0) {
         HBFP_COPY_NEXT(0);
-        if (nst > 1) HBFP_COPY_NEXT(1);
-        if (nst > 2) HBFP_COPY_NEXT(2);
-        if (nst > 3) HBFP_COPY_NEXT(3);
-        if (nst > 3) HBFP_WAIT_COPIES(9); else if (nst == 3) HBFP_WAIT_COPIES(6); else if (nst == 2) HBFP_WAIT_COPIES(3); else HBFP_WAIT_COPIES(0);
+        HBFP_COPY_NEXT(1);
+        if (nst > 2) { HBFP_COPY_NEXT(2); HBFP_COPY_NEXT(3); }
+        if (nst > 2) HBFP_WAIT_COPIES(6); else HBFP_WAIT_COPIES(0);
     }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -476,20 +485,17 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             d1 = row_constants(rowc, one_hot);
         }
     }
-    int pos = 0;                           // stage within its exponent block (splits start on block boundaries)
+    int pos = 0;
     for (int st = st_begin; st < st_end;) {
-        HBFP_STAGE(0);
-        if (++st >= st_end) break;
-        HBFP_STAGE(1);
-        if (++st >= st_end) break;
-        HBFP_STAGE(2);
-        if (++st >= st_end) break;
-        HBFP_STAGE(3);
-        ++st;
+        HBFP_PAIR(0);
+        st += 2;
+        if (st >= st_end) break;
+        HBFP_PAIR(2);
+        st += 2;
     }
+#undef HBFP_PAIR
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
-#undef HBFP_STAGE
 #undef HBFP_COPY_NEXT
 #undef HBFP_WAIT_COPIES
 
