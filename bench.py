@@ -261,6 +261,8 @@ def main():
         sys.exit(2)
     import torch
     import synth
+    import __graft_entry__
+    __graft_entry__.ensure_built()
     from paper_1804_01526_amd import hbfp
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

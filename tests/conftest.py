@@ -8,6 +8,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+import __graft_entry__  # noqa: E402
+
+__graft_entry__.ensure_built()     # a tree without the HIP library (fresh clone): build once; never a CPU fallback
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
