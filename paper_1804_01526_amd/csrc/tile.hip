@@ -1,8 +1,8 @@
 // 2-D exponent tiles of at most 32 x 32 (Sec. 4.2 "Tiling": weight matrices are cut into tiles that
 // share an exponent; the paper uses 24 x 24), converted in one pass with the tile held in registers.
 //
-// A lane owns 4 neighbouring source columns of one tile and walks down the tile's rows (up to 32 rows:
-// up to 128 values in registers); the 8 lanes of a tile combine their maxima with three DPP steps.  From
+// A lane owns 4 neighbouring source columns of half of a tile's rows (at most 16 x 4 values in
+// registers); the 16 lanes of a tile combine their maxima with four DPP steps.  From
 // there the same values can be written in any of the operand layouts of the public header:
 //   contraction along the source rows' direction (axis 1): 4 mantissas per lane and row, one store each;
 //   contraction down the source rows (axis 0): a lane's column of a tile is 32 consecutive mantissas of
@@ -24,10 +24,11 @@ template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
 }
-__device__ __forceinline__ uint32_t max_of_8_lanes(uint32_t v) {
+__device__ __forceinline__ uint32_t max_of_16_lanes(uint32_t v) {
     v = max(v, dpp_u32<0xB1>(v));    // quad_perm [1,0,3,2]
     v = max(v, dpp_u32<0x4E>(v));    // quad_perm [2,3,0,1]
     v = max(v, dpp_u32<0x141>(v));   // row_half_mirror: the other quad of the 8
+    v = max(v, dpp_u32<0x140>(v));   // row_mirror: the other half of the 16
     return v;
 }
 __device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
@@ -59,27 +60,34 @@ struct TileParams {
 
 constexpr int kLineStride = 144;   // a 128-byte line of a transposed output in LDS, padded against bank conflicts
 
+// BR: tile height rounded up to 8.  A tile is shared by 16 lanes: lane (h, j) owns columns 4j .. 4j + 3 of rows
+// h * BR/2 .. (h + 1) * BR/2 - 1 (at most 16 x 4 values in registers), a wave holds 4 tiles, a workgroup 4 tile
+// columns x 4 tile rows (one tile row per wave): the four 32-byte pieces of a 128-byte line of a transposed
+// output are then produced by one workgroup.
 template <int BR, int ROUND>
 __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
-    __shared__ __attribute__((aligned(16))) uint8_t lines[256 * kLineStride];
+    constexpr int RPL = BR / 2;       // rows per lane
+    __shared__ __attribute__((aligned(16))) uint8_t lines[128 * kLineStride];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = lane & 7;
-    // a workgroup takes 8 tile columns x 4 tile rows (one tile row per wave): the four 32-byte pieces of a
-    // 128-byte line of a transposed output are then written at about the same time and merge in L2
-    const int64_t tc = (int64_t)blockIdx.x * 8 + (lane >> 3);
+    const int j = lane & 7, h = (lane >> 3) & 1, tw = lane >> 4;
+    const int64_t tc = (int64_t)blockIdx.x * 4 + tw;
     const int64_t tr = (int64_t)blockIdx.y * 4 + wave;
-    const int64_t row0 = tr * p.br, col0 = tc * p.bc + 4 * j;
+    const int64_t row0 = tr * p.br + h * RPL, col0 = tc * p.bc + 4 * j;
     const bool col_ok = tc < p.nbc && 4 * j < p.bc && col0 < p.cols;       // cols and bc are multiples of 4
-    int br_eff = 0;
-    if (tr < p.nbr) br_eff = (int)((p.rows - row0) < p.br ? (p.rows - row0) : p.br);
+    int rows_here = 0;                                                     // rows of this lane that exist
+    if (tr < p.nbr) {
+        const int64_t tile_rows = (p.rows - tr * p.br) < p.br ? (p.rows - tr * p.br) : p.br;
+        const int64_t mine = tile_rows - h * RPL;
+        rows_here = mine <= 0 ? 0 : (mine < RPL ? (int)mine : RPL);
+    }
 
-    float v[BR][4];
+    float v[RPL][4];
     int we = 0;
-    if (p.w_mant && col_ok && br_eff > 0) we = (int)p.w_exps[row0 * p.w_expld + tc] - 125 - p.w_m;
+    if (p.w_mant && col_ok && rows_here > 0) we = (int)p.w_exps[row0 * p.w_expld + tc] - 125 - p.w_m;
 #pragma unroll
-    for (int r = 0; r < BR; ++r) {
+    for (int r = 0; r < RPL; ++r) {
         v[r][0] = v[r][1] = v[r][2] = v[r][3] = 0.0f;
-        if (r < br_eff && col_ok) {
+        if (r < rows_here && col_ok) {
             const float4 d = *reinterpret_cast<const float4 *>(p.src + (row0 + r) * p.ld + col0);
             if (p.w_mant) {
                 const uint32_t *wp = reinterpret_cast<const uint32_t *>(p.w_mant + ((row0 + r) * p.w_kpad + tc * 32 + 4 * j) * 2);
@@ -95,86 +103,115 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
     }
     uint32_t amax = 0;
 #pragma unroll
-    for (int r = 0; r < BR; ++r)
+    for (int r = 0; r < RPL; ++r)
 #pragma unroll
         for (int e = 0; e < 4; ++e) amax = max(amax, __float_as_uint(v[r][e]) & 0x7fffffffu);
-    amax = max_of_8_lanes(amax);
+    amax = max_of_16_lanes(amax);
 
     for (int oi = 0; oi < 3; ++oi) {
         const TileOut &o = p.o[oi];
         if (!o.present) continue;
         const uint32_t Eb = block_exponent<ROUND>(amax, o.m);
         const bool wide = o.m > 8;
+        // Stochastic rounding: the hashes of a whole tile, computed side by side, need more than 256 registers.
+        // `chain` is always zero, but the compiler cannot know: each group of hashes waits for the previous store.
+        uint32_t chain = 0;
+        if (ROUND) {
+            asm volatile("" : "+v"(chain));
+            // likewise nothing derived from the values (sign, exponent, significand of each) may be kept across outputs
+#pragma unroll
+            for (int r = 0; r < RPL; ++r)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(v[r][e]));
+        }
         // element (row0 + r, col0 + e) of the source; the stochastic-rounding counter is its logical index
         auto q = [&](int r, int e) -> int {
-            const uint64_t idx = (uint64_t)(row0 + r) * (uint64_t)p.cols + (uint64_t)(col0 + e);
-            return quantise<ROUND>(v[r][e], Eb, o.m, (uint32_t)idx, (uint32_t)(idx >> 32), o.s0, o.s1);
+            if (!ROUND) return quantise<0>(v[r][e], Eb, o.m, 0u, 0u, 0u, 0u);
+            // index of the row's first element once per row; adding `chain` before the column offset keeps the
+            // compiler from holding all of a tile's indices in registers across the three outputs
+            const uint64_t rbase = (uint64_t)(row0 + r) * (uint64_t)p.cols + (uint64_t)col0;
+            const uint32_t lo = ((uint32_t)rbase + chain) + (uint32_t)e;
+            const uint32_t hi = (uint32_t)(rbase >> 32) + (lo < (uint32_t)e ? 1u : 0u);
+            float x = v[r][e];
+            asm volatile("" : "+v"(x) : "v"(chain));     // the value's decomposition waits for the previous group too
+            return quantise<ROUND>(x, Eb, o.m, lo, hi, o.s0, o.s1);
         };
         if (o.axis == 1) {
             // operand row = source row; block tc of it holds this tile's columns (lanes without columns write the zero padding)
             if (tc < o.ntile_k) {
 #pragma unroll
-                for (int r = 0; r < BR; ++r) {
-                    if (r >= br_eff) continue;
+                for (int r = 0; r < RPL; ++r) {
+                    if (r >= rows_here) continue;
                     uint8_t *dst = o.mant + ((row0 + r) * o.kpad + tc * 32 + 4 * j) * (wide ? 2 : 1);
-                    if (!wide) *reinterpret_cast<uint32_t *>(dst) = pack4_i8(q(r, 0), q(r, 1), q(r, 2), q(r, 3));
-                    else *reinterpret_cast<uint2 *>(dst) = make_uint2(pack2_i16(q(r, 0), q(r, 1)), pack2_i16(q(r, 2), q(r, 3)));
+                    uint32_t w0, w1 = 0;
+                    if (!wide) {
+                        w0 = pack4_i8(q(r, 0), q(r, 1), q(r, 2), q(r, 3));
+                        *reinterpret_cast<uint32_t *>(dst) = w0;
+                    } else {
+                        w0 = pack2_i16(q(r, 0), q(r, 1));
+                        w1 = pack2_i16(q(r, 2), q(r, 3));
+                        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
+                    }
+                    if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0), "v"(w1));
                 }
             }
             if (tc < o.exp_ld) {
                 const uint8_t eb = tc < p.nbc ? (uint8_t)Eb : (uint8_t)1;
-                for (int r = j; r < br_eff; r += 8) o.exps[(row0 + r) * o.exp_ld + tc] = eb;
+                for (int r = j; r < rows_here; r += 8) o.exps[(row0 + r) * o.exp_ld + tc] = eb;
             }
-        } else {
-            // operand row = source column; block tr of it holds this tile's rows: 32 consecutive mantissas per column
-            if (!wide) {
-                // the four waves (tile rows 4 by .. 4 by + 3) fill [column][4 x 32 bytes], then every 8 threads store one line
-                const int64_t tr0 = (int64_t)blockIdx.y * 4, tc0 = (int64_t)blockIdx.x * 8;
-                __syncthreads();                      // the previous output's lines have been read
+        } else if (!wide) {
+            // operand row = source column; block tr of it holds this tile's rows: 32 consecutive mantissas per column.
+            // The four waves (tile rows 4 by .. 4 by + 3) fill [column][4 x 32 bytes], then every 8 threads store one line.
+            const int64_t tr0 = (int64_t)blockIdx.y * 4, tc0 = (int64_t)blockIdx.x * 4;
+            __syncthreads();                          // the previous output's lines have been read
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t w[8];
+            for (int e = 0; e < 4; ++e) {
+                uint8_t *l = lines + (tw * 32 + 4 * j + e) * kLineStride + wave * 32;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k)
-                        w[k] = 4 * k < BR ? pack4_i8(4 * k + 0 < BR ? q(4 * k + 0, e) : 0, 4 * k + 1 < BR ? q(4 * k + 1, e) : 0,
-                                                     4 * k + 2 < BR ? q(4 * k + 2, e) : 0, 4 * k + 3 < BR ? q(4 * k + 3, e) : 0)
-                                          : 0u;
-                    uint8_t *l = lines + ((lane >> 3) * 32 + 4 * j + e) * kLineStride + wave * 32;
-                    *reinterpret_cast<uint4 *>(l) = make_uint4(w[0], w[1], w[2], w[3]);
-                    *reinterpret_cast<uint4 *>(l + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+                for (int k = 0; k < RPL / 4; ++k)
+                {
+                    const uint32_t w0 = pack4_i8(q(4 * k, e), q(4 * k + 1, e), q(4 * k + 2, e), q(4 * k + 3, e));
+                    *reinterpret_cast<uint32_t *>(l + h * RPL + 4 * k) = w0;
+                    if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0));
                 }
-                __syncthreads();
-                if (tr0 < o.ntile_k) {                // ntile_k is a multiple of 4: all four tile rows are stored or none
-                    for (int g = threadIdx.x; g < 256 * 8; g += kThreads) {
-                        const int lc = g >> 3, ch = g & 7;
-                        const int64_t tcc = tc0 + (lc >> 5), c = tcc * p.bc + (lc & 31);
-                        if (tcc < p.nbc && (lc & 31) < p.bc && c < p.cols)
-                            *reinterpret_cast<uint4 *>(o.mant + c * o.kpad + tr0 * 32 + ch * 16) =
-                                *reinterpret_cast<const uint4 *>(lines + lc * kLineStride + ch * 16);
+                if (h == 1) {                         // rows BR .. 31 of the block are padding
+#pragma unroll
+                    for (int k = BR / 4; k < 8; ++k) *reinterpret_cast<uint32_t *>(l + 4 * k) = 0u;
+                }
+            }
+            __syncthreads();
+            if (tr0 < o.ntile_k) {                    // ntile_k is a multiple of 4: all four tile rows are stored or none
+                for (int g = threadIdx.x; g < 128 * 8; g += kThreads) {
+                    const int lc = g >> 3, ch = g & 7;
+                    const int64_t tcc = tc0 + (lc >> 5), c = tcc * p.bc + (lc & 31);
+                    if (tcc < p.nbc && (lc & 31) < p.bc && c < p.cols)
+                        *reinterpret_cast<uint4 *>(o.mant + c * o.kpad + tr0 * 32 + ch * 16) =
+                            *reinterpret_cast<const uint4 *>(lines + lc * kLineStride + ch * 16);
+                }
+            }
+            if (col_ok && h == 0 && tr < o.exp_ld) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o.exps[(col0 + e) * o.exp_ld + tr] = tr < p.nbr ? (uint8_t)Eb : (uint8_t)1;
+            }
+        } else if (col_ok) {
+            // 16-bit transposed output: each lane stores its rows of its four columns directly (8 bytes at a time)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (tr < o.ntile_k) {
+                    uint8_t *dst = o.mant + ((col0 + e) * o.kpad + tr * 32) * 2;
+#pragma unroll
+                    for (int k = 0; k < RPL / 4; ++k)
+                    {
+                        const uint32_t w0 = pack2_i16(q(4 * k, e), q(4 * k + 1, e)), w1 = pack2_i16(q(4 * k + 2, e), q(4 * k + 3, e));
+                        *reinterpret_cast<uint2 *>(dst + (h * RPL + 4 * k) * 2) = make_uint2(w0, w1);
+                        if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0), "v"(w1));
+                    }
+                    if (h == 1) {
+#pragma unroll
+                        for (int k = BR / 4; k < 8; ++k) *reinterpret_cast<uint2 *>(dst + 8 * k) = make_uint2(0u, 0u);
                     }
                 }
-                if (col_ok && tr < o.exp_ld) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o.exps[(col0 + e) * o.exp_ld + tr] = tr < p.nbr ? (uint8_t)Eb : (uint8_t)1;
-                }
-            } else if (col_ok) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (tr < o.ntile_k) {
-                        uint8_t *dst = o.mant + ((col0 + e) * o.kpad + tr * 32) * 2;
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            uint32_t w[4];
-#pragma unroll
-                            for (int k = 0; k < 4; ++k) {
-                                const int r0 = 8 * g + 2 * k;
-                                w[k] = r0 < BR ? pack2_i16(q(r0, e), r0 + 1 < BR ? q(r0 + 1, e) : 0) : 0u;
-                            }
-                            *reinterpret_cast<uint4 *>(dst + 16 * g) = make_uint4(w[0], w[1], w[2], w[3]);
-                        }
-                    }
-                    if (tr < o.exp_ld) o.exps[(col0 + e) * o.exp_ld + tr] = tr < p.nbr ? (uint8_t)Eb : (uint8_t)1;
-                }
+                if (h == 0 && tr < o.exp_ld) o.exps[(col0 + e) * o.exp_ld + tr] = tr < p.nbr ? (uint8_t)Eb : (uint8_t)1;
             }
         }
     }
@@ -198,7 +235,7 @@ bool tile_path_ok(const hbfp_tensor *const *outs, int n, const hbfp_tensor *wide
     const hbfp_tensor *f = outs[0];
     const int64_t br = f->contract_axis == 1 ? f->rblock : f->kblock, bc = f->contract_axis == 1 ? f->kblock : f->rblock;
     if (br < 1 || br > 32 || bc < 4 || bc > 32 || (bc & 3) || (f->src_cols & 3) || (ld & 3) || ((uintptr_t)src & 15)) return false;
-    if (ceil_div(f->src_rows, br) / 4 + 4 > 65535 || ceil_div(f->src_cols, bc) / 8 + 2 > 0x7fffffff) return false;
+    if (ceil_div(f->src_rows, br) / 4 + 4 > 65535 || ceil_div(f->src_cols, bc) / 4 + 2 > 0x7fffffff) return false;
     for (int i = 0; i < n; ++i)
         if (!fits(outs[i], br, bc) || outs[i]->rounding != f->rounding || outs[i]->src_rows != f->src_rows ||
             outs[i]->src_cols != f->src_cols)
@@ -244,7 +281,7 @@ int launch_tile_encode(const float *src, int64_t ld, float alpha, const hbfp_ten
         if (o.axis == 1) tcs = ext > tcs ? ext : tcs;
         else trs = ext > trs ? ext : trs;
     }
-    const dim3 grid((unsigned)ceil_div(tcs, 8), (unsigned)ceil_div(trs, 4));
+    const dim3 grid((unsigned)ceil_div(tcs, 4), (unsigned)ceil_div(trs, 4));
     const int rounding = f->rounding;
     if (p.br <= 8) launch_br<8>(p, grid, rounding, s);
     else if (p.br <= 16) launch_br<16>(p, grid, rounding, s);
