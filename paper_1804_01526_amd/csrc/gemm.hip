@@ -514,14 +514,23 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         }
 }
 
-// fixed-order sum over the split-K slices: deterministic, no float atomics
+// fixed-order sum over the split-K slices: deterministic, no float atomics.  The slices of one output are
+// requested eight at a time and added in slice order, so the result does not depend on the unrolling.
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *partial, float *C, int64_t M, int64_t N,
                                                                   int64_t ldc, int splits, int beta) {
     const int64_t n = M * N;
     for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kThreads) {
         const int64_t i = e / N, j = e % N;
         float s = beta ? C[i * ldc + j] : 0.0f;
-        for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * n + e];
+        int z = 0;
+        for (; z + 8 <= splits; z += 8) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = partial[(int64_t)(z + u) * n + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
+        }
+        for (; z < splits; ++z) s += partial[(int64_t)z * n + e];
         C[i * ldc + j] = s;
     }
 }
