@@ -256,6 +256,7 @@ struct ColParams {
     int32_t kblock, nblk, nb_stored, m;
     int32_t rblock;     // operand rows (lanes) sharing one exponent: 1 for 1-D blocks, up to 64 for 2-D tiles
     int32_t lanes;      // lanes of a wave that carry operand rows: the largest multiple of rblock <= 64
+    uint32_t row_groups;   // workgroups per group of blocks (the grid is flat: block group = blockIdx.x / row_groups)
     uint32_t s0, s1;
 };
 
@@ -271,8 +272,8 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     __shared__ uint32_t lane_amax[4][64];
 
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-    const int64_t r = (int64_t)blockIdx.x * p.lanes + lane;
-    const int64_t blk0 = (int64_t)blockIdx.y * NBT;
+    const int64_t r = (int64_t)(blockIdx.x % p.row_groups) * p.lanes + lane;
+    const int64_t blk0 = (int64_t)(blockIdx.x / p.row_groups) * NBT;
     const bool r_ok = lane < p.lanes && r < p.R;
     const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
 
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 #pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
         const int rl = pass * 8 + (t >> 5);
-        const int64_t rr = (int64_t)blockIdx.x * p.lanes + rl;
+        const int64_t rr = (int64_t)(blockIdx.x % p.row_groups) * p.lanes + rl;
         if (rl < p.lanes && rr < p.R && piece * 16 < valid_bytes) {
             const uint4 d = *reinterpret_cast<const uint4 *>(tile + rl * kColStride + piece * 16);
             *reinterpret_cast<uint4 *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16) = d;
@@ -517,8 +518,9 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
     // cover every stored block and every exponent byte up to exp_ld
     const int64_t nb_cover = p.nb_stored > g.exp_ld ? p.nb_stored : g.exp_ld;
     const int64_t gx = ceil_div(g.R, p.lanes), gy = ceil_div(nb_cover, nbt);
-    if (gx > 0x7fffffff || gy > 65535) return HBFP_ERR_ARG;
-    const dim3 grid((unsigned)gx, (unsigned)gy);
+    if (gx > 0x7fffffff || gx * gy > 0x7fffffff) return HBFP_ERR_ARG;
+    p.row_groups = (uint32_t)gx;
+    const dim3 grid((unsigned)(gx * gy));
     if (g.kbp == 32) launch_col_k<32>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 64) launch_col_k<64>(p, grid, wide, g.rounding, s);
     else return HBFP_ERR_FORMAT;

@@ -160,6 +160,16 @@ def test_gemm_wide_mantissas_many_tiles_ragged(hb):
     _run(hb, _rand((150, 704), 43), _rand((704, 300), 44), (1, 64, 12, 1, 3), (64, 1, 12, 1, 4), partials=False, beta=1.0)
 
 
+def test_gemm_contraction_too_long_for_32_bit_tile_offsets(hb):
+    """K = 34 000 000: 127 stored rows of k no longer fit a 32-bit offset, so the product takes the 4-wave kernel
+    (with split-K); the FP32 sum of a million block terms stays within the same bound."""
+    rng = np.random.default_rng(77)
+    K = 34_000_000
+    A = rng.standard_normal((2, K)).astype(np.float32)
+    B = rng.standard_normal((K, 3)).astype(np.float32)
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False)
+
+
 @pytest.mark.parametrize("trans_a,trans_b", [(0, 0), (0, 1), (1, 0), (1, 1)])
 def test_gemm_f32_transposes(hb, trans_a, trans_b):
     """Forward (N,N), data gradient (N,T) and weight gradient (T,N) shapes in one call each."""
