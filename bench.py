@@ -35,9 +35,9 @@ HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/bench_default_hbm_traffic_counters.txt),
 # scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 GEMM launch: 141777 KiB x 2.0 + 65536 KiB = 357.5 MB   (algorithmic 113.6 MB: panels re-read across XCD L2s)
-#   config 2 encode m=8 RNE launch: 131662 KiB x 2.0 + 67589 KiB = 338.8 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 357.5e6
+#   config 4 GEMM launch: 141527 KiB x 2.0 + 65536 KiB = 357.0 MB   (algorithmic 113.6 MB: panels re-read across XCD L2s)
+#   config 2 encode m=8 RNE launch: 131652 KiB x 2.0 + 67589 KiB = 338.8 MB   (algorithmic 337.6 MB)
+TRAFFIC_GEMM_C4_BYTES = 357.0e6
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.8e6
 
 
