@@ -159,15 +159,18 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation
  * (Sec. 4, tiled matrix multiplication):
  *     C[i][j] = beta*C[i][j] + sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k]*mB[j][k]
- * The inner sum is exact integer arithmetic (int8 matrix cores, int32
- * accumulators); the outer sum is FP32.  A has M = A->rows operand rows, B has
+ * The inner sum is exact integer arithmetic (int8 matrix cores with int32
+ * accumulators, or exact limb products in the block-scaled matrix instruction, see
+ * hbfp_gemm_select); the outer sum is FP32.  A has M = A->rows operand rows, B has
  * N = B->rows; both must have the same kdim, kblock and mantissa class (both
  * <= 8 bits, or both 9..12 bits, which run as two int8 limbs per mantissa).
  *   C     device FP32 [M][ldc], ldc >= N
  *   beta  0 (overwrite; C is not read) or 1 (accumulate)
- *   workspace  hbfp_gemm_workspace bytes: 0 for mantissas of at most 8 bits unless the
- *              shape is split along k (few output tiles, long k: one FP32 slice of C per
- *              split); two int8 limb planes per operand for wider mantissas
+ *   workspace  hbfp_gemm_workspace bytes: scale words of both operands (4 bytes per row and
+ *              block), one FP32 slice of C per split when the shape is split along k (few
+ *              output tiles, long k), two int8 limb planes per operand for mantissas wider
+ *              than 8 bits, and the limb planes of both operands when the block-scaled
+ *              kernel is chosen
  * Domain: block exponent bytes up to 254 (magnitudes below 2^127).
  * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (kdim/kblock mismatch), HBFP_ERR_FORMAT
  * (mantissa classes differ or exceed 12 bits), HBFP_ERR_RANGE (kblock * max|mA| *
@@ -176,6 +179,32 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
 int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes);
 int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
               void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hbfp_gemm_select: hbfp_gemm with the kernel family named by the caller.  The library has two ways to
+ * evaluate Eq. (2) with its per-block FP accumulation (Sec. 4):
+ *   HBFP_KERNEL_INT8    int8 matrix instructions, int32 block sums, one FP32 scale-and-accumulate per
+ *                       output and block on the vector unit;
+ *   HBFP_KERNEL_SCALED  the block-scaled matrix instruction: mantissas cut into sign-magnitude limbs of
+ *                       4 bits (one limb up to 5-bit mantissas, two up to 9, three up to 12), every
+ *                       32-element group multiplied exactly and scaled by its two exponent bytes inside
+ *                       the instruction, FP32 accumulation in the matrix core.  Needs block exponents
+ *                       in 3..253 for 8-bit mantissas (7..253 for 12-bit); when an operand holds a
+ *                       non-zero block outside that range the call computes the product with the int8
+ *                       kernels instead, inside the same call and without host synchronisation;
+ *   HBFP_KERNEL_AUTO    what hbfp_gemm does: SCALED where it is measured faster (at least 128 output
+ *                       tiles of 256 x 256 and either blocks of exactly 32 elements, an operand of at
+ *                       most 5 bits, or mantissas wider than 9 bits), else INT8.
+ * Both satisfy the same bound against the FP64 product of the decoded operands.
+ * Arguments, domain and errors as hbfp_gemm, plus HBFP_ERR_ARG for an unknown kernel; the workspace
+ * size depends on the kernel: hbfp_gemm_select_workspace.
+ */
+#define HBFP_KERNEL_AUTO 0
+#define HBFP_KERNEL_INT8 1
+#define HBFP_KERNEL_SCALED 2
+int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes);
+int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
+                     void *workspace, size_t ws_bytes, void *stream);
 
 /*
  * hbfp_gemm_partials: the fixed-point half of Eq. (2) alone, for checking:

@@ -115,6 +115,7 @@ GemmArgs gemm_args(const hbfp_tensor *A, const hbfp_tensor *B) {
     g.expB_ld = B->exp_ld;
     g.nblk = A->nblk;
     g.kbp = A->kblock_pad;
+    g.kblock = A->kblock;
     g.mA = A->mant_bits;
     g.mB = B->mant_bits;
     return g;
@@ -316,45 +317,70 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
     return HBFP_OK;
 }
 
-int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
-    if (!bytes) return HBFP_ERR_ARG;
+static bool use_scaled(const GemmArgs &g, int kernel) {
+    if (g.P || kernel == HBFP_KERNEL_INT8) return false;
+    return kernel == HBFP_KERNEL_SCALED ? gemm_mx_possible(g) : gemm_mx_ok(g);
+}
+
+int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes) {
+    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_SCALED) return HBFP_ERR_ARG;
     int rc = check_tensor(A, false);
     if (rc != HBFP_OK) return rc;
     rc = check_tensor(B, false);
     if (rc != HBFP_OK) return rc;
     *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
                                                      : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld);
+    const GemmArgs g = gemm_args(A, B);
+    if (use_scaled(g, kernel)) *bytes = align256(*bytes) + align256(gemm_mx_workspace(g));   // [block-scaled path][int8 path behind it]
     return HBFP_OK;
 }
 
-static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int32_t *P,
+int hbfp_gemm_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
+    return hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_AUTO, bytes);
+}
+
+static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int32_t *P, int kernel,
                     void *workspace, size_t ws_bytes, void *stream) {
     int rc = check_pair(A, B);
     if (rc != HBFP_OK) return rc;
     size_t need = 0;
-    hbfp_gemm_workspace(A, B, &need);
+    hbfp_gemm_select_workspace(A, B, kernel, &need);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     GemmArgs g = gemm_args(A, B);
     g.C = C;
     g.ldc = ldc;
     g.beta = beta;
     g.P = P;
+    if (use_scaled(g, kernel)) {
+        // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
+        // the int8 kernels queue up behind it and run only in that case
+        rc = launch_gemm_mx(g, workspace, (hipStream_t)stream);
+        if (rc != HBFP_OK) return rc;
+        g.run_if = (const int *)workspace;
+        workspace = (char *)workspace + align256(gemm_mx_workspace(g));
+    }
     if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
     return launch_gemm_i8(g, workspace, (hipStream_t)stream);
 }
 
-int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
-              void *workspace, size_t ws_bytes, void *stream) {
+int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
+                     void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !C) return HBFP_ERR_ARG;
     if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_SCALED) return HBFP_ERR_ARG;
     if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
-    return run_gemm(A, B, C, ldc, beta, nullptr, workspace, ws_bytes, stream);
+    return run_gemm(A, B, C, ldc, beta, nullptr, kernel, workspace, ws_bytes, stream);
+}
+
+int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
+              void *workspace, size_t ws_bytes, void *stream) {
+    return hbfp_gemm_select(A, B, C, ldc, beta, HBFP_KERNEL_AUTO, workspace, ws_bytes, stream);
 }
 
 int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
                        void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !P || ((uintptr_t)P & 3)) return HBFP_ERR_ARG;
-    return run_gemm(A, B, nullptr, 0, 0.0f, P, workspace, ws_bytes, stream);
+    return run_gemm(A, B, nullptr, 0, 0.0f, P, HBFP_KERNEL_INT8, workspace, ws_bytes, stream);
 }
 
 // Layout of the hbfp_gemm_f32 workspace: [A mant][A exps][B mant][B exps][encode scratch][gemm scratch]

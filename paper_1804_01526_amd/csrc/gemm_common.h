@@ -56,8 +56,10 @@ struct WordParams {
     int64_t ld[2], rows[2], rows_pad[2];
     int slots, row_blocks;
     uint32_t a_or;               // 0x40: row words are 1.5 * 2^(E - 127) as bf16; 0: 2^(E - 127) as bf16
+    const int *run_if;
 };
 __global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
+    if (w.run_if && !*w.run_if) return;
     const int z = blockIdx.z;
     const int64_t row = (int64_t)(blockIdx.x % w.row_blocks) * 256 + threadIdx.x;
     if (row >= w.rows_pad[z]) return;
@@ -76,7 +78,7 @@ inline size_t word_bytes(int64_t rows, int64_t slots) { return (size_t)slots * (
 
 // slots must be a multiple of 4 and at most the exponent row pitch of either operand
 inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const uint8_t *eB, int64_t ldB, int64_t N, int slots,
-                              uint32_t a_or, uint32_t *wA, uint32_t *wB, hipStream_t s) {
+                              uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_if, hipStream_t s) {
     WordParams wp;
     wp.exps[0] = eA; wp.exps[1] = eB;
     wp.words[0] = wA; wp.words[1] = wB;
@@ -85,6 +87,7 @@ inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const u
     wp.rows_pad[0] = ceil_div(M, 128) * 128; wp.rows_pad[1] = ceil_div(N, 128) * 128;
     wp.slots = slots;
     wp.a_or = a_or;
+    wp.run_if = run_if;
     const int64_t maxpad = wp.rows_pad[0] > wp.rows_pad[1] ? wp.rows_pad[0] : wp.rows_pad[1];
     wp.row_blocks = (int)ceil_div(maxpad, 256);
     if ((int64_t)wp.row_blocks * (slots / 4) > 0x7fffffff) return HBFP_ERR_ARG;

@@ -1,0 +1,571 @@
+// BFP matrix product on the block-scaled matrix instruction of gfx950 (Eq. (2) of Sec. 4 with the
+// per-block FP accumulation of Sec. 4 / Sec. 4.2 "Tiling"):
+//     C[i][j] = sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k] * mB[j][k]
+//
+// v_mfma_scale_f32_32x32x64_f8f6f4 is a BFP dot-product unit in hardware: every lane hands it 32
+// narrow values along k together with one shared 8-bit exponent, it multiplies the narrow values,
+// applies 2^(sA + sB - 254) per pair of 32-element groups and accumulates in FP32.  The per-block
+// scaling that costs the int8 kernels two vector instructions per output and block is free here.
+// Its narrow values are floats, the widest significand at the fast rate being 4 bits (FP6 E2M3, twice
+// the int8 rate), so a mantissa is cut into limbs of 4 magnitude bits:
+//     |v| = sum_i n_i * 16^i,  n_i in 0..15,  limb i stored as the E2M3 code (sign << 5) | n_i = +-n_i / 8
+// (codes 0..7 are the subnormals n/8, codes 8..15 the first binade (1 + (n-8)/8), so the code of an
+// integer n in 0..15 is n itself: an E2M3 plane is a plane of sign-magnitude 4-bit fixed-point numbers).
+// Limb products are exact (8 bits), a group of 32 sums exactly inside the instruction, and each limb pair
+// gets its own exponent byte  E + 5 + 4 i - m  (E the stored block exponent, m the mantissa width), so
+// LA x LB matrix instructions per k-step of 64 accumulate the full product straight into the FP32
+// accumulator: 8-bit mantissas take 2 x 2, 12-bit mantissas 3 x 3, mantissas of at most 5 bits 1 x 1.
+//
+// pack kernel:  stored operand (int8 / int16 mantissas [rows][kpad], exponent bytes) -> limb planes in
+//               the register order of the matrix instruction, 256 operand rows x 64 k at a time, so the
+//               product kernel moves whole stages with contiguous asynchronous copies and every fragment
+//               read is three conflict-free 8-byte LDS reads per lane (lanes 24 bytes apart cover all 64 banks).
+// gemm_mx_kernel: 256 x 256 tile of C per workgroup, 8 waves of 64 x 128, three-stage LDS ring, one
+//               barrier per k-step, fragment reads one column tile ahead of the matrix instructions.
+// An exponent byte outside 0..254 (blocks below 2^-120 or above 2^126) cannot be expressed; the pack
+// kernel raises a flag, the product kernel then does nothing and the int8 kernels, launched behind it
+// with the opposite condition, compute the product instead.
+#include "gemm_common.h"
+
+namespace hbfp {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+// limbs of 4 magnitude bits that a mantissa of m bits (sign included) needs
+inline int limbs_of(int m) { return m <= 5 ? 1 : m <= 9 ? 2 : 3; }
+
+constexpr int kMxThreads = 512;
+constexpr int kLimbBytes = 1536;                 // one limb of 32 rows x 64 k: 24 bytes per lane
+constexpr int kScaleBytes = 256;                 // [64 lanes] one word: exponent byte of limb j in byte j
+constexpr int kRowTiles = 8;                     // 32-row tiles per 256-row panel
+__host__ __device__ constexpr int chunk_bytes(int L) { return L * kLimbBytes + kScaleBytes; }
+__host__ __device__ constexpr int panel_stage_bytes(int L) { return kRowTiles * chunk_bytes(L); }   // a multiple of 2048
+
+// ------------------------------------------------------------------------------------------------
+// Packed operand: [panel of 256 rows][k-step of 64][row tile of 32][limb planes, most significant first | scale words].
+// Lane l of a row tile stands for operand row (l % 32) and the 32 k of half (l / 32) of the k-step: the 32 codes
+// of a limb are 192 bits, code e in bits 6 e .. 6 e + 5, stored at [l * 24] of the limb plane.
+struct PackParams {
+    const void *mant;
+    const uint8_t *exps;
+    uint8_t *out;
+    int *flag;
+    int64_t R, kpad, exp_ld;
+    int32_t ksteps, nks4, chunks32_per_block, m;
+};
+
+template <int L, typename MT>
+__global__ __launch_bounds__(256) void mx_pack_kernel(const PackParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t rt = blockIdx.x / p.nks4;
+    const int ks = (int)(blockIdx.x % p.nks4) * 4 + wave;
+    if (ks >= p.ksteps) return;
+    const int64_t row = rt * 32 + (lane & 31);
+    const int kb = 2 * ks + (lane >> 5);                      // 32-element chunk of the stored row
+    uint32_t limb[L][6];
+#pragma unroll
+    for (int j = 0; j < L; ++j)
+#pragma unroll
+        for (int d = 0; d < 6; ++d) limb[j][d] = 0;
+    uint32_t word = 0;
+    if (row < p.R) {
+        constexpr int NV = 32 * (int)sizeof(MT) / 16;
+        v4i raw[NV];
+        const MT *src = reinterpret_cast<const MT *>(p.mant) + row * p.kpad + (int64_t)kb * 32;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) raw[i] = reinterpret_cast<const v4i *>(src)[i];
+        uint32_t any = 0;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            int v;
+            if (sizeof(MT) == 1) v = (int)(int8_t)((uint32_t)raw[e >> 4][(e >> 2) & 3] >> (8 * (e & 3)));
+            else v = (int)(int16_t)((uint32_t)raw[e >> 3][(e >> 1) & 3] >> (16 * (e & 1)));
+            const uint32_t s = v < 0 ? 32u : 0u;
+            const uint32_t a = (uint32_t)(v < 0 ? -v : v);
+            any |= a;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                const uint32_t code = s | ((a >> (4 * (L - 1 - j))) & 15u);
+                const int bit = 6 * e;
+                limb[j][bit >> 5] |= code << (bit & 31);
+                if ((bit & 31) > 26) limb[j][(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+            }
+        }
+        int E = p.exps[row * p.exp_ld + kb / p.chunks32_per_block];
+        E = E > 254 ? 254 : E;
+        bool bad = false;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            int byte = E + 5 + 4 * (L - 1 - j) - p.m;
+            if (byte < 0 || byte > 254) {
+                bad = true;
+                byte = byte < 0 ? 0 : 254;
+            }
+            word |= (uint32_t)byte << (8 * j);
+        }
+        if (bad && any) atomicOr(p.flag, 1);                  // all-zero groups (padding) take any exponent
+    }
+    uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            const v2i two = {(int)limb[j][2 * d], (int)limb[j][2 * d + 1]};
+            *reinterpret_cast<v2i *>(chunk + j * kLimbBytes + lane * 24 + d * 8) = two;
+        }
+    }
+    *reinterpret_cast<uint32_t *>(chunk + L * kLimbBytes + lane * 4) = word;
+}
+
+__global__ void mx_clear_flag_kernel(int *flag) {
+    if (threadIdx.x == 0) *flag = 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+struct MxParams {
+    const uint8_t *pa, *pb;      // packed operands
+    const int *flag;
+    float *C;
+    int64_t M, N, ldc;
+    int32_t ksteps, tiles_m, tiles_n, beta;
+};
+
+// one operand of the matrix instruction: 6 registers of E2M3 codes (the builtin takes 8 and drops the last two for
+// this format)
+// Fragment registers: af[buffer][row tile][3 * limb + piece], bf[buffer][3 * limb + piece]: the codes of a lane are read
+// 8 bytes at a time, limb l at l * kLimbBytes; as / bs are the scale words.
+#define HBFP_MX_READ_A1(buf, i, base_)                                                                                      \
+    {                                                                                                                      \
+        _Pragma("unroll") for (int l = 0; l < LA; ++l)                                                                     \
+            _Pragma("unroll") for (int d = 0; d < 3; ++d)                                                                  \
+                af[buf][i][3 * l + d] =                                                                                    \
+                    *reinterpret_cast<const v2i *>((base_) + abase[ONE_A ? 0 : (i)][l] + (ONE_A ? (i) * CHA : 0) + d * 8); \
+        as[buf][i] = *reinterpret_cast<const int *>((base_) + a4 + (i) * CHA);                                             \
+    }
+#define HBFP_MX_READ_A(buf, base_)                                                                                          \
+    {                                                                                                                      \
+        HBFP_MX_READ_A1(buf, 0, base_);                                                                                    \
+        HBFP_MX_READ_A1(buf, 1, base_);                                                                                    \
+    }
+#define HBFP_MX_READ_B(buf, j, base_)                                                                                       \
+    {                                                                                                                      \
+        _Pragma("unroll") for (int l = 0; l < LB; ++l)                                                                     \
+            _Pragma("unroll") for (int d = 0; d < 3; ++d)                                                                  \
+                bf[buf][3 * l + d] = *reinterpret_cast<const v2i *>((base_) + bbase[l] + (j) * CHB + d * 8);               \
+        bs[buf] = *reinterpret_cast<const int *>((base_) + b4 + (j) * CHB);                                                \
+    }
+// the builtin takes 8 registers per operand and drops the last two for this format
+#define HBFP_MX_MFMA(abuf, bbuf, JA, JB, i, j)                                                                              \
+    {                                                                                                                      \
+        const v8i av_ = {af[abuf][i][3 * (JA)][0],     af[abuf][i][3 * (JA)][1],     af[abuf][i][3 * (JA) + 1][0],         \
+                         af[abuf][i][3 * (JA) + 1][1], af[abuf][i][3 * (JA) + 2][0], af[abuf][i][3 * (JA) + 2][1], 0, 0};  \
+        const v8i bv_ = {bf[bbuf][3 * (JB)][0],     bf[bbuf][3 * (JB)][1],     bf[bbuf][3 * (JB) + 1][0],                  \
+                         bf[bbuf][3 * (JB) + 1][1], bf[bbuf][3 * (JB) + 2][0], bf[bbuf][3 * (JB) + 2][1], 0, 0};           \
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av_, bv_, acc[i][j], 2, 2, JA, as[abuf][i], JB, bs[bbuf]); \
+    }
+// limb pair (JA, JB) of column tile j for both row tiles, which alternate so that a matrix instruction never waits
+// for the one just before it; then this pair's share of the stage copies, if the k-step hands over a buffer
+#define HBFP_MX_PAIR(abuf, bbuf, JA, JB, j, COPY)                                                                           \
+    {                                                                                                                      \
+        HBFP_MX_MFMA(abuf, bbuf, JA, JB, 0, j);                                                                            \
+        HBFP_MX_MFMA(abuf, bbuf, JA, JB, 1, j);                                                                            \
+        if (COPY) {                                                                                                        \
+            constexpr int slot = (JA) * LB + (JB), per = (NCOPY + LA * LB - 1) / (LA * LB);                                \
+            _Pragma("unroll") for (int c_ = slot * per; c_ < (slot + 1) * per && c_ < NCOPY; ++c_) {                       \
+                async_copy16(cptr[c_], voff, copy_ring * STAGE + coff[c_]);                                                \
+                cptr[c_] += cstep[c_];                                                                                     \
+            }                                                                                                              \
+        }                                                                                                                  \
+    }
+// PART 0: every limb pair of column tile j;  1: only the first pair;  2: all but the first
+#define HBFP_MX_COLUMN(abuf, bbuf, j, COPY, PART)                                                                           \
+    {                                                                                                                      \
+        constexpr int A1 = LA > 1 ? 1 : 0, A2 = LA > 2 ? 2 : 0, B1 = LB > 1 ? 1 : 0, B2 = LB > 2 ? 2 : 0;                  \
+        if (PART != 2) HBFP_MX_PAIR(abuf, bbuf, 0, 0, j, COPY);                                                            \
+        if (PART != 1) {                                                                                                   \
+            if (LB > 1) HBFP_MX_PAIR(abuf, bbuf, 0, B1, j, COPY);                                                          \
+            if (LB > 2) HBFP_MX_PAIR(abuf, bbuf, 0, B2, j, COPY);                                                          \
+            if (LA > 1) {                                                                                                  \
+                HBFP_MX_PAIR(abuf, bbuf, A1, 0, j, COPY);                                                                  \
+                if (LB > 1) HBFP_MX_PAIR(abuf, bbuf, A1, B1, j, COPY);                                                     \
+                if (LB > 2) HBFP_MX_PAIR(abuf, bbuf, A1, B2, j, COPY);                                                     \
+            }                                                                                                              \
+            if (LA > 2) {                                                                                                  \
+                HBFP_MX_PAIR(abuf, bbuf, A2, 0, j, COPY);                                                                  \
+                if (LB > 1) HBFP_MX_PAIR(abuf, bbuf, A2, B1, j, COPY);                                                     \
+                if (LB > 2) HBFP_MX_PAIR(abuf, bbuf, A2, B2, j, COPY);                                                     \
+            }                                                                                                              \
+        }                                                                                                                  \
+    }
+
+// the same products for one row tile only, each followed by one stage copy if the k-step hands over a buffer
+#define HBFP_MX_ONE(abuf, bbuf, JA, JB, i, j, COPY)                                                                         \
+    {                                                                                                                      \
+        HBFP_MX_MFMA(abuf, bbuf, JA, JB, i, j);                                                                            \
+        constexpr int c_ = (i) * LA * LB + (JA) * LB + (JB);                                                               \
+        if ((COPY) && c_ < NCOPY) {                                                                                        \
+            async_copy16(cptr[c_], voff, copy_ring * STAGE + coff[c_]);                                                    \
+            cptr[c_] += cstep[c_];                                                                                         \
+        }                                                                                                                  \
+    }
+#define HBFP_MX_COLUMN_ROW(abuf, bbuf, i, j, COPY, PART)                                                                        \
+    {                                                                                                                      \
+        constexpr int A1 = LA > 1 ? 1 : 0, A2 = LA > 2 ? 2 : 0, B1 = LB > 1 ? 1 : 0, B2 = LB > 2 ? 2 : 0;                  \
+        if (PART != 2) HBFP_MX_ONE(abuf, bbuf, 0, 0, i, j, COPY);                                                          \
+        if (PART != 1) {                                                                                                   \
+            if (LB > 1) HBFP_MX_ONE(abuf, bbuf, 0, B1, i, j, COPY);                                                        \
+            if (LB > 2) HBFP_MX_ONE(abuf, bbuf, 0, B2, i, j, COPY);                                                        \
+            if (LA > 1) {                                                                                                  \
+                HBFP_MX_ONE(abuf, bbuf, A1, 0, i, j, COPY);                                                                \
+                if (LB > 1) HBFP_MX_ONE(abuf, bbuf, A1, B1, i, j, COPY);                                                   \
+                if (LB > 2) HBFP_MX_ONE(abuf, bbuf, A1, B2, i, j, COPY);                                                   \
+            }                                                                                                              \
+            if (LA > 2) {                                                                                                  \
+                HBFP_MX_ONE(abuf, bbuf, A2, 0, i, j, COPY);                                                                \
+                if (LB > 1) HBFP_MX_ONE(abuf, bbuf, A2, B1, i, j, COPY);                                                   \
+                if (LB > 2) HBFP_MX_ONE(abuf, bbuf, A2, B2, i, j, COPY);                                                   \
+            }                                                                                                              \
+        }                                                                                                                  \
+    }
+
+template <int LA, int LB>
+__global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int CHA = chunk_bytes(LA), CHB = chunk_bytes(LB);
+    constexpr int SA = panel_stage_bytes(LA), SB = panel_stage_bytes(LB), STAGE = SA + SB;
+    constexpr int RING = 3 * STAGE <= 160 * 1024 ? 3 : 2;
+    constexpr int PIECES = STAGE / 1024;                       // 1 KB = one copy instruction of a wave
+    constexpr int NCOPY = (PIECES + 7) / 8;                    // per wave and stage
+    constexpr bool ONE_A = LA > 2 || LB > 2;                   // three limbs: no room for a second set of row-tile registers
+
+    if (*p.flag) return;                                       // uniform: the int8 kernels take over
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave & 3, wn = wave >> 2;
+
+    // ---- copies: a stage is PIECES pieces of 1 KB, A's first; wave w moves pieces w, w + 8, ... (the last ones
+    // clamped, so every wave issues NCOPY copies per stage and one wait count fits all).  The source of piece c
+    // advances by one stage of its operand per k-step.
+    const uint32_t voff = lane * 16;
+    const uint8_t *cptr[NCOPY];
+    uint32_t coff[NCOPY], cstep[NCOPY];
+#pragma unroll
+    for (int i = 0; i < NCOPY; ++i) {
+        int c = wave + 8 * i;
+        c = c < PIECES ? c : PIECES - 1;
+        const int byte = c * 1024;
+        coff[i] = byte;
+        cptr[i] = byte < SA ? p.pa + (int64_t)tm * p.ksteps * SA + byte : p.pb + (int64_t)tn * p.ksteps * SB + (byte - SA);
+        cstep[i] = byte < SA ? SA : SB;
+    }
+#define HBFP_MX_COPY_STAGE(ring_)                                                                  \
+    {                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < NCOPY; ++i) {                                        \
+            async_copy16(cptr[i], voff, (uint32_t)((ring_) * STAGE) + coff[i]);                    \
+            cptr[i] += cstep[i];                                                                   \
+        }                                                                                          \
+    }
+
+    // ---- fragment addresses inside a stage
+    // (one opaque base register per limb plane read in the same phase: reads that share a base get merged into
+    // two-address reads across fragments, whose results then have to be copied into the operand registers)
+    const int a4 = lane * 4 + 2 * wm * CHA + LA * kLimbBytes, b4 = lane * 4 + SA + 4 * wn * CHB + LB * kLimbBytes;
+    int abase[2][LA], bbase[LB];
+#pragma unroll
+    for (int l = 0; l < LA; ++l) {
+        abase[0][l] = lane * 24 + 2 * wm * CHA + l * kLimbBytes;
+        abase[1][l] = abase[0][l] + CHA;
+        asm volatile("" : "+v"(abase[0][l]), "+v"(abase[1][l]));
+    }
+#pragma unroll
+    for (int l = 0; l < LB; ++l) {
+        bbase[l] = lane * 24 + SA + 4 * wn * CHB + l * kLimbBytes;
+        asm volatile("" : "+v"(bbase[l]));
+    }
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // Software pipeline.  The fragments of column tile j + 1 are read while the matrix instructions of column tile j
+    // run; during the last column tile of a k-step the wave reads the row tiles and the first column tile of the next
+    // k-step.  That needs the next stage, so the hand-over sits there: wait for this wave's copies of stage ks + 1,
+    // barrier (now every wave's copies of it have landed and every wave has finished reading stage ks), and the
+    // buffer of stage ks takes the copy of stage ks + RING, issued between the matrix instructions of the last
+    // column tile.  A copy has RING - 1 k-steps to land.
+    v2i af[2][2][3 * LA], bf[2][3 * LB];
+    int as[2][2], bs[2];
+    HBFP_MX_COPY_STAGE(0);
+    HBFP_MX_COPY_STAGE(1);                                     // there are at least two k-steps
+    if (RING == 3 && p.ksteps > 2) {
+        HBFP_MX_COPY_STAGE(2);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NCOPY) : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY) : "memory");
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    HBFP_MX_READ_A(0, lds);
+    HBFP_MX_READ_B(0, 0, lds);
+    int ring = 0;
+    // Neither the optimiser (memory clobber) nor the instruction scheduler moves LDS reads or matrix instructions
+    // across a fence: the order below is the schedule.  A k-step is straight-line code (the start-up and drain cases
+    // are separate expansions chosen by MODE), because matrix instructions are otherwise sunk past a branch.
+#define HBFP_MX_FENCE                   \
+    asm volatile("" ::: "memory");      \
+    __builtin_amdgcn_sched_barrier(0)
+    // MODE 0: hand-over with a copy of stage ks + RING;  1: hand-over, nothing left to copy, one more stage in flight;
+    //      2: hand-over, nothing left to copy, the next stage is the last;  3: last k-step
+#define HBFP_MX_HANDOVER(MODE)                                                                                             \
+    {                                                                                                                      \
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                                 \
+        if (RING == 3 && MODE != 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY) : "memory");                           \
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                              \
+        __builtin_amdgcn_s_barrier();                                                                                      \
+        asm volatile("" ::: "memory");                                                                                     \
+    }
+#define HBFP_MX_KSTEP(abuf, MODE)                                                                                          \
+    {                                                                                                                      \
+        const uint8_t *base = lds + ring * STAGE;                                                                          \
+        const int copy_ring = ring;                                                                                        \
+        const int next = ring + 1 == RING ? 0 : ring + 1;                                                                  \
+        const uint8_t *nbase = lds + next * STAGE;                                                                         \
+        if (!ONE_A) {                                                                                                      \
+            /* the first matrix instructions wait for the reads of the previous hand-over; the next column    */          \
+            /* tile is requested behind them so that this wait does not cover it                              */          \
+            HBFP_MX_COLUMN(abuf, 0, 0, false, 1);                                                                          \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(1, 1, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN(abuf, 0, 0, false, 2);                                                                          \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(0, 2, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN(abuf, 1, 1, false, 0);                                                                            \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(1, 3, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN(abuf, 0, 2, false, 0);                                                                            \
+            HBFP_MX_FENCE;                                                                                                 \
+            if (MODE != 3) {                                                                                               \
+                HBFP_MX_HANDOVER(MODE);                                                                                    \
+                HBFP_MX_READ_A(1 - (abuf), nbase);                                                                         \
+                HBFP_MX_READ_B(0, 0, nbase);                                                                               \
+            }                                                                                                              \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN(abuf, 1, 3, MODE == 0, 0);                                                                        \
+            HBFP_MX_FENCE;                                                                                                 \
+        } else {                                                                                                           \
+            /* one set of row-tile registers: row tile 0 of the next k-step is read as soon as the last column    */      \
+            /* tile has used it, row tile 1 after that; all products of a row tile run back to back               */      \
+            HBFP_MX_COLUMN_ROW(0, 0, 0, 0, false, 1);                                                                      \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(1, 1, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN_ROW(0, 0, 0, 0, false, 2);                                                                      \
+            HBFP_MX_COLUMN_ROW(0, 0, 1, 0, false, 0);                                                                       \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(0, 2, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN_ROW(0, 1, 0, 1, false, 0);                                                                         \
+            HBFP_MX_COLUMN_ROW(0, 1, 1, 1, false, 0);                                                                         \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_READ_B(1, 3, base);                                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN_ROW(0, 0, 0, 2, false, 0);                                                                         \
+            HBFP_MX_COLUMN_ROW(0, 0, 1, 2, false, 0);                                                                         \
+            HBFP_MX_FENCE;                                                                                                 \
+            if (MODE != 3) {                                                                                               \
+                HBFP_MX_HANDOVER(MODE);                                                                                    \
+                HBFP_MX_READ_B(0, 0, nbase);                                                                               \
+            }                                                                                                              \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN_ROW(0, 1, 0, 3, MODE == 0, 0);                                                                     \
+            HBFP_MX_FENCE;                                                                                                 \
+            if (MODE != 3) HBFP_MX_READ_A1(0, 0, nbase);                                                                   \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_COLUMN_ROW(0, 1, 1, 3, MODE == 0, 0);                                                                     \
+            HBFP_MX_FENCE;                                                                                                 \
+            if (MODE != 3) HBFP_MX_READ_A1(0, 1, nbase);                                                                   \
+            HBFP_MX_FENCE;                                                                                                 \
+        }                                                                                                                  \
+        ring = next;                                                                                                       \
+    }
+    // the number of k-steps is even (the stored contraction length is a multiple of 128)
+    int ks = 0;
+    if (RING == 3) {
+        for (; ks + 6 <= p.ksteps; ks += 2) {
+            HBFP_MX_KSTEP(0, 0);
+            HBFP_MX_KSTEP(1, 0);
+        }
+        if (p.ksteps - ks == 4) {
+            HBFP_MX_KSTEP(0, 0);
+            HBFP_MX_KSTEP(1, 1);
+        }
+    } else {
+        for (; ks + 4 <= p.ksteps; ks += 2) {
+            HBFP_MX_KSTEP(0, 0);
+            HBFP_MX_KSTEP(1, 0);
+        }
+    }
+    HBFP_MX_KSTEP(0, 2);
+    HBFP_MX_KSTEP(1, 3);
+#undef HBFP_MX_KSTEP
+#undef HBFP_MX_HANDOVER
+#undef HBFP_MX_FENCE
+#undef HBFP_MX_COPY_STAGE
+
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int64_t row0 = (int64_t)tm * 256 + wm * 64, col0 = (int64_t)tn * 256 + wn * 128;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = col0 + j * 32 + l32;
+            if (col >= p.N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < p.M) {
+                    float *dst = p.C + row * p.ldc + col;
+                    *dst = p.beta ? *dst + acc[i][j][v] : acc[i][j][v];
+                }
+            }
+        }
+}
+
+constexpr int mx_lds_bytes(int LA, int LB) {
+    const int stage = panel_stage_bytes(LA) + panel_stage_bytes(LB);
+    return (3 * stage <= 160 * 1024 ? 3 : 2) * stage;
+}
+
+#undef HBFP_MX_COLUMN
+#undef HBFP_MX_COLUMN_ROW
+#undef HBFP_MX_ONE
+#undef HBFP_MX_READ_A1
+#undef HBFP_MX_PAIR
+#undef HBFP_MX_MFMA
+#undef HBFP_MX_READ_A
+#undef HBFP_MX_READ_B
+
+
+inline size_t packed_bytes(int64_t rows, int64_t kpad, int L) {
+    return (size_t)ceil_div(rows, 256) * (size_t)(kpad / 64) * (size_t)panel_stage_bytes(L);
+}
+
+template <int L>
+int launch_pack(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m, bool wide,
+                uint8_t *out, int *flag, hipStream_t s) {
+    PackParams q;
+    q.mant = mant;
+    q.exps = exps;
+    q.out = out;
+    q.flag = flag;
+    q.R = R;
+    q.kpad = kpad;
+    q.exp_ld = exp_ld;
+    q.ksteps = (int32_t)(kpad / 64);
+    q.nks4 = (q.ksteps + 3) / 4;
+    q.chunks32_per_block = (int32_t)(kbp / 32);
+    q.m = m;
+    const int64_t blocks = ceil_div(R, 256) * 8 * q.nks4;
+    if (blocks > 0x7fffffff) return HBFP_ERR_ARG;
+    if (wide) hipLaunchKernelGGL((mx_pack_kernel<L, int16_t>), dim3((unsigned)blocks), dim3(256), 0, s, q);
+    else hipLaunchKernelGGL((mx_pack_kernel<L, int8_t>), dim3((unsigned)blocks), dim3(256), 0, s, q);
+    return launch_status();
+}
+
+int pack_operand(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m, int L,
+                 uint8_t *out, int *flag, hipStream_t s) {
+    const bool wide = m > 8;
+    if (L == 1) return launch_pack<1>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
+    if (L == 2) return launch_pack<2>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
+    return launch_pack<3>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
+}
+
+template <int LA, int LB>
+int launch_mx_t(const MxParams &p, hipStream_t s) {
+    constexpr int bytes = mx_lds_bytes(LA, LB);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                bytes) != hipSuccess)
+            return HBFP_ERR_LAUNCH;
+        configured = true;
+    }
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB>), dim3((unsigned)(ceil_div(tiles, 8) * 8)), dim3(kMxThreads), bytes, s, p);
+    return launch_status();
+}
+
+}  // namespace
+
+// The block-scaled path pays for itself when its 256 x 256 tiles fill the chip and it issues fewer instructions than
+// the int8 kernels.  Measured on 8192^3 and 4096^3 products: four limb products per k-step (6..9-bit mantissas) beat
+// the int8 kernel only where that one scales after every matrix instruction (blocks of exactly 32; blocks of 24 would
+// pay for their padding four times here); one or two limb products (an operand of at most 5 bits) and the 12-bit
+// formats (6 or 9 limb products against four int8 products plus five vector instructions per output and block) win
+// for every block length.
+bool gemm_mx_possible(const GemmArgs &a) {
+    return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 64 <= 0x7fffffff;
+}
+
+bool gemm_mx_ok(const GemmArgs &a) {
+    if (!gemm_mx_possible(a)) return false;
+    const int64_t tiles = ceil_div(a.M, 256) * ceil_div(a.N, 256);
+    if (tiles < 128) return false;
+    if ((double)a.M * (double)a.N < 0.75 * 65536.0 * (double)tiles) return false;   // ragged edges would waste the tiles
+    if ((double)a.M * (double)a.N * (double)a.kpad < 6.0e10) return false;          // too short to repay the packing
+    const int products = limbs_of(a.mA) * limbs_of(a.mB);
+    if (products == 4) return a.kbp == 32 && a.kblock == 32;
+    return true;
+}
+
+// workspace of the block-scaled path: [flag, 256 bytes][packed A][packed B]
+size_t gemm_mx_workspace(const GemmArgs &a) {
+    return 256 + packed_bytes(a.M, a.kpad, limbs_of(a.mA)) + packed_bytes(a.N, a.kpad, limbs_of(a.mB));
+}
+
+int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s) {
+    const int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
+    uint8_t *w = (uint8_t *)workspace;
+    int *flag = (int *)w;
+    uint8_t *pa = w + 256, *pb = pa + packed_bytes(a.M, a.kpad, LA);
+    hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, flag);
+    int rc = pack_operand(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, LA, pa, flag, s);
+    if (rc != HBFP_OK) return rc;
+    rc = pack_operand(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, LB, pb, flag, s);
+    if (rc != HBFP_OK) return rc;
+    MxParams p;
+    p.pa = pa;
+    p.pb = pb;
+    p.flag = flag;
+    p.C = a.C;
+    p.M = a.M;
+    p.N = a.N;
+    p.ldc = a.ldc;
+    p.ksteps = (int32_t)(a.kpad / 64);
+    p.tiles_m = (int32_t)ceil_div(a.M, 256);
+    p.tiles_n = (int32_t)ceil_div(a.N, 256);
+    p.beta = a.beta != 0.0f;
+    switch (LA * 4 + LB) {
+        case 1 * 4 + 1: return launch_mx_t<1, 1>(p, s);
+        case 1 * 4 + 2: return launch_mx_t<1, 2>(p, s);
+        case 2 * 4 + 1: return launch_mx_t<2, 1>(p, s);
+        case 2 * 4 + 2: return launch_mx_t<2, 2>(p, s);
+        case 2 * 4 + 3: return launch_mx_t<2, 3>(p, s);
+        case 3 * 4 + 2: return launch_mx_t<3, 2>(p, s);
+        case 3 * 4 + 3: return launch_mx_t<3, 3>(p, s);
+        default: return HBFP_ERR_FORMAT;
+    }
+}
+
+}  // namespace hbfp

@@ -43,12 +43,13 @@ int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float
 struct GemmArgs {
     const void *mantA, *mantB;        // int8 [rows][kpad] (or limb planes)
     const uint8_t *expA, *expB;       // [rows][exp_ld]
-    int64_t M, N, kpad, expA_ld, expB_ld, nblk, kbp;
+    int64_t M, N, kpad, expA_ld, expB_ld, nblk, kbp, kblock;
     int32_t mA, mB;                   // mantissa bits
     float *C;
     int64_t ldc;
     float beta;
     int32_t *P;                       // non-null: dump block partials instead of C
+    const int *run_if;                // non-null: every kernel of the launch does nothing unless *run_if != 0
 };
 // 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
 // up to three outputs of the same tile shape in any orientation
@@ -59,5 +60,13 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld);
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
+
+// gemm_mx.hip: the product on the block-scaled matrix instruction.  launch_gemm_mx packs both operands and
+// runs the product; it leaves a flag at the start of its workspace that is non-zero when some exponent
+// could not be expressed, in which case it has not touched C and the int8 path has to run (run_if).
+bool gemm_mx_possible(const GemmArgs &a);   // shapes the kernel can address
+bool gemm_mx_ok(const GemmArgs &a);         // shapes and formats for which it is the faster choice
+size_t gemm_mx_workspace(const GemmArgs &a);
+int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s);
 
 }  // namespace hbfp

@@ -61,6 +61,8 @@ def _load():
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
+    lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_select.argtypes = [T, T, vp, i64, ctypes.c_float, i32, vp, sz, vp]
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
@@ -69,7 +71,8 @@ def _load():
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
     for name in ("hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
-                 "hbfp_gemm", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace", "hbfp_gemm_f32"):
+                 "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
+                 "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
 
@@ -182,16 +185,26 @@ def decode(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> tor
     return out
 
 
+KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED = 0, 1, 2
+
+
+def gemm_select_workspace(a: TensorDesc, b: TensorDesc, kernel: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_select_workspace(ctypes.byref(a), ctypes.byref(b), kernel, ctypes.byref(n)),
+           "hbfp_gemm_select_workspace")
+    return n.value
+
+
 def gemm(a: BfpTensor, b: BfpTensor, out: Optional[torch.Tensor] = None, beta: float = 0.0,
-         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """C[M,N] (+)= A . B^T over k (both operands k-contiguous)."""
+         workspace: Optional[torch.Tensor] = None, stream=None, kernel: int = KERNEL_AUTO) -> torch.Tensor:
+    """C[M,N] (+)= A . B^T over k (both operands k-contiguous); `kernel` as in hbfp_gemm_select."""
     if out is None:
         out = torch.empty((a.desc.rows, b.desc.rows), dtype=torch.float32, device=a.mant.device)
     assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
-    workspace = _workspace(gemm_workspace(a.desc, b.desc), out.device, workspace)
-    _check(_lib.hbfp_gemm(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(out), out.stride(0), beta,
-                          _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
-                          _stream_ptr(stream)), "hbfp_gemm")
+    workspace = _workspace(gemm_select_workspace(a.desc, b.desc, kernel), out.device, workspace)
+    _check(_lib.hbfp_gemm_select(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(out), out.stride(0), beta, kernel,
+                                 _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                 _stream_ptr(stream)), "hbfp_gemm_select")
     return out
 
 

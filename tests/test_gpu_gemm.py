@@ -24,11 +24,12 @@ def _rand(shape, seed, spread=4):
     return (rng.standard_normal(shape) * np.exp2(rng.integers(-spread, spread + 1, size=shape))).astype(np.float32)
 
 
-def _run(hb, A, B, fa, fb, partials=True, rows=None, beta=0.0):
-    """A [M,K], B [K,N] (source orientation).  fa = (br, bc, m, rounding, seed) for A, fb for B."""
+def _run(hb, A, B, fa, fb, partials=True, rows=None, beta=0.0, kernel=0):
+    """A [M,K], B [K,N] (source orientation).  fa = (br, bc, m, rounding, seed) for A, fb for B.
+    kernel: 0 = the library's choice, 1 = int8 kernels, 2 = block-scaled kernel."""
     M, K = A.shape
     N = B.shape[1]
-    print(f"[case] M={M} N={N} K={K} fa={fa} fb={fb}", flush=True)
+    print(f"[case] M={M} N={N} K={K} fa={fa} fb={fb} kernel={kernel}", flush=True)
     ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(fa[2], fa[0], fa[1], fa[3], fa[4]))
     tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(fb[2], fb[0], fb[1], fb[3], fb[4]))
     oa = ref.encode(A, fa[0], fa[1], fa[2], fa[3], fa[4])
@@ -47,9 +48,9 @@ def _run(hb, A, B, fa, fb, partials=True, rows=None, beta=0.0):
     C0 = None
     if beta:
         C0 = _rand((M, N), 1234, 1)
-        C = hb.gemm(ta, tb, out=torch.from_numpy(C0).cuda(), beta=1.0)
+        C = hb.gemm(ta, tb, out=torch.from_numpy(C0).cuda(), beta=1.0, kernel=kernel)
     else:
-        C = hb.gemm(ta, tb)
+        C = hb.gemm(ta, tb, kernel=kernel)
     torch.cuda.synchronize()
     C = C.cpu().numpy()
     C64 = ref.gemm(ref.decode(oa), ref.decode(ob), rows=rows)
@@ -239,3 +240,112 @@ def test_config5_wide_range_bfp12_sampled(hb):
     rows = np.random.default_rng(6).choice(8192, size=16, replace=False)
     rows.sort()
     _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows)
+
+
+# ---- the block-scaled kernel (hbfp_gemm_select with HBFP_KERNEL_SCALED): 256 x 256 tiles, k-steps of 64
+
+SCALED = 2
+
+
+@pytest.mark.parametrize("K", [32, 64, 160, 256, 330, 512, 640, 1100])
+def test_scaled_kernel_every_pipeline_length(hb, K):
+    """1 to 18 k-steps of 64 (padded to an even count): start-up, steady state and every drain path of the
+    three-buffer ring; 2 x 3 tiles with ragged edges."""
+    A, B = _rand((300, K), K + 5), _rand((K, 520), K + 6)
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=SCALED)
+
+
+@pytest.mark.parametrize("ma,mb", [(8, 8), (4, 4), (5, 8), (8, 5), (2, 6), (9, 9), (12, 12), (10, 9), (9, 12), (11, 10)])
+def test_scaled_kernel_limb_counts(hb, ma, mb):
+    """One, two and three limbs per operand in every combination the mantissa classes allow; with beta = 1."""
+    A, B = _rand((290, 700), ma * 7 + mb), _rand((700, 270), ma + mb * 11)
+    _run(hb, A, B, (1, 32, ma, 0, 0), (32, 1, mb, 0, 0), partials=False, kernel=SCALED)
+    _run(hb, A, B, (1, 32, ma, 1, 3), (32, 1, mb, 1, 4), partials=False, kernel=SCALED, beta=1.0)
+
+
+@pytest.mark.parametrize("blk,m", [(24, 8), (64, 8), (200, 8), (0, 8), (64, 12), (24, 10), (512, 12)])
+def test_scaled_kernel_block_lengths(hb, blk, m):
+    """Padded blocks (24), blocks that span several 32-element groups, one exponent per row; 2-D weight tiles."""
+    A, B = _rand((130, 1000), blk + m), _rand((1000, 300), blk + 2 * m)
+    _run(hb, A, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
+    if blk == 24:
+        _run(hb, A, (B * 0.02).astype(np.float32), (1, 24, m, 0, 0), (24, 24, m, 0, 0), partials=False, kernel=SCALED)
+
+
+def test_scaled_kernel_extreme_mantissas(hb):
+    """Every mantissa +-127 (limbs 7 and 15) and +-2047 (limbs 7, 15, 15): the largest limb products and block sums."""
+    M, N, K = 64, 96, 2048
+    rng = np.random.default_rng(0)
+    A = (rng.choice([-1.0, 1.0], size=(M, K)) * 127.0).astype(np.float32)
+    B = (np.ones((K, N)) * 127.0).astype(np.float32)
+    B[:, ::2] *= -1
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=SCALED)
+    A12 = (A / 127.0 * 2047.0).astype(np.float32)
+    B12 = (B / 127.0 * 2047.0).astype(np.float32)
+    _run(hb, A12, B12, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False, kernel=SCALED)
+
+
+def test_scaled_kernel_power_of_two_inputs_are_exact(hb):
+    rng = np.random.default_rng(4)
+    A = (rng.choice([-1.0, 1.0], size=(64, 256)) * np.exp2(rng.integers(-3, 3, size=(64, 256)))).astype(np.float32)
+    B = (rng.choice([-1.0, 1.0], size=(256, 64)) * np.exp2(rng.integers(-3, 3, size=(256, 64)))).astype(np.float32)
+    ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(8, 1, 32))
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 32, 1))
+    C = hb.gemm(ta, tb, kernel=SCALED).cpu().numpy()
+    np.testing.assert_array_equal(C.astype(np.float64), A.astype(np.float64) @ B.astype(np.float64))
+
+
+def test_scaled_kernel_wide_exponent_range(hb):
+    """Rows and columns spread over 2^+-20, then the whole product moved towards both ends of the FP32 range but
+    still inside what the scale bytes of the instruction can hold."""
+    rng = np.random.default_rng(8)
+    M, N, K = 96, 80, 512
+    A = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * np.exp2(rng.integers(-20, 21, size=(K, 1)))).astype(np.float32)
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=SCALED)
+    A2 = (A.astype(np.float64) * 2.0 ** -60).astype(np.float32)
+    B2 = (B.astype(np.float64) * 2.0 ** 55).astype(np.float32)
+    _run(hb, A2, B2, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=SCALED)
+
+
+@pytest.mark.parametrize("m,blk", [(8, 32), (12, 64)])
+def test_scaled_kernel_hands_over_to_int8_outside_its_exponent_range(hb, m, blk):
+    """Blocks below 2^-120 (exponent byte under 3) and subnormal operands cannot be expressed by the scale bytes:
+    the same call must still return the product (the int8 kernels run behind the block-scaled one)."""
+    A, B = _rand((150, 256), 5 + m), _rand((256, 140), 6 + m)
+    A2 = (A.astype(np.float64) * 2.0 ** -124).astype(np.float32)          # partly subnormal
+    B2 = (B.astype(np.float64) * 2.0 ** 100).astype(np.float32)
+    _run(hb, A2, B2, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
+    _run(hb, A2, B2, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED, beta=1.0)
+    # a single tiny block among ordinary ones
+    A3 = A.copy()
+    A3[7, 64:96] = (A[7, 64:96].astype(np.float64) * 2.0 ** -126).astype(np.float32)
+    _run(hb, A3, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
+    # the workspace flag is cleared by every call: an in-range product right after still takes the scaled kernel
+    _run(hb, A, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
+
+
+def test_scaled_and_int8_kernels_agree(hb):
+    """Same operands through both kernel families: each within the bound of the oracle, and close to each other."""
+    A, B = _rand((400, 900), 71), _rand((900, 300), 72)
+    ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(8, 1, 32))
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 32, 1))
+    c1 = hb.gemm(ta, tb, kernel=1).cpu().numpy()
+    c2 = hb.gemm(ta, tb, kernel=SCALED).cpu().numpy()
+    assert rel_fro(c2, c1) <= 2e-6
+
+
+def test_scaled_kernel_large_product_sampled(hb):
+    """4096 x 4096 outputs (the launch shape the automatic choice uses: 256 tiles, one per compute unit), K = 1024,
+    blocks of 32, checked on sampled rows; then the automatic choice on 4096^3 takes the same kernel."""
+    rng = np.random.default_rng(9)
+    A = rng.standard_normal((4096, 1024)).astype(np.float32)
+    B = (rng.standard_normal((1024, 4096)) * 0.02).astype(np.float32)
+    rows = np.sort(rng.choice(4096, size=24, replace=False))
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, rows=rows, kernel=SCALED)
+    A4 = np.concatenate([A] * 4, axis=1)
+    B4 = np.concatenate([B] * 4, axis=0)
+    ta = hb.plan(hb.make_format(8, 1, 32), 4096, 4096, 1)
+    tb = hb.plan(hb.make_format(8, 32, 1), 4096, 4096, 0)
+    assert hb.gemm_workspace(ta, tb) > hb.gemm_select_workspace(ta, tb, hb.KERNEL_INT8)
+    _run(hb, A4, B4, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, rows=rows[:12])
