@@ -4,8 +4,9 @@
 A step is one pass of the whole path over one batch of config 4 (dense layer,
 M = K = N = 4096, 8-bit mantissas, 1 x 24 activation/gradient blocks, 24 x 24 weight
 tiles): for each of the forward, data-gradient and weight-gradient products, both
-operands are converted FP32 -> BFP and multiplied (int8 matrix cores per exponent
-block, FP32 scale-and-accumulate).  Each of the three FP32 matrices (input, weights,
+operands are converted FP32 -> BFP and multiplied (hbfp_gemm: for this shape the
+library picks the block-scaled matrix instruction, 8-bit mantissas as two 4-bit limbs,
+exponent bytes applied in the instruction, FP32 accumulation).  Each of the three FP32 matrices (input, weights,
 output gradient) is converted into both operand layouts it is needed in by one
 hbfp_encode_multi call (the weight tiles from a single read; the 1-D activation blocks
 by one kernel per layout); the cpu_baseline leg does the same six conversions one by
@@ -30,6 +31,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 matrix peak, published
+FP6_PEAK_TFLOPS = 10100.0  # MI355X dense FP6 / FP4 matrix peak, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X FP32 vector peak, published (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
@@ -38,6 +40,9 @@ HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 #   config 4 GEMM launch: 141527 KiB x 2.0 + 65536 KiB = 357.0 MB   (algorithmic 113.6 MB: panels re-read across XCD L2s)
 #   config 2 encode m=8 RNE launch: 131652 KiB x 2.0 + 67589 KiB = 338.8 MB   (algorithmic 337.6 MB)
 TRAFFIC_GEMM_C4_BYTES = 357.0e6
+# algorithmic bytes of one config 4 product: both operands as stored (int8 mantissas padded to 5504 per row + exponent
+# bytes) read once, C written once
+ALG_BYTES_GEMM_C4 = 2 * 4096 * 5504 + 2 * 4096 * 172 + 4096 * 4096 * 4
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.8e6
 
 
@@ -213,7 +218,8 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                      "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
         del ta, tb, out, ws
     del X, W, dY
-    # config 5: 8192^3, 12-bit mantissas as two int8 limbs, blocks of 64, stochastic rounding
+    # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the
+    # block-scaled matrix instruction with three 4-bit limbs per mantissa)
     Ah, Bh = synth.c5_wide_range()
     A, B = torch.from_numpy(Ah).cuda(), torch.from_numpy(Bh).cuda()
     fa, fb = hbfp.make_format(12, 1, 64, hbfp.STOCHASTIC, 51), hbfp.make_format(12, 64, 1, hbfp.STOCHASTIC, 52)
@@ -230,6 +236,33 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                        "TOPS_kernel": round(flops / ms_k / 1e9, 1),
                        "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
     return res
+
+
+def _kernel_families(torch, hbfp, reps=8):
+    """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
+    int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
+    (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included)."""
+    res = {}
+    g = torch.Generator(device="cuda").manual_seed(7)
+    for name, n, m, blk in (("4096_bfp8_b32", 4096, 8, 32), ("8192_bfp8_b32", 8192, 8, 32), ("4096_bfp8_b24", 4096, 8, 24),
+                            ("4096_bfp4_b32", 4096, 4, 32), ("8192_bfp12_b64", 8192, 12, 64)):
+        A = torch.randn((n, n), device="cuda", generator=g)
+        B = torch.randn((n, n), device="cuda", generator=g)
+        ta, tb = hbfp.encode(A, 1, hbfp.make_format(m, 1, blk)), hbfp.encode(B, 0, hbfp.make_format(m, blk, 1))
+        del A, B
+        out = torch.empty((n, n), dtype=torch.float32, device="cuda")
+        entry = {}
+        for tag, kernel in (("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)):
+            ws = torch.empty(max(hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel), 256), dtype=torch.uint8, device="cuda")
+            ms = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws, kernel=kernel), reps)
+            entry[tag + "_ms"] = round(ms, 4)
+            entry[tag + "_TOPS"] = round(2.0 * n ** 3 / ms / 1e9, 1)
+            del ws
+        auto = hbfp.gemm_workspace(ta.desc, tb.desc) > hbfp.gemm_select_workspace(ta.desc, tb.desc, hbfp.KERNEL_INT8)
+        entry["automatic_choice"] = "scaled" if auto else "int8"
+        res[name] = entry
+        del ta, tb, out
+    return {"kernel_families": res}
 
 
 def _cpu_baseline(synth):
@@ -309,9 +342,9 @@ def main():
 
     gemm_ms = timer.total_ms("gemm") / timer.count("gemm")
     gemm_tops = flops_product / gemm_ms / 1e9
-    nblk = -(-shape["K"] // 24)
-    alu_flop = 3.0 * shape["M"] * shape["N"] * nblk
-    alu_tflops = alu_flop / (gemm_ms * 1e-3) / 1e12
+    # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
+    limb_flop = 4.0 * flops_product
+    limb_tflops = limb_flop / (gemm_ms * 1e-3) / 1e12
     enc_act_ms = timer.total_ms("encode_act") / args.steps
     enc_w_ms = timer.total_ms("encode_w") / args.steps
     gemm_step_ms = timer.total_ms("gemm") / args.steps
@@ -328,7 +361,7 @@ def main():
         "metric": "BFP8 GEMM effective TOPS incl. encode (% int8 MFMA peak); encode GB/s",
         "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 mantissas x int32 block sums, FP32 accumulate", "data": "synthetic",
+        "dtype": "int8 mantissas as 4-bit limbs in FP6 (E2M3), block-scaled matrix instruction, FP32 accumulate", "data": "synthetic",
         "config": {"workload": "config 4: dense layer M=K=N=4096, BFP8, 1x24 activation blocks, 24x24 weight tiles, "
                                "forward + data gradient + weight gradient, all six operand encodes included (3 conversion calls, 3 products)", **shape},
         "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
@@ -336,21 +369,22 @@ def main():
                                   "encode_weights_x2": round(enc_w_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
         "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
-        # Blocks of 24 (padded to 32) mean one matrix instruction (65536 int8 ops) per 32 x 32 outputs and block,
-        # against 2 FP32 vector instructions (a subtraction and a multiply-add: 3 flop) per output and block for
-        # the scaling: the vector ALU, not the matrix core, bounds this kernel, so that is the roofline stated;
-        # the matrix-core fraction is given beside it.
-        "roofline": {"bound": "alu", "kernel": "gemm_i8_w8_kernel", "achieved": round(alu_tflops, 2),
-                     "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(alu_tflops / FP32_VECTOR_PEAK_TFLOPS, 4),
+        # The product runs on the block-scaled matrix instruction with FP6 (E2M3) operands: an 8-bit mantissa is two
+        # sign-magnitude limbs of 4 bits, so a mantissa product is 4 limb products, all of them matrix-core work
+        # (the per-block scaling happens inside the instruction).  Algorithmic flop per launch = 4 * 2*M*N*K (padding
+        # of the 24-element blocks to 32 not counted), against the published dense FP6 peak.
+        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2>", "achieved": round(limb_tflops, 1),
+                     "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
-                     "algorithmic_bytes": 113.6e6, "avg_launch_ms": round(gemm_ms, 4),
-                     "algorithmic_flop_per_launch": alu_flop,
-                     "issue_slot_frac": round(2.0 * shape["M"] * shape["N"] * nblk / (gemm_ms * 1e-3) / (FP32_VECTOR_PEAK_TFLOPS * 0.5e12), 4),
-                     "int8_TOPS": round(gemm_tops, 2), "int8_matrix_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
-                     "note": "3 flop (v_sub_f32 + v_fmac_f32) per output element and exponent block, 171 blocks of 24 along K; "
-                             "issue_slot_frac counts the 2 instructions against the peak instruction rate (a subtraction fills a "
-                             "slot but is 1 flop); avg_launch_ms is the HIP-event time of one product call = this kernel plus a "
-                             "5 us kernel that expands exponent bytes to scale words"},
+                     "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(gemm_ms, 4),
+                     "algorithmic_flop_per_launch": limb_flop,
+                     "int8_equivalent_TOPS": round(gemm_tops, 2), "int8_matrix_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "power_limited_peak_measured": {"fp6_TFLOPS_random_operands": 5750.0, "int8_TOPS_random_operands": 3400.0,
+                                                     "note": "register-only loops of the matrix instruction on this box: the chip "
+                                                             "lowers its clock to 1.4 GHz (FP6) / 1.6 GHz (int8) when the operand bits are random"},
+                     "note": "avg_launch_ms is the HIP-event time of one product call: a one-workgroup kernel that clears the range "
+                             "flag, the pack kernel (both operands into limb planes, about 15 % of the call), the product kernel, and "
+                             "the int8 kernel that exits at once when every exponent is in range; the rocprofv3 summary lists each"},
     }
     if not args.no_extra:
         extra = _encode_config2(torch, hbfp, synth)
@@ -362,6 +396,7 @@ def main():
                                   "algorithmic_bytes": e["bytes"], "avg_launch_ms": e["ms"]}
         extra.update(_gemm_side_configs(torch, hbfp, synth))
         extra.update(_weight_update_config4(torch, hbfp, synth))
+        extra.update(_kernel_families(torch, hbfp))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)

@@ -618,7 +618,8 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        if (use_w8(a.kpad)) {
+        // behind the block-scaled kernel (run_if) the product almost never runs: one launch, no scale-word kernel
+        if (use_w8(a.kpad) && !a.run_if) {
             static bool configured = false;
             if (!configured) {
                 for (const void *f : {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),

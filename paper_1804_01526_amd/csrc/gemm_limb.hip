@@ -497,7 +497,7 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.final_scale = ldexpf(1.0f, 4 - a.mA - a.mB);
     p.run_if = a.run_if;
     const dim3 grid((unsigned)(tm * tn));
-    if (!a.P && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
+    if (!a.P && !a.run_if && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
         static bool configured = false;
         if (!configured) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_limb_w8_kernel),

@@ -56,10 +56,10 @@ struct PackParams {
 };
 
 template <int L, typename MT>
-__global__ __launch_bounds__(256) void mx_pack_kernel(const PackParams p) {
+__device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t block) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t rt = blockIdx.x / p.nks4;
-    const int ks = (int)(blockIdx.x % p.nks4) * 4 + wave;
+    const int64_t rt = block / p.nks4;
+    const int ks = (int)(block % p.nks4) * 4 + wave;
     if (ks >= p.ksteps) return;
     const int64_t row = rt * 32 + (lane & 31);
     const int kb = 2 * ks + (lane >> 5);                      // 32-element chunk of the stored row
@@ -116,6 +116,17 @@ __global__ __launch_bounds__(256) void mx_pack_kernel(const PackParams p) {
         }
     }
     *reinterpret_cast<uint32_t *>(chunk + L * kLimbBytes + lane * 4) = word;
+}
+
+// both operands of a product in one launch: the first blocks_a workgroups pack A, the rest B
+struct PackPair {
+    PackParams op[2];
+    uint32_t blocks_a;
+};
+template <int LA, int LB, typename MT>
+__global__ __launch_bounds__(256) void mx_pack_kernel(const PackPair q) {
+    if (blockIdx.x < q.blocks_a) mx_pack_block<LA, MT>(q.op[0], blockIdx.x);
+    else mx_pack_block<LB, MT>(q.op[1], blockIdx.x - q.blocks_a);
 }
 
 __global__ void mx_clear_flag_kernel(int *flag) {
@@ -461,9 +472,8 @@ inline size_t packed_bytes(int64_t rows, int64_t kpad, int L) {
     return (size_t)ceil_div(rows, 256) * (size_t)(kpad / 64) * (size_t)panel_stage_bytes(L);
 }
 
-template <int L>
-int launch_pack(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m, bool wide,
-                uint8_t *out, int *flag, hipStream_t s) {
+PackParams pack_params(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m,
+                       uint8_t *out, int *flag) {
     PackParams q;
     q.mant = mant;
     q.exps = exps;
@@ -476,19 +486,34 @@ int launch_pack(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, 
     q.nks4 = (q.ksteps + 3) / 4;
     q.chunks32_per_block = (int32_t)(kbp / 32);
     q.m = m;
-    const int64_t blocks = ceil_div(R, 256) * 8 * q.nks4;
-    if (blocks > 0x7fffffff) return HBFP_ERR_ARG;
-    if (wide) hipLaunchKernelGGL((mx_pack_kernel<L, int16_t>), dim3((unsigned)blocks), dim3(256), 0, s, q);
-    else hipLaunchKernelGGL((mx_pack_kernel<L, int8_t>), dim3((unsigned)blocks), dim3(256), 0, s, q);
+    return q;
+}
+
+template <int LA, int LB, typename MT>
+int launch_pack_t(const PackPair &q, unsigned blocks, hipStream_t s) {
+    hipLaunchKernelGGL((mx_pack_kernel<LA, LB, MT>), dim3(blocks), dim3(256), 0, s, q);
     return launch_status();
 }
 
-int pack_operand(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m, int L,
-                 uint8_t *out, int *flag, hipStream_t s) {
-    const bool wide = m > 8;
-    if (L == 1) return launch_pack<1>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
-    if (L == 2) return launch_pack<2>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
-    return launch_pack<3>(mant, exps, R, kpad, exp_ld, kbp, m, wide, out, flag, s);
+int launch_pack(const GemmArgs &a, int LA, int LB, uint8_t *pa, uint8_t *pb, int *flag, hipStream_t s) {
+    PackPair q;
+    q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, pa, flag);
+    q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, pb, flag);
+    const int64_t ba = ceil_div(a.M, 256) * 8 * q.op[0].nks4, bb = ceil_div(a.N, 256) * 8 * q.op[1].nks4;
+    if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
+    q.blocks_a = (uint32_t)ba;
+    const unsigned blocks = (unsigned)(ba + bb);
+    switch (LA * 4 + LB + (a.mA > 8 ? 16 : 0)) {               // both operands are of the same mantissa class
+        case 1 * 4 + 1: return launch_pack_t<1, 1, int8_t>(q, blocks, s);
+        case 1 * 4 + 2: return launch_pack_t<1, 2, int8_t>(q, blocks, s);
+        case 2 * 4 + 1: return launch_pack_t<2, 1, int8_t>(q, blocks, s);
+        case 2 * 4 + 2: return launch_pack_t<2, 2, int8_t>(q, blocks, s);
+        case 16 + 2 * 4 + 2: return launch_pack_t<2, 2, int16_t>(q, blocks, s);
+        case 16 + 2 * 4 + 3: return launch_pack_t<2, 3, int16_t>(q, blocks, s);
+        case 16 + 3 * 4 + 2: return launch_pack_t<3, 2, int16_t>(q, blocks, s);
+        case 16 + 3 * 4 + 3: return launch_pack_t<3, 3, int16_t>(q, blocks, s);
+        default: return HBFP_ERR_FORMAT;
+    }
 }
 
 template <int LA, int LB>
@@ -508,12 +533,12 @@ int launch_mx_t(const MxParams &p, hipStream_t s) {
 
 }  // namespace
 
-// The block-scaled path pays for itself when its 256 x 256 tiles fill the chip and it issues fewer instructions than
-// the int8 kernels.  Measured on 8192^3 and 4096^3 products: four limb products per k-step (6..9-bit mantissas) beat
-// the int8 kernel only where that one scales after every matrix instruction (blocks of exactly 32; blocks of 24 would
-// pay for their padding four times here); one or two limb products (an operand of at most 5 bits) and the 12-bit
-// formats (6 or 9 limb products against four int8 products plus five vector instructions per output and block) win
-// for every block length.
+// The block-scaled path pays for itself when its 256 x 256 tiles fill the chip and it spends less energy than the int8
+// kernels (both are limited by the power the chip may draw, not by issue slots).  Measured on 4096^3 and 8192^3
+// products: four limb products per k-step (6..9-bit mantissas) beat the int8 kernel where that one scales after every
+// matrix instruction (blocks of at most 32, stored padded to 32: 8 to 20 % faster), not for longer blocks; one or two
+// limb products (an operand of at most 5 bits: 2 x faster) and the 12-bit formats (6 or 9 limb products against four
+// int8 products plus five vector instructions per output and block: 1.4 x faster) win for every block length.
 bool gemm_mx_possible(const GemmArgs &a) {
     return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 64 <= 0x7fffffff;
 }
@@ -525,7 +550,7 @@ bool gemm_mx_ok(const GemmArgs &a) {
     if ((double)a.M * (double)a.N < 0.75 * 65536.0 * (double)tiles) return false;   // ragged edges would waste the tiles
     if ((double)a.M * (double)a.N * (double)a.kpad < 6.0e10) return false;          // too short to repay the packing
     const int products = limbs_of(a.mA) * limbs_of(a.mB);
-    if (products == 4) return a.kbp == 32 && a.kblock == 32;
+    if (products == 4) return a.kbp == 32;
     return true;
 }
 
@@ -540,9 +565,7 @@ int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s) {
     int *flag = (int *)w;
     uint8_t *pa = w + 256, *pb = pa + packed_bytes(a.M, a.kpad, LA);
     hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, flag);
-    int rc = pack_operand(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, LA, pa, flag, s);
-    if (rc != HBFP_OK) return rc;
-    rc = pack_operand(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, LB, pb, flag, s);
+    const int rc = launch_pack(a, LA, LB, pa, pb, flag, s);
     if (rc != HBFP_OK) return rc;
     MxParams p;
     p.pa = pa;
