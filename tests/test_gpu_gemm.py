@@ -203,14 +203,18 @@ def test_config3_conv_shapes_sampled(hb):
 
 
 def test_config4_linear_layer_sampled(hb):
-    """Config 4 at full size: 1 x 24 activation blocks, 24 x 24 weight tiles, K = 4096 = 170*24 + 16."""
+    """Config 4 at full size: 1 x 24 activation blocks, 24 x 24 weight tiles, K = 4096 = 170*24 + 16.  The library's
+    choice for these products is the block-scaled kernel; the int8 kernels are checked on the same operands."""
     import synth
     X, W, dY = synth.c4_linear()
+    tx, tw = hb.plan(hb.make_format(8, 1, 24), 4096, 4096, 1), hb.plan(hb.make_format(8, 24, 24), 4096, 4096, 0)
+    assert hb.gemm_workspace(tx, tw) > hb.gemm_select_workspace(tx, tw, hb.KERNEL_INT8)
     rows = np.random.default_rng(5).choice(4096, size=32, replace=False)
     rows.sort()
     _run(hb, X, W, (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)                        # forward
     _run(hb, dY, np.ascontiguousarray(W.T), (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)  # dgrad
     _run(hb, np.ascontiguousarray(X.T), dY, (1, 24, 8, 0, 0), (24, 1, 8, 0, 0), partials=False, rows=rows)   # wgrad
+    _run(hb, X, W, (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows, kernel=1)              # forward, int8 kernels
 
 
 @pytest.mark.parametrize("M,N,K,B,m,rounding", [
@@ -234,12 +238,14 @@ def test_gemm_wide_mantissas_extreme_values(hb):
 
 
 def test_config5_wide_range_bfp12_sampled(hb):
-    """Config 5 at full size: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20."""
+    """Config 5 at full size: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20:
+    the library's choice (block-scaled kernel, three limbs per mantissa), then the int8 limb kernels."""
     import synth
     A, B = synth.c5_wide_range()
     rows = np.random.default_rng(6).choice(8192, size=16, replace=False)
     rows.sort()
     _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows)
+    _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows, kernel=1)
 
 
 # ---- the block-scaled kernel (hbfp_gemm_select with HBFP_KERNEL_SCALED): 256 x 256 tiles, k-steps of 64
@@ -337,15 +343,9 @@ def test_scaled_and_int8_kernels_agree(hb):
 
 def test_scaled_kernel_large_product_sampled(hb):
     """4096 x 4096 outputs (the launch shape the automatic choice uses: 256 tiles, one per compute unit), K = 1024,
-    blocks of 32, checked on sampled rows; then the automatic choice on 4096^3 takes the same kernel."""
+    blocks of 32, checked on sampled rows."""
     rng = np.random.default_rng(9)
     A = rng.standard_normal((4096, 1024)).astype(np.float32)
     B = (rng.standard_normal((1024, 4096)) * 0.02).astype(np.float32)
     rows = np.sort(rng.choice(4096, size=24, replace=False))
     _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, rows=rows, kernel=SCALED)
-    A4 = np.concatenate([A] * 4, axis=1)
-    B4 = np.concatenate([B] * 4, axis=0)
-    ta = hb.plan(hb.make_format(8, 1, 32), 4096, 4096, 1)
-    tb = hb.plan(hb.make_format(8, 32, 1), 4096, 4096, 0)
-    assert hb.gemm_workspace(ta, tb) > hb.gemm_select_workspace(ta, tb, hb.KERNEL_INT8)
-    _run(hb, A4, B4, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, rows=rows[:12])
