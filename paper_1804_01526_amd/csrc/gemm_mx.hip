@@ -76,20 +76,46 @@ __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t bloc
 #pragma unroll
         for (int i = 0; i < NV; ++i) raw[i] = reinterpret_cast<const v4i *>(src)[i];
         uint32_t any = 0;
+        if constexpr (sizeof(MT) == 1) {
+            // four int8 mantissas per register at a time: |v| byte-wise (v = -128 does not occur), limbs and signs
+            // as bytes, then the four 6-bit codes of a register squeezed into 24 bits and eight such groups laid end
+            // to end in the six registers of a limb
+            uint32_t g[L][8];
 #pragma unroll
-        for (int e = 0; e < 32; ++e) {
-            int v;
-            if (sizeof(MT) == 1) v = (int)(int8_t)((uint32_t)raw[e >> 4][(e >> 2) & 3] >> (8 * (e & 3)));
-            else v = (int)(int16_t)((uint32_t)raw[e >> 3][(e >> 1) & 3] >> (16 * (e & 1)));
-            const uint32_t s = v < 0 ? 32u : 0u;
-            const uint32_t a = (uint32_t)(v < 0 ? -v : v);
-            any |= a;
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t x = (uint32_t)raw[i >> 2][i & 3];
+                const uint32_t sg = (x >> 7) & 0x01010101u;               // 1 in the bytes of negative mantissas
+                const uint32_t a = (x ^ (sg * 255u)) + sg;                // byte-wise two's complement negation
+                any |= a;
 #pragma unroll
-            for (int j = 0; j < L; ++j) {
-                const uint32_t code = s | ((a >> (4 * (L - 1 - j))) & 15u);
-                const int bit = 6 * e;
-                limb[j][bit >> 5] |= code << (bit & 31);
-                if ((bit & 31) > 26) limb[j][(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+                for (int j = 0; j < L; ++j) {
+                    const uint32_t w = ((a >> (4 * (L - 1 - j))) & 0x0f0f0f0fu) | (sg << 5);   // codes, one per byte
+                    const uint32_t t = (w & 0x003f003fu) | ((w >> 2) & 0x0fc00fc0u);          // two 12-bit pairs
+                    g[j][i] = (t & 0xfffu) | ((t >> 4) & 0xfff000u);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < L; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    limb[j][3 * h + 0] = g[j][4 * h] | (g[j][4 * h + 1] << 24);
+                    limb[j][3 * h + 1] = (g[j][4 * h + 1] >> 8) | (g[j][4 * h + 2] << 16);
+                    limb[j][3 * h + 2] = (g[j][4 * h + 2] >> 16) | (g[j][4 * h + 3] << 8);
+                }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const int v = (int)(int16_t)((uint32_t)raw[e >> 3][(e >> 1) & 3] >> (16 * (e & 1)));
+                const uint32_t s = v < 0 ? 32u : 0u;
+                const uint32_t a = (uint32_t)(v < 0 ? -v : v);
+                any |= a;
+#pragma unroll
+                for (int j = 0; j < L; ++j) {
+                    const uint32_t code = s | ((a >> (4 * (L - 1 - j))) & 15u);
+                    const int bit = 6 * e;
+                    limb[j][bit >> 5] |= code << (bit & 31);
+                    if ((bit & 31) > 26) limb[j][(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+                }
             }
         }
         int E = p.exps[row * p.exp_ld + kb / p.chunks32_per_block];
@@ -165,6 +191,14 @@ struct MxParams {
             _Pragma("unroll") for (int d = 0; d < 3; ++d)                                                                  \
                 bf[buf][3 * l + d] = *reinterpret_cast<const v2i *>((base_) + bbase[l] + (j) * CHB + d * 8);               \
         bs[buf] = *reinterpret_cast<const int *>((base_) + b4 + (j) * CHB);                                                \
+    }
+// Two-limb fragments in pieces, so that the reads of the next column tile can be issued between the matrix
+// instructions of the current one (a wave that finds the LDS queue full then still has matrix instructions in flight)
+#define HBFP_MX_READ_B_PIECE(buf, j, base_, FIRST, LAST, SCALE)                                                             \
+    {                                                                                                                      \
+        _Pragma("unroll") for (int x = (FIRST); x <= (LAST); ++x)                                                          \
+            bf[buf][x] = *reinterpret_cast<const v2i *>((base_) + bbase[x / 3] + (j) * CHB + (x % 3) * 8);                 \
+        if (SCALE) bs[buf] = *reinterpret_cast<const int *>((base_) + b4 + (j) * CHB);                                     \
     }
 // the builtin takes 8 registers per operand and drops the last two for this format
 #define HBFP_MX_MFMA(abuf, bbuf, JA, JB, i, j)                                                                              \
@@ -335,6 +369,22 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
     __builtin_amdgcn_sched_barrier(0)
     // MODE 0: hand-over with a copy of stage ks + RING;  1: hand-over, nothing left to copy, one more stage in flight;
     //      2: hand-over, nothing left to copy, the next stage is the last;  3: last k-step
+    /* column tile j from B buffer bbuf, fragment of column tile jn into B buffer bn in four pieces */
+#define HBFP_MX_COLUMN22(abuf, bbuf, j, bn, jn, base_, COPY)                                                               \
+    {                                                                                                                      \
+        HBFP_MX_PAIR(abuf, bbuf, 0, 0, j, COPY);                                                                           \
+        HBFP_MX_READ_B_PIECE(bn, jn, base_, 0, 1, false);                                                                  \
+        HBFP_MX_FENCE;                                                                                                     \
+        HBFP_MX_PAIR(abuf, bbuf, 0, 1, j, COPY);                                                                           \
+        HBFP_MX_READ_B_PIECE(bn, jn, base_, 2, 2, true);                                                                   \
+        HBFP_MX_FENCE;                                                                                                     \
+        HBFP_MX_PAIR(abuf, bbuf, 1, 0, j, COPY);                                                                           \
+        HBFP_MX_READ_B_PIECE(bn, jn, base_, 3, 4, false);                                                                  \
+        HBFP_MX_FENCE;                                                                                                     \
+        HBFP_MX_PAIR(abuf, bbuf, 1, 1, j, COPY);                                                                           \
+        HBFP_MX_READ_B_PIECE(bn, jn, base_, 5, 5, false);                                                                  \
+        HBFP_MX_FENCE;                                                                                                     \
+    }
 #define HBFP_MX_HANDOVER(MODE)                                                                                             \
     {                                                                                                                      \
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                                 \
@@ -349,7 +399,25 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
         const int copy_ring = ring;                                                                                        \
         const int next = ring + 1 == RING ? 0 : ring + 1;                                                                  \
         const uint8_t *nbase = lds + next * STAGE;                                                                         \
-        if (!ONE_A) {                                                                                                      \
+        if (LA == 2 && LB == 2) {                                                                                          \
+            /* two limbs each: four pairs of matrix instructions per column tile, a quarter of the next column   */       \
+            /* tile's fragment requested after each pair                                                         */       \
+            HBFP_MX_COLUMN22(abuf, 0, 0, 1, 1, base, false);                                                               \
+            HBFP_MX_COLUMN22(abuf, 1, 1, 0, 2, base, false);                                                               \
+            HBFP_MX_COLUMN22(abuf, 0, 2, 1, 3, base, false);                                                               \
+            if (MODE != 3) HBFP_MX_HANDOVER(MODE);                                                                         \
+            HBFP_MX_PAIR(abuf, 1, 0, 0, 3, MODE == 0);                                                                     \
+            if (MODE != 3) HBFP_MX_READ_B(0, 0, nbase);                                                                    \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_PAIR(abuf, 1, 0, 1, 3, MODE == 0);                                                                     \
+            if (MODE != 3) HBFP_MX_READ_A1(1 - (abuf), 0, nbase);                                                          \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_PAIR(abuf, 1, 1, 0, 3, MODE == 0);                                                                     \
+            if (MODE != 3) HBFP_MX_READ_A1(1 - (abuf), 1, nbase);                                                          \
+            HBFP_MX_FENCE;                                                                                                 \
+            HBFP_MX_PAIR(abuf, 1, 1, 1, 3, MODE == 0);                                                                     \
+            HBFP_MX_FENCE;                                                                                                 \
+        } else if (!ONE_A) {                                                                                               \
             /* the first matrix instructions wait for the reads of the previous hand-over; the next column    */          \
             /* tile is requested behind them so that this wait does not cover it                              */          \
             HBFP_MX_COLUMN(abuf, 0, 0, false, 1);                                                                          \
@@ -431,6 +499,7 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
     HBFP_MX_KSTEP(1, 3);
 #undef HBFP_MX_KSTEP
 #undef HBFP_MX_HANDOVER
+#undef HBFP_MX_COLUMN22
 #undef HBFP_MX_FENCE
 #undef HBFP_MX_COPY_STAGE
 
@@ -466,6 +535,7 @@ constexpr int mx_lds_bytes(int LA, int LB) {
 #undef HBFP_MX_MFMA
 #undef HBFP_MX_READ_A
 #undef HBFP_MX_READ_B
+#undef HBFP_MX_READ_B_PIECE
 
 
 inline size_t packed_bytes(int64_t rows, int64_t kpad, int L) {

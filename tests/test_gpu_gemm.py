@@ -349,3 +349,26 @@ def test_scaled_kernel_large_product_sampled(hb):
     B = (rng.standard_normal((1024, 4096)) * 0.02).astype(np.float32)
     rows = np.sort(rng.choice(4096, size=24, replace=False))
     _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, rows=rows, kernel=SCALED)
+
+
+def test_gemm_f32_large_takes_the_scaled_kernel(hb):
+    """hbfp_gemm_f32 on a product the automatic choice hands to the block-scaled kernel (4-bit mantissas: one limb),
+    forward and weight-gradient orientation, checked on sampled rows."""
+    rng = np.random.default_rng(12)
+    M, N, K = 3072, 3072, 6500
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    fa, fb = hb.make_format(4, 1, 32), hb.make_format(4, 32, 1)
+    assert hb.gemm_workspace(hb.plan(fa, M, K, 1), hb.plan(fb, K, N, 0)) > \
+        hb.gemm_select_workspace(hb.plan(fa, M, K, 1), hb.plan(fb, K, N, 0), hb.KERNEL_INT8)
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    print("[case] gemm_f32 3072 x 3072 x 6500, 4-bit mantissas", flush=True)
+    C = hb.gemm_f32(0, 0, torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), fa, fb)
+    torch.cuda.synchronize()
+    oa, ob = ref.encode(A, 1, 32, 4), ref.encode(B, 32, 1, 4)
+    C64 = ref.gemm(ref.decode(oa), ref.decode(ob), rows=rows)
+    assert rel_fro(C.cpu().numpy()[rows], C64) <= TOL
+    At = np.ascontiguousarray(A.T)                                  # op(A) = At^T: contraction down the rows of At
+    C2 = hb.gemm_f32(1, 0, torch.from_numpy(At).cuda(), torch.from_numpy(B).cuda(), hb.make_format(4, 32, 1), fb)
+    torch.cuda.synchronize()
+    assert rel_fro(C2.cpu().numpy()[rows], C64) <= TOL
