@@ -21,7 +21,8 @@
 //               product kernel moves whole stages with contiguous asynchronous copies and every fragment
 //               read is three conflict-free 8-byte LDS reads per lane (lanes 24 bytes apart cover all 64 banks).
 // gemm_mx_kernel: 256 x 256 tile of C per workgroup, 8 waves of 64 x 128, three-stage LDS ring, one
-//               barrier per k-step, fragment reads one column tile ahead of the matrix instructions.
+//               barrier per k-step, fragment reads one column tile ahead of the matrix instructions that use them
+//               and issued between the matrix instructions of the column tile before.
 // An exponent byte outside 0..254 (blocks below 2^-120 or above 2^126) cannot be expressed; the pack
 // kernel raises a flag, the product kernel then does nothing and the int8 kernels, launched behind it
 // with the opposite condition, compute the product instead.
@@ -168,8 +169,8 @@ struct MxParams {
     int32_t ksteps, tiles_m, tiles_n, beta;
 };
 
-// one operand of the matrix instruction: 6 registers of E2M3 codes (the builtin takes 8 and drops the last two for
-// this format)
+// The product kernel is a set of macros over its local arrays (function templates taking the fragment arrays by
+// reference left them in scratch memory).
 // Fragment registers: af[buffer][row tile][3 * limb + piece], bf[buffer][3 * limb + piece]: the codes of a lane are read
 // 8 bytes at a time, limb l at l * kLimbBytes; as / bs are the scale words.
 #define HBFP_MX_READ_A1(buf, i, base_)                                                                                      \
