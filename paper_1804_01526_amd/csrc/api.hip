@@ -354,7 +354,7 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
     if (use_scaled(g, kernel)) {
         // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
         // the int8 kernels queue up behind it and run only in that case
-        rc = launch_gemm_mx(g, workspace, (hipStream_t)stream);
+        rc = launch_gemm_mx(g, workspace, (hipStream_t)stream, &g.run_val);
         if (rc != HBFP_OK) return rc;
         g.run_if = (const int *)workspace;
         workspace = (char *)workspace + align256(gemm_mx_workspace(g));

@@ -57,9 +57,10 @@ struct WordParams {
     int slots, row_blocks;
     uint32_t a_or;               // 0x40: row words are 1.5 * 2^(E - 127) as bf16; 0: 2^(E - 127) as bf16
     const int *run_if;
+    int32_t run_val;
 };
 __global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
-    if (w.run_if && !*w.run_if) return;
+    if (w.run_if && *w.run_if != w.run_val) return;
     const int z = blockIdx.z;
     const int64_t row = (int64_t)(blockIdx.x % w.row_blocks) * 256 + threadIdx.x;
     if (row >= w.rows_pad[z]) return;
@@ -78,7 +79,8 @@ inline size_t word_bytes(int64_t rows, int64_t slots) { return (size_t)slots * (
 
 // slots must be a multiple of 4 and at most the exponent row pitch of either operand
 inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const uint8_t *eB, int64_t ldB, int64_t N, int slots,
-                              uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_if, hipStream_t s) {
+                              uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_if, int32_t run_val,
+                              hipStream_t s) {
     WordParams wp;
     wp.exps[0] = eA; wp.exps[1] = eB;
     wp.words[0] = wA; wp.words[1] = wB;
@@ -88,6 +90,7 @@ inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const u
     wp.slots = slots;
     wp.a_or = a_or;
     wp.run_if = run_if;
+    wp.run_val = run_val;
     const int64_t maxpad = wp.rows_pad[0] > wp.rows_pad[1] ? wp.rows_pad[0] : wp.rows_pad[1];
     wp.row_blocks = (int)ceil_div(maxpad, 256);
     if ((int64_t)wp.row_blocks * (slots / 4) > 0x7fffffff) return HBFP_ERR_ARG;

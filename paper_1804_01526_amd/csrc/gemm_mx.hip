@@ -26,6 +26,9 @@
 // An exponent byte outside 0..254 (blocks below 2^-120 or above 2^126) cannot be expressed; the pack
 // kernel raises a flag, the product kernel then does nothing and the int8 kernels, launched behind it
 // with the opposite condition, compute the product instead.
+#include <atomic>
+#include <chrono>
+
 #include "gemm_common.h"
 
 namespace hbfp {
@@ -54,6 +57,7 @@ struct PackParams {
     int *flag;
     int64_t R, kpad, exp_ld;
     int32_t ksteps, nks4, chunks32_per_block, m;
+    int32_t epoch;               // written to *flag when an exponent byte is out of range
 };
 
 template <int L, typename MT>
@@ -131,7 +135,7 @@ __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t bloc
             }
             word |= (uint32_t)byte << (8 * j);
         }
-        if (bad && any) atomicOr(p.flag, 1);                  // all-zero groups (padding) take any exponent
+        if (bad && any) *p.flag = p.epoch;                    // all-zero groups (padding) take any exponent
     }
     uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
 #pragma unroll
@@ -164,6 +168,7 @@ __global__ void mx_clear_flag_kernel(int *flag) {
 struct MxParams {
     const uint8_t *pa, *pb;      // packed operands
     const int *flag;
+    int32_t epoch;               // *flag == epoch: an operand of this call is outside the range of the scale bytes
     float *C;
     int64_t M, N, ldc;
     int32_t ksteps, tiles_m, tiles_n, beta;
@@ -285,7 +290,7 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
     constexpr int NCOPY = (PIECES + 7) / 8;                    // per wave and stage
     constexpr bool ONE_A = LA > 2 || LB > 2;                   // three limbs: no room for a second set of row-tile registers
 
-    if (*p.flag) return;                                       // uniform: the int8 kernels take over
+    if (*p.flag == p.epoch) return;                            // uniform: the int8 kernels take over
     int tm, tn;
     if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
 
@@ -544,12 +549,13 @@ inline size_t packed_bytes(int64_t rows, int64_t kpad, int L) {
 }
 
 PackParams pack_params(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m,
-                       uint8_t *out, int *flag) {
+                       uint8_t *out, int *flag, int32_t epoch) {
     PackParams q;
     q.mant = mant;
     q.exps = exps;
     q.out = out;
     q.flag = flag;
+    q.epoch = epoch;
     q.R = R;
     q.kpad = kpad;
     q.exp_ld = exp_ld;
@@ -566,10 +572,10 @@ int launch_pack_t(const PackPair &q, unsigned blocks, hipStream_t s) {
     return launch_status();
 }
 
-int launch_pack(const GemmArgs &a, int LA, int LB, uint8_t *pa, uint8_t *pb, int *flag, hipStream_t s) {
+int launch_pack(const GemmArgs &a, int LA, int LB, uint8_t *pa, uint8_t *pb, int *flag, int32_t epoch, hipStream_t s) {
     PackPair q;
-    q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, pa, flag);
-    q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, pb, flag);
+    q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, pa, flag, epoch);
+    q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, pb, flag, epoch);
     const int64_t ba = ceil_div(a.M, 256) * 8 * q.op[0].nks4, bb = ceil_div(a.N, 256) * 8 * q.op[1].nks4;
     if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
     q.blocks_a = (uint32_t)ba;
@@ -635,18 +641,34 @@ size_t gemm_mx_workspace(const GemmArgs &a) {
     return 256 + packed_bytes(a.M, a.kpad, limbs_of(a.mA)) + packed_bytes(a.N, a.kpad, limbs_of(a.mB));
 }
 
-int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s) {
+// A call marks its out-of-range flag with a value of its own, so the flag word never has to be cleared between
+// calls: whatever an earlier call (or nobody) left there differs from this call's value.  (Should stale memory
+// match by accident, the int8 kernels compute the product: slower, still correct.)  A captured call is replayed
+// with the same value, so there the flag is cleared by a small kernel first.
+static int32_t next_epoch() {
+    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+    uint32_t e;
+    do e = counter.fetch_add(1, std::memory_order_relaxed); while (e == 0);
+    return (int32_t)e;
+}
+
+int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s, int32_t *run_val) {
     const int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
     uint8_t *w = (uint8_t *)workspace;
     int *flag = (int *)w;
     uint8_t *pa = w + 256, *pb = pa + packed_bytes(a.M, a.kpad, LA);
-    hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, flag);
-    const int rc = launch_pack(a, LA, LB, pa, pb, flag, s);
+    const int32_t epoch = next_epoch();
+    *run_val = epoch;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone)
+        hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, flag);
+    const int rc = launch_pack(a, LA, LB, pa, pb, flag, epoch, s);
     if (rc != HBFP_OK) return rc;
     MxParams p;
     p.pa = pa;
     p.pb = pb;
     p.flag = flag;
+    p.epoch = epoch;
     p.C = a.C;
     p.M = a.M;
     p.N = a.N;

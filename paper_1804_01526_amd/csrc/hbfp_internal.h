@@ -49,7 +49,8 @@ struct GemmArgs {
     int64_t ldc;
     float beta;
     int32_t *P;                       // non-null: dump block partials instead of C
-    const int *run_if;                // non-null: every kernel of the launch does nothing unless *run_if != 0
+    const int *run_if;                // non-null: every kernel of the launch does nothing unless *run_if == run_val
+    int32_t run_val;
 };
 // 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
 // up to three outputs of the same tile shape in any orientation
@@ -62,11 +63,11 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
 
 // gemm_mx.hip: the product on the block-scaled matrix instruction.  launch_gemm_mx packs both operands and
-// runs the product; it leaves a flag at the start of its workspace that is non-zero when some exponent
-// could not be expressed, in which case it has not touched C and the int8 path has to run (run_if).
+// runs the product; the word at the start of its workspace equals *run_val afterwards when some exponent
+// could not be expressed, in which case it has not touched C and the int8 path has to run (run_if, run_val).
 bool gemm_mx_possible(const GemmArgs &a);   // shapes the kernel can address
 bool gemm_mx_ok(const GemmArgs &a);         // shapes and formats for which it is the faster choice
 size_t gemm_mx_workspace(const GemmArgs &a);
-int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s);
+int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s, int32_t *run_val);
 
 }  // namespace hbfp

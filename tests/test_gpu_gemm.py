@@ -327,7 +327,7 @@ def test_scaled_kernel_hands_over_to_int8_outside_its_exponent_range(hb, m, blk)
     A3 = A.copy()
     A3[7, 64:96] = (A[7, 64:96].astype(np.float64) * 2.0 ** -126).astype(np.float32)
     _run(hb, A3, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
-    # the workspace flag is cleared by every call: an in-range product right after still takes the scaled kernel
+    # every call marks the flag with a value of its own: an in-range product right after takes the scaled kernel again
     _run(hb, A, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0), partials=False, kernel=SCALED)
 
 
@@ -372,3 +372,39 @@ def test_gemm_f32_large_takes_the_scaled_kernel(hb):
     C2 = hb.gemm_f32(1, 0, torch.from_numpy(At).cuda(), torch.from_numpy(B).cuda(), hb.make_format(4, 32, 1), fb)
     torch.cuda.synchronize()
     assert rel_fro(C2.cpu().numpy()[rows], C64) <= TOL
+
+
+def test_scaled_kernel_in_a_replayed_graph(hb):
+    """One product call with the block-scaled kernel captured in a HIP graph and replayed on operands that are
+    re-encoded in place between replays: ordinary values, then values below the range of the scale bytes (the
+    replay has to hand over to the int8 kernels), then ordinary values again.  Every replay is compared with an
+    eager call on the same operands."""
+    M, N, K = 300, 280, 384
+    fa, fb = hb.make_format(8, 1, 32), hb.make_format(8, 32, 1)
+    A0, B0 = _rand((M, K), 91), _rand((K, N), 92)
+    tiny = (A0.astype(np.float64) * 2.0 ** -124).astype(np.float32)
+    xa, xb = torch.from_numpy(A0).cuda(), torch.from_numpy(B0).cuda()
+    ta, tb = hb.encode(xa, 1, fa), hb.encode(xb, 0, fb)
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(hb.gemm_select_workspace(ta.desc, tb.desc, SCALED), dtype=torch.uint8, device="cuda")
+    hb.gemm(ta, tb, out=out, workspace=ws, kernel=SCALED)             # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            hb.gemm(ta, tb, out=out, workspace=ws, kernel=SCALED)
+    torch.cuda.current_stream().wait_stream(side)
+    for step, src in enumerate([A0, tiny, A0, tiny, tiny, A0]):
+        print(f"[case] graph replay {step}", flush=True)
+        hb.encode(torch.from_numpy(src).cuda(), 1, fa, out=ta)        # same buffers, new contents
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = hb.gemm(ta, tb, kernel=1)
+        torch.cuda.synchronize()
+        want = ref.gemm(ref.decode(ref.encode(src, 1, 32, 8)), ref.decode(ref.encode(B0, 32, 1, 8)))
+        assert rel_fro(out.cpu().numpy(), want) <= TOL
+        assert rel_fro(out.cpu().numpy(), eager.cpu().numpy()) <= 2e-6
