@@ -408,3 +408,23 @@ def test_scaled_kernel_in_a_replayed_graph(hb):
         want = ref.gemm(ref.decode(ref.encode(src, 1, 32, 8)), ref.decode(ref.encode(B0, 32, 1, 8)))
         assert rel_fro(out.cpu().numpy(), want) <= TOL
         assert rel_fro(out.cpu().numpy(), eager.cpu().numpy()) <= 2e-6
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_scaled_kernel_random_shapes(hb, case):
+    """Seeded random shapes (down to a single row, column or contraction element), block lengths, mantissa widths of
+    either class, rounding modes and beta, through the block-scaled kernel."""
+    rng = np.random.default_rng(1000 + case)
+    M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+    K = int(rng.choice([1, 7, 31, 32, 33, 63, 64, 65, 127, 129, 500, 1023, 1500]))
+    blk = int(rng.choice([8, 16, 24, 32, 48, 64, 100, 0]))
+    if rng.integers(2):
+        ma, mb = int(rng.integers(2, 9)), int(rng.integers(2, 9))
+    else:
+        ma, mb = int(rng.integers(9, 13)), int(rng.integers(9, 13))
+    if blk == 0 and max(ma, mb) > 8:
+        blk = 256                                                        # keeps 12-bit block sums inside int32
+    ra, rb = int(rng.integers(2)), int(rng.integers(2))
+    A, B = _rand((M, K), 2000 + case), _rand((K, N), 3000 + case)
+    _run(hb, A, B, (1, blk, ma, ra, 17 + case), (blk, 1, mb, rb, 29 + case), partials=False, kernel=SCALED,
+         beta=float(rng.integers(2)))

@@ -323,6 +323,33 @@ def test_limb_identity_for_12_bit_mantissas_exhaustive():
     np.testing.assert_array_equal(prod, rec)
 
 
+def test_four_bit_limb_identity_and_scale_bytes_exhaustive():
+    """The identity a product on 4-bit sign-magnitude limbs relies on (host-side check of the arithmetic, no GPU):
+    |v| = sum_i n_i 16^i with n_i in 0..15; limb i of a block with stored exponent byte E and m-bit mantissas is the
+    narrow float +-n_i / 8 times 2^(byte_i - 127) with byte_i = E + 5 + 4 i - m; summed over the limbs that is
+    Eq. (1), v * 2^(E - 125 - m), and the products of all limb pairs sum to the product of two decoded values."""
+    for m, limbs in ((4, 1), (5, 1), (8, 2), (9, 2), (12, 3)):
+        q = (1 << (m - 1)) - 1
+        v = np.arange(-q, q + 1, dtype=np.int64)
+        a = np.abs(v)
+        n = [(a >> (4 * i)) & 15 for i in range(limbs)]
+        assert sum(ni << (4 * i) for i, ni in enumerate(n)).tolist() == a.tolist()      # nothing left above the top limb
+        for E in (m - 5, 97, 140, 250 - 4 * (limbs - 1)):                               # both ends of the byte range
+            byte = [E + 5 + 4 * i - m for i in range(limbs)]
+            assert min(byte) >= 0 and max(byte) <= 254
+            val = sum(np.sign(v) * (ni / 8.0) * np.exp2(float(b - 127)) for ni, b in zip(n, byte))
+            np.testing.assert_array_equal(val, v * np.exp2(float(E - 125 - m)))
+    # all limb pairs of two 8-bit mantissas with their own exponents: exact in FP64, equal to the decoded product
+    v = np.arange(-127, 128, dtype=np.int64)
+    a = np.abs(v)
+    lo, hi = a & 15, a >> 4
+    Ea, Eb = 131, 118
+    limb = lambda e: [np.sign(v) * (lo / 8.0) * np.exp2(e - 3.0 - 127.0), np.sign(v) * (hi / 8.0) * np.exp2(e + 1.0 - 127.0)]
+    total = sum(np.multiply.outer(x, y) for x in limb(Ea) for y in limb(Eb))
+    want = np.multiply.outer(v * np.exp2(Ea - 133.0), v * np.exp2(Eb - 133.0))
+    np.testing.assert_array_equal(total, want)
+
+
 # ---------------------------------------------------------------- GEMM
 def test_gemm_is_the_fp64_product():
     rng = np.random.default_rng(17)
