@@ -241,11 +241,14 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
 def _kernel_families(torch, hbfp, reps=8):
     """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
     int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
-    (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included)."""
+    (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included).  Block length 0 is one
+    exponent per row of A and per column of B (Sec. 4), where the int8 family runs its 256 x 256-tile kernel
+    (one chain of matrix instructions, exponents applied at the store)."""
     res = {}
     g = torch.Generator(device="cuda").manual_seed(7)
     for name, n, m, blk in (("4096_bfp8_b32", 4096, 8, 32), ("8192_bfp8_b32", 8192, 8, 32), ("4096_bfp8_b24", 4096, 8, 24),
-                            ("4096_bfp4_b32", 4096, 4, 32), ("8192_bfp12_b64", 8192, 12, 64)):
+                            ("4096_bfp4_b32", 4096, 4, 32), ("8192_bfp12_b64", 8192, 12, 64),
+                            ("4096_bfp8_one_exponent_per_row", 4096, 8, 0), ("8192_bfp8_one_exponent_per_row", 8192, 8, 0)):
         A = torch.randn((n, n), device="cuda", generator=g)
         B = torch.randn((n, n), device="cuda", generator=g)
         ta, tb = hbfp.encode(A, 1, hbfp.make_format(m, 1, blk)), hbfp.encode(B, 0, hbfp.make_format(m, blk, 1))

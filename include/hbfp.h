@@ -192,6 +192,12 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
  *                       in 3..253 for 8-bit mantissas (7..253 for 12-bit); when an operand holds a
  *                       non-zero block outside that range the call computes the product with the int8
  *                       kernels instead, inside the same call and without host synchronisation;
+ *   HBFP_KERNEL_INT8_WIDE  the member of the int8 family for one exponent per operand row (a single block
+ *                       along k, the basic scheme of Sec. 4) and mantissas of at most 8 bits: 256 x 256 tiles,
+ *                       one uninterrupted chain of matrix instructions, exponents applied when C is stored.
+ *                       HBFP_KERNEL_INT8 and HBFP_KERNEL_AUTO take it by themselves when at least 128 such
+ *                       tiles are at least 75 % full; naming it runs it on any shape (HBFP_ERR_FORMAT if the
+ *                       operands have more than one block or wider mantissas);
  *   HBFP_KERNEL_AUTO    what hbfp_gemm does: SCALED where it is measured faster (at least 128 output
  *                       tiles of 256 x 256, M*N*kpad >= 6e10, and either blocks shorter than 32
  *                       elements, blocks of 32 with M*N*kpad >= 2e11, an operand of at most 5 bits, or
@@ -203,6 +209,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 #define HBFP_KERNEL_AUTO 0
 #define HBFP_KERNEL_INT8 1
 #define HBFP_KERNEL_SCALED 2
+#define HBFP_KERNEL_INT8_WIDE 3
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes);
 int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
                      void *workspace, size_t ws_bytes, void *stream);

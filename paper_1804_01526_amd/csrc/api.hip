@@ -318,12 +318,12 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
 }
 
 static bool use_scaled(const GemmArgs &g, int kernel) {
-    if (g.P || kernel == HBFP_KERNEL_INT8) return false;
+    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE) return false;
     return kernel == HBFP_KERNEL_SCALED ? gemm_mx_possible(g) : gemm_mx_ok(g);
 }
 
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes) {
-    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_SCALED) return HBFP_ERR_ARG;
+    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
     int rc = check_tensor(A, false);
     if (rc != HBFP_OK) return rc;
     rc = check_tensor(B, false);
@@ -351,6 +351,10 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
     g.ldc = ldc;
     g.beta = beta;
     g.P = P;
+    if (kernel == HBFP_KERNEL_INT8_WIDE) {
+        if (!gemm_wide_possible(g)) return HBFP_ERR_FORMAT;
+        g.wide = 1;
+    }
     if (use_scaled(g, kernel)) {
         // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
         // the int8 kernels queue up behind it and run only in that case
@@ -367,7 +371,7 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !C) return HBFP_ERR_ARG;
     if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_SCALED) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
     if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
     return run_gemm(A, B, C, ldc, beta, nullptr, kernel, workspace, ws_bytes, stream);
 }

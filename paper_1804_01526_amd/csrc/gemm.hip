@@ -584,6 +584,7 @@ size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_
 }
 
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
+    if (a.wide ? gemm_wide_possible(a) : gemm_wide_ok(a)) return launch_gemm_wide(a, s);
     GemmParams p;
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;

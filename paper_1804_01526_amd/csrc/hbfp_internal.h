@@ -51,6 +51,7 @@ struct GemmArgs {
     int32_t *P;                       // non-null: dump block partials instead of C
     const int *run_if;                // non-null: every kernel of the launch does nothing unless *run_if == run_val
     int32_t run_val;
+    int32_t wide;                     // 1: the caller asked for the 256 x 256-tile int8 kernel whatever the shape
 };
 // 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
 // up to three outputs of the same tile shape in any orientation
@@ -61,6 +62,11 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld);
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
+
+// gemm_wide.hip: int8 kernel for one exponent per operand row (a single block along k), 256 x 256 tiles
+bool gemm_wide_possible(const GemmArgs &a);
+bool gemm_wide_ok(const GemmArgs &a);
+int launch_gemm_wide(const GemmArgs &a, hipStream_t s);
 
 // gemm_mx.hip: the product on the block-scaled matrix instruction.  launch_gemm_mx packs both operands and
 // runs the product; the word at the start of its workspace equals *run_val afterwards when some exponent

@@ -185,7 +185,7 @@ def decode(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> tor
     return out
 
 
-KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED = 0, 1, 2
+KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED, KERNEL_INT8_WIDE = 0, 1, 2, 3
 
 
 def gemm_select_workspace(a: TensorDesc, b: TensorDesc, kernel: int) -> int:

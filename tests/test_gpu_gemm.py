@@ -428,3 +428,71 @@ def test_scaled_kernel_random_shapes(hb, case):
     A, B = _rand((M, K), 2000 + case), _rand((K, N), 3000 + case)
     _run(hb, A, B, (1, blk, ma, ra, 17 + case), (blk, 1, mb, rb, 29 + case), partials=False, kernel=SCALED,
          beta=float(rng.integers(2)))
+
+
+# ---- the 256 x 256-tile int8 kernel for one exponent per operand row (HBFP_KERNEL_INT8_WIDE)
+
+WIDE = 3
+
+
+@pytest.mark.parametrize("K", [1, 64, 128, 129, 200, 256, 320, 448, 1000, 4100])
+def test_wide_kernel_every_pipeline_length(hb, K):
+    """2 to 66 stages of 64: start-up, steady state and every drain path of the four-buffer ring; 2 x 3 tiles with
+    ragged edges; one exponent per row of A and per column of B."""
+    A, B = _rand((300, K), K + 15), _rand((K, 520), K + 16)
+    _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, kernel=WIDE)
+    _run(hb, A, B, (1, 0, 8, 1, 5), (0, 1, 8, 1, 6), partials=False, kernel=WIDE, beta=1.0)
+
+
+@pytest.mark.parametrize("M,N,K,ma,mb", [(1, 1, 300, 8, 8), (33, 257, 640, 8, 4), (513, 31, 777, 2, 8), (256, 256, 128, 6, 7)])
+def test_wide_kernel_shapes_and_widths(hb, M, N, K, ma, mb):
+    _run(hb, _rand((M, K), M + K), _rand((K, N), N + K), (1, 0, ma, 0, 0), (0, 1, mb, 0, 0), partials=False, kernel=WIDE)
+
+
+def test_wide_kernel_extreme_mantissas_and_exponents(hb):
+    """Every mantissa +-127 over K = 4096 (integer sums of 6.6e7, beyond 2^24: the conversion to FP32 rounds), then
+    rows and columns spread over 2^+-20 and pushed towards the ends of the FP32 range."""
+    M, N, K = 64, 96, 4096
+    rng = np.random.default_rng(0)
+    A = (rng.choice([-1.0, 1.0], size=(M, K)) * 127.0).astype(np.float32)
+    B = (np.ones((K, N)) * 127.0).astype(np.float32)
+    B[:, ::2] *= -1
+    _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, kernel=WIDE)
+    A = (rng.standard_normal((M, 512)) * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)
+    B = (rng.standard_normal((512, N)) * np.exp2(rng.integers(-20, 21, size=(1, N)))).astype(np.float32)
+    _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, kernel=WIDE)
+    A2 = (A.astype(np.float64) * 2.0 ** -70).astype(np.float32)
+    B2 = (B.astype(np.float64) * 2.0 ** 60).astype(np.float32)
+    _run(hb, A2, B2, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, kernel=WIDE)
+
+
+def test_wide_kernel_is_the_scaled_integer_product(hb):
+    """With one exponent per row and column the result is 2^(eA_i + eB_j) times an integer matrix product: exact
+    in FP32 whenever the integer sums stay below 2^24."""
+    rng = np.random.default_rng(21)
+    A = rng.integers(-127, 128, size=(100, 512)).astype(np.float32)
+    B = rng.integers(-127, 128, size=(512, 90)).astype(np.float32)
+    A[:, 0] = 127.0                                                  # every row and column keeps the full scale
+    B[0, :] = 127.0
+    ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(8, 1, 0))
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 0, 1))
+    C = hb.gemm(ta, tb, kernel=WIDE).cpu().numpy()
+    np.testing.assert_array_equal(C.astype(np.float64), A.astype(np.float64) @ B.astype(np.float64))
+
+
+def test_wide_kernel_needs_a_single_block(hb):
+    ta = hb.encode(torch.from_numpy(_rand((64, 256), 1)).cuda(), 1, hb.make_format(8, 1, 32))
+    tb = hb.encode(torch.from_numpy(_rand((256, 64), 2)).cuda(), 0, hb.make_format(8, 32, 1))
+    with pytest.raises(hb.HbfpError) as e:
+        hb.gemm(ta, tb, kernel=WIDE)
+    assert e.value.status == hb.ERR_FORMAT
+
+
+def test_wide_kernel_large_product_sampled(hb):
+    """4096 x 4096 outputs, K = 2048, one exponent per row / column: the library's own choice for this shape."""
+    rng = np.random.default_rng(19)
+    A = rng.standard_normal((4096, 2048)).astype(np.float32)
+    B = (rng.standard_normal((2048, 4096)) * 0.02).astype(np.float32)
+    rows = np.sort(rng.choice(4096, size=24, replace=False))
+    _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, rows=rows)
+    _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, rows=rows, kernel=WIDE)
