@@ -169,7 +169,13 @@ def test_gemm_select_validation():
         return d
 
     a, b = desc(8, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)
-    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 3, fake, 1 << 20, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 4, fake, 1 << 20, None) == hbfp.ERR_ARG
+    # the 256 x 256-tile int8 kernel is for one exponent per operand row: these operands have 8 blocks of 32
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_INT8_WIDE, fake, 1 << 20, None) == hbfp.ERR_FORMAT
+    a1, b1 = desc(8, 128, 256, 1, 1, 0), desc(8, 256, 64, 0, 0, 1)
+    assert hbfp.gemm_select_workspace(a1, b1, hbfp.KERNEL_INT8_WIDE) == hbfp.gemm_select_workspace(a1, b1, hbfp.KERNEL_INT8)
+    a12, b12 = desc(12, 128, 256, 1, 1, 0), desc(12, 256, 64, 0, 0, 1)
+    assert lib.hbfp_gemm_select(byref(a12), byref(b12), fake, 64, 0.0, hbfp.KERNEL_INT8_WIDE, fake, 1 << 24, None) == hbfp.ERR_FORMAT
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, -1, fake, 1 << 20, None) == hbfp.ERR_ARG
     assert _status(hbfp.gemm_select_workspace, a, b, 7) == hbfp.ERR_ARG
     n_int8 = hbfp.gemm_select_workspace(a, b, hbfp.KERNEL_INT8)
