@@ -37,9 +37,9 @@ HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/bench_default_hbm_traffic_counters.txt),
 # scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 product kernel (gemm_mx_kernel<2, 2>): 101165 KiB x 2.0 + 65536 KiB = 274.3 MB
+#   config 4 product kernel (gemm_mx_kernel<2, 2>): 97206 KiB x 2.0 + 65536 KiB = 266.2 MB
 #   config 2 encode m=8 RNE launch: 131652 KiB x 2.0 + 67589 KiB = 338.8 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 274.3e6
+TRAFFIC_GEMM_C4_BYTES = 266.2e6
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.8e6
 # algorithmic bytes of the config 4 product kernel: both operands as limb planes read once (16 panels of 256 rows x 86
 # k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
@@ -385,9 +385,9 @@ def main():
                      "power_limited_peak_measured": {"fp6_TFLOPS_random_operands": 5750.0, "int8_TOPS_random_operands": 3400.0,
                                                      "note": "register-only loops of the matrix instruction on this box: the chip "
                                                              "lowers its clock to 1.4 GHz (FP6) / 1.6 GHz (int8) when the operand bits are random"},
-                     "note": "avg_launch_ms is the HIP-event time of one product call: a one-workgroup kernel that clears the range "
-                             "flag, the pack kernel (both operands into limb planes, about 15 % of the call), the product kernel, and "
-                             "the int8 kernel that exits at once when every exponent is in range; the rocprofv3 summary lists each"},
+                     "note": "avg_launch_ms is the HIP-event time of one product call: the pack kernel (both operands into limb "
+                             "planes, about 14 % of the call), the product kernel, and the int8 kernel that exits at once when "
+                             "every exponent is in range; the rocprofv3 summary lists each"},
     }
     if not args.no_extra:
         extra = _encode_config2(torch, hbfp, synth)
