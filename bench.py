@@ -310,7 +310,7 @@ def main():
     torch.cuda.synchronize()
     run_step = step
     if args.graph:
-        # one HIP graph of the 12 launches of a step (no memset nodes: the library clears nothing with
+        # one HIP graph of the launches of a step (no memset nodes: the library clears nothing with
         # hipMemsetAsync on this path); replayed outputs are checked against the eager ones below
         eager = [o.clone() for o in outs]
         side = torch.cuda.Stream()
