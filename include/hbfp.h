@@ -215,6 +215,27 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_pack / hbfp_gemm_packed: the block-scaled kernel in two steps, for operands that take part in many
+ * products (weights between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders
+ * an encoded operand (mantissas of at most 12 bits) into the limb planes that kernel reads:
+ *   packed  device buffer of hbfp_pack_bytes bytes, 256-byte aligned, owned by the caller; its contents are
+ *           opaque and stay valid until the operand is encoded again (then pack it again)
+ * hbfp_gemm_packed is hbfp_gemm_select with HBFP_KERNEL_SCALED on operands packed beforehand: C and beta as in
+ * hbfp_gemm; A and B are the descriptors the buffers were packed from (their mantissas and exponents are read
+ * only when an operand holds a non-zero block outside the range of the scale bytes, in which case the int8
+ * kernels compute the product inside the same call); workspace: hbfp_gemm_packed_workspace bytes (what the int8
+ * kernels need).
+ * Errors: HBFP_ERR_ARG (null or misaligned pointers, beta, ldc), HBFP_ERR_FORMAT (mantissas wider than 12 bits,
+ * mixed classes), HBFP_ERR_LAYOUT, HBFP_ERR_RANGE as hbfp_gemm, HBFP_ERR_WORKSPACE (packed buffer or workspace too
+ * small), HBFP_ERR_LAUNCH.
+ */
+int hbfp_pack_bytes(const hbfp_tensor *t, size_t *bytes);
+int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream);
+int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes);
+int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tensor *B, const void *packed_b, float *C,
+                     int64_t ldc, float beta, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_gemm_partials: the fixed-point half of Eq. (2) alone, for checking:
  *     P[(i*N + j)*nblk + b] = sum_{k in block b} mA[i][k] * mB[j][k]     (int32, exact)
  * computed by the same matrix-core path as hbfp_gemm.  Same operand rules.

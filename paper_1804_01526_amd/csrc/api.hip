@@ -331,7 +331,8 @@ int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int k
     *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
                                                      : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld);
     const GemmArgs g = gemm_args(A, B);
-    if (use_scaled(g, kernel)) *bytes = align256(*bytes) + align256(gemm_mx_workspace(g));   // [block-scaled path][int8 path behind it]
+    if (use_scaled(g, kernel))                                   // [packed A][packed B][int8 path behind the block-scaled kernel]
+        *bytes = align256(*bytes) + mx_packed_bytes(g.M, g.kpad, g.mA) + mx_packed_bytes(g.N, g.kpad, g.mB);
     return HBFP_OK;
 }
 
@@ -358,10 +359,13 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
     if (use_scaled(g, kernel)) {
         // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
         // the int8 kernels queue up behind it and run only in that case
-        rc = launch_gemm_mx(g, workspace, (hipStream_t)stream, &g.run_val);
+        void *pa = workspace, *pb = (char *)workspace + mx_packed_bytes(g.M, g.kpad, g.mA);
+        rc = launch_mx_pack(g, pa, pb, (hipStream_t)stream);
+        if (rc == HBFP_OK) rc = launch_mx_product(g, pa, pb, (hipStream_t)stream);
         if (rc != HBFP_OK) return rc;
-        g.run_if = (const int *)workspace;
-        workspace = (char *)workspace + align256(gemm_mx_workspace(g));
+        g.run_a = (const int *)pa;
+        g.run_b = (const int *)pb;
+        workspace = (char *)pb + mx_packed_bytes(g.N, g.kpad, g.mB);
     }
     if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
     return launch_gemm_i8(g, workspace, (hipStream_t)stream);
@@ -379,6 +383,62 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
 int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta,
               void *workspace, size_t ws_bytes, void *stream) {
     return hbfp_gemm_select(A, B, C, ldc, beta, HBFP_KERNEL_AUTO, workspace, ws_bytes, stream);
+}
+
+int hbfp_pack_bytes(const hbfp_tensor *t, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    const int rc = check_tensor(t, false);
+    if (rc != HBFP_OK) return rc;
+    if (t->mant_bits > 12) return HBFP_ERR_FORMAT;
+    *bytes = mx_packed_bytes(t->rows, t->kpad, t->mant_bits);
+    return HBFP_OK;
+}
+
+int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream) {
+    int rc = check_tensor(t, true);
+    if (rc != HBFP_OK) return rc;
+    if (t->mant_bits > 12) return HBFP_ERR_FORMAT;
+    if (!packed || ((uintptr_t)packed & 255)) return HBFP_ERR_ARG;
+    if (bytes < mx_packed_bytes(t->rows, t->kpad, t->mant_bits)) return HBFP_ERR_WORKSPACE;
+    if (ceil_div(t->rows, 256) * 8 * ceil_div(t->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = t->mant;
+    g.expA = t->exps;
+    g.M = t->rows;
+    g.kpad = t->kpad;
+    g.expA_ld = t->exp_ld;
+    g.kbp = t->kblock_pad;
+    g.mA = g.mB = t->mant_bits;
+    return launch_mx_pack(g, packed, nullptr, (hipStream_t)stream);
+}
+
+int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
+    return hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_INT8, bytes);
+}
+
+int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tensor *B, const void *packed_b, float *C,
+                     int64_t ldc, float beta, void *workspace, size_t ws_bytes, void *stream) {
+    if (!A || !B || !C || !packed_a || !packed_b) return HBFP_ERR_ARG;
+    if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
+    if (((uintptr_t)packed_a & 255) || ((uintptr_t)packed_b & 255)) return HBFP_ERR_ARG;
+    int rc = check_pair(A, B);
+    if (rc != HBFP_OK) return rc;
+    if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_gemm_packed_workspace(A, B, &need);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    GemmArgs g = gemm_args(A, B);
+    g.C = C;
+    g.ldc = ldc;
+    g.beta = beta;
+    if (!gemm_mx_possible(g)) return HBFP_ERR_ARG;
+    rc = launch_mx_product(g, packed_a, packed_b, (hipStream_t)stream);
+    if (rc != HBFP_OK) return rc;
+    g.run_a = (const int *)packed_a;
+    g.run_b = (const int *)packed_b;
+    if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
+    return launch_gemm_i8(g, workspace, (hipStream_t)stream);
 }
 
 int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,

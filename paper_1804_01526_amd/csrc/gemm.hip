@@ -48,8 +48,7 @@ struct GemmParams {
     int32_t tiles_m, tiles_n;
     int32_t beta;
     float final_scale;
-    const int *run_if;           // non-null: do nothing unless *run_if == run_val
-    int32_t run_val;
+    const int *run_a, *run_b;    // non-null: do nothing unless a packed operand is marked out of range
 };
 
 struct StageRegs {
@@ -97,7 +96,7 @@ __device__ __forceinline__ void store_stage(const StageRegs &r, uint8_t *base, c
 template <int SPB, bool DUMP>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (p.run_if && *p.run_if != p.run_val) return;
+    if (stands_down(p.run_a, p.run_b)) return;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -317,7 +316,7 @@ template <int SPB>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const GemmParams &p = q.g;
-    if (p.run_if && *p.run_if != p.run_val) return;
+    if (stands_down(p.run_a, p.run_b)) return;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave & 3, wn = wave >> 2;
@@ -521,9 +520,9 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 // fixed-order sum over the split-K slices: deterministic, no float atomics.  The slices of one output are
 // requested eight at a time and added in slice order, so the result does not depend on the unrolling.
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *partial, float *C, int64_t M, int64_t N,
-                                                                  int64_t ldc, int splits, int beta, const int *run_if,
-                                                                  int run_val) {
-    if (run_if && *run_if != run_val) return;
+                                                                  int64_t ldc, int splits, int beta, const int *run_a,
+                                                                  const int *run_b) {
+    if (stands_down(run_a, run_b)) return;
     const int64_t n = M * N;
     for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < n; e += (int64_t)gridDim.x * kThreads) {
         const int64_t i = e / N, j = e % N;
@@ -608,8 +607,8 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.tiles_n = (int32_t)tn;
     p.beta = a.beta != 0.0f;
     p.final_scale = ldexpf(1.0f, 27 - a.mA - a.mB);
-    p.run_if = a.run_if;
-    p.run_val = a.run_val;
+    p.run_a = a.run_a;
+    p.run_b = a.run_b;
     const int stages_per_block = p.spb >= 4 ? p.spb / 4 : 1;
     p.splits = a.P ? 1 : choose_splits(a.M, a.N, p.nstage, stages_per_block);
     {
@@ -622,8 +621,8 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        // behind the block-scaled kernel (run_if) the product almost never runs: one launch, no scale-word kernel
-        if (use_w8(a.kpad) && !a.run_if) {
+        // behind the block-scaled kernel the product almost never runs: one launch, no scale-word kernel
+        if (use_w8(a.kpad) && !a.run_a) {
             static bool configured = false;
             if (!configured) {
                 for (const void *f : {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),
@@ -640,7 +639,7 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
             q.wA = (const uint32_t *)w;
             q.wB = (const uint32_t *)(w + word_bytes(a.M, a.expA_ld));
             rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0x40u,
-                                    const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_if, a.run_val, s);
+                                    const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_a, a.run_b, s);
             if (rc != HBFP_OK) return rc;
             if (p.spb == 1) hipLaunchKernelGGL(gemm_i8_w8_kernel<1>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             else if (p.spb == 2) hipLaunchKernelGGL(gemm_i8_w8_kernel<2>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
@@ -655,7 +654,7 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
         int64_t nb = ceil_div(a.M * a.N, kThreads);
         if (nb > 8192) nb = 8192;
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, p.partial, p.C, p.M, p.N,
-                           p.ldc, p.splits, p.beta, p.run_if, p.run_val);
+                           p.ldc, p.splits, p.beta, p.run_a, p.run_b);
         rc = launch_status();
     }
     return rc;

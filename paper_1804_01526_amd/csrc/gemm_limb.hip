@@ -29,8 +29,8 @@ constexpr int kLdsBytes = 2 * kStageBytes;
 
 // int16 mantissas [rows][kpad] -> two int8 planes [rows][kpad]: hi = v >> 6, lo = v & 63
 __global__ __launch_bounds__(kThreads) void limb_split_kernel(const int16_t *src, int8_t *hi, int8_t *lo, int64_t n8,
-                                                              const int *run_if, int run_val) {
-    if (run_if && *run_if != run_val) return;
+                                                              const int *run_a, const int *run_b) {
+    if (stands_down(run_a, run_b)) return;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kThreads) {
         const v4i d = *reinterpret_cast<const v4i *>(src + i * 8);
         uint32_t h[2] = {0, 0}, l[2] = {0, 0};
@@ -56,8 +56,7 @@ struct LimbParams {
     int32_t tiles_n;
     int32_t beta;
     float final_scale;
-    const int *run_if;                  // non-null: do nothing unless *run_if == run_val
-    int32_t run_val;
+    const int *run_a, *run_b;           // non-null: do nothing unless a packed operand is marked out of range
 };
 
 struct LimbRegs {
@@ -69,7 +68,7 @@ struct LimbRegs {
 template <int SPB, bool DUMP>
 __global__ __launch_bounds__(kThreads, 2) void gemm_limb_kernel(const LimbParams p) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
-    if (p.run_if && *p.run_if != p.run_val) return;
+    if (stands_down(p.run_a, p.run_b)) return;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -283,7 +282,7 @@ struct LimbW8Params {
 __global__ __launch_bounds__(kLwThreads, 4) void gemm_limb_w8_kernel(const LimbW8Params q) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const LimbParams &p = q.g;
-    if (p.run_if && *p.run_if != p.run_val) return;
+    if (stands_down(p.run_a, p.run_b)) return;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave & 1, wn = wave >> 1;
@@ -472,9 +471,9 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
         ga = ga > 65536 ? 65536 : ga;
         gb = gb > 65536 ? 65536 : gb;
         hipLaunchKernelGGL(limb_split_kernel, dim3((unsigned)ga), dim3(kThreads), 0, s, (const int16_t *)a.mantA,
-                           (int8_t *)p.AH, (int8_t *)p.AL, na, a.run_if, a.run_val);
+                           (int8_t *)p.AH, (int8_t *)p.AL, na, a.run_a, a.run_b);
         hipLaunchKernelGGL(limb_split_kernel, dim3((unsigned)gb), dim3(kThreads), 0, s, (const int16_t *)a.mantB,
-                           (int8_t *)p.BH, (int8_t *)p.BL, nb, a.run_if, a.run_val);
+                           (int8_t *)p.BH, (int8_t *)p.BL, nb, a.run_a, a.run_b);
         if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
     }
     p.eA = a.expA;
@@ -496,10 +495,10 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.tiles_n = (int32_t)tn;
     p.beta = a.beta != 0.0f;
     p.final_scale = ldexpf(1.0f, 4 - a.mA - a.mB);
-    p.run_if = a.run_if;
-    p.run_val = a.run_val;
+    p.run_a = a.run_a;
+    p.run_b = a.run_b;
     const dim3 grid((unsigned)(tm * tn));
-    if (!a.P && !a.run_if && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
+    if (!a.P && !a.run_a && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
         static bool configured = false;
         if (!configured) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_limb_w8_kernel),
@@ -516,7 +515,7 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
         q.wA = (const uint32_t *)ww;
         q.wB = (const uint32_t *)(ww + word_bytes(a.M, a.expA_ld));
         const int rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0u,
-                                          const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_if, a.run_val, s);
+                                          const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_a, a.run_b, s);
         if (rc != HBFP_OK) return rc;
         hipLaunchKernelGGL(gemm_limb_w8_kernel, dim3((unsigned)(ceil_div(tm * tn, 8) * 8)), dim3(kLwThreads), kLwLdsBytes, s, q);
         return launch_status();

@@ -24,8 +24,10 @@
 //               barrier per k-step, fragment reads one column tile ahead of the matrix instructions that use them
 //               and issued between the matrix instructions of the column tile before.
 // An exponent byte outside 0..254 (blocks below 2^-120 or above 2^126) cannot be expressed; the pack
-// kernel raises a flag, the product kernel then does nothing and the int8 kernels, launched behind it
-// with the opposite condition, compute the product instead.
+// kernel then marks the header of the packed operand, the product kernel does nothing when either header
+// is marked and the int8 kernels, launched behind it with the opposite condition, compute the product instead.
+// A packed operand (header + limb planes) stays valid until the operand is encoded again, so weights are
+// packed once per update and serve every product until the next.
 #include <atomic>
 #include <chrono>
 
@@ -54,15 +56,17 @@ struct PackParams {
     const void *mant;
     const uint8_t *exps;
     uint8_t *out;
-    int *flag;
+    int *header;                 // first 256 bytes of the packed operand: word 1 = this pack's mark, word 0 = the mark of
+                                 // the last pack that found an exponent byte out of range
     int64_t R, kpad, exp_ld;
     int32_t ksteps, nks4, chunks32_per_block, m;
-    int32_t epoch;               // written to *flag when an exponent byte is out of range
+    int32_t mark;
 };
 
 template <int L, typename MT>
 __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t block) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
     const int64_t rt = block / p.nks4;
     const int ks = (int)(block % p.nks4) * 4 + wave;
     if (ks >= p.ksteps) return;
@@ -135,7 +139,7 @@ __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t bloc
             }
             word |= (uint32_t)byte << (8 * j);
         }
-        if (bad && any) *p.flag = p.epoch;                    // all-zero groups (padding) take any exponent
+        if (bad && any) p.header[0] = p.mark;                 // all-zero groups (padding) take any exponent
     }
     uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
 #pragma unroll
@@ -160,15 +164,18 @@ __global__ __launch_bounds__(256) void mx_pack_kernel(const PackPair q) {
     else mx_pack_block<LB, MT>(q.op[1], blockIdx.x - q.blocks_a);
 }
 
-__global__ void mx_clear_flag_kernel(int *flag) {
-    if (threadIdx.x == 0) *flag = 0;
+// under graph capture a pack is replayed with the same mark: the out-of-range word is reset first
+__global__ void mx_clear_flag_kernel(int *header_a, int *header_b) {
+    if (threadIdx.x == 0) {
+        if (header_a) header_a[0] = 0;
+        if (header_b) header_b[0] = 0;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
 struct MxParams {
-    const uint8_t *pa, *pb;      // packed operands
-    const int *flag;
-    int32_t epoch;               // *flag == epoch: an operand of this call is outside the range of the scale bytes
+    const uint8_t *pa, *pb;      // limb planes of the packed operands
+    const int *ha, *hb;          // their headers: words 0 and 1 equal = outside the range of the scale bytes
     float *C;
     int64_t M, N, ldc;
     int32_t ksteps, tiles_m, tiles_n, beta;
@@ -290,7 +297,7 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
     constexpr int NCOPY = (PIECES + 7) / 8;                    // per wave and stage
     constexpr bool ONE_A = LA > 2 || LB > 2;                   // three limbs: no room for a second set of row-tile registers
 
-    if (*p.flag == p.epoch) return;                            // uniform: the int8 kernels take over
+    if (p.ha[0] == p.ha[1] || p.hb[0] == p.hb[1]) return;      // uniform: the int8 kernels take over
     int tm, tn;
     if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
 
@@ -548,14 +555,26 @@ inline size_t packed_bytes(int64_t rows, int64_t kpad, int L) {
     return (size_t)ceil_div(rows, 256) * (size_t)(kpad / 64) * (size_t)panel_stage_bytes(L);
 }
 
+// A pack marks the operand with a value of its own (word 1 of the header) and copies it to word 0 when an exponent
+// is out of range, so nothing has to be cleared between packs: whatever an earlier pack (or nobody) left in word 0
+// differs from this pack's mark.  (Should stale memory match by accident, the int8 kernels compute the product:
+// slower, still correct.)  A captured pack is replayed with the same mark, so there word 0 is cleared by a small
+// kernel first.
+int32_t next_mark() {
+    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+    uint32_t e;
+    do e = counter.fetch_add(1, std::memory_order_relaxed); while (e == 0);
+    return (int32_t)e;
+}
+
 PackParams pack_params(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m,
-                       uint8_t *out, int *flag, int32_t epoch) {
+                       void *packed) {
     PackParams q;
     q.mant = mant;
     q.exps = exps;
-    q.out = out;
-    q.flag = flag;
-    q.epoch = epoch;
+    q.header = (int *)packed;
+    q.out = (uint8_t *)packed + 256;
+    q.mark = next_mark();
     q.R = R;
     q.kpad = kpad;
     q.exp_ld = exp_ld;
@@ -570,27 +589,6 @@ template <int LA, int LB, typename MT>
 int launch_pack_t(const PackPair &q, unsigned blocks, hipStream_t s) {
     hipLaunchKernelGGL((mx_pack_kernel<LA, LB, MT>), dim3(blocks), dim3(256), 0, s, q);
     return launch_status();
-}
-
-int launch_pack(const GemmArgs &a, int LA, int LB, uint8_t *pa, uint8_t *pb, int *flag, int32_t epoch, hipStream_t s) {
-    PackPair q;
-    q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, pa, flag, epoch);
-    q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, pb, flag, epoch);
-    const int64_t ba = ceil_div(a.M, 256) * 8 * q.op[0].nks4, bb = ceil_div(a.N, 256) * 8 * q.op[1].nks4;
-    if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
-    q.blocks_a = (uint32_t)ba;
-    const unsigned blocks = (unsigned)(ba + bb);
-    switch (LA * 4 + LB + (a.mA > 8 ? 16 : 0)) {               // both operands are of the same mantissa class
-        case 1 * 4 + 1: return launch_pack_t<1, 1, int8_t>(q, blocks, s);
-        case 1 * 4 + 2: return launch_pack_t<1, 2, int8_t>(q, blocks, s);
-        case 2 * 4 + 1: return launch_pack_t<2, 1, int8_t>(q, blocks, s);
-        case 2 * 4 + 2: return launch_pack_t<2, 2, int8_t>(q, blocks, s);
-        case 16 + 2 * 4 + 2: return launch_pack_t<2, 2, int16_t>(q, blocks, s);
-        case 16 + 2 * 4 + 3: return launch_pack_t<2, 3, int16_t>(q, blocks, s);
-        case 16 + 3 * 4 + 2: return launch_pack_t<3, 2, int16_t>(q, blocks, s);
-        case 16 + 3 * 4 + 3: return launch_pack_t<3, 3, int16_t>(q, blocks, s);
-        default: return HBFP_ERR_FORMAT;
-    }
 }
 
 template <int LA, int LB>
@@ -636,39 +634,50 @@ bool gemm_mx_ok(const GemmArgs &a) {
     return true;
 }
 
-// workspace of the block-scaled path: [flag, 256 bytes][packed A][packed B]
-size_t gemm_mx_workspace(const GemmArgs &a) {
-    return 256 + packed_bytes(a.M, a.kpad, limbs_of(a.mA)) + packed_bytes(a.N, a.kpad, limbs_of(a.mB));
-}
+size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits) { return 256 + packed_bytes(rows, kpad, limbs_of(mant_bits)); }
 
-// A call marks its out-of-range flag with a value of its own, so the flag word never has to be cleared between
-// calls: whatever an earlier call (or nobody) left there differs from this call's value.  (Should stale memory
-// match by accident, the int8 kernels compute the product: slower, still correct.)  A captured call is replayed
-// with the same value, so there the flag is cleared by a small kernel first.
-static int32_t next_epoch() {
-    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
-    uint32_t e;
-    do e = counter.fetch_add(1, std::memory_order_relaxed); while (e == 0);
-    return (int32_t)e;
-}
-
-int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s, int32_t *run_val) {
-    const int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
-    uint8_t *w = (uint8_t *)workspace;
-    int *flag = (int *)w;
-    uint8_t *pa = w + 256, *pb = pa + packed_bytes(a.M, a.kpad, LA);
-    const int32_t epoch = next_epoch();
-    *run_val = epoch;
+int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s) {
+    if (!packed_a && !packed_b) return HBFP_OK;
+    PackPair q;
+    int64_t ba = 0, bb = 0;
+    int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
+    if (packed_a) {
+        q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, packed_a);
+        ba = ceil_div(a.M, 256) * 8 * q.op[0].nks4;
+    }
+    if (packed_b) {
+        q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, packed_b);
+        bb = ceil_div(a.N, 256) * 8 * q.op[1].nks4;
+    }
+    if (!packed_a) LA = LB;                                     // the absent operand has no workgroups; any instantiation does
+    if (!packed_b) LB = LA;
+    if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
+    q.blocks_a = (uint32_t)ba;
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone)
-        hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, flag);
-    const int rc = launch_pack(a, LA, LB, pa, pb, flag, epoch, s);
-    if (rc != HBFP_OK) return rc;
+        hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, (int *)packed_a, (int *)packed_b);
+    const unsigned blocks = (unsigned)(ba + bb);
+    const bool wide = (packed_a ? a.mA : a.mB) > 8;             // both operands of a product are of the same mantissa class
+    switch (LA * 4 + LB + (wide ? 16 : 0)) {
+        case 1 * 4 + 1: return launch_pack_t<1, 1, int8_t>(q, blocks, s);
+        case 1 * 4 + 2: return launch_pack_t<1, 2, int8_t>(q, blocks, s);
+        case 2 * 4 + 1: return launch_pack_t<2, 1, int8_t>(q, blocks, s);
+        case 2 * 4 + 2: return launch_pack_t<2, 2, int8_t>(q, blocks, s);
+        case 16 + 2 * 4 + 2: return launch_pack_t<2, 2, int16_t>(q, blocks, s);
+        case 16 + 2 * 4 + 3: return launch_pack_t<2, 3, int16_t>(q, blocks, s);
+        case 16 + 3 * 4 + 2: return launch_pack_t<3, 2, int16_t>(q, blocks, s);
+        case 16 + 3 * 4 + 3: return launch_pack_t<3, 3, int16_t>(q, blocks, s);
+        default: return HBFP_ERR_FORMAT;
+    }
+}
+
+int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s) {
+    const int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
     MxParams p;
-    p.pa = pa;
-    p.pb = pb;
-    p.flag = flag;
-    p.epoch = epoch;
+    p.ha = (const int *)packed_a;
+    p.hb = (const int *)packed_b;
+    p.pa = (const uint8_t *)packed_a + 256;
+    p.pb = (const uint8_t *)packed_b + 256;
     p.C = a.C;
     p.M = a.M;
     p.N = a.N;

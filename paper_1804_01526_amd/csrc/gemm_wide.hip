@@ -33,13 +33,12 @@ struct WideParams {
     int32_t nstage;              // kpad / 64 (even)
     int32_t tiles_m, tiles_n, beta;
     int32_t exp_offset;          // C = acc * 2^(Ea + Eb + exp_offset)
-    const int *run_if;
-    int32_t run_val;
+    const int *run_a, *run_b;
 };
 
 __global__ __launch_bounds__(kWideThreads, 1) void gemm_i8_wide_kernel(const WideParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (p.run_if && *p.run_if != p.run_val) return;
+    if (stands_down(p.run_a, p.run_b)) return;
     int tm, tn;
     if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
 
@@ -248,8 +247,8 @@ int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
     p.tiles_n = (int32_t)ceil_div(a.N, kWideRows);
     p.beta = a.beta != 0.0f;
     p.exp_offset = -250 - a.mA - a.mB;
-    p.run_if = a.run_if;
-    p.run_val = a.run_val;
+    p.run_a = a.run_a;
+    p.run_b = a.run_b;
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     hipLaunchKernelGGL(gemm_i8_wide_kernel, dim3((unsigned)(ceil_div(tiles, 8) * 8)), dim3(kWideThreads), kWideLds, s, p);
     return launch_status();

@@ -49,8 +49,9 @@ struct GemmArgs {
     int64_t ldc;
     float beta;
     int32_t *P;                       // non-null: dump block partials instead of C
-    const int *run_if;                // non-null: every kernel of the launch does nothing unless *run_if == run_val
-    int32_t run_val;
+    // stand-by launches (behind the block-scaled kernel): non-null pointers to the headers of the two packed operands;
+    // every kernel of the launch does nothing unless one of them is marked out of range (word 0 == word 1)
+    const int *run_a, *run_b;
     int32_t wide;                     // 1: the caller asked for the 256 x 256-tile int8 kernel whatever the shape
 };
 // 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
@@ -68,12 +69,14 @@ bool gemm_wide_possible(const GemmArgs &a);
 bool gemm_wide_ok(const GemmArgs &a);
 int launch_gemm_wide(const GemmArgs &a, hipStream_t s);
 
-// gemm_mx.hip: the product on the block-scaled matrix instruction.  launch_gemm_mx packs both operands and
-// runs the product; the word at the start of its workspace equals *run_val afterwards when some exponent
-// could not be expressed, in which case it has not touched C and the int8 path has to run (run_if, run_val).
+// gemm_mx.hip: the product on the block-scaled matrix instruction.  A packed operand is a 256-byte header followed
+// by the limb planes; the header's first two words are equal when some exponent of the operand could not be
+// expressed, in which case the product kernel does not touch C and the int8 path has to run (run_a, run_b).
 bool gemm_mx_possible(const GemmArgs &a);   // shapes the kernel can address
 bool gemm_mx_ok(const GemmArgs &a);         // shapes and formats for which it is the faster choice
-size_t gemm_mx_workspace(const GemmArgs &a);
-int launch_gemm_mx(const GemmArgs &a, void *workspace, hipStream_t s, int32_t *run_val);
+size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits);   // header + planes, a multiple of 256
+// packs operand A (rows a.M) and / or operand B (rows a.N) of `a` in one launch; a null buffer skips that operand
+int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
+int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s);
 
 }  // namespace hbfp

@@ -63,6 +63,10 @@ def _load():
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
     lib.hbfp_gemm_select.argtypes = [T, T, vp, i64, ctypes.c_float, i32, vp, sz, vp]
+    lib.hbfp_pack_bytes.argtypes = [T, ctypes.POINTER(sz)]
+    lib.hbfp_pack.argtypes = [T, vp, sz, vp]
+    lib.hbfp_gemm_packed_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_packed.argtypes = [T, vp, T, vp, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
@@ -71,7 +75,8 @@ def _load():
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
     for name in ("hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
-                 "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
+                 "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
+                 "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
@@ -205,6 +210,41 @@ def gemm(a: BfpTensor, b: BfpTensor, out: Optional[torch.Tensor] = None, beta: f
     _check(_lib.hbfp_gemm_select(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(out), out.stride(0), beta, kernel,
                                  _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                                  _stream_ptr(stream)), "hbfp_gemm_select")
+    return out
+
+
+def pack_bytes(desc: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_pack_bytes(ctypes.byref(desc), ctypes.byref(n)), "hbfp_pack_bytes")
+    return int(n.value)
+
+
+def pack(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Limb planes of an encoded operand for gemm_packed (opaque bytes; pack again after encoding again)."""
+    n = pack_bytes(t.desc)
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=t.mant.device)
+    _check(_lib.hbfp_pack(ctypes.byref(t.desc), _dev_ptr(out), out.numel(), _stream_ptr(stream)), "hbfp_pack")
+    return out
+
+
+def gemm_packed_workspace(a: TensorDesc, b: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_packed_workspace(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)), "hbfp_gemm_packed_workspace")
+    return int(n.value)
+
+
+def gemm_packed(a: BfpTensor, packed_a: torch.Tensor, b: BfpTensor, packed_b: torch.Tensor,
+                out: Optional[torch.Tensor] = None, beta: float = 0.0, workspace: Optional[torch.Tensor] = None,
+                stream=None) -> torch.Tensor:
+    """C[M,N] (+)= A . B^T on the block-scaled kernel from operands packed beforehand."""
+    if out is None:
+        out = torch.empty((a.desc.rows, b.desc.rows), dtype=torch.float32, device=a.mant.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
+    workspace = _workspace(gemm_packed_workspace(a.desc, b.desc), out.device, workspace)
+    _check(_lib.hbfp_gemm_packed(ctypes.byref(a.desc), _dev_ptr(packed_a), ctypes.byref(b.desc), _dev_ptr(packed_b),
+                                 _dev_ptr(out), out.stride(0), beta, _dev_ptr(workspace),
+                                 0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_gemm_packed")
     return out
 
 

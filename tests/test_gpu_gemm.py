@@ -410,6 +410,132 @@ def test_scaled_kernel_in_a_replayed_graph(hb):
         assert rel_fro(out.cpu().numpy(), eager.cpu().numpy()) <= 2e-6
 
 
+def _oracle_product(A, B, fa, fb):
+    oa = ref.encode(A, fa[0], fa[1], fa[2], fa[3], fa[4])
+    ob = ref.encode(B, fb[0], fb[1], fb[2], fb[3], fb[4])
+    return ref.gemm(ref.decode(oa), ref.decode(ob))
+
+
+@pytest.mark.parametrize("m,blk,M,N,K", [(8, 32, 300, 270, 700), (4, 24, 130, 520, 330), (12, 64, 260, 140, 512), (9, 0, 70, 90, 200)])
+def test_packed_operands_two_step_product(hb, m, blk, M, N, K):
+    """hbfp_pack once, hbfp_gemm_packed many times: the weights' planes serve several activations, results
+    within the bound of the oracle and identical to the one-call block-scaled product."""
+    print(f"[case] packed m={m} blk={blk} M={M} N={N} K={K}", flush=True)
+    fa, fb = (1, blk, m, 0, 0), (blk, 1, m, 0, 0)
+    W = (_rand((K, N), 31 + m, 1) * 0.05).astype(np.float32)
+    tw = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(m, blk, 1))
+    pw = hb.pack(tw)
+    assert pw.numel() == hb.pack_bytes(tw.desc)
+    for seed in (1, 2, 3):
+        X = _rand((M, K), seed * 17 + m)
+        tx = hb.encode(torch.from_numpy(X).cuda(), 1, hb.make_format(m, 1, blk))
+        px = hb.pack(tx)
+        C = hb.gemm_packed(tx, px, tw, pw)
+        C1 = hb.gemm(tx, tw, kernel=SCALED)
+        torch.cuda.synchronize()
+        assert torch.equal(C, C1)
+        err = rel_fro(C.cpu().numpy(), _oracle_product(X, W, fa, fb))
+        print(f"        rel fro err = {err:.3e}", flush=True)
+        assert err <= TOL
+    # accumulate on top (beta = 1)
+    C0 = torch.from_numpy(_rand((M, N), 77, 1)).cuda()
+    C2 = hb.gemm_packed(tx, px, tw, pw, out=C0.clone(), beta=1.0)
+    torch.cuda.synchronize()
+    assert rel_fro(C2.cpu().numpy(), _oracle_product(X, W, fa, fb) + C0.cpu().numpy().astype(np.float64)) <= TOL
+
+
+def test_packed_operands_outside_the_scale_range_and_repacking(hb):
+    """A packed operand with a block below the range of the scale bytes: hbfp_gemm_packed still returns the product
+    (int8 kernels inside the same call), for either operand; packing in-range data into the same buffer afterwards
+    takes the block-scaled kernel again."""
+    m, blk = 8, 32
+    fa, fb = (1, blk, m, 0, 0), (blk, 1, m, 0, 0)
+    A, B = _rand((150, 256), 5), _rand((256, 140), 6)
+    A2 = (A.astype(np.float64) * 2.0 ** -124).astype(np.float32)
+    B2 = (B.astype(np.float64) * 2.0 ** 100).astype(np.float32)
+    B3 = B.copy()
+    B3[32:64, 9] = (B[32:64, 9].astype(np.float64) * 2.0 ** -126).astype(np.float32)
+
+    def enc(X, side):
+        return hb.encode(torch.from_numpy(X).cuda(), side, hb.make_format(m, 1, blk) if side else hb.make_format(m, blk, 1))
+
+    ta, ta2, tb, tb2, tb3 = enc(A, 1), enc(A2, 1), enc(B, 0), enc(B2, 0), enc(B3, 0)
+    pa, pb = hb.pack(ta), hb.pack(tb)
+    for name, (x, px, X), (w, pw, W) in [
+        ("A out of range", (ta2, hb.pack(ta2), A2), (tb2, hb.pack(tb2), B2)),
+        ("B out of range", (ta, pa, A), (tb3, hb.pack(tb3), B3)),
+        ("both in range", (ta, pa, A), (tb, pb, B)),
+    ]:
+        print(f"[case] packed, {name}", flush=True)
+        C = hb.gemm_packed(x, px, w, pw)
+        torch.cuda.synchronize()
+        assert rel_fro(C.cpu().numpy(), _oracle_product(X, W, fa, fb)) <= TOL
+    # the same buffer packed again: out of range, then in range
+    buf = torch.empty(hb.pack_bytes(tb.desc), dtype=torch.uint8, device="cuda")
+    for t, W in [(tb3, B3), (tb, B), (tb3, B3), (tb, B)]:
+        hb.pack(t, out=buf)
+        C = hb.gemm_packed(ta, pa, t, buf)
+        torch.cuda.synchronize()
+        assert rel_fro(C.cpu().numpy(), _oracle_product(A, W, fa, fb)) <= TOL
+
+
+def test_packed_product_in_a_replayed_graph(hb):
+    """Weights packed outside, activations encoded and packed inside a captured graph; every replay (new activations
+    in the same buffers, eager work and synchronisation between replays) must equal the eager result.  One replay
+    has activations outside the scale range, the next is in range again."""
+    m, blk, M, N, K = 8, 32, 260, 300, 640
+    rng = np.random.default_rng(4)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
+    tw = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(m, blk, 1))
+    pw = hb.pack(tw)
+    x = torch.zeros((M, K), device="cuda")
+    fmt = hb.make_format(m, 1, blk)
+    tx = hb.encode(x, 1, fmt)
+    px = torch.empty(hb.pack_bytes(tx.desc), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(hb.gemm_packed_workspace(tx.desc, tw.desc), 256), dtype=torch.uint8, device="cuda")
+    out = torch.empty((M, N), device="cuda")
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        hb.encode(x, 1, fmt, out=tx, stream=stream)
+        hb.pack(tx, out=px, stream=stream)
+        hb.gemm_packed(tx, px, tw, pw, out=out, workspace=ws, stream=stream)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            hb.encode(x, 1, fmt, out=tx, stream=stream)
+            hb.pack(tx, out=px, stream=stream)
+            hb.gemm_packed(tx, px, tw, pw, out=out, workspace=ws, stream=stream)
+    for i, scale in enumerate([1.0, 2.0 ** -124, 1.0, 3.0]):
+        X = (rng.standard_normal((M, K)) * scale).astype(np.float32)
+        x.copy_(torch.from_numpy(X).cuda())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        eager = hb.gemm(hb.encode(x, 1, fmt), tw, kernel=SCALED)
+        torch.cuda.synchronize()
+        print(f"[case] packed graph replay {i} scale={scale}", flush=True)
+        assert rel_fro(got.cpu().numpy(), eager.cpu().numpy()) <= 2e-6
+        assert rel_fro(got.cpu().numpy(), _oracle_product(X, W, (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
+
+
+def test_pack_argument_checks(hb):
+    import ctypes
+    t = hb.encode(torch.randn((64, 128), device="cuda"), 1, hb.make_format(8, 1, 32))
+    n = hb.pack_bytes(t.desc)
+    assert n % 256 == 0 and n > 64 * 128
+    small = torch.empty(n - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hb.HbfpError):
+        hb.pack(t, out=small)
+    t16 = hb.encode(torch.randn((64, 128), device="cuda"), 1, hb.make_format(16, 1, 32))
+    with pytest.raises(hb.HbfpError):
+        hb.pack_bytes(t16.desc)
+    p = hb.pack(t)
+    with pytest.raises(hb.HbfpError):                               # mixed mantissa classes
+        t12 = hb.encode(torch.randn((128, 32), device="cuda"), 0, hb.make_format(12, 32, 1))
+        hb.gemm_packed(t, p, t12, hb.pack(t12))
+
+
 @pytest.mark.parametrize("case", range(24))
 def test_scaled_kernel_random_shapes(hb, case):
     """Seeded random shapes (down to a single row, column or contraction element), block lengths, mantissa widths of
