@@ -22,7 +22,13 @@ struct DecParams {
     int32_t chunks, lpr_log2, nseg, vec_ok, gp_log2;
 };
 
-// row path: k is contiguous in the destination; each lane turns 8 stored mantissas into 8 floats
+// row path: k is contiguous in the destination.  A lane turns 4 stored mantissas into one 16-byte store, so a wave
+// writes 1 KB of consecutive floats per instruction; it handles kUnroll such chunks per pass, all of their loads
+// issued before the first conversion (chunks that do not exist read chunk 0 of the row and store nothing).
+// The output is written once and not read again by this kernel: streaming stores.
+constexpr int kUnroll = 4;
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 template <bool WIDE, bool AXPY>
 __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
     const int t = threadIdx.x;
@@ -30,58 +36,77 @@ __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
     const int64_t row = (int64_t)blockIdx.x * (kThreads >> p.lpr_log2) + (t >> p.lpr_log2);
     if (row >= p.R) return;
     const int lr = t & (lpr - 1);
-    for (int seg = blockIdx.y; seg < p.nseg; seg += gridDim.y) {
-        const int cl = seg * lpr + lr;
-        if (cl >= p.chunks) continue;
-        const int blk = cl >> p.gp_log2, j = cl & ((1 << p.gp_log2) - 1);
-        if (blk >= p.nblk) continue;
-        const int64_t k0 = (int64_t)blk * p.kblock;
-        const int64_t blen = (p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock;
-        const int64_t left = blen - 8 * j;
-        if (left <= 0) continue;
-        const int cnt = left >= 8 ? 8 : (int)left;
-        int q[8];
-        if (!WIDE) {
-            const uint2 d = *reinterpret_cast<const uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8);
+    const uint8_t *mrow = p.mant + row * p.kpad * (WIDE ? 2 : 1);
+    const uint8_t *erow = p.exps + row * p.exp_ld;
+    for (int seg0 = blockIdx.y * kUnroll; seg0 < p.nseg; seg0 += gridDim.y * kUnroll) {
+        uint32_t raw[kUnroll][2];
+        int ue[kUnroll], cnt[kUnroll];
+        int64_t at[kUnroll];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                q[e] = (int)(int8_t)(d.x >> (8 * e));
-                q[4 + e] = (int)(int8_t)(d.y >> (8 * e));
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t cl = (int64_t)(seg0 + u) * lpr + lr;
+            const int64_t blk = cl >> p.gp_log2;
+            const int j = (int)(cl & ((1 << p.gp_log2) - 1));
+            int c = 0;
+            if (seg0 + u < p.nseg && cl < p.chunks && blk < p.nblk) {
+                const int64_t k0 = blk * p.kblock;
+                const int64_t left = ((p.K - k0 < p.kblock) ? (p.K - k0) : p.kblock) - 4 * j;
+                c = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
             }
-        } else {
-            const uint4 d = *reinterpret_cast<const uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2);
-            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                q[2 * e] = (int)(int16_t)(w[e] & 0xffffu);
-                q[2 * e + 1] = (int)(int16_t)(w[e] >> 16);
+            cnt[u] = c;
+            at[u] = blk * p.kblock + 4 * j;
+            const int64_t cs = c ? cl : 0, bs = c ? blk : 0;
+            if (!WIDE) {
+                raw[u][0] = *reinterpret_cast<const uint32_t *>(mrow + cs * 4);
+                raw[u][1] = 0;
+            } else {
+                const uint2 d = *reinterpret_cast<const uint2 *>(mrow + cs * 8);
+                raw[u][0] = d.x;
+                raw[u][1] = d.y;
             }
+            ue[u] = (int)erow[bs] - 125 - p.m;
         }
-        const int ue = (int)p.exps[row * p.exp_ld + blk] - 125 - p.m;
-        float f[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = __builtin_amdgcn_ldexpf((float)q[e], ue);
-        float *o = p.dst + row * p.ld + k0 + 8 * j;
-        if (AXPY) {
-            const float *g = p.delta + row * p.ldd + k0 + 8 * j;
-            if (cnt == 8 && p.vec_ok) {
-                const float4 g0 = *reinterpret_cast<const float4 *>(g), g1 = *reinterpret_cast<const float4 *>(g + 4);
-                const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        for (int u = 0; u < kUnroll; ++u) {
+            if (cnt[u] == 0) continue;
+            int q[4];
+            if (!WIDE) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) f[e] = fmaf(p.alpha, gv[e], f[e]);
+                for (int e = 0; e < 4; ++e) q[e] = (int)(int8_t)(raw[u][0] >> (8 * e));
+            } else {
+                q[0] = (int)(int16_t)(raw[u][0] & 0xffffu);
+                q[1] = (int)(int16_t)(raw[u][0] >> 16);
+                q[2] = (int)(int16_t)(raw[u][1] & 0xffffu);
+                q[3] = (int)(int16_t)(raw[u][1] >> 16);
+            }
+            float f[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = __builtin_amdgcn_ldexpf((float)q[e], ue[u]);
+            float *o = p.dst + row * p.ld + at[u];
+            const bool vec = cnt[u] == 4 && p.vec_ok;
+            if (AXPY) {
+                const float *g = p.delta + row * p.ldd + at[u];
+                if (vec) {
+                    const float4 g0 = *reinterpret_cast<const float4 *>(g);
+                    f[0] = fmaf(p.alpha, g0.x, f[0]);
+                    f[1] = fmaf(p.alpha, g0.y, f[1]);
+                    f[2] = fmaf(p.alpha, g0.z, f[2]);
+                    f[3] = fmaf(p.alpha, g0.w, f[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < cnt[u]) f[e] = fmaf(p.alpha, g[e], f[e]);
+                }
+            }
+            if (vec) {
+                v4f o4;
+                o4.x = f[0]; o4.y = f[1]; o4.z = f[2]; o4.w = f[3];
+                __builtin_nontemporal_store(o4, reinterpret_cast<v4f *>(o));
             } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (e < cnt) f[e] = fmaf(p.alpha, g[e], f[e]);
+                for (int e = 0; e < 4; ++e)
+                    if (e < cnt[u]) o[e] = f[e];
             }
-        }
-        if (cnt == 8 && p.vec_ok) {
-            *reinterpret_cast<float4 *>(o) = make_float4(f[0], f[1], f[2], f[3]);
-            *reinterpret_cast<float4 *>(o + 4) = make_float4(f[4], f[5], f[6], f[7]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (e < cnt) o[e] = f[e];
         }
     }
 }
@@ -130,20 +155,21 @@ int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float
     p.m = t->mant_bits;
     p.chunks = p.lpr_log2 = p.nseg = p.vec_ok = p.gp_log2 = 0;
     const bool wide = t->mant_bits > 8;
-    const bool row_path = t->contract_axis == 1 && t->kblock_pad <= 128 && t->kpad / 8 <= 0x7fffffff &&
+    const bool row_path = t->contract_axis == 1 && t->kblock_pad <= 128 && t->kpad / 4 <= 0x7fffffff &&
                           t->nblk <= 0x7fffffff;
     if (row_path) {
-        p.chunks = (int32_t)(t->kpad / 8);
+        p.chunks = (int32_t)(t->kpad / 4);
         int l2 = 0;
         while (((int64_t)1 << l2) < p.chunks) ++l2;
         l2 = l2 < 4 ? 4 : (l2 > 8 ? 8 : l2);
         p.lpr_log2 = l2;
         p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
-        p.gp_log2 = t->kblock_pad == 32 ? 2 : t->kblock_pad == 64 ? 3 : 4;
+        p.gp_log2 = t->kblock_pad == 32 ? 3 : t->kblock_pad == 64 ? 4 : 5;
         p.vec_ok = (((uintptr_t)dst & 15) == 0 && (ld % 4) == 0 && (t->kblock % 4) == 0) ? 1 : 0;
         if (axpy && (((uintptr_t)delta & 15) != 0 || (ldd % 4) != 0)) p.vec_ok = 0;
         const int64_t gx = ceil_div(t->rows, (int64_t)(kThreads >> l2));
-        int64_t gy = p.nseg > 65535 ? 65535 : p.nseg;
+        int64_t gy = ceil_div(p.nseg, kUnroll);
+        gy = gy > 65535 ? 65535 : gy;
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
         const dim3 grid((unsigned)gx, (unsigned)gy);
         if (axpy) {

@@ -81,26 +81,37 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
         rows_here = mine <= 0 ? 0 : (mine < RPL ? (int)mine : RPL);
     }
 
-    float v[RPL][4];
-    int we = 0;
-    if (p.w_mant && col_ok && rows_here > 0) we = (int)p.w_exps[row0 * p.w_expld + tc] - 125 - p.w_m;
+    // Every load is issued before the first value is used: rows that do not exist read the lane's first row again
+    // (lanes without any element read the first element of the matrix) and are zeroed afterwards, so no load hides
+    // behind a branch and all of a lane's rows are in flight together.
+    const bool any = col_ok && rows_here > 0;
+    const float *sbase = any ? p.src + row0 * p.ld + col0 : p.src;
+    float4 d[RPL];
 #pragma unroll
-    for (int r = 0; r < RPL; ++r) {
-        v[r][0] = v[r][1] = v[r][2] = v[r][3] = 0.0f;
-        if (r < rows_here && col_ok) {
-            const float4 d = *reinterpret_cast<const float4 *>(p.src + (row0 + r) * p.ld + col0);
-            if (p.w_mant) {
-                const uint32_t *wp = reinterpret_cast<const uint32_t *>(p.w_mant + ((row0 + r) * p.w_kpad + tc * 32 + 4 * j) * 2);
-                const uint32_t w01 = wp[0], w23 = wp[1];
-                v[r][0] = fmaf(p.alpha, d.x, __builtin_amdgcn_ldexpf((float)(int16_t)(w01 & 0xffffu), we));
-                v[r][1] = fmaf(p.alpha, d.y, __builtin_amdgcn_ldexpf((float)(int16_t)(w01 >> 16), we));
-                v[r][2] = fmaf(p.alpha, d.z, __builtin_amdgcn_ldexpf((float)(int16_t)(w23 & 0xffffu), we));
-                v[r][3] = fmaf(p.alpha, d.w, __builtin_amdgcn_ldexpf((float)(int16_t)(w23 >> 16), we));
-            } else {
-                v[r][0] = d.x; v[r][1] = d.y; v[r][2] = d.z; v[r][3] = d.w;
-            }
+    for (int r = 0; r < RPL; ++r) d[r] = *reinterpret_cast<const float4 *>(sbase + (r < rows_here ? r : 0) * p.ld);
+    float v[RPL][4];
+    if (p.w_mant) {
+        const int we = any ? (int)p.w_exps[row0 * p.w_expld + tc] - 125 - p.w_m : 0;
+        const uint8_t *wbase = any ? p.w_mant + (row0 * p.w_kpad + tc * 32 + 4 * j) * 2 : p.w_mant;
+        uint2 w[RPL];
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) w[r] = *reinterpret_cast<const uint2 *>(wbase + (r < rows_here ? r : 0) * p.w_kpad * 2);
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) {
+            v[r][0] = fmaf(p.alpha, d[r].x, __builtin_amdgcn_ldexpf((float)(int16_t)(w[r].x & 0xffffu), we));
+            v[r][1] = fmaf(p.alpha, d[r].y, __builtin_amdgcn_ldexpf((float)(int16_t)(w[r].x >> 16), we));
+            v[r][2] = fmaf(p.alpha, d[r].z, __builtin_amdgcn_ldexpf((float)(int16_t)(w[r].y & 0xffffu), we));
+            v[r][3] = fmaf(p.alpha, d[r].w, __builtin_amdgcn_ldexpf((float)(int16_t)(w[r].y >> 16), we));
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) {
+            v[r][0] = d[r].x; v[r][1] = d[r].y; v[r][2] = d[r].z; v[r][3] = d[r].w;
         }
     }
+#pragma unroll
+    for (int r = 0; r < RPL; ++r)
+        if (!(any && r < rows_here)) v[r][0] = v[r][1] = v[r][2] = v[r][3] = 0.0f;
     uint32_t amax = 0;
 #pragma unroll
     for (int r = 0; r < RPL; ++r)
