@@ -129,8 +129,9 @@ int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_a
 /*
  * hbfp_encode_workspace (host only): bytes of scratch hbfp_encode needs for this
  * plan: 0 for blocks of at most 64 elements along k and at most 64 across it (128 and
- * 1024 when k is the contiguous source axis); otherwise 4 bytes per exponent block,
- * rounded up to 256.
+ * 32 when k is the contiguous source axis); otherwise (long blocks, one exponent per row
+ * or column, large tiles, one exponent for the matrix) the conversion takes two passes
+ * and needs 4 bytes per exponent block, rounded up to 256.
  */
 int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes);
 

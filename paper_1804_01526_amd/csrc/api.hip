@@ -81,7 +81,7 @@ int check_tensor(const hbfp_tensor *t, bool need_ptrs) {
 
 // Block shapes the single-pass kernels cover; everything else takes the max pass + quantise pass.
 bool needs_tile_pass(const hbfp_tensor &t) {
-    if (t.contract_axis == 1) return t.kblock > 128 || t.rblock > 1024;
+    if (t.contract_axis == 1) return t.kblock > 128 || t.rblock > 32;
     return t.kblock > 64 || t.rblock > 64;
 }
 

@@ -44,21 +44,23 @@ __device__ __forceinline__ int quant_rne(float x, int neg_unit_exp) {
     return __float_as_int(t) - 0x4B400000;
 }
 
-// Stochastic rounding in integer arithmetic on the bit pattern.  shbase = 25 - m + Eb.
+// Stochastic rounding in integer arithmetic on the bit pattern.  shbase = 25 - m + Eb, so the shift
+// sh = shbase - (element's exponent) is at least 25 - m >= 9.  The definition
+//     q = (sig + (h >> (32 - sh))) >> sh   (sh <= 31),   carry of sig + h   (sh = 32),   0   (sh > 32)
+// equals bits 32 and up of (sig << (32 - sh)) + h for every sh <= 32: the bits of h dropped before the
+// sum of the definition are a fraction below one unit of sig and cannot change the floor.  So one
+// add-with-carry serves all cases; a zero (padding) value always gives 0.
 __device__ __forceinline__ int quant_sr(uint32_t bits, int shbase, uint32_t h) {
     const uint32_t a = bits & 0x7fffffffu;
     const uint32_t be = a >> 23;
-    const uint32_t sig = (a & 0x7fffffu) | (be ? 0x800000u : 0u);
+    uint32_t sig = be ? ((a & 0x7fffffu) | 0x800000u) : a;
     const int sh = shbase - (int)(be ? be : 1u);
-    uint32_t q;
-    if (sh > 32) {
-        q = 0;
-    } else if (sh == 32) {
-        q = (sig + h) < h ? 1u : 0u;  // carry out of 32 bits
-    } else {
-        q = (sig + (h >> (32 - sh))) >> sh;
-    }
-    return (bits >> 31) ? -(int)q : (int)q;
+    sig = sh > 32 ? 0u : sig;
+    const uint32_t lo = sig << ((32 - sh) & 31);
+    const uint32_t hi = (sig >> 8) >> ((sh - 8) & 31);
+    const uint32_t q = hi + ((lo + h) < h ? 1u : 0u);
+    const uint32_t sgn = (uint32_t)((int32_t)bits >> 31);
+    return (int)((q ^ sgn) - sgn);
 }
 
 template <int ROUND>

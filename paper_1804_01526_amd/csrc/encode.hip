@@ -53,6 +53,11 @@ struct RowParams {
     int32_t nseg;       // segments per row = ceil(chunks / lanes-per-row)
     int32_t vec_ok;     // 16-byte vector loads are aligned
     uint32_t s0, s1;
+    // GP = 0 (second pass of the two-pass conversion): the largest magnitude of every exponent block has been
+    // computed already, table[(row / rblock) * nblk + block]; a stored block is gp chunks long
+    const uint32_t *table;
+    int64_t rblock;
+    int32_t gp;
 };
 
 template <int GP, bool WIDE, int ROUND, int U>
@@ -83,7 +88,8 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             cl[u] = (int)(g - (uint64_t)row * (uint64_t)p.chunks);
         }
         rows[u] = in ? row : -1;
-        const int blk = cl[u] / GP, j = cl[u] % GP;
+        const int gp = GP ? GP : p.gp;
+        const int blk = cl[u] / gp, j = cl[u] % gp;
         int cnt = 0;
         if (in && blk < p.nblk) {
             const int64_t k0 = (int64_t)blk * p.kblock;
@@ -105,12 +111,17 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int blk = cl[u] / GP, j = cl[u] % GP;
+        const int gp = GP ? GP : p.gp;
+        const int blk = cl[u] / gp, j = cl[u] % gp;
         const int64_t row = rows[u];
         uint32_t amax = 0;
+        if (GP) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
-        amax = group_max<GP>(amax);
+            for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
+            amax = group_max<(GP ? GP : 4)>(amax);
+        } else if (row >= 0 && blk < p.nblk) {
+            amax = p.table[(int64_t)((uint32_t)row / (uint32_t)p.rblock) * p.nblk + blk];     // rows fit 31 bits here
+        }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
         int q[8];
         const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
@@ -118,7 +129,6 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         for (int e = 0; e < 8; ++e) {
             const uint64_t idx = idx0 + e;
             q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
-            if (ROUND && e >= n[u]) q[e] = 0;
         }
         if (row >= 0) {
             if (!WIDE) {
@@ -263,12 +273,18 @@ struct ColParams {
     int32_t lanes;      // lanes of a wave that carry operand rows: the largest multiple of rblock <= 64
     uint32_t row_groups;   // workgroups per group of blocks (the grid is flat: block group = blockIdx.x / row_groups)
     uint32_t s0, s1;
+    // TABLE (second pass of the two-pass conversion): the largest magnitude of every exponent block has been computed
+    // already, table[block * ntc + row / rblock_t]; the kernel then walks stored pieces of KBP elements, spb of which
+    // make up one stored block (nblk, kblock and exp_ld still describe the exponent blocks)
+    const uint32_t *table;
+    int64_t rblock_t, ntc;
+    int32_t spb;
 };
 
 constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
 constexpr int kColStride = 528;     // padded LDS row stride: 16-byte writes of 16 lanes hit 16 bank groups
 
-template <int KBP, bool WIDE, int ROUND>
+template <int KBP, bool WIDE, int ROUND, bool TABLE>
 __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     constexpr int ESZ = WIDE ? 2 : 1;
     constexpr int NBT = kColRowBytes / (KBP * ESZ);  // exponent blocks per tile row: 16, 8, 8 or 4
@@ -283,20 +299,26 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
 
     for (int bi = wave; bi < NBT; bi += 4) {
-        const int64_t blk = blk0 + bi;
+        const int64_t piece = blk0 + bi;                                  // stored piece of KBP elements
+        const int64_t blk = TABLE ? piece / p.spb : piece;                // exponent block
+        const int sub = TABLE ? (int)(piece % p.spb) * KBP : 0;           // the piece's offset in its block
         int blen = 0;
         if (blk < p.nblk) {
-            const int64_t left = p.K - blk * p.kblock;
-            blen = left < p.kblock ? (int)left : p.kblock;
+            int64_t left = p.K - blk * p.kblock;
+            left = (left < p.kblock ? left : p.kblock) - sub;
+            blen = left < 0 ? 0 : (left < KBP ? (int)left : KBP);
         }
-        const float *s = p.src + blk * p.kblock * p.ld + (r_ok ? r : 0);
+        const int64_t kfirst = (blk < p.nblk ? blk : 0) * p.kblock + (blen ? sub : 0);
+        const float *s = p.src + kfirst * p.ld + (r_ok ? r : 0);
         float v[KBP];
 #pragma unroll
         for (int kk = 0; kk < KBP; ++kk) v[kk] = (kk < blen && r_ok) ? s[(int64_t)kk * p.ld] : 0.0f;
         uint32_t amax = 0;
 #pragma unroll
         for (int kk = 0; kk < KBP; ++kk) amax = max(amax, __float_as_uint(v[kk]) & 0x7fffffffu);
-        if (p.rblock > 1) {
+        if (TABLE) {
+            amax = (blk < p.nblk && r_ok) ? p.table[blk * p.ntc + (uint32_t)r / (uint32_t)p.rblock_t] : 0u;   // rows fit 31 bits here
+        } else if (p.rblock > 1) {
             // 2-D tile: the maximum also runs over the rblock neighbouring operand rows (lanes of this wave)
             lane_amax[wave][lane] = amax;
             __builtin_amdgcn_wave_barrier();
@@ -304,16 +326,16 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
             __builtin_amdgcn_wave_barrier();
         }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
-        etile[lane * NBT + bi] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+        if (!TABLE) etile[lane * NBT + bi] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+        else if (sub == 0 && r_ok && blk < p.nblk) p.exps[r * p.exp_ld + blk] = (uint8_t)Eb;
         uint8_t *out = tile + lane * kColStride + bi * KBP * ESZ;
 #pragma unroll
         for (int kk = 0; kk < KBP; kk += 8) {
             int q[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint64_t idx = (uint64_t)(blk * p.kblock + kk + e) * (uint64_t)p.src_cols + (uint64_t)r;
+                const uint64_t idx = (uint64_t)(kfirst + kk + e) * (uint64_t)p.src_cols + (uint64_t)r;
                 q[e] = quantise<ROUND>(v[kk + e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
-                if (ROUND && kk + e >= blen) q[e] = 0;
             }
             if (!WIDE) {
                 uint2 o;
@@ -345,7 +367,10 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
             *reinterpret_cast<uint4 *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16) = d;
         }
     }
-    if (t < 64 && r_ok) {
+    if (TABLE) {
+        if (blk0 == 0 && t < 64 && r_ok)                                 // exponent bytes past the last block
+            for (int64_t b = p.nblk; b < p.exp_ld; ++b) p.exps[r * p.exp_ld + b] = 1;
+    } else if (t < 64 && r_ok) {
 #pragma unroll
         for (int w = 0; w < NBT / 4; ++w) {
             const int64_t b = blk0 + 4 * w;
@@ -358,87 +383,95 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 
 template <int KBP>
 void launch_col_k(const ColParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
-    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 0>), grid, dim3(kThreads), 0, s, p);
-    else if (!wide) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 1>), grid, dim3(kThreads), 0, s, p);
-    else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, true, 0>), grid, dim3(kThreads), 0, s, p);
-    else hipLaunchKernelGGL((enc_col_kernel<KBP, true, 1>), grid, dim3(kThreads), 0, s, p);
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 0, false>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 1, false>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, true, 0, false>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_col_kernel<KBP, true, 1, false>), grid, dim3(kThreads), 0, s, p);
+}
+
+void launch_col_table(const ColParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_col_kernel<32, false, 0, true>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_col_kernel<32, false, 1, true>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<32, true, 0, true>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_col_kernel<32, true, 1, true>), grid, dim3(kThreads), 0, s, p);
 }
 
 // ------------------------------------------------------------------------------------------
-// tile path: any block shape
+// two-pass path: any block shape
 struct TileParams {
     const float *src;
-    uint8_t *mant;
-    uint8_t *exps;
     uint32_t *tile_amax;   // [nbr][nbc] largest magnitude bit pattern per exponent block
     int64_t ld, src_rows, src_cols, br, bc, nbr, nbc;
-    int64_t R, K, kblock, kbp, nblk, kpad, exp_ld, nb_stored;
-    int32_t axis, m;
-    uint32_t s0, s1;
 };
 
 __global__ __launch_bounds__(kThreads) void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) p[i] = v;
 }
 
-// one workgroup per (source row, 1024-column span); the max over unsigned bit patterns is
-// order independent, so the atomics leave a deterministic result
-__global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p) {
-    for (int64_t r = blockIdx.y; r < p.src_rows; r += gridDim.y) {
-        const int64_t tr = r / p.br;
-        const float *s = p.src + r * p.ld;
-        const int64_t c0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
-        uint32_t a[4];
-        int64_t tc[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int64_t c = c0 + e;
-            a[e] = c < p.src_cols ? (__float_as_uint(s[c]) & 0x7fffffffu) : 0u;
-            tc[e] = (c < p.src_cols ? c : p.src_cols - 1) / p.bc;
-        }
-        if (c0 < p.src_cols) {
-            // merge neighbours that fall into the same block before touching memory
-            uint32_t run = a[0];
-#pragma unroll
-            for (int e = 1; e < 4; ++e) {
-                if (tc[e] == tc[e - 1]) {
-                    run = max(run, a[e]);
-                } else {
-                    if (run) atomicMax(p.tile_amax + tr * p.nbc + tc[e - 1], run);
-                    run = a[e];
-                }
-            }
-            if (run) atomicMax(p.tile_amax + tr * p.nbc + tc[3], run);
-        }
-    }
-}
+// First pass of the two-pass conversion: the largest magnitude of every exponent block, any block shape.
+// A workgroup covers kAmaxRows source rows x 1024 columns; a lane keeps the maxima of its 4 columns in
+// registers down the rows of one row of blocks.  When all columns of a wave fall into one block the wave
+// combines its lanes first and touches the table once; the max over unsigned bit patterns is order
+// independent, so the atomics leave a deterministic result.
+constexpr int kAmaxRows = 64;
 
-template <bool WIDE, int ROUND>
-__global__ __launch_bounds__(kThreads) void tile_quant_kernel(const TileParams p) {
-    const int64_t kp = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // stored position along k
-    if (kp >= p.kpad) return;
-    const int64_t blk = kp / p.kbp, kk = kp % p.kbp;
-    for (int64_t r = blockIdx.y; r < p.R; r += gridDim.y) {
-        int q = 0;
-        uint32_t Eb = 1;
-        if (blk < p.nblk) {
-            const int64_t kfirst = blk * p.kblock;
-            const int64_t sr0 = p.axis == 1 ? r : kfirst, sc0 = p.axis == 1 ? kfirst : r;
-            const uint32_t amax = p.tile_amax[(sr0 / p.br) * p.nbc + (sc0 / p.bc)];
-            Eb = block_exponent<ROUND>(amax, p.m);
-            const int64_t k = kfirst + kk;
-            if (kk < p.kblock && k < p.K) {
-                const int64_t sr = p.axis == 1 ? r : k, sc = p.axis == 1 ? k : r;
-                const float x = p.src[sr * p.ld + sc];
-                const uint64_t idx = (uint64_t)sr * (uint64_t)p.src_cols + (uint64_t)sc;
-                q = quantise<ROUND>(x, Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+__global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p, int vec_ok) {
+    const int64_t c0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    int64_t tc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tc[e] = ((c0 + e < p.src_cols) ? c0 + e : p.src_cols - 1) / p.bc;
+    const int ncol = c0 >= p.src_cols ? 0 : (p.src_cols - c0 >= 4 ? 4 : (int)(p.src_cols - c0));
+    const int64_t wave_tc = __shfl(tc[0], 0);
+    const bool wave_one = __all(tc[0] == wave_tc && tc[3] == wave_tc);
+    for (int64_t r0 = (int64_t)blockIdx.y * kAmaxRows; r0 < p.src_rows; r0 += (int64_t)gridDim.y * kAmaxRows) {
+        const int64_t r1 = r0 + kAmaxRows < p.src_rows ? r0 + kAmaxRows : p.src_rows;
+        int64_t r = r0;
+        int64_t tr = r0 / p.br, tile_end = (tr + 1) * p.br;              // one division per strip, none per row
+        while (r < r1) {
+            const int64_t rend = tile_end < r1 ? tile_end : r1;
+            uint32_t a[4] = {0u, 0u, 0u, 0u};
+            if (ncol == 4 && vec_ok) {
+#pragma unroll 8
+                for (int64_t rr = r; rr < rend; ++rr) {
+                    const float4 d = *reinterpret_cast<const float4 *>(p.src + rr * p.ld + c0);
+                    a[0] = max(a[0], __float_as_uint(d.x) & 0x7fffffffu);
+                    a[1] = max(a[1], __float_as_uint(d.y) & 0x7fffffffu);
+                    a[2] = max(a[2], __float_as_uint(d.z) & 0x7fffffffu);
+                    a[3] = max(a[3], __float_as_uint(d.w) & 0x7fffffffu);
+                }
+            } else {
+                for (int64_t rr = r; rr < rend; ++rr)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < ncol) a[e] = max(a[e], __float_as_uint(p.src[rr * p.ld + c0 + e]) & 0x7fffffffu);
+            }
+            r = rend;
+            uint32_t *row_of_table = p.tile_amax + tr * p.nbc;
+            if (rend == tile_end) {
+                ++tr;
+                tile_end += p.br;
+            }
+            if (wave_one) {
+                uint32_t v = max(max(a[0], a[1]), max(a[2], a[3]));
+                v = group_max<16>(v);
+                v = max(v, (uint32_t)__shfl_xor((int)v, 16));
+                v = max(v, (uint32_t)__shfl_xor((int)v, 32));
+                if ((threadIdx.x & 63) == 0 && v) atomicMax(row_of_table + wave_tc, v);
+            } else if (ncol) {
+                // merge neighbours that fall into the same block before touching memory
+                uint32_t run = a[0];
+#pragma unroll
+                for (int e = 1; e < 4; ++e) {
+                    if (tc[e] == tc[e - 1]) {
+                        run = max(run, a[e]);
+                    } else {
+                        if (run) atomicMax(row_of_table + tc[e - 1], run);
+                        run = a[e];
+                    }
+                }
+                if (run) atomicMax(row_of_table + tc[3], run);
             }
         }
-        if (!WIDE) reinterpret_cast<int8_t *>(p.mant)[r * p.kpad + kp] = (int8_t)q;
-        else reinterpret_cast<int16_t *>(p.mant)[r * p.kpad + kp] = (int16_t)q;
-        if (kk == 0) p.exps[r * p.exp_ld + blk] = (uint8_t)Eb;
-        if (kp == 0)
-            for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) p.exps[r * p.exp_ld + b] = 1;
     }
 }
 
@@ -473,6 +506,9 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
+    p.table = nullptr;
+    p.rblock = 1;
+    p.gp = 0;
     if (g.rblock > 1) {
         p.nseg = (int32_t)ceil_div(p.chunks, kThreads);
         const int64_t gx = ceil_div(g.R, g.rblock);
@@ -518,6 +554,10 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
     if (g.rblock < 1 || g.rblock > 64) return HBFP_ERR_FORMAT;
     p.rblock = (int32_t)g.rblock;
     p.lanes = (int32_t)((64 / g.rblock) * g.rblock);
+    p.table = nullptr;
+    p.rblock_t = 1;
+    p.ntc = 0;
+    p.spb = 1;
     const bool wide = g.m > 8;
     const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
     // cover every stored block and every exponent byte up to exp_ld
@@ -532,52 +572,92 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
     return launch_status();
 }
 
+// Two passes for block shapes the single-pass kernels do not cover (long blocks, one exponent per row or column,
+// large 2-D tiles, one exponent for the whole matrix): the largest magnitude of every block into a table, then the
+// row / column kernels quantise with the exponents of the table (the second read mostly hits the last-level cache).
 int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
                           uint32_t *tile_amax, hipStream_t s) {
-    TileParams p;
-    p.src = src;
-    p.mant = (uint8_t *)mant;
-    p.exps = exps;
-    p.tile_amax = tile_amax;
-    p.ld = g.ld;
-    p.src_rows = g.src_rows;
-    p.src_cols = g.src_cols;
-    p.br = g.br;
-    p.bc = g.bc;
-    p.nbr = g.nbr;
-    p.nbc = g.nbc;
-    p.R = g.R;
-    p.K = g.K;
-    p.kblock = g.kblock;
-    p.kbp = g.kbp;
-    p.nblk = g.nblk;
-    p.kpad = g.kpad;
-    p.exp_ld = g.exp_ld;
-    p.nb_stored = g.kpad / g.kbp;
-    p.axis = g.axis;
-    p.m = g.m;
-    p.s0 = g.seed_lo;
-    p.s1 = g.seed_hi;
-    const int64_t ntile = g.nbr * g.nbc;
-    int64_t fb = ceil_div(ntile, kThreads);
-    if (fb > 4096) fb = 4096;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)fb), dim3(kThreads), 0, s, tile_amax, ntile, 0u);
+    const bool wide = g.m > 8;
     {
+        TileParams p;
+        p.src = src;
+        p.tile_amax = tile_amax;
+        p.ld = g.ld;
+        p.src_rows = g.src_rows;
+        p.src_cols = g.src_cols;
+        p.br = g.br;
+        p.bc = g.bc;
+        p.nbr = g.nbr;
+        p.nbc = g.nbc;
+        const int64_t ntile = g.nbr * g.nbc;
+        int64_t fb = ceil_div(ntile, kThreads);
+        if (fb > 4096) fb = 4096;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)fb), dim3(kThreads), 0, s, tile_amax, ntile, 0u);
         const int64_t gx = ceil_div(g.src_cols, kThreads * 4);
-        int64_t gy = g.src_rows > 65535 ? 65535 : g.src_rows;
+        int64_t gy = ceil_div(g.src_rows, kAmaxRows);
+        gy = gy > 65535 ? 65535 : gy;
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
-        hipLaunchKernelGGL(tile_amax_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p);
+        const int vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0) ? 1 : 0;
+        hipLaunchKernelGGL(tile_amax_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p, vec_ok);
     }
-    {
-        const int64_t gx = ceil_div(g.kpad, kThreads);
-        int64_t gy = g.R > 65535 ? 65535 : g.R;
+    if (g.axis == 1) {
+        RowParams p;
+        p.src = src;
+        p.mant = (uint8_t *)mant;
+        p.exps = exps;
+        p.ld = g.ld;
+        p.R = g.R;
+        p.K = g.K;
+        p.kpad = g.kpad;
+        p.exp_ld = g.exp_ld;
+        p.src_cols = g.src_cols;
+        if (g.kpad / 8 > 0x7fffffff || g.nblk > 0x7fffffff || g.kblock > 0x7fffffff || g.R > 0x7fffffff) return HBFP_ERR_ARG;
+        p.kblock = (int32_t)g.kblock;
+        p.nblk = (int32_t)g.nblk;
+        p.nb_stored = (int32_t)(g.kpad / g.kbp);
+        p.m = g.m;
+        p.chunks = (int32_t)(g.kpad / 8);
+        const int l2 = ilog2_ceil(p.chunks);
+        p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
+        p.nseg = 0;
+        p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
+        p.s0 = g.seed_lo;
+        p.s1 = g.seed_hi;
+        p.table = tile_amax;
+        p.rblock = g.rblock;
+        p.gp = (int32_t)(g.kbp / 8);
+        const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
-        const dim3 grid((unsigned)gx, (unsigned)gy);
-        const bool wide = g.m > 8;
-        if (!wide && g.rounding == 0) hipLaunchKernelGGL((tile_quant_kernel<false, 0>), grid, dim3(kThreads), 0, s, p);
-        else if (!wide) hipLaunchKernelGGL((tile_quant_kernel<false, 1>), grid, dim3(kThreads), 0, s, p);
-        else if (g.rounding == 0) hipLaunchKernelGGL((tile_quant_kernel<true, 0>), grid, dim3(kThreads), 0, s, p);
-        else hipLaunchKernelGGL((tile_quant_kernel<true, 1>), grid, dim3(kThreads), 0, s, p);
+        launch_row_g<0>(p, dim3((unsigned)gx), wide, g.rounding, s);
+    } else {
+        ColParams p;
+        p.src = src;
+        p.mant = (uint8_t *)mant;
+        p.exps = exps;
+        p.ld = g.ld;
+        p.R = g.R;
+        p.K = g.K;
+        p.kpad = g.kpad;
+        p.exp_ld = g.exp_ld;
+        p.src_cols = g.src_cols;
+        if (g.nblk > 0x7fffffff || g.kblock > 0x7fffffff || g.kpad / 32 > 0x7fffffff || g.R > 0x7fffffff) return HBFP_ERR_ARG;
+        p.kblock = (int32_t)g.kblock;
+        p.nblk = (int32_t)g.nblk;
+        p.nb_stored = (int32_t)(g.kpad / 32);                       // stored pieces of 32 elements
+        p.m = g.m;
+        p.s0 = g.seed_lo;
+        p.s1 = g.seed_hi;
+        p.rblock = 1;
+        p.lanes = 64;
+        p.table = tile_amax;
+        p.rblock_t = g.rblock;
+        p.ntc = g.nbc;
+        p.spb = (int32_t)(g.kbp / 32);
+        const int nbt = kColRowBytes / (32 * (wide ? 2 : 1));
+        const int64_t gx = ceil_div(g.R, 64), gy = ceil_div(p.nb_stored, nbt);
+        if (gx > 0x7fffffff || gx * gy > 0x7fffffff) return HBFP_ERR_ARG;
+        p.row_groups = (uint32_t)gx;
+        launch_col_table(p, dim3((unsigned)(gx * gy)), wide, g.rounding, s);
     }
     return launch_status();
 }

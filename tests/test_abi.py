@@ -78,7 +78,8 @@ def test_encode_workspace_sizes():
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 24, 24), 100, 100, 1)) == 0
     n = hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 96, 96), 500, 500, 0))
     assert n >= 6 * 6 * 4 and n % 256 == 0
-    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 100, 100, 1)) == 0
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 32, 100), 100, 100, 1)) == 0
+    assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 100, 100, 1)) == 256
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 0, 0), 2000, 2000, 1)) == 256
 
 

@@ -74,6 +74,10 @@ TILE_CASES = [
     (129, 1030, 1, 1, 200, 8, 0), (1030, 129, 0, 200, 1, 8, 1), (33, 65, 1, 2, 32, 8, 0), (65, 33, 0, 32, 2, 8, 0),
     (48, 4100, 1, 24, 24, 8, 0), (4100, 48, 0, 24, 24, 8, 1), (300, 200, 0, 100, 100, 8, 0), (200, 300, 1, 100, 100, 8, 1),
     (150, 150, 0, 64, 64, 12, 0), (130, 2100, 1, 1100, 128, 8, 0), (64, 200, 0, 16, 3, 8, 0), (200, 64, 1, 3, 16, 8, 1),
+    # several row strips of the maximum pass, blocks that cross them, widths that are no multiple of 4
+    (700, 2100, 0, 0, 1, 8, 0), (700, 2100, 1, 1, 0, 8, 1), (520, 1300, 0, 256, 1, 12, 0), (520, 1300, 1, 1, 256, 12, 1),
+    (300, 1100, 0, 64, 64, 8, 0), (300, 1100, 1, 64, 64, 8, 1), (131, 1029, 1, 1, 0, 8, 0), (1029, 131, 0, 0, 1, 8, 1),
+    (400, 1500, 0, 0, 0, 8, 0), (400, 1500, 1, 0, 0, 12, 1), (257, 515, 0, 130, 70, 8, 0), (257, 515, 1, 70, 130, 8, 0),
 ]
 
 
