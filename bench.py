@@ -105,6 +105,12 @@ def _linear_layer(torch, hbfp, synth):
               ("encode_w", W, [enc["w_fwd"], enc["w_dgrad"]])]
     assert all(hbfp.encode_multi_workspace(outs_) == 0 for _, _, outs_ in groups)
 
+    # buffers of the two-step form of the same product (hbfp_pack + hbfp_gemm_packed), used only by the pass that
+    # times the product kernel by itself
+    packed = {k: torch.empty(hbfp.pack_bytes(t.desc), dtype=torch.uint8, device="cuda") for k, t in enc.items()}
+    ws_packed = [torch.empty(max(hbfp.gemm_packed_workspace(enc[a].desc, enc[b].desc), 256), dtype=torch.uint8, device="cuda")
+                 for a, b in prods]
+
     def step(timer=None):
         for name, src, outs_ in groups:
             if timer:
@@ -119,6 +125,18 @@ def _linear_layer(torch, hbfp, synth):
                 a.record()
             hbfp.gemm(enc[pa], enc[pb], out=outs[i], workspace=ws_gemm[i])
             if timer:
+                b.record()
+        if timer:
+            # the same three products once more in two steps, with events around the product kernel alone
+            for i, (pa, pb) in enumerate(prods):
+                a, b = timer.region("pack")
+                a.record()
+                hbfp.pack(enc[pa], out=packed[pa])
+                hbfp.pack(enc[pb], out=packed[pb])
+                b.record()
+                a, b = timer.region("product")
+                a.record()
+                hbfp.gemm_packed(enc[pa], packed[pa], enc[pb], packed[pb], out=outs[i], workspace=ws_packed[i])
                 b.record()
 
     flops_per_product = 2.0 * M * N * K
@@ -251,10 +269,15 @@ def _kernel_families(torch, hbfp, reps=8):
                             ("4096_bfp8_one_exponent_per_row", 4096, 8, 0), ("8192_bfp8_one_exponent_per_row", 8192, 8, 0)):
         A = torch.randn((n, n), device="cuda", generator=g)
         B = torch.randn((n, n), device="cuda", generator=g)
-        ta, tb = hbfp.encode(A, 1, hbfp.make_format(m, 1, blk)), hbfp.encode(B, 0, hbfp.make_format(m, blk, 1))
+        fa, fb = hbfp.make_format(m, 1, blk), hbfp.make_format(m, blk, 1)
+        ta, tb = hbfp.encode(A, 1, fa), hbfp.encode(B, 0, fb)
+        entry = {}
+        for tag, src, ax, fmt, t in (("encode_a_ms", A, 1, fa, ta), ("encode_b_ms", B, 0, fb, tb)):
+            wse = torch.empty(max(hbfp.encode_workspace(t.desc), 256), dtype=torch.uint8, device="cuda")
+            entry[tag] = round(_time_call(torch, lambda: hbfp.encode(src, ax, fmt, out=t, workspace=wse), reps), 4)
+            del wse
         del A, B
         out = torch.empty((n, n), dtype=torch.float32, device="cuda")
-        entry = {}
         for tag, kernel in (("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)):
             ws = torch.empty(max(hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel), 256), dtype=torch.uint8, device="cuda")
             ms = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws, kernel=kernel), reps)
@@ -263,6 +286,8 @@ def _kernel_families(torch, hbfp, reps=8):
             del ws
         auto = hbfp.gemm_workspace(ta.desc, tb.desc) > hbfp.gemm_select_workspace(ta.desc, tb.desc, hbfp.KERNEL_INT8)
         entry["automatic_choice"] = "scaled" if auto else "int8"
+        best = min(entry["int8_ms"], entry["scaled_ms"])
+        entry["best_TOPS_incl_encode"] = round(2.0 * n ** 3 / (best + entry["encode_a_ms"] + entry["encode_b_ms"]) / 1e9, 1)
         res[name] = entry
         del ta, tb, out
     return {"kernel_families": res}
@@ -345,9 +370,13 @@ def main():
 
     gemm_ms = timer.total_ms("gemm") / timer.count("gemm")
     gemm_tops = flops_product / gemm_ms / 1e9
+    # the product kernel by itself (hbfp_gemm_packed on operands packed just before: the same kernel the one-call
+    # form launches, plus the int8 stand-by that exits at once)
+    product_ms = timer.total_ms("product") / timer.count("product")
+    pack_ms = timer.total_ms("pack") / timer.count("pack")
     # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
     limb_flop = 4.0 * flops_product
-    limb_tflops = limb_flop / (gemm_ms * 1e-3) / 1e12
+    limb_tflops = limb_flop / (product_ms * 1e-3) / 1e12
     enc_act_ms = timer.total_ms("encode_act") / args.steps
     enc_w_ms = timer.total_ms("encode_w") / args.steps
     gemm_step_ms = timer.total_ms("gemm") / args.steps
@@ -379,15 +408,19 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2>", "achieved": round(limb_tflops, 1),
                      "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
-                     "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(gemm_ms, 4),
+                     "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
                      "algorithmic_flop_per_launch": limb_flop,
-                     "int8_equivalent_TOPS": round(gemm_tops, 2), "int8_matrix_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "whole_call_ms": round(gemm_ms, 4), "pack_ms_two_launches": round(pack_ms, 4),
+                     "int8_equivalent_TOPS": round(flops_product / product_ms / 1e9, 2),
+                     "int8_equivalent_TOPS_whole_call": round(gemm_tops, 2),
+                     "int8_matrix_frac": round(flops_product / product_ms / 1e9 / INT8_PEAK_TOPS, 4),
                      "power_limited_peak_measured": {"fp6_TFLOPS_random_operands": 5750.0, "int8_TOPS_random_operands": 3400.0,
                                                      "note": "register-only loops of the matrix instruction on this box: the chip "
                                                              "lowers its clock to 1.4 GHz (FP6) / 1.6 GHz (int8) when the operand bits are random"},
-                     "note": "avg_launch_ms is the HIP-event time of one product call: the pack kernel (both operands into limb "
-                             "planes, about 14 % of the call), the product kernel, and the int8 kernel that exits at once when "
-                             "every exponent is in range; the rocprofv3 summary lists each"},
+                     "note": "avg_launch_ms is the HIP-event time of the product kernel on operands packed beforehand "
+                             "(hbfp_gemm_packed: gemm_mx_kernel plus the int8 stand-by kernel, which exits at once when every "
+                             "exponent is in range); whole_call_ms is one hbfp_gemm call of the timed step (pack kernel for both "
+                             "operands + product + stand-by); the rocprofv3 summary lists each kernel"},
     }
     if not args.no_extra:
         extra = _encode_config2(torch, hbfp, synth)

@@ -90,6 +90,13 @@ typedef struct hbfp_format {
     int64_t block_rows;  /* block extent along the source rows; 0 = all rows */
     int64_t block_cols;  /* block extent along the source columns; 0 = all columns */
     uint64_t seed;       /* stochastic rounding only */
+    int64_t k_slot;      /* 0, or the length of the stored blocks along the contraction axis when the exponent
+                            block is longer: the operand is then stored (and scaled in the product) in blocks
+                            of k_slot elements that repeat the exponent of the block_rows x block_cols block
+                            they lie in.  The block extent along the contraction axis must be a multiple of
+                            k_slot or the whole extent.  This is how an operand with one exponent per row
+                            (activations with one exponent per training input, Sec. 5.1) meets an operand cut
+                            into tiles (24 x 24 weight tiles): both are stored in blocks of 24. */
 } hbfp_format;
 
 /* An encoded operand.  hbfp_plan fills everything but the two pointers. */
@@ -104,6 +111,7 @@ typedef struct hbfp_tensor {
     int64_t kpad;
     int64_t exp_ld;
     int64_t rblock;        /* operand rows that share one exponent (block extent across k) */
+    int64_t kshare;        /* consecutive k blocks that repeat one exponent (1 unless hbfp_format.k_slot is used) */
     int64_t src_rows, src_cols; /* shape of the source matrix */
     int32_t contract_axis; /* 0: k runs down the source rows, 1: along the source columns */
     int32_t mant_bits;

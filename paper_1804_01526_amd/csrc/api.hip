@@ -13,13 +13,13 @@ int check_format(const hbfp_format *f) {
     if (!f) return HBFP_ERR_ARG;
     if (f->mant_bits < 2 || f->mant_bits > 16) return HBFP_ERR_FORMAT;
     if (f->rounding != HBFP_RNE && f->rounding != HBFP_STOCHASTIC) return HBFP_ERR_FORMAT;
-    if (f->block_rows < 0 || f->block_cols < 0) return HBFP_ERR_FORMAT;
+    if (f->block_rows < 0 || f->block_cols < 0 || f->k_slot < 0) return HBFP_ERR_FORMAT;
     return HBFP_OK;
 }
 
 bool same_plan(const hbfp_tensor &a, const hbfp_tensor &b) {
     return a.rows == b.rows && a.kdim == b.kdim && a.kblock == b.kblock && a.kblock_pad == b.kblock_pad &&
-           a.nblk == b.nblk && a.kpad == b.kpad && a.exp_ld == b.exp_ld && a.rblock == b.rblock &&
+           a.nblk == b.nblk && a.kpad == b.kpad && a.exp_ld == b.exp_ld && a.rblock == b.rblock && a.kshare == b.kshare &&
            a.src_rows == b.src_rows && a.src_cols == b.src_cols && a.contract_axis == b.contract_axis &&
            a.mant_bits == b.mant_bits && a.rounding == b.rounding && a.seed == b.seed &&
            a.mant_bytes == b.mant_bytes && a.exp_bytes == b.exp_bytes;
@@ -31,13 +31,16 @@ EncodeGeom geom_of(const hbfp_tensor &t, int64_t ld) {
     g.src_cols = t.src_cols;
     g.ld = ld;
     g.axis = t.contract_axis;
+    // exponent blocks in source coordinates: kshare stored blocks along k repeat one exponent
+    const int64_t kext = t.kshare >= t.nblk ? t.kdim : t.kshare * t.kblock;
     if (t.contract_axis == 1) {
         g.br = t.rblock;
-        g.bc = t.kblock;
+        g.bc = kext;
     } else {
-        g.br = t.kblock;
+        g.br = kext;
         g.bc = t.rblock;
     }
+    g.kshare = t.kshare;
     g.nbr = ceil_div(g.src_rows, g.br);
     g.nbc = ceil_div(g.src_cols, g.bc);
     g.R = t.rows;
@@ -64,11 +67,14 @@ int check_tensor(const hbfp_tensor *t, bool need_ptrs) {
     f.mant_bits = t->mant_bits;
     f.rounding = t->rounding;
     f.seed = t->seed;
+    if (t->kshare < 1) return HBFP_ERR_LAYOUT;
+    f.k_slot = t->kshare > 1 ? t->kblock : 0;
+    const int64_t kext = t->kshare == 1 ? t->kblock : (t->kshare >= t->nblk ? 0 : t->kshare * t->kblock);
     if (t->contract_axis == 1) {
         f.block_rows = t->rblock;
-        f.block_cols = t->kblock;
+        f.block_cols = kext;
     } else {
-        f.block_rows = t->kblock;
+        f.block_rows = kext;
         f.block_cols = t->rblock;
     }
     hbfp_tensor p;
@@ -81,6 +87,7 @@ int check_tensor(const hbfp_tensor *t, bool need_ptrs) {
 
 // Block shapes the single-pass kernels cover; everything else takes the max pass + quantise pass.
 bool needs_tile_pass(const hbfp_tensor &t) {
+    if (t.kshare > 1) return true;
     if (t.contract_axis == 1) return t.kblock > 128 || t.rblock > 32;
     return t.kblock > 64 || t.rblock > 64;
 }
@@ -166,6 +173,14 @@ int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_a
         out->kblock = br;
         out->rblock = bc;
     }
+    out->kshare = 1;
+    if (fmt->k_slot > 0 && fmt->k_slot < out->kblock) {
+        // stored blocks of k_slot elements repeat the exponent of the longer exponent block they lie in
+        const int64_t kext = out->kblock;
+        if (kext != out->kdim && kext % fmt->k_slot != 0) return HBFP_ERR_FORMAT;
+        out->kblock = fmt->k_slot;
+        out->kshare = kext == out->kdim ? ceil_div(out->kdim, out->kblock) : kext / out->kblock;
+    }
     out->kblock_pad = out->kblock <= 32 ? 32 : out->kblock <= 64 ? 64 : round_up(out->kblock, 128);
     out->nblk = ceil_div(out->kdim, out->kblock);
     out->kpad = round_up(out->nblk * out->kblock_pad, 128);
@@ -183,7 +198,7 @@ int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes) {
         *bytes = 0;
         return HBFP_OK;
     }
-    const int64_t ntile = ceil_div(plan->rows, plan->rblock) * plan->nblk;
+    const int64_t ntile = ceil_div(plan->rows, plan->rblock) * ceil_div(plan->nblk, plan->kshare);
     *bytes = align256((size_t)ntile * 4);
     return HBFP_OK;
 }

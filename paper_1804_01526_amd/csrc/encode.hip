@@ -54,10 +54,10 @@ struct RowParams {
     int32_t vec_ok;     // 16-byte vector loads are aligned
     uint32_t s0, s1;
     // GP = 0 (second pass of the two-pass conversion): the largest magnitude of every exponent block has been
-    // computed already, table[(row / rblock) * nblk + block]; a stored block is gp chunks long
+    // computed already, table[(row / rblock) * ntk + block / kshare]; a stored block is gp chunks long
     const uint32_t *table;
-    int64_t rblock;
-    int32_t gp;
+    int64_t rblock, ntk;
+    int32_t gp, kshare;
 };
 
 template <int GP, bool WIDE, int ROUND, int U>
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
             amax = group_max<(GP ? GP : 4)>(amax);
         } else if (row >= 0 && blk < p.nblk) {
-            amax = p.table[(int64_t)((uint32_t)row / (uint32_t)p.rblock) * p.nblk + blk];     // rows fit 31 bits here
+            amax = p.table[(int64_t)((uint32_t)row / (uint32_t)p.rblock) * p.ntk + (uint32_t)blk / (uint32_t)p.kshare];   // rows fit 31 bits here
         }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
         int q[8];
@@ -274,11 +274,11 @@ struct ColParams {
     uint32_t row_groups;   // workgroups per group of blocks (the grid is flat: block group = blockIdx.x / row_groups)
     uint32_t s0, s1;
     // TABLE (second pass of the two-pass conversion): the largest magnitude of every exponent block has been computed
-    // already, table[block * ntc + row / rblock_t]; the kernel then walks stored pieces of KBP elements, spb of which
-    // make up one stored block (nblk, kblock and exp_ld still describe the exponent blocks)
+    // already, table[(block / kshare) * ntc + row / rblock_t]; the kernel then walks stored pieces of KBP elements,
+    // spb of which make up one stored block
     const uint32_t *table;
     int64_t rblock_t, ntc;
-    int32_t spb;
+    int32_t spb, kshare;
 };
 
 constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
@@ -317,7 +317,9 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 #pragma unroll
         for (int kk = 0; kk < KBP; ++kk) amax = max(amax, __float_as_uint(v[kk]) & 0x7fffffffu);
         if (TABLE) {
-            amax = (blk < p.nblk && r_ok) ? p.table[blk * p.ntc + (uint32_t)r / (uint32_t)p.rblock_t] : 0u;   // rows fit 31 bits here
+            amax = (blk < p.nblk && r_ok)
+                       ? p.table[(int64_t)((uint32_t)blk / (uint32_t)p.kshare) * p.ntc + (uint32_t)r / (uint32_t)p.rblock_t]
+                       : 0u;                                              // rows and blocks fit 31 bits here
         } else if (p.rblock > 1) {
             // 2-D tile: the maximum also runs over the rblock neighbouring operand rows (lanes of this wave)
             lane_amax[wave][lane] = amax;
@@ -508,7 +510,9 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.s1 = g.seed_hi;
     p.table = nullptr;
     p.rblock = 1;
+    p.ntk = 0;
     p.gp = 0;
+    p.kshare = 1;
     if (g.rblock > 1) {
         p.nseg = (int32_t)ceil_div(p.chunks, kThreads);
         const int64_t gx = ceil_div(g.R, g.rblock);
@@ -558,6 +562,7 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.rblock_t = 1;
     p.ntc = 0;
     p.spb = 1;
+    p.kshare = 1;
     const bool wide = g.m > 8;
     const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
     // cover every stored block and every exponent byte up to exp_ld
@@ -625,7 +630,9 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         p.s1 = g.seed_hi;
         p.table = tile_amax;
         p.rblock = g.rblock;
+        p.ntk = g.nbc;
         p.gp = (int32_t)(g.kbp / 8);
+        p.kshare = (int32_t)(g.kshare > g.nblk ? g.nblk : g.kshare);
         const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
         launch_row_g<0>(p, dim3((unsigned)gx), wide, g.rounding, s);
@@ -653,6 +660,7 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         p.rblock_t = g.rblock;
         p.ntc = g.nbc;
         p.spb = (int32_t)(g.kbp / 32);
+        p.kshare = (int32_t)(g.kshare > g.nblk ? g.nblk : g.kshare);
         const int nbt = kColRowBytes / (32 * (wide ? 2 : 1));
         const int64_t gx = ceil_div(g.R, 64), gy = ceil_div(p.nb_stored, nbt);
         if (gx > 0x7fffffff || gx * gy > 0x7fffffff) return HBFP_ERR_ARG;

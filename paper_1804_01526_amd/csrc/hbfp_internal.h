@@ -23,6 +23,7 @@ struct EncodeGeom {
     int32_t axis;                     // contraction axis in the source
     // operand side
     int64_t R, K, kblock, kbp, nblk, kpad, exp_ld, rblock;
+    int64_t kshare;                   // stored blocks along k that repeat one exponent
     int32_t m, rounding;
     uint32_t seed_lo, seed_hi;
 };

@@ -236,7 +236,7 @@ void launch_br(const TileParams &p, dim3 grid, int rounding, hipStream_t s) {
 
 bool fits(const hbfp_tensor *t, int64_t br, int64_t bc) {
     const int64_t tbr = t->contract_axis == 1 ? t->rblock : t->kblock, tbc = t->contract_axis == 1 ? t->kblock : t->rblock;
-    return tbr == br && tbc == bc && t->kblock_pad == 32 && ((uintptr_t)t->mant & 15) == 0;
+    return tbr == br && tbc == bc && t->kblock_pad == 32 && t->kshare == 1 && ((uintptr_t)t->mant & 15) == 0;
 }
 
 }  // namespace

@@ -29,7 +29,8 @@ class HbfpError(RuntimeError):
 class Format(ctypes.Structure):
     """hbfp_format: how a source matrix is cut into exponent blocks."""
     _fields_ = [("mant_bits", ctypes.c_int32), ("rounding", ctypes.c_int32),
-                ("block_rows", ctypes.c_int64), ("block_cols", ctypes.c_int64), ("seed", ctypes.c_uint64)]
+                ("block_rows", ctypes.c_int64), ("block_cols", ctypes.c_int64), ("seed", ctypes.c_uint64),
+                ("k_slot", ctypes.c_int64)]
 
 
 class TensorDesc(ctypes.Structure):
@@ -37,7 +38,7 @@ class TensorDesc(ctypes.Structure):
     _fields_ = [("mant", ctypes.c_void_p), ("exps", ctypes.c_void_p),
                 ("rows", ctypes.c_int64), ("kdim", ctypes.c_int64), ("kblock", ctypes.c_int64),
                 ("kblock_pad", ctypes.c_int64), ("nblk", ctypes.c_int64), ("kpad", ctypes.c_int64),
-                ("exp_ld", ctypes.c_int64), ("rblock", ctypes.c_int64),
+                ("exp_ld", ctypes.c_int64), ("rblock", ctypes.c_int64), ("kshare", ctypes.c_int64),
                 ("src_rows", ctypes.c_int64), ("src_cols", ctypes.c_int64),
                 ("contract_axis", ctypes.c_int32), ("mant_bits", ctypes.c_int32),
                 ("rounding", ctypes.c_int32), ("reserved", ctypes.c_int32),
@@ -112,8 +113,9 @@ def _dev_ptr(t: Optional[torch.Tensor]):
     return ctypes.c_void_p(0 if t is None else t.data_ptr())
 
 
-def make_format(mant_bits: int, block_rows: int, block_cols: int, rounding: int = RNE, seed: int = 0) -> Format:
-    return Format(mant_bits, rounding, block_rows, block_cols, seed)
+def make_format(mant_bits: int, block_rows: int, block_cols: int, rounding: int = RNE, seed: int = 0,
+                k_slot: int = 0) -> Format:
+    return Format(mant_bits, rounding, block_rows, block_cols, seed, k_slot)
 
 
 # ---------------------------------------------------------------------------- C ABI, one to one

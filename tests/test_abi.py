@@ -28,8 +28,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header():
-    assert ctypes.sizeof(hbfp.Format) == 32
-    assert ctypes.sizeof(hbfp.TensorDesc) == 136
+    assert ctypes.sizeof(hbfp.Format) == 40
+    assert ctypes.sizeof(hbfp.TensorDesc) == 144
 
 
 @pytest.mark.parametrize("rows,cols,axis,br,bc,m,want", [
@@ -48,6 +48,32 @@ def test_plan_geometry(rows, cols, axis, br, bc, m, want):
     got = (d.rows, d.kdim, d.kblock, d.kblock_pad, d.nblk, d.kpad, d.exp_ld, d.rblock, d.mant_bytes)
     assert got == want
     assert d.exp_bytes == d.rows * d.exp_ld and d.mant is None and d.exps is None
+
+
+@pytest.mark.parametrize("rows,cols,axis,br,bc,slot,want", [
+    # exponent blocks longer than the stored blocks -> (kblock, kbp, nblk, kshare, kpad, exp_ld, rblock)
+    (64, 4096, 1, 1, 0, 24, (24, 32, 171, 171, 5504, 172, 1)),          # one exponent per row, stored like 24-wide tiles
+    (4096, 64, 0, 0, 1, 24, (24, 32, 171, 171, 5504, 172, 1)),
+    (64, 4096, 1, 1, 96, 24, (24, 32, 171, 4, 5504, 172, 1)),
+    (128, 4096, 1, 64, 64, 32, (32, 32, 128, 2, 4096, 128, 64)),
+    (64, 4096, 1, 1, 24, 24, (24, 32, 171, 1, 5504, 172, 1)),           # slot = block: nothing changes
+    (64, 4096, 1, 1, 24, 32, (24, 32, 171, 1, 5504, 172, 1)),           # slot longer than the block: ignored
+    (64, 100, 1, 1, 0, 128, (100, 128, 1, 1, 128, 4, 1)),
+])
+def test_plan_geometry_with_k_slot(rows, cols, axis, br, bc, slot, want):
+    d = hbfp.plan(hbfp.make_format(8, br, bc, k_slot=slot), rows, cols, axis)
+    assert (d.kblock, d.kblock_pad, d.nblk, d.kshare, d.kpad, d.exp_ld, d.rblock) == want
+    n = hbfp.encode_workspace(d)
+    assert (n > 0) == (d.kshare > 1 or d.kblock > 128)
+
+
+def test_k_slot_must_divide_the_exponent_block():
+    with pytest.raises(hbfp.HbfpError) as e:
+        hbfp.plan(hbfp.make_format(8, 1, 100, k_slot=24), 64, 4096, 1)
+    assert e.value.status == hbfp.ERR_FORMAT
+    with pytest.raises(hbfp.HbfpError) as e:
+        hbfp.plan(hbfp.make_format(8, 1, 0, k_slot=-1), 64, 4096, 1)
+    assert e.value.status == hbfp.ERR_FORMAT
 
 
 def _status(fn, *a):

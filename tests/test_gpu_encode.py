@@ -86,6 +86,33 @@ def test_encode_tiles_and_long_blocks(hb, rows, cols, axis, br, bc, m, rounding)
     _check(hb, _data((rows, cols), rows + 13 * cols), axis, br, bc, m, rounding, seed=0xABCD)
 
 
+SLOT_CASES = [
+    # rows, cols, axis, br, bc, k_slot, m, rounding: exponent blocks longer than the stored blocks
+    (70, 1000, 1, 1, 0, 24, 8, 0), (1000, 70, 0, 0, 1, 24, 8, 1), (130, 2000, 1, 1, 96, 24, 8, 1), (2000, 130, 0, 96, 1, 24, 12, 0),
+    (200, 1030, 1, 64, 64, 32, 8, 0), (1030, 200, 0, 64, 64, 32, 8, 1), (300, 520, 1, 0, 0, 64, 12, 0), (520, 300, 0, 0, 0, 24, 8, 0),
+    (33, 4100, 1, 1, 0, 32, 8, 0), (4100, 33, 0, 0, 1, 128, 8, 0), (90, 777, 1, 3, 0, 20, 8, 1), (777, 90, 0, 0, 3, 20, 8, 0),
+]
+
+
+@pytest.mark.parametrize("rows,cols,axis,br,bc,slot,m,rounding", SLOT_CASES)
+def test_encode_exponent_blocks_longer_than_stored_blocks(hb, rows, cols, axis, br, bc, slot, m, rounding):
+    """hbfp_format.k_slot: mantissas and exponents are those of the br x bc blocks (the oracle knows nothing of the
+    stored blocks); the stored blocks repeat the exponent (checked by unpack)."""
+    x = _data((rows, cols), rows + 7 * cols + slot)
+    print(f"[case] shape={x.shape} axis={axis} block=({br},{bc}) k_slot={slot} m={m} rounding={rounding}", flush=True)
+    fmt = hb.make_format(m, br, bc, rounding, 0x51075, k_slot=slot)
+    bt = hb.encode(torch.from_numpy(x).cuda(), axis, fmt)
+    torch.cuda.synchronize()
+    assert bt.desc.kblock == slot and bt.desc.kshare > 1
+    want = ref.encode(x, br, bc, m, rounding, 0x51075)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    back = hb.decode(bt)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(back.cpu().numpy(), ref.decode(want))
+
+
 REGISTER_TILE_CASES = [
     # tiles of at most 32 x 32 with column counts and tile widths that are multiples of 4: the register-tile kernel
     # rows, cols, br, bc, m, rounding

@@ -410,6 +410,51 @@ def test_scaled_kernel_in_a_replayed_graph(hb):
         assert rel_fro(out.cpu().numpy(), eager.cpu().numpy()) <= 2e-6
 
 
+@pytest.mark.parametrize("kernel", [0, 1, SCALED])
+@pytest.mark.parametrize("m", [8, 12])
+def test_gemm_one_exponent_per_training_input_against_weight_tiles(hb, kernel, m):
+    """The format of Sec. 5.1: activations with one exponent per row (training input), weights in 24 x 24 tiles.
+    The activations are stored in blocks of 24 that repeat the row's exponent (hbfp_format.k_slot), so the product
+    scales block by block as for any other pair; forward and data-gradient orientation of the weights."""
+    M, K, N = 150, 500, 130
+    X, W = _rand((M, K), 3 + m, 1), (_rand((K, N), 4 + m, 1) * 0.02).astype(np.float32)
+    print(f"[case] row exponent x 24x24 tiles M={M} K={K} N={N} m={m} kernel={kernel}", flush=True)
+    tx = hb.encode(torch.from_numpy(X).cuda(), 1, hb.make_format(m, 1, 0, k_slot=24))
+    tw = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(m, 24, 24))
+    ox, ow = ref.encode(X, 1, 0, m), ref.encode(W, 24, 24, m)
+    mx, ex = unpack(tx)
+    np.testing.assert_array_equal(mx, ox.mant)
+    np.testing.assert_array_equal(ex, ox.exps)
+    P = hb.gemm_partials(tx, tw)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(P.cpu().numpy(), ref.block_dots(ox.mant, ow.mant, 24))
+    C = hb.gemm(tx, tw, kernel=kernel)
+    torch.cuda.synchronize()
+    err = rel_fro(C.cpu().numpy(), ref.gemm(ref.decode(ox), ref.decode(ow)))
+    print(f"        rel fro err = {err:.3e}", flush=True)
+    assert err <= TOL
+    # data gradient: dY [M, N] with one exponent per row, contracted with the same tiles along N
+    dY = _rand((M, N), 9 + m, 2)
+    tdy = hb.encode(torch.from_numpy(dY).cuda(), 1, hb.make_format(m, 1, 0, k_slot=24))
+    twt = hb.encode(torch.from_numpy(W).cuda(), 1, hb.make_format(m, 24, 24))
+    dX = hb.gemm(tdy, twt, kernel=kernel)
+    torch.cuda.synchronize()
+    err = rel_fro(dX.cpu().numpy(), ref.gemm(ref.decode(ref.encode(dY, 1, 0, m)), ref.decode(ow).T))
+    print(f"        rel fro err (data gradient) = {err:.3e}", flush=True)
+    assert err <= TOL
+
+
+def test_gemm_f32_with_k_slot_formats(hb):
+    """hbfp_gemm_f32 with one exponent per activation row against 24 x 24 weight tiles."""
+    M, K, N = 200, 700, 260
+    X, W = _rand((M, K), 41, 1), (_rand((K, N), 42, 1) * 0.05).astype(np.float32)
+    fa, fb = hb.make_format(8, 1, 0, k_slot=24), hb.make_format(8, 24, 24)
+    C = hb.gemm_f32(0, 0, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), fa, fb)
+    torch.cuda.synchronize()
+    want = ref.gemm(ref.decode(ref.encode(X, 1, 0, 8)), ref.decode(ref.encode(W, 24, 24, 8)))
+    assert rel_fro(C.cpu().numpy(), want) <= TOL
+
+
 def _oracle_product(A, B, fa, fb):
     oa = ref.encode(A, fa[0], fa[1], fa[2], fa[3], fa[4])
     ob = ref.encode(B, fb[0], fb[1], fb[2], fb[3], fb[4])

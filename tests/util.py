@@ -22,6 +22,9 @@ def unpack(bt):
     op = op[:, :K]
     assert (exps[:, nblk:] == 1).all(), "exponent padding must be 1"
     e = exps[:, :nblk]
+    ks = min(d.kshare, nblk)
+    assert (np.repeat(e[:, ::ks], ks, axis=1)[:, :nblk] == e).all(), "stored blocks of one exponent block must repeat the exponent"
+    e = e[:, ::ks]
     rb = d.rblock
     first = e[::rb]
     assert (np.repeat(first, rb, axis=0)[:R] == e).all(), "rows of one 2-D block must repeat the exponent"
