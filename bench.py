@@ -256,6 +256,50 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     return res
 
 
+def _time_product(torch, hbfp, sa, axa, fa, sb, axb, fb, reps):
+    """One product with both of its conversions (workspaces allocated outside the timed calls)."""
+    ta, tb = hbfp.alloc(fa, sa.shape[0], sa.shape[1], axa), hbfp.alloc(fb, sb.shape[0], sb.shape[1], axb)
+    out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")
+    wa = torch.empty(max(hbfp.encode_workspace(ta.desc), 256), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(max(hbfp.encode_workspace(tb.desc), 256), dtype=torch.uint8, device="cuda")
+    hbfp.encode(sa, axa, fa, out=ta, workspace=wa)
+    hbfp.encode(sb, axb, fb, out=tb, workspace=wb)
+    flops = 2.0 * ta.desc.rows * tb.desc.rows * ta.desc.kdim
+    ms_k = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws), reps)
+    ms_ea = _time_call(torch, lambda: hbfp.encode(sa, axa, fa, out=ta, workspace=wa), reps)
+    ms_eb = _time_call(torch, lambda: hbfp.encode(sb, axb, fb, out=tb, workspace=wb), reps)
+    return {"gemm_ms": round(ms_k, 4), "encode_a_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+            "TOPS_kernel": round(flops / ms_k / 1e9, 1), "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
+
+
+def _paper_formats(torch, hbfp, reps=8):
+    """Two more workloads of the paper, with synthetic N(0,1) activations and N(0, 0.02) weights:
+    (1) config 4's layer in the format of the paper's own experiments (Sec. 5.1): one exponent per training input
+        for activations and gradients, 24 x 24 weight tiles (hbfp_format.k_slot = 24 stores the activations in
+        blocks that match the tiles);
+    (2) the gate products of an LSTM language model (Sec. 5.2 evaluates one on PTB): 35 steps x batch 20 = 700 rows,
+        hidden size 1500, four gates, in config 4's formats."""
+    res = {}
+    g = torch.Generator(device="cuda").manual_seed(11)
+    n = 4096
+    X = torch.randn((n, n), device="cuda", generator=g)
+    W = torch.randn((n, n), device="cuda", generator=g) * 0.02
+    act, tile = hbfp.make_format(8, 1, 0, k_slot=24), hbfp.make_format(8, 24, 24)
+    res["c4_row_exponent_x_24x24_tiles_fwd"] = _time_product(torch, hbfp, X, 1, act, W, 0, tile, reps)
+    res["c4_row_exponent_x_24x24_tiles_dgrad"] = _time_product(torch, hbfp, X, 1, act, W, 1, tile, reps)
+    del X, W
+    M, H = 700, 1500
+    Xl = torch.randn((M, H), device="cuda", generator=g)
+    Wl = torch.randn((H, 4 * H), device="cuda", generator=g) * 0.02
+    dG = torch.randn((M, 4 * H), device="cuda", generator=g)
+    row, col = hbfp.make_format(8, 1, 24), hbfp.make_format(8, 24, 1)
+    res["lstm_gates_fwd"] = _time_product(torch, hbfp, Xl, 1, row, Wl, 0, tile, reps)
+    res["lstm_gates_dgrad"] = _time_product(torch, hbfp, dG, 1, row, Wl, 1, tile, reps)
+    res["lstm_gates_wgrad"] = _time_product(torch, hbfp, Xl, 0, col, dG, 0, col, reps)
+    return {"paper_formats": res}
+
+
 def _kernel_families(torch, hbfp, reps=8):
     """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
     int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
@@ -433,6 +477,7 @@ def main():
         extra.update(_gemm_side_configs(torch, hbfp, synth))
         extra.update(_weight_update_config4(torch, hbfp, synth))
         extra.update(_kernel_families(torch, hbfp))
+        extra.update(_paper_formats(torch, hbfp))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)

@@ -477,6 +477,112 @@ __global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p,
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// One wave per (operand row, exponent block), k contiguous in the source: exponent blocks of up to 64 * 8 * NV
+// stored elements (one exponent per row of a matrix a few thousand columns wide, Sec. 4; with k_slot the stored
+// blocks are shorter than the exponent block and repeat its exponent).  The wave holds the whole exponent block
+// in registers, so the source is read once: all loads first, maximum across the wave, quantise, store.
+struct WaveParams {
+    const float *src;
+    uint8_t *mant;
+    uint8_t *exps;
+    int64_t ld, R, K, kpad, exp_ld, src_cols;
+    int32_t kblock, nblk, nb_stored, m;
+    int32_t gp;            // 8-element chunks per stored block
+    int32_t kshare;        // stored blocks per exponent block
+    int32_t nreg;          // exponent blocks per row
+    int32_t chunks;        // chunks per stored row
+    int32_t vec_ok;
+    uint32_t s0, s1;
+};
+
+template <bool WIDE, int ROUND, int NV>
+__global__ __launch_bounds__(kThreads) void enc_rowwave_kernel(const WaveParams p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);    // (row, exponent block)
+    if (item >= p.R * p.nreg) return;                                                   // whole waves leave together
+    const int64_t row = item / p.nreg;
+    const int reg = (int)(item - row * p.nreg);
+    // chunks of this exponent block; the last one also covers the padding blocks at the end of the stored row
+    const int c_first = reg * p.kshare * p.gp;
+    const int c_end = reg == p.nreg - 1 ? p.chunks : c_first + p.kshare * p.gp;
+    const float *srow = p.src + row * p.ld;
+    float v[NV][8];
+    int cnt[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int cl = c_first + lane + 64 * i;
+        const int blk = cl / p.gp, j = cl - blk * p.gp;
+        int c = 0;
+        if (cl < c_end && blk < p.nblk) {
+            const int k0 = blk * p.kblock;
+            const int blen = (p.K - k0 < p.kblock) ? (int)(p.K - k0) : p.kblock;
+            const int left = blen - 8 * j;
+            c = left <= 0 ? 0 : (left >= 8 ? 8 : left);
+        }
+        cnt[i] = c;
+        const float *s = srow + (c ? (int64_t)blk * p.kblock + 8 * j : 0);
+        if (c == 8 && p.vec_ok) {
+            const float4 a = *reinterpret_cast<const float4 *>(s);
+            const float4 b = *reinterpret_cast<const float4 *>(s + 4);
+            v[i][0] = a.x; v[i][1] = a.y; v[i][2] = a.z; v[i][3] = a.w;
+            v[i][4] = b.x; v[i][5] = b.y; v[i][6] = b.z; v[i][7] = b.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = (e < c) ? s[e] : 0.0f;
+        }
+    }
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[i][e]) & 0x7fffffffu);
+    amax = group_max<16>(amax);
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 16));
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));
+    const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
+    uint8_t *erow = p.exps + row * p.exp_ld;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int cl = c_first + lane + 64 * i;
+        if (cl >= c_end) continue;
+        const int blk = cl / p.gp, j = cl - blk * p.gp;
+        int q[8];
+        const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t idx = idx0 + e;
+            q[e] = quantise<ROUND>(v[i][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+        }
+        if (!WIDE) {
+            uint2 o;
+            o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+            o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+            *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8) = o;
+        } else {
+            uint4 o;
+            o.x = pack2_i16(q[0], q[1]);
+            o.y = pack2_i16(q[2], q[3]);
+            o.z = pack2_i16(q[4], q[5]);
+            o.w = pack2_i16(q[6], q[7]);
+            *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2) = o;
+        }
+        if (j == 0) {
+            if (blk < p.exp_ld) erow[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
+            if (blk == p.nb_stored - 1)
+                for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) erow[b] = 1;
+        }
+    }
+}
+
+template <int NV>
+void launch_rowwave_n(const WaveParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_rowwave_kernel<false, 0, NV>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_rowwave_kernel<false, 1, NV>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_rowwave_kernel<true, 0, NV>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_rowwave_kernel<true, 1, NV>), grid, dim3(kThreads), 0, s, p);
+}
+
 int ilog2_ceil(int64_t x) {
     int l = 0;
     while (((int64_t)1 << l) < x) ++l;
@@ -580,8 +686,52 @@ int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, u
 // Two passes for block shapes the single-pass kernels do not cover (long blocks, one exponent per row or column,
 // large 2-D tiles, one exponent for the whole matrix): the largest magnitude of every block into a table, then the
 // row / column kernels quantise with the exponents of the table (the second read mostly hits the last-level cache).
+// Exponent blocks of one operand row each, short enough for the registers of a wave (k contiguous in the source).
+static bool rowwave_ok(const EncodeGeom &g) {
+    if (g.axis != 1 || g.rblock != 1 || g.kpad > 0x7fffffff || g.R > 0x7fffffff) return false;
+    const int64_t gp = g.kbp / 8, nreg = ceil_div(g.nblk, g.kshare);
+    // the last exponent block of a row also covers the padding blocks behind it
+    const int64_t most = nreg == 1 ? g.kpad / 8 : max(g.kshare * gp, g.kpad / 8 - (nreg - 1) * g.kshare * gp);
+    return most <= 64 * 16;
+}
+
+static int launch_encode_rowwave(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s) {
+    WaveParams p;
+    p.src = src;
+    p.mant = (uint8_t *)mant;
+    p.exps = exps;
+    p.ld = g.ld;
+    p.R = g.R;
+    p.K = g.K;
+    p.kpad = g.kpad;
+    p.exp_ld = g.exp_ld;
+    p.src_cols = g.src_cols;
+    p.kblock = (int32_t)g.kblock;
+    p.nblk = (int32_t)g.nblk;
+    p.nb_stored = (int32_t)(g.kpad / g.kbp);
+    p.m = g.m;
+    p.gp = (int32_t)(g.kbp / 8);
+    p.kshare = (int32_t)(g.kshare > g.nblk ? g.nblk : g.kshare);
+    p.nreg = (int32_t)ceil_div(g.nblk, g.kshare);
+    p.chunks = (int32_t)(g.kpad / 8);
+    p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
+    p.s0 = g.seed_lo;
+    p.s1 = g.seed_hi;
+    const int64_t most = p.nreg == 1 ? p.chunks : max((int64_t)p.kshare * p.gp, p.chunks - (int64_t)(p.nreg - 1) * p.kshare * p.gp);
+    const int64_t items = g.R * p.nreg, gx = ceil_div(items, kThreads / 64);
+    if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+    const dim3 grid((unsigned)gx);
+    const bool wide = g.m > 8;
+    if (most <= 64 * 2) launch_rowwave_n<2>(p, grid, wide, g.rounding, s);
+    else if (most <= 64 * 4) launch_rowwave_n<4>(p, grid, wide, g.rounding, s);
+    else if (most <= 64 * 8) launch_rowwave_n<8>(p, grid, wide, g.rounding, s);
+    else launch_rowwave_n<16>(p, grid, wide, g.rounding, s);
+    return launch_status();
+}
+
 int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
                           uint32_t *tile_amax, hipStream_t s) {
+    if (rowwave_ok(g)) return launch_encode_rowwave(src, g, mant, exps, s);
     const bool wide = g.m > 8;
     {
         TileParams p;

@@ -202,6 +202,23 @@ def test_config3_conv_shapes_sampled(hb):
     _run(hb, np.ascontiguousarray(X.T), dY, f_row, f_col, partials=False, rows=krows)     # dW = X^T dY
 
 
+def test_lstm_gate_products_sampled(hb):
+    """Gate products of an LSTM language model (the paper's second workload, Sec. 5.2): 35 steps x batch 20 = 700
+    rows, hidden size 1500, four gates; forward, data gradient and weight gradient in config 4's formats (blocks of
+    24, ragged: 1500 = 62 * 24 + 12, 700 = 29 * 24 + 4), checked on sampled rows."""
+    rng = np.random.default_rng(21)
+    M, H = 700, 1500
+    X = rng.standard_normal((M, H)).astype(np.float32)
+    W = (rng.standard_normal((H, 4 * H)) * 0.02).astype(np.float32)
+    dG = rng.standard_normal((M, 4 * H)).astype(np.float32)
+    act, tile = (1, 24, 8, 0, 0), (24, 24, 8, 0, 0)
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    _run(hb, X, W, act, tile, partials=False, rows=rows)                                   # gates = X W
+    _run(hb, dG, np.ascontiguousarray(W.T), act, tile, partials=False, rows=rows)          # dX = dG W^T
+    rows_w = np.sort(rng.choice(H, size=16, replace=False))
+    _run(hb, np.ascontiguousarray(X.T), dG, act, (24, 1, 8, 0, 0), partials=False, rows=rows_w)   # dW = X^T dG
+
+
 def test_config4_linear_layer_sampled(hb):
     """Config 4 at full size: 1 x 24 activation blocks, 24 x 24 weight tiles, K = 4096 = 170*24 + 16.  The library's
     choice for these products is the block-scaled kernel; the int8 kernels are checked on the same operands."""
