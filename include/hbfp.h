@@ -165,6 +165,29 @@ int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int co
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
 
 /*
+ * hbfp_encode_im2col: the activation operand of a convolution executed as a matrix product (Sec. 5.1: convolutions
+ * and their backward passes get the treatment of matrix multiplications), converted straight from the image
+ * tensor, so the lowered FP32 matrix (R*S times the size of the input) never exists in memory.
+ *   x     device FP32 tensor [n][h][w][c] (channels innermost), 16-byte aligned
+ *   conv  geometry: filter r x s, zero padding pad_h / pad_w on each side, strides; output size
+ *         ho = (h + 2 pad_h - r) / stride_h + 1, wo likewise
+ *   out   descriptor from hbfp_plan(fmt, rows = n*ho*wo, cols = r*s*c, contract_axis = 1) with mant/exps set:
+ *         operand row (img, oy, ox) holds the values under the filter window, k = (fr * s + fs) * c + ch,
+ *         zero where the window leaves the image.  The result is bit for bit what hbfp_encode gives for the
+ *         materialised lowered matrix (same logical indices for stochastic rounding).
+ * Supported formats: 1-D blocks along k of at most 128 elements, block length and c multiples of 8
+ * (HBFP_ERR_FORMAT otherwise).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
+ * convolution's.
+ */
+typedef struct hbfp_conv2d {
+    int64_t n, h, w, c;
+    int32_t r, s;
+    int32_t pad_h, pad_w;
+    int32_t stride_h, stride_w;
+} hbfp_conv2d;
+int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *stream);
+
+/*
  * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation
  * (Sec. 4, tiled matrix multiplication):
  *     C[i][j] = beta*C[i][j] + sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k]*mB[j][k]

@@ -119,6 +119,23 @@ def decode(t: BFP) -> np.ndarray:
     return out
 
 
+def im2col(x: np.ndarray, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1, stride_w: int = 1) -> np.ndarray:
+    """Activation operand of a convolution executed as a matrix product (Sec. 5.1 treats convolutions like matrix
+    multiplications): x [n, h, w, c] -> [n*ho*wo, r*s*c]; row (img, oy, ox) holds the values under the filter
+    window, column (fr*s + fs)*c + ch = x[img, oy*stride_h - pad_h + fr, ox*stride_w - pad_w + fs, ch], zero
+    outside the image.  Written out tap by tap on a zero-padded copy."""
+    n, h, w, c = x.shape
+    ho = (h + 2 * pad_h - r) // stride_h + 1
+    wo = (w + 2 * pad_w - s) // stride_w + 1
+    xp = np.zeros((n, h + 2 * pad_h, w + 2 * pad_w, c), dtype=x.dtype)
+    xp[:, pad_h:pad_h + h, pad_w:pad_w + w, :] = x
+    out = np.empty((n, ho, wo, r, s, c), dtype=x.dtype)
+    for fr in range(r):
+        for fs in range(s):
+            out[:, :, :, fr, fs, :] = xp[:, fr:fr + stride_h * (ho - 1) + 1:stride_h, fs:fs + stride_w * (wo - 1) + 1:stride_w, :]
+    return out.reshape(n * ho * wo, r * s * c)
+
+
 def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:
     """Integer block partials P[i, j, b] of Eq. (2); mA [M, K], mB [K, N]."""
     mA = np.ascontiguousarray(mA, dtype=np.int32)

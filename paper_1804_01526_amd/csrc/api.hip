@@ -266,6 +266,24 @@ int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *co
     return HBFP_OK;
 }
 
+int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *stream) {
+    if (!x || !conv || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
+    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
+        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0)
+        return HBFP_ERR_ARG;
+    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    int rc = check_tensor(out, true);
+    if (rc != HBFP_OK) return rc;
+    const int64_t ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
+    const int64_t wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
+    if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || ho * wo > 0x7fffffff) return HBFP_ERR_ARG;
+    if (out->contract_axis != 1 || out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c)
+        return HBFP_ERR_LAYOUT;
+    if (out->rblock != 1 || out->kshare != 1 || out->kblock > 128 || (out->kblock & 7) || (conv->c & 7)) return HBFP_ERR_FORMAT;
+    const EncodeGeom g = geom_of(*out, 0);
+    return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, (hipStream_t)stream);
+}
+
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
     if (!dst) return HBFP_ERR_ARG;
     int rc = check_tensor(t, true);

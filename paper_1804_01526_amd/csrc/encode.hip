@@ -58,9 +58,20 @@ struct RowParams {
     const uint32_t *table;
     int64_t rblock, ntk;
     int32_t gp, kshare;
+    // CONV: the source is an NHWC image tensor and the operand is its lowered form, never materialised: operand row
+    // (n, ho, wo) holds the values under the filter window, k = (r * S + s) * C + c, zero outside the image
+    int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
+    uint32_t dC[2], dS[2], dP[2], dW[2];   // divisions by C, S, Ho*Wo and Wo as multiply-high + shift (magic_of)
 };
 
-template <int GP, bool WIDE, int ROUND, int U>
+// n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
+// floor(n * m / 2^(31 + l)) = floor(n / d) for every such n (round-up method of Granlund and Montgomery).
+// magic[0] = m, magic[1] = l - 1; d = 1 is stored as m = 0.
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, const uint32_t (&magic)[2]) {
+    return magic[0] ? __umulhi(n, magic[0]) >> magic[1] : n;
+}
+
+template <int GP, bool WIDE, int ROUND, int U, bool CONV = false>
 __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     // The (row, chunk) pairs of the whole operand form one flat index space: a workgroup takes U * 256
     // consecutive chunks.  A row holds a multiple of 16 chunks, so the 4/8/16 lanes of a block never
@@ -98,7 +109,22 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             cnt = left <= 0 ? 0 : (left >= 8 ? 8 : (int)left);
         }
         n[u] = cnt;
-        const float *s = p.src + (in ? row : 0) * p.ld + (int64_t)blk * p.kblock + 8 * j;
+        const float *s;
+        if (!CONV) {
+            s = p.src + (in ? row : 0) * p.ld + (int64_t)blk * p.kblock + 8 * j;
+        } else {
+            // a chunk of 8 never leaves its filter tap (C and the block length are multiples of 8)
+            const uint32_t k0 = (uint32_t)blk * (uint32_t)p.kblock + 8u * (uint32_t)j;
+            const uint32_t tap = div_magic(k0, p.dC), c0 = k0 - tap * (uint32_t)p.cC;
+            const uint32_t fr = div_magic(tap, p.dS), fs = tap - fr * (uint32_t)p.cS;
+            const uint32_t pos = in ? (uint32_t)row : 0u, per_img = (uint32_t)(p.cHo * p.cWo);
+            const uint32_t img = div_magic(pos, p.dP), rem = pos - img * per_img;
+            const uint32_t ho = div_magic(rem, p.dW), wo = rem - ho * (uint32_t)p.cWo;
+            const int hi = (int)ho * p.str_h - p.pad_h + (int)fr, wi = (int)wo * p.str_w - p.pad_w + (int)fs;
+            const bool inside = hi >= 0 && hi < p.cH && wi >= 0 && wi < p.cW;
+            if (!inside) cnt = 0;                                        // zeros; they still count as elements of the block
+            s = p.src + (inside ? (((int64_t)img * p.cH + hi) * p.cW + wi) * p.cC + c0 : 0);
+        }
         if (cnt == 8 && p.vec_ok) {
             const float4 a = *reinterpret_cast<const float4 *>(s);
             const float4 b = *reinterpret_cast<const float4 *>(s + 4);
@@ -251,6 +277,14 @@ void launch_row_tiled_g(const RowParams &p, int rblock, dim3 grid, bool wide, in
 template <int GP, bool WIDE, int ROUND>
 void launch_row_t(const RowParams &p, dim3 grid, hipStream_t s) {
     hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 4>), grid, dim3(kThreads), 0, s, p);
+}
+
+template <int GP>
+void launch_row_conv_g(const RowParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_row_kernel<GP, false, 0, 4, true>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_row_kernel<GP, false, 1, 4, true>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_row_kernel<GP, true, 0, 4, true>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_row_kernel<GP, true, 1, 4, true>), grid, dim3(kThreads), 0, s, p);
 }
 
 template <int GP>
@@ -639,6 +673,73 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     if (g.kbp == 32) launch_row_g<4>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 64) launch_row_g<8>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 128) launch_row_g<16>(p, grid, wide, g.rounding, s);
+    else return HBFP_ERR_FORMAT;
+    return launch_status();
+}
+
+static void magic_of(uint32_t d, uint32_t (&magic)[2]) {
+    if (d == 1) {
+        magic[0] = magic[1] = 0;
+        return;
+    }
+    int l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    const unsigned __int128 two = (unsigned __int128)1 << (31 + l);
+    magic[0] = (uint32_t)((two + d - 1) / d);
+    magic[1] = (uint32_t)(l - 1);
+}
+
+// The activation operand of a convolution, converted straight from the NHWC tensor (1-D blocks along k = (r, s, c)).
+int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
+                         uint8_t *exps, hipStream_t s) {
+    RowParams p;
+    p.src = x;
+    p.mant = (uint8_t *)mant;
+    p.exps = exps;
+    p.ld = 0;
+    p.R = g.R;
+    p.K = g.K;
+    p.kpad = g.kpad;
+    p.exp_ld = g.exp_ld;
+    p.src_cols = g.src_cols;
+    if (g.kpad / 8 > 0x7fffffff || g.nblk > 0x7fffffff || g.R > 0x7fffffff || g.K > 0x7fffffff) return HBFP_ERR_ARG;
+    p.kblock = (int32_t)g.kblock;
+    p.nblk = (int32_t)g.nblk;
+    p.nb_stored = (int32_t)(g.kpad / g.kbp);
+    p.m = g.m;
+    p.chunks = (int32_t)(g.kpad / 8);
+    const int l2 = ilog2_ceil(p.chunks);
+    p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
+    p.nseg = 0;
+    p.vec_ok = (((uintptr_t)x & 15) == 0) ? 1 : 0;                      // C is a multiple of 8
+    p.s0 = g.seed_lo;
+    p.s1 = g.seed_hi;
+    p.table = nullptr;
+    p.rblock = 1;
+    p.ntk = 0;
+    p.gp = 0;
+    p.kshare = 1;
+    p.cH = (int32_t)c.h;
+    p.cW = (int32_t)c.w;
+    p.cC = (int32_t)c.c;
+    p.cS = c.s;
+    p.cHo = (int32_t)ho;
+    p.cWo = (int32_t)wo;
+    p.pad_h = c.pad_h;
+    p.pad_w = c.pad_w;
+    p.str_h = c.stride_h;
+    p.str_w = c.stride_w;
+    magic_of((uint32_t)c.c, p.dC);
+    magic_of((uint32_t)c.s, p.dS);
+    magic_of((uint32_t)(ho * wo), p.dP);
+    magic_of((uint32_t)wo, p.dW);
+    const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
+    if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+    const dim3 grid((unsigned)gx);
+    const bool wide = g.m > 8;
+    if (g.kbp == 32) launch_row_conv_g<4>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 64) launch_row_conv_g<8>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 128) launch_row_conv_g<16>(p, grid, wide, g.rounding, s);
     else return HBFP_ERR_FORMAT;
     return launch_status();
 }

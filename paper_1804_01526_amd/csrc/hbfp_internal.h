@@ -31,6 +31,8 @@ struct EncodeGeom {
 // encode.hip
 int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
 int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
+int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
+                         uint8_t *exps, hipStream_t s);
 int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
                           uint32_t *tile_amax, hipStream_t s);
 

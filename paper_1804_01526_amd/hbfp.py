@@ -33,6 +33,16 @@ class Format(ctypes.Structure):
                 ("k_slot", ctypes.c_int64)]
 
 
+class Conv2d(ctypes.Structure):
+    """hbfp_conv2d: NHWC input, filter r x s, zero padding and strides."""
+    _fields_ = [("n", ctypes.c_int64), ("h", ctypes.c_int64), ("w", ctypes.c_int64), ("c", ctypes.c_int64),
+                ("r", ctypes.c_int32), ("s", ctypes.c_int32), ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32),
+                ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32)]
+
+    def out_hw(self):
+        return ((self.h + 2 * self.pad_h - self.r) // self.stride_h + 1, (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1)
+
+
 class TensorDesc(ctypes.Structure):
     """hbfp_tensor: an encoded operand (layout in include/hbfp.h)."""
     _fields_ = [("mant", ctypes.c_void_p), ("exps", ctypes.c_void_p),
@@ -60,6 +70,7 @@ def _load():
     lib.hbfp_encode_workspace.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_encode.argtypes = [vp, i64, i64, i64, i32, F, T, vp, sz, vp]
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
+    lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp]
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
@@ -75,7 +86,7 @@ def _load():
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -305,6 +316,17 @@ def _desc_array(outs):
     for i, t in enumerate(outs):
         arr[i] = ctypes.pointer(t.desc)
     return arr
+
+
+def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, out: Optional[BfpTensor] = None, stream=None) -> BfpTensor:
+    """hbfp_encode_im2col on an NHWC FP32 device tensor: the lowered activation operand of a convolution."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and tuple(x.shape) == (conv.n, conv.h, conv.w, conv.c)
+    ho, wo = conv.out_hw()
+    if out is None:
+        out = alloc(fmt, conv.n * ho * wo, conv.r * conv.s * conv.c, 1, x.device)
+    _check(_lib.hbfp_encode_im2col(_dev_ptr(x), ctypes.byref(conv), ctypes.byref(out.desc), _stream_ptr(stream)),
+           "hbfp_encode_im2col")
+    return out
 
 
 def encode_multi_workspace(outs) -> int:

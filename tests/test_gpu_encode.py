@@ -113,6 +113,46 @@ def test_encode_exponent_blocks_longer_than_stored_blocks(hb, rows, cols, axis, 
     np.testing.assert_array_equal(back.cpu().numpy(), ref.decode(want))
 
 
+CONV_CASES = [
+    # n, h, w, c, r, s, pad_h, pad_w, stride_h, stride_w, block, m, rounding
+    (2, 9, 10, 16, 3, 3, 1, 1, 1, 1, 32, 8, 0), (3, 8, 7, 8, 3, 3, 1, 1, 1, 1, 24, 8, 1), (2, 12, 11, 40, 1, 1, 0, 0, 1, 1, 8, 8, 0),
+    (2, 11, 13, 24, 5, 3, 2, 1, 2, 1, 64, 12, 0), (1, 14, 14, 32, 3, 3, 0, 0, 2, 2, 128, 8, 1), (5, 6, 6, 16, 3, 3, 1, 1, 1, 1, 16, 4, 0),
+    (2, 7, 9, 48, 2, 4, 1, 2, 1, 3, 40, 12, 1), (1, 28, 28, 128, 3, 3, 1, 1, 1, 1, 32, 8, 0),
+]
+
+
+@pytest.mark.parametrize("n,h,w,c,r,s,ph,pw,sh,sw,B,m,rounding", CONV_CASES)
+def test_encode_im2col_equals_encoding_the_lowered_matrix(hb, n, h, w, c, r, s, ph, pw, sh, sw, B, m, rounding):
+    """hbfp_encode_im2col against the oracle's encode of the oracle's lowered matrix, bit for bit."""
+    print(f"[case] conv n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) block={B} m={m} rounding={rounding}", flush=True)
+    x = _data((n, h, w, c), n + 3 * h + 5 * w + c)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(m, 1, B, rounding, 0xC0DE))
+    torch.cuda.synchronize()
+    low = ref.im2col(x, r, s, ph, pw, sh, sw)
+    assert (bt.desc.src_rows, bt.desc.src_cols) == low.shape
+    want = ref.encode(low, 1, B, m, rounding, 0xC0DE)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+
+
+def test_encode_im2col_argument_checks(hb):
+    x = torch.zeros((2, 8, 8, 16), device="cuda")
+    conv = hb.Conv2d(2, 8, 8, 16, 3, 3, 1, 1, 1, 1)
+    for fmt, status in ((hb.make_format(8, 1, 20), hb.ERR_FORMAT), (hb.make_format(8, 1, 0), hb.ERR_FORMAT),
+                        (hb.make_format(8, 2, 32), hb.ERR_FORMAT)):
+        with pytest.raises(hb.HbfpError) as e:
+            hb.encode_im2col(x, conv, fmt)
+        assert e.value.status == status
+    with pytest.raises(hb.HbfpError) as e:                          # descriptor of another shape
+        hb.encode_im2col(x, conv, hb.make_format(8, 1, 32), out=hb.alloc(hb.make_format(8, 1, 32), 100, 144, 1))
+    assert e.value.status == hb.ERR_LAYOUT
+    with pytest.raises(hb.HbfpError) as e:                          # channels not a multiple of 8
+        hb.encode_im2col(torch.zeros((1, 8, 8, 12), device="cuda"), hb.Conv2d(1, 8, 8, 12, 3, 3, 1, 1, 1, 1), hb.make_format(8, 1, 24))
+    assert e.value.status == hb.ERR_FORMAT
+
+
 REGISTER_TILE_CASES = [
     # tiles of at most 32 x 32 with column counts and tile widths that are multiples of 4: the register-tile kernel
     # rows, cols, br, bc, m, rounding

@@ -351,6 +351,30 @@ def test_four_bit_limb_identity_and_scale_bytes_exhaustive():
 
 
 # ---------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("h,w,c,r,s,pad_h,pad_w,sh,sw", [(5, 6, 3, 3, 3, 1, 1, 1, 1), (7, 5, 2, 3, 2, 0, 1, 2, 1), (4, 4, 4, 1, 1, 0, 0, 1, 1),
+                                                         (6, 7, 2, 5, 3, 2, 1, 2, 3)])
+def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h, pad_w, sh, sw):
+    """The lowered operand against the textbook definition: y[img, oy, ox, f] = sum over (fr, fs, ch) of
+    x[img, oy*sh - pad_h + fr, ox*sw - pad_w + fs, ch] * wgt[fr, fs, ch, f], by brute-force loops."""
+    rng = np.random.default_rng(h * 100 + w)
+    n, f = 2, 3
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float64)
+    wgt = rng.integers(-3, 4, size=(r, s, c, f)).astype(np.float64)
+    ho, wo = (h + 2 * pad_h - r) // sh + 1, (w + 2 * pad_w - s) // sw + 1
+    want = np.zeros((n, ho, wo, f))
+    for img in range(n):
+        for oy in range(ho):
+            for ox in range(wo):
+                for fr in range(r):
+                    for fs in range(s):
+                        iy, ix = oy * sh - pad_h + fr, ox * sw - pad_w + fs
+                        if 0 <= iy < h and 0 <= ix < w:
+                            for ch in range(c):
+                                want[img, oy, ox, :] += x[img, iy, ix, ch] * wgt[fr, fs, ch, :]
+    got = ref.im2col(x, r, s, pad_h, pad_w, sh, sw) @ wgt.reshape(r * s * c, f)
+    np.testing.assert_array_equal(got.reshape(n, ho, wo, f), want)
+
+
 def test_gemm_is_the_fp64_product():
     rng = np.random.default_rng(17)
     A = rng.standard_normal((37, 129)).astype(np.float32)
