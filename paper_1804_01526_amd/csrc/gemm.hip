@@ -102,10 +102,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    int tm, tn;
-    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    int tm, tn, split = 0;
+    if (p.splits > 1 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
+                     : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
+        return;                                                                  // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-    const int split = blockIdx.y;
     const int st_begin = split * p.stages_per_split;
     int st_end = st_begin + p.stages_per_split;
     if (st_end > p.nstage) st_end = p.nstage;
@@ -322,10 +323,11 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     const int wm = wave & 3, wn = wave >> 2;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    int tm, tn;
-    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    int tm, tn, split = 0;
+    if (p.splits > 1 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
+                     : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
+        return;                                                                  // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
-    const int split = blockIdx.y;
     const int st_begin = 2 * split * p.stages_per_split;                         // in 64-byte stages
     int st_end = st_begin + 2 * p.stages_per_split;
     if (st_end > 2 * p.nstage) st_end = 2 * p.nstage;
@@ -564,6 +566,7 @@ static int choose_splits(int64_t M, int64_t N, int64_t nstage, int64_t stages_pe
     int64_t s = ceil_div(512, tiles);
     if (s > units / 4) s = units / 4;
     if (s > 128) s = 128;
+    if (s > 8) s -= s % 8;                             // the k ranges are dealt to the 8 XCDs in turn: keep them level
     return s < 1 ? 1 : (int)s;
 }
 
@@ -616,7 +619,7 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
         p.stages_per_split = (int32_t)(ceil_div(units, p.splits) * stages_per_block);
         p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
     }
-    const dim3 grid((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
+    const dim3 grid(p.splits > 1 ? (unsigned)(8 * tm * tn * ceil_div(p.splits, 8)) : (unsigned)(ceil_div(tm * tn, 8) * 8));
     int rc;
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);

@@ -26,6 +26,22 @@ __device__ __forceinline__ bool tile_of_workgroup(int wg, int tiles_m, int tiles
     return true;
 }
 
+// Split-K launches (few tiles, very long k): a one-dimensional grid of 8 * tiles * ceil(splits / 8) workgroups.
+// XCD x takes the k ranges x, x + 8, ... and, for each, every tile: the tiles of one k range share their operand
+// panels in that XCD's L2, and the work is spread over all 8 XCDs however few tiles there are (dealing tiles to
+// XCDs as above would leave XCDs idle when there are fewer than 8 tiles).  Returns false for padding workgroups.
+__device__ __forceinline__ bool tile_and_split_of_workgroup(int wg, int tiles_m, int tiles_n, int splits, int &tm, int &tn,
+                                                            int &split) {
+    const int ntiles = tiles_m * tiles_n;
+    const int slot = wg >> 3;
+    split = (slot / ntiles) * 8 + (wg & 7);
+    if (split >= splits) return false;
+    const int t = slot % ntiles;
+    tn = t / tiles_m;
+    tm = t - tn * tiles_m;
+    return true;
+}
+
 __device__ __forceinline__ void async_copy16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
 }
