@@ -37,6 +37,9 @@ namespace hbfp {
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
+struct __attribute__((aligned(4))) Bytes12 {   // 12 bytes stored at a 4-byte aligned address
+    uint32_t a, b, c;
+};
 
 // limbs of 4 magnitude bits that a mantissa of m bits (sign included) needs
 inline int limbs_of(int m) { return m <= 5 ? 1 : m <= 9 ? 2 : 3; }
@@ -63,8 +66,84 @@ struct PackParams {
     int32_t mark;
 };
 
+// Scale bytes of the limbs of one group of 32 codes with stored exponent byte E; `bad` if one is out of range.
+template <int L>
+__device__ __forceinline__ uint32_t mx_scale_word(int E, int m, bool &bad) {
+    E = E > 254 ? 254 : E;
+    uint32_t word = 0;
+    bad = false;
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        int byte = E + 5 + 4 * (L - 1 - j) - m;
+        if (byte < 0 || byte > 254) {
+            bad = true;
+            byte = byte < 0 ? 0 : 254;
+        }
+        word |= (uint32_t)byte << (8 * j);
+    }
+    return word;
+}
+
+// int8 mantissas: a lane converts 16 consecutive mantissas (one 16-byte load; the 4 lanes of a row read its 64 bytes
+// of the k-step, so a wave instruction reads 16 whole 64-byte pieces) into the 12 bytes they occupy in each limb plane.
+template <int L>
+__device__ __forceinline__ void mx_pack_block_i8(const PackParams &p, uint32_t block) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
+    const int64_t rt = block / p.nks4;
+    const int ks = (int)(block % p.nks4) * 4 + wave;
+    if (ks >= p.ksteps) return;
+    const int q = lane & 3;                                   // quarter of the k-step: 16 mantissas
+    const int kb = 2 * ks + (q >> 1);                         // 32-element chunk of the stored row
+    uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
+    v4i raw[2];
+    int E[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t row = rt * 32 + h * 16 + (lane >> 2);
+        const int64_t rs = row < p.R ? row : 0;               // rows past the end read row 0 and store zeros
+        raw[h] = *reinterpret_cast<const v4i *>(reinterpret_cast<const int8_t *>(p.mant) + rs * p.kpad + (int64_t)ks * 64 + q * 16);
+        E[h] = p.exps[rs * p.exp_ld + kb / p.chunks32_per_block];
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = h * 16 + (lane >> 2);
+        const bool live = rt * 32 + r < p.R;
+        // four mantissas per register at a time: |v| byte-wise (v = -128 does not occur), limbs and signs as bytes,
+        // then the four 6-bit codes of a register squeezed into 24 bits and four such groups laid end to end
+        uint32_t g[L][4], any = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t x = live ? (uint32_t)raw[h][i] : 0u;
+            const uint32_t sg = (x >> 7) & 0x01010101u;                   // 1 in the bytes of negative mantissas
+            const uint32_t a = (x ^ (sg * 255u)) + sg;                    // byte-wise two's complement negation
+            any |= a;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                const uint32_t w = ((a >> (4 * (L - 1 - j))) & 0x0f0f0f0fu) | (sg << 5);       // codes, one per byte
+                const uint32_t t = (w & 0x003f003fu) | ((w >> 2) & 0x0fc00fc0u);              // two 12-bit pairs
+                g[j][i] = (t & 0xfffu) | ((t >> 4) & 0xfff000u);
+            }
+        }
+        bool bad;
+        const uint32_t word = live ? mx_scale_word<L>(E[h], p.m, bad) : (bad = false, 0u);
+        if (bad && any) p.header[0] = p.mark;                 // all-zero groups (padding) take any exponent
+        const int lo = r + 32 * (q >> 1);                     // the lane of the matrix instruction that owns these codes
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            const Bytes12 three = {g[j][0] | (g[j][1] << 24), (g[j][1] >> 8) | (g[j][2] << 16), (g[j][2] >> 16) | (g[j][3] << 8)};
+            *reinterpret_cast<Bytes12 *>(chunk + j * kLimbBytes + lo * 24 + (q & 1) * 12) = three;
+        }
+        if ((q & 1) == 0) *reinterpret_cast<uint32_t *>(chunk + L * kLimbBytes + lo * 4) = word;
+    }
+}
+
 template <int L, typename MT>
 __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t block) {
+    if constexpr (sizeof(MT) == 1) {
+        mx_pack_block_i8<L>(p, block);
+        return;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
     const int64_t rt = block / p.nks4;
@@ -85,33 +164,7 @@ __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t bloc
 #pragma unroll
         for (int i = 0; i < NV; ++i) raw[i] = reinterpret_cast<const v4i *>(src)[i];
         uint32_t any = 0;
-        if constexpr (sizeof(MT) == 1) {
-            // four int8 mantissas per register at a time: |v| byte-wise (v = -128 does not occur), limbs and signs
-            // as bytes, then the four 6-bit codes of a register squeezed into 24 bits and eight such groups laid end
-            // to end in the six registers of a limb
-            uint32_t g[L][8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t x = (uint32_t)raw[i >> 2][i & 3];
-                const uint32_t sg = (x >> 7) & 0x01010101u;               // 1 in the bytes of negative mantissas
-                const uint32_t a = (x ^ (sg * 255u)) + sg;                // byte-wise two's complement negation
-                any |= a;
-#pragma unroll
-                for (int j = 0; j < L; ++j) {
-                    const uint32_t w = ((a >> (4 * (L - 1 - j))) & 0x0f0f0f0fu) | (sg << 5);   // codes, one per byte
-                    const uint32_t t = (w & 0x003f003fu) | ((w >> 2) & 0x0fc00fc0u);          // two 12-bit pairs
-                    g[j][i] = (t & 0xfffu) | ((t >> 4) & 0xfff000u);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < L; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    limb[j][3 * h + 0] = g[j][4 * h] | (g[j][4 * h + 1] << 24);
-                    limb[j][3 * h + 1] = (g[j][4 * h + 1] >> 8) | (g[j][4 * h + 2] << 16);
-                    limb[j][3 * h + 2] = (g[j][4 * h + 2] >> 16) | (g[j][4 * h + 3] << 8);
-                }
-        } else {
+        {
 #pragma unroll
             for (int e = 0; e < 32; ++e) {
                 const int v = (int)(int16_t)((uint32_t)raw[e >> 3][(e >> 1) & 3] >> (16 * (e & 1)));
@@ -127,18 +180,8 @@ __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t bloc
                 }
             }
         }
-        int E = p.exps[row * p.exp_ld + kb / p.chunks32_per_block];
-        E = E > 254 ? 254 : E;
-        bool bad = false;
-#pragma unroll
-        for (int j = 0; j < L; ++j) {
-            int byte = E + 5 + 4 * (L - 1 - j) - p.m;
-            if (byte < 0 || byte > 254) {
-                bad = true;
-                byte = byte < 0 ? 0 : 254;
-            }
-            word |= (uint32_t)byte << (8 * j);
-        }
+        bool bad;
+        word = mx_scale_word<L>(p.exps[row * p.exp_ld + kb / p.chunks32_per_block], p.m, bad);
         if (bad && any) p.header[0] = p.mark;                 // all-zero groups (padding) take any exponent
     }
     uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
