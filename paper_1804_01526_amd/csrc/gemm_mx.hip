@@ -668,12 +668,9 @@ bool gemm_mx_ok(const GemmArgs &a) {
     if ((double)a.M * (double)a.N < 0.75 * 65536.0 * (double)tiles) return false;   // ragged edges would waste the tiles
     if ((double)a.M * (double)a.N * (double)a.kpad < 6.0e10) return false;          // too short to repay the packing
     const int products = limbs_of(a.mA) * limbs_of(a.mB);
-    if (products == 4) {
-        if (a.kbp != 32) return false;
-        // blocks of exactly 32: a tie at 4096^3, 20 % ahead at 8192^3; shorter blocks, stored padded to 32, cost the
-        // int8 kernel a scaling pass per padded block as well: ahead from 4096^3 on
-        return a.kblock < 32 || (double)a.M * (double)a.N * (double)a.kpad >= 2.0e11;
-    }
+    // blocks of exactly 32: 3 to 8 % ahead at 4096^3, 20 % at 8192^3; shorter blocks, stored padded to 32, cost the int8
+    // kernel a scaling pass per padded block as well: 15 to 20 % ahead at 4096^3
+    if (products == 4) return a.kbp == 32;
     return true;
 }
 

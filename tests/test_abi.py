@@ -211,12 +211,14 @@ def test_gemm_select_validation():
     # one 256-row panel per operand, 4 k-steps of 64, two limbs: 8 row tiles x (2 x 1536 + 256) bytes per k-step
     assert n_scaled >= n_int8 + 2 * 4 * 8 * 3328
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_SCALED, fake, n_int8, None) == hbfp.ERR_WORKSPACE
-    # automatic choice on a 4096^3 product: blocks of 24 (padded to 32) -> block-scaled; blocks of 32 (a tie at this
-    # size) and of 64 -> int8; 12-bit and 4-bit mantissas -> block-scaled
+    # automatic choice on a 4096^3 product: blocks of 24 (padded to 32) and of 32 -> block-scaled; blocks of 64 -> int8;
+    # 12-bit and 4-bit mantissas -> block-scaled; a 2048^3 product (64 tiles of 256 x 256) -> int8
     def auto_is_scaled(m, blk):
         x, w = desc(m, 4096, 4096, 1, 1, blk), desc(m, 4096, 4096, 0, blk, 1)
         return hbfp.gemm_workspace(x, w) > hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
-    assert not auto_is_scaled(8, 32) and auto_is_scaled(8, 24) and not auto_is_scaled(8, 64)
+    assert auto_is_scaled(8, 32) and auto_is_scaled(8, 24) and not auto_is_scaled(8, 64)
+    x, w = desc(8, 2048, 2048, 1, 1, 32), desc(8, 2048, 2048, 0, 32, 1)
+    assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
     assert auto_is_scaled(12, 64) and auto_is_scaled(4, 64) and auto_is_scaled(5, 24)
     # narrow output: tiles of 256 x 256 would be half empty
     x, w = desc(8, 100352, 1152, 1, 1, 32), desc(8, 1152, 128, 0, 32, 1)
