@@ -252,6 +252,18 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                                 "TOPS_kernel": round(flops / ms_k / 1e9, 1),
                                 "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1),
                                 "note": "activation operand from the 51 MB image tensor instead of the 462 MB lowered matrix"}
+    del ta, tb, out, ws
+    # ... and its weight gradient dW [1152, 128] = lowered(X)^T dY with the lowered operand gathered the same way
+    ta, tb = hbfp.alloc(col, 100352, 1152, 0), hbfp.encode(dY, 0, col)
+    out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")
+    hbfp.encode_im2col(img, conv, col, 0, out=ta)
+    ms_k = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws), reps)
+    ms_ea = _time_call(torch, lambda: hbfp.encode_im2col(img, conv, col, 0, out=ta), reps)
+    ms_eb = _time_call(torch, lambda: hbfp.encode(dY, 0, col, out=tb), reps)
+    res["c3_wgrad_from_image"] = {"gemm_ms": round(ms_k, 4), "encode_im2col_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+                                  "TOPS_kernel": round(flops / ms_k / 1e9, 1),
+                                  "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
     del ta, tb, out, ws, img
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the

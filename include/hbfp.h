@@ -171,12 +171,15 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  *   x     device FP32 tensor [n][h][w][c] (channels innermost), 16-byte aligned
  *   conv  geometry: filter r x s, zero padding pad_h / pad_w on each side, strides; output size
  *         ho = (h + 2 pad_h - r) / stride_h + 1, wo likewise
- *   out   descriptor from hbfp_plan(fmt, rows = n*ho*wo, cols = r*s*c, contract_axis = 1) with mant/exps set:
- *         operand row (img, oy, ox) holds the values under the filter window, k = (fr * s + fs) * c + ch,
- *         zero where the window leaves the image.  The result is bit for bit what hbfp_encode gives for the
- *         materialised lowered matrix (same logical indices for stochastic rounding).
- * Supported formats: 1-D blocks along k of at most 128 elements, block length and c multiples of 8
- * (HBFP_ERR_FORMAT otherwise).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
+ *   out   descriptor from hbfp_plan(fmt, rows = n*ho*wo, cols = r*s*c, contract_axis) with mant/exps set.  The
+ *         lowered matrix has one row per output position (img, oy, ox) holding the values under the filter
+ *         window, column (fr * s + fs) * c + ch, zero where the window leaves the image.  contract_axis 1 gives
+ *         the operand of the forward product (k runs along the window), contract_axis 0 that of the weight
+ *         gradient (operand rows = window entries, k runs over the output positions).  The result is bit for
+ *         bit what hbfp_encode gives for the materialised lowered matrix (same logical indices for stochastic
+ *         rounding).
+ * Supported formats: 1-D blocks along k; contract_axis 1: at most 128 elements, block length and c multiples
+ * of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
  * convolution's.
  */
 typedef struct hbfp_conv2d {

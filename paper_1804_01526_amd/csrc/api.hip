@@ -277,9 +277,10 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     const int64_t ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
     const int64_t wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
     if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || ho * wo > 0x7fffffff) return HBFP_ERR_ARG;
-    if (out->contract_axis != 1 || out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c)
-        return HBFP_ERR_LAYOUT;
-    if (out->rblock != 1 || out->kshare != 1 || out->kblock > 128 || (out->kblock & 7) || (conv->c & 7)) return HBFP_ERR_FORMAT;
+    if (out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
+    if (out->src_rows > 0x7fffffff || out->src_cols > 0x7fffffff) return HBFP_ERR_ARG;
+    if (out->rblock != 1 || out->kshare != 1) return HBFP_ERR_FORMAT;
+    if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7)) : out->kblock > 64) return HBFP_ERR_FORMAT;
     const EncodeGeom g = geom_of(*out, 0);
     return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, (hipStream_t)stream);
 }

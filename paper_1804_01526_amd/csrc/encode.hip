@@ -313,12 +313,16 @@ struct ColParams {
     const uint32_t *table;
     int64_t rblock_t, ntc;
     int32_t spb, kshare;
+    // CONV: the source is an NHWC image tensor; operand row = (fr * S + fs) * C + ch of the lowered matrix, k = the
+    // output position (img, oy, ox): the operand of the weight-gradient product, never materialised
+    int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
+    uint32_t dC[2], dS[2], dP[2], dW[2];
 };
 
 constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
 constexpr int kColStride = 528;     // padded LDS row stride: 16-byte writes of 16 lanes hit 16 bank groups
 
-template <int KBP, bool WIDE, int ROUND, bool TABLE>
+template <int KBP, bool WIDE, int ROUND, bool TABLE, bool CONV = false>
 __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     constexpr int ESZ = WIDE ? 2 : 1;
     constexpr int NBT = kColRowBytes / (KBP * ESZ);  // exponent blocks per tile row: 16, 8, 8 or 4
@@ -326,11 +330,20 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     __shared__ __attribute__((aligned(4))) uint8_t etile[64 * NBT];
     __shared__ uint32_t lane_amax[4][64];
 
-    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    // the wave index as a scalar: block indices, block lengths and (CONV) output positions stay on the scalar unit
+    const int t = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const int64_t r = (int64_t)(blockIdx.x % p.row_groups) * p.lanes + lane;
     const int64_t blk0 = (int64_t)(blockIdx.x / p.row_groups) * NBT;
     const bool r_ok = lane < p.lanes && r < p.R;
     const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
+    int conv_fr = 0, conv_fs = 0, conv_ch = 0;          // CONV: this lane's filter tap and channel
+    if (CONV) {
+        const uint32_t rr = r_ok ? (uint32_t)r : 0u;
+        const uint32_t tap = div_magic(rr, p.dC);
+        conv_ch = (int)(rr - tap * (uint32_t)p.cC);
+        conv_fr = (int)div_magic(tap, p.dS);
+        conv_fs = (int)(tap - (uint32_t)conv_fr * (uint32_t)p.cS);
+    }
 
     for (int bi = wave; bi < NBT; bi += 4) {
         const int64_t piece = blk0 + bi;                                  // stored piece of KBP elements
@@ -345,8 +358,21 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
         const int64_t kfirst = (blk < p.nblk ? blk : 0) * p.kblock + (blen ? sub : 0);
         const float *s = p.src + kfirst * p.ld + (r_ok ? r : 0);
         float v[KBP];
+        if (!CONV) {
 #pragma unroll
-        for (int kk = 0; kk < KBP; ++kk) v[kk] = (kk < blen && r_ok) ? s[(int64_t)kk * p.ld] : 0.0f;
+            for (int kk = 0; kk < KBP; ++kk) v[kk] = (kk < blen && r_ok) ? s[(int64_t)kk * p.ld] : 0.0f;
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KBP; ++kk) {
+                // the output position is the same for the whole wave; the window offset is the lane's
+                const uint32_t pos = (uint32_t)kfirst + (uint32_t)(kk < blen ? kk : 0);
+                const uint32_t img = div_magic(pos, p.dP), rem = pos - img * (uint32_t)(p.cHo * p.cWo);
+                const uint32_t oy = div_magic(rem, p.dW), ox = rem - oy * (uint32_t)p.cWo;
+                const int iy = (int)oy * p.str_h - p.pad_h + conv_fr, ix = (int)ox * p.str_w - p.pad_w + conv_fs;
+                const bool inside = kk < blen && r_ok && iy >= 0 && iy < p.cH && ix >= 0 && ix < p.cW;
+                v[kk] = inside ? p.src[(((int64_t)img * p.cH + iy) * p.cW + ix) * p.cC + conv_ch] : 0.0f;
+            }
+        }
         uint32_t amax = 0;
 #pragma unroll
         for (int kk = 0; kk < KBP; ++kk) amax = max(amax, __float_as_uint(v[kk]) & 0x7fffffffu);
@@ -423,6 +449,14 @@ void launch_col_k(const ColParams &p, dim3 grid, bool wide, int rounding, hipStr
     else if (!wide) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 1, false>), grid, dim3(kThreads), 0, s, p);
     else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, true, 0, false>), grid, dim3(kThreads), 0, s, p);
     else hipLaunchKernelGGL((enc_col_kernel<KBP, true, 1, false>), grid, dim3(kThreads), 0, s, p);
+}
+
+template <int KBP>
+void launch_col_conv_k(const ColParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
+    if (!wide && rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 0, false, true>), grid, dim3(kThreads), 0, s, p);
+    else if (!wide) hipLaunchKernelGGL((enc_col_kernel<KBP, false, 1, false, true>), grid, dim3(kThreads), 0, s, p);
+    else if (rounding == 0) hipLaunchKernelGGL((enc_col_kernel<KBP, true, 0, false, true>), grid, dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_col_kernel<KBP, true, 1, false, true>), grid, dim3(kThreads), 0, s, p);
 }
 
 void launch_col_table(const ColParams &p, dim3 grid, bool wide, int rounding, hipStream_t s) {
@@ -692,6 +726,58 @@ static void magic_of(uint32_t d, uint32_t (&magic)[2]) {
 // The activation operand of a convolution, converted straight from the NHWC tensor (1-D blocks along k = (r, s, c)).
 int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
                          uint8_t *exps, hipStream_t s) {
+    if (g.axis == 0) {
+        // weight-gradient orientation: operand rows = (filter tap, channel), k = output positions
+        ColParams p;
+        p.src = x;
+        p.mant = (uint8_t *)mant;
+        p.exps = exps;
+        p.ld = 0;
+        p.R = g.R;
+        p.K = g.K;
+        p.kpad = g.kpad;
+        p.exp_ld = g.exp_ld;
+        p.src_cols = g.src_cols;
+        if (g.nblk > 0x7fffffff || g.R > 0x7fffffff || g.K > 0x7fffffff) return HBFP_ERR_ARG;
+        p.kblock = (int32_t)g.kblock;
+        p.nblk = (int32_t)g.nblk;
+        p.nb_stored = (int32_t)(g.kpad / g.kbp);
+        p.m = g.m;
+        p.s0 = g.seed_lo;
+        p.s1 = g.seed_hi;
+        p.rblock = 1;
+        p.lanes = 64;
+        p.table = nullptr;
+        p.rblock_t = 1;
+        p.ntc = 0;
+        p.spb = 1;
+        p.kshare = 1;
+        p.cH = (int32_t)c.h;
+        p.cW = (int32_t)c.w;
+        p.cC = (int32_t)c.c;
+        p.cS = c.s;
+        p.cHo = (int32_t)ho;
+        p.cWo = (int32_t)wo;
+        p.pad_h = c.pad_h;
+        p.pad_w = c.pad_w;
+        p.str_h = c.stride_h;
+        p.str_w = c.stride_w;
+        magic_of((uint32_t)c.c, p.dC);
+        magic_of((uint32_t)c.s, p.dS);
+        magic_of((uint32_t)(ho * wo), p.dP);
+        magic_of((uint32_t)wo, p.dW);
+        const bool wide = g.m > 8;
+        const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
+        const int64_t nb_cover = p.nb_stored > g.exp_ld ? p.nb_stored : g.exp_ld;
+        const int64_t gx = ceil_div(g.R, 64), gy = ceil_div(nb_cover, nbt);
+        if (gx > 0x7fffffff || gx * gy > 0x7fffffff) return HBFP_ERR_ARG;
+        p.row_groups = (uint32_t)gx;
+        const dim3 grid((unsigned)(gx * gy));
+        if (g.kbp == 32) launch_col_conv_k<32>(p, grid, wide, g.rounding, s);
+        else if (g.kbp == 64) launch_col_conv_k<64>(p, grid, wide, g.rounding, s);
+        else return HBFP_ERR_FORMAT;
+        return launch_status();
+    }
     RowParams p;
     p.src = x;
     p.mant = (uint8_t *)mant;

@@ -318,12 +318,14 @@ def _desc_array(outs):
     return arr
 
 
-def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, out: Optional[BfpTensor] = None, stream=None) -> BfpTensor:
-    """hbfp_encode_im2col on an NHWC FP32 device tensor: the lowered activation operand of a convolution."""
+def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, contract_axis: int = 1, out: Optional[BfpTensor] = None,
+                  stream=None) -> BfpTensor:
+    """hbfp_encode_im2col on an NHWC FP32 device tensor: the lowered activation operand of a convolution
+    (contract_axis 1: forward product, 0: weight gradient)."""
     assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and tuple(x.shape) == (conv.n, conv.h, conv.w, conv.c)
     ho, wo = conv.out_hw()
     if out is None:
-        out = alloc(fmt, conv.n * ho * wo, conv.r * conv.s * conv.c, 1, x.device)
+        out = alloc(fmt, conv.n * ho * wo, conv.r * conv.s * conv.c, contract_axis, x.device)
     _check(_lib.hbfp_encode_im2col(_dev_ptr(x), ctypes.byref(conv), ctypes.byref(out.desc), _stream_ptr(stream)),
            "hbfp_encode_im2col")
     return out

@@ -137,6 +137,29 @@ def test_encode_im2col_equals_encoding_the_lowered_matrix(hb, n, h, w, c, r, s, 
     np.testing.assert_array_equal(mant, want.mant)
 
 
+CONV_WGRAD_CASES = [
+    # n, h, w, c, r, s, pad_h, pad_w, stride_h, stride_w, block (output positions), m, rounding
+    (2, 9, 10, 16, 3, 3, 1, 1, 1, 1, 32, 8, 0), (3, 8, 7, 5, 3, 3, 1, 1, 1, 1, 24, 8, 1), (2, 12, 11, 40, 1, 1, 0, 0, 1, 1, 8, 8, 0),
+    (2, 11, 13, 24, 5, 3, 2, 1, 2, 1, 64, 12, 0), (1, 14, 14, 33, 3, 3, 0, 0, 2, 2, 20, 8, 1), (4, 28, 28, 16, 3, 3, 1, 1, 1, 1, 32, 8, 0),
+]
+
+
+@pytest.mark.parametrize("n,h,w,c,r,s,ph,pw,sh,sw,B,m,rounding", CONV_WGRAD_CASES)
+def test_encode_im2col_weight_gradient_orientation(hb, n, h, w, c, r, s, ph, pw, sh, sw, B, m, rounding):
+    """contract_axis 0: operand rows = window entries, k = output positions in blocks of B; bit for bit the oracle's
+    encode of the oracle's lowered matrix with B x 1 blocks."""
+    print(f"[case] conv wgrad n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) block={B} m={m} rounding={rounding}", flush=True)
+    x = _data((n, h, w, c), 2 * n + 3 * h + 5 * w + c)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(m, B, 1, rounding, 0xFACE), contract_axis=0)
+    torch.cuda.synchronize()
+    low = ref.im2col(x, r, s, ph, pw, sh, sw)
+    want = ref.encode(low, B, 1, m, rounding, 0xFACE)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+
+
 def test_encode_im2col_argument_checks(hb):
     x = torch.zeros((2, 8, 8, 16), device="cuda")
     conv = hb.Conv2d(2, 8, 8, 16, 3, 3, 1, 1, 1, 1)
