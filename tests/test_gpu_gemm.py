@@ -202,6 +202,34 @@ def test_config3_conv_shapes_sampled(hb):
     _run(hb, np.ascontiguousarray(X.T), dY, f_row, f_col, partials=False, rows=krows)     # dW = X^T dY
 
 
+def test_convolution_products_from_the_image_tensor(hb):
+    """A 3 x 3 convolution executed as matrix products (Sec. 5.1) without the lowered matrix in memory: forward
+    Y = lowered(X) W and weight gradient dW = lowered(X)^T dY, the lowered operand coming from hbfp_encode_im2col,
+    against the oracle's encode of its own lowered matrix and the FP64 product."""
+    rng = np.random.default_rng(31)
+    n, h, w, c, f = 4, 12, 13, 16, 40
+    x = np.maximum(rng.standard_normal((n, h, w, c)), 0).astype(np.float32)
+    wmat = (rng.standard_normal((9 * c, f)) * 0.1).astype(np.float32)
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1)
+    low = ref.im2col(x, 3, 3, 1, 1)
+    dy = (rng.standard_normal((low.shape[0], f)) * 1e-2).astype(np.float32)
+    xg = torch.from_numpy(x).cuda()
+    # forward
+    ta = hb.encode_im2col(xg, conv, hb.make_format(8, 1, 32))
+    tb = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, 32, 1))
+    y = hb.gemm(ta, tb)
+    torch.cuda.synchronize()
+    want = ref.gemm(ref.decode(ref.encode(low, 1, 32, 8)), ref.decode(ref.encode(wmat, 32, 1, 8)))
+    assert rel_fro(y.cpu().numpy(), want) <= TOL
+    # weight gradient: contraction over the n * ho * wo output positions
+    ta = hb.encode_im2col(xg, conv, hb.make_format(8, 32, 1), contract_axis=0)
+    tb = hb.encode(torch.from_numpy(dy).cuda(), 0, hb.make_format(8, 32, 1))
+    dw = hb.gemm(ta, tb)
+    torch.cuda.synchronize()
+    want = ref.gemm(ref.decode(ref.encode(low, 32, 1, 8)).T, ref.decode(ref.encode(dy, 32, 1, 8)))
+    assert dw.shape == (9 * c, f) and rel_fro(dw.cpu().numpy(), want) <= TOL
+
+
 def test_lstm_gate_products_sampled(hb):
     """Gate products of an LSTM language model (the paper's second workload, Sec. 5.2): 35 steps x batch 20 = 700
     rows, hidden size 1500, four gates; forward, data gradient and weight gradient in config 4's formats (blocks of
