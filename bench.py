@@ -253,6 +253,21 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                                 "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1),
                                 "note": "activation operand from the 51 MB image tensor instead of the 462 MB lowered matrix"}
     del ta, tb, out, ws
+    # ... in the format of Sec. 5.1: one exponent per training input (gathered and converted from the image tensor,
+    # stored in blocks of 24) against the filter matrix in 24 x 24 tiles
+    per_input, tile24 = hbfp.make_format(8, 28 * 28, 0, k_slot=24), hbfp.make_format(8, 24, 24)
+    ta, tb = hbfp.alloc(per_input, 100352, 1152, 1), hbfp.encode(W, 0, tile24)
+    out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")
+    wse = torch.empty(max(hbfp.encode_workspace(ta.desc), 256), dtype=torch.uint8, device="cuda")
+    hbfp.encode_im2col(img, conv, per_input, out=ta, workspace=wse)
+    ms_k = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws), reps)
+    ms_ea = _time_call(torch, lambda: hbfp.encode_im2col(img, conv, per_input, out=ta, workspace=wse), reps)
+    ms_eb = _time_call(torch, lambda: hbfp.encode(W, 0, tile24, out=tb), reps)
+    res["c3_fwd_from_image_exponent_per_input_x_24x24_tiles"] = {
+        "gemm_ms": round(ms_k, 4), "encode_im2col_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+        "TOPS_kernel": round(flops / ms_k / 1e9, 1), "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
+    del ta, tb, out, ws, wse
     # ... and its weight gradient dW [1152, 128] = lowered(X)^T dY with the lowered operand gathered the same way
     ta, tb = hbfp.alloc(col, 100352, 1152, 0), hbfp.encode(dY, 0, col)
     out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")

@@ -179,7 +179,14 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  *         bit what hbfp_encode gives for the materialised lowered matrix (same logical indices for stochastic
  *         rounding).
  * Supported formats: 1-D blocks along k; contract_axis 1: at most 128 elements, block length and c multiples
- * of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
+ * of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).
+ * One exponent per training input (Sec. 5.1: the x tensor gets one exponent per training input), contract_axis 1:
+ * a format with block_rows = ho*wo (the rows of one image), block_cols = 0 and k_slot = the stored block length
+ * (a multiple of 8, at most 128).  The exponent is that of the largest value of the whole image x[img] (also of
+ * pixels no window reaches when the stride exceeds the filter), each value is converted as if the image had been
+ * converted once and lowered afterwards (stochastic rounding draws by the index in x, so a pixel gets the same
+ * mantissa in every window), and `workspace` must hold hbfp_encode_workspace(out) bytes (4 per image; HBFP_ERR_WORKSPACE);
+ * the other formats need no workspace (NULL, 0).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
  * convolution's.
  */
 typedef struct hbfp_conv2d {
@@ -188,7 +195,8 @@ typedef struct hbfp_conv2d {
     int32_t pad_h, pad_w;
     int32_t stride_h, stride_w;
 } hbfp_conv2d;
-int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *stream);
+int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
+                       void *stream);
 
 /*
  * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation

@@ -266,7 +266,8 @@ int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *co
     return HBFP_OK;
 }
 
-int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *stream) {
+int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
+                       void *stream) {
     if (!x || !conv || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
     if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
         conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0)
@@ -279,10 +280,18 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || ho * wo > 0x7fffffff) return HBFP_ERR_ARG;
     if (out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
     if (out->src_rows > 0x7fffffff || out->src_cols > 0x7fffffff) return HBFP_ERR_ARG;
-    if (out->rblock != 1 || out->kshare != 1) return HBFP_ERR_FORMAT;
+    // one exponent per training input (Sec. 5.1): the rows of one image and the whole window share it
+    const bool per_image = out->contract_axis == 1 && out->rblock == ho * wo && out->kshare >= out->nblk && out->kshare > 1;
+    if (!per_image && (out->rblock != 1 || out->kshare != 1)) return HBFP_ERR_FORMAT;
     if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7)) : out->kblock > 64) return HBFP_ERR_FORMAT;
+    uint32_t *table = nullptr;
+    if (per_image) {
+        const size_t need = align256((size_t)conv->n * 4);
+        if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+        table = (uint32_t *)workspace;
+    }
     const EncodeGeom g = geom_of(*out, 0);
-    return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, (hipStream_t)stream);
+    return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, table, (hipStream_t)stream);
 }
 
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {

@@ -62,6 +62,7 @@ struct RowParams {
     // (n, ho, wo) holds the values under the filter window, k = (r * S + s) * C + c, zero outside the image
     int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
     uint32_t dC[2], dS[2], dP[2], dW[2];   // divisions by C, S, Ho*Wo and Wo as multiply-high + shift (magic_of)
+    uint32_t dChunks[2], dGp[2], dR[2], dK[2];   // likewise by chunks, gp, rblock and kshare (GP = 0 only)
 };
 
 // n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
@@ -82,6 +83,7 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     float v[U][8];
     int n[U], cl[U];
     int64_t rows[U];
+    int64_t at[U];        // CONV with one exponent per image: index of the chunk's first value in the image tensor, else -1
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint64_t g = g0 + (uint64_t)u * kThreads;
@@ -90,6 +92,10 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         if (p.lpr_log2 >= 0) {                       // chunks per row is a power of two
             row = (int64_t)(g >> p.lpr_log2);
             cl[u] = (int)(g & (uint64_t)(p.chunks - 1));
+        } else if (GP == 0 && total <= 0x7fffffffull) {
+            const uint32_t q = div_magic((uint32_t)g, p.dChunks);
+            row = q;
+            cl[u] = (int)((uint32_t)g - q * (uint32_t)p.chunks);
         } else if (total <= 0xffffffffull) {
             const uint32_t q = (uint32_t)g / (uint32_t)p.chunks;
             row = q;
@@ -99,8 +105,8 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             cl[u] = (int)(g - (uint64_t)row * (uint64_t)p.chunks);
         }
         rows[u] = in ? row : -1;
-        const int gp = GP ? GP : p.gp;
-        const int blk = cl[u] / gp, j = cl[u] % gp;
+        const int blk = GP ? cl[u] / (GP ? GP : 1) : (int)div_magic((uint32_t)cl[u], p.dGp);
+        const int j = cl[u] - blk * (GP ? GP : p.gp);
         int cnt = 0;
         if (in && blk < p.nblk) {
             const int64_t k0 = (int64_t)blk * p.kblock;
@@ -123,7 +129,9 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             const int hi = (int)ho * p.str_h - p.pad_h + (int)fr, wi = (int)wo * p.str_w - p.pad_w + (int)fs;
             const bool inside = hi >= 0 && hi < p.cH && wi >= 0 && wi < p.cW;
             if (!inside) cnt = 0;                                        // zeros; they still count as elements of the block
-            s = p.src + (inside ? (((int64_t)img * p.cH + hi) * p.cW + wi) * p.cC + c0 : 0);
+            const int64_t off = inside ? (((int64_t)img * p.cH + hi) * p.cW + wi) * p.cC + c0 : 0;
+            s = p.src + off;
+            at[u] = (p.table && inside) ? off : -1;
         }
         if (cnt == 8 && p.vec_ok) {
             const float4 a = *reinterpret_cast<const float4 *>(s);
@@ -137,8 +145,8 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int gp = GP ? GP : p.gp;
-        const int blk = cl[u] / gp, j = cl[u] % gp;
+        const int blk = GP ? cl[u] / (GP ? GP : 1) : (int)div_magic((uint32_t)cl[u], p.dGp);
+        const int j = cl[u] - blk * (GP ? GP : p.gp);
         const int64_t row = rows[u];
         uint32_t amax = 0;
         if (GP) {
@@ -146,11 +154,15 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             for (int e = 0; e < 8; ++e) amax = max(amax, __float_as_uint(v[u][e]) & 0x7fffffffu);
             amax = group_max<(GP ? GP : 4)>(amax);
         } else if (row >= 0 && blk < p.nblk) {
-            amax = p.table[(int64_t)((uint32_t)row / (uint32_t)p.rblock) * p.ntk + (uint32_t)blk / (uint32_t)p.kshare];   // rows fit 31 bits here
+            amax = p.table[(int64_t)div_magic((uint32_t)row, p.dR) * p.ntk + div_magic((uint32_t)blk, p.dK)];   // rows fit 31 bits here
         }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
         int q[8];
-        const uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+        // stochastic rounding draws by logical index: of the (lowered) source matrix, or, when a whole image shares one
+        // exponent, of the image tensor: a pixel is then rounded the same way in every window it appears in, as if
+        // the image had been converted once and lowered afterwards
+        uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+        if (CONV && GP == 0 && at[u] >= 0) idx0 = (uint64_t)at[u];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const uint64_t idx = idx0 + e;
@@ -485,7 +497,17 @@ __global__ __launch_bounds__(kThreads) void fill_u32_kernel(uint32_t *p, int64_t
 // independent, so the atomics leave a deterministic result.
 constexpr int kAmaxRows = 64;
 
-__global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p, int vec_ok) {
+// strip height: 64 rows; 8 when every row is a block of its own (no more atomics than with 64, more workgroups)
+int amax_strip_rows(int64_t block_rows) { return block_rows == 1 ? 8 : kAmaxRows; }
+
+__device__ __forceinline__ void amax_flush_wave(uint32_t v, uint32_t *slot) {
+    v = group_max<16>(v);
+    v = max(v, (uint32_t)__shfl_xor((int)v, 16));
+    v = max(v, (uint32_t)__shfl_xor((int)v, 32));
+    if ((threadIdx.x & 63) == 0 && v) atomicMax(slot, v);
+}
+
+__global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p, int vec_ok, int strip_rows) {
     const int64_t c0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
     int64_t tc[4];
 #pragma unroll
@@ -493,8 +515,26 @@ __global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p,
     const int ncol = c0 >= p.src_cols ? 0 : (p.src_cols - c0 >= 4 ? 4 : (int)(p.src_cols - c0));
     const int64_t wave_tc = __shfl(tc[0], 0);
     const bool wave_one = __all(tc[0] == wave_tc && tc[3] == wave_tc);
-    for (int64_t r0 = (int64_t)blockIdx.y * kAmaxRows; r0 < p.src_rows; r0 += (int64_t)gridDim.y * kAmaxRows) {
-        const int64_t r1 = r0 + kAmaxRows < p.src_rows ? r0 + kAmaxRows : p.src_rows;
+    for (int64_t r0 = (int64_t)blockIdx.y * strip_rows; r0 < p.src_rows; r0 += (int64_t)gridDim.y * strip_rows) {
+        const int64_t r1 = r0 + strip_rows < p.src_rows ? r0 + strip_rows : p.src_rows;
+        if (p.br == 1 && wave_one && vec_ok && __all(ncol == 4)) {
+            // one exponent block per row (and per wave): 8 rows in flight at a time instead of a load, a reduction
+            // and an atomic in turn for every row
+            for (int64_t r = r0; r < r1; r += 8) {
+                float4 d[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    d[i] = *reinterpret_cast<const float4 *>(p.src + (r + i < r1 ? r + i : r1 - 1) * p.ld + c0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (r + i >= r1) break;
+                    const uint32_t v = max(max(__float_as_uint(d[i].x) & 0x7fffffffu, __float_as_uint(d[i].y) & 0x7fffffffu),
+                                           max(__float_as_uint(d[i].z) & 0x7fffffffu, __float_as_uint(d[i].w) & 0x7fffffffu));
+                    amax_flush_wave(v, p.tile_amax + (r + i) * p.nbc + wave_tc);
+                }
+            }
+            continue;
+        }
         int64_t r = r0;
         int64_t tr = r0 / p.br, tile_end = (tr + 1) * p.br;              // one division per strip, none per row
         while (r < r1) {
@@ -522,11 +562,7 @@ __global__ __launch_bounds__(kThreads) void tile_amax_kernel(const TileParams p,
                 tile_end += p.br;
             }
             if (wave_one) {
-                uint32_t v = max(max(a[0], a[1]), max(a[2], a[3]));
-                v = group_max<16>(v);
-                v = max(v, (uint32_t)__shfl_xor((int)v, 16));
-                v = max(v, (uint32_t)__shfl_xor((int)v, 32));
-                if ((threadIdx.x & 63) == 0 && v) atomicMax(row_of_table + wave_tc, v);
+                amax_flush_wave(max(max(a[0], a[1]), max(a[2], a[3])), row_of_table + wave_tc);
             } else if (ncol) {
                 // merge neighbours that fall into the same block before touching memory
                 uint32_t run = a[0];
@@ -651,6 +687,132 @@ void launch_rowwave_n(const WaveParams &p, dim3 grid, bool wide, int rounding, h
     else hipLaunchKernelGGL((enc_rowwave_kernel<true, 1, NV>), grid, dim3(kThreads), 0, s, p);
 }
 
+void magic_of(uint32_t d, uint32_t (&magic)[2]) {
+    if (d == 1) {
+        magic[0] = magic[1] = 0;
+        return;
+    }
+    int l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    const unsigned __int128 two = (unsigned __int128)1 << (31 + l);
+    magic[0] = (uint32_t)((two + d - 1) / d);
+    magic[1] = (uint32_t)(l - 1);
+}
+
+// The same pass when one exponent block spans all columns (one exponent per row of a long row, per image, per band of
+// rows, or for the whole matrix): a workgroup walks up to 16 chunks of 1024 columns, keeps one maximum per row of
+// blocks and combines its four waves through LDS, so the table sees one atomic per workgroup and block row.
+constexpr int kAmaxChunks = 16;
+
+__global__ __launch_bounds__(kThreads) void tile_amax_wide_kernel(const TileParams p, int vec_ok, int strip_rows, int cpw) {
+    __shared__ uint32_t wave_max[kThreads / 64];
+    __shared__ uint32_t wave_max8[kThreads / 64][8];
+    const int64_t cbase = ((int64_t)blockIdx.x * cpw * kThreads + threadIdx.x) * 4;
+    for (int64_t r0 = (int64_t)blockIdx.y * strip_rows; r0 < p.src_rows; r0 += (int64_t)gridDim.y * strip_rows) {
+        const int64_t r1 = r0 + strip_rows < p.src_rows ? r0 + strip_rows : p.src_rows;
+        if (p.br == 1 && vec_ok) {
+            // every row is a block row: 8 rows at a time, all of their loads in flight together, one exchange
+            // through LDS for the 8 maxima
+            for (int64_t r = r0; r < r1; r += 8) {
+                uint32_t a8[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) a8[i] = 0;
+                for (int cc = 0; cc < cpw; ++cc) {
+                    const int64_t c0 = cbase + (int64_t)cc * kThreads * 4;
+                    if (c0 + 3 < p.src_cols) {
+                        float4 d[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            d[i] = *reinterpret_cast<const float4 *>(p.src + (r + i < r1 ? r + i : r1 - 1) * p.ld + c0);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            a8[i] = max(a8[i], max(max(__float_as_uint(d[i].x) & 0x7fffffffu, __float_as_uint(d[i].y) & 0x7fffffffu),
+                                                   max(__float_as_uint(d[i].z) & 0x7fffffffu, __float_as_uint(d[i].w) & 0x7fffffffu)));
+                    } else {
+                        for (int i = 0; i < 8 && r + i < r1; ++i)
+                            for (int e = 0; e < 4; ++e)
+                                if (c0 + e < p.src_cols) a8[i] = max(a8[i], __float_as_uint(p.src[(r + i) * p.ld + c0 + e]) & 0x7fffffffu);
+                    }
+                }
+                __syncthreads();                               // the previous group's maxima have been read
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint32_t v = group_max<16>(a8[i]);
+                    v = max(v, (uint32_t)__shfl_xor((int)v, 16));
+                    v = max(v, (uint32_t)__shfl_xor((int)v, 32));
+                    if ((threadIdx.x & 63) == 0) wave_max8[threadIdx.x >> 6][i] = v;
+                }
+                __syncthreads();
+                if (threadIdx.x < 8 && r + threadIdx.x < r1) {
+                    const int i = threadIdx.x;
+                    const uint32_t v = max(max(wave_max8[0][i], wave_max8[1][i]), max(wave_max8[2][i], wave_max8[3][i]));
+                    if (v) atomicMax(p.tile_amax + r + i, v);
+                }
+            }
+            continue;
+        }
+        int64_t r = r0;
+        int64_t tr = r0 / p.br, tile_end = (tr + 1) * p.br;
+        while (r < r1) {
+            const int64_t rend = tile_end < r1 ? tile_end : r1;
+            uint32_t a = 0;
+            for (int64_t rr = r; rr < rend; ++rr) {
+                const float *srow = p.src + rr * p.ld;
+#pragma unroll 4
+                for (int cc = 0; cc < cpw; ++cc) {
+                    const int64_t c0 = cbase + (int64_t)cc * kThreads * 4;
+                    if (c0 + 3 < p.src_cols && vec_ok) {
+                        const float4 d = *reinterpret_cast<const float4 *>(srow + c0);
+                        a = max(a, max(max(__float_as_uint(d.x) & 0x7fffffffu, __float_as_uint(d.y) & 0x7fffffffu),
+                                       max(__float_as_uint(d.z) & 0x7fffffffu, __float_as_uint(d.w) & 0x7fffffffu)));
+                    } else {
+                        for (int e = 0; e < 4; ++e)
+                            if (c0 + e < p.src_cols) a = max(a, __float_as_uint(srow[c0 + e]) & 0x7fffffffu);
+                    }
+                }
+            }
+            r = rend;
+            a = group_max<16>(a);
+            a = max(a, (uint32_t)__shfl_xor((int)a, 16));
+            a = max(a, (uint32_t)__shfl_xor((int)a, 32));
+            __syncthreads();                                   // the previous block row's maxima have been read
+            if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = a;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                const uint32_t v = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+                if (v) atomicMax(p.tile_amax + tr, v);
+            }
+            if (rend == tile_end) {
+                ++tr;
+                tile_end += p.br;
+            }
+        }
+    }
+}
+
+// launches the maximum pass (the table has been cleared)
+int launch_tile_amax(const TileParams &p, hipStream_t s) {
+    const int vec_ok = (((uintptr_t)p.src & 15) == 0 && (p.ld % 4) == 0) ? 1 : 0;
+    const int strip = amax_strip_rows(p.br);
+    int64_t gy = ceil_div(p.src_rows, strip);
+    gy = gy > 65535 ? 65535 : gy;
+    if (p.nbc == 1) {
+        // chunks per workgroup: as many as still leave about a thousand workgroups
+        const int64_t chunks = ceil_div(p.src_cols, kThreads * 4);
+        int64_t want = chunks * gy / 1024;
+        want = want < 1 ? 1 : (want > kAmaxChunks ? kAmaxChunks : want);
+        const int cpw = (int)(want < chunks ? want : chunks);
+        const int64_t gx = ceil_div(chunks, cpw);
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        hipLaunchKernelGGL(tile_amax_wide_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p, vec_ok, strip, cpw);
+    } else {
+        const int64_t gx = ceil_div(p.src_cols, kThreads * 4);
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        hipLaunchKernelGGL(tile_amax_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p, vec_ok, strip);
+    }
+    return HBFP_OK;
+}
+
 int ilog2_ceil(int64_t x) {
     int l = 0;
     while (((int64_t)1 << l) < x) ++l;
@@ -711,21 +873,28 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     return launch_status();
 }
 
-static void magic_of(uint32_t d, uint32_t (&magic)[2]) {
-    if (d == 1) {
-        magic[0] = magic[1] = 0;
-        return;
-    }
-    int l = 0;
-    while (((uint64_t)1 << l) < d) ++l;
-    const unsigned __int128 two = (unsigned __int128)1 << (31 + l);
-    magic[0] = (uint32_t)((two + d - 1) / d);
-    magic[1] = (uint32_t)(l - 1);
-}
-
 // The activation operand of a convolution, converted straight from the NHWC tensor (1-D blocks along k = (r, s, c)).
 int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
-                         uint8_t *exps, hipStream_t s) {
+                         uint8_t *exps, uint32_t *table, hipStream_t s) {
+    if (table) {
+        // one exponent per image: largest magnitude of each image (the tensor as a matrix [n][h * w * c], one block per
+        // row) into table[n]; the gather below then looks its exponent up there
+        TileParams t;
+        t.src = x;
+        t.tile_amax = table;
+        t.src_rows = c.n;
+        t.src_cols = c.h * c.w * c.c;
+        t.ld = t.src_cols;
+        t.br = 1;
+        t.bc = t.src_cols;
+        t.nbr = c.n;
+        t.nbc = 1;
+        int64_t fb = ceil_div(c.n, kThreads);
+        if (fb > 4096) fb = 4096;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)fb), dim3(kThreads), 0, s, table, c.n, 0u);
+        const int rc = launch_tile_amax(t, s);
+        if (rc != HBFP_OK) return rc;
+    }
     if (g.axis == 0) {
         // weight-gradient orientation: operand rows = (filter tap, channel), k = output positions
         ColParams p;
@@ -800,11 +969,15 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     p.vec_ok = (((uintptr_t)x & 15) == 0) ? 1 : 0;                      // C is a multiple of 8
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
-    p.table = nullptr;
-    p.rblock = 1;
-    p.ntk = 0;
-    p.gp = 0;
-    p.kshare = 1;
+    p.table = table;
+    p.rblock = table ? g.rblock : 1;                                     // rows of one image
+    p.ntk = 1;
+    p.gp = (int32_t)(g.kbp / 8);
+    p.kshare = (int32_t)g.nblk;
+    magic_of((uint32_t)p.chunks, p.dChunks);
+    magic_of((uint32_t)p.gp, p.dGp);
+    magic_of((uint32_t)p.rblock, p.dR);
+    magic_of((uint32_t)p.kshare, p.dK);
     p.cH = (int32_t)c.h;
     p.cW = (int32_t)c.w;
     p.cC = (int32_t)c.c;
@@ -823,7 +996,8 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     if (gx > 0x7fffffff) return HBFP_ERR_ARG;
     const dim3 grid((unsigned)gx);
     const bool wide = g.m > 8;
-    if (g.kbp == 32) launch_row_conv_g<4>(p, grid, wide, g.rounding, s);
+    if (table) launch_row_conv_g<0>(p, grid, wide, g.rounding, s);
+    else if (g.kbp == 32) launch_row_conv_g<4>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 64) launch_row_conv_g<8>(p, grid, wide, g.rounding, s);
     else if (g.kbp == 128) launch_row_conv_g<16>(p, grid, wide, g.rounding, s);
     else return HBFP_ERR_FORMAT;
@@ -935,12 +1109,8 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         int64_t fb = ceil_div(ntile, kThreads);
         if (fb > 4096) fb = 4096;
         hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)fb), dim3(kThreads), 0, s, tile_amax, ntile, 0u);
-        const int64_t gx = ceil_div(g.src_cols, kThreads * 4);
-        int64_t gy = ceil_div(g.src_rows, kAmaxRows);
-        gy = gy > 65535 ? 65535 : gy;
-        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
-        const int vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0) ? 1 : 0;
-        hipLaunchKernelGGL(tile_amax_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p, vec_ok);
+        const int rc = launch_tile_amax(p, s);
+        if (rc != HBFP_OK) return rc;
     }
     if (g.axis == 1) {
         RowParams p;
@@ -970,6 +1140,11 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         p.ntk = g.nbc;
         p.gp = (int32_t)(g.kbp / 8);
         p.kshare = (int32_t)(g.kshare > g.nblk ? g.nblk : g.kshare);
+        if (g.rblock > 0x7fffffff) return HBFP_ERR_ARG;
+        magic_of((uint32_t)p.chunks, p.dChunks);
+        magic_of((uint32_t)p.gp, p.dGp);
+        magic_of((uint32_t)p.rblock, p.dR);
+        magic_of((uint32_t)p.kshare, p.dK);
         const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
         if (gx > 0x7fffffff) return HBFP_ERR_ARG;
         launch_row_g<0>(p, dim3((unsigned)gx), wide, g.rounding, s);

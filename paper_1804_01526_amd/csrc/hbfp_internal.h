@@ -32,7 +32,7 @@ struct EncodeGeom {
 int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
 int launch_encode_col_fused(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps, hipStream_t s);
 int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
-                         uint8_t *exps, hipStream_t s);
+                         uint8_t *exps, uint32_t *table, hipStream_t s);
 int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uint8_t *exps,
                           uint32_t *tile_amax, hipStream_t s);
 

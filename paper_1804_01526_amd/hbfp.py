@@ -70,7 +70,7 @@ def _load():
     lib.hbfp_encode_workspace.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_encode.argtypes = [vp, i64, i64, i64, i32, F, T, vp, sz, vp]
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
-    lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp]
+    lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp, sz, vp]
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
@@ -319,15 +319,16 @@ def _desc_array(outs):
 
 
 def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, contract_axis: int = 1, out: Optional[BfpTensor] = None,
-                  stream=None) -> BfpTensor:
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> BfpTensor:
     """hbfp_encode_im2col on an NHWC FP32 device tensor: the lowered activation operand of a convolution
     (contract_axis 1: forward product, 0: weight gradient)."""
     assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and tuple(x.shape) == (conv.n, conv.h, conv.w, conv.c)
     ho, wo = conv.out_hw()
     if out is None:
         out = alloc(fmt, conv.n * ho * wo, conv.r * conv.s * conv.c, contract_axis, x.device)
-    _check(_lib.hbfp_encode_im2col(_dev_ptr(x), ctypes.byref(conv), ctypes.byref(out.desc), _stream_ptr(stream)),
-           "hbfp_encode_im2col")
+    workspace = _workspace(encode_workspace(out.desc), x.device, workspace)
+    _check(_lib.hbfp_encode_im2col(_dev_ptr(x), ctypes.byref(conv), ctypes.byref(out.desc), _dev_ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_im2col")
     return out
 
 

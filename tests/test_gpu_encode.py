@@ -1,5 +1,7 @@
 """GPU parity of FP32 -> BFP -> FP32 against the CPU oracle, through the C ABI.
 Mantissas, exponent bytes and decoded values must match bit for bit."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -158,6 +160,33 @@ def test_encode_im2col_weight_gradient_orientation(hb, n, h, w, c, r, s, ph, pw,
     mant, exps = unpack(bt)
     np.testing.assert_array_equal(exps, want.exps)
     np.testing.assert_array_equal(mant, want.mant)
+
+
+@pytest.mark.parametrize("n,h,w,c,r,s,ph,pw,sh,sw,slot,m,rounding", [
+    (3, 9, 10, 16, 3, 3, 1, 1, 1, 1, 24, 8, 0), (2, 8, 7, 8, 3, 3, 1, 1, 1, 1, 24, 8, 1), (4, 12, 11, 40, 1, 1, 0, 0, 1, 1, 8, 12, 1),
+    (2, 11, 13, 24, 5, 3, 2, 1, 2, 1, 64, 8, 0), (2, 15, 15, 32, 2, 2, 0, 0, 3, 3, 32, 8, 1), (70, 6, 6, 16, 3, 3, 1, 1, 1, 1, 16, 8, 0),
+])
+def test_encode_im2col_one_exponent_per_training_input(hb, n, h, w, c, r, s, ph, pw, sh, sw, slot, m, rounding):
+    """Sec. 5.1: the x tensor gets one exponent per training input.  The oracle converts the image tensor as a matrix
+    [n][h*w*c] with one block per row and lowers the mantissas afterwards; the library gathers and converts in one go
+    (with stride 3 and a 2 x 2 filter some pixels lie in no window: they still count for the exponent)."""
+    print(f"[case] conv per-image n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) slot={slot} m={m} rounding={rounding}", flush=True)
+    x = _data((n, h, w, c), 5 * n + 3 * h + w + c, spread=3)
+    x *= np.exp2(np.random.default_rng(n).integers(-6, 7, size=(n, 1, 1, 1))).astype(np.float32)      # images of different scale
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    ho, wo = conv.out_hw()
+    fmt = hb.make_format(m, ho * wo, 0, rounding, 0x1A6E, k_slot=slot)
+    bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, fmt)
+    torch.cuda.synchronize()
+    img = ref.encode(x.reshape(n, h * w * c), 1, 0, m, rounding, 0x1A6E)
+    want_mant = ref.im2col(img.mant.reshape(n, h, w, c), r, s, ph, pw, sh, sw)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, img.exps)
+    np.testing.assert_array_equal(mant, want_mant)
+    with pytest.raises(hb.HbfpError) as e:                          # the table of image maxima needs its workspace
+        hb._check(hb._lib.hbfp_encode_im2col(bt.mant.data_ptr(), ctypes.byref(conv), ctypes.byref(bt.desc), None, 0, None),
+                  "hbfp_encode_im2col")
+    assert e.value.status == hb.ERR_WORKSPACE
 
 
 def test_encode_im2col_argument_checks(hb):

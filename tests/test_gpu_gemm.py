@@ -230,6 +230,24 @@ def test_convolution_products_from_the_image_tensor(hb):
     assert dw.shape == (9 * c, f) and rel_fro(dw.cpu().numpy(), want) <= TOL
 
 
+def test_convolution_forward_in_the_format_of_the_experiments(hb):
+    """Sec. 5.1's pairing on a convolution: activations with one exponent per training input, gathered straight from the
+    image tensor, against the filter matrix in 24 x 24 tiles; the oracle converts the image, lowers the decoded
+    values and takes the FP64 product."""
+    rng = np.random.default_rng(32)
+    n, h, w, c, f = 6, 10, 10, 24, 50
+    x = (np.maximum(rng.standard_normal((n, h, w, c)), 0) * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
+    wmat = (rng.standard_normal((9 * c, f)) * 0.1).astype(np.float32)
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1)
+    ta = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(8, 100, 0, k_slot=24))
+    tb = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, 24, 24))
+    y = hb.gemm(ta, tb)
+    torch.cuda.synchronize()
+    xq = ref.decode(ref.encode(x.reshape(n, -1), 1, 0, 8)).reshape(n, h, w, c)
+    want = ref.gemm(ref.im2col(xq, 3, 3, 1, 1), ref.decode(ref.encode(wmat, 24, 24, 8)))
+    assert rel_fro(y.cpu().numpy(), want) <= TOL
+
+
 def test_lstm_gate_products_sampled(hb):
     """Gate products of an LSTM language model (the paper's second workload, Sec. 5.2): 35 steps x batch 20 = 700
     rows, hidden size 1500, four gates; forward, data gradient and weight gradient in config 4's formats (blocks of
