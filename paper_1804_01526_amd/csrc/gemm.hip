@@ -357,7 +357,6 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 
     // stages are requested in order, so the three source pointers of this wave just advance
     const uint8_t *nextA = tileA + (int64_t)st_begin * kHalfK, *nextB = tileB + (int64_t)st_begin * kHalfK;
-    int st_req = st_begin;                                                       // next stage to request
     const uint32_t *nextW = wordsrc + (SPB == 1 ? 2 * (int64_t)st_begin + (wc >> 1) : SPB == 2 ? (int64_t)st_begin : (int64_t)st_begin / spb64) * wordpitch;
     const int64_t stepW = (SPB == 1 ? 2 : 1) * wordpitch;                        // words per stage (long blocks: per block)
     int req_pos = 0;                                                             // SPB == 0: stage within its block
@@ -369,7 +368,6 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         async_copy4(nextW, voffW, lb + ldsW);                                                           \
         nextA += kHalfK;                                                                                \
         nextB += kHalfK;                                                                                \
-        ++st_req;                                                                                       \
         if (SPB != 0) nextW += stepW;                                                                   \
         else if (++req_pos == spb64) { req_pos = 0; nextW += stepW; }                                   \
     }
