@@ -62,7 +62,8 @@ struct RowParams {
     // (n, ho, wo) holds the values under the filter window, k = (r * S + s) * C + c, zero outside the image
     int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
     uint32_t dC[2], dS[2], dP[2], dW[2];   // divisions by C, S, Ho*Wo and Wo as multiply-high + shift (magic_of)
-    uint32_t dChunks[2], dGp[2], dR[2], dK[2];   // likewise by chunks, gp, rblock and kshare (GP = 0 only)
+    uint32_t dChunks[2];                         // likewise by the chunks per row (when that is no power of two)
+    uint32_t dGp[2], dR[2], dK[2];               // and by gp, rblock and kshare (GP = 0 only)
 };
 
 // n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         if (p.lpr_log2 >= 0) {                       // chunks per row is a power of two
             row = (int64_t)(g >> p.lpr_log2);
             cl[u] = (int)(g & (uint64_t)(p.chunks - 1));
-        } else if (GP == 0 && total <= 0x7fffffffull) {
+        } else if (total <= 0x7fffffffull) {
             const uint32_t q = div_magic((uint32_t)g, p.dChunks);
             row = q;
             cl[u] = (int)((uint32_t)g - q * (uint32_t)p.chunks);
@@ -849,6 +850,7 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.ntk = 0;
     p.gp = 0;
     p.kshare = 1;
+    magic_of((uint32_t)p.chunks, p.dChunks);
     if (g.rblock > 1) {
         p.nseg = (int32_t)ceil_div(p.chunks, kThreads);
         const int64_t gx = ceil_div(g.R, g.rblock);
