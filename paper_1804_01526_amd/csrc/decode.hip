@@ -19,8 +19,26 @@ struct DecParams {
     float alpha;
     int64_t ld, src_rows, src_cols, R, K, kblock, kbp, nblk, kpad, exp_ld;
     int32_t axis, m;
-    int32_t chunks, lpr_log2, nseg, vec_ok, gp_log2;
+    int32_t chunks, lpr_log2, nseg, vec_ok, gp;
+    uint32_t dGp[2];             // division by gp (chunks per stored block) as multiply-high + shift
 };
+
+// n / d for 0 <= n < 2^31: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d), floor(n * m / 2^(31 + l)) = floor(n / d)
+// (round-up method of Granlund and Montgomery); magic[0] = m, magic[1] = l - 1, d = 1 is stored as m = 0.
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, const uint32_t (&magic)[2]) {
+    return magic[0] ? __umulhi(n, magic[0]) >> magic[1] : n;
+}
+void magic_of(uint32_t d, uint32_t (&magic)[2]) {
+    if (d == 1) {
+        magic[0] = magic[1] = 0;
+        return;
+    }
+    int l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    const unsigned __int128 two = (unsigned __int128)1 << (31 + l);
+    magic[0] = (uint32_t)((two + d - 1) / d);
+    magic[1] = (uint32_t)(l - 1);
+}
 
 // row path: k is contiguous in the destination.  A lane turns 4 stored mantissas into one 16-byte store, so a wave
 // writes 1 KB of consecutive floats per instruction; it handles kUnroll such chunks per pass, all of their loads
@@ -44,9 +62,9 @@ __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
         int64_t at[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int64_t cl = (int64_t)(seg0 + u) * lpr + lr;
-            const int64_t blk = cl >> p.gp_log2;
-            const int j = (int)(cl & ((1 << p.gp_log2) - 1));
+            const int64_t cl = (int64_t)(seg0 + u) * lpr + lr;                  // < 2^31: the launcher checks
+            const int64_t blk = div_magic((uint32_t)cl, p.dGp);
+            const int j = (int)(cl - blk * p.gp);
             int c = 0;
             if (seg0 + u < p.nseg && cl < p.chunks && blk < p.nblk) {
                 const int64_t k0 = blk * p.kblock;
@@ -111,6 +129,65 @@ __global__ __launch_bounds__(kThreads) void dec_row_kernel(const DecParams p) {
     }
 }
 
+// column path: k runs down the rows of the destination (operand row r is destination column r).  A workgroup
+// takes 64 operand rows x 64 stored positions: whole 64-byte (128-byte for 16-bit mantissas) row pieces are read,
+// turned in LDS, and every wave instruction then writes 64 consecutive floats of one destination row.
+constexpr int kColTileRows = 64, kColTileK = 64;
+
+template <bool WIDE, bool AXPY>
+__global__ __launch_bounds__(kThreads) void dec_col_kernel(const DecParams p) {
+    constexpr int ESZ = WIDE ? 2 : 1;
+    constexpr int kStride = kColTileK * ESZ + 4;                  // bytes per operand row in LDS: lanes 17 / 33 words apart
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kColTileRows * kStride];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * kColTileRows, s0 = (int64_t)blockIdx.y * kColTileK;   // stored position
+    {   // load: thread -> (row, 16-byte piece); 4 (8) pieces per row
+        constexpr int PPR = kColTileK * ESZ / 16;
+#pragma unroll
+        for (int i = 0; i < PPR / 4; ++i) {
+            const int idx = t + i * kThreads, row = idx / PPR, piece = idx % PPR;
+            uint4 d = make_uint4(0u, 0u, 0u, 0u);
+            if (r0 + row < p.R) d = *reinterpret_cast<const uint4 *>(p.mant + ((r0 + row) * p.kpad + s0) * ESZ + piece * 16);
+            uint32_t *l = reinterpret_cast<uint32_t *>(tile + row * kStride + piece * 16);
+            l[0] = d.x; l[1] = d.y; l[2] = d.z; l[3] = d.w;
+        }
+    }
+    __syncthreads();
+    const int64_t r = r0 + lane;                                  // this lane's operand row = destination column
+    if (r >= p.R) return;
+    // wave w converts stored positions 4 (w + 4 i) .. + 3, i = 0..3; a group of 4 never leaves its stored block
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int g4 = 4 * (wave + 4 * i);
+        const int64_t sp = s0 + g4;
+        const int64_t blk = (uint32_t)sp / (uint32_t)p.kbp;      // stored positions fit 31 bits: the launcher checks
+        const int kk = (int)(sp - blk * p.kbp);
+        if (blk >= p.nblk || kk >= p.kblock) continue;
+        const int ue = (int)p.exps[r * p.exp_ld + blk] - 125 - p.m;
+        int q[4];
+        if (!WIDE) {
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(tile + lane * kStride + g4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q[e] = (int)(int8_t)(w >> (8 * e));
+        } else {
+            const uint32_t w0 = *reinterpret_cast<const uint32_t *>(tile + lane * kStride + g4 * 2);
+            const uint32_t w1 = *reinterpret_cast<const uint32_t *>(tile + lane * kStride + g4 * 2 + 4);
+            q[0] = (int)(int16_t)(w0 & 0xffffu);
+            q[1] = (int)(int16_t)(w0 >> 16);
+            q[2] = (int)(int16_t)(w1 & 0xffffu);
+            q[3] = (int)(int16_t)(w1 >> 16);
+        }
+        const int64_t k = blk * p.kblock + kk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (kk + e >= p.kblock || k + e >= p.K) break;
+            float f = __builtin_amdgcn_ldexpf((float)q[e], ue);
+            if (AXPY) f = fmaf(p.alpha, p.delta[(k + e) * p.ldd + r], f);
+            p.dst[(k + e) * p.ld + r] = f;
+        }
+    }
+}
+
 // any orientation: one thread per destination element
 template <bool WIDE, bool AXPY>
 __global__ __launch_bounds__(kThreads) void dec_any_kernel(const DecParams p) {
@@ -153,10 +230,11 @@ int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float
     p.exp_ld = t->exp_ld;
     p.axis = t->contract_axis;
     p.m = t->mant_bits;
-    p.chunks = p.lpr_log2 = p.nseg = p.vec_ok = p.gp_log2 = 0;
+    p.chunks = p.lpr_log2 = p.nseg = p.vec_ok = p.gp = 0;
+    p.dGp[0] = p.dGp[1] = 0;
     const bool wide = t->mant_bits > 8;
-    const bool row_path = t->contract_axis == 1 && t->kblock_pad <= 128 && t->kpad / 4 <= 0x7fffffff &&
-                          t->nblk <= 0x7fffffff;
+    const bool row_path = t->contract_axis == 1 && t->kpad / 4 + 256 <= 0x7fffffff && t->nblk <= 0x7fffffff;
+    const bool col_path = t->contract_axis == 0 && t->kpad <= 0x7fffffff && t->kpad / kColTileK <= 65535 && t->rows <= 0x7fffffff;
     if (row_path) {
         p.chunks = (int32_t)(t->kpad / 4);
         int l2 = 0;
@@ -164,7 +242,8 @@ int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float
         l2 = l2 < 4 ? 4 : (l2 > 8 ? 8 : l2);
         p.lpr_log2 = l2;
         p.nseg = (int32_t)ceil_div(p.chunks, (int64_t)1 << l2);
-        p.gp_log2 = t->kblock_pad == 32 ? 3 : t->kblock_pad == 64 ? 4 : 5;
+        p.gp = (int32_t)(t->kblock_pad / 4);
+        magic_of((uint32_t)p.gp, p.dGp);
         p.vec_ok = (((uintptr_t)dst & 15) == 0 && (ld % 4) == 0 && (t->kblock % 4) == 0) ? 1 : 0;
         if (axpy && (((uintptr_t)delta & 15) != 0 || (ldd % 4) != 0)) p.vec_ok = 0;
         const int64_t gx = ceil_div(t->rows, (int64_t)(kThreads >> l2));
@@ -178,6 +257,17 @@ int launch_decode_axpy(const hbfp_tensor *t, float *dst, int64_t ld, const float
         } else {
             if (wide) hipLaunchKernelGGL((dec_row_kernel<true, false>), grid, dim3(kThreads), 0, s, p);
             else hipLaunchKernelGGL((dec_row_kernel<false, false>), grid, dim3(kThreads), 0, s, p);
+        }
+    } else if (col_path) {
+        const int64_t gx = ceil_div(t->rows, kColTileRows), gy = t->kpad / kColTileK;      // kpad is a multiple of 128
+        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        const dim3 grid((unsigned)gx, (unsigned)gy);
+        if (axpy) {
+            if (wide) hipLaunchKernelGGL((dec_col_kernel<true, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_col_kernel<false, true>), grid, dim3(kThreads), 0, s, p);
+        } else {
+            if (wide) hipLaunchKernelGGL((dec_col_kernel<true, false>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((dec_col_kernel<false, false>), grid, dim3(kThreads), 0, s, p);
         }
     } else {
         const int64_t gx = ceil_div(t->src_cols, kThreads);
