@@ -239,7 +239,7 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     # (128 x 28 x 28 x 128, 3 x 3 filter, padding 1: the same 100352 x 1152 operand, never materialised in FP32)
     gi = torch.Generator(device="cuda").manual_seed(33)
     img = torch.relu(torch.randn((128, 28, 28, 128), device="cuda", generator=gi))
-    conv = hbfp.Conv2d(128, 28, 28, 128, 3, 3, 1, 1, 1, 1)
+    conv = hbfp.Conv2d(128, 28, 28, 128, 3, 3, 1, 1, 1, 1, 0, 0)
     ta, tb = hbfp.alloc(row, 100352, 1152, 1), hbfp.encode(W, 0, col)
     out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
     ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")

@@ -178,8 +178,8 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  *         gradient (operand rows = window entries, k runs over the output positions).  The result is bit for
  *         bit what hbfp_encode gives for the materialised lowered matrix (same logical indices for stochastic
  *         rounding).
- * Supported formats: 1-D blocks along k; contract_axis 1: at most 128 elements, block length and c multiples
- * of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).
+ * Supported formats: 1-D blocks along k; contract_axis 1: at most 128 elements, block length, c and c_block
+ * multiples of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).
  * One exponent per training input (Sec. 5.1: the x tensor gets one exponent per training input), contract_axis 1:
  * a format with block_rows = ho*wo (the rows of one image), block_cols = 0 and k_slot = the stored block length
  * (a multiple of 8, at most 128).  The exponent is that of the largest value of the whole image x[img] (also of
@@ -194,6 +194,15 @@ typedef struct hbfp_conv2d {
     int32_t r, s;
     int32_t pad_h, pad_w;
     int32_t stride_h, stride_w;
+    int32_t c_block;   /* 0 (or >= c): window entries in the order k = (fr * s + fs) * c + ch.  Otherwise the channels are
+                          cut into blocks of c_block (the last may be shorter) and k runs block by block:
+                          k = (cb * r * s + fr * s + fs) * c_block + ci for channel ch = cb * c_block + ci (with the last
+                          block's width in its own range).  The r * s * c_block entries of a channel block are then
+                          consecutive, so a filter matrix [k][filters] in the same order, cut into tiles of
+                          (r * s * c_block) x (filter block) with k_slot = c_block, shares one exponent over a channel
+                          block, a filter block and the whole window: the tiling of the two outer filter dimensions
+                          of Sec. 5.1. */
+    int32_t reserved;
 } hbfp_conv2d;
 int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
                        void *stream);

@@ -119,11 +119,13 @@ def decode(t: BFP) -> np.ndarray:
     return out
 
 
-def im2col(x: np.ndarray, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1, stride_w: int = 1) -> np.ndarray:
+def im2col(x: np.ndarray, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1, stride_w: int = 1,
+           c_block: int = 0) -> np.ndarray:
     """Activation operand of a convolution executed as a matrix product (Sec. 5.1 treats convolutions like matrix
     multiplications): x [n, h, w, c] -> [n*ho*wo, r*s*c]; row (img, oy, ox) holds the values under the filter
     window, column (fr*s + fs)*c + ch = x[img, oy*stride_h - pad_h + fr, ox*stride_w - pad_w + fs, ch], zero
-    outside the image.  Written out tap by tap on a zero-padded copy."""
+    outside the image.  Written out tap by tap on a zero-padded copy.  With c_block the channels are cut into
+    blocks and the columns run block by block (all taps of the first c_block channels, then the next block, ...)."""
     n, h, w, c = x.shape
     ho = (h + 2 * pad_h - r) // stride_h + 1
     wo = (w + 2 * pad_w - s) // stride_w + 1
@@ -133,7 +135,17 @@ def im2col(x: np.ndarray, r: int, s: int, pad_h: int, pad_w: int, stride_h: int 
     for fr in range(r):
         for fs in range(s):
             out[:, :, :, fr, fs, :] = xp[:, fr:fr + stride_h * (ho - 1) + 1:stride_h, fs:fs + stride_w * (wo - 1) + 1:stride_w, :]
-    return out.reshape(n * ho * wo, r * s * c)
+    if c_block <= 0 or c_block >= c:
+        return out.reshape(n * ho * wo, r * s * c)
+    return np.concatenate([out[..., c0:c0 + c_block].reshape(n * ho * wo, -1) for c0 in range(0, c, c_block)], axis=1)
+
+
+def filter_matrix(w4: np.ndarray, c_block: int = 0) -> np.ndarray:
+    """Filter tensor [r, s, c, f] -> the matrix [r*s*c, f] whose rows are in the column order of im2col."""
+    r, s, c, f = w4.shape
+    if c_block <= 0 or c_block >= c:
+        return w4.reshape(r * s * c, f)
+    return np.concatenate([w4[:, :, c0:c0 + c_block, :].reshape(-1, f) for c0 in range(0, c, c_block)], axis=0)
 
 
 def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:

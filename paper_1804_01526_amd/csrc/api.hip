@@ -270,7 +270,7 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
                        void *stream) {
     if (!x || !conv || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
     if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
-        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0)
+        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
         return HBFP_ERR_ARG;
     if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
     int rc = check_tensor(out, true);
@@ -283,7 +283,9 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     // one exponent per training input (Sec. 5.1): the rows of one image and the whole window share it
     const bool per_image = out->contract_axis == 1 && out->rblock == ho * wo && out->kshare >= out->nblk && out->kshare > 1;
     if (!per_image && (out->rblock != 1 || out->kshare != 1)) return HBFP_ERR_FORMAT;
-    if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7)) : out->kblock > 64) return HBFP_ERR_FORMAT;
+    if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7) || (conv->c_block & 7)) : out->kblock > 64)
+        return HBFP_ERR_FORMAT;
+    if ((int64_t)conv->r * conv->s * (conv->c_block > 0 && conv->c_block < conv->c ? conv->c_block : conv->c) > 0x7fffffff) return HBFP_ERR_ARG;
     uint32_t *table = nullptr;
     if (per_image) {
         const size_t need = align256((size_t)conv->n * 4);

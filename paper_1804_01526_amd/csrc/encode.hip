@@ -41,6 +41,54 @@ __device__ __forceinline__ uint32_t pack2_i16(int a, int b) {
 }
 
 // ------------------------------------------------------------------------------------------
+// n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
+// floor(n * m / 2^(31 + l)) = floor(n / d) for every such n (round-up method of Granlund and Montgomery).
+// magic[0] = m, magic[1] = l - 1; d = 1 is stored as m = 0.
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, const uint32_t (&magic)[2]) {
+    return magic[0] ? __umulhi(n, magic[0]) >> magic[1] : n;
+}
+
+// A convolution's lowered activation matrix, never materialised: row = output position (img, oy, ox), column k =
+// an entry of the filter window.  The channels are cut into blocks of cbs (the last may be shorter) and k runs
+// block by block: k = (cb * R * S + fr * S + fs) * cbs + ci inside full blocks, the same with the last block's
+// width after them; one block of all channels gives the plain order (fr * S + fs) * C + c.  With this order
+// the R * S * cbs values of a channel block are consecutive, so a filter matrix cut into tiles of
+// (R * S * cbs) x (output channels) shares exponents over the two outer filter dimensions (Sec. 5.1).
+struct ConvGeom {
+    int32_t H, W, C, S, Ho, Wo, pad_h, pad_w, str_h, str_w;
+    int32_t cbs, per_blk, c_last, k_last;   // channel block, R*S*cbs, width of the last block, first k of the last block
+    uint32_t dPer[2], dCb[2], dCl[2], dS[2], dP[2], dW[2];   // divisions by per_blk, cbs, c_last, S, Ho*Wo, Wo
+};
+
+// window entry k -> filter row, filter column, channel
+__device__ __forceinline__ void conv_window_entry(const ConvGeom &c, uint32_t k, int &fr, int &fs, int &ch) {
+    uint32_t base, off, tap, width;
+    if (k < (uint32_t)c.k_last) {
+        const uint32_t cb = div_magic(k, c.dPer);
+        off = k - cb * (uint32_t)c.per_blk;
+        tap = div_magic(off, c.dCb);
+        width = (uint32_t)c.cbs;
+        base = cb * (uint32_t)c.cbs;
+    } else {
+        off = k - (uint32_t)c.k_last;
+        tap = div_magic(off, c.dCl);
+        width = (uint32_t)c.c_last;
+        base = (uint32_t)(c.C - c.c_last);
+    }
+    ch = (int)(base + off - tap * width);
+    fr = (int)div_magic(tap, c.dS);
+    fs = (int)(tap - (uint32_t)fr * (uint32_t)c.S);
+}
+
+// output position -> image, top-left corner of its window
+__device__ __forceinline__ void conv_position(const ConvGeom &c, uint32_t pos, uint32_t &img, int &y0, int &x0) {
+    img = div_magic(pos, c.dP);
+    const uint32_t rem = pos - img * (uint32_t)(c.Ho * c.Wo);
+    const uint32_t oy = div_magic(rem, c.dW), ox = rem - oy * (uint32_t)c.Wo;
+    y0 = (int)oy * c.str_h - c.pad_h;
+    x0 = (int)ox * c.str_w - c.pad_w;
+}
+
 // row path
 struct RowParams {
     const float *src;
@@ -60,18 +108,11 @@ struct RowParams {
     int32_t gp, kshare;
     // CONV: the source is an NHWC image tensor and the operand is its lowered form, never materialised: operand row
     // (n, ho, wo) holds the values under the filter window, k = (r * S + s) * C + c, zero outside the image
-    int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
-    uint32_t dC[2], dS[2], dP[2], dW[2];   // divisions by C, S, Ho*Wo and Wo as multiply-high + shift (magic_of)
+    ConvGeom cv;
     uint32_t dChunks[2];                         // likewise by the chunks per row (when that is no power of two)
     uint32_t dGp[2], dR[2], dK[2];               // and by gp, rblock and kshare (GP = 0 only)
 };
 
-// n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
-// floor(n * m / 2^(31 + l)) = floor(n / d) for every such n (round-up method of Granlund and Montgomery).
-// magic[0] = m, magic[1] = l - 1; d = 1 is stored as m = 0.
-__device__ __forceinline__ uint32_t div_magic(uint32_t n, const uint32_t (&magic)[2]) {
-    return magic[0] ? __umulhi(n, magic[0]) >> magic[1] : n;
-}
 
 template <int GP, bool WIDE, int ROUND, int U, bool CONV = false>
 __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
@@ -120,17 +161,16 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         if (!CONV) {
             s = p.src + (in ? row : 0) * p.ld + (int64_t)blk * p.kblock + 8 * j;
         } else {
-            // a chunk of 8 never leaves its filter tap (C and the block length are multiples of 8)
+            // a chunk of 8 never leaves its filter tap (channel blocks and the block length are multiples of 8)
             const uint32_t k0 = (uint32_t)blk * (uint32_t)p.kblock + 8u * (uint32_t)j;
-            const uint32_t tap = div_magic(k0, p.dC), c0 = k0 - tap * (uint32_t)p.cC;
-            const uint32_t fr = div_magic(tap, p.dS), fs = tap - fr * (uint32_t)p.cS;
-            const uint32_t pos = in ? (uint32_t)row : 0u, per_img = (uint32_t)(p.cHo * p.cWo);
-            const uint32_t img = div_magic(pos, p.dP), rem = pos - img * per_img;
-            const uint32_t ho = div_magic(rem, p.dW), wo = rem - ho * (uint32_t)p.cWo;
-            const int hi = (int)ho * p.str_h - p.pad_h + (int)fr, wi = (int)wo * p.str_w - p.pad_w + (int)fs;
-            const bool inside = hi >= 0 && hi < p.cH && wi >= 0 && wi < p.cW;
+            int fr, fs, c0, y0, x0;
+            uint32_t img;
+            conv_window_entry(p.cv, cnt ? k0 : 0u, fr, fs, c0);
+            conv_position(p.cv, in ? (uint32_t)row : 0u, img, y0, x0);
+            const int hi = y0 + fr, wi = x0 + fs;
+            const bool inside = hi >= 0 && hi < p.cv.H && wi >= 0 && wi < p.cv.W;
             if (!inside) cnt = 0;                                        // zeros; they still count as elements of the block
-            const int64_t off = inside ? (((int64_t)img * p.cH + hi) * p.cW + wi) * p.cC + c0 : 0;
+            const int64_t off = inside ? (((int64_t)img * p.cv.H + hi) * p.cv.W + wi) * p.cv.C + c0 : 0;
             s = p.src + off;
             at[u] = (p.table && inside) ? off : -1;
         }
@@ -328,8 +368,7 @@ struct ColParams {
     int32_t spb, kshare;
     // CONV: the source is an NHWC image tensor; operand row = (fr * S + fs) * C + ch of the lowered matrix, k = the
     // output position (img, oy, ox): the operand of the weight-gradient product, never materialised
-    int32_t cH, cW, cC, cS, cHo, cWo, pad_h, pad_w, str_h, str_w;
-    uint32_t dC[2], dS[2], dP[2], dW[2];
+    ConvGeom cv;
 };
 
 constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
@@ -350,13 +389,7 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     const bool r_ok = lane < p.lanes && r < p.R;
     const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
     int conv_fr = 0, conv_fs = 0, conv_ch = 0;          // CONV: this lane's filter tap and channel
-    if (CONV) {
-        const uint32_t rr = r_ok ? (uint32_t)r : 0u;
-        const uint32_t tap = div_magic(rr, p.dC);
-        conv_ch = (int)(rr - tap * (uint32_t)p.cC);
-        conv_fr = (int)div_magic(tap, p.dS);
-        conv_fs = (int)(tap - (uint32_t)conv_fr * (uint32_t)p.cS);
-    }
+    if (CONV) conv_window_entry(p.cv, r_ok ? (uint32_t)r : 0u, conv_fr, conv_fs, conv_ch);
 
     for (int bi = wave; bi < NBT; bi += 4) {
         const int64_t piece = blk0 + bi;                                  // stored piece of KBP elements
@@ -378,12 +411,12 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 #pragma unroll
             for (int kk = 0; kk < KBP; ++kk) {
                 // the output position is the same for the whole wave; the window offset is the lane's
-                const uint32_t pos = (uint32_t)kfirst + (uint32_t)(kk < blen ? kk : 0);
-                const uint32_t img = div_magic(pos, p.dP), rem = pos - img * (uint32_t)(p.cHo * p.cWo);
-                const uint32_t oy = div_magic(rem, p.dW), ox = rem - oy * (uint32_t)p.cWo;
-                const int iy = (int)oy * p.str_h - p.pad_h + conv_fr, ix = (int)ox * p.str_w - p.pad_w + conv_fs;
-                const bool inside = kk < blen && r_ok && iy >= 0 && iy < p.cH && ix >= 0 && ix < p.cW;
-                v[kk] = inside ? p.src[(((int64_t)img * p.cH + iy) * p.cW + ix) * p.cC + conv_ch] : 0.0f;
+                uint32_t img;
+                int y0, x0;
+                conv_position(p.cv, (uint32_t)kfirst + (uint32_t)(kk < blen ? kk : 0), img, y0, x0);
+                const int iy = y0 + conv_fr, ix = x0 + conv_fs;
+                const bool inside = kk < blen && r_ok && iy >= 0 && iy < p.cv.H && ix >= 0 && ix < p.cv.W;
+                v[kk] = inside ? p.src[(((int64_t)img * p.cv.H + iy) * p.cv.W + ix) * p.cv.C + conv_ch] : 0.0f;
             }
         }
         uint32_t amax = 0;
@@ -875,7 +908,34 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     return launch_status();
 }
 
-// The activation operand of a convolution, converted straight from the NHWC tensor (1-D blocks along k = (r, s, c)).
+static ConvGeom conv_geom(const hbfp_conv2d &c, int64_t ho, int64_t wo) {
+    ConvGeom g;
+    g.H = (int32_t)c.h;
+    g.W = (int32_t)c.w;
+    g.C = (int32_t)c.c;
+    g.S = c.s;
+    g.Ho = (int32_t)ho;
+    g.Wo = (int32_t)wo;
+    g.pad_h = c.pad_h;
+    g.pad_w = c.pad_w;
+    g.str_h = c.stride_h;
+    g.str_w = c.stride_w;
+    g.cbs = (c.c_block > 0 && c.c_block < c.c) ? c.c_block : (int32_t)c.c;
+    g.per_blk = c.r * c.s * g.cbs;
+    const int32_t full = g.C / g.cbs;                   // channel blocks of full width
+    g.c_last = g.C - full * g.cbs;                      // 0: no shorter block at the end
+    g.k_last = full * g.per_blk;
+    if (g.c_last == 0) g.c_last = g.cbs;                // never used then (k < k_last always); keeps the division defined
+    magic_of((uint32_t)g.per_blk, g.dPer);
+    magic_of((uint32_t)g.cbs, g.dCb);
+    magic_of((uint32_t)g.c_last, g.dCl);
+    magic_of((uint32_t)c.s, g.dS);
+    magic_of((uint32_t)(ho * wo), g.dP);
+    magic_of((uint32_t)wo, g.dW);
+    return g;
+}
+
+// The activation operand of a convolution, converted straight from the NHWC tensor (1-D blocks along k).
 int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64_t wo, const EncodeGeom &g, void *mant,
                          uint8_t *exps, uint32_t *table, hipStream_t s) {
     if (table) {
@@ -923,20 +983,7 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
         p.ntc = 0;
         p.spb = 1;
         p.kshare = 1;
-        p.cH = (int32_t)c.h;
-        p.cW = (int32_t)c.w;
-        p.cC = (int32_t)c.c;
-        p.cS = c.s;
-        p.cHo = (int32_t)ho;
-        p.cWo = (int32_t)wo;
-        p.pad_h = c.pad_h;
-        p.pad_w = c.pad_w;
-        p.str_h = c.stride_h;
-        p.str_w = c.stride_w;
-        magic_of((uint32_t)c.c, p.dC);
-        magic_of((uint32_t)c.s, p.dS);
-        magic_of((uint32_t)(ho * wo), p.dP);
-        magic_of((uint32_t)wo, p.dW);
+        p.cv = conv_geom(c, ho, wo);
         const bool wide = g.m > 8;
         const int nbt = kColRowBytes / ((int)g.kbp * (wide ? 2 : 1));
         const int64_t nb_cover = p.nb_stored > g.exp_ld ? p.nb_stored : g.exp_ld;
@@ -980,20 +1027,7 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     magic_of((uint32_t)p.gp, p.dGp);
     magic_of((uint32_t)p.rblock, p.dR);
     magic_of((uint32_t)p.kshare, p.dK);
-    p.cH = (int32_t)c.h;
-    p.cW = (int32_t)c.w;
-    p.cC = (int32_t)c.c;
-    p.cS = c.s;
-    p.cHo = (int32_t)ho;
-    p.cWo = (int32_t)wo;
-    p.pad_h = c.pad_h;
-    p.pad_w = c.pad_w;
-    p.str_h = c.stride_h;
-    p.str_w = c.stride_w;
-    magic_of((uint32_t)c.c, p.dC);
-    magic_of((uint32_t)c.s, p.dS);
-    magic_of((uint32_t)(ho * wo), p.dP);
-    magic_of((uint32_t)wo, p.dW);
+    p.cv = conv_geom(c, ho, wo);
     const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
     if (gx > 0x7fffffff) return HBFP_ERR_ARG;
     const dim3 grid((unsigned)gx);

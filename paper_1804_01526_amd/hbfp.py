@@ -37,7 +37,8 @@ class Conv2d(ctypes.Structure):
     """hbfp_conv2d: NHWC input, filter r x s, zero padding and strides."""
     _fields_ = [("n", ctypes.c_int64), ("h", ctypes.c_int64), ("w", ctypes.c_int64), ("c", ctypes.c_int64),
                 ("r", ctypes.c_int32), ("s", ctypes.c_int32), ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32),
-                ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32)]
+                ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32), ("c_block", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
     def out_hw(self):
         return ((self.h + 2 * self.pad_h - self.r) // self.stride_h + 1, (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1)

@@ -128,7 +128,7 @@ def test_encode_im2col_equals_encoding_the_lowered_matrix(hb, n, h, w, c, r, s, 
     """hbfp_encode_im2col against the oracle's encode of the oracle's lowered matrix, bit for bit."""
     print(f"[case] conv n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) block={B} m={m} rounding={rounding}", flush=True)
     x = _data((n, h, w, c), n + 3 * h + 5 * w + c)
-    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw, 0, 0)
     bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(m, 1, B, rounding, 0xC0DE))
     torch.cuda.synchronize()
     low = ref.im2col(x, r, s, ph, pw, sh, sw)
@@ -152,7 +152,7 @@ def test_encode_im2col_weight_gradient_orientation(hb, n, h, w, c, r, s, ph, pw,
     encode of the oracle's lowered matrix with B x 1 blocks."""
     print(f"[case] conv wgrad n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) block={B} m={m} rounding={rounding}", flush=True)
     x = _data((n, h, w, c), 2 * n + 3 * h + 5 * w + c)
-    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw, 0, 0)
     bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(m, B, 1, rounding, 0xFACE), contract_axis=0)
     torch.cuda.synchronize()
     low = ref.im2col(x, r, s, ph, pw, sh, sw)
@@ -173,7 +173,7 @@ def test_encode_im2col_one_exponent_per_training_input(hb, n, h, w, c, r, s, ph,
     print(f"[case] conv per-image n={n} h={h} w={w} c={c} filter={r}x{s} pad=({ph},{pw}) stride=({sh},{sw}) slot={slot} m={m} rounding={rounding}", flush=True)
     x = _data((n, h, w, c), 5 * n + 3 * h + w + c, spread=3)
     x *= np.exp2(np.random.default_rng(n).integers(-6, 7, size=(n, 1, 1, 1))).astype(np.float32)      # images of different scale
-    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw, 0, 0)
     ho, wo = conv.out_hw()
     fmt = hb.make_format(m, ho * wo, 0, rounding, 0x1A6E, k_slot=slot)
     bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, fmt)
@@ -189,9 +189,29 @@ def test_encode_im2col_one_exponent_per_training_input(hb, n, h, w, c, r, s, ph,
     assert e.value.status == hb.ERR_WORKSPACE
 
 
+@pytest.mark.parametrize("n,h,w,c,r,s,ph,pw,sh,sw,cb,B,m,rounding,axis", [
+    (2, 9, 10, 48, 3, 3, 1, 1, 1, 1, 24, 24, 8, 0, 1), (2, 8, 7, 40, 3, 3, 1, 1, 1, 1, 16, 16, 8, 1, 1), (3, 7, 7, 128, 3, 3, 1, 1, 1, 1, 24, 24, 8, 0, 1),
+    (2, 11, 9, 56, 5, 3, 2, 1, 2, 1, 32, 32, 12, 1, 1), (2, 9, 10, 48, 3, 3, 1, 1, 1, 1, 24, 32, 8, 0, 0), (2, 8, 7, 21, 3, 3, 1, 1, 1, 1, 5, 24, 8, 1, 0),
+])
+def test_encode_im2col_channel_block_order(hb, n, h, w, c, r, s, ph, pw, sh, sw, cb, B, m, rounding, axis):
+    """hbfp_conv2d.c_block: the window entries run channel block by channel block (the last block may be shorter:
+    40 = 16 + 16 + 8, 128 = 5 * 24 + 8); both operand orientations, against the oracle's lowering in the same order."""
+    print(f"[case] conv c_block n={n} h={h} w={w} c={c} filter={r}x{s} c_block={cb} block={B} m={m} rounding={rounding} axis={axis}", flush=True)
+    x = _data((n, h, w, c), n + 7 * h + 3 * w + c + cb)
+    conv = hb.Conv2d(n, h, w, c, r, s, ph, pw, sh, sw, cb, 0)
+    fmt = hb.make_format(m, 1, B, rounding, 0xB10C) if axis == 1 else hb.make_format(m, B, 1, rounding, 0xB10C)
+    bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, fmt, contract_axis=axis)
+    torch.cuda.synchronize()
+    low = ref.im2col(x, r, s, ph, pw, sh, sw, cb)
+    want = ref.encode(low, 1, B, m, rounding, 0xB10C) if axis == 1 else ref.encode(low, B, 1, m, rounding, 0xB10C)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+
+
 def test_encode_im2col_argument_checks(hb):
     x = torch.zeros((2, 8, 8, 16), device="cuda")
-    conv = hb.Conv2d(2, 8, 8, 16, 3, 3, 1, 1, 1, 1)
+    conv = hb.Conv2d(2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 0, 0)
     for fmt, status in ((hb.make_format(8, 1, 20), hb.ERR_FORMAT), (hb.make_format(8, 1, 0), hb.ERR_FORMAT),
                         (hb.make_format(8, 2, 32), hb.ERR_FORMAT)):
         with pytest.raises(hb.HbfpError) as e:
@@ -201,7 +221,7 @@ def test_encode_im2col_argument_checks(hb):
         hb.encode_im2col(x, conv, hb.make_format(8, 1, 32), out=hb.alloc(hb.make_format(8, 1, 32), 100, 144, 1))
     assert e.value.status == hb.ERR_LAYOUT
     with pytest.raises(hb.HbfpError) as e:                          # channels not a multiple of 8
-        hb.encode_im2col(torch.zeros((1, 8, 8, 12), device="cuda"), hb.Conv2d(1, 8, 8, 12, 3, 3, 1, 1, 1, 1), hb.make_format(8, 1, 24))
+        hb.encode_im2col(torch.zeros((1, 8, 8, 12), device="cuda"), hb.Conv2d(1, 8, 8, 12, 3, 3, 1, 1, 1, 1, 0, 0), hb.make_format(8, 1, 24))
     assert e.value.status == hb.ERR_FORMAT
 
 

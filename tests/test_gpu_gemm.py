@@ -210,7 +210,7 @@ def test_convolution_products_from_the_image_tensor(hb):
     n, h, w, c, f = 4, 12, 13, 16, 40
     x = np.maximum(rng.standard_normal((n, h, w, c)), 0).astype(np.float32)
     wmat = (rng.standard_normal((9 * c, f)) * 0.1).astype(np.float32)
-    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1)
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1, 0, 0)
     low = ref.im2col(x, 3, 3, 1, 1)
     dy = (rng.standard_normal((low.shape[0], f)) * 1e-2).astype(np.float32)
     xg = torch.from_numpy(x).cuda()
@@ -238,13 +238,40 @@ def test_convolution_forward_in_the_format_of_the_experiments(hb):
     n, h, w, c, f = 6, 10, 10, 24, 50
     x = (np.maximum(rng.standard_normal((n, h, w, c)), 0) * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
     wmat = (rng.standard_normal((9 * c, f)) * 0.1).astype(np.float32)
-    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1)
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1, 0, 0)
     ta = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(8, 100, 0, k_slot=24))
     tb = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, 24, 24))
     y = hb.gemm(ta, tb)
     torch.cuda.synchronize()
     xq = ref.decode(ref.encode(x.reshape(n, -1), 1, 0, 8)).reshape(n, h, w, c)
     want = ref.gemm(ref.im2col(xq, 3, 3, 1, 1), ref.decode(ref.encode(wmat, 24, 24, 8)))
+    assert rel_fro(y.cpu().numpy(), want) <= TOL
+
+
+def test_convolution_with_exponents_tiled_over_the_outer_filter_dimensions(hb):
+    """Sec. 5.1 in full for a convolution: activations with one exponent per training input, filter exponents shared by
+    a 24-channel block, a 24-filter block and the whole 3 x 3 window.  With the window entries in channel-block order
+    such a filter tile is a (9 * 24) x 24 tile of the filter matrix, stored in blocks of 24.  The oracle takes the
+    exponents from the four-dimensional filter tensor directly (maximum over [3][3][24 channels][24 filters])."""
+    rng = np.random.default_rng(33)
+    n, h, w, c, f, cb = 5, 9, 9, 56, 50, 24                     # 56 = 24 + 24 + 8 channels
+    x = (np.maximum(rng.standard_normal((n, h, w, c)), 0) * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
+    w4 = (rng.standard_normal((3, 3, c, f)) * np.exp2(rng.integers(-4, 5, size=(1, 1, c, 1))) * 0.1).astype(np.float32)
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1, cb, 0)
+    ta = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(8, 81, 0, k_slot=24))
+    wmat = ref.filter_matrix(w4, cb)
+    tb = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, 9 * cb, 24, k_slot=24))
+    # the filter side, from the 4-D tensor: one exponent per (channel block, filter block), whole window
+    mant_w, exps_w = unpack(tb)
+    for c0 in range(0, c, cb):
+        for f0 in range(0, f, 24):
+            blockmax = np.abs(w4[:, :, c0:c0 + cb, f0:f0 + 24]).max()
+            want_e = ref.encode(np.array([[blockmax]], dtype=np.float32), 1, 1, 8).exps[0, 0]
+            assert exps_w[c0 // cb, f0 // 24] == want_e
+    y = hb.gemm(ta, tb)
+    torch.cuda.synchronize()
+    xq = ref.decode(ref.encode(x.reshape(n, -1), 1, 0, 8)).reshape(n, h, w, c)
+    want = ref.gemm(ref.im2col(xq, 3, 3, 1, 1, 1, 1, cb), ref.decode(ref.encode(wmat, 9 * cb, 24, 8)))
     assert rel_fro(y.cpu().numpy(), want) <= TOL
 
 

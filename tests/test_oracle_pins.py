@@ -351,9 +351,9 @@ def test_four_bit_limb_identity_and_scale_bytes_exhaustive():
 
 
 # ---------------------------------------------------------------- GEMM
-@pytest.mark.parametrize("h,w,c,r,s,pad_h,pad_w,sh,sw", [(5, 6, 3, 3, 3, 1, 1, 1, 1), (7, 5, 2, 3, 2, 0, 1, 2, 1), (4, 4, 4, 1, 1, 0, 0, 1, 1),
-                                                         (6, 7, 2, 5, 3, 2, 1, 2, 3)])
-def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h, pad_w, sh, sw):
+@pytest.mark.parametrize("h,w,c,r,s,pad_h,pad_w,sh,sw,cb", [(5, 6, 3, 3, 3, 1, 1, 1, 1, 0), (7, 5, 2, 3, 2, 0, 1, 2, 1, 0), (4, 4, 4, 1, 1, 0, 0, 1, 1, 0),
+                                                            (6, 7, 2, 5, 3, 2, 1, 2, 3, 0), (5, 6, 7, 3, 3, 1, 1, 1, 1, 3), (6, 5, 8, 2, 3, 1, 0, 1, 2, 4)])
+def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h, pad_w, sh, sw, cb):
     """The lowered operand against the textbook definition: y[img, oy, ox, f] = sum over (fr, fs, ch) of
     x[img, oy*sh - pad_h + fr, ox*sw - pad_w + fs, ch] * wgt[fr, fs, ch, f], by brute-force loops."""
     rng = np.random.default_rng(h * 100 + w)
@@ -371,7 +371,7 @@ def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h,
                         if 0 <= iy < h and 0 <= ix < w:
                             for ch in range(c):
                                 want[img, oy, ox, :] += x[img, iy, ix, ch] * wgt[fr, fs, ch, :]
-    got = ref.im2col(x, r, s, pad_h, pad_w, sh, sw) @ wgt.reshape(r * s * c, f)
+    got = ref.im2col(x, r, s, pad_h, pad_w, sh, sw, cb) @ ref.filter_matrix(wgt, cb)     # cb: channel-block order of the columns
     np.testing.assert_array_equal(got.reshape(n, ho, wo, f), want)
 
 
