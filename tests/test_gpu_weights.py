@@ -18,13 +18,13 @@ def hb():
     return hbfp
 
 
-def _case(hb, rows, cols, br, bc, m_wide, m_narrow, alpha, seed, rounding=0, steps=1, wide_axis=1):
+def _case(hb, rows, cols, br, bc, m_wide, m_narrow, alpha, seed, rounding=0, steps=1, wide_axis=1, slot=0):
     print(f"[case] {rows}x{cols} tiles {br}x{bc} m {m_wide}->{m_narrow} alpha={alpha} rounding={rounding} "
           f"steps={steps} wide_axis={wide_axis}", flush=True)
     rng = np.random.default_rng(seed)
     W = (rng.standard_normal((rows, cols)) * 0.05).astype(np.float32)
-    f_wide = hb.make_format(m_wide, br, bc, rounding, 77)
-    f_nar = hb.make_format(m_narrow, br, bc, rounding, 78)
+    f_wide = hb.make_format(m_wide, br, bc, rounding, 77, k_slot=slot)
+    f_nar = hb.make_format(m_narrow, br, bc, rounding, 78, k_slot=slot)
     wide = hb.encode(torch.from_numpy(W).cuda(), wide_axis, f_wide)
     na = hb.alloc(f_nar, rows, cols, 0)     # operand of the forward product: contraction down the rows
     nb = hb.alloc(f_nar, rows, cols, 1)     # operand of the data gradient: contraction along the rows
@@ -52,6 +52,14 @@ def test_weight_update_several_steps_and_stochastic_rounding(hb):
     _case(hb, 120, 168, 24, 24, 16, 8, -0.05, 4, rounding=1, steps=3)
     _case(hb, 90, 100, 24, 24, 16, 8, 0.02, 5, wide_axis=0, steps=2)
     _case(hb, 90, 100, 24, 24, 12, 8, 0.02, 6)
+
+
+def test_weight_update_of_a_filter_matrix_with_tiles_over_the_outer_filter_dimensions(hb):
+    """The filter matrix of a 3 x 3 convolution (56 channels in blocks of 24, 50 filters) in tiles of (9 * 24) x 24,
+    stored in blocks of 24 (k_slot): wide storage along k, narrow copies in both orientations."""
+    _case(hb, 504, 50, 216, 24, 16, 8, -0.02, 11, wide_axis=0, slot=24, steps=2)
+    _case(hb, 504, 50, 216, 24, 16, 8, -0.02, 12, rounding=1, wide_axis=0, slot=24)
+    _case(hb, 300, 90, 1, 0, 16, 8, 0.01, 13, slot=24)                     # one exponent per row, stored in blocks of 24
 
 
 def test_weight_update_zero_step_is_identity(hb):
