@@ -225,6 +225,41 @@ def test_encode_im2col_argument_checks(hb):
     assert e.value.status == hb.ERR_FORMAT
 
 
+@pytest.mark.parametrize("axis,br,bc,slot", [(1, 1, 0, 0), (0, 0, 1, 0), (0, 0, 0, 0), (1, 64, 64, 0), (0, 64, 64, 0), (1, 1, 0, 24), (1, 1, 256, 0)])
+def test_paper_block_shapes_at_layer_size_bit_exact(hb, axis, br, bc, slot):
+    """2048 x 4096 (the launch shapes of a layer-sized conversion: several strips and column groups of the maximum
+    pass, whole rows in the registers of a wave) in the block shapes of Sec. 4 and Sec. 6: one exponent per row,
+    per column, for the matrix, 64 x 64 tiles, one exponent per row stored in blocks of 24; compared in full,
+    decode included."""
+    rng = np.random.default_rng(axis * 100 + br + bc + slot)
+    x = (rng.standard_normal((2048, 4096)) * np.exp2(rng.integers(-6, 7, size=(2048, 1)))).astype(np.float32)
+    print(f"[case] 2048x4096 axis={axis} block=({br},{bc}) k_slot={slot}", flush=True)
+    fmt = hb.make_format(8, br, bc, 0, 0, k_slot=slot)
+    bt = hb.encode(torch.from_numpy(x).cuda(), axis, fmt)
+    torch.cuda.synchronize()
+    want = ref.encode(x, br, bc, 8)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    back = hb.decode(bt)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(back.cpu().numpy(), ref.decode(want))
+
+
+def test_config3_activation_operand_from_the_image_tensor_full_size(hb):
+    """Config 3's forward operand (128 x 28 x 28 x 128 image, 3 x 3 window, padding 1 -> 100352 x 1152, blocks of 32) in the
+    launch shape the benchmark times, against the oracle's encode of its own lowered matrix, in full."""
+    rng = np.random.default_rng(303)
+    x = np.maximum(rng.standard_normal((128, 28, 28, 128)), 0).astype(np.float32)
+    conv = hb.Conv2d(128, 28, 28, 128, 3, 3, 1, 1, 1, 1, 0, 0)
+    bt = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(8, 1, 32))
+    torch.cuda.synchronize()
+    want = ref.encode(ref.im2col(x, 3, 3, 1, 1), 1, 32, 8)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+
+
 REGISTER_TILE_CASES = [
     # tiles of at most 32 x 32 with column counts and tile widths that are multiples of 4: the register-tile kernel
     # rows, cols, br, bc, m, rounding
