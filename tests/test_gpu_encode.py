@@ -209,6 +209,52 @@ def test_encode_im2col_channel_block_order(hb, n, h, w, c, r, s, ph, pw, sh, sw,
     np.testing.assert_array_equal(mant, want.mant)
 
 
+@pytest.mark.parametrize("case", range(40))
+def test_encode_im2col_random_geometries(hb, case):
+    """Random images, windows, paddings, strides, channel blocks, block lengths and modes (blocks along the window,
+    blocks over the output positions, one exponent per image) against the oracle's lowering + conversion."""
+    rng = np.random.default_rng(8000 + case)
+    mode = ("fwd", "wgrad", "per_image")[case % 3]
+    n, h, w = int(rng.integers(1, 5)), int(rng.integers(3, 13)), int(rng.integers(3, 13))
+    r, s_ = int(rng.integers(1, min(h, 5) + 1)), int(rng.integers(1, min(w, 5) + 1))
+    ph, pw = int(rng.integers(0, r)), int(rng.integers(0, s_))
+    sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    c = int(rng.integers(1, 9)) * 8 if mode != "wgrad" else int(rng.integers(1, 50))
+    cb = 0
+    if rng.random() < 0.5:
+        cb = int(rng.choice([8, 16, 24])) if mode != "wgrad" else int(rng.integers(1, c + 1))
+    m, rounding = int(rng.choice([4, 8, 12])), int(rng.integers(0, 2))
+    x = _data((n, h, w, c), 8500 + case, spread=4)
+    conv = hb.Conv2d(n, h, w, c, r, s_, ph, pw, sh, sw, cb, 0)
+    ho, wo = conv.out_hw()
+    low = ref.im2col(x, r, s_, ph, pw, sh, sw, cb)
+    print(f"[case] {case}: {mode} n={n} h={h} w={w} c={c} window={r}x{s_} pad=({ph},{pw}) stride=({sh},{sw}) c_block={cb} m={m} rounding={rounding}", flush=True)
+    xg = torch.from_numpy(x).cuda()
+    if mode == "fwd":
+        B = int(rng.choice([8, 16, 24, 32, 64, 128]))
+        bt = hb.encode_im2col(xg, conv, hb.make_format(m, 1, B, rounding, 77 + case))
+        want = ref.encode(low, 1, B, m, rounding, 77 + case)
+        want_mant, want_exps = want.mant, want.exps
+    elif mode == "wgrad":
+        B = int(rng.choice([8, 20, 24, 32, 64]))
+        bt = hb.encode_im2col(xg, conv, hb.make_format(m, B, 1, rounding, 77 + case), contract_axis=0)
+        want = ref.encode(low, B, 1, m, rounding, 77 + case)
+        want_mant, want_exps = want.mant, want.exps
+    else:
+        slot = int(rng.choice([8, 16, 24, 32]))
+        if slot >= r * s_ * c:
+            slot = 8
+        if r * s_ * c <= 8:
+            pytest.skip("window of 8 entries: nothing to cut into stored blocks")
+        bt = hb.encode_im2col(xg, conv, hb.make_format(m, ho * wo, 0, rounding, 77 + case, k_slot=slot))
+        img = ref.encode(x.reshape(n, -1), 1, 0, m, rounding, 77 + case)
+        want_mant, want_exps = ref.im2col(img.mant.reshape(n, h, w, c), r, s_, ph, pw, sh, sw, cb), img.exps
+    torch.cuda.synchronize()
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want_exps)
+    np.testing.assert_array_equal(mant, want_mant)
+
+
 def test_encode_im2col_argument_checks(hb):
     x = torch.zeros((2, 8, 8, 16), device="cuda")
     conv = hb.Conv2d(2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 0, 0)
@@ -258,6 +304,45 @@ def test_config3_activation_operand_from_the_image_tensor_full_size(hb):
     mant, exps = unpack(bt)
     np.testing.assert_array_equal(exps, want.exps)
     np.testing.assert_array_equal(mant, want.mant)
+
+
+def _random_format_case(case):
+    rng = np.random.default_rng(7000 + case)
+    rows, cols = int(rng.integers(1, 400)), int(rng.integers(1, 1400))
+    if rng.random() < 0.3:
+        cols = int(rng.integers(1, 350)) * 4                         # aligned widths take the vector paths
+    axis = int(rng.integers(0, 2))
+    pick = lambda n: int(rng.choice([0, 1, 2, 3, 8, 20, 24, 32, 33, 64, 100, 128, 200, 256, n]))
+    br, bc = pick(rows), pick(cols)
+    m = int(rng.choice([2, 4, 8, 8, 8, 12, 16]))
+    rounding = int(rng.integers(0, 2))
+    slot = 0
+    kext = (bc if bc and bc < cols else cols) if axis == 1 else (br if br and br < rows else rows)
+    whole = kext == (cols if axis == 1 else rows)
+    if rng.random() < 0.4:
+        divs = [d for d in (4, 8, 12, 20, 24, 32, 50, 64) if d < kext and (whole or kext % d == 0)]
+        if divs:
+            slot = int(rng.choice(divs))
+    return rows, cols, axis, br, bc, m, rounding, slot
+
+
+@pytest.mark.parametrize("case", range(60))
+def test_encode_random_shapes_and_formats(hb, case):
+    """Random shapes, block shapes, widths, rounding modes and stored-block lengths: every conversion path (row, column,
+    register tile, one wave per row, two passes in either orientation) against the oracle, decode included."""
+    rows, cols, axis, br, bc, m, rounding, slot = _random_format_case(case)
+    print(f"[case] {case}: shape=({rows},{cols}) axis={axis} block=({br},{bc}) m={m} rounding={rounding} k_slot={slot}", flush=True)
+    x = _data((rows, cols), 9000 + case, spread=10)
+    fmt = hb.make_format(m, br, bc, rounding, 0xF00D + case, k_slot=slot)
+    bt = hb.encode(torch.from_numpy(x).cuda(), axis, fmt)
+    torch.cuda.synchronize()
+    want = ref.encode(x, br, bc, m, rounding, 0xF00D + case)
+    mant, exps = unpack(bt)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    back = hb.decode(bt)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(back.cpu().numpy(), ref.decode(want))
 
 
 REGISTER_TILE_CASES = [
