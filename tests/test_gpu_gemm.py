@@ -534,6 +534,40 @@ def test_gemm_one_exponent_per_training_input_against_weight_tiles(hb, kernel, m
     assert err <= TOL
 
 
+@pytest.mark.parametrize("case", range(30))
+def test_gemm_random_exponent_blocks_over_common_stored_blocks(hb, case):
+    """Operands whose exponent blocks differ (rows, multiples of the stored block, whole rows, 2-D tiles) but which are
+    stored in blocks of one length: integer block sums bit for bit, C within the bound, all kernel families."""
+    rng = np.random.default_rng(6000 + case)
+    M, N, K = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(8, 1200))
+    slot = int(rng.choice([8, 16, 24, 32, 64]))
+    slot = min(slot, K)
+    m = int(rng.choice([4, 8, 12]))
+    mult = lambda: int(rng.choice([slot, 2 * slot, 5 * slot, 0]))
+    fa = (int(rng.choice([1, 3, 24, 0])), mult())                 # A [M, K]: rows x k extent
+    fb = (mult(), int(rng.choice([1, 24, 0])))                    # B [K, N]: k extent x columns
+    kernel = int(rng.choice([0, 1, SCALED]))
+    print(f"[case] {case}: M={M} N={N} K={K} slot={slot} m={m} A blocks={fa} B blocks={fb} kernel={kernel}", flush=True)
+    A, B = _rand((M, K), 6100 + case, 3), _rand((K, N), 6200 + case, 3)
+    ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(m, fa[0], fa[1], k_slot=slot))
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(m, fb[0], fb[1], k_slot=slot))
+    assert ta.desc.kblock == tb.desc.kblock == slot
+    oa, ob = ref.encode(A, fa[0], fa[1], m), ref.encode(B, fb[0], fb[1], m)
+    ma, ea = unpack(ta)
+    mb, eb = unpack(tb)
+    np.testing.assert_array_equal(ma, oa.mant)
+    np.testing.assert_array_equal(mb, ob.mant)
+    np.testing.assert_array_equal(ea, oa.exps)
+    np.testing.assert_array_equal(eb, ob.exps)
+    P = hb.gemm_partials(ta, tb)
+    C = hb.gemm(ta, tb, kernel=kernel)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(P.cpu().numpy(), ref.block_dots(oa.mant, ob.mant, slot))
+    err = rel_fro(C.cpu().numpy(), ref.gemm(ref.decode(oa), ref.decode(ob)))
+    print(f"        rel fro err = {err:.3e}", flush=True)
+    assert err <= TOL
+
+
 def test_gemm_f32_with_k_slot_formats(hb):
     """hbfp_gemm_f32 with one exponent per activation row against 24 x 24 weight tiles."""
     M, K, N = 200, 700, 260
