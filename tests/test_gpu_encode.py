@@ -306,6 +306,48 @@ def test_config3_activation_operand_from_the_image_tensor_full_size(hb):
     np.testing.assert_array_equal(mant, want.mant)
 
 
+def test_two_pass_conversions_in_a_replayed_graph(hb):
+    """The two-pass conversions (table of block maxima cleared by a fill kernel, not a memset) and the convolution
+    gather with one exponent per image, captured in a HIP graph and replayed on new inputs in the same buffers, with
+    eager work and synchronisation between the replays; every replay must equal the eager conversion."""
+    rows, cols = 300, 1100
+    x = torch.zeros((rows, cols), device="cuda")
+    img = torch.zeros((3, 10, 10, 16), device="cuda")
+    conv = hb.Conv2d(3, 10, 10, 16, 3, 3, 1, 1, 1, 1, 0, 0)
+    jobs = [(hb.make_format(8, 0, 1), 0), (hb.make_format(8, 0, 0), 1), (hb.make_format(8, 64, 64), 1), (hb.make_format(8, 1, 0, k_slot=24), 1)]
+    outs = [hb.alloc(f, rows, cols, ax) for f, ax in jobs]
+    wss = [torch.empty(max(hb.encode_workspace(o.desc), 256), dtype=torch.uint8, device="cuda") for o in outs]
+    f_img = hb.make_format(8, 100, 0, k_slot=24)
+    o_img = hb.alloc(f_img, 300, 144, 1)
+    ws_img = torch.empty(max(hb.encode_workspace(o_img.desc), 256), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def run():
+        for (f, ax), o, ws in zip(jobs, outs, wss):
+            hb.encode(x, ax, f, out=o, workspace=ws, stream=stream)
+        hb.encode_im2col(img, conv, f_img, out=o_img, workspace=ws_img, stream=stream)
+
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+    rng = np.random.default_rng(5)
+    for step in range(4):
+        print(f"[case] two-pass graph replay {step}", flush=True)
+        x.copy_(torch.from_numpy((rng.standard_normal((rows, cols)) * 2.0 ** (3 * step - 4)).astype(np.float32)))
+        img.copy_(torch.from_numpy(rng.standard_normal((3, 10, 10, 16)).astype(np.float32) * (step + 1)))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [(o.mant.clone(), o.exps.clone()) for o in outs + [o_img]]
+        eager = [hb.encode(x, ax, f) for f, ax in jobs] + [hb.encode_im2col(img, conv, f_img)]
+        torch.cuda.synchronize()
+        for (gm, ge), e in zip(got, eager):
+            assert torch.equal(gm, e.mant) and torch.equal(ge, e.exps)
+
+
 def _random_format_case(case):
     rng = np.random.default_rng(7000 + case)
     rows, cols = int(rng.integers(1, 400)), int(rng.integers(1, 1400))
