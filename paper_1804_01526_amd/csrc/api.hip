@@ -281,7 +281,7 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     if (out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
     if (out->src_rows > 0x7fffffff || out->src_cols > 0x7fffffff) return HBFP_ERR_ARG;
     // one exponent per training input (Sec. 5.1): the rows of one image and the whole window share it
-    const bool per_image = out->contract_axis == 1 && out->rblock == ho * wo && out->kshare >= out->nblk && out->kshare > 1;
+    const bool per_image = out->contract_axis == 1 && out->rblock == ho * wo && out->rblock > 1 && out->kshare >= out->nblk;
     if (!per_image && (out->rblock != 1 || out->kshare != 1)) return HBFP_ERR_FORMAT;
     if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7) || (conv->c_block & 7)) : out->kblock > 64)
         return HBFP_ERR_FORMAT;
