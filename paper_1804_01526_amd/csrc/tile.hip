@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
     amax = max_of_16_lanes(amax);
 
     for (int oi = 0; oi < 3; ++oi) {
-        const TileOut &o = p.o[oi];
+        const TileOut o = p.o[oi];        // by value: its fields stay in scalar registers instead of being fetched at every use
         if (!o.present) continue;
         const uint32_t Eb = block_exponent<ROUND>(amax, o.m);
         const bool wide = o.m > 8;
@@ -150,20 +150,27 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
         if (o.axis == 1) {
             // operand row = source row; block tc of it holds this tile's columns (lanes without columns write the zero padding)
             if (tc < o.ntile_k) {
+                // one address computation per output; the rows are a fixed stride apart
+                const int64_t row_bytes = o.kpad * (wide ? 2 : 1);
+                uint8_t *dst = o.mant + (row0 * o.kpad + tc * 32 + 4 * j) * (wide ? 2 : 1);
+                if (!wide) {
 #pragma unroll
-                for (int r = 0; r < RPL; ++r) {
-                    if (r >= rows_here) continue;
-                    uint8_t *dst = o.mant + ((row0 + r) * o.kpad + tc * 32 + 4 * j) * (wide ? 2 : 1);
-                    uint32_t w0, w1 = 0;
-                    if (!wide) {
-                        w0 = pack4_i8(q(r, 0), q(r, 1), q(r, 2), q(r, 3));
-                        *reinterpret_cast<uint32_t *>(dst) = w0;
-                    } else {
-                        w0 = pack2_i16(q(r, 0), q(r, 1));
-                        w1 = pack2_i16(q(r, 2), q(r, 3));
-                        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
+                    for (int r = 0; r < RPL; ++r) {
+                        if (r < rows_here) {
+                            const uint32_t w0 = pack4_i8(q(r, 0), q(r, 1), q(r, 2), q(r, 3));
+                            *reinterpret_cast<uint32_t *>(dst + r * row_bytes) = w0;
+                            if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0));
+                        }
                     }
-                    if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0), "v"(w1));
+                } else {
+#pragma unroll
+                    for (int r = 0; r < RPL; ++r) {
+                        if (r < rows_here) {
+                            const uint32_t w0 = pack2_i16(q(r, 0), q(r, 1)), w1 = pack2_i16(q(r, 2), q(r, 3));
+                            *reinterpret_cast<uint2 *>(dst + r * row_bytes) = make_uint2(w0, w1);
+                            if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0), "v"(w1));
+                        }
+                    }
                 }
             }
             if (tc < o.exp_ld) {
