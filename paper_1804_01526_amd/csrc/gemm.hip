@@ -102,9 +102,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    int tm, tn, split = 0;
-    if (p.splits > 1 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
-                     : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
+    // 8 and more k ranges are dealt to the XCDs (few tiles, very long k); fewer ride in blockIdx.y while the tiles are
+    // dealt to the XCDs as in an unsplit product
+    int tm, tn, split = blockIdx.y;
+    if (p.splits >= 8 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
+                      : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
         return;                                                                  // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
     const int st_begin = split * p.stages_per_split;
@@ -323,9 +325,11 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     const int wm = wave & 3, wn = wave >> 2;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    int tm, tn, split = 0;
-    if (p.splits > 1 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
-                     : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
+    // 8 and more k ranges are dealt to the XCDs (few tiles, very long k); fewer ride in blockIdx.y while the tiles are
+    // dealt to the XCDs as in an unsplit product
+    int tm, tn, split = blockIdx.y;
+    if (p.splits >= 8 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
+                      : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
         return;                                                                  // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
     const int st_begin = 2 * split * p.stages_per_split;                         // in 64-byte stages
@@ -617,7 +621,8 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
         p.stages_per_split = (int32_t)(ceil_div(units, p.splits) * stages_per_block);
         p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
     }
-    const dim3 grid(p.splits > 1 ? (unsigned)(8 * tm * tn * ceil_div(p.splits, 8)) : (unsigned)(ceil_div(tm * tn, 8) * 8));
+    const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
+                                    : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
     int rc;
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);

@@ -26,7 +26,8 @@ __device__ __forceinline__ bool tile_of_workgroup(int wg, int tiles_m, int tiles
     return true;
 }
 
-// Split-K launches (few tiles, very long k): a one-dimensional grid of 8 * tiles * ceil(splits / 8) workgroups.
+// Split-K launches with at least 8 k ranges (few tiles, very long k): a one-dimensional grid of
+// 8 * tiles * ceil(splits / 8) workgroups.
 // XCD x takes the k ranges x, x + 8, ... and, for each, every tile: the tiles of one k range share their operand
 // panels in that XCD's L2, and the work is spread over all 8 XCDs however few tiles there are (dealing tiles to
 // XCDs as above would leave XCDs idle when there are fewer than 8 tiles).  Returns false for padding workgroups.
