@@ -36,7 +36,9 @@
  * Stored ("operand") layout.  A tensor is always encoded FOR a dot product, i.e.
  * with a contraction axis (the k of Eq. (2)).  The other axis indexes operand
  * rows.  With R operand rows and K contraction elements:
- *     kblock      elements of one exponent block along k
+ *     kblock      elements of one stored block along k: the exponent block, or a shorter
+ *                 stretch of it when hbfp_format.k_slot is used (kshare consecutive stored
+ *                 blocks then repeat one exponent)
  *     kblock_pad  stored length of a block: 32 if kblock <= 32, 64 if <= 64,
  *                 otherwise kblock rounded up to a multiple of 128
  *     nblk        ceil(K / kblock)           (the last block may be short)
