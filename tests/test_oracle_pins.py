@@ -375,6 +375,31 @@ def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h,
     np.testing.assert_array_equal(got.reshape(n, ho, wo, f), want)
 
 
+def test_filter_matrix_tiles_in_channel_block_order_are_the_outer_dimension_tiles():
+    """Sec. 5.1 tiles the two outer dimensions of a convolution's filter.  With the window entries in channel-block order
+    a tile of (r*s*cb) x fb of the filter matrix holds exactly one (channel block, filter block) pair with the whole
+    window: its exponent must be that of the largest magnitude over w4[:, :, channel block, filter block], and every
+    element's decoded value must lie within half a unit of that exponent."""
+    rng = np.random.default_rng(15)
+    r, s, c, f, cb, fb, m = 3, 3, 56, 50, 24, 24, 8
+    w4 = (rng.standard_normal((r, s, c, f)) * np.exp2(rng.integers(-5, 6, size=(1, 1, c, 1)))).astype(np.float32)
+    wmat = ref.filter_matrix(w4, cb)
+    enc = ref.encode(wmat, r * s * cb, fb, m)
+    dec = ref.decode(enc)
+    row0 = 0
+    for ci, c0 in enumerate(range(0, c, cb)):
+        cw = min(cb, c - c0)
+        for fi, f0 in enumerate(range(0, f, fb)):
+            block = w4[:, :, c0:c0 + cw, f0:f0 + fb]
+            top = np.abs(block).max()
+            e_ieee = int(np.frexp(top)[1]) + 126                                  # biased exponent of the maximum
+            assert enc.exps[ci, fi] in (e_ieee, e_ieee + 1)                         # + 1 only when the maximum rounds up
+            unit = 2.0 ** (int(enc.exps[ci, fi]) - 125 - m)
+            got = dec[row0:row0 + r * s * cw, f0:f0 + fb].reshape(r, s, cw, -1)     # rows of the tile: (fr, fs, ci)
+            assert np.abs(got.astype(np.float64) - block.astype(np.float64)).max() <= unit / 2
+        row0 += r * s * cw
+
+
 def test_gemm_is_the_fp64_product():
     rng = np.random.default_rng(17)
     A = rng.standard_normal((37, 129)).astype(np.float32)
