@@ -572,7 +572,9 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
                 const int64_t row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (row < p.M) {
                     float *dst = p.C + row * p.ldc + col;
-                    *dst = p.beta ? *dst + acc[i][j][v] : acc[i][j][v];
+                    // C is written once and not read again here: streaming stores leave the operand panels in the caches
+                    if (p.beta) *dst = *dst + acc[i][j][v];
+                    else __builtin_nontemporal_store(acc[i][j][v], dst);
                 }
             }
         }
