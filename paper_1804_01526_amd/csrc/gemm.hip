@@ -516,7 +516,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
                 const float val = acc[ni][v] * p.final_scale;
                 if (p.splits > 1) p.partial[((int64_t)split * p.M + i) * p.N + j] = val;
                 else if (p.beta) p.C[i * p.ldc + j] += val;
-                else p.C[i * p.ldc + j] = val;
+                else __builtin_nontemporal_store(val, p.C + i * p.ldc + j);   // written once, not read again here
             }
         }
 }

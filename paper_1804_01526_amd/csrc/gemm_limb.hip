@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_limb_kernel(const LimbParams
             if (i < p.M && j < p.N) {
                 const float val = acc[ni][v] * p.final_scale;
                 if (p.beta) p.C[i * p.ldc + j] += val;
-                else p.C[i * p.ldc + j] = val;
+                else __builtin_nontemporal_store(val, p.C + i * p.ldc + j);   // written once, not read again here
             }
         }
 }
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(kLwThreads, 4) void gemm_limb_w8_kernel(const LimbW
         if (i < p.M && j < p.N) {
             const float val = acc[v] * p.final_scale;
             if (p.beta) p.C[i * p.ldc + j] += val;
-            else p.C[i * p.ldc + j] = val;
+            else __builtin_nontemporal_store(val, p.C + i * p.ldc + j);   // written once, not read again here
         }
     }
 }

@@ -202,7 +202,8 @@ __global__ __launch_bounds__(kWideThreads, 1) void gemm_i8_wide_kernel(const Wid
                 if (col >= p.N) continue;
                 const float val = ldexpf((float)acc[i][j][v], ea + eb[j]);
                 float *dst = p.C + row * p.ldc + col;
-                *dst = p.beta ? *dst + val : val;
+                if (p.beta) *dst = *dst + val;
+                else __builtin_nontemporal_store(val, dst);               // written once, not read again here
             }
         }
 }
