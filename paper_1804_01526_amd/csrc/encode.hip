@@ -40,6 +40,18 @@ __device__ __forceinline__ uint32_t pack2_i16(int a, int b) {
     return (uint32_t)(a & 0xffff) | ((uint32_t)b << 16);
 }
 
+// streaming stores: an encoded operand is written once and not read again by the kernel that writes it
+typedef unsigned v2u_t __attribute__((ext_vector_type(2)));
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream(uint8_t *dst, uint2 v) {
+    const v2u_t w = {v.x, v.y};
+    __builtin_nontemporal_store(w, reinterpret_cast<v2u_t *>(dst));
+}
+__device__ __forceinline__ void store_stream(uint8_t *dst, uint4 v) {
+    const v4u_t w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<v4u_t *>(dst));
+}
+
 // ------------------------------------------------------------------------------------------
 // n / d for 0 <= n < 2^31 as a multiplication: with l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (fits 32 bits),
 // floor(n * m / 2^(31 + l)) = floor(n / d) for every such n (round-up method of Granlund and Montgomery).
@@ -299,14 +311,14 @@ __global__ __launch_bounds__(kThreads) void enc_row_tiled_kernel(const RowParams
                     uint2 o;
                     o.x = pack4_i8(q[0], q[1], q[2], q[3]);
                     o.y = pack4_i8(q[4], q[5], q[6], q[7]);
-                    *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8) = o;
+                    store_stream(p.mant + row * p.kpad + (int64_t)cl * 8, o);
                 } else {
                     uint4 o;
                     o.x = pack2_i16(q[0], q[1]);
                     o.y = pack2_i16(q[2], q[3]);
                     o.z = pack2_i16(q[4], q[5]);
                     o.w = pack2_i16(q[6], q[7]);
-                    *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2) = o;
+                    store_stream(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2, o);
                 }
                 if (j == 0) {
                     uint8_t *e = p.exps + row * p.exp_ld;
@@ -472,7 +484,9 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
         const int64_t rr = (int64_t)(blockIdx.x % p.row_groups) * p.lanes + rl;
         if (rl < p.lanes && rr < p.R && piece * 16 < valid_bytes) {
             const uint4 d = *reinterpret_cast<const uint4 *>(tile + rl * kColStride + piece * 16);
-            *reinterpret_cast<uint4 *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16) = d;
+            typedef unsigned v4u __attribute__((ext_vector_type(4)));
+            const v4u d4 = {d.x, d.y, d.z, d.w};
+            __builtin_nontemporal_store(d4, reinterpret_cast<v4u *>(p.mant + (rr * p.kpad + blk0 * KBP) * ESZ + piece * 16));
         }
     }
     if (TABLE) {
@@ -696,14 +710,14 @@ __global__ __launch_bounds__(kThreads) void enc_rowwave_kernel(const WaveParams 
             uint2 o;
             o.x = pack4_i8(q[0], q[1], q[2], q[3]);
             o.y = pack4_i8(q[4], q[5], q[6], q[7]);
-            *reinterpret_cast<uint2 *>(p.mant + row * p.kpad + (int64_t)cl * 8) = o;
+            store_stream(p.mant + row * p.kpad + (int64_t)cl * 8, o);
         } else {
             uint4 o;
             o.x = pack2_i16(q[0], q[1]);
             o.y = pack2_i16(q[2], q[3]);
             o.z = pack2_i16(q[4], q[5]);
             o.w = pack2_i16(q[6], q[7]);
-            *reinterpret_cast<uint4 *>(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2) = o;
+            store_stream(p.mant + (row * p.kpad + (int64_t)cl * 8) * 2, o);
         }
         if (j == 0) {
             if (blk < p.exp_ld) erow[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
                     for (int r = 0; r < RPL; ++r) {
                         if (r < rows_here) {
                             const uint32_t w0 = pack4_i8(q(r, 0), q(r, 1), q(r, 2), q(r, 3));
-                            *reinterpret_cast<uint32_t *>(dst + r * row_bytes) = w0;
+                            __builtin_nontemporal_store(w0, reinterpret_cast<uint32_t *>(dst + r * row_bytes));
                             if (ROUND) asm volatile("" : "+v"(chain) : "v"(w0));
                         }
                     }
@@ -202,9 +202,12 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const TileParams p) {
                 for (int g = threadIdx.x; g < 128 * 8; g += kThreads) {
                     const int lc = g >> 3, ch = g & 7;
                     const int64_t tcc = tc0 + (lc >> 5), c = tcc * p.bc + (lc & 31);
-                    if (tcc < p.nbc && (lc & 31) < p.bc && c < p.cols)
-                        *reinterpret_cast<uint4 *>(o.mant + c * o.kpad + tr0 * 32 + ch * 16) =
-                            *reinterpret_cast<const uint4 *>(lines + lc * kLineStride + ch * 16);
+                    if (tcc < p.nbc && (lc & 31) < p.bc && c < p.cols) {
+                        typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+                        const uint4 d = *reinterpret_cast<const uint4 *>(lines + lc * kLineStride + ch * 16);
+                        const v4u_t w = {d.x, d.y, d.z, d.w};            // streaming store: written once, not read again here
+                        __builtin_nontemporal_store(w, reinterpret_cast<v4u_t *>(o.mant + c * o.kpad + tr0 * 32 + ch * 16));
+                    }
                 }
             }
             if (col_ok && h == 0 && tr < o.exp_ld) {
