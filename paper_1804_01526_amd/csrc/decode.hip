@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void dec_col_kernel(const DecParams p) {
             if (kk + e >= p.kblock || k + e >= p.K) break;
             float f = __builtin_amdgcn_ldexpf((float)q[e], ue);
             if (AXPY) f = fmaf(p.alpha, p.delta[(k + e) * p.ldd + r], f);
-            p.dst[(k + e) * p.ld + r] = f;
+            __builtin_nontemporal_store(f, p.dst + (k + e) * p.ld + r);      // written once, not read again here
         }
     }
 }
