@@ -345,6 +345,33 @@ def _paper_formats(torch, hbfp, reps=8):
     return {"paper_formats": res}
 
 
+def _batched_products(torch, hbfp, reps=10):
+    """hbfp_gemm_batch: four independent products of 2048 x 2048 x 4096 in config 4's formats (64 output tiles of
+    256 x 256 each).  One call shares a launch of the block-scaled kernel among them; the same products one after
+    the other go to the int8 kernels."""
+    g = torch.Generator(device="cuda").manual_seed(12)
+    row, tile = hbfp.make_format(8, 1, 24), hbfp.make_format(8, 24, 24)
+    pairs, outs = [], []
+    for _ in range(4):
+        X = torch.randn((2048, 4096), device="cuda", generator=g)
+        W = torch.randn((4096, 2048), device="cuda", generator=g) * 0.02
+        pairs.append((hbfp.encode(X, 1, row), hbfp.encode(W, 0, tile)))
+        outs.append(torch.empty((2048, 2048), dtype=torch.float32, device="cuda"))
+    ws_one = [torch.empty(max(hbfp.gemm_workspace(a.desc, b.desc), 256), dtype=torch.uint8, device="cuda") for a, b in pairs]
+    ws_all = torch.empty(max(hbfp.gemm_batch_workspace(pairs), 256), dtype=torch.uint8, device="cuda")
+
+    def one_by_one():
+        for i, (a, b) in enumerate(pairs):
+            hbfp.gemm(a, b, out=outs[i], workspace=ws_one[i])
+
+    ms_seq = _time_call(torch, one_by_one, reps)
+    ms_bat = _time_call(torch, lambda: hbfp.gemm_batch(pairs, outs, workspace=ws_all), reps)
+    flops = 4 * 2.0 * 2048 * 2048 * 4096
+    return {"batch_4x_2048x2048x4096": {"one_by_one_ms": round(ms_seq, 4), "one_call_ms": round(ms_bat, 4),
+                                        "TOPS_one_by_one": round(flops / ms_seq / 1e9, 1),
+                                        "TOPS_one_call": round(flops / ms_bat / 1e9, 1)}}
+
+
 def _kernel_families(torch, hbfp, reps=8):
     """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
     int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
@@ -523,6 +550,7 @@ def main():
         extra.update(_weight_update_config4(torch, hbfp, synth))
         extra.update(_kernel_families(torch, hbfp))
         extra.update(_paper_formats(torch, hbfp))
+        extra.update(_batched_products(torch, hbfp))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)

@@ -269,6 +269,22 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_gemm_batch: up to HBFP_BATCH_MAX independent products C[i] (+)= A[i] . B[i]^T in one call (the data-gradient
+ * and weight-gradient products of a layer, Sec. 5.1; the products of several layers or micro-batches).  Every
+ * product is what hbfp_gemm_select computes for it.  Products that take the block-scaled kernel with the same limb
+ * counts share one launch, so that a compute unit that finishes a tile of one product goes on with a tile of
+ * the next while its stores drain; the others run one after the other.
+ *   A, B, C, ldc   host arrays of n descriptors / device pointers / leading dimensions
+ *   kernel         HBFP_KERNEL_* as for hbfp_gemm_select, applied to every product
+ *   workspace      hbfp_gemm_batch_workspace bytes (the sum of the products' own workspaces)
+ * Errors: as hbfp_gemm_select for the first product that fails a check (nothing has been launched then).
+ */
+#define HBFP_BATCH_MAX 4
+int hbfp_gemm_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, size_t *bytes);
+int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, float *const *C, const int64_t *ldc,
+                    float beta, int kernel, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_pack / hbfp_gemm_packed: the block-scaled kernel in two steps, for operands that take part in many
  * products (weights between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders
  * an encoded operand (mantissas of at most 12 bits) into the limb planes that kernel reads:

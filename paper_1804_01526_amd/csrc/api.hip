@@ -430,6 +430,92 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
     return hbfp_gemm_select(A, B, C, ldc, beta, HBFP_KERNEL_AUTO, workspace, ws_bytes, stream);
 }
 
+// Checks the products of a batch and decides whether they share one launch of the block-scaled kernel; part[i] is
+// product i's share of the workspace.
+static int batch_plan(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, GemmArgs *g, size_t *part,
+                      bool *grouped) {
+    if (!A || !B || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    bool all_scaled = true, same = true;
+    for (int i = 0; i < n; ++i) {
+        if (!A[i] || !B[i]) return HBFP_ERR_ARG;
+        const int rc = check_pair(A[i], B[i]);
+        if (rc != HBFP_OK) return rc;
+        g[i] = gemm_args(A[i], B[i]);
+        all_scaled = all_scaled && use_scaled(g[i], kernel);
+        same = same && (A[i]->mant_bits > 8) == (A[0]->mant_bits > 8) && mx_same_limbs(g[i], g[0]);
+    }
+    // products that would each take the block-scaled kernel anyway, or (automatic choice) that fill the chip only together
+    *grouped = n > 1 && same && (all_scaled || (kernel == HBFP_KERNEL_AUTO && gemm_mx_group_ok(n, g)));
+    for (int i = 0; i < n; ++i) {
+        hbfp_gemm_select_workspace(A[i], B[i], *grouped ? HBFP_KERNEL_SCALED : kernel, &part[i]);
+        part[i] = align256(part[i]);
+    }
+    return HBFP_OK;
+}
+
+int hbfp_gemm_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    GemmArgs g[HBFP_BATCH_MAX];
+    size_t part[HBFP_BATCH_MAX];
+    bool grouped = false;
+    const int rc = batch_plan(n, A, B, kernel, g, part, &grouped);
+    if (rc != HBFP_OK) return rc;
+    *bytes = 0;
+    for (int i = 0; i < n; ++i) *bytes += part[i];
+    return HBFP_OK;
+}
+
+int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, float *const *C, const int64_t *ldc,
+                    float beta, int kernel, void *workspace, size_t ws_bytes, void *stream) {
+    if (!C || !ldc) return HBFP_ERR_ARG;
+    if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
+    GemmArgs g[HBFP_BATCH_MAX];
+    size_t part[HBFP_BATCH_MAX], need = 0;
+    bool grouped = false;
+    int rc = batch_plan(n, A, B, kernel, g, part, &grouped);
+    if (rc != HBFP_OK) return rc;
+    for (int i = 0; i < n; ++i) {
+        if (!C[i] || ldc[i] < B[i]->rows || ((uintptr_t)C[i] & 3)) return HBFP_ERR_ARG;
+        if (kernel == HBFP_KERNEL_INT8_WIDE && !gemm_wide_possible(g[i])) return HBFP_ERR_FORMAT;
+        need += part[i];
+        g[i].C = C[i];
+        g[i].ldc = ldc[i];
+        g[i].beta = beta;
+    }
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    if (!grouped) {
+        for (int i = 0; i < n; ++i) {
+            rc = run_gemm(A[i], B[i], C[i], ldc[i], beta, nullptr, kernel, ws, part[i], stream);
+            if (rc != HBFP_OK) return rc;
+            ws += part[i];
+        }
+        return HBFP_OK;
+    }
+    const void *pa[HBFP_BATCH_MAX], *pb[HBFP_BATCH_MAX];
+    void *standby[HBFP_BATCH_MAX];
+    for (int i = 0; i < n; ++i) {                                    // product i: [packed A][packed B][int8 workspace]
+        char *a = ws, *b = a + mx_packed_bytes(g[i].M, g[i].kpad, g[i].mA);
+        standby[i] = b + mx_packed_bytes(g[i].N, g[i].kpad, g[i].mB);
+        rc = launch_mx_pack(g[i], a, b, s);
+        if (rc != HBFP_OK) return rc;
+        pa[i] = a;
+        pb[i] = b;
+        ws += part[i];
+    }
+    rc = launch_mx_products(n, g, pa, pb, s);
+    if (rc != HBFP_OK) return rc;
+    for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
+        g[i].run_a = (const int *)pa[i];
+        g[i].run_b = (const int *)pb[i];
+        rc = A[i]->mant_bits > 8 ? launch_gemm_limb(g[i], standby[i], s) : launch_gemm_i8(g[i], standby[i], s);
+        if (rc != HBFP_OK) return rc;
+    }
+    return HBFP_OK;
+}
+
 int hbfp_pack_bytes(const hbfp_tensor *t, size_t *bytes) {
     if (!bytes) return HBFP_ERR_ARG;
     const int rc = check_tensor(t, false);

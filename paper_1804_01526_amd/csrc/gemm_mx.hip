@@ -224,6 +224,17 @@ struct MxParams {
     int32_t ksteps, tiles_m, tiles_n, beta;
 };
 
+// Up to kMxGroup independent products in one launch (the data-gradient and weight-gradient products of a layer, the
+// products of several layers or micro-batches): workgroups first[i] .. first[i + 1] - 1 belong to product i.  A
+// CU that finishes a tile of one product goes on with a tile of the next, so the stores of the first drain under the
+// matrix instructions of the second; launched one by one, every product ends with all CUs storing at once.
+constexpr int kMxGroup = 4;
+struct MxGroup {
+    MxParams p[kMxGroup];
+    int32_t first[kMxGroup + 1];
+    int32_t n;
+};
+
 // The product kernel is a set of macros over its local arrays (function templates taking the fragment arrays by
 // reference left them in scratch memory).
 // Fragment registers: af[buffer][row tile][3 * limb + piece], bf[buffer][3 * limb + piece]: the codes of a lane are read
@@ -331,7 +342,7 @@ struct MxParams {
     }
 
 template <int LA, int LB>
-__global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p) {
+__global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxGroup g) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int CHA = chunk_bytes(LA), CHB = chunk_bytes(LB);
     constexpr int SA = panel_stage_bytes(LA), SB = panel_stage_bytes(LB), STAGE = SA + SB;
@@ -340,9 +351,19 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxParams p
     constexpr int NCOPY = (PIECES + 7) / 8;                    // per wave and stage
     constexpr bool ONE_A = LA > 2 || LB > 2;                   // three limbs: no room for a second set of row-tile registers
 
+    // which product this workgroup belongs to: selected with constant indices, so that the parameters stay in
+    // scalar registers (the copy instructions take their base addresses from there)
+    MxParams p = g.p[0];
+    int first_wg = 0;
+#pragma unroll
+    for (int i = 1; i < kMxGroup; ++i)
+        if (i < g.n && (int)blockIdx.x >= g.first[i]) {
+            p = g.p[i];
+            first_wg = g.first[i];
+        }
     if (p.ha[0] == p.ha[1] || p.hb[0] == p.hb[1]) return;      // uniform: the int8 kernels take over
     int tm, tn;
-    if (!tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    if (!tile_of_workgroup((int)blockIdx.x - first_wg, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -637,7 +658,7 @@ int launch_pack_t(const PackPair &q, unsigned blocks, hipStream_t s) {
 }
 
 template <int LA, int LB>
-int launch_mx_t(const MxParams &p, hipStream_t s) {
+int launch_mx_t(const MxGroup &g, hipStream_t s) {
     constexpr int bytes = mx_lds_bytes(LA, LB);
     static bool configured = false;
     if (!configured) {
@@ -646,8 +667,7 @@ int launch_mx_t(const MxParams &p, hipStream_t s) {
             return HBFP_ERR_LAUNCH;
         configured = true;
     }
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB>), dim3((unsigned)(ceil_div(tiles, 8) * 8)), dim3(kMxThreads), bytes, s, p);
+    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB>), dim3((unsigned)g.first[g.n]), dim3(kMxThreads), bytes, s, g);
     return launch_status();
 }
 
@@ -659,6 +679,10 @@ int launch_mx_t(const MxParams &p, hipStream_t s) {
 // matrix instruction (blocks of at most 32, stored padded to 32: 8 to 20 % faster), not for longer blocks; one or two
 // limb products (an operand of at most 5 bits: 2 x faster) and the 12-bit formats (6 or 9 limb products against four
 // int8 products plus five vector instructions per output and block: 1.4 x faster) win for every block length.
+bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b) {
+    return limbs_of(a.mA) == limbs_of(b.mA) && limbs_of(a.mB) == limbs_of(b.mB);
+}
+
 bool gemm_mx_possible(const GemmArgs &a) {
     return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 64 <= 0x7fffffff;
 }
@@ -674,6 +698,23 @@ bool gemm_mx_ok(const GemmArgs &a) {
     // kernel a scaling pass per padded block as well: 15 to 20 % ahead at 4096^3
     if (products == 4) return a.kbp == 32;
     return true;
+}
+
+// Products that share one launch.  Measured with 8-bit mantissas in blocks of 32 against the int8 kernels run one
+// after the other: four products of 64 tiles each (2048 x 2048) 5 to 14 % ahead for contractions of 1024 to 4096;
+// 128 tiles or fewer in the whole group (four of 2048 x 1024 x 8192, four of 1024 x 1024 x 4096) 5 to 7 % behind.
+bool gemm_mx_group_ok(int n, const GemmArgs *args) {
+    int64_t tiles = 0;
+    double area = 0.0, work = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const GemmArgs &a = args[i];
+        if (!gemm_mx_possible(a) || !mx_same_limbs(a, args[0])) return false;
+        if (limbs_of(a.mA) * limbs_of(a.mB) == 4 && a.kbp != 32) return false;
+        tiles += ceil_div(a.M, 256) * ceil_div(a.N, 256);
+        area += (double)a.M * (double)a.N;
+        work += (double)a.M * (double)a.N * (double)a.kpad;
+    }
+    return tiles >= 256 && area >= 0.75 * 65536.0 * (double)tiles && work >= 1.5e10;
 }
 
 size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits) { return 256 + packed_bytes(rows, kpad, limbs_of(mant_bits)); }
@@ -713,31 +754,48 @@ int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
     }
 }
 
-int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s) {
-    const int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
-    MxParams p;
-    p.ha = (const int *)packed_a;
-    p.hb = (const int *)packed_b;
-    p.pa = (const uint8_t *)packed_a + 256;
-    p.pb = (const uint8_t *)packed_b + 256;
-    p.C = a.C;
-    p.M = a.M;
-    p.N = a.N;
-    p.ldc = a.ldc;
-    p.ksteps = (int32_t)(a.kpad / 64);
-    p.tiles_m = (int32_t)ceil_div(a.M, 256);
-    p.tiles_n = (int32_t)ceil_div(a.N, 256);
-    p.beta = a.beta != 0.0f;
+// n <= kMxGroup products with the same limb counts in one launch
+int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
+    if (n < 1 || n > kMxGroup) return HBFP_ERR_ARG;
+    const int LA = limbs_of(args[0].mA), LB = limbs_of(args[0].mB);
+    MxGroup g = {};
+    g.n = n;
+    int64_t first = 0;
+    for (int i = 0; i < n; ++i) {
+        const GemmArgs &a = args[i];
+        if (limbs_of(a.mA) != LA || limbs_of(a.mB) != LB) return HBFP_ERR_FORMAT;
+        MxParams &p = g.p[i];
+        p.ha = (const int *)packed_a[i];
+        p.hb = (const int *)packed_b[i];
+        p.pa = (const uint8_t *)packed_a[i] + 256;
+        p.pb = (const uint8_t *)packed_b[i] + 256;
+        p.C = a.C;
+        p.M = a.M;
+        p.N = a.N;
+        p.ldc = a.ldc;
+        p.ksteps = (int32_t)(a.kpad / 64);
+        p.tiles_m = (int32_t)ceil_div(a.M, 256);
+        p.tiles_n = (int32_t)ceil_div(a.N, 256);
+        p.beta = a.beta != 0.0f;
+        g.first[i] = (int32_t)first;
+        first += ceil_div((int64_t)p.tiles_m * p.tiles_n, 8) * 8;      // a multiple of 8: the XCD of a tile does not depend on the group
+        if (first > 0x7ffffff0) return HBFP_ERR_ARG;
+    }
+    for (int i = n; i <= kMxGroup; ++i) g.first[i] = (int32_t)first;
     switch (LA * 4 + LB) {
-        case 1 * 4 + 1: return launch_mx_t<1, 1>(p, s);
-        case 1 * 4 + 2: return launch_mx_t<1, 2>(p, s);
-        case 2 * 4 + 1: return launch_mx_t<2, 1>(p, s);
-        case 2 * 4 + 2: return launch_mx_t<2, 2>(p, s);
-        case 2 * 4 + 3: return launch_mx_t<2, 3>(p, s);
-        case 3 * 4 + 2: return launch_mx_t<3, 2>(p, s);
-        case 3 * 4 + 3: return launch_mx_t<3, 3>(p, s);
+        case 1 * 4 + 1: return launch_mx_t<1, 1>(g, s);
+        case 1 * 4 + 2: return launch_mx_t<1, 2>(g, s);
+        case 2 * 4 + 1: return launch_mx_t<2, 1>(g, s);
+        case 2 * 4 + 2: return launch_mx_t<2, 2>(g, s);
+        case 2 * 4 + 3: return launch_mx_t<2, 3>(g, s);
+        case 3 * 4 + 2: return launch_mx_t<3, 2>(g, s);
+        case 3 * 4 + 3: return launch_mx_t<3, 3>(g, s);
         default: return HBFP_ERR_FORMAT;
     }
+}
+
+int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s) {
+    return launch_mx_products(1, &a, &packed_a, &packed_b, s);
 }
 
 }  // namespace hbfp

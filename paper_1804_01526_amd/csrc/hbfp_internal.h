@@ -80,6 +80,9 @@ bool gemm_mx_ok(const GemmArgs &a);         // shapes and formats for which it i
 size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits);   // header + planes, a multiple of 256
 // packs operand A (rows a.M) and / or operand B (rows a.N) of `a` in one launch; a null buffer skips that operand
 int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
+bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);
+bool gemm_mx_group_ok(int n, const GemmArgs *args);
+int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
 int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s);
 
 }  // namespace hbfp

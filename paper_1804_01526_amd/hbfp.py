@@ -76,6 +76,9 @@ def _load():
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
     lib.hbfp_gemm_select.argtypes = [T, T, vp, i64, ctypes.c_float, i32, vp, sz, vp]
+    lib.hbfp_gemm_batch_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(T), i32, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_batch.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(T), ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                    ctypes.c_float, i32, vp, sz, vp]
     lib.hbfp_pack_bytes.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_pack.argtypes = [T, vp, sz, vp]
     lib.hbfp_gemm_packed_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
@@ -87,7 +90,7 @@ def _load():
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -227,6 +230,28 @@ def gemm(a: BfpTensor, b: BfpTensor, out: Optional[torch.Tensor] = None, beta: f
     return out
 
 
+def gemm_batch_workspace(pairs, kernel: int = KERNEL_AUTO) -> int:
+    """pairs: sequence of (A, B), each a BfpTensor or a TensorDesc."""
+    n = ctypes.c_size_t(0)
+    a, b = _desc_array([p[0] for p in pairs]), _desc_array([p[1] for p in pairs])
+    _check(_lib.hbfp_gemm_batch_workspace(len(pairs), a, b, kernel, ctypes.byref(n)), "hbfp_gemm_batch_workspace")
+    return int(n.value)
+
+
+def gemm_batch(pairs, outs, beta: float = 0.0, kernel: int = KERNEL_AUTO, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_gemm_batch: outs[i] (+)= A[i] . B[i]^T for up to 4 independent products in one call."""
+    n = len(pairs)
+    a, b = _desc_array([p[0] for p in pairs]), _desc_array([p[1] for p in pairs])
+    for o in outs:
+        assert o.is_cuda and o.dtype == torch.float32 and o.stride(1) == 1
+    c = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+    ld = (ctypes.c_int64 * n)(*[o.stride(0) for o in outs])
+    workspace = _workspace(gemm_batch_workspace(pairs, kernel), outs[0].device, workspace)
+    _check(_lib.hbfp_gemm_batch(n, a, b, c, ld, beta, kernel, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                _stream_ptr(stream)), "hbfp_gemm_batch")
+    return outs
+
+
 def pack_bytes(desc: TensorDesc) -> int:
     n = ctypes.c_size_t(0)
     _check(_lib.hbfp_pack_bytes(ctypes.byref(desc), ctypes.byref(n)), "hbfp_pack_bytes")
@@ -315,7 +340,7 @@ def weight_update(wide: BfpTensor, delta: torch.Tensor, alpha: float, narrow_a: 
 def _desc_array(outs):
     arr = (ctypes.POINTER(TensorDesc) * len(outs))()
     for i, t in enumerate(outs):
-        arr[i] = ctypes.pointer(t.desc)
+        arr[i] = ctypes.pointer(t.desc if hasattr(t, "desc") else t)     # BfpTensor or bare descriptor
     return arr
 
 

@@ -225,6 +225,49 @@ def test_gemm_select_validation():
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
 
 
+def test_gemm_batch_validation():
+    """hbfp_gemm_batch: argument checks happen before any launch; products that fill the chip only together are
+    grouped by the automatic choice (seen through the workspace, which then holds limb planes)."""
+    lib = hbfp._lib
+    fake = ctypes.c_void_p(0x1000)
+
+    def desc(m, rows, cols, axis, br, bc):
+        d = hbfp.plan(hbfp.make_format(m, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    def pair(m, M, N, K, blk):
+        return desc(m, M, K, 1, 1, blk), desc(m, K, N, 0, blk, 1)
+
+    def call(pairs, kernel=0, ws_bytes=1 << 30, n=None, ldc=None):
+        n = len(pairs) if n is None else n
+        a, b = hbfp._desc_array([p[0] for p in pairs]), hbfp._desc_array([p[1] for p in pairs])
+        c = (ctypes.c_void_p * len(pairs))(*[0x3000] * len(pairs))
+        ld = (ctypes.c_int64 * len(pairs))(*(ldc or [p[1].rows for p in pairs]))
+        return lib.hbfp_gemm_batch(n, a, b, c, ld, 0.0, kernel, fake, ws_bytes, None)
+
+    small = pair(8, 128, 64, 256, 32)
+    assert call([small] * 5) == hbfp.ERR_ARG and call([small], n=0) == hbfp.ERR_ARG
+    assert call([small, small], kernel=9) == hbfp.ERR_ARG
+    assert call([small, small], ldc=[64, 63]) == hbfp.ERR_ARG
+    assert call([small, (small[0], desc(8, 256, 64, 0, 64, 1))]) != hbfp.OK            # blocks disagree
+    need = hbfp.gemm_batch_workspace([small, small], hbfp.KERNEL_SCALED)
+    assert need == 2 * hbfp.gemm_select_workspace(small[0], small[1], hbfp.KERNEL_SCALED)
+    assert call([small, small], kernel=hbfp.KERNEL_SCALED, ws_bytes=need - 256) == hbfp.ERR_WORKSPACE
+    assert hbfp.gemm_batch_workspace([small, small]) == 2 * hbfp.gemm_workspace(small[0], small[1])
+    # four products of 64 tiles each: alone each takes the int8 kernels, together the block-scaled kernel
+    q = pair(8, 2048, 2048, 2048, 32)
+    alone, scaled = hbfp.gemm_workspace(q[0], q[1]), hbfp.gemm_select_workspace(q[0], q[1], hbfp.KERNEL_SCALED)
+    assert alone < scaled
+    assert hbfp.gemm_batch_workspace([q] * 4) == 4 * scaled
+    assert hbfp.gemm_batch_workspace([q] * 2) == 2 * alone                         # 128 tiles: not together either
+    assert hbfp.gemm_batch_workspace([q] * 4, hbfp.KERNEL_INT8) == 4 * alone
+    q64 = pair(8, 2048, 2048, 2048, 64)                                            # blocks of 64: the int8 kernels are ahead
+    assert hbfp.gemm_batch_workspace([q64] * 4) == 4 * hbfp.gemm_workspace(q64[0], q64[1])
+    q12 = pair(12, 2048, 2048, 2048, 64)                                           # limb counts differ: one after the other
+    assert hbfp.gemm_batch_workspace([q, q, q12, q12]) == 2 * alone + 2 * hbfp.gemm_workspace(q12[0], q12[1])
+
+
 def test_gemm_f32_validation():
     lib = hbfp._lib
     byref = ctypes.byref

@@ -791,3 +791,141 @@ def test_wide_kernel_large_product_sampled(hb):
     rows = np.sort(rng.choice(4096, size=24, replace=False))
     _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, rows=rows)
     _run(hb, A, B, (1, 0, 8, 0, 0), (0, 1, 8, 0, 0), partials=False, rows=rows, kernel=WIDE)
+
+
+@pytest.mark.parametrize("m,blk,kernel", [(8, 32, SCALED), (12, 64, SCALED), (8, 24, 0), (8, 32, 1)])
+def test_batch_of_products(hb, m, blk, kernel):
+    """hbfp_gemm_batch: products of different shapes in one call (block-scaled kernel: one grouped launch; otherwise
+    one after the other); each equals the single-product call bit for bit and the oracle within the bound."""
+    print(f"[case] batch m={m} blk={blk} kernel={kernel}", flush=True)
+    fa, fb = (1, blk, m, 0, 0), (blk, 1, m, 0, 0)
+    shapes = [(300, 270, 704), (520, 130, 330), (257, 513, 64), (70, 90, 1000)]
+    pairs, mats = [], []
+    for i, (M, N, K) in enumerate(shapes):
+        A, B = _rand((M, K), 40 + i), _rand((K, N), 50 + i)
+        ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(m, 1, blk))
+        tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(m, blk, 1))
+        pairs.append((ta, tb))
+        mats.append((A, B))
+    for n in (1, 2, 4):
+        outs = [torch.full((M, N), 7.0, device="cuda") for (M, N, K) in shapes[:n]]
+        hb.gemm_batch(pairs[:n], outs, kernel=kernel)
+        torch.cuda.synchronize()
+        for i in range(n):
+            single = hb.gemm(pairs[i][0], pairs[i][1], kernel=kernel)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[i], single), f"product {i} of {n}"
+            if n == 4:
+                assert rel_fro(outs[i].cpu().numpy(), _oracle_product(mats[i][0], mats[i][1], fa, fb)) <= TOL
+    # accumulate on top of the previous result (beta = 1)
+    before = [o.clone() for o in outs]
+    hb.gemm_batch(pairs, outs, beta=1.0, kernel=kernel)
+    torch.cuda.synchronize()
+    for i in range(4):
+        want = _oracle_product(mats[i][0], mats[i][1], fa, fb) + before[i].cpu().numpy().astype(np.float64)
+        assert rel_fro(outs[i].cpu().numpy(), want) <= TOL
+
+
+def test_batch_with_one_product_outside_the_scale_range(hb):
+    """A grouped launch in which one product has exponents the scale bytes cannot hold: that product comes from
+    the int8 kernels behind the group, the others from the block-scaled kernel."""
+    m, blk = 8, 32
+    fa, fb = (1, blk, m, 0, 0), (blk, 1, m, 0, 0)
+    pairs, mats = [], []
+    for i in range(3):
+        A, B = _rand((260 + 8 * i, 256), 60 + i), _rand((256, 300 - 16 * i), 70 + i)
+        if i == 1:
+            A = (A.astype(np.float64) * 2.0 ** -124).astype(np.float32)
+            B = (B.astype(np.float64) * 2.0 ** 100).astype(np.float32)
+        pairs.append((hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(m, 1, blk)),
+                      hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(m, blk, 1))))
+        mats.append((A, B))
+    outs = [torch.full((p[0].desc.rows, p[1].desc.rows), -3.0, device="cuda") for p in pairs]
+    hb.gemm_batch(pairs, outs, kernel=SCALED)
+    torch.cuda.synchronize()
+    for i in range(3):
+        print(f"[case] batch, product {i}", flush=True)
+        assert rel_fro(outs[i].cpu().numpy(), _oracle_product(mats[i][0], mats[i][1], fa, fb)) <= TOL
+
+
+def test_batch_mixed_formats_and_argument_checks(hb):
+    """Products whose limb counts differ cannot share a launch and run one after the other; bad arguments are
+    reported before anything runs."""
+    A, B = _rand((130, 256), 1), _rand((256, 140), 2)
+    t8 = (hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(8, 1, 32)), hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 32, 1)))
+    t12 = (hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(12, 1, 64)), hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(12, 64, 1)))
+    outs = [torch.empty((130, 140), device="cuda") for _ in range(2)]
+    hb.gemm_batch([t8, t12], outs, kernel=SCALED)
+    torch.cuda.synchronize()
+    assert rel_fro(outs[0].cpu().numpy(), _oracle_product(A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0))) <= TOL
+    assert rel_fro(outs[1].cpu().numpy(), _oracle_product(A, B, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0))) <= TOL
+    with pytest.raises(hb.HbfpError):
+        hb.gemm_batch([t8] * 5, [outs[0]] * 5)
+    with pytest.raises(hb.HbfpError):
+        hb.gemm_batch([t8, (t8[0], t12[1])], outs)                     # operands of one product disagree
+    with pytest.raises(hb.HbfpError):
+        hb.gemm_batch([t8, t8], outs, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"), kernel=SCALED)
+
+
+def test_batch_that_fills_the_chip_only_together_sampled(hb):
+    """Four products of 64 output tiles each: alone the library gives each to the int8 kernels, in one batch they
+    share a launch of the block-scaled kernel.  Sampled rows against the oracle; every product bit for bit what
+    the block-scaled kernel returns for it alone."""
+    M = N = 2048
+    K = 1024
+    fa, fb = (1, 32, 8, 0, 0), (32, 1, 8, 0, 0)
+    rows = np.sort(np.random.default_rng(9).choice(M, size=24, replace=False))
+    pairs, want = [], []
+    for i in range(4):
+        A, B = _rand((M, K), 80 + i), (_rand((K, N), 90 + i, 2) * 0.02).astype(np.float32)
+        pairs.append((hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(8, 1, 32)),
+                      hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 32, 1))))
+        want.append(ref.gemm(ref.decode(ref.encode(A, *fa)), ref.decode(ref.encode(B, *fb)), rows=rows))
+    assert hb.gemm_workspace(pairs[0][0].desc, pairs[0][1].desc) == hb.gemm_select_workspace(pairs[0][0].desc, pairs[0][1].desc, 1)
+    assert hb.gemm_batch_workspace(pairs) == 4 * hb.gemm_select_workspace(pairs[0][0].desc, pairs[0][1].desc, SCALED)
+    outs = [torch.full((M, N), 5.0, device="cuda") for _ in range(4)]
+    hb.gemm_batch(pairs, outs)
+    torch.cuda.synchronize()
+    for i in range(4):
+        print(f"[case] grouped batch, product {i}", flush=True)
+        assert rel_fro(outs[i].cpu().numpy()[rows], want[i]) <= TOL
+        alone = hb.gemm(pairs[i][0], pairs[i][1], kernel=SCALED)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[i], alone)
+
+
+def test_batch_in_a_replayed_graph(hb):
+    """A captured batch (activations encoded inside the graph, two products sharing a launch): every replay, with new
+    activations and eager work between replays, equals the eager result; one replay is outside the scale range."""
+    m, blk, M, N, K = 8, 32, 260, 300, 640
+    rng = np.random.default_rng(14)
+    fmt = hb.make_format(m, 1, blk)
+    Ws = [(rng.standard_normal((K, N - 40 * i)) * 0.05).astype(np.float32) for i in range(2)]
+    tws = [hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(m, blk, 1)) for W in Ws]
+    x = torch.zeros((M, K), device="cuda")
+    tx = hb.encode(x, 1, fmt)
+    pairs = [(tx, tw) for tw in tws]
+    ws = torch.empty(hb.gemm_batch_workspace(pairs, SCALED), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty((M, W.shape[1]), device="cuda") for W in Ws]
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        hb.encode(x, 1, fmt, out=tx, stream=stream)
+        hb.gemm_batch(pairs, outs, kernel=SCALED, workspace=ws, stream=stream)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            hb.encode(x, 1, fmt, out=tx, stream=stream)
+            hb.gemm_batch(pairs, outs, kernel=SCALED, workspace=ws, stream=stream)
+    for i, scale in enumerate([1.0, 2.0 ** -124, 1.0, 3.0]):
+        X = (rng.standard_normal((M, K)) * scale).astype(np.float32)
+        x.copy_(torch.from_numpy(X).cuda())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        print(f"[case] batch graph replay {i} scale={scale}", flush=True)
+        for j in range(2):
+            eager = hb.gemm(hb.encode(x, 1, fmt), tws[j], kernel=SCALED)
+            torch.cuda.synchronize()
+            assert rel_fro(got[j].cpu().numpy(), eager.cpu().numpy()) <= 2e-6
+            assert rel_fro(got[j].cpu().numpy(), _oracle_product(X, Ws[j], (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
