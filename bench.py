@@ -372,6 +372,34 @@ def _batched_products(torch, hbfp, reps=10):
                                         "TOPS_one_call": round(flops / ms_bat / 1e9, 1)}}
 
 
+def _encoded_output(torch, hbfp, reps=10):
+    """hbfp_gemm_bfp: a 4096^3 product (activations in 1 x 32 blocks, weights in 32 x 32 tiles) delivered as the next
+    product's operand (ReLU, 1 x 32 blocks, stochastic rounding), against hbfp_gemm followed by hbfp_encode."""
+    g = torch.Generator(device="cuda").manual_seed(13)
+    n = 4096
+    X = torch.randn((n, n), device="cuda", generator=g)
+    W = torch.randn((n, n), device="cuda", generator=g) * 0.02
+    tx, tw = hbfp.encode(X, 1, hbfp.make_format(8, 1, 32)), hbfp.encode(W, 0, hbfp.make_format(8, 32, 32))
+    del X, W
+    res = {}
+    for tag, rounding in (("rne", hbfp.RNE), ("sr", hbfp.STOCHASTIC)):
+        fmt = hbfp.make_format(8, 1, 32, rounding, 5)
+        out = hbfp.alloc(fmt, n, n, 1)
+        C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+        ws = torch.empty(hbfp.gemm_workspace(tx.desc, tw.desc), dtype=torch.uint8, device="cuda")
+        wsb = torch.empty(hbfp.gemm_bfp_workspace(tx.desc, tw.desc, out.desc), dtype=torch.uint8, device="cuda")
+
+        def two_calls():
+            hbfp.gemm(tx, tw, out=C, workspace=ws)
+            C.clamp_(min=0)                                   # the ReLU as a pass of its own over the FP32 product
+            hbfp.encode(C, 1, fmt, out=out)
+
+        ms2 = _time_call(torch, two_calls, reps)
+        ms1 = _time_call(torch, lambda: hbfp.gemm_bfp(tx, tw, fmt, 1, relu=True, out=out, workspace=wsb), reps)
+        res[tag] = {"gemm_relu_encode_ms": round(ms2, 4), "gemm_bfp_ms": round(ms1, 4)}
+    return {"encoded_output_4096_cubed": res}
+
+
 def _kernel_families(torch, hbfp, reps=8):
     """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
     int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
@@ -551,6 +579,7 @@ def main():
         extra.update(_kernel_families(torch, hbfp))
         extra.update(_paper_formats(torch, hbfp))
         extra.update(_batched_products(torch, hbfp))
+        extra.update(_encoded_output(torch, hbfp))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)

@@ -285,6 +285,25 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
                     float beta, int kernel, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_gemm_bfp: the product A . B^T delivered as an encoded operand instead of FP32: out = encode(relu?(A . B^T)),
+ * the FP -> BFP conversion of Sec. 4.1 (with the rounding of Sec. 5.3 that `out` names) applied where the product
+ * is produced, so that the next product's operand never makes the trip through an FP32 matrix in memory.
+ *   out      planned with hbfp_plan for a source matrix of A->rows x B->rows (either contraction axis, any format);
+ *            out->mant / out->exps device, written; stochastic rounding draws by position in the product matrix
+ *   relu     0 or 1: max(x, 0) on the FP32 values before the conversion (the one floating-point operation between two
+ *            products that needs no other operand)
+ *   kernel   HBFP_KERNEL_* as for hbfp_gemm_select
+ * The result equals hbfp_gemm_select followed by hbfp_encode of its output, bit for bit.  When the block-scaled kernel
+ * computes the product and out has k along the columns of the product in blocks of 32 or 64 (one exponent per block
+ * and row), the kernel converts its accumulators itself; otherwise the FP32 product goes through the workspace.
+ *   workspace  hbfp_gemm_bfp_workspace bytes (includes A->rows * B->rows floats), 256-byte aligned
+ * Errors: as hbfp_gemm_select; HBFP_ERR_LAYOUT if out is not the plan of an A->rows x B->rows matrix.
+ */
+int hbfp_gemm_bfp_workspace(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, size_t *bytes);
+int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int relu, int kernel, void *workspace,
+                  size_t ws_bytes, void *stream);
+
+/*
  * hbfp_pack / hbfp_gemm_packed: the block-scaled kernel in two steps, for operands that take part in many
  * products (weights between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders
  * an encoded operand (mantissas of at most 12 bits) into the limb planes that kernel reads:

@@ -516,6 +516,73 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
     return HBFP_OK;
 }
 
+// Workspace of hbfp_gemm_bfp: [FP32 product M x N][workspace of the product][workspace of the conversion]
+static int gemm_bfp_plan(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, bool need_ptrs,
+                         bool *fused, size_t part[3]) {
+    if (!A || !B || !out) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    int rc = need_ptrs ? check_pair(A, B) : check_tensor(A, false);
+    if (rc == HBFP_OK && !need_ptrs) rc = check_tensor(B, false);
+    if (rc == HBFP_OK) rc = check_tensor(out, need_ptrs);
+    if (rc != HBFP_OK) return rc;
+    if (out->src_rows != A->rows || out->src_cols != B->rows) return HBFP_ERR_LAYOUT;
+    const GemmArgs g = gemm_args(A, B);
+    *fused = use_scaled(g, kernel) && mx_encoded_output_ok(*out);
+    part[0] = align256((size_t)A->rows * (size_t)B->rows * sizeof(float));
+    hbfp_gemm_select_workspace(A, B, kernel, &part[1]);
+    part[1] = align256(part[1]);
+    part[2] = 0;
+    if (!*fused) hbfp_encode_workspace(out, &part[2]);
+    part[2] = align256(part[2]);
+    return HBFP_OK;
+}
+
+int hbfp_gemm_bfp_workspace(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    bool fused = false;
+    size_t part[3];
+    const int rc = gemm_bfp_plan(A, B, out, kernel, false, &fused, part);
+    if (rc != HBFP_OK) return rc;
+    *bytes = part[0] + part[1] + part[2];
+    return HBFP_OK;
+}
+
+int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int relu, int kernel, void *workspace,
+                  size_t ws_bytes, void *stream) {
+    bool fused = false;
+    size_t part[3];
+    int rc = gemm_bfp_plan(A, B, out, kernel, true, &fused, part);
+    if (rc != HBFP_OK) return rc;
+    if (relu != 0 && relu != 1) return HBFP_ERR_ARG;
+    if (!workspace || ws_bytes < part[0] + part[1] + part[2] || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    float *C = (float *)workspace;
+    char *ws_gemm = (char *)workspace + part[0], *ws_enc = ws_gemm + part[1];
+    const int64_t M = A->rows, N = B->rows;
+    if (!fused) {
+        rc = run_gemm(A, B, C, N, 0.0f, nullptr, kernel, ws_gemm, part[1], stream);
+        if (rc == HBFP_OK && relu) rc = launch_relu(C, M * N, s);
+        if (rc != HBFP_OK) return rc;
+        return encode_planned(C, N, out, part[2] != 0, ws_enc, s);
+    }
+    // the block-scaled kernel converts its accumulators; should an exponent be outside its range, the int8 kernels behind
+    // it write the FP32 product to the workspace and a conversion behind them produces the same output
+    GemmArgs g = gemm_args(A, B);
+    g.C = C;
+    g.ldc = N;
+    g.beta = 0.0f;
+    void *pa = ws_gemm, *pb = ws_gemm + mx_packed_bytes(g.M, g.kpad, g.mA);
+    rc = launch_mx_pack(g, pa, pb, s);
+    if (rc == HBFP_OK) rc = launch_mx_product_encoded(g, pa, pb, *out, relu, s);
+    if (rc != HBFP_OK) return rc;
+    g.run_a = (const int *)pa;
+    g.run_b = (const int *)pb;
+    void *standby = (char *)pb + mx_packed_bytes(g.N, g.kpad, g.mB);
+    rc = A->mant_bits > 8 ? launch_gemm_limb(g, standby, s) : launch_gemm_i8(g, standby, s);
+    if (rc != HBFP_OK) return rc;
+    return launch_mx_encode_standby(C, N, *out, relu, g.run_a, g.run_b, s);
+}
+
 int hbfp_pack_bytes(const hbfp_tensor *t, size_t *bytes) {
     if (!bytes) return HBFP_ERR_ARG;
     const int rc = check_tensor(t, false);

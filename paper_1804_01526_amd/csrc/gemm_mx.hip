@@ -31,6 +31,7 @@
 #include <atomic>
 #include <chrono>
 
+#include "bfp_device.h"
 #include "gemm_common.h"
 
 namespace hbfp {
@@ -229,11 +230,112 @@ struct MxParams {
 // CU that finishes a tile of one product goes on with a tile of the next, so the stores of the first drain under the
 // matrix instructions of the second; launched one by one, every product ends with all CUs storing at once.
 constexpr int kMxGroup = 4;
+
+// The product written as an encoded operand instead of FP32 (the conversion of Sec. 4.1 / Sec. 5.3 applied to the
+// accumulators: the next product's activation operand, k along the columns of C, blocks of 32 or 64).
+struct MxOut {
+    uint8_t *mant, *exps;        // mant == nullptr: FP32 output
+    int64_t kpad, exp_ld;
+    int32_t nblk, kblock, m, rounding, wide, relu;
+    uint32_t s0, s1;
+};
+
 struct MxGroup {
     MxParams p[kMxGroup];
     int32_t first[kMxGroup + 1];
     int32_t n;
+    MxOut out;                   // of product 0 of a launch with a single product
 };
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t mx_dpp(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+// maximum over lanes 0..31 and over lanes 32..63, in every lane
+__device__ __forceinline__ uint32_t max_of_half_wave(uint32_t v) {
+    v = max(v, mx_dpp<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = max(v, mx_dpp<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = max(v, mx_dpp<0x141>(v));   // row_half_mirror
+    v = max(v, mx_dpp<0x140>(v));   // row_mirror
+    return max(v, (uint32_t)__shfl_xor((int)v, 16));
+}
+
+// Encoded output of a wave's 64 x 128 accumulators.  The kernel variant that produces it multiplies with the operands
+// of the matrix instruction exchanged, so that its 32 x 32 results arrive transposed: lane (l32, lh) holds row l32
+// of the row tile and, in register v, column 8 * (v / 4) + 4 * lh + v % 4 of the column tile.  The 32 columns of an
+// exponent block are then 16 registers of lane l32 and 16 of lane l32 + 32: one maximum over registers and one
+// exchange across the wave halves per block (a block of 64 combines two column tiles).  Same arithmetic and the same
+// stochastic-rounding index (position in C) as the conversion kernels, so the result equals converting the FP32 product.
+template <int ROUND>
+__device__ __forceinline__ void mx_store_encoded(const MxOut &o, const v16f (&acc)[2][4], int64_t row0, int64_t col0, int64_t M,
+                                                 int64_t N, int lane) {
+    const int l32 = lane & 31, lh = lane >> 5;
+    const bool relu = o.relu != 0;
+    // value v of column tile j as it is converted: zero beyond the last column, ReLU if asked for
+#define HBFP_MX_VALUE(i, j, v, left) (((8 * ((v) >> 2) + ((v) & 3)) < (left)) ? (relu && acc[i][j][v] < 0.0f ? 0.0f : acc[i][j][v]) : 0.0f)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int64_t row = row0 + i * 32 + l32;
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp) {                       // two column tiles at a time: one block of 64 or two of 32
+            uint32_t am[2], eb[2];
+            int left[2];                                        // columns of this lane's run that exist
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int jj = 2 * jp + h;
+                const int64_t c0 = col0 + jj * 32 + 4 * lh;
+                const int64_t rest = N - c0;
+                left[h] = rest > 32 ? 32 : (rest < 0 ? 0 : (int)rest);
+                am[h] = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) am[h] = max(am[h], __float_as_uint(HBFP_MX_VALUE(i, jj, v, left[h])) & 0x7fffffffu);
+                am[h] = max(am[h], (uint32_t)__shfl_xor((int)am[h], 32));
+            }
+            if (o.kblock == 64) am[0] = am[1] = max(am[0], am[1]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int jj = 2 * jp + h;
+                eb[h] = block_exponent<ROUND>(am[h], o.m);
+                const int64_t c0 = col0 + jj * 32 + 4 * lh;
+                const uint64_t idx0 = (uint64_t)row * (uint64_t)N + (uint64_t)c0;
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    int q[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint64_t idx = idx0 + (uint64_t)(8 * gq + e);
+                        q[e] = quantise<ROUND>(HBFP_MX_VALUE(i, jj, 4 * gq + e, left[h]), eb[h], o.m, (uint32_t)idx, (uint32_t)(idx >> 32),
+                                               o.s0, o.s1);
+                    }
+                    const int64_t col = c0 + 8 * gq;           // a multiple of 4, like the stored row length
+                    if (row < M && col < o.kpad) {
+                        if (o.wide) {
+                            const v2i w = {(int)((uint32_t)(q[0] & 0xffff) | ((uint32_t)q[1] << 16)),
+                                           (int)((uint32_t)(q[2] & 0xffff) | ((uint32_t)q[3] << 16))};
+                            *reinterpret_cast<v2i *>(o.mant + (row * o.kpad + col) * 2) = w;
+                        } else {
+                            *reinterpret_cast<uint32_t *>(o.mant + row * o.kpad + col) =
+                                (uint32_t)(q[0] & 0xff) | ((uint32_t)(q[1] & 0xff) << 8) | ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
+                        }
+                    }
+                }
+            }
+            // exponent bytes of these 64 columns of the row: two blocks of 32 (one half word) or one block of 64
+            if (lh == 0 && row < M) {
+                if (o.kblock == 32) {
+                    const int64_t b0 = (col0 >> 5) + 2 * jp;   // even, like the row length of the exponents
+                    const uint32_t w = (b0 < o.nblk ? eb[0] : 1u) | ((b0 + 1 < o.nblk ? eb[1] : 1u) << 8);
+                    if (b0 < o.exp_ld) *reinterpret_cast<uint16_t *>(o.exps + row * o.exp_ld + b0) = (uint16_t)w;
+                } else {
+                    const int64_t b0 = (col0 >> 6) + jp;
+                    if (b0 < o.exp_ld) o.exps[row * o.exp_ld + b0] = b0 < o.nblk ? (uint8_t)eb[0] : (uint8_t)1;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);                 // the unrolled epilogue must not pile up temporaries
+        }
+    }
+#undef HBFP_MX_VALUE
+}
 
 // The product kernel is a set of macros over its local arrays (function templates taking the fragment arrays by
 // reference left them in scratch memory).
@@ -274,7 +376,9 @@ struct MxGroup {
                          af[abuf][i][3 * (JA) + 1][1], af[abuf][i][3 * (JA) + 2][0], af[abuf][i][3 * (JA) + 2][1], 0, 0};  \
         const v8i bv_ = {bf[bbuf][3 * (JB)][0],     bf[bbuf][3 * (JB)][1],     bf[bbuf][3 * (JB) + 1][0],                  \
                          bf[bbuf][3 * (JB) + 1][1], bf[bbuf][3 * (JB) + 2][0], bf[bbuf][3 * (JB) + 2][1], 0, 0};           \
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av_, bv_, acc[i][j], 2, 2, JA, as[abuf][i], JB, bs[bbuf]); \
+        /* TR: operands exchanged, the 32 x 32 result arrives transposed (same products, same sums) */                    \
+        if (TR) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv_, av_, acc[i][j], 2, 2, JB, bs[bbuf], JA, as[abuf][i]); \
+        else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av_, bv_, acc[i][j], 2, 2, JA, as[abuf][i], JB, bs[bbuf]); \
     }
 // limb pair (JA, JB) of column tile j for both row tiles, which alternate so that a matrix instruction never waits
 // for the one just before it; then this pair's share of the stage copies, if the k-step hands over a buffer
@@ -341,7 +445,8 @@ struct MxGroup {
         }                                                                                                                  \
     }
 
-template <int LA, int LB>
+// TR: the variant whose output is an encoded operand (g.out)
+template <int LA, int LB, bool TR>
 __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxGroup g) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     constexpr int CHA = chunk_bytes(LA), CHB = chunk_bytes(LB);
@@ -582,6 +687,11 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxGroup g)
 
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t row0 = (int64_t)tm * 256 + wm * 64, col0 = (int64_t)tn * 256 + wn * 128;
+    if (TR) {
+        if (g.out.rounding) mx_store_encoded<1>(g.out, acc, row0, col0, p.M, p.N, lane);
+        else mx_store_encoded<0>(g.out, acc, row0, col0, p.M, p.N, lane);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -657,18 +767,85 @@ int launch_pack_t(const PackPair &q, unsigned blocks, hipStream_t s) {
     return launch_status();
 }
 
-template <int LA, int LB>
-int launch_mx_t(const MxGroup &g, hipStream_t s) {
+// The conversion of an FP32 product into the same encoded output, queued behind the int8 kernels that stand by for the
+// block-scaled kernel: runs only when they ran.  One half wave per row and exponent block (padding entries included).
+template <int ROUND>
+__device__ __forceinline__ void encode_block_of_c(const float *C, int64_t ldc, int64_t M, int64_t N, const MxOut &o, int64_t unit,
+                                                  int l32) {
+    const int64_t row = unit / o.exp_ld, blk = unit - row * o.exp_ld;
+    float x[2];
+    uint32_t am = 0;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int64_t col = blk * o.kblock + e * 32 + l32;
+        x[e] = (e * 32 < o.kblock && col < N) ? C[row * ldc + col] : 0.0f;
+        if (o.relu) x[e] = x[e] < 0.0f ? 0.0f : x[e];
+        am = max(am, __float_as_uint(x[e]) & 0x7fffffffu);
+    }
+    am = max_of_half_wave(am);
+    const uint32_t eb = block_exponent<ROUND>(am, o.m);
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int64_t col = blk * o.kblock + e * 32 + l32;
+        const uint64_t idx = (uint64_t)row * (uint64_t)N + (uint64_t)col;
+        const int q = quantise<ROUND>(x[e], eb, o.m, (uint32_t)idx, (uint32_t)(idx >> 32), o.s0, o.s1);
+        if (e * 32 < o.kblock && col < o.kpad) {
+            if (o.wide) reinterpret_cast<int16_t *>(o.mant)[row * o.kpad + col] = (int16_t)q;
+            else reinterpret_cast<int8_t *>(o.mant)[row * o.kpad + col] = (int8_t)q;
+        }
+    }
+    if (l32 == 0) o.exps[row * o.exp_ld + blk] = blk < o.nblk ? (uint8_t)eb : (uint8_t)1;
+}
+
+__global__ __launch_bounds__(256) void mx_encode_standby_kernel(const float *C, int64_t ldc, int64_t M, int64_t N, const MxOut o,
+                                                                const int *run_a, const int *run_b) {
+    if (stands_down(run_a, run_b)) return;
+    // a small grid that strides over the blocks: in the usual case, where it has nothing to do, it is gone in microseconds
+    for (int64_t unit = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5); unit < M * o.exp_ld; unit += (int64_t)gridDim.x * 8) {   // per half wave
+        if (o.rounding) encode_block_of_c<1>(C, ldc, M, N, o, unit, threadIdx.x & 31);
+        else encode_block_of_c<0>(C, ldc, M, N, o, unit, threadIdx.x & 31);
+    }
+}
+
+__global__ __launch_bounds__(256) void relu_kernel(float *x, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) x[i] = x[i] < 0.0f ? 0.0f : x[i];
+}
+
+MxOut mx_out_of(const hbfp_tensor &t, int relu) {
+    MxOut o = {};
+    o.mant = (uint8_t *)t.mant;
+    o.exps = t.exps;
+    o.kpad = t.kpad;
+    o.exp_ld = t.exp_ld;
+    o.nblk = (int32_t)t.nblk;
+    o.kblock = (int32_t)t.kblock;
+    o.m = t.mant_bits;
+    o.rounding = t.rounding;
+    o.wide = t.mant_bits > 8;
+    o.relu = relu != 0;
+    o.s0 = (uint32_t)t.seed;
+    o.s1 = (uint32_t)(t.seed >> 32);
+    return o;
+}
+
+template <int LA, int LB, bool TR>
+int launch_mx_tr(const MxGroup &g, hipStream_t s) {
     constexpr int bytes = mx_lds_bytes(LA, LB);
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB, TR>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 bytes) != hipSuccess)
             return HBFP_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB>), dim3((unsigned)g.first[g.n]), dim3(kMxThreads), bytes, s, g);
+    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB, TR>), dim3((unsigned)g.first[g.n]), dim3(kMxThreads), bytes, s, g);
     return launch_status();
+}
+
+template <int LA, int LB>
+int launch_mx_t(const MxGroup &g, hipStream_t s) {
+    return g.out.mant ? launch_mx_tr<LA, LB, true>(g, s) : launch_mx_tr<LA, LB, false>(g, s);
 }
 
 }  // namespace
@@ -755,11 +932,13 @@ int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
 }
 
 // n <= kMxGroup products with the same limb counts in one launch
-int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
-    if (n < 1 || n > kMxGroup) return HBFP_ERR_ARG;
+static int launch_mx_group(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, const MxOut *out,
+                           hipStream_t s) {
+    if (n < 1 || n > kMxGroup || (out && n != 1)) return HBFP_ERR_ARG;
     const int LA = limbs_of(args[0].mA), LB = limbs_of(args[0].mB);
     MxGroup g = {};
     g.n = n;
+    if (out) g.out = *out;
     int64_t first = 0;
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
@@ -794,8 +973,43 @@ int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a,
     }
 }
 
+int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
+    return launch_mx_group(n, args, packed_a, packed_b, nullptr, s);
+}
+
 int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s) {
-    return launch_mx_products(1, &a, &packed_a, &packed_b, s);
+    return launch_mx_group(1, &a, &packed_a, &packed_b, nullptr, s);
+}
+
+// The block-scaled kernel can write its accumulators as an encoded operand when the output's exponent blocks are
+// runs of 32 or 64 columns of a row of C.
+bool mx_encoded_output_ok(const hbfp_tensor &out) {
+    return out.contract_axis == 1 && out.rblock == 1 && out.kshare == 1 && (out.kblock == 32 || out.kblock == 64) &&
+           out.kblock_pad == out.kblock && out.rows * out.exp_ld < ((int64_t)1 << 33);
+}
+
+int launch_mx_product_encoded(const GemmArgs &a, const void *packed_a, const void *packed_b, const hbfp_tensor &out, int relu,
+                              hipStream_t s) {
+    if (!mx_encoded_output_ok(out)) return HBFP_ERR_FORMAT;
+    const MxOut o = mx_out_of(out, relu);
+    return launch_mx_group(1, &a, &packed_a, &packed_b, &o, s);
+}
+
+// behind the int8 kernels that stood by for launch_mx_product_encoded and wrote the FP32 product to C
+int launch_mx_encode_standby(const float *C, int64_t ldc, const hbfp_tensor &out, int relu, const int *run_a, const int *run_b,
+                             hipStream_t s) {
+    if (!mx_encoded_output_ok(out)) return HBFP_ERR_FORMAT;
+    const int64_t units = out.rows * out.exp_ld;
+    const int64_t wgs = ceil_div(units, 8);
+    hipLaunchKernelGGL(mx_encode_standby_kernel, dim3((unsigned)(wgs < 2048 ? wgs : 2048)), dim3(256), 0, s, C, ldc, out.rows, out.src_cols,
+                       mx_out_of(out, relu), run_a, run_b);
+    return launch_status();
+}
+
+int launch_relu(float *x, int64_t n, hipStream_t s) {
+    if (ceil_div(n, 256) > 0x7fffffff) return HBFP_ERR_ARG;
+    hipLaunchKernelGGL(relu_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, x, n);
+    return launch_status();
 }
 
 }  // namespace hbfp

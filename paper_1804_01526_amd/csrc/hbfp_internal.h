@@ -82,6 +82,12 @@ size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits);   // header +
 int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
 bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);
 bool gemm_mx_group_ok(int n, const GemmArgs *args);
+bool mx_encoded_output_ok(const hbfp_tensor &out);
+int launch_mx_product_encoded(const GemmArgs &a, const void *packed_a, const void *packed_b, const hbfp_tensor &out, int relu,
+                              hipStream_t s);
+int launch_mx_encode_standby(const float *C, int64_t ldc, const hbfp_tensor &out, int relu, const int *run_a, const int *run_b,
+                             hipStream_t s);
+int launch_relu(float *x, int64_t n, hipStream_t s);
 int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
 int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s);
 

@@ -79,6 +79,8 @@ def _load():
     lib.hbfp_gemm_batch_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(T), i32, ctypes.POINTER(sz)]
     lib.hbfp_gemm_batch.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(T), ctypes.POINTER(vp), ctypes.POINTER(i64),
                                     ctypes.c_float, i32, vp, sz, vp]
+    lib.hbfp_gemm_bfp_workspace.argtypes = [T, T, T, i32, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_bfp.argtypes = [T, T, T, i32, i32, vp, sz, vp]
     lib.hbfp_pack_bytes.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_pack.argtypes = [T, vp, sz, vp]
     lib.hbfp_gemm_packed_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
@@ -90,7 +92,7 @@ def _load():
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -250,6 +252,25 @@ def gemm_batch(pairs, outs, beta: float = 0.0, kernel: int = KERNEL_AUTO, worksp
     _check(_lib.hbfp_gemm_batch(n, a, b, c, ld, beta, kernel, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                                 _stream_ptr(stream)), "hbfp_gemm_batch")
     return outs
+
+
+def gemm_bfp_workspace(a: TensorDesc, b: TensorDesc, out: TensorDesc, kernel: int = KERNEL_AUTO) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_bfp_workspace(ctypes.byref(a), ctypes.byref(b), ctypes.byref(out), kernel, ctypes.byref(n)),
+           "hbfp_gemm_bfp_workspace")
+    return int(n.value)
+
+
+def gemm_bfp(a: BfpTensor, b: BfpTensor, fmt: Format, contract_axis: int = 1, relu: bool = False, kernel: int = KERNEL_AUTO,
+             out: Optional[BfpTensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> BfpTensor:
+    """hbfp_gemm_bfp: encode(relu?(A . B^T)) as an operand in format `fmt` (the next product's input)."""
+    if out is None:
+        out = alloc(fmt, a.desc.rows, b.desc.rows, contract_axis, a.mant.device)
+    workspace = _workspace(gemm_bfp_workspace(a.desc, b.desc, out.desc, kernel), a.mant.device, workspace)
+    _check(_lib.hbfp_gemm_bfp(ctypes.byref(a.desc), ctypes.byref(b.desc), ctypes.byref(out.desc), int(relu), kernel,
+                              _dev_ptr(workspace), 0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
+           "hbfp_gemm_bfp")
+    return out
 
 
 def pack_bytes(desc: TensorDesc) -> int:

@@ -929,3 +929,93 @@ def test_batch_in_a_replayed_graph(hb):
             torch.cuda.synchronize()
             assert rel_fro(got[j].cpu().numpy(), eager.cpu().numpy()) <= 2e-6
             assert rel_fro(got[j].cpu().numpy(), _oracle_product(X, Ws[j], (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
+
+
+def _check_bfp_output(hb, A, B, fa, fb, fo, axis, relu, kernel, fused):
+    """out = hbfp_gemm_bfp(A, B) against the oracle's conversion of the FP32 product the library returns for the same
+    operands and kernel (the quantisation decision is taken on the same FP32 values on both sides), bit for bit;
+    that FP32 product is itself held to the oracle's bound."""
+    ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(fa[2], fa[0], fa[1]))
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(fb[2], fb[0], fb[1]))
+    br, bc, m, rounding, seed = fo
+    fmt = hb.make_format(m, br, bc, rounding, seed)
+    out = hb.alloc(fmt, A.shape[0], B.shape[1], axis)
+    out.mant.fill_(0x55)
+    out.exps.fill_(0x55)
+    n_fused = hb.gemm_select_workspace(ta.desc, tb.desc, kernel) + 4 * A.shape[0] * B.shape[1]
+    ws = hb.gemm_bfp_workspace(ta.desc, tb.desc, out.desc, kernel)
+    assert ws >= n_fused
+    hb.gemm_bfp(ta, tb, fmt, axis, relu=relu, kernel=kernel, out=out)
+    C = hb.gemm(ta, tb, kernel=kernel)
+    torch.cuda.synchronize()
+    C = C.cpu().numpy()
+    assert rel_fro(C, _oracle_product(A, B, fa + (0, 0), fb + (0, 0))) <= TOL
+    if relu:
+        C = np.maximum(C, np.float32(0))
+    want = ref.encode(C, br, bc, m, rounding, seed)
+    mant, exps = unpack(out)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    if fused:
+        assert ws <= n_fused + 512          # no scratch for the conversion beyond the product's own
+
+
+@pytest.mark.parametrize("fo,relu", [((1, 32, 8, 0, 0), False), ((1, 32, 8, 1, 77), True), ((1, 64, 8, 0, 0), True),
+                                     ((1, 64, 12, 1, 5), False), ((1, 32, 4, 0, 0), False), ((1, 32, 16, 0, 0), True)])
+@pytest.mark.parametrize("M,N,K", [(300, 270, 704), (256, 512, 128), (70, 33, 200)])
+def test_product_delivered_as_an_encoded_operand(hb, fo, relu, M, N, K):
+    """The block-scaled kernel converting its own accumulators: blocks of 32 and 64 along the columns of the product,
+    8-, 12-, 4- and 16-bit outputs, both roundings, with and without ReLU, ragged edges in every direction."""
+    print(f"[case] encoded output fo={fo} relu={relu} M={M} N={N} K={K}", flush=True)
+    A, B = _rand((M, K), 3 + M), (_rand((K, N), 4 + N, 2) * 0.05).astype(np.float32)
+    _check_bfp_output(hb, A, B, (1, 32, 8), (32, 1, 8), fo, 1, relu, SCALED, True)
+
+
+@pytest.mark.parametrize("fo,axis,kernel", [((1, 24, 8, 0, 0), 1, SCALED), ((1, 0, 8, 1, 3), 1, SCALED), ((32, 1, 8, 0, 0), 0, SCALED),
+                                            ((24, 24, 8, 0, 0), 0, SCALED), ((1, 32, 8, 0, 0), 1, 1), ((1, 32, 8, 1, 9), 1, 0),
+                                            ((1, 128, 8, 0, 0), 1, SCALED)])
+def test_encoded_product_in_formats_the_kernel_does_not_convert_itself(hb, fo, axis, kernel):
+    """Other output formats (blocks of 24, one exponent per row, k down the rows of the product, tiles) and the int8
+    kernels: the FP32 product goes through the workspace; the result is the same conversion."""
+    print(f"[case] encoded output through the workspace fo={fo} axis={axis} kernel={kernel}", flush=True)
+    A, B = _rand((200, 320), 21), (_rand((320, 150), 22, 2) * 0.05).astype(np.float32)
+    _check_bfp_output(hb, A, B, (1, 32, 8), (32, 1, 8), fo, axis, True, kernel, False)
+
+
+def test_encoded_product_with_wide_operands_and_outside_the_scale_range(hb):
+    """12-bit operands (3 x 3 limb products) with an encoded output, and operands whose exponents the scale bytes
+    cannot hold: the int8 kernels behind the block-scaled kernel produce the FP32 product and the conversion queued
+    behind them the same output."""
+    A, B = _rand((260, 256), 31), _rand((256, 300), 32)
+    print("[case] encoded output, 12-bit operands", flush=True)
+    _check_bfp_output(hb, A, B, (1, 64, 12), (64, 1, 12), (1, 32, 8, 1, 11), 1, False, SCALED, True)
+    A2 = (A.astype(np.float64) * 2.0 ** -124).astype(np.float32)
+    B2 = (B.astype(np.float64) * 2.0 ** 100).astype(np.float32)
+    for fo in [(1, 32, 8, 0, 0), (1, 64, 12, 1, 4)]:
+        print(f"[case] encoded output, operands outside the scale range, fo={fo}", flush=True)
+        _check_bfp_output(hb, A2, B2, (1, 32, 8), (32, 1, 8), fo, 1, True, SCALED, True)
+
+
+def test_encoded_product_feeds_the_next_product_full_size(hb):
+    """Two layers of 4096 x 4096 (the library's own choice of kernel: block-scaled): the first product delivered as
+    the second's operand.  Conversion bit for bit against the oracle on the FP32 product; the second product on
+    sampled rows against the oracle's product of the dequantised operands."""
+    import synth
+    X, W, _ = synth.c4_linear()
+    rng = np.random.default_rng(3)
+    W2 = (rng.standard_normal((4096, 4096)) * 0.02).astype(np.float32)
+    tx = hb.encode(torch.from_numpy(X).cuda(), 1, hb.make_format(8, 1, 32))
+    tw = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(8, 32, 32))
+    tw2 = hb.encode(torch.from_numpy(W2).cuda(), 0, hb.make_format(8, 32, 32))
+    fmt = hb.make_format(8, 1, 32, hb.STOCHASTIC, 21)
+    h = hb.gemm_bfp(tx, tw, fmt, 1, relu=True)
+    C = hb.gemm(tx, tw)
+    Y = hb.gemm(h, tw2)
+    torch.cuda.synchronize()
+    want = ref.encode(np.maximum(C.cpu().numpy(), np.float32(0)), 1, 32, 8, ref.STOCHASTIC, 21)
+    mant, exps = unpack(h)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    rows = np.sort(rng.choice(4096, size=16, replace=False))
+    Y64 = ref.gemm(ref.decode(want), ref.decode(ref.encode(W2, 32, 32, 8)), rows=rows)
+    assert rel_fro(Y.cpu().numpy()[rows], Y64) <= TOL
