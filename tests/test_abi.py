@@ -268,6 +268,40 @@ def test_gemm_batch_validation():
     assert hbfp.gemm_batch_workspace([q, q, q12, q12]) == 2 * alone + 2 * hbfp.gemm_workspace(q12[0], q12[1])
 
 
+def test_gemm_bfp_validation():
+    """hbfp_gemm_bfp: the output plan must be that of an A->rows x B->rows matrix; the workspace always holds the FP32
+    product (for the int8 kernels that stand by, or as the route to the conversion kernels) plus the product's own
+    and, for two-pass output formats, the conversion's."""
+    lib = hbfp._lib
+    byref = ctypes.byref
+    fake = ctypes.c_void_p(0x1000)
+
+    def desc(m, rows, cols, axis, br, bc):
+        d = hbfp.plan(hbfp.make_format(m, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    a, b = desc(8, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)
+    out = desc(8, 128, 64, 1, 1, 32)
+    c_bytes = 128 * 64 * 4
+    for kernel in (hbfp.KERNEL_AUTO, hbfp.KERNEL_INT8, hbfp.KERNEL_SCALED):
+        assert hbfp.gemm_bfp_workspace(a, b, out, kernel) == c_bytes + -(-hbfp.gemm_select_workspace(a, b, kernel) // 256) * 256
+    row_exp = desc(8, 128, 64, 1, 1, 0)                                   # one exponent per row: two-pass conversion
+    assert hbfp.gemm_bfp_workspace(a, b, row_exp, hbfp.KERNEL_SCALED) == \
+        hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED) + -(-hbfp.encode_workspace(row_exp) // 256) * 256
+    assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 128, 65, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
+    assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 64, 128, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
+    assert _status(hbfp.gemm_bfp_workspace, a, b, out, 5) == hbfp.ERR_ARG
+    need = hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED)
+    call = lib.hbfp_gemm_bfp
+    assert call(byref(a), byref(b), byref(out), 0, hbfp.KERNEL_SCALED, fake, need - 1, None) == hbfp.ERR_WORKSPACE
+    assert call(byref(a), byref(b), byref(out), 0, hbfp.KERNEL_SCALED, None, need, None) == hbfp.ERR_WORKSPACE
+    assert call(byref(a), byref(b), byref(out), 2, hbfp.KERNEL_SCALED, fake, need, None) == hbfp.ERR_ARG
+    assert call(byref(a), None, byref(out), 0, 0, fake, need, None) == hbfp.ERR_ARG
+    no_ptr = hbfp.plan(hbfp.make_format(8, 1, 32), 128, 64, 1)
+    assert call(byref(a), byref(b), byref(no_ptr), 0, 0, fake, need, None) == hbfp.ERR_ARG
+
+
 def test_gemm_f32_validation():
     lib = hbfp._lib
     byref = ctypes.byref
