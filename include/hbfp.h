@@ -252,10 +252,10 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
  *                       HBFP_KERNEL_INT8 and HBFP_KERNEL_AUTO take it by themselves when at least 128 such
  *                       tiles are at least 75 % full; naming it runs it on any shape (HBFP_ERR_FORMAT if the
  *                       operands have more than one block or wider mantissas);
- *   HBFP_KERNEL_AUTO    what hbfp_gemm does: SCALED where it is measured faster (at least 128 output
- *                       tiles of 256 x 256, M*N*kpad >= 6e10, and either blocks of at most 32
- *                       elements, an operand of at most 5 bits, or mantissas wider than 9 bits),
- *                       else INT8.
+ *   HBFP_KERNEL_AUTO    what hbfp_gemm does: SCALED where it is measured faster (at least 144 output
+ *                       tiles of 256 x 256, a stored contraction length of at least 2048, or 1024 from
+ *                       512 tiles on, and either blocks of at most 32 elements, an operand of at most
+ *                       5 bits, or mantissas wider than 9 bits), else INT8.
  * Both satisfy the same bound against the FP64 product of the decoded operands.
  * Arguments, domain and errors as hbfp_gemm, plus HBFP_ERR_ARG for an unknown kernel; the workspace
  * size depends on the kernel: hbfp_gemm_select_workspace.

@@ -867,9 +867,14 @@ bool gemm_mx_possible(const GemmArgs &a) {
 bool gemm_mx_ok(const GemmArgs &a) {
     if (!gemm_mx_possible(a)) return false;
     const int64_t tiles = ceil_div(a.M, 256) * ceil_div(a.N, 256);
-    if (tiles < 128) return false;
+    // 128 tiles on 256 CUs (4096 x 2048) lose to the int8 kernels at every contraction length measured (30 to 45 %);
+    // 144 tiles (3072^2) win from a contraction of 2048 to 3072 on
+    if (tiles < 144) return false;
     if ((double)a.M * (double)a.N < 0.75 * 65536.0 * (double)tiles) return false;   // ragged edges would waste the tiles
-    if ((double)a.M * (double)a.N * (double)a.kpad < 6.0e10) return false;          // too short to repay the packing
+    // short contractions do not repay the packing and the start-up of the three-stage ring: blocks of 32 at 4096^2 are
+    // 5 to 9 % ahead from 2048 on and 6 % behind at 1024; with two or more rounds of tiles (8192 x 4096, 8192^2) the
+    // break-even is 1024 (2 to 5 % ahead there, 10 to 20 % behind at 512)
+    if (a.kpad < (tiles >= 512 ? 1024 : 2048)) return false;
     const int products = limbs_of(a.mA) * limbs_of(a.mB);
     // blocks of exactly 32: 3 to 8 % ahead at 4096^3, 20 % at 8192^3; shorter blocks, stored padded to 32, cost the int8
     // kernel a scaling pass per padded block as well: 15 to 20 % ahead at 4096^3
