@@ -35,11 +35,11 @@ FP6_PEAK_TFLOPS = 10100.0  # MI355X dense FP6 / FP4 matrix peak, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X FP32 vector peak, published (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/bench_default_hbm_traffic_counters.txt),
-# scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 product kernel (gemm_mx_kernel<2, 2>): 100912 KiB x 2.0 + 65536 KiB = 273.8 MB
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_config4_hbm_traffic_counters.txt for the
+# product kernel of config 4 alone, profiles/bench_default_hbm_traffic_counters.txt for the encode), scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
+#   config 4 product kernel (gemm_mx_kernel<2, 2, false>): 107504 KiB x 2.0 + 65536 KiB = 287.3 MB
 #   config 2 encode m=8 RNE launch: 131704 KiB x 2.0 + 67587 KiB = 338.9 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 273.8e6
+TRAFFIC_GEMM_C4_BYTES = 287.3e6
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.9e6
 # algorithmic bytes of the config 4 product kernel: both operands as limb planes read once (16 panels of 256 rows x 86
 # k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
@@ -549,7 +549,7 @@ def main():
         # sign-magnitude limbs of 4 bits, so a mantissa product is 4 limb products, all of them matrix-core work
         # (the per-block scaling happens inside the instruction).  Algorithmic flop per launch = 4 * 2*M*N*K (padding
         # of the 24-element blocks to 32 not counted), against the published dense FP6 peak.
-        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2>", "achieved": round(limb_tflops, 1),
+        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2, false>", "achieved": round(limb_tflops, 1),
                      "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
                      "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
