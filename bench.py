@@ -279,7 +279,24 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     res["c3_wgrad_from_image"] = {"gemm_ms": round(ms_k, 4), "encode_im2col_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
                                   "TOPS_kernel": round(flops / ms_k / 1e9, 1),
                                   "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
-    del ta, tb, out, ws, img
+    del ta, tb, out, ws
+    # ... and its data gradient as a forward-shaped product: dY (128 x 28 x 28 x 128 as an image of gradients) gathered
+    # with padding r - 1 - pad = 1 against the mirrored filter with its channel axes exchanged gives dX [100352, 128]
+    # itself, where the lowered form (c3_dgrad) leaves 462 MB of FP32 that a scatter-add still has to fold
+    Wd = W.view(3, 3, 128, 128).flip(0, 1).permute(0, 1, 3, 2).reshape(1152, 128).contiguous()
+    dimg = dY.view(128, 28, 28, 128)
+    ta, tb = hbfp.alloc(row, 100352, 1152, 1), hbfp.encode(Wd, 0, col)
+    out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_workspace(ta.desc, tb.desc), 256), dtype=torch.uint8, device="cuda")
+    hbfp.encode_im2col(dimg, conv, row, out=ta)
+    ms_k = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws), reps)
+    ms_ea = _time_call(torch, lambda: hbfp.encode_im2col(dimg, conv, row, out=ta), reps)
+    ms_eb = _time_call(torch, lambda: hbfp.encode(Wd, 0, col, out=tb), reps)
+    res["c3_dgrad_from_gradient_image"] = {"gemm_ms": round(ms_k, 4), "encode_im2col_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+                                           "TOPS_kernel": round(flops / ms_k / 1e9, 1),
+                                           "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1),
+                                           "note": "dX directly (51 MB), no lowered gradient and no scatter-add"}
+    del ta, tb, out, ws, img, Wd, dimg
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the
     # block-scaled matrix instruction with three 4-bit limbs per mantissa)

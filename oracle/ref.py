@@ -148,6 +148,16 @@ def filter_matrix(w4: np.ndarray, c_block: int = 0) -> np.ndarray:
     return np.concatenate([w4[:, :, c0:c0 + c_block, :].reshape(-1, f) for c0 in range(0, c, c_block)], axis=0)
 
 
+def filter_matrix_dgrad(w4: np.ndarray, c_block: int = 0) -> np.ndarray:
+    """Filter of the data gradient of a stride-1 convolution (Sec. 5.1: the backward pass is executed like the
+    forward pass).  With y[oy, ox, f] = sum x[oy - pad + fr, ox - pad + fs, c] w4[fr, fs, c, f], the gradient is
+    dx[h, w, c] = sum dy[h + pad - fr, w + pad - fs, f] w4[fr, fs, c, f]: a convolution of dy with padding
+    r - 1 - pad, whose filter is w4 mirrored in both spatial axes with its two channel axes exchanged.  Returns that
+    filter as the matrix [r*s*f, c] in the column order of im2col(dy, ...)."""
+    mirrored = w4[::-1, ::-1, :, :].transpose(0, 1, 3, 2)
+    return filter_matrix(np.ascontiguousarray(mirrored), c_block)
+
+
 def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:
     """Integer block partials P[i, j, b] of Eq. (2); mA [M, K], mB [K, N]."""
     mA = np.ascontiguousarray(mA, dtype=np.int32)

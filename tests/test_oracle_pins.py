@@ -375,6 +375,34 @@ def test_im2col_times_filter_matrix_is_the_convolution_sum(h, w, c, r, s, pad_h,
     np.testing.assert_array_equal(got.reshape(n, ho, wo, f), want)
 
 
+@pytest.mark.parametrize("h,w,c,f,r,s,pad_h,pad_w,cb", [(5, 6, 3, 4, 3, 3, 1, 1, 0), (6, 5, 2, 3, 3, 2, 0, 1, 0), (4, 7, 4, 8, 5, 3, 2, 1, 4),
+                                                        (5, 5, 3, 2, 1, 1, 0, 0, 0), (6, 6, 2, 6, 3, 3, 2, 2, 3)])
+def test_data_gradient_of_a_convolution_as_a_forward_product(h, w, c, f, r, s, pad_h, pad_w, cb):
+    """Stride 1: the gradient with respect to the input, written out from its definition as the adjoint of the
+    convolution sum (every product x * wgt that feeds y[oy, ox, f] sends dy[oy, ox, f] * wgt back to that x), equals
+    the lowered dy with padding r - 1 - pad times the mirrored, channel-exchanged filter; and <y, dy> = <x, dx>."""
+    rng = np.random.default_rng(h * 10 + w + r)
+    n = 2
+    ho, wo = h + 2 * pad_h - r + 1, w + 2 * pad_w - s + 1
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float64)
+    wgt = rng.integers(-3, 4, size=(r, s, c, f)).astype(np.float64)
+    dy = rng.integers(-5, 6, size=(n, ho, wo, f)).astype(np.float64)
+    want = np.zeros((n, h, w, c))
+    for img in range(n):
+        for oy in range(ho):
+            for ox in range(wo):
+                for fr in range(r):
+                    for fs in range(s):
+                        iy, ix = oy - pad_h + fr, ox - pad_w + fs
+                        if 0 <= iy < h and 0 <= ix < w:
+                            want[img, iy, ix, :] += wgt[fr, fs, :, :] @ dy[img, oy, ox, :]
+    got = ref.im2col(dy, r, s, r - 1 - pad_h, s - 1 - pad_w, 1, 1, cb) @ ref.filter_matrix_dgrad(wgt, cb)
+    assert got.shape == (n * h * w, c)
+    np.testing.assert_array_equal(got.reshape(n, h, w, c), want)
+    y = (ref.im2col(x, r, s, pad_h, pad_w) @ ref.filter_matrix(wgt)).reshape(n, ho, wo, f)
+    assert np.sum(y * dy) == np.sum(x * want)
+
+
 def test_filter_matrix_tiles_in_channel_block_order_are_the_outer_dimension_tiles():
     """Sec. 5.1 tiles the two outer dimensions of a convolution's filter.  With the window entries in channel-block order
     a tile of (r*s*cb) x fb of the filter matrix holds exactly one (channel block, filter block) pair with the whole
