@@ -885,18 +885,22 @@ bool gemm_mx_ok(const GemmArgs &a) {
 // Products that share one launch.  Measured with 8-bit mantissas in blocks of 32 against the int8 kernels run one
 // after the other: four products of 64 tiles each (2048 x 2048) 5 to 14 % ahead for contractions of 1024 to 4096;
 // 128 tiles or fewer in the whole group (four of 2048 x 1024 x 8192, four of 1024 x 1024 x 4096) 5 to 7 % behind.
+// Tiles of very different contraction lengths do not share well (the gate products of an LSTM step, contractions of
+// 640, 2048 and 8192: 60 % behind, the few long tiles run on alone at the end), so the lengths must be within a
+// factor of two of each other and none below the 1024 that a product of its own needs.
 bool gemm_mx_group_ok(int n, const GemmArgs *args) {
-    int64_t tiles = 0;
-    double area = 0.0, work = 0.0;
+    int64_t tiles = 0, kmin = args[0].kpad, kmax = args[0].kpad;
+    double area = 0.0;
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
         if (!gemm_mx_possible(a) || !mx_same_limbs(a, args[0])) return false;
         if (limbs_of(a.mA) * limbs_of(a.mB) == 4 && a.kbp != 32) return false;
         tiles += ceil_div(a.M, 256) * ceil_div(a.N, 256);
         area += (double)a.M * (double)a.N;
-        work += (double)a.M * (double)a.N * (double)a.kpad;
+        kmin = a.kpad < kmin ? a.kpad : kmin;
+        kmax = a.kpad > kmax ? a.kpad : kmax;
     }
-    return tiles >= 256 && area >= 0.75 * 65536.0 * (double)tiles && work >= 1.5e10;
+    return tiles >= 256 && area >= 0.75 * 65536.0 * (double)tiles && kmin >= 1024 && kmax <= 2 * kmin;
 }
 
 size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits) { return 256 + packed_bytes(rows, kpad, limbs_of(mant_bits)); }

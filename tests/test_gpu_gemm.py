@@ -1049,3 +1049,42 @@ def test_convolution_data_gradient_without_col2im(hb, r, pad, blk, cb):
     assert rel_fro(dx.cpu().numpy(), ref.gemm(ref.decode(oa), ref.decode(ob))) <= TOL
     exact = low.astype(np.float64) @ wd.astype(np.float64)
     assert rel_fro(dx.cpu().numpy(), exact) < 0.03
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_encoded_output_random_shapes_and_formats(hb, case):
+    """Random shapes, operand widths, output widths, block lengths, roundings: the kernel's own conversion (blocks of
+    32 / 64 with the block-scaled kernel) and the route through the workspace (anything else)."""
+    rng = np.random.default_rng(9000 + case)
+    M, N, K = int(rng.integers(1, 600)), int(rng.integers(1, 600)), int(rng.integers(32, 700))
+    m_op, blk_op = [(8, 32), (4, 64), (12, 64), (8, 24)][case % 4]
+    fo = (1, int(rng.choice([32, 64, 24, 0])), int(rng.choice([4, 8, 12, 16])), int(rng.integers(0, 2)), int(rng.integers(0, 1 << 30)))
+    relu = bool(rng.integers(0, 2))
+    print(f"[case] {case}: M={M} N={N} K={K} operands m={m_op} blk={blk_op} out={fo} relu={relu}", flush=True)
+    A, B = _rand((M, K), 11000 + case), (_rand((K, N), 12000 + case, 2) * 0.05).astype(np.float32)
+    _check_bfp_output(hb, A, B, (1, blk_op, m_op), (blk_op, 1, m_op), fo, 1, relu, SCALED, None)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_batch_random_shapes(hb, case):
+    """Random groups of two to four products with the block-scaled kernel: each bit-equal to its single call and
+    within the bound of the oracle."""
+    rng = np.random.default_rng(7000 + case)
+    n = int(rng.integers(2, 5))
+    m, blk = [(8, 32), (12, 64), (4, 32), (8, 24)][case % 4]
+    pairs, mats = [], []
+    for i in range(n):
+        M, N, K = int(rng.integers(1, 700)), int(rng.integers(1, 700)), int(rng.integers(1, 600))
+        A, B = _rand((M, K), 7100 + 10 * case + i), _rand((K, N), 7200 + 10 * case + i)
+        pairs.append((hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(m, 1, blk)),
+                      hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(m, blk, 1))))
+        mats.append((A, B))
+    print(f"[case] batch {case}: m={m} blk={blk} shapes={[(a.shape[0], b.shape[1], a.shape[1]) for a, b in mats]}", flush=True)
+    outs = [torch.full((a.shape[0], b.shape[1]), 3.0, device="cuda") for a, b in mats]
+    hb.gemm_batch(pairs, outs, kernel=SCALED)
+    torch.cuda.synchronize()
+    for i in range(n):
+        single = hb.gemm(pairs[i][0], pairs[i][1], kernel=SCALED)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[i], single)
+        assert rel_fro(outs[i].cpu().numpy(), _oracle_product(mats[i][0], mats[i][1], (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
