@@ -267,7 +267,7 @@ __device__ __forceinline__ uint32_t max_of_half_wave(uint32_t v) {
 // exchange across the wave halves per block (a block of 64 combines two column tiles).  Same arithmetic and the same
 // stochastic-rounding index (position in C) as the conversion kernels, so the result equals converting the FP32 product.
 template <int ROUND>
-__device__ __forceinline__ void mx_store_encoded(const MxOut &o, const v16f (&acc)[2][4], int64_t row0, int64_t col0, int64_t M,
+__device__ __forceinline__ void mx_store_encoded(const MxOut &o, v16f (&acc)[2][4], int64_t row0, int64_t col0, int64_t M,
                                                  int64_t N, int lane) {
     const int l32 = lane & 31, lh = lane >> 5;
     const bool relu = o.relu != 0;
@@ -288,7 +288,11 @@ __device__ __forceinline__ void mx_store_encoded(const MxOut &o, const v16f (&ac
                 left[h] = rest > 32 ? 32 : (rest < 0 ? 0 : (int)rest);
                 am[h] = 0;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) am[h] = max(am[h], __float_as_uint(HBFP_MX_VALUE(i, jj, v, left[h])) & 0x7fffffffu);
+                for (int v = 0; v < 16; ++v) {
+                    const float f = HBFP_MX_VALUE(i, jj, v, left[h]);
+                    acc[i][jj][v] = f;                         // in place: the second pass reads the value as converted
+                    am[h] = max(am[h], __float_as_uint(f) & 0x7fffffffu);
+                }
                 am[h] = max(am[h], (uint32_t)__shfl_xor((int)am[h], 32));
             }
             if (o.kblock == 64) am[0] = am[1] = max(am[0], am[1]);
@@ -298,25 +302,46 @@ __device__ __forceinline__ void mx_store_encoded(const MxOut &o, const v16f (&ac
                 eb[h] = block_exponent<ROUND>(am[h], o.m);
                 const int64_t c0 = col0 + jj * 32 + 4 * lh;
                 const uint64_t idx0 = (uint64_t)row * (uint64_t)N + (uint64_t)c0;
+                // this lane's 16 mantissas are four runs of 4 (columns 8 g + 4 lh ..); the partner in the other wave half
+                // has the runs in between.  One exchange gives each of the two 16 consecutive columns, so a row's 32
+                // mantissas leave as two 16-byte stores (32-byte for 16-bit mantissas) instead of eight 4-byte ones.
+                int w[4][2];
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     int q[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint64_t idx = idx0 + (uint64_t)(8 * gq + e);
-                        q[e] = quantise<ROUND>(HBFP_MX_VALUE(i, jj, 4 * gq + e, left[h]), eb[h], o.m, (uint32_t)idx, (uint32_t)(idx >> 32),
+                        q[e] = quantise<ROUND>(acc[i][jj][4 * gq + e], eb[h], o.m, (uint32_t)idx, (uint32_t)(idx >> 32),
                                                o.s0, o.s1);
                     }
-                    const int64_t col = c0 + 8 * gq;           // a multiple of 4, like the stored row length
-                    if (row < M && col < o.kpad) {
-                        if (o.wide) {
-                            const v2i w = {(int)((uint32_t)(q[0] & 0xffff) | ((uint32_t)q[1] << 16)),
-                                           (int)((uint32_t)(q[2] & 0xffff) | ((uint32_t)q[3] << 16))};
-                            *reinterpret_cast<v2i *>(o.mant + (row * o.kpad + col) * 2) = w;
-                        } else {
-                            *reinterpret_cast<uint32_t *>(o.mant + row * o.kpad + col) =
-                                (uint32_t)(q[0] & 0xff) | ((uint32_t)(q[1] & 0xff) << 8) | ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24);
-                        }
+                    if (o.wide) {
+                        w[gq][0] = (int)((uint32_t)(q[0] & 0xffff) | ((uint32_t)q[1] << 16));
+                        w[gq][1] = (int)((uint32_t)(q[2] & 0xffff) | ((uint32_t)q[3] << 16));
+                    } else {
+                        w[gq][0] = (int)((uint32_t)(q[0] & 0xff) | ((uint32_t)(q[1] & 0xff) << 8) | ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)q[3] << 24));
+                        w[gq][1] = 0;
+                    }
+                }
+                // lower half keeps runs 0 and 1 and receives the partner's runs 0 and 1; upper half keeps 2 and 3
+                const int nw = o.wide ? 2 : 1;
+                int got[2][2];
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+#pragma unroll
+                    for (int y = 0; y < 2; ++y) got[x][y] = y < nw ? __shfl_xor(lh ? w[x][y] : w[2 + x][y], 32) : 0;
+                const int64_t col = col0 + jj * 32 + 16 * lh;  // first of this lane's 16 consecutive columns
+                if (row < M && col0 + jj * 32 < o.kpad) {
+                    typedef int v4i_t __attribute__((ext_vector_type(4)));
+                    if (o.wide) {
+                        const v4i_t a = lh ? v4i_t{got[0][0], got[0][1], w[2][0], w[2][1]} : v4i_t{w[0][0], w[0][1], got[0][0], got[0][1]};
+                        const v4i_t b = lh ? v4i_t{got[1][0], got[1][1], w[3][0], w[3][1]} : v4i_t{w[1][0], w[1][1], got[1][0], got[1][1]};
+                        v4i_t *dst = reinterpret_cast<v4i_t *>(o.mant + (row * o.kpad + col) * 2);
+                        dst[0] = a;
+                        dst[1] = b;
+                    } else {
+                        const v4i_t a = lh ? v4i_t{got[0][0], w[2][0], got[1][0], w[3][0]} : v4i_t{w[0][0], got[0][0], w[1][0], got[1][0]};
+                        *reinterpret_cast<v4i_t *>(o.mant + row * o.kpad + col) = a;
                     }
                 }
             }
