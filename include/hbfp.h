@@ -271,9 +271,13 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
 /*
  * hbfp_gemm_batch: up to HBFP_BATCH_MAX independent products C[i] (+)= A[i] . B[i]^T in one call (the data-gradient
  * and weight-gradient products of a layer, Sec. 5.1; the products of several layers or micro-batches).  Every
- * product is what hbfp_gemm_select computes for it.  Products that take the block-scaled kernel with the same limb
- * counts share one launch, so that a compute unit that finishes a tile of one product goes on with a tile of
- * the next while its stores drain; the others run one after the other.
+ * product is what hbfp_gemm_select computes for it (bit for bit with HBFP_KERNEL_SCALED and HBFP_KERNEL_INT8; with
+ * HBFP_KERNEL_AUTO within the same bound, because the choice of kernel may differ, see below).  Products whose limb
+ * counts agree can share one launch of the block-scaled kernel (workgroup ranges of one grid), so that products
+ * too small to fill the chip alone fill it together.  They do with HBFP_KERNEL_SCALED, and with HBFP_KERNEL_AUTO
+ * when every product would take that kernel anyway or when the group has at least 256 output tiles of 256 x 256,
+ * contraction lengths of at least 1024 within a factor of two of each other, and a format the block-scaled kernel
+ * is ahead in; otherwise the products run one after the other, each as hbfp_gemm_select runs it.
  *   A, B, C, ldc   host arrays of n descriptors / device pointers / leading dimensions
  *   kernel         HBFP_KERNEL_* as for hbfp_gemm_select, applied to every product
  *   workspace      hbfp_gemm_batch_workspace bytes (the sum of the products' own workspaces)
