@@ -1088,3 +1088,45 @@ def test_batch_random_shapes(hb, case):
         torch.cuda.synchronize()
         assert torch.equal(outs[i], single)
         assert rel_fro(outs[i].cpu().numpy(), _oracle_product(mats[i][0], mats[i][1], (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
+
+
+def test_encoded_product_in_a_replayed_graph(hb):
+    """hbfp_gemm_bfp captured in a HIP graph together with the conversion of its input: every replay (new activations,
+    eager work between replays, one replay outside the scale range) gives the bytes of the eager call."""
+    m, blk, M, N, K = 8, 32, 260, 300, 640
+    rng = np.random.default_rng(24)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
+    tw = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(m, blk, 1))
+    fmt_in, fmt_out = hb.make_format(m, 1, blk), hb.make_format(8, 1, 32, hb.STOCHASTIC, 17)
+    x = torch.zeros((M, K), device="cuda")
+    tx = hb.encode(x, 1, fmt_in)
+    out = hb.alloc(fmt_out, M, N, 1)
+    ws = torch.empty(hb.gemm_bfp_workspace(tx.desc, tw.desc, out.desc, SCALED), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        hb.encode(x, 1, fmt_in, out=tx, stream=stream)
+        hb.gemm_bfp(tx, tw, fmt_out, 1, relu=True, kernel=SCALED, out=out, workspace=ws, stream=stream)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            hb.encode(x, 1, fmt_in, out=tx, stream=stream)
+            hb.gemm_bfp(tx, tw, fmt_out, 1, relu=True, kernel=SCALED, out=out, workspace=ws, stream=stream)
+    for i, scale in enumerate([1.0, 2.0 ** -124, 1.0, 3.0]):
+        X = (rng.standard_normal((M, K)) * scale).astype(np.float32)
+        x.copy_(torch.from_numpy(X).cuda())
+        torch.cuda.synchronize()
+        out.mant.fill_(0x33)
+        out.exps.fill_(0x33)
+        graph.replay()
+        torch.cuda.synchronize()
+        got_m, got_e = out.mant.clone(), out.exps.clone()
+        eager = hb.gemm_bfp(hb.encode(x, 1, fmt_in), tw, fmt_out, 1, relu=True, kernel=SCALED)
+        C = hb.gemm(hb.encode(x, 1, fmt_in), tw, kernel=SCALED)
+        torch.cuda.synchronize()
+        print(f"[case] encoded output, graph replay {i} scale={scale}", flush=True)
+        want = ref.encode(np.maximum(C.cpu().numpy(), np.float32(0)), 1, 32, 8, ref.STOCHASTIC, 17)
+        mant, exps = unpack(out)
+        np.testing.assert_array_equal(mant, want.mant)
+        np.testing.assert_array_equal(exps, want.exps)
+        if scale == 1.0 or scale == 3.0:
+            assert torch.equal(got_m, eager.mant) and torch.equal(got_e, eager.exps)
