@@ -1130,3 +1130,25 @@ def test_encoded_product_in_a_replayed_graph(hb):
         np.testing.assert_array_equal(exps, want.exps)
         if scale == 1.0 or scale == 3.0:
             assert torch.equal(got_m, eager.mant) and torch.equal(got_e, eager.exps)
+
+
+def test_config3_data_gradient_without_col2im_full_size(hb):
+    """Config 3's data gradient in the launch shape the benchmark times: dY (100352 x 128, Student-t, viewed as a
+    128 x 28 x 28 x 128 image) gathered with padding 1 against the mirrored filter gives dX [100352, 128].  The gathered
+    operand bit for bit in full, the product on sampled rows, against the oracle on its own lowered dY."""
+    import synth
+    _, W, dY = synth.c3_conv_as_gemm()
+    dimg = dY.reshape(128, 28, 28, 128)
+    w4 = W.reshape(3, 3, 128, 128)                               # [r, s, c, f]
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4))
+    conv = hb.Conv2d(128, 28, 28, 128, 3, 3, 1, 1, 1, 1, 0, 0)
+    ta = hb.encode_im2col(torch.from_numpy(dimg).cuda(), conv, hb.make_format(8, 1, 32))
+    tb = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, 32, 1))
+    dx = hb.gemm(ta, tb)
+    torch.cuda.synchronize()
+    oa, ob = ref.encode(ref.im2col(dimg, 3, 3, 1, 1), 1, 32, 8), ref.encode(wd, 32, 1, 8)
+    mant, exps = unpack(ta)
+    np.testing.assert_array_equal(exps, oa.exps)
+    np.testing.assert_array_equal(mant, oa.mant)
+    rows = np.sort(np.random.default_rng(8).choice(100352, size=64, replace=False))
+    assert rel_fro(dx.cpu().numpy()[rows], ref.gemm(ref.decode(oa), ref.decode(ob), rows=rows)) <= TOL
