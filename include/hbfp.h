@@ -184,7 +184,9 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  * multiples of 8; contract_axis 0: at most 64 elements (HBFP_ERR_FORMAT otherwise).
  * One exponent per training input (Sec. 5.1: the x tensor gets one exponent per training input), contract_axis 1:
  * a format with block_rows = ho*wo (the rows of one image), block_cols = 0 and k_slot = the stored block length
- * (a multiple of 8, at most 128).  The exponent is that of the largest value of the whole image x[img] (also of
+ * (a multiple of 8, at most 128); ho*wo must exceed 1 (with one output position per image the format reads as one
+ * exponent per lowered row, which this entry point does not produce: HBFP_ERR_FORMAT).  The exponent is that of the
+ * largest value of the whole image x[img] (also of
  * pixels no window reaches when the stride exceeds the filter), each value is converted as if the image had been
  * converted once and lowered afterwards (stochastic rounding draws by the index in x, so a pixel gets the same
  * mantissa in every window), and `workspace` must hold hbfp_encode_workspace(out) bytes (4 per image; HBFP_ERR_WORKSPACE);

@@ -246,6 +246,10 @@ def test_encode_im2col_random_geometries(hb, case):
             slot = 8
         if r * s_ * c <= 8:
             pytest.skip("window of 8 entries: nothing to cut into stored blocks")
+        if ho * wo == 1:
+            with pytest.raises(hb.HbfpError):      # one output position per image: not the per-image format
+                hb.encode_im2col(xg, conv, hb.make_format(m, 1, 0, rounding, 77 + case, k_slot=slot))
+            return
         bt = hb.encode_im2col(xg, conv, hb.make_format(m, ho * wo, 0, rounding, 77 + case, k_slot=slot))
         img = ref.encode(x.reshape(n, -1), 1, 0, m, rounding, 77 + case)
         want_mant, want_exps = ref.im2col(img.mant.reshape(n, h, w, c), r, s_, ph, pw, sh, sw, cb), img.exps
