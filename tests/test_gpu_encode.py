@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from oracle import ref
-from tests.util import unpack
+from tests.util import random_cases, unpack
 
 pytestmark = pytest.mark.gpu
 
@@ -209,7 +209,7 @@ def test_encode_im2col_channel_block_order(hb, n, h, w, c, r, s, ph, pw, sh, sw,
     np.testing.assert_array_equal(mant, want.mant)
 
 
-@pytest.mark.parametrize("case", range(40))
+@pytest.mark.parametrize("case", random_cases(40))
 def test_encode_im2col_random_geometries(hb, case):
     """Random images, windows, paddings, strides, channel blocks, block lengths and modes (blocks along the window,
     blocks over the output positions, one exponent per image) against the oracle's lowering + conversion."""
@@ -372,7 +372,7 @@ def _random_format_case(case):
     return rows, cols, axis, br, bc, m, rounding, slot
 
 
-@pytest.mark.parametrize("case", range(60))
+@pytest.mark.parametrize("case", random_cases(60))
 def test_encode_random_shapes_and_formats(hb, case):
     """Random shapes, block shapes, widths, rounding modes and stored-block lengths: every conversion path (row, column,
     register tile, one wave per row, two passes in either orientation) against the oracle, decode included."""

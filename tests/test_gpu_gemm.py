@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from oracle import ref
-from tests.util import rel_fro, unpack
+from tests.util import random_cases, rel_fro, unpack
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
@@ -534,7 +534,7 @@ def test_gemm_one_exponent_per_training_input_against_weight_tiles(hb, kernel, m
     assert err <= TOL
 
 
-@pytest.mark.parametrize("case", range(30))
+@pytest.mark.parametrize("case", random_cases(30))
 def test_gemm_random_exponent_blocks_over_common_stored_blocks(hb, case):
     """Operands whose exponent blocks differ (rows, multiples of the stored block, whole rows, 2-D tiles) but which are
     stored in blocks of one length: integer block sums bit for bit, C within the bound, all kernel families."""
@@ -705,7 +705,7 @@ def test_pack_argument_checks(hb):
         hb.gemm_packed(t, p, t12, hb.pack(t12))
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", random_cases(24))
 def test_scaled_kernel_random_shapes(hb, case):
     """Seeded random shapes (down to a single row, column or contraction element), block lengths, mantissa widths of
     either class, rounding modes and beta, through the block-scaled kernel."""
@@ -1051,7 +1051,7 @@ def test_convolution_data_gradient_without_col2im(hb, r, pad, blk, cb):
     assert rel_fro(dx.cpu().numpy(), exact) < 0.03
 
 
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", random_cases(16))
 def test_encoded_output_random_shapes_and_formats(hb, case):
     """Random shapes, operand widths, output widths, block lengths, roundings: the kernel's own conversion (blocks of
     32 / 64 with the block-scaled kernel) and the route through the workspace (anything else)."""
@@ -1065,7 +1065,7 @@ def test_encoded_output_random_shapes_and_formats(hb, case):
     _check_bfp_output(hb, A, B, (1, blk_op, m_op), (blk_op, 1, m_op), fo, 1, relu, SCALED, None)
 
 
-@pytest.mark.parametrize("case", range(8))
+@pytest.mark.parametrize("case", random_cases(8))
 def test_batch_random_shapes(hb, case):
     """Random groups of two to four products with the block-scaled kernel: each bit-equal to its single call and
     within the bound of the oracle."""

@@ -1,6 +1,13 @@
 """Test helpers: move encoded operands between the GPU library's stored layout and the
 source-orientation arrays the oracle works on.  Pure index shuffling, no arithmetic."""
+import os
+
 import numpy as np
+
+
+def random_cases(default):
+    """Seeds of a randomised test: `default` of them, or HBFP_RANDOM_CASES if set (a longer soak of the same test)."""
+    return range(int(os.environ.get("HBFP_RANDOM_CASES", default)))
 
 
 def unpack(bt):
