@@ -24,8 +24,8 @@
  *   - Mantissas are two's complement integers of `mant_bits` bits, the sign
  *     included, in the symmetric range +-(2^(mant_bits-1) - 1).
  *   - A block of elements shares one exponent, stored as one byte Eb in 1..255:
- *     the IEEE-754 biased exponent of the block's largest magnitude (Sec. 4.1,
- *     Sec. 5.3: "exponent of the largest value"), raised by one when rounding
+ *     the IEEE-754 biased exponent of the block's largest magnitude (the exponent
+ *     rule of Sec. 4.1 and Sec. 5.3), raised by one when rounding
  *     that largest value would reach 2^(mant_bits-1).  One mantissa unit is worth
  *     2^(Eb - 125 - mant_bits); an all-zero or subnormal-only block has Eb = 1.
  *   - Rounding acts on the magnitude, then the sign is applied: round to
@@ -146,9 +146,9 @@ int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_a
 int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes);
 
 /*
- * hbfp_encode: FP32 -> BFP (Sec. 4.1 "convert tensors to BFP before every dot
- * product, using the exponent of the largest tensor value"; Sec. 5.3 FP-to-BFP
- * unit: detect the maximum exponent, normalise the mantissas).
+ * hbfp_encode: FP32 -> BFP (the conversion rule of Sec. 4.1, applied to the inputs
+ * of every dot product; Sec. 5.3, FP-to-BFP unit: the block's largest exponent is
+ * found and the mantissas are aligned to it).
  *   src   device FP32 source matrix, element (r, c) at src[r*ld + c], ld >= cols
  *   out   descriptor from hbfp_plan for the same (fmt, rows, cols, contract_axis),
  *         with mant/exps set by the caller; fully overwritten, padding included
@@ -333,10 +333,18 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
 /*
  * hbfp_gemm_partials: the fixed-point half of Eq. (2) alone, for checking:
  *     P[(i*N + j)*nblk + b] = sum_{k in block b} mA[i][k] * mB[j][k]     (int32, exact)
- * computed by the same matrix-core path as hbfp_gemm.  Same operand rules.
+ * computed with the int8 matrix instruction (v_mfma_i32_32x32x32_i8) by the member of the int8 kernel family
+ * that can write its int32 accumulators out: a kernel of its own, not one that hbfp_gemm launches (those keep
+ * the block sums in registers and scale them at once).  The kernels hbfp_gemm runs are checked separately, on
+ * inputs for which the FP32 result itself is exact.  Same operand rules.
+ *   row0, rows / col0, cols (hbfp_gemm_partials_window): only the block sums of that window of the product are
+ *   computed and written, P[((i - row0) * cols + (j - col0)) * nblk + b]: a few tiles of a product whose full
+ *   dump would not fit in memory.  HBFP_ERR_ARG if the window is empty or leaves the product.
  */
 int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
                        void *workspace, size_t ws_bytes, void *stream);
+int hbfp_gemm_partials_window(const hbfp_tensor *A, const hbfp_tensor *B, int64_t row0, int64_t rows, int64_t col0, int64_t cols,
+                              int32_t *P, void *workspace, size_t ws_bytes, void *stream);
 
 /*
  * hbfp_gemm_f32: convert-multiply-convert in one call (Sec. 4.1), BLAS style,

@@ -645,6 +645,31 @@ int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
     return run_gemm(A, B, nullptr, 0, 0.0f, P, HBFP_KERNEL_INT8, workspace, ws_bytes, stream);
 }
 
+int hbfp_gemm_partials_window(const hbfp_tensor *A, const hbfp_tensor *B, int64_t row0, int64_t rows, int64_t col0, int64_t cols,
+                              int32_t *P, void *workspace, size_t ws_bytes, void *stream) {
+    if (!A || !B || !P || ((uintptr_t)P & 3)) return HBFP_ERR_ARG;
+    int rc = check_pair(A, B);
+    if (rc != HBFP_OK) return rc;
+    if (row0 < 0 || col0 < 0 || rows <= 0 || cols <= 0 || rows > A->rows || cols > B->rows || row0 > A->rows - rows || col0 > B->rows - cols)
+        return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_INT8, &need);      // that of the whole product covers any window
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    // rows of an operand are kpad mantissas and exp_ld exponent bytes apart, so a window of the product is the
+    // product of two operands that start further down and have fewer rows
+    GemmArgs g = gemm_args(A, B);
+    const int64_t es = A->mant_bits > 8 ? 2 : 1;
+    g.mantA = (const char *)A->mant + row0 * A->kpad * es;
+    g.mantB = (const char *)B->mant + col0 * B->kpad * es;
+    g.expA = A->exps + row0 * A->exp_ld;
+    g.expB = B->exps + col0 * B->exp_ld;
+    g.M = rows;
+    g.N = cols;
+    g.P = P;
+    if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
+    return launch_gemm_i8(g, workspace, (hipStream_t)stream);
+}
+
 // Layout of the hbfp_gemm_f32 workspace: [A mant][A exps][B mant][B exps][encode scratch][gemm scratch]
 struct F32Plan {
     hbfp_tensor ta, tb;

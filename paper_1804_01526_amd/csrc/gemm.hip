@@ -189,8 +189,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_kernel(const GemmParams p
             if (SPB == 1) { first = true; last = true; slot = s; }
             else if (SPB == 2) { first = (s & 1) == 0; last = (s & 1) == 1; slot = s >> 1; }
             else {
-                first = s == 0 && (st % stages_per_block) == 0;
-                last = s == 3 && ((st + 1) % stages_per_block) == 0;
+                // The product kernel closes the chain every 256 elements of k (two stages) as well as at the end of
+                // the block: 256 * 127 * 127 < 2^22 keeps the block sum inside the range in which adding it to the bit
+                // pattern of the row constant is exact, however long the block.  The dump keeps whole-block int32 sums.
+                const int in_block = st % stages_per_block;
+                first = s == 0 && (DUMP ? in_block == 0 : (in_block & 1) == 0);
+                last = s == 3 && (in_block + 1 == stages_per_block || (!DUMP && (in_block & 1) == 1));
                 slot = 0;
             }
             v4i a[2], b[2];
@@ -313,8 +317,10 @@ struct W8Params {
 };
 
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (a block is spb / 2 whole stages).  A block
-// that spans several k-steps chains its matrix instructions through the C input and is scaled once, at its
-// last k-step; the longer the block, the closer the kernel gets to the matrix core's own pace.
+// that spans several k-steps chains its matrix instructions through the C input and is scaled at its last
+// k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
+// chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
+// row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
 template <int SPB>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -453,13 +459,13 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #define HBFP_PAIR(ring)                                                                                 \
     {                                                                                                   \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                         \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (pos & 3) == 3;       \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
             HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                 \
             HBFP_STEP(1, SPB == 1, last1, HBFP_READ_STEP((ring) + 1, 0, 0));                            \
         }                                                                                               \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1;                         \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (pos & 3) == 3;       \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
             HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP((ring) + 1, 1, 1));                           \
             HBFP_STEP(1, SPB == 1, last1, {                                                             \
@@ -546,13 +552,8 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *pa
 
 template <int SPB, bool DUMP>
 int launch_t(const GemmParams &p, dim3 grid, hipStream_t s) {
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_kernel<SPB, DUMP>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
-            return HBFP_ERR_LAUNCH;
-        configured = true;
-    }
+    static std::atomic<bool> configured{false};
+    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_i8_kernel<SPB, DUMP>), kLdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
     hipLaunchKernelGGL((gemm_i8_kernel<SPB, DUMP>), grid, dim3(kThreads), kLdsBytes, s, p);
     return launch_status();
 }
@@ -629,13 +630,11 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     } else {
         // behind the block-scaled kernel the product almost never runs: one launch, no scale-word kernel
         if (use_w8(a.kpad) && !a.run_a) {
-            static bool configured = false;
-            if (!configured) {
-                for (const void *f : {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),
-                                      reinterpret_cast<const void *>(&gemm_i8_w8_kernel<0>)})
-                    if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kW8LdsBytes) != hipSuccess) return HBFP_ERR_LAUNCH;
-                configured = true;
-            }
+            static std::atomic<bool> configured[3];
+            const void *const kernels[3] = {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),
+                                            reinterpret_cast<const void *>(&gemm_i8_w8_kernel<0>)};
+            for (int i = 0; i < 3; ++i)
+                if (allow_dynamic_lds(configured[i], kernels[i], kW8LdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
             if (!workspace) return HBFP_ERR_WORKSPACE;
             W8Params q;
             q.g = p;

@@ -499,13 +499,8 @@ int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.run_b = a.run_b;
     const dim3 grid((unsigned)(tm * tn));
     if (!a.P && !a.run_a && p.spb == 2 && (uint64_t)127 * (uint64_t)a.kpad + 64 < ((uint64_t)1 << 32) && ceil_div(tm * tn, 8) * 8 <= 0x7fffffff) {
-        static bool configured = false;
-        if (!configured) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_limb_w8_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLwLdsBytes) != hipSuccess)
-                return HBFP_ERR_LAUNCH;
-            configured = true;
-        }
+        static std::atomic<bool> configured{false};
+        if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_limb_w8_kernel), kLwLdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
         LimbW8Params q;
         q.g = p;
         q.mpad = ceil_div(a.M, 128) * 128;

@@ -857,13 +857,8 @@ MxOut mx_out_of(const hbfp_tensor &t, int relu) {
 template <int LA, int LB, bool TR>
 int launch_mx_tr(const MxGroup &g, hipStream_t s) {
     constexpr int bytes = mx_lds_bytes(LA, LB);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB, TR>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                bytes) != hipSuccess)
-            return HBFP_ERR_LAUNCH;
-        configured = true;
-    }
+    static std::atomic<bool> configured{false};
+    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB, TR>), bytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
     hipLaunchKernelGGL((gemm_mx_kernel<LA, LB, TR>), dim3((unsigned)g.first[g.n]), dim3(kMxThreads), bytes, s, g);
     return launch_status();
 }

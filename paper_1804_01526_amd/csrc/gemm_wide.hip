@@ -224,13 +224,8 @@ bool gemm_wide_ok(const GemmArgs &a) {
 }
 
 int launch_gemm_wide(const GemmArgs &a, hipStream_t s) {
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_i8_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kWideLds) != hipSuccess)
-            return HBFP_ERR_LAUNCH;
-        configured = true;
-    }
+    static std::atomic<bool> configured{false};
+    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_i8_wide_kernel), kWideLds) != HBFP_OK) return HBFP_ERR_LAUNCH;
     WideParams p;
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;

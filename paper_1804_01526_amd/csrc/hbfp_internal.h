@@ -3,6 +3,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -14,6 +16,15 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? HBFP_OK : HBFP_ERR_LAUNCH; }
+
+// Raises a kernel's dynamic LDS limit the first time it is launched.  `done` is that kernel's own flag; two threads
+// that meet here both make the (idempotent) runtime call, which is all a race can do.
+inline int allow_dynamic_lds(std::atomic<bool> &done, const void *kernel, int bytes) {
+    if (done.load(std::memory_order_acquire)) return HBFP_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return HBFP_ERR_LAUNCH;
+    done.store(true, std::memory_order_release);
+    return HBFP_OK;
+}
 
 // Geometry of one encode/decode call in terms of the SOURCE matrix.
 struct EncodeGeom {

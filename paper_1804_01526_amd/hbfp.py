@@ -86,6 +86,7 @@ def _load():
     lib.hbfp_gemm_packed_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm_packed.argtypes = [T, vp, T, vp, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
+    lib.hbfp_gemm_partials_window.argtypes = [T, T, i64, i64, i64, i64, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
     lib.hbfp_encode_multi_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(sz)]
@@ -94,7 +95,7 @@ def _load():
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
     for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
-                 "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_f32_workspace",
+                 "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
@@ -314,6 +315,17 @@ def gemm_partials(a: BfpTensor, b: BfpTensor, workspace: Optional[torch.Tensor] 
     _check(_lib.hbfp_gemm_partials(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(P), _dev_ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
            "hbfp_gemm_partials")
+    return P
+
+
+def gemm_partials_window(a: BfpTensor, b: BfpTensor, row0: int, rows: int, col0: int, cols: int,
+                          workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hbfp_gemm_partials_window: the integer block sums of rows row0.. x columns col0.. of the product only."""
+    P = torch.empty((rows, cols, a.desc.nblk), dtype=torch.int32, device=a.mant.device)
+    workspace = _workspace(gemm_select_workspace(a.desc, b.desc, KERNEL_INT8), P.device, workspace)
+    _check(_lib.hbfp_gemm_partials_window(ctypes.byref(a.desc), ctypes.byref(b.desc), row0, rows, col0, cols, _dev_ptr(P),
+                                          _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                          _stream_ptr(stream)), "hbfp_gemm_partials_window")
     return P
 
 

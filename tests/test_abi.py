@@ -181,6 +181,12 @@ def test_gemm_validation():
     over_a, over_b = desc(8, 8, 133145, 1, 1, 0), desc(8, 133145, 8, 0, 0, 1)
     assert lib.hbfp_gemm(byref(over_a), byref(over_b), fake, 8, 0.0, None, 0, None) == hbfp.ERR_RANGE
     assert lib.hbfp_gemm_partials(byref(a), byref(b), None, None, 0, None) == hbfp.ERR_ARG
+    # a window of the block sums must lie inside the product (a: 128 operand rows, b: 64)
+    big = 1 << 22
+    for row0, rows, col0, cols in ((0, 0, 0, 8), (-1, 8, 0, 8), (121, 8, 0, 8), (0, 129, 0, 8), (0, 8, 57, 8), (0, 8, 0, 65), (0, 8, -2, 4)):
+        assert lib.hbfp_gemm_partials_window(byref(a), byref(b), row0, rows, col0, cols, fake, fake, big, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_partials_window(byref(a), byref(b), 0, 8, 0, 8, None, fake, big, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_partials_window(byref(a), byref(b), 120, 8, 56, 8, fake, None, 0, None) == hbfp.ERR_WORKSPACE
 
 
 def test_gemm_select_validation():
