@@ -160,6 +160,23 @@ int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int co
                 const hbfp_format *fmt, hbfp_tensor *out, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_encode_static: hbfp_encode for callers that cannot allocate device memory or pass scratch of their own (code
+ * under HIP graph capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc).  Same arguments,
+ * result and errors as hbfp_encode, without the workspace: the table of block maxima that the two-pass conversions
+ * need (hbfp_encode_workspace bytes: 4 per exponent block; one exponent per row or column, per image, per matrix,
+ * long blocks, large tiles) lives in a device array inside the library of hbfp_encode_static_limit() = 1 MiB bytes,
+ * i.e. up to 262144 exponent blocks, which every GPU the library runs on holds until the process ends.
+ * HBFP_ERR_WORKSPACE if the format needs more.  The call allocates nothing and frees nothing.  The first call on a
+ * device looks the array's address up (make that call outside a graph capture).  All calls on one GPU share the
+ * array: calls that overlap on one GPU (different streams) race; calls ordered on one stream do not, because each
+ * call clears the entries it uses before using them.  Formats that need no table (hbfp_encode_workspace = 0) do
+ * not touch the array.
+ */
+size_t hbfp_encode_static_limit(void);
+int hbfp_encode_static(const float *src, int64_t rows, int64_t cols, int64_t ld, int contract_axis,
+                       const hbfp_format *fmt, hbfp_tensor *out, void *stream);
+
+/*
  * hbfp_decode: BFP -> FP32, Eq. (1): dst[r*ld + c] = mant * 2^(Eb - 125 - mant_bits),
  * written in the SOURCE orientation [src_rows][src_cols] of the tensor.  Exact,
  * subnormal results included.

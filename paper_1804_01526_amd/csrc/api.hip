@@ -3,9 +3,32 @@
 // behave the same on a machine without a GPU.
 #include <string.h>
 
+#include <atomic>
+
 #include "hbfp_internal.h"
 
 using namespace hbfp;
+
+// ---- hbfp_encode_static: hbfp_encode for callers that cannot pass device scratch of their own.
+// The table of block maxima of the two-pass conversions lives in this array.  Its name is a host-side stand-in: the
+// address kernels can use comes from hipGetSymbolAddress, once per device (every device has its own copy).
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static int static_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> address[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HBFP_ERR_LAUNCH;
+    void *p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HBFP_ERR_LAUNCH;
+        address[dev].store(p, std::memory_order_release);       // a race stores the same address twice
+    }
+    *out = p;
+    return HBFP_OK;
+}
+
 
 namespace {
 
@@ -227,6 +250,29 @@ int hbfp_encode(const float *src, int64_t rows, int64_t cols, int64_t ld, int co
         if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     }
     return encode_planned(src, ld, out, need != 0, workspace, (hipStream_t)stream);
+}
+
+size_t hbfp_encode_static_limit(void) { return kStaticScratchBytes; }
+
+int hbfp_encode_static(const float *src, int64_t rows, int64_t cols, int64_t ld, int contract_axis, const hbfp_format *fmt,
+                       hbfp_tensor *out, void *stream) {
+    if (!src || !fmt || !out || rows <= 0 || cols <= 0 || ld < cols) return HBFP_ERR_ARG;
+    hbfp_tensor p;
+    int rc = hbfp_plan(fmt, rows, cols, contract_axis, &p);
+    if (rc != HBFP_OK) return rc;
+    if (!same_plan(p, *out)) return HBFP_ERR_LAYOUT;
+    if (!out->mant || !out->exps) return HBFP_ERR_ARG;
+    if (((uintptr_t)out->mant & 15) || ((uintptr_t)out->exps & 3) || ((uintptr_t)src & 3)) return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_encode_workspace(&p, &need);
+    if (need > kStaticScratchBytes) return HBFP_ERR_WORKSPACE;     // more exponent blocks than the array holds
+    void *table = nullptr;
+    if (need) {
+        rc = static_scratch(&table);
+        if (rc != HBFP_OK) return rc;
+    }
+    // the first kernel of a two-pass conversion clears the entries it is going to use (a fill kernel, no memset node)
+    return encode_planned(src, ld, out, need != 0, table, (hipStream_t)stream);
 }
 
 static int encode_multi_check(int n, const hbfp_tensor *const *outs, size_t *scratch) {

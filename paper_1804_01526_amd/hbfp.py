@@ -70,6 +70,9 @@ def _load():
     lib.hbfp_plan.argtypes = [F, i64, i64, i32, T]
     lib.hbfp_encode_workspace.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_encode.argtypes = [vp, i64, i64, i64, i32, F, T, vp, sz, vp]
+    lib.hbfp_encode_static.argtypes = [vp, i64, i64, i64, i32, F, T, vp]
+    lib.hbfp_encode_static_limit.restype = sz
+    lib.hbfp_encode_static_limit.argtypes = []
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
     lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp, sz, vp]
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
@@ -93,7 +96,7 @@ def _load():
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -199,6 +202,21 @@ def encode(src: torch.Tensor, contract_axis: int, fmt: Format, out: Optional[Bfp
     _check(_lib.hbfp_encode(_dev_ptr(src), rows, cols, ld, contract_axis, ctypes.byref(fmt), ctypes.byref(out.desc),
                             _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                             _stream_ptr(stream)), "hbfp_encode")
+    return out
+
+
+def encode_static_limit() -> int:
+    return int(_lib.hbfp_encode_static_limit())
+
+
+def encode_static(src: torch.Tensor, contract_axis: int, fmt: Format, out: BfpTensor, stream=None) -> BfpTensor:
+    """hbfp_encode_static: hbfp_encode whose scratch is a fixed array inside the library (nothing is allocated;
+    `out` comes from ``alloc``)."""
+    assert src.is_cuda and src.dtype == torch.float32 and src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(src.stride(0), cols)
+    _check(_lib.hbfp_encode_static(_dev_ptr(src), rows, cols, ld, contract_axis, ctypes.byref(fmt), ctypes.byref(out.desc),
+                                   _stream_ptr(stream)), "hbfp_encode_static")
     return out
 
 
