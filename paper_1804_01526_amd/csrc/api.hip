@@ -653,6 +653,8 @@ int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream) {
     g.kpad = t->kpad;
     g.expA_ld = t->exp_ld;
     g.kbp = t->kblock_pad;
+    g.kblock = t->kblock;
+    g.nblk = t->nblk;
     g.mA = g.mB = t->mant_bits;
     return launch_mx_pack(g, packed, nullptr, (hipStream_t)stream);
 }

@@ -65,6 +65,7 @@ struct PackParams {
     int64_t R, kpad, exp_ld;
     int32_t ksteps, nks4, chunks32_per_block, m;
     int32_t mark;
+    int32_t ob, noct;            // dense layout: octets (8 elements) per exponent block and in the whole row; ob = 0: padded layout
 };
 
 // Scale bytes of the limbs of one group of 32 codes with stored exponent byte E; `bad` if one is out of range.
@@ -139,10 +140,111 @@ __device__ __forceinline__ void mx_pack_block_i8(const PackParams &p, uint32_t b
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Dense layout for exponent blocks of 8, 16 or 24 elements.  Such blocks are STORED padded to 32, and packing them as
+// stored would make a quarter (24), half (16) or three quarters (8) of the matrix instructions multiply zeros.  The
+// instruction scales groups of 32 codes, but an E2M3 code carries two exponent bits of its own: the integer n * 2^d
+// (n in 0..15, d in 0..2) is still a code.  So the k axis is packed without the padding, a group of 32 consecutive
+// elements takes the SMALLEST exponent among its (two to four) blocks as its scale, and the elements of a block whose
+// exponent is d binades above it are stored as n * 2^d: the same numbers, exactly.  A group whose non-zero blocks are
+// more than 2 binades apart cannot be written that way; it marks the operand's header like an exponent out of range,
+// and the int8 kernels queued behind the product compute it from the stored operand.  Both operands of a product
+// pack k the same way (the rule depends on the block length alone).
+//
+// Unit of the mapping is the octet (8 consecutive elements; block lengths are multiples of 8): octet j of the dense
+// axis lies in block j / ob at offset 8 * (j % ob), i.e. at stored position 32 * (j / ob) + 8 * (j % ob).
+__device__ __forceinline__ uint32_t dense_block_of(uint32_t j, int ob) {
+    return ob == 3 ? __umulhi(j, 0xAAAAAAABu) >> 1 : ob == 2 ? j >> 1 : j;
+}
+// the code of twice the value of each byte's code: normal codes (>= 8) gain one in their exponent field (+ 8),
+// subnormal codes (< 8) double as integers (7 -> 14 is the normal code of 14 / 8)
+__device__ __forceinline__ uint32_t e2m3_double_bytes(uint32_t c) {
+    const uint32_t normal = ((c + 0x78787878u) >> 7) & 0x01010101u;   // 1 in the bytes that hold a code >= 8
+    return c + normal * 8u + (c & ((normal ^ 0x01010101u) * 255u));
+}
+
+template <int L>
+__device__ __forceinline__ void mx_pack_block_i8_dense(const PackParams &p, uint32_t block) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
+    const int64_t rt = block / p.nks4;
+    const int ks = (int)(block % p.nks4) * 4 + wave;
+    if (ks >= p.ksteps) return;
+    const int q = lane & 3;                                   // quarter of the k-step: 16 elements = 2 octets
+    uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
+    v2i raw[2][2];
+    int E[2][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int64_t row = rt * 32 + h * 16 + (lane >> 2);
+        const bool live = row < p.R;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            const uint32_t j = (uint32_t)ks * 8u + (uint32_t)q * 2u + (uint32_t)o;
+            raw[h][o] = v2i{0, 0};
+            E[h][o] = 255;                                    // an octet without a non-zero mantissa takes any exponent
+            if (live && j < (uint32_t)p.noct) {
+                const uint32_t b = dense_block_of(j, p.ob);
+                raw[h][o] = *reinterpret_cast<const v2i *>(reinterpret_cast<const int8_t *>(p.mant) + row * p.kpad + (int64_t)b * 32 +
+                                                           8 * (int)(j - b * (uint32_t)p.ob));
+                if (raw[h][o][0] | raw[h][o][1]) {
+                    const int e = p.exps[row * p.exp_ld + b];
+                    E[h][o] = e > 254 ? 254 : e;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = h * 16 + (lane >> 2);
+        // the group of 32 is this lane's two octets and those of the neighbouring lane (q ^ 1)
+        int emin = E[h][0] < E[h][1] ? E[h][0] : E[h][1];
+        const int other = __builtin_amdgcn_update_dpp(0, emin, 0xB1, 0xF, 0xF, false);   // quad_perm [1, 0, 3, 2]
+        emin = other < emin ? other : emin;
+        const bool empty = emin == 255;                       // the whole group is zero
+        bool far = false;
+        uint32_t g[L][4];
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            int d = E[h][o] == 255 ? 0 : E[h][o] - emin;
+            if (d > 2) {
+                far = true;
+                d = 2;
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t x = (uint32_t)raw[h][o][i];
+                const uint32_t sg = (x >> 7) & 0x01010101u;
+                const uint32_t a = (x ^ (sg * 255u)) + sg;
+#pragma unroll
+                for (int j = 0; j < L; ++j) {
+                    uint32_t w = (a >> (4 * (L - 1 - j))) & 0x0f0f0f0fu;
+                    if (d > 0) w = e2m3_double_bytes(w);
+                    if (d > 1) w = e2m3_double_bytes(w);
+                    w |= sg << 5;
+                    const uint32_t t = (w & 0x003f003fu) | ((w >> 2) & 0x0fc00fc0u);
+                    g[j][2 * o + i] = (t & 0xfffu) | ((t >> 4) & 0xfff000u);
+                }
+            }
+        }
+        bool bad;
+        const uint32_t word = empty ? 0u : mx_scale_word<L>(emin, p.m, bad);
+        if (far || (!empty && bad)) p.header[0] = p.mark;
+        const int lo = r + 32 * (q >> 1);
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            const Bytes12 three = {g[j][0] | (g[j][1] << 24), (g[j][1] >> 8) | (g[j][2] << 16), (g[j][2] >> 16) | (g[j][3] << 8)};
+            *reinterpret_cast<Bytes12 *>(chunk + j * kLimbBytes + lo * 24 + (q & 1) * 12) = three;
+        }
+        if ((q & 1) == 0) *reinterpret_cast<uint32_t *>(chunk + L * kLimbBytes + lo * 4) = word;
+    }
+}
+
 template <int L, typename MT>
 __device__ __forceinline__ void mx_pack_block(const PackParams &p, uint32_t block) {
     if constexpr (sizeof(MT) == 1) {
-        mx_pack_block_i8<L>(p, block);
+        if (p.ob) mx_pack_block_i8_dense<L>(p, block);
+        else mx_pack_block_i8<L>(p, block);
         return;
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -768,8 +870,15 @@ int32_t next_mark() {
     return (int32_t)e;
 }
 
-PackParams pack_params(const void *mant, const uint8_t *exps, int64_t R, int64_t kpad, int64_t exp_ld, int64_t kbp, int m,
-                       void *packed) {
+// octets per exponent block when the operands of `a` are packed densely (8-bit class, blocks of 8, 16 or 24), else 0
+int dense_octets(const GemmArgs &a) {
+    return (a.kbp == 32 && a.kblock < 32 && a.kblock % 8 == 0 && a.mA <= 8 && a.mB <= 8) ? (int)(a.kblock / 8) : 0;
+}
+// k-steps of 64 that the product kernel walks: the stored length, or the unpadded one for the dense layout
+int64_t mx_ksteps(const GemmArgs &a) { return (dense_octets(a) ? round_up(a.nblk * a.kblock, 128) : a.kpad) / 64; }
+
+PackParams pack_params(const GemmArgs &a, const void *mant, const uint8_t *exps, int64_t R, int64_t exp_ld, int m, void *packed) {
+    const int64_t kpad = a.kpad, kbp = a.kbp;
     PackParams q;
     q.mant = mant;
     q.exps = exps;
@@ -779,10 +888,12 @@ PackParams pack_params(const void *mant, const uint8_t *exps, int64_t R, int64_t
     q.R = R;
     q.kpad = kpad;
     q.exp_ld = exp_ld;
-    q.ksteps = (int32_t)(kpad / 64);
+    q.ksteps = (int32_t)mx_ksteps(a);
     q.nks4 = (q.ksteps + 3) / 4;
     q.chunks32_per_block = (int32_t)(kbp / 32);
     q.m = m;
+    q.ob = dense_octets(a);
+    q.noct = (int32_t)(a.nblk * q.ob);
     return q;
 }
 
@@ -881,7 +992,7 @@ bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b) {
 }
 
 bool gemm_mx_possible(const GemmArgs &a) {
-    return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 64 <= 0x7fffffff;
+    return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 64 <= 0x7fffffff && a.nblk * 4 <= 0x7fffffff;
 }
 
 bool gemm_mx_ok(const GemmArgs &a) {
@@ -931,11 +1042,11 @@ int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
     int64_t ba = 0, bb = 0;
     int LA = limbs_of(a.mA), LB = limbs_of(a.mB);
     if (packed_a) {
-        q.op[0] = pack_params(a.mantA, a.expA, a.M, a.kpad, a.expA_ld, a.kbp, a.mA, packed_a);
+        q.op[0] = pack_params(a, a.mantA, a.expA, a.M, a.expA_ld, a.mA, packed_a);
         ba = ceil_div(a.M, 256) * 8 * q.op[0].nks4;
     }
     if (packed_b) {
-        q.op[1] = pack_params(a.mantB, a.expB, a.N, a.kpad, a.expB_ld, a.kbp, a.mB, packed_b);
+        q.op[1] = pack_params(a, a.mantB, a.expB, a.N, a.expB_ld, a.mB, packed_b);
         bb = ceil_div(a.N, 256) * 8 * q.op[1].nks4;
     }
     if (!packed_a) LA = LB;                                     // the absent operand has no workgroups; any instantiation does
@@ -981,7 +1092,7 @@ static int launch_mx_group(int n, const GemmArgs *args, const void *const *packe
         p.M = a.M;
         p.N = a.N;
         p.ldc = a.ldc;
-        p.ksteps = (int32_t)(a.kpad / 64);
+        p.ksteps = (int32_t)mx_ksteps(a);
         p.tiles_m = (int32_t)ceil_div(a.M, 256);
         p.tiles_n = (int32_t)ceil_div(a.N, 256);
         p.beta = a.beta != 0.0f;

@@ -221,3 +221,53 @@ def test_encoded_output_of_an_exact_product(hb, kernel, out_kb, out_m, relu):
     m, e = unpack(got)
     np.testing.assert_array_equal(e, want.exps)
     np.testing.assert_array_equal(m, want.mant)
+
+
+# ------------------------------------------------------------------ dense packing of blocks shorter than 32
+def _stepped(rng, shape, kb, axis, steps, small=15):
+    """Integer mantissas with one +-127 per block as in _integers, block b of every operand row scaled by 2^steps[row, b]."""
+    x = _integers(rng, shape, kb, axis, 127, small=small)
+    xs = np.moveaxis(x, axis, 1)
+    K = xs.shape[1]
+    for b, b0 in enumerate(range(0, K, kb)):
+        xs[:, b0:b0 + kb] *= np.exp2(steps[:, b])[:, None].astype(np.float32)
+    return x
+
+
+@pytest.mark.parametrize("kernel", [SCALED, INT8])
+@pytest.mark.parametrize("kb", [24, 16, 8])
+@pytest.mark.parametrize("which", ["a", "b", "both"])
+def test_dense_packing_neighbouring_blocks_up_to_two_binades_apart(hb, kernel, kb, which):
+    """Blocks shorter than 32 are packed without their padding for the block-scaled kernel: a group of 32 consecutive
+    elements spans two to four blocks, takes the smallest of their exponents and holds the other blocks' limbs shifted
+    left by up to 2 bits.  Exponents of neighbouring blocks differ by 0, 1 or 2 here; every sum stays below 2^24."""
+    rng = np.random.default_rng(7000 + kb + kernel + len(which))
+    M, N, K = 270, 280, {24: 480, 16: 400, 8: 264}[kb]
+    nblk = -(-K // kb)
+    sa = rng.integers(0, 3, size=(M, nblk)) if which in ("a", "both") else np.zeros((M, nblk), dtype=np.int64)
+    sb = rng.integers(0, 3, size=(N, nblk)) if which in ("b", "both") else np.zeros((N, nblk), dtype=np.int64)
+    small = 50 if which == "both" else 127
+    A = _stepped(rng, (M, K), kb, 1, sa, small)
+    B = _stepped(rng, (K, N), kb, 0, sb, small)
+    assert (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)).max() < 2 ** 24, "test input: sums must stay exact"
+    _exact(hb, A, B, (1, kb, 8), (kb, 1, 8), kernel)
+
+
+@pytest.mark.parametrize("kb", [24, 16])
+def test_dense_packing_falls_back_when_blocks_are_far_apart(hb, kb):
+    """A jump of three and more binades between neighbouring blocks cannot be written into one group of 32: the
+    call must still deliver the exact product (the int8 kernels behind the block-scaled kernel compute it)."""
+    rng = np.random.default_rng(7100 + kb)
+    M, N, K = 260, 300, 240
+    nblk = -(-K // kb)
+    sa = np.zeros((M, nblk), dtype=np.int64)
+    sa[5, 3] = 3                                   # a single far block in one row is enough
+    sa[200:, ::2] = 6
+    A = _stepped(rng, (M, K), kb, 1, sa, small=3)
+    B = _integers(rng, (K, N), kb, 0, 127, small=3)
+    _exact(hb, A, B, (1, kb, 8), (kb, 1, 8), SCALED)
+    # all-zero blocks between non-zero ones take any exponent: no fallback needed, still exact
+    A2 = _integers(rng, (M, K), kb, 1, 127)
+    A2[:, kb:2 * kb] = 0.0
+    A2[7, :] = 0.0
+    _exact(hb, A2, B, (1, kb, 8), (kb, 1, 8), SCALED)
