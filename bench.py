@@ -36,14 +36,15 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X FP32 vector peak, published (256 CUs 
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_config4_hbm_traffic_counters.txt for the
-# product kernel of config 4 alone, profiles/bench_default_hbm_traffic_counters.txt for the encode), scaled by what the same counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 product kernel (gemm_mx_kernel<2, 2, false>): 107504 KiB x 2.0 + 65536 KiB = 287.3 MB
+# product kernel of config 4 alone, profiles/bench_default_hbm_traffic_counters.txt for the encode), scaled by what the same
+# counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
+#   config 4 product kernel (gemm_mx_kernel<2, 2, false>, 64 k-steps): see profiles/gemm_config4_hbm_traffic_counters.txt
 #   config 2 encode m=8 RNE launch: 131704 KiB x 2.0 + 67587 KiB = 338.9 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 287.3e6
+TRAFFIC_GEMM_C4_BYTES = None
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.9e6
-# algorithmic bytes of the config 4 product kernel: both operands as limb planes read once (16 panels of 256 rows x 86
-# k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
-ALG_BYTES_GEMM_C4 = 2 * 16 * 86 * 26624 + 4096 * 4096 * 4
+# algorithmic bytes of the config 4 product kernel: both operands as densely packed limb planes read once (16 panels of
+# 256 rows x 64 k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
+ALG_BYTES_GEMM_C4 = 2 * 16 * 64 * 26624 + 4096 * 4096 * 4
 
 
 def _parse():
@@ -54,6 +55,7 @@ def _parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph instead of 12 separate launches")
     ap.add_argument("--no-extra", action="store_true", help="skip the config 2 / 3 / 5 side measurements")
+    ap.add_argument("--no-probe", action="store_true", help="skip the register-only matrix-instruction loops")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run can scale FETCH_SIZE/WRITE_SIZE")
     return ap.parse_args()
@@ -97,46 +99,28 @@ def _linear_layer(torch, hbfp, synth):
     enc = {k: hbfp.alloc(f, s.shape[0], s.shape[1], ax) for k, (s, ax, f) in ops.items()}
     prods = [("x_fwd", "w_fwd"), ("dy_dgrad", "w_dgrad"), ("x_wgrad", "dy_wgrad")]
     outs = [torch.empty((enc[a].desc.rows, enc[b].desc.rows), dtype=torch.float32, device="cuda") for a, b in prods]
-    ws_gemm = [torch.empty(max(hbfp.gemm_workspace(enc[a].desc, enc[b].desc), 256), dtype=torch.uint8, device="cuda")
-               for a, b in prods]
-
-    # each source matrix is converted into both of its operand layouts by one call (hbfp_encode_multi)
-    groups = [("encode_act", X, [enc["x_fwd"], enc["x_wgrad"]]), ("encode_act", dY, [enc["dy_dgrad"], enc["dy_wgrad"]]),
-              ("encode_w", W, [enc["w_fwd"], enc["w_dgrad"]])]
-    assert all(hbfp.encode_multi_workspace(outs_) == 0 for _, _, outs_ in groups)
-
-    # buffers of the two-step form of the same product (hbfp_pack + hbfp_gemm_packed), used only by the pass that
-    # times the product kernel by itself
+    # each source matrix is converted into both of its operand layouts, stored and packed for the block-scaled kernel,
+    # by one call that reads it once (hbfp_encode_packed)
     packed = {k: torch.empty(hbfp.pack_bytes(t.desc), dtype=torch.uint8, device="cuda") for k, t in enc.items()}
+    groups = [("encode_act", X, ["x_fwd", "x_wgrad"]), ("encode_act", dY, ["dy_dgrad", "dy_wgrad"]), ("encode_w", W, ["w_fwd", "w_dgrad"])]
+    assert all(hbfp.encode_packed_workspace([enc[k] for k in names]) == 0 for _, _, names in groups)
     ws_packed = [torch.empty(max(hbfp.gemm_packed_workspace(enc[a].desc, enc[b].desc), 256), dtype=torch.uint8, device="cuda")
                  for a, b in prods]
 
     def step(timer=None):
-        for name, src, outs_ in groups:
+        for name, src, names in groups:
             if timer:
                 a, b = timer.region(name)
                 a.record()
-            hbfp.encode_multi(src, outs_)
+            hbfp.encode_packed(src, [enc[k] for k in names], [packed[k] for k in names])
             if timer:
                 b.record()
         for i, (pa, pb) in enumerate(prods):
             if timer:
                 a, b = timer.region("gemm")
                 a.record()
-            hbfp.gemm(enc[pa], enc[pb], out=outs[i], workspace=ws_gemm[i])
+            hbfp.gemm_packed(enc[pa], packed[pa], enc[pb], packed[pb], out=outs[i], workspace=ws_packed[i])
             if timer:
-                b.record()
-        if timer:
-            # the same three products once more in two steps, with events around the product kernel alone
-            for i, (pa, pb) in enumerate(prods):
-                a, b = timer.region("pack")
-                a.record()
-                hbfp.pack(enc[pa], out=packed[pa])
-                hbfp.pack(enc[pb], out=packed[pb])
-                b.record()
-                a, b = timer.region("product")
-                a.record()
-                hbfp.gemm_packed(enc[pa], packed[pa], enc[pb], packed[pb], out=outs[i], workspace=ws_packed[i])
                 b.record()
 
     flops_per_product = 2.0 * M * N * K
@@ -454,6 +438,39 @@ def _kernel_families(torch, hbfp, reps=8):
     return {"kernel_families": res}
 
 
+def _matrix_probe(torch, hbfp, iters=3000):
+    """What the matrix core sustains on this machine: register-only loops (hbfp_probe_matrix_rate) of the int8 and of the
+    block-scaled FP6 matrix instruction at 1 and 2 workgroups of 4 waves per compute unit, with constant and with
+    random operand bits; the shader clock is the cycle counter against the 100 MHz wall clock inside the kernel."""
+    res = {}
+    sink = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(1)
+    operands = {"constant_bits": torch.full((64 * 64,), 0x01010101, dtype=torch.int32, device="cuda"),
+                "random_bits": torch.randint(-2 ** 31, 2 ** 31 - 1, (64 * 64,), dtype=torch.int64, device="cuda", generator=g).to(torch.int32)}
+    for name, instr, flop in (("int8_32x32x32", 0, 2.0 * 32 * 32 * 32), ("scaled_fp6_32x32x64", 1, 2.0 * 32 * 32 * 64)):
+        for tag, words in operands.items():
+            best = None
+            for wgs in (512, 1024):
+                hbfp.probe_matrix_rate(instr, words, wgs, 100, sink, clocks)
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                hbfp.probe_matrix_rate(instr, words, wgs, iters, sink, clocks)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b)
+                c = clocks.cpu().tolist()
+                rate = wgs * 4 * iters * 16 * flop / ms / 1e9
+                if best is None or rate > best["T_per_s"]:
+                    best = {"T_per_s": round(rate, 1), "shader_clock_GHz": round(c[0] / max(c[1], 1) * 0.1, 3), "waves_per_simd": wgs // 512,
+                            "ms": round(ms, 3)}
+            res[f"{name}_{tag}"] = best
+    res["note"] = ("T_per_s: tera-operations per second of the loop (int8: TOP/s, FP6: TFLOP/s), best of 1 and 2 waves per SIMD; "
+                   "the published peaks are 5000 and 10100")
+    return res
+
+
 def _cpu_baseline(synth):
     """The oracle as it stands on the host cores: one whole step of config 4 (forward, data gradient and
     weight gradient: six encodes, FP64 products of the dequantised operands)."""
@@ -529,15 +546,12 @@ def main():
     ms_step = t_begin.elapsed_time(t_end) / args.steps
     tops = flops_step / ms_step / 1e9
 
-    gemm_ms = timer.total_ms("gemm") / timer.count("gemm")
-    gemm_tops = flops_product / gemm_ms / 1e9
-    # the product kernel by itself (hbfp_gemm_packed on operands packed just before: the same kernel the one-call
-    # form launches, plus the int8 stand-by that exits at once)
-    product_ms = timer.total_ms("product") / timer.count("product")
-    pack_ms = timer.total_ms("pack") / timer.count("pack")
+    # one hbfp_gemm_packed call = the product kernel plus the int8 stand-by launch behind it, which exits at once
+    # when every exponent is in range (4 us of the bracket; the rocprofv3 summary lists the two separately)
+    product_ms = timer.total_ms("gemm") / timer.count("gemm")
+    product_tops = flops_product / product_ms / 1e9
     # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
-    limb_flop = 4.0 * flops_product
-    limb_tflops = limb_flop / (product_ms * 1e-3) / 1e12
+    limb_tflops = 4.0 * product_tops
     enc_act_ms = timer.total_ms("encode_act") / args.steps
     enc_w_ms = timer.total_ms("encode_w") / args.steps
     gemm_step_ms = timer.total_ms("gemm") / args.steps
@@ -562,27 +576,24 @@ def main():
                                   "encode_weights_x2": round(enc_w_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
         "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
-        # The product runs on the block-scaled matrix instruction with FP6 (E2M3) operands: an 8-bit mantissa is two
-        # sign-magnitude limbs of 4 bits, so a mantissa product is 4 limb products, all of them matrix-core work
-        # (the per-block scaling happens inside the instruction).  Algorithmic flop per launch = 4 * 2*M*N*K (padding
-        # of the 24-element blocks to 32 not counted), against the published dense FP6 peak.
-        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2, false>", "achieved": round(limb_tflops, 1),
-                     "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
-                     "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
+        # Roofline of the dominant kernel against the peak the metric names: effective operations 2*M*N*K, counted once
+        # per mantissa product, over the product kernel's launch time, against the published dense int8 matrix peak.
+        # The kernel reaches them with 4 limb products per mantissa product on the FP6 rate of the block-scaled
+        # instruction (limb_products: the same time against the published FP6 peak).
+        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2, false>", "achieved": round(product_tops, 1),
+                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(product_tops / INT8_PEAK_TOPS, 4),
+                     "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
                      "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
-                     "algorithmic_flop_per_launch": limb_flop,
-                     "whole_call_ms": round(gemm_ms, 4), "pack_ms_two_launches": round(pack_ms, 4),
-                     "int8_equivalent_TOPS": round(flops_product / product_ms / 1e9, 2),
-                     "int8_equivalent_TOPS_whole_call": round(gemm_tops, 2),
-                     "int8_matrix_frac": round(flops_product / product_ms / 1e9 / INT8_PEAK_TOPS, 4),
-                     "power_limited_peak_measured": {"fp6_TFLOPS_random_operands": 5750.0, "int8_TOPS_random_operands": 3400.0,
-                                                     "note": "register-only loops of the matrix instruction on this box: the chip "
-                                                             "lowers its clock to 1.4 GHz (FP6) / 1.6 GHz (int8) when the operand bits are random"},
-                     "note": "avg_launch_ms is the HIP-event time of the product kernel on operands packed beforehand "
-                             "(hbfp_gemm_packed: gemm_mx_kernel plus the int8 stand-by kernel, which exits at once when every "
-                             "exponent is in range); whole_call_ms is one hbfp_gemm call of the timed step (pack kernel for both "
-                             "operands + product + stand-by); the rocprofv3 summary lists each kernel"},
+                     "algorithmic_ops_per_launch": flops_product,
+                     "limb_products": {"achieved": round(limb_tflops, 1), "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
+                                       "note": "4 exact limb products per 8-bit mantissa product, every one of them matrix-core work"},
+                     "note": "avg_launch_ms is the HIP-event time of one hbfp_gemm_packed call of the timed step on the launch stream: "
+                             "the product kernel plus the int8 stand-by kernel behind it (exits at once when every exponent is in "
+                             "range); the operands were packed by the conversion calls; the rocprofv3 summary lists each kernel"},
     }
+    if not args.no_probe:
+        out["roofline"]["matrix_probe"] = _matrix_probe(torch, hbfp)
     if not args.no_extra:
         extra = _encode_config2(torch, hbfp, synth)
         e = extra["encode_m8_rne"]

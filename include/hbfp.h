@@ -402,6 +402,26 @@ int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *co
                       void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_encode_packed: hbfp_encode_multi followed by hbfp_pack of its outputs, in one call: every output is converted
+ * (Sec. 4.1) and, where packed[i] is not NULL, also written as the limb planes the block-scaled kernel reads, so that
+ * hbfp_gemm_packed can multiply it without a pass in between.  A training step converts each of its three FP32
+ * matrices (input, weights, output gradient) into the two operand layouts its products need (Sec. 5.1), and each
+ * operand is multiplied once: this is the conversion for that case.
+ *   outs, n, src, ld, workspace   as hbfp_encode_multi (workspace: hbfp_encode_packed_workspace bytes)
+ *   packed[i]        NULL, or a device buffer of at least hbfp_pack_bytes(outs[i]) bytes, 256-byte aligned
+ *   packed_bytes[i]  its size
+ * Both results are what the two separate calls produce, bit for bit (the packed buffer from its byte 256 on; the
+ * words before are a per-call mark).  When the outputs (at most two) have exponent blocks of 24 along k - 1 x 24 or
+ * 24 x 1 blocks, or 24 x 24 tiles - with mantissas of at most 8 bits, equal limb counts and rounding, a source aligned
+ * to 16 bytes with ld and the number of columns multiples of 4, and all are packed, one kernel reads the source once
+ * and writes everything; any other combination runs the separate kernels one after the other.
+ * Errors: as hbfp_encode_multi and hbfp_pack.
+ */
+int hbfp_encode_packed_workspace(int n, const hbfp_tensor *const *outs, size_t *bytes);
+int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed,
+                       const size_t *packed_bytes, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_weight_update: one step on weights kept in BFP with wide mantissas
  * (Sec. 4.2 "Wide weight storage"; Sec. 5.1, the optimizer shell: the update is
  * computed in FP32 and the result is converted to two BFP formats, the wide one
@@ -430,6 +450,22 @@ int hbfp_weight_update_workspace(const hbfp_tensor *wide, const hbfp_tensor *nar
 int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, float alpha,
                        const hbfp_tensor *narrow_a, const hbfp_tensor *narrow_b,
                        void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * hbfp_probe_matrix_rate: measurement aid, not part of the path.  Runs a register-only loop of one matrix instruction
+ * (no memory traffic inside the loop) on every compute unit, so that a caller can time what the matrix core sustains
+ * for given operand bits: the chip lowers its clock under its power limit, and how far depends on the bits.
+ *   instruction  0: v_mfma_i32_32x32x32_i8;  1: v_mfma_scale_f32_32x32x64_f8f6f4 with FP6 (E2M3) operands
+ *   words        device, 64 x 64 ints: register r of lane l at words[r * 64 + l]; registers 0..31 feed the first
+ *                operands of the 4 x 4 independent chains of a wave, 32..63 the second operands
+ *   workgroups   workgroups of 4 waves (8 .. 65536); iters: loop trips, 16 matrix instructions per wave each
+ *   sink         device, workgroups * 256 floats (written, so that the loop is not removed)
+ *   clocks       device, 2 x int64: shader cycles and 100 MHz wall-clock ticks of the loop of workgroup 7
+ * One trip is 16 instructions of 2 * 32 * 32 * 32 (int8) or 2 * 32 * 32 * 64 (FP6) operations per wave.
+ * Errors: HBFP_ERR_ARG, HBFP_ERR_LAUNCH.
+ */
+int hbfp_probe_matrix_rate(int instruction, const int *words, int workgroups, int iters, float *sink, long long *clocks,
+                           void *stream);
 
 #ifdef __cplusplus
 }

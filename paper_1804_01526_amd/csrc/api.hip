@@ -312,6 +312,47 @@ int hbfp_encode_multi(const float *src, int64_t ld, int n, const hbfp_tensor *co
     return HBFP_OK;
 }
 
+int hbfp_encode_packed_workspace(int n, const hbfp_tensor *const *outs, size_t *bytes) {
+    return hbfp_encode_multi_workspace(n, outs, bytes);
+}
+
+static int pack_one(const hbfp_tensor *t, void *packed, hipStream_t s) {
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = t->mant;
+    g.expA = t->exps;
+    g.M = t->rows;
+    g.kpad = t->kpad;
+    g.expA_ld = t->exp_ld;
+    g.kbp = t->kblock_pad;
+    g.kblock = t->kblock;
+    g.nblk = t->nblk;
+    g.mA = g.mB = t->mant_bits;
+    return launch_mx_pack(g, packed, nullptr, s);
+}
+
+int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed,
+                       const size_t *packed_bytes, void *workspace, size_t ws_bytes, void *stream) {
+    size_t need = 0;
+    int rc = encode_multi_check(n, outs, &need);
+    if (rc != HBFP_OK) return rc;
+    if (!packed || !packed_bytes || !src || ((uintptr_t)src & 3) || ld < outs[0]->src_cols) return HBFP_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        if (!packed[i]) continue;
+        if ((uintptr_t)packed[i] & 255) return HBFP_ERR_ARG;
+        if (outs[i]->mant_bits > 12) return HBFP_ERR_FORMAT;
+        if (packed_bytes[i] < mx_packed_bytes(outs[i]->rows, outs[i]->kpad, outs[i]->mant_bits)) return HBFP_ERR_WORKSPACE;
+        if (ceil_div(outs[i]->rows, 256) * 8 * ceil_div(outs[i]->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
+    }
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (encode_pack_ok(src, ld, n, outs, packed)) return launch_encode_pack(src, ld, n, outs, packed, s);
+    rc = hbfp_encode_multi(src, ld, n, outs, workspace, ws_bytes, stream);
+    for (int i = 0; i < n && rc == HBFP_OK; ++i)
+        if (packed[i]) rc = pack_one(outs[i], packed[i], s);
+    return rc;
+}
+
 int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
                        void *stream) {
     if (!x || !conv || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
@@ -645,18 +686,7 @@ int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream) {
     if (!packed || ((uintptr_t)packed & 255)) return HBFP_ERR_ARG;
     if (bytes < mx_packed_bytes(t->rows, t->kpad, t->mant_bits)) return HBFP_ERR_WORKSPACE;
     if (ceil_div(t->rows, 256) * 8 * ceil_div(t->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
-    GemmArgs g;
-    memset(&g, 0, sizeof g);
-    g.mantA = t->mant;
-    g.expA = t->exps;
-    g.M = t->rows;
-    g.kpad = t->kpad;
-    g.expA_ld = t->exp_ld;
-    g.kbp = t->kblock_pad;
-    g.kblock = t->kblock;
-    g.nblk = t->nblk;
-    g.mA = g.mB = t->mant_bits;
-    return launch_mx_pack(g, packed, nullptr, (hipStream_t)stream);
+    return pack_one(t, packed, (hipStream_t)stream);
 }
 
 int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {

@@ -32,25 +32,13 @@
 #include <chrono>
 
 #include "bfp_device.h"
-#include "gemm_common.h"
+#include "mx_pack.h"
 
 namespace hbfp {
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
-struct __attribute__((aligned(4))) Bytes12 {   // 12 bytes stored at a 4-byte aligned address
-    uint32_t a, b, c;
-};
-
-// limbs of 4 magnitude bits that a mantissa of m bits (sign included) needs
-inline int limbs_of(int m) { return m <= 5 ? 1 : m <= 9 ? 2 : 3; }
-
 constexpr int kMxThreads = 512;
-constexpr int kLimbBytes = 1536;                 // one limb of 32 rows x 64 k: 24 bytes per lane
-constexpr int kScaleBytes = 256;                 // [64 lanes] one word: exponent byte of limb j in byte j
-constexpr int kRowTiles = 8;                     // 32-row tiles per 256-row panel
-__host__ __device__ constexpr int chunk_bytes(int L) { return L * kLimbBytes + kScaleBytes; }
-__host__ __device__ constexpr int panel_stage_bytes(int L) { return kRowTiles * chunk_bytes(L); }   // a multiple of 2048
 
 // ------------------------------------------------------------------------------------------------
 // Packed operand: [panel of 256 rows][k-step of 64][row tile of 32][limb planes, most significant first | scale words].
@@ -67,24 +55,6 @@ struct PackParams {
     int32_t mark;
     int32_t ob, noct;            // dense layout: octets (8 elements) per exponent block and in the whole row; ob = 0: padded layout
 };
-
-// Scale bytes of the limbs of one group of 32 codes with stored exponent byte E; `bad` if one is out of range.
-template <int L>
-__device__ __forceinline__ uint32_t mx_scale_word(int E, int m, bool &bad) {
-    E = E > 254 ? 254 : E;
-    uint32_t word = 0;
-    bad = false;
-#pragma unroll
-    for (int j = 0; j < L; ++j) {
-        int byte = E + 5 + 4 * (L - 1 - j) - m;
-        if (byte < 0 || byte > 254) {
-            bad = true;
-            byte = byte < 0 ? 0 : 254;
-        }
-        word |= (uint32_t)byte << (8 * j);
-    }
-    return word;
-}
 
 // int8 mantissas: a lane converts 16 consecutive mantissas (one 16-byte load; the 4 lanes of a row read its 64 bytes
 // of the k-step, so a wave instruction reads 16 whole 64-byte pieces) into the 12 bytes they occupy in each limb plane.
@@ -118,7 +88,7 @@ __device__ __forceinline__ void mx_pack_block_i8(const PackParams &p, uint32_t b
         for (int i = 0; i < 4; ++i) {
             const uint32_t x = live ? (uint32_t)raw[h][i] : 0u;
             const uint32_t sg = (x >> 7) & 0x01010101u;                   // 1 in the bytes of negative mantissas
-            const uint32_t a = (x ^ (sg * 255u)) + sg;                    // byte-wise two's complement negation
+            const uint32_t a = (x ^ byte_mask(sg)) + sg;                  // byte-wise two's complement negation
             any |= a;
 #pragma unroll
             for (int j = 0; j < L; ++j) {
@@ -140,29 +110,6 @@ __device__ __forceinline__ void mx_pack_block_i8(const PackParams &p, uint32_t b
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Dense layout for exponent blocks of 8, 16 or 24 elements.  Such blocks are STORED padded to 32, and packing them as
-// stored would make a quarter (24), half (16) or three quarters (8) of the matrix instructions multiply zeros.  The
-// instruction scales groups of 32 codes, but an E2M3 code carries two exponent bits of its own: the integer n * 2^d
-// (n in 0..15, d in 0..2) is still a code.  So the k axis is packed without the padding, a group of 32 consecutive
-// elements takes the SMALLEST exponent among its (two to four) blocks as its scale, and the elements of a block whose
-// exponent is d binades above it are stored as n * 2^d: the same numbers, exactly.  A group whose non-zero blocks are
-// more than 2 binades apart cannot be written that way; it marks the operand's header like an exponent out of range,
-// and the int8 kernels queued behind the product compute it from the stored operand.  Both operands of a product
-// pack k the same way (the rule depends on the block length alone).
-//
-// Unit of the mapping is the octet (8 consecutive elements; block lengths are multiples of 8): octet j of the dense
-// axis lies in block j / ob at offset 8 * (j % ob), i.e. at stored position 32 * (j / ob) + 8 * (j % ob).
-__device__ __forceinline__ uint32_t dense_block_of(uint32_t j, int ob) {
-    return ob == 3 ? __umulhi(j, 0xAAAAAAABu) >> 1 : ob == 2 ? j >> 1 : j;
-}
-// the code of twice the value of each byte's code: normal codes (>= 8) gain one in their exponent field (+ 8),
-// subnormal codes (< 8) double as integers (7 -> 14 is the normal code of 14 / 8)
-__device__ __forceinline__ uint32_t e2m3_double_bytes(uint32_t c) {
-    const uint32_t normal = ((c + 0x78787878u) >> 7) & 0x01010101u;   // 1 in the bytes that hold a code >= 8
-    return c + normal * 8u + (c & ((normal ^ 0x01010101u) * 255u));
-}
-
 template <int L>
 __device__ __forceinline__ void mx_pack_block_i8_dense(const PackParams &p, uint32_t block) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -174,6 +121,7 @@ __device__ __forceinline__ void mx_pack_block_i8_dense(const PackParams &p, uint
     uint8_t *chunk = p.out + (((rt >> 3) * p.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
     v2i raw[2][2];
     int E[2][2];
+    // all loads first (mantissas and exponent bytes side by side), then the conversion
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int64_t row = rt * 32 + h * 16 + (lane >> 2);
@@ -181,63 +129,24 @@ __device__ __forceinline__ void mx_pack_block_i8_dense(const PackParams &p, uint
 #pragma unroll
         for (int o = 0; o < 2; ++o) {
             const uint32_t j = (uint32_t)ks * 8u + (uint32_t)q * 2u + (uint32_t)o;
-            raw[h][o] = v2i{0, 0};
-            E[h][o] = 255;                                    // an octet without a non-zero mantissa takes any exponent
-            if (live && j < (uint32_t)p.noct) {
-                const uint32_t b = dense_block_of(j, p.ob);
-                raw[h][o] = *reinterpret_cast<const v2i *>(reinterpret_cast<const int8_t *>(p.mant) + row * p.kpad + (int64_t)b * 32 +
-                                                           8 * (int)(j - b * (uint32_t)p.ob));
-                if (raw[h][o][0] | raw[h][o][1]) {
-                    const int e = p.exps[row * p.exp_ld + b];
-                    E[h][o] = e > 254 ? 254 : e;
-                }
-            }
+            const bool there = live && j < (uint32_t)p.noct;
+            const uint32_t b = there ? dense_block_of(j, p.ob) : 0u;
+            const int64_t rs = there ? row : 0;               // octets that do not exist read the first one and become zero
+            raw[h][o] = *reinterpret_cast<const v2i *>(reinterpret_cast<const int8_t *>(p.mant) + rs * p.kpad + (int64_t)b * 32 +
+                                                       (there ? 8 * (int)(j - b * (uint32_t)p.ob) : 0));
+            E[h][o] = p.exps[rs * p.exp_ld + b];
+            if (!there) raw[h][o] = v2i{0, 0};
         }
     }
+    bool bad = false;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int o = 0; o < 2; ++o) E[h][o] = (raw[h][o][0] | raw[h][o][1]) ? (E[h][o] > 254 ? 254 : E[h][o]) : 255;
         const int r = h * 16 + (lane >> 2);
-        // the group of 32 is this lane's two octets and those of the neighbouring lane (q ^ 1)
-        int emin = E[h][0] < E[h][1] ? E[h][0] : E[h][1];
-        const int other = __builtin_amdgcn_update_dpp(0, emin, 0xB1, 0xF, 0xF, false);   // quad_perm [1, 0, 3, 2]
-        emin = other < emin ? other : emin;
-        const bool empty = emin == 255;                       // the whole group is zero
-        bool far = false;
-        uint32_t g[L][4];
-#pragma unroll
-        for (int o = 0; o < 2; ++o) {
-            int d = E[h][o] == 255 ? 0 : E[h][o] - emin;
-            if (d > 2) {
-                far = true;
-                d = 2;
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const uint32_t x = (uint32_t)raw[h][o][i];
-                const uint32_t sg = (x >> 7) & 0x01010101u;
-                const uint32_t a = (x ^ (sg * 255u)) + sg;
-#pragma unroll
-                for (int j = 0; j < L; ++j) {
-                    uint32_t w = (a >> (4 * (L - 1 - j))) & 0x0f0f0f0fu;
-                    if (d > 0) w = e2m3_double_bytes(w);
-                    if (d > 1) w = e2m3_double_bytes(w);
-                    w |= sg << 5;
-                    const uint32_t t = (w & 0x003f003fu) | ((w >> 2) & 0x0fc00fc0u);
-                    g[j][2 * o + i] = (t & 0xfffu) | ((t >> 4) & 0xfff000u);
-                }
-            }
-        }
-        bool bad;
-        const uint32_t word = empty ? 0u : mx_scale_word<L>(emin, p.m, bad);
-        if (far || (!empty && bad)) p.header[0] = p.mark;
-        const int lo = r + 32 * (q >> 1);
-#pragma unroll
-        for (int j = 0; j < L; ++j) {
-            const Bytes12 three = {g[j][0] | (g[j][1] << 24), (g[j][1] >> 8) | (g[j][2] << 16), (g[j][2] >> 16) | (g[j][3] << 8)};
-            *reinterpret_cast<Bytes12 *>(chunk + j * kLimbBytes + lo * 24 + (q & 1) * 12) = three;
-        }
-        if ((q & 1) == 0) *reinterpret_cast<uint32_t *>(chunk + L * kLimbBytes + lo * 4) = word;
+        bad |= pack_half_group_dense<L>(raw[h], E[h], p.m, chunk, r + 32 * (q >> 1), q);
     }
+    if (bad) p.header[0] = p.mark;
 }
 
 template <int L, typename MT>
@@ -1032,6 +941,18 @@ bool gemm_mx_group_ok(int n, const GemmArgs *args) {
         kmax = a.kpad > kmax ? a.kpad : kmax;
     }
     return tiles >= 256 && area >= 0.75 * 65536.0 * (double)tiles && kmin >= 1024 && kmax <= 2 * kmin;
+}
+
+// What a kernel that writes a packed operand itself needs first: this pack's mark and, under graph capture (where a
+// replay repeats the mark), a cleared out-of-range word.
+int mx_pack_begin(void *packed, hipStream_t s, int32_t *mark) {
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone) {
+        hipLaunchKernelGGL(mx_clear_flag_kernel, dim3(1), dim3(64), 0, s, (int *)packed, (int *)nullptr);
+        if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
+    }
+    *mark = next_mark();
+    return HBFP_OK;
 }
 
 size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits) { return 256 + packed_bytes(rows, kpad, limbs_of(mant_bits)); }

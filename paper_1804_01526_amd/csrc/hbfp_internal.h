@@ -91,6 +91,10 @@ bool gemm_mx_ok(const GemmArgs &a);         // shapes and formats for which it i
 size_t mx_packed_bytes(int64_t rows, int64_t kpad, int mant_bits);   // header + planes, a multiple of 256
 // packs operand A (rows a.M) and / or operand B (rows a.N) of `a` in one launch; a null buffer skips that operand
 int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
+int mx_pack_begin(void *packed, hipStream_t s, int32_t *mark);
+// encode_pack.hip: conversion and packing in one kernel (blocks of 24 along k, up to two outputs from one read)
+bool encode_pack_ok(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed);
+int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed, hipStream_t s);
 bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);
 bool gemm_mx_group_ok(int n, const GemmArgs *args);
 bool mx_encoded_output_ok(const hbfp_tensor &out);

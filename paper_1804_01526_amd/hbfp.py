@@ -94,9 +94,13 @@ def _load():
     lib.hbfp_gemm_f32.argtypes = [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, F, F, vp, sz, vp]
     lib.hbfp_encode_multi_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(sz)]
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
+    lib.hbfp_encode_packed_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(sz)]
+    lib.hbfp_encode_packed.argtypes = [vp, i64, i32, ctypes.POINTER(T), ctypes.POINTER(vp), ctypes.POINTER(sz), vp, sz, vp]
+    lib.hbfp_probe_matrix_rate.argtypes = [i32, vp, i32, i32, vp, vp, vp]
+    lib.hbfp_probe_matrix_rate.restype = i32
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_encode_packed_workspace", "hbfp_encode_packed", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -426,3 +430,33 @@ def encode_multi(src: torch.Tensor, outs, workspace: Optional[torch.Tensor] = No
                                   0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_multi")
     return outs
 
+
+
+def encode_packed_workspace(outs) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_packed_workspace(len(outs), _desc_array(outs), ctypes.byref(n)), "hbfp_encode_packed_workspace")
+    return int(n.value)
+
+
+def encode_packed(src: torch.Tensor, outs, packed, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_encode_packed: one FP32 matrix into planned operand tensors and their packed forms (``packed[i]`` a uint8
+    device tensor of ``pack_bytes`` bytes, or None)."""
+    assert src.is_cuda and src.dtype == torch.float32 and src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else max(src.stride(0), cols)
+    n = len(outs)
+    ptrs = (ctypes.c_void_p * n)(*[None if b is None else b.data_ptr() for b in packed])
+    sizes = (ctypes.c_size_t * n)(*[0 if b is None else b.numel() for b in packed])
+    workspace = _workspace(encode_packed_workspace(outs), src.device, workspace)
+    _check(_lib.hbfp_encode_packed(_dev_ptr(src), ld, n, _desc_array(outs), ptrs, sizes, _dev_ptr(workspace),
+                                   0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_packed")
+    return outs
+
+
+def probe_matrix_rate(instruction: int, words: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor,
+                      clocks: torch.Tensor, stream=None) -> None:
+    """hbfp_probe_matrix_rate: one launch of the register-only loop (the caller times it with events)."""
+    assert words.dtype == torch.int32 and words.numel() >= 64 * 64 and sink.numel() >= workgroups * 256
+    assert clocks.dtype == torch.int64 and clocks.numel() >= 2
+    _check(_lib.hbfp_probe_matrix_rate(instruction, _dev_ptr(words), workgroups, iters, _dev_ptr(sink), _dev_ptr(clocks),
+                                       _stream_ptr(stream)), "hbfp_probe_matrix_rate")

@@ -1,0 +1,139 @@
+"""hbfp_encode_packed (conversion and limb planes from one read of the source) against the calls it stands for,
+hbfp_encode_multi and hbfp_pack, and against the oracle: stored operands and packed planes bit for bit, the product
+of the packed operands against the FP64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from tests.util import rel_fro, unpack
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_1804_01526_amd import hbfp
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return hbfp
+
+
+def _rand(shape, seed, spread=2):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(shape) * np.exp2(rng.integers(-spread, spread + 1, size=shape))).astype(np.float32)
+
+
+def _flagged(buf):
+    w = buf[:8].view(torch.int32).cpu().numpy()
+    return bool(w[0] == w[1])
+
+
+def _planes_end(d):
+    """First byte past the limb planes a pack writes: 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
+    bytes behind the 256-byte header; blocks of 8, 16 and 24 are packed without their padding (buffers are sized for
+    the padded length, the rest is never written)."""
+    limbs = 1 if d.mant_bits <= 5 else 2 if d.mant_bits <= 9 else 3
+    dense = d.mant_bits <= 8 and d.kblock < 32 and d.kblock % 8 == 0
+    klen = -(-(d.nblk * d.kblock) // 128) * 128 if dense else d.kpad
+    return 256 + -(-d.rows // 256) * (klen // 64) * 8 * (limbs * 1536 + 256)
+
+
+def _check_against_separate_calls(hb, x, specs):
+    """specs: [(block rows, block cols, mantissa bits, rounding, seed, contraction axis)], all packed."""
+    src = torch.from_numpy(x).cuda()
+    rows, cols = x.shape
+    fmts = [hb.make_format(m, br, bc, rnd, seed) for br, bc, m, rnd, seed, _ in specs]
+    outs = [hb.alloc(f, rows, cols, s[5]) for f, s in zip(fmts, specs)]
+    packed = [torch.full((hb.pack_bytes(o.desc),), 0x5a, dtype=torch.uint8, device="cuda") for o in outs]
+    for o in outs:
+        o.mant.fill_(0x33)
+        o.exps.fill_(0x33)
+    hb.encode_packed(src, outs, packed)
+    torch.cuda.synchronize()
+    for o, pk, f, s in zip(outs, packed, fmts, specs):
+        want = hb.encode(src, s[5], f)
+        want_pk = hb.pack(want)
+        torch.cuda.synchronize()
+        assert torch.equal(o.mant, want.mant), f"stored mantissas differ for {s}"
+        assert torch.equal(o.exps, want.exps), f"exponent bytes differ for {s}"
+        end = _planes_end(o.desc)
+        assert end <= pk.numel()
+        assert torch.equal(pk[256:end], want_pk[256:end]), f"limb planes differ for {s}"
+        assert _flagged(pk) == _flagged(want_pk), f"fallback mark differs for {s}"
+        oo = ref.encode(x, s[0], s[1], s[2], s[3], s[4])
+        m, e = unpack(o)
+        np.testing.assert_array_equal(m, oo.mant)
+        np.testing.assert_array_equal(e, oo.exps)
+    return outs, packed
+
+
+SHAPES = [(300, 520), (192, 192), (24, 24), (1000, 1004), (97, 388)]
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES)
+def test_activation_layouts_from_one_read(hb, rows, cols):
+    """1 x 24 blocks for the product that contracts along the rows' direction and 24 x 1 blocks for the one that contracts
+    down the rows (config 4's activations and gradients)."""
+    print(f"[encode_packed] activations {rows}x{cols}", flush=True)
+    _check_against_separate_calls(hb, _rand((rows, cols), rows + cols), [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES)
+def test_weight_tiles_both_orientations(hb, rows, cols):
+    print(f"[encode_packed] weight tiles {rows}x{cols}", flush=True)
+    _check_against_separate_calls(hb, _rand((rows, cols), 7 * rows + cols) * 0.02, [(24, 24, 8, 0, 0, 0), (24, 24, 8, 0, 0, 1)])
+
+
+def test_single_outputs_stochastic_rounding_and_narrow_mantissas(hb):
+    x = _rand((260, 300), 5)
+    for spec in ([(1, 24, 8, 0, 0, 1)], [(24, 1, 8, 0, 0, 0)], [(24, 24, 6, 0, 0, 1)],
+                 [(1, 24, 8, 1, 77, 1), (24, 1, 8, 1, 78, 0)], [(24, 24, 4, 0, 0, 0), (1, 24, 5, 0, 0, 1)],
+                 [(24, 24, 4, 1, 9, 1)]):
+        print(f"[encode_packed] {spec}", flush=True)
+        _check_against_separate_calls(hb, x, spec)
+
+
+def test_heavy_tails_and_zero_blocks_mark_the_same_operands(hb):
+    """Student-t values put neighbouring blocks more than 2 binades apart (the operand must be marked, as hbfp_pack marks
+    it); all-zero rows, columns and blocks take any exponent."""
+    rng = np.random.default_rng(3)
+    x = (rng.standard_t(1.5, size=(300, 400)) * 1e-3).astype(np.float32)
+    outs, packed = _check_against_separate_calls(hb, x, [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
+    assert _flagged(packed[0]) and _flagged(packed[1]), "test input: these operands were meant to need the fallback"
+    y = _rand((300, 400), 4, 0)
+    y[:, 48:72] = 0.0
+    y[96:120] = 0.0
+    y[7] = 0.0
+    outs, packed = _check_against_separate_calls(hb, y, [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
+    assert not _flagged(packed[0]) and not _flagged(packed[1])
+
+
+def test_other_formats_take_the_separate_kernels(hb):
+    x = _rand((200, 320), 6)
+    _check_against_separate_calls(hb, x, [(1, 32, 8, 0, 0, 1), (32, 1, 8, 0, 0, 0)])
+    _check_against_separate_calls(hb, x, [(1, 64, 12, 0, 0, 1)])
+    _check_against_separate_calls(hb, x, [(1, 24, 8, 0, 0, 1), (32, 1, 8, 0, 0, 0)])
+
+
+@pytest.mark.parametrize("M,K,N", [(300, 1000, 280), (520, 4096, 260)])
+def test_product_of_operands_packed_by_the_conversion(hb, M, K, N):
+    """A training step's three products from operands converted and packed by hbfp_encode_packed: forward X W, data
+    gradient dY W^T, weight gradient X^T dY (1 x 24 / 24 x 1 blocks, 24 x 24 weight tiles)."""
+    X, W, dY = _rand((M, K), 1, 1), (_rand((K, N), 2, 1) * 0.02).astype(np.float32), (_rand((M, N), 3, 1) * 1e-3).astype(np.float32)
+    act_r, act_c, tile = (1, 24, 8, 0, 0), (24, 1, 8, 0, 0), (24, 24, 8, 0, 0)
+    enc = {}
+    for name, src, specs in (("x", X, [act_r + (1,), act_c + (0,)]), ("w", W, [tile + (0,), tile + (1,)]),
+                             ("dy", dY, [act_r + (1,), act_c + (0,)])):
+        enc[name] = _check_against_separate_calls(hb, src, specs)
+    (x_f, x_w), (px_f, px_w) = enc["x"]
+    (w_f, w_d), (pw_f, pw_d) = enc["w"]
+    (dy_d, dy_w), (pdy_d, pdy_w) = enc["dy"]
+    Xq, Wq, dYq = (ref.decode(ref.encode(a, *f[:3])) for a, f in ((X, act_r), (W, tile), (dY, act_r)))
+    Xc, dYc = (ref.decode(ref.encode(a, *act_c[:3])) for a in (X, dY))
+    for a, pa, b, pb, want in ((x_f, px_f, w_f, pw_f, ref.gemm(Xq, Wq)), (dy_d, pdy_d, w_d, pw_d, ref.gemm(dYq, Wq.T)),
+                               (x_w, px_w, dy_w, pdy_w, ref.gemm(Xc.T, dYc))):
+        C = hb.gemm_packed(a, pa, b, pb)
+        torch.cuda.synchronize()
+        err = rel_fro(C.cpu().numpy(), want)
+        print(f"        rel fro err = {err:.3e}", flush=True)
+        assert err <= 1e-5
