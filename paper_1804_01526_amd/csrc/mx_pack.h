@@ -49,9 +49,12 @@ __device__ __forceinline__ uint32_t mx_scale_word(int E, int m, bool &bad) {
 // instruction scales groups of 32 codes, but an E2M3 code carries two exponent bits of its own: the integer n * 2^d
 // (n in 0..15, d in 0..2) is still a code.  So the k axis is packed without the padding, a group of 32 consecutive
 // elements takes the SMALLEST exponent among its (two to four) blocks as its scale, and the elements of a block whose
-// exponent is d binades above it are stored as n * 2^d: the same numbers, exactly.  A group whose non-zero blocks are
-// more than 2 binades apart cannot be written that way; it marks the operand's header like an exponent out of range,
-// and the int8 kernels queued behind the product compute it from the stored operand.  Both operands of a product
+// exponent is d binades above it are stored as n * 2^d: the same numbers, exactly (and one more binade comes for
+// free where the mantissas leave a spare bit in their limbs, see pack_half_group_dense).  A group whose non-zero
+// blocks are further apart cannot be written that way; it marks the operand's header like an exponent out of range,
+// and the int8 kernels queued behind the product compute it from the stored operand.  For values drawn from one
+// normal distribution, block maxima 4 binades apart do not occur in practice (3 apart: about once in 3 million
+// groups of config 4's operands); heavy-tailed gradients do take the fallback.  Both operands of a product
 // pack k the same way (the rule depends on the block length alone).
 //
 // Unit of the mapping is the octet (8 consecutive elements; block lengths are multiples of 8): octet j of the dense
@@ -74,7 +77,8 @@ __device__ __forceinline__ uint32_t e2m3_double_bytes(uint32_t c) {
 // non-zero mantissa (it then takes any exponent).  Lanes q and q ^ 1 of a quad hold the two halves of a group of 32:
 // q even the first 16.  Writes this lane's 12 bytes of every limb plane of the row tile at `chunk` (lane `lo` of the
 // matrix instruction: operand row + 32 * half of the k-step) and, from the even lane, the group's scale word.
-// Returns true when the group cannot be expressed (blocks more than 2 binades apart, or a scale byte out of range).
+// Returns true when the group cannot be expressed (blocks more than 3 binades apart, 2 for 5-bit mantissas, or a scale
+// byte out of range).
 //
 // An octet d binades above the group's exponent holds its magnitudes times 2^d.  When the mantissas leave a spare bit
 // in their limbs (m <= 4 L: 8-bit mantissas in two limbs, 4-bit ones in one) the first binade costs nothing: twice the
@@ -91,9 +95,9 @@ __device__ __forceinline__ bool pack_half_group_dense(const v2i (&raw)[2], const
 #pragma unroll
     for (int o = 0; o < 2; ++o) {
         const int d = E[o] == 255 ? 0 : E[o] - emin;
-        far = far || d > 2;
         const int sh = (m <= 4 * L && d > 0) ? 1 : 0;                     // binades taken by doubling the magnitudes
-        const int dbl = d - sh;                                           // and by doubling the codes
+        const int dbl = d - sh;                                           // and by doubling the codes: at most two
+        far = far || dbl > 2;
         uint32_t w[L][2], sign[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {

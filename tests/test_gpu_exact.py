@@ -237,16 +237,17 @@ def _stepped(rng, shape, kb, axis, steps, small=15):
 @pytest.mark.parametrize("kernel", [SCALED, INT8])
 @pytest.mark.parametrize("kb", [24, 16, 8])
 @pytest.mark.parametrize("which", ["a", "b", "both"])
-def test_dense_packing_neighbouring_blocks_up_to_two_binades_apart(hb, kernel, kb, which):
+def test_dense_packing_neighbouring_blocks_up_to_three_binades_apart(hb, kernel, kb, which):
     """Blocks shorter than 32 are packed without their padding for the block-scaled kernel: a group of 32 consecutive
-    elements spans two to four blocks, takes the smallest of their exponents and holds the other blocks' limbs shifted
-    left by up to 2 bits.  Exponents of neighbouring blocks differ by 0, 1 or 2 here; every sum stays below 2^24."""
+    elements spans two to four blocks, takes the smallest of their exponents and holds the other blocks' magnitudes
+    shifted left by up to 3 bits (one in the limbs, two in the codes' own exponent bits).  Exponents of neighbouring
+    blocks differ by 0 to 3 here; every sum stays below 2^24."""
     rng = np.random.default_rng(7000 + kb + kernel + len(which))
     M, N, K = 270, 280, {24: 480, 16: 400, 8: 264}[kb]
     nblk = -(-K // kb)
-    sa = rng.integers(0, 3, size=(M, nblk)) if which in ("a", "both") else np.zeros((M, nblk), dtype=np.int64)
-    sb = rng.integers(0, 3, size=(N, nblk)) if which in ("b", "both") else np.zeros((N, nblk), dtype=np.int64)
-    small = 50 if which == "both" else 127
+    sa = rng.integers(0, 4, size=(M, nblk)) if which in ("a", "both") else np.zeros((M, nblk), dtype=np.int64)
+    sb = rng.integers(0, 4, size=(N, nblk)) if which in ("b", "both") else np.zeros((N, nblk), dtype=np.int64)
+    small = 20 if which == "both" else 90
     A = _stepped(rng, (M, K), kb, 1, sa, small)
     B = _stepped(rng, (K, N), kb, 0, sb, small)
     assert (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)).max() < 2 ** 24, "test input: sums must stay exact"
@@ -255,13 +256,13 @@ def test_dense_packing_neighbouring_blocks_up_to_two_binades_apart(hb, kernel, k
 
 @pytest.mark.parametrize("kb", [24, 16])
 def test_dense_packing_falls_back_when_blocks_are_far_apart(hb, kb):
-    """A jump of three and more binades between neighbouring blocks cannot be written into one group of 32: the
+    """A jump of four and more binades between neighbouring blocks cannot be written into one group of 32: the
     call must still deliver the exact product (the int8 kernels behind the block-scaled kernel compute it)."""
     rng = np.random.default_rng(7100 + kb)
     M, N, K = 260, 300, 240
     nblk = -(-K // kb)
     sa = np.zeros((M, nblk), dtype=np.int64)
-    sa[5, 3] = 3                                   # a single far block in one row is enough
+    sa[5, 3] = 4                                   # a single far block in one row is enough
     sa[200:, ::2] = 6
     A = _stepped(rng, (M, K), kb, 1, sa, small=3)
     B = _integers(rng, (K, N), kb, 0, 127, small=3)
