@@ -188,20 +188,6 @@ def test_gemm_f32_transposes(hb, trans_a, trans_b):
     assert rel_fro(C.cpu().numpy(), C64) <= TOL
 
 
-def test_config3_conv_shapes_sampled(hb):
-    """Config 3 at full size (forward, data gradient, weight gradient), checked on sampled rows."""
-    import synth
-    X, W, dY = synth.c3_conv_as_gemm()
-    rows = np.random.default_rng(3).choice(X.shape[0], size=48, replace=False)
-    rows.sort()
-    f_row, f_col = (1, 32, 8, 0, 0), (32, 1, 8, 0, 0)
-    _run(hb, X, W, f_row, f_col, partials=False, rows=rows)                               # Y = X W
-    _run(hb, dY, np.ascontiguousarray(W.T), f_row, f_col, partials=False, rows=rows)      # dX = dY W^T
-    krows = np.random.default_rng(4).choice(X.shape[1], size=48, replace=False)
-    krows.sort()
-    _run(hb, np.ascontiguousarray(X.T), dY, f_row, f_col, partials=False, rows=krows)     # dW = X^T dY
-
-
 def test_convolution_products_from_the_image_tensor(hb):
     """A 3 x 3 convolution executed as matrix products (Sec. 5.1) without the lowered matrix in memory: forward
     Y = lowered(X) W and weight gradient dW = lowered(X)^T dY, the lowered operand coming from hbfp_encode_im2col,
@@ -292,21 +278,6 @@ def test_lstm_gate_products_sampled(hb):
     _run(hb, np.ascontiguousarray(X.T), dG, act, (24, 1, 8, 0, 0), partials=False, rows=rows_w)   # dW = X^T dG
 
 
-def test_config4_linear_layer_sampled(hb):
-    """Config 4 at full size: 1 x 24 activation blocks, 24 x 24 weight tiles, K = 4096 = 170*24 + 16.  The library's
-    choice for these products is the block-scaled kernel; the int8 kernels are checked on the same operands."""
-    import synth
-    X, W, dY = synth.c4_linear()
-    tx, tw = hb.plan(hb.make_format(8, 1, 24), 4096, 4096, 1), hb.plan(hb.make_format(8, 24, 24), 4096, 4096, 0)
-    assert hb.gemm_workspace(tx, tw) > hb.gemm_select_workspace(tx, tw, hb.KERNEL_INT8)
-    rows = np.random.default_rng(5).choice(4096, size=32, replace=False)
-    rows.sort()
-    _run(hb, X, W, (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)                        # forward
-    _run(hb, dY, np.ascontiguousarray(W.T), (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows)  # dgrad
-    _run(hb, np.ascontiguousarray(X.T), dY, (1, 24, 8, 0, 0), (24, 1, 8, 0, 0), partials=False, rows=rows)   # wgrad
-    _run(hb, X, W, (1, 24, 8, 0, 0), (24, 24, 8, 0, 0), partials=False, rows=rows, kernel=1)              # forward, int8 kernels
-
-
 @pytest.mark.parametrize("M,N,K,B,m,rounding", [
     (100, 150, 640, 64, 12, 1), (64, 128, 256, 64, 12, 0), (130, 70, 1000, 32, 12, 0), (65, 129, 520, 24, 10, 1),
     (96, 96, 1024, 256, 12, 0), (70, 200, 1152, 0, 9, 0), (1, 1, 64, 64, 12, 0), (200, 100, 1000, 512, 12, 1),
@@ -325,17 +296,6 @@ def test_gemm_wide_mantissas_extreme_values(hb):
     A[:, ::3] *= -1
     _run(hb, A, B, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0))
     _run(hb, A, np.abs(B), (1, 512, 12, 0, 0), (512, 1, 12, 0, 0))      # 512 * 2047^2 = 2.15e9 - the int32 limit
-
-
-def test_config5_wide_range_bfp12_sampled(hb):
-    """Config 5 at full size: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20:
-    the library's choice (block-scaled kernel, three limbs per mantissa), then the int8 limb kernels."""
-    import synth
-    A, B = synth.c5_wide_range()
-    rows = np.random.default_rng(6).choice(8192, size=16, replace=False)
-    rows.sort()
-    _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows)
-    _run(hb, A, B, (1, 64, 12, 1, 51), (64, 1, 12, 1, 52), partials=False, rows=rows, kernel=1)
 
 
 # ---- the block-scaled kernel (hbfp_gemm_select with HBFP_KERNEL_SCALED): 256 x 256 tiles, k-steps of 64
