@@ -137,6 +137,15 @@ const char *hbfp_status_string(int status);
 int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_axis, hbfp_tensor *out);
 
 /*
+ * hbfp_sizes (host only): the three numbers a caller needs to allocate an operand, without the descriptor:
+ * bytes of mantissas, bytes of exponents and the stored contraction length kpad of the operand that encoding a source
+ * matrix [rows][cols] along contract_axis produces.  A thin wrapper over hbfp_plan (same errors); any of the three
+ * output pointers may be NULL.
+ */
+int hbfp_sizes(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_axis, size_t *mant_bytes, size_t *exp_bytes,
+               int64_t *kpad);
+
+/*
  * hbfp_encode_workspace (host only): bytes of scratch hbfp_encode needs for this
  * plan: 0 for blocks of at most 64 elements along k and at most 64 across it (128 and
  * 32 when k is the contiguous source axis); otherwise (long blocks, one exponent per row
@@ -331,7 +340,12 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
  * products (weights between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders
  * an encoded operand (mantissas of at most 12 bits) into the limb planes that kernel reads:
  *   packed  device buffer of hbfp_pack_bytes bytes, 256-byte aligned, owned by the caller; its contents are
- *           opaque and stay valid until the operand is encoded again (then pack it again)
+ *           opaque and stay valid until the operand is encoded again (then pack it again).  The first 256 bytes
+ *           hold a mark that differs from pack to pack (it lets a pack signal "exponent out of range" without
+ *           anything having to be cleared first), so two packs of the same operand agree from byte 256 on, not
+ *           before: the rule "same inputs, same bytes" holds for every result except this header.  The buffer is
+ *           sized for blocks stored padded to 32; blocks of 8, 16 and 24 elements are packed without their
+ *           padding and leave its tail unwritten.
  * hbfp_gemm_packed is hbfp_gemm_select with HBFP_KERNEL_SCALED on operands packed beforehand: C and beta as in
  * hbfp_gemm; A and B are the descriptors the buffers were packed from (their mantissas and exponents are read
  * only when an operand holds a non-zero block outside the range of the scale bytes, in which case the int8

@@ -213,6 +213,17 @@ int hbfp_plan(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_a
     return HBFP_OK;
 }
 
+int hbfp_sizes(const hbfp_format *fmt, int64_t rows, int64_t cols, int contract_axis, size_t *mant_bytes, size_t *exp_bytes,
+               int64_t *kpad) {
+    hbfp_tensor t;
+    const int rc = hbfp_plan(fmt, rows, cols, contract_axis, &t);
+    if (rc != HBFP_OK) return rc;
+    if (mant_bytes) *mant_bytes = (size_t)t.mant_bytes;
+    if (exp_bytes) *exp_bytes = (size_t)t.exp_bytes;
+    if (kpad) *kpad = t.kpad;
+    return HBFP_OK;
+}
+
 int hbfp_encode_workspace(const hbfp_tensor *plan, size_t *bytes) {
     if (!plan || !bytes) return HBFP_ERR_ARG;
     int rc = check_tensor(plan, false);

@@ -68,6 +68,8 @@ def _load():
     lib.hbfp_status_string.restype = ctypes.c_char_p
     lib.hbfp_status_string.argtypes = [i32]
     lib.hbfp_plan.argtypes = [F, i64, i64, i32, T]
+    lib.hbfp_sizes.argtypes = [F, i64, i64, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(i64)]
+    lib.hbfp_sizes.restype = i32
     lib.hbfp_encode_workspace.argtypes = [T, ctypes.POINTER(sz)]
     lib.hbfp_encode.argtypes = [vp, i64, i64, i64, i32, F, T, vp, sz, vp]
     lib.hbfp_encode_static.argtypes = [vp, i64, i64, i64, i32, F, T, vp]
@@ -148,6 +150,13 @@ def plan(fmt: Format, rows: int, cols: int, contract_axis: int) -> TensorDesc:
     d = TensorDesc()
     _check(_lib.hbfp_plan(ctypes.byref(fmt), rows, cols, contract_axis, ctypes.byref(d)), "hbfp_plan")
     return d
+
+
+def sizes(fmt: Format, rows: int, cols: int, contract_axis: int):
+    """hbfp_sizes: (mantissa bytes, exponent bytes, stored contraction length) of the operand a conversion produces."""
+    mb, eb, kp = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int64(0)
+    _check(_lib.hbfp_sizes(ctypes.byref(fmt), rows, cols, contract_axis, ctypes.byref(mb), ctypes.byref(eb), ctypes.byref(kp)), "hbfp_sizes")
+    return int(mb.value), int(eb.value), int(kp.value)
 
 
 def encode_workspace(desc: TensorDesc) -> int:

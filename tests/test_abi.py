@@ -27,6 +27,18 @@ def test_library_exports_every_declared_symbol():
     assert hbfp.status_string(0) == "ok" and "workspace" in hbfp.status_string(hbfp.ERR_WORKSPACE)
 
 
+def test_sizes_is_the_plan_in_three_numbers():
+    for rows, cols, axis, br, bc, m in ((4096, 4096, 1, 1, 24, 8), (8192, 8192, 0, 64, 1, 12), (100, 1000, 1, 1, 0, 8), (77, 130, 0, 24, 24, 16)):
+        fmt = hbfp.make_format(m, br, bc)
+        d = hbfp.plan(fmt, rows, cols, axis)
+        assert hbfp.sizes(fmt, rows, cols, axis) == (d.mant_bytes, d.exp_bytes, d.kpad)
+    fmt = hbfp.make_format(8, 1, 32)
+    assert hbfp._lib.hbfp_sizes(ctypes.byref(fmt), 0, 5, 1, None, None, None) == hbfp.ERR_ARG
+    assert hbfp._lib.hbfp_sizes(ctypes.byref(fmt), 5, 5, 1, None, None, None) == hbfp.OK
+    bad = hbfp.make_format(17, 1, 32)
+    assert hbfp._lib.hbfp_sizes(ctypes.byref(bad), 5, 5, 1, None, None, None) == hbfp.ERR_FORMAT
+
+
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(hbfp.Format) == 40
     assert ctypes.sizeof(hbfp.TensorDesc) == 144
