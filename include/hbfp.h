@@ -238,6 +238,31 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
                        void *stream);
 
 /*
+ * hbfp_gemm_conv2d: a convolution executed as a BFP matrix product (Sec. 5.1) whose activation operand is never
+ * lowered at all: the image is converted ONCE, as the matrix [n*h*w pixels][c channels] with blocks of 32 channels
+ * (hbfp_encode, contraction axis 1), and the product kernel gathers every filter tap from it while it stages its
+ * operand (one address per operand row and 64 channels; taps outside the image read zeros).
+ *     Y[(img, oy, ox)][f] = beta * Y + sum over (fr, fs, ch) of x[img][oy*stride_h - pad_h + fr][ox*stride_w - pad_w + fs][ch]
+ *                                                             * w[(fr * s + fs) * c + ch][f]
+ * with both factors as their BFP values and the sum taken as Eq. (2) takes it (integer sums over 32 channels of one
+ * tap, scaled by the two block exponents, accumulated in FP32).  Because a block of the lowered matrix is a block of
+ * the image, the result equals hbfp_gemm_select(HBFP_KERNEL_INT8) on hbfp_encode_im2col's operand bit for bit (with
+ * round to nearest; stochastic rounding draws by position in the image here, by position in the lowered matrix there).
+ * The data gradient of a stride-1 convolution is the same call on the output gradient (as the image, with padding
+ * r - 1 - pad) and the mirrored filter with its channel axes exchanged.
+ *   image    encoded [n*h*w][c], contraction axis 1, blocks of 32 along the channels, c a multiple of 64, <= 8 bits
+ *   conv     geometry (c_block must be 0: window entries in the order (fr, fs, ch))
+ *   filters  encoded filter matrix [r*s*c][filters], contraction axis 0, blocks of 32 down its rows, <= 8 bits
+ *   Y        device FP32 [n*ho*wo][ldy], ldy >= filters; beta 0 or 1
+ *   workspace  hbfp_gemm_conv2d_workspace bytes (scale words of both operands, split-k slices), 256-byte aligned
+ * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (operands do not match the geometry), HBFP_ERR_FORMAT (other block shapes,
+ * mantissas wider than 8 bits, c not a multiple of 64, c_block set), HBFP_ERR_WORKSPACE, HBFP_ERR_LAUNCH.
+ */
+int hbfp_gemm_conv2d_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes);
+int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *Y, int64_t ldy, float beta,
+                     void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation
  * (Sec. 4, tiled matrix multiplication):
  *     C[i][j] = beta*C[i][j] + sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k]*mB[j][k]

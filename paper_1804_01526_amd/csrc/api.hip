@@ -394,6 +394,72 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, table, (hipStream_t)stream);
 }
 
+// geometry and operand checks shared by hbfp_gemm_conv2d and its workspace query
+static int conv_gemm_check(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, int64_t *ho,
+                           int64_t *wo) {
+    if (!image || !conv || !filters) return HBFP_ERR_ARG;
+    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
+        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
+        return HBFP_ERR_ARG;
+    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    if (conv->c_block > 0 && conv->c_block < conv->c) return HBFP_ERR_FORMAT;          // plain window order only
+    int rc = check_tensor(image, need_ptrs);
+    if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
+    if (rc != HBFP_OK) return rc;
+    *ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
+    *wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
+    const int64_t pixels = conv->n * conv->h * conv->w;
+    if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || pixels > 0x7fffffff || conv->n * *ho * *wo > 0x7fffffff)
+        return HBFP_ERR_ARG;
+    if (image->contract_axis != 1 || image->src_rows != pixels || image->src_cols != conv->c) return HBFP_ERR_LAYOUT;
+    if (filters->contract_axis != 0 || filters->src_rows != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
+    if (image->mant_bits > 8 || filters->mant_bits > 8) return HBFP_ERR_FORMAT;
+    if (image->kblock != 32 || image->rblock != 1 || image->kshare != 1 || filters->kblock != 32 || filters->rblock != 1 ||
+        filters->kshare != 1 || (conv->c & 63))
+        return HBFP_ERR_FORMAT;
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    int64_t ho = 0, wo = 0;
+    const int rc = conv_gemm_check(image, conv, filters, false, &ho, &wo);
+    if (rc != HBFP_OK) return rc;
+    *bytes = align256(gemm_conv_workspace(conv->n * ho * wo, filters->rows, filters->kpad, image->rows, (int)(conv->c / 32)));
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *Y, int64_t ldy, float beta,
+                     void *workspace, size_t ws_bytes, void *stream) {
+    int64_t ho = 0, wo = 0;
+    int rc = conv_gemm_check(image, conv, filters, true, &ho, &wo);
+    if (rc != HBFP_OK) return rc;
+    if (!Y || ((uintptr_t)Y & 3) || ldy < filters->rows || (beta != 0.0f && beta != 1.0f)) return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_gemm_conv2d_workspace(image, conv, filters, &need);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = image->mant;
+    g.expA = image->exps;
+    g.expA_ld = image->exp_ld;
+    g.mantB = filters->mant;
+    g.expB = filters->exps;
+    g.expB_ld = filters->exp_ld;
+    g.M = conv->n * ho * wo;
+    g.N = filters->rows;
+    g.kpad = filters->kpad;
+    g.nblk = filters->nblk;
+    g.kbp = 32;
+    g.kblock = 32;
+    g.mA = image->mant_bits;
+    g.mB = filters->mant_bits;
+    g.C = Y;
+    g.ldc = ldy;
+    g.beta = beta;
+    return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream);
+}
+
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
     if (!dst) return HBFP_ERR_ARG;
     int rc = check_tensor(t, true);

@@ -310,10 +310,25 @@ constexpr int kHalfStage = 2 * kHalfTile + 2 * kHalfWords;  // 18 KB
 constexpr int kW8Ring = 4;
 constexpr int kW8LdsBytes = kW8Ring * kHalfStage;           // 72 KB: two workgroups per CU
 
+// Operand A gathered from an encoded image instead of read as a stored matrix (a convolution executed as a matrix
+// product, Sec. 5.1): operand row = output position (img, oy, ox), k = (filter row, filter column, channel).  The
+// image is an operand of its own, [pixels][channels] with blocks of 32 channels; a stage of 64 bytes of k is 64
+// channels of one filter tap, i.e. of one pixel, so the gather is one address per lane and stage.  Taps that fall
+// outside the image read a page of zeros.
+struct ConvA {
+    const uint8_t *zeros;        // at least 64 zero bytes; behind them, at +64, one row-constant word for them
+    const uint32_t *words;       // row constants of the image [channel block][pixel pitch]
+    int64_t word_pitch;
+    int32_t H, W, Ho, Wo, S, ntaps, spt;   // image, output, filter columns, taps, stages (64 channels) per tap
+    int32_t pad_h, pad_w, str_h, str_w;
+    int32_t pix_bytes;           // bytes between pixels of the encoded image
+};
+
 struct W8Params {
     GemmParams g;
     const uint32_t *wA, *wB;     // scale words [kpad / 32][rows_pad]
     int64_t mpad, npad;
+    ConvA cv;                    // CONV only
 };
 
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (a block is spb / 2 whole stages).  A block
@@ -321,7 +336,7 @@ struct W8Params {
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-template <int SPB>
+template <int SPB, bool CONV = false>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const GemmParams &p = q.g;
@@ -357,6 +372,26 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         voffB = (uint32_t)rb * (uint32_t)p.kpad + chunk * 16;
         voffW = lane * 4;
     }
+    // CONV: where this lane's operand rows sit in the image.  cy / cx: input row and column under filter tap (0, 0) of
+    // the row whose mantissas the lane copies; wy / wx the same for the row whose row constants it copies (waves 0..3).
+    int cy = 0, cx = 0, wy = 0, wx = 0;
+    int64_t cpix = 0, wpix = 0;                                                  // pixel index of that corner (may lie outside)
+    int cchunk = 0;
+    if (CONV) {
+        const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM);
+        const int rm = 16 * wave + (lane >> 2), rw = 64 * (wave & 1) + lane;
+        const int64_t pm = row0 + (rm < rows_a ? rm : rows_a - 1), pw = row0 + (rw < rows_a ? rw : rows_a - 1);
+        const int64_t per_img = (int64_t)q.cv.Ho * q.cv.Wo;
+        const int64_t im = pm / per_img, iw = pw / per_img;
+        const int remm = (int)(pm - im * per_img), remw = (int)(pw - iw * per_img);
+        cy = remm / q.cv.Wo * q.cv.str_h - q.cv.pad_h;
+        cx = remm % q.cv.Wo * q.cv.str_w - q.cv.pad_w;
+        wy = remw / q.cv.Wo * q.cv.str_h - q.cv.pad_h;
+        wx = remw % q.cv.Wo * q.cv.str_w - q.cv.pad_w;
+        cchunk = ((lane & 3) ^ ((rm >> 2) & 3)) * 16;
+        cpix = ((im * q.cv.H + cy) * q.cv.W + cx) * q.cv.pix_bytes + cchunk;     // byte offset of that corner's chunk in the image
+        wpix = (iw * q.cv.H + wy) * q.cv.W + wx;
+    }
     const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
     const int wc = wave_u & 3;                                                   // word copy: block wc >> 1, rows 64 (wc & 1) ..
     const uint32_t *wordsrc = wave_u < 4 ? q.wA + row0 + 64 * (wc & 1) : q.wB + col0 + 64 * (wc & 1);
@@ -370,16 +405,40 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     const uint32_t *nextW = wordsrc + (SPB == 1 ? 2 * (int64_t)st_begin + (wc >> 1) : SPB == 2 ? (int64_t)st_begin : (int64_t)st_begin / spb64) * wordpitch;
     const int64_t stepW = (SPB == 1 ? 2 : 1) * wordpitch;                        // words per stage (long blocks: per block)
     int req_pos = 0;                                                             // SPB == 0: stage within its block
+    // CONV: filter tap and 64-channel piece of the stage requested next (uniform)
+    int ctap = CONV ? st_begin / q.cv.spt : 0, csub = CONV ? st_begin % q.cv.spt : 0;
+    int cfr = CONV ? ctap / q.cv.S : 0, cfs = CONV ? ctap % q.cv.S : 0;
 #define HBFP_COPY_NEXT(ring)                                                                            \
     {                                                                                                   \
         const uint32_t lb = (ring) * kHalfStage;                                                        \
-        async_copy16(nextA, voffA, lb + ldsM);                                                          \
+        if (CONV) {                                                                                     \
+            const bool tap_ok = ctap < q.cv.ntaps;                                                      \
+            const uint8_t *tapA = p.A + ((int64_t)cfr * q.cv.W + cfs) * q.cv.pix_bytes + csub * kHalfK;  /* uniform */ \
+            const bool in_m = tap_ok && (unsigned)(cy + cfr) < (unsigned)q.cv.H && (unsigned)(cx + cfs) < (unsigned)q.cv.W; \
+            const uint8_t *srcA = in_m ? tapA + cpix : q.cv.zeros;                                      \
+            async_copy16_at(srcA, lb + ldsM);                                                           \
+        } else {                                                                                        \
+            async_copy16(nextA, voffA, lb + ldsM);                                                      \
+        }                                                                                               \
         async_copy16(nextB, voffB, lb + kHalfTile + ldsM);                                              \
-        async_copy4(nextW, voffW, lb + ldsW);                                                           \
+        if (CONV && wave_u < 4) {                                                                       \
+            const bool tap_ok = ctap < q.cv.ntaps;                                                      \
+            const uint32_t *tapW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + ((int64_t)cfr * q.cv.W + cfs);  /* uniform */ \
+            const bool in_w = tap_ok && (unsigned)(wy + cfr) < (unsigned)q.cv.H && (unsigned)(wx + cfs) < (unsigned)q.cv.W; \
+            const uint32_t *srcW = in_w ? tapW + wpix : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64); \
+            async_copy4_at(srcW, lb + ldsW);                                                            \
+        } else {                                                                                        \
+            async_copy4(nextW, voffW, lb + ldsW);                                                       \
+        }                                                                                               \
         nextA += kHalfK;                                                                                \
         nextB += kHalfK;                                                                                \
         if (SPB != 0) nextW += stepW;                                                                   \
         else if (++req_pos == spb64) { req_pos = 0; nextW += stepW; }                                   \
+        if (CONV && ++csub == q.cv.spt) {                                                               \
+            csub = 0;                                                                                   \
+            ++ctap;                                                                                     \
+            if (++cfs == q.cv.S) { cfs = 0; ++cfr; }                                                    \
+        }                                                                                               \
     }
 #define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 
@@ -586,6 +645,120 @@ size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_
     size_t n = split_bytes(M, N, splits);
     if (use_w8(kpad)) n += word_bytes(M, exp_ld) + word_bytes(N, exp_ld);
     return n;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Convolution as a matrix product whose activation operand is gathered from the encoded image by the product
+// kernel's own copies (Sec. 5.1).  Row constants of the image [channel block][pixels], column scales of the filter
+// matrix [k block][filters] and the page of zeros that out-of-image taps read, all in one small kernel.
+namespace {
+__global__ __launch_bounds__(256) void conv_words_kernel(const uint8_t *eimg, int64_t eimg_ld, int64_t pixels, int cblocks, int64_t pitch,
+                                                         uint32_t *wimg, const uint8_t *eflt, int64_t eflt_ld, int64_t N, int kblocks,
+                                                         int64_t npad, uint32_t *wflt, uint32_t *zeros) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.y == 0) {
+        if (i < pixels) {
+            for (int b = 0; b < cblocks; ++b) {
+                uint32_t e = eimg[i * eimg_ld + b];
+                e = e > 254u ? 254u : e;
+                wimg[(int64_t)b * pitch + i] = (e << 7) | 0x40u;            // bf16 pattern of 1.5 * 2^(E - 127)
+            }
+        }
+        if (i < 64) zeros[i] = i == 16 ? 0xC0u : 0u;                        // 64 zero bytes, then the row constant of E = 1
+    } else if (i < npad) {
+        for (int b = 0; b < kblocks; ++b) {
+            uint32_t e = i < N ? eflt[i * eflt_ld + b] : 1u;
+            e = e > 254u ? 254u : e;
+            wflt[(int64_t)b * npad + i] = e << 23;                         // the float 2^(E - 127)
+        }
+    }
+}
+}  // namespace
+
+size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, int cblocks) {
+    const int splits = choose_splits(M, N, kpad / BK, 1);
+    return split_bytes(M, N, splits) + (size_t)cblocks * (size_t)(ceil_div(pixels, 128) * 128) * 4 + word_bytes(N, kpad / 32) + 256;
+}
+
+// a: M = output positions, N = filters, mantB/expB = the filter matrix, kpad = its stored k extent (r * s * c rounded up to
+// 128); mantA/expA = the encoded image [pixels][pix_bytes], expA_ld its exponent pitch.
+int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
+                        hipStream_t s) {
+    GemmParams p = {};
+    p.A = (const uint8_t *)a.mantA;
+    p.B = (const uint8_t *)a.mantB;
+    p.eA = a.expA;
+    p.eB = a.expB;
+    p.C = a.C;
+    p.M = a.M;
+    p.N = a.N;
+    p.kpad = a.kpad;
+    p.eA_ld = a.expA_ld;
+    p.eB_ld = a.expB_ld;
+    p.ldc = a.ldc;
+    p.nblk = a.nblk;
+    p.nstage = (int32_t)(a.kpad / BK);
+    p.spb = 1;
+    const int64_t tm = ceil_div(a.M, BM), tn = ceil_div(a.N, BN);
+    if (tm * tn > 0x7ffffff0 || a.kpad / BK > 0x7fffffff || !use_w8(a.kpad)) return HBFP_ERR_ARG;
+    p.tiles_m = (int32_t)tm;
+    p.tiles_n = (int32_t)tn;
+    p.beta = a.beta != 0.0f;
+    p.final_scale = ldexpf(1.0f, 27 - a.mA - a.mB);
+    p.splits = choose_splits(a.M, a.N, p.nstage, 1);
+    p.stages_per_split = (int32_t)ceil_div(p.nstage, p.splits);
+    p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
+    p.partial = (float *)workspace;
+    const int64_t pixels = c.n * c.h * c.w;
+    const int cblocks = (int)(c.c / 32);
+    W8Params q = {};
+    q.g = p;
+    q.mpad = ceil_div(a.M, 128) * 128;
+    q.npad = ceil_div(a.N, 128) * 128;
+    uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
+    const int64_t pitch = ceil_div(pixels, 128) * 128;
+    uint32_t *wimg = (uint32_t *)w;
+    uint32_t *wflt = wimg + (size_t)cblocks * pitch;
+    uint32_t *zeros = wflt + word_bytes(a.N, a.kpad / 32) / 4;
+    q.wA = wimg;                 // unused by the gathering kernel
+    q.wB = wflt;
+    q.cv.zeros = (const uint8_t *)zeros;
+    q.cv.words = wimg;
+    q.cv.word_pitch = pitch;
+    q.cv.H = (int32_t)c.h;
+    q.cv.W = (int32_t)c.w;
+    q.cv.Ho = (int32_t)ho;
+    q.cv.Wo = (int32_t)wo;
+    q.cv.S = c.s;
+    q.cv.ntaps = c.r * c.s;
+    q.cv.spt = (int32_t)(c.c / 64);
+    q.cv.pad_h = c.pad_h;
+    q.cv.pad_w = c.pad_w;
+    q.cv.str_h = c.stride_h;
+    q.cv.str_w = c.stride_w;
+    q.cv.pix_bytes = (int32_t)pix_bytes;
+    {
+        const int64_t most = pixels > q.npad ? pixels : q.npad;
+        if (ceil_div(most, 256) > 0x7fffffff) return HBFP_ERR_ARG;
+        hipLaunchKernelGGL(conv_words_kernel, dim3((unsigned)ceil_div(most, 256), 2), dim3(256), 0, s, a.expA, a.expA_ld, pixels, cblocks,
+                           pitch, wimg, a.expB, a.expB_ld, a.N, (int)(a.kpad / 32), q.npad, wflt, zeros);
+        if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
+    }
+    static std::atomic<bool> configured{false};
+    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true>), kW8LdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
+                                    : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
+    hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    int rc = launch_status();
+    if (rc != HBFP_OK) return rc;
+    if (p.splits > 1) {
+        int64_t nb = ceil_div(a.M * a.N, kThreads);
+        if (nb > 8192) nb = 8192;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, p.partial, p.C, p.M, p.N, p.ldc, p.splits,
+                           p.beta, (const int *)nullptr, (const int *)nullptr);
+        rc = launch_status();
+    }
+    return rc;
 }
 
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {

@@ -46,6 +46,13 @@ __device__ __forceinline__ bool tile_and_split_of_workgroup(int wg, int tiles_m,
 __device__ __forceinline__ void async_copy16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
 }
+// the same copies from a full 64-bit address per lane (gathers whose sources do not share one base)
+__device__ __forceinline__ void async_copy16_at(const void *addr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(addr) : "memory");
+}
+__device__ __forceinline__ void async_copy4_at(const void *addr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(addr) : "memory");
+}
 __device__ __forceinline__ void async_copy4(const void *gbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
 }

@@ -75,6 +75,9 @@ int launch_tile_encode(const float *src, int64_t ld, float alpha, const hbfp_ten
                        int n, hipStream_t s);
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld);
+size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, int cblocks);
+int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
+                        hipStream_t s);
 int launch_gemm_limb(const GemmArgs &a, void *workspace, hipStream_t s);
 size_t gemm_limb_workspace(const hbfp_tensor *A, const hbfp_tensor *B);
 

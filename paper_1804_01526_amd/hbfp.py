@@ -77,6 +77,10 @@ def _load():
     lib.hbfp_encode_static_limit.argtypes = []
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
     lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp, sz, vp]
+    lib.hbfp_gemm_conv2d_workspace.argtypes = [T, ctypes.POINTER(Conv2d), T, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_conv2d_workspace.restype = i32
+    lib.hbfp_gemm_conv2d.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
+    lib.hbfp_gemm_conv2d.restype = i32
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
@@ -469,3 +473,25 @@ def probe_matrix_rate(instruction: int, words: torch.Tensor, workgroups: int, it
     assert clocks.dtype == torch.int64 and clocks.numel() >= 2
     _check(_lib.hbfp_probe_matrix_rate(instruction, _dev_ptr(words), workgroups, iters, _dev_ptr(sink), _dev_ptr(clocks),
                                        _stream_ptr(stream)), "hbfp_probe_matrix_rate")
+
+
+def gemm_conv2d_workspace(image: TensorDesc, conv: Conv2d, filters: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_conv2d_workspace(ctypes.byref(image), ctypes.byref(conv), ctypes.byref(filters), ctypes.byref(n)),
+           "hbfp_gemm_conv2d_workspace")
+    return int(n.value)
+
+
+def gemm_conv2d(image: BfpTensor, conv: Conv2d, filters: BfpTensor, out: Optional[torch.Tensor] = None, beta: float = 0.0,
+                workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hbfp_gemm_conv2d: Y[n*ho*wo, filters] from the image encoded once as [n*h*w, c] (blocks of 32 channels) and
+    the filter matrix [r*s*c, filters] (blocks of 32 down its rows)."""
+    ho, wo = conv.out_hw()
+    if out is None:
+        out = torch.empty((conv.n * ho * wo, filters.desc.rows), dtype=torch.float32, device=image.mant.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
+    workspace = _workspace(gemm_conv2d_workspace(image.desc, conv, filters.desc), out.device, workspace)
+    _check(_lib.hbfp_gemm_conv2d(ctypes.byref(image.desc), ctypes.byref(conv), ctypes.byref(filters.desc), _dev_ptr(out),
+                                 out.stride(0), beta, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                 _stream_ptr(stream)), "hbfp_gemm_conv2d")
+    return out

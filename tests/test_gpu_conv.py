@@ -1,0 +1,136 @@
+"""hbfp_gemm_conv2d: the convolution whose activation operand is gathered from the image converted once (Sec. 5.1:
+convolutions are executed like matrix products), against the oracle - which lowers the image explicitly - and against
+the library's own product on the lowered operand of hbfp_encode_im2col (bit for bit: a block of 32 channels of a pixel
+is the same block in the image and in every window that contains the pixel)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from tests.util import random_cases, rel_fro
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_1804_01526_amd import hbfp
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return hbfp
+
+
+def _conv_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0, against_lowered=True):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((n, h, w, c)) * np.exp2(rng.integers(-3, 4, size=(n, h, w, 1)))).astype(np.float32)
+    wm = (rng.standard_normal((r * s * c, f)) * 0.1).astype(np.float32)
+    conv = hb.Conv2d(n, h, w, c, r, s, pad_h, pad_w, sh, sw, 0, 0)
+    ho, wo = conv.out_hw()
+    print(f"[conv] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad=({pad_h},{pad_w}) stride=({sh},{sw}) -> {n * ho * wo} x {f}", flush=True)
+    img = hb.encode(torch.from_numpy(x.reshape(n * h * w, c)).cuda(), 1, hb.make_format(8, 1, 32))
+    flt = hb.encode(torch.from_numpy(wm).cuda(), 0, hb.make_format(8, 32, 1))
+    y0 = None
+    if beta:
+        y0 = rng.standard_normal((n * ho * wo, f)).astype(np.float32)
+        y = hb.gemm_conv2d(img, conv, flt, out=torch.from_numpy(y0).cuda(), beta=1.0)
+    else:
+        y = hb.gemm_conv2d(img, conv, flt)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    # the oracle: convert the image (blocks of 32 channels), lower the decoded values tap by tap, multiply in FP64
+    xq = ref.decode(ref.encode(x.reshape(n * h * w, c), 1, 32, 8)).reshape(n, h, w, c)
+    low = ref.im2col(xq, r, s, pad_h, pad_w, sh, sw)
+    # converting the lowered matrix instead gives the same operand (pinned here on the CPU side of the test)
+    np.testing.assert_array_equal(ref.decode(ref.encode(ref.im2col(x, r, s, pad_h, pad_w, sh, sw), 1, 32, 8)), low)
+    want = ref.gemm(low, ref.decode(ref.encode(wm, 32, 1, 8)))
+    if y0 is not None:
+        want = want + y0.astype(np.float64)
+    err = rel_fro(y, want)
+    print(f"        rel fro err = {err:.3e}", flush=True)
+    assert err <= TOL
+    if against_lowered and not beta:
+        ta = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, hb.make_format(8, 1, 32))
+        yl = hb.gemm(ta, flt, kernel=hb.KERNEL_INT8)
+        torch.cuda.synchronize()
+        assert np.array_equal(y, yl.cpu().numpy()), "differs from the product on the lowered operand"
+
+
+@pytest.mark.parametrize("geom", [
+    # n, h, w, c, f, r, s, pad_h, pad_w, stride_h, stride_w
+    (2, 12, 13, 64, 40, 3, 3, 1, 1, 1, 1),
+    (3, 9, 9, 128, 130, 3, 3, 1, 1, 1, 1),
+    (2, 10, 11, 64, 24, 1, 1, 0, 0, 1, 1),          # a 1 x 1 convolution: a plain product, k = 64 stored as 128
+    (2, 14, 9, 64, 50, 5, 3, 2, 1, 1, 1),
+    (2, 15, 16, 128, 64, 3, 3, 1, 1, 2, 2),          # strided
+    (1, 8, 8, 192, 33, 3, 3, 0, 0, 1, 1),            # no padding, three 64-channel stages per tap (27 stages: odd)
+    (2, 7, 7, 64, 20, 3, 3, 2, 2, 1, 3),             # padding wider than the usual, mixed strides
+    (5, 6, 6, 64, 16, 2, 2, 0, 1, 2, 1),
+])
+def test_conv_geometries(hb, geom):
+    _conv_case(hb, *geom, seed=sum(geom))
+
+
+def test_conv_accumulates_and_splits_k(hb):
+    _conv_case(hb, 2, 12, 13, 64, 40, 3, 3, 1, 1, 1, 1, seed=5, beta=1.0)
+    _conv_case(hb, 1, 6, 6, 1024, 100, 3, 3, 1, 1, 1, 1, seed=6)            # few tiles, k = 9216: split along k
+    _conv_case(hb, 1, 6, 6, 1024, 100, 3, 3, 1, 1, 1, 1, seed=7, beta=1.0)
+
+
+def test_conv_random_geometries(hb):
+    for seed in random_cases(12):
+        rng = np.random.default_rng(9000 + seed)
+        r, s = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        h, w = int(rng.integers(r, 14)), int(rng.integers(s, 14))
+        geom = (int(rng.integers(1, 4)), h, w, 64 * int(rng.integers(1, 4)), int(rng.integers(1, 150)), r, s,
+                int(rng.integers(0, r)), int(rng.integers(0, s)), int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        _conv_case(hb, *geom, seed=seed)
+
+
+def test_conv_data_gradient_of_a_stride_one_convolution(hb):
+    """dX of y = conv(x, w) with padding 1: the same call on dY with padding r - 1 - pad = 1 and the mirrored filter with
+    its channel axes exchanged, against the adjoint of the convolution sum taken in FP64 from the decoded operands."""
+    rng = np.random.default_rng(44)
+    n, h, w, c, f = 2, 9, 10, 64, 128
+    w4 = (rng.standard_normal((3, 3, c, f)) * 0.1).astype(np.float32)
+    dy = (rng.standard_normal((n, h, w, f)) * 1e-2).astype(np.float32)
+    wd = ref.filter_matrix_dgrad(w4)                                       # [3*3*f, c]
+    conv = hb.Conv2d(n, h, w, f, 3, 3, 1, 1, 1, 1, 0, 0)
+    img = hb.encode(torch.from_numpy(dy.reshape(n * h * w, f)).cuda(), 1, hb.make_format(8, 1, 32))
+    flt = hb.encode(torch.from_numpy(np.ascontiguousarray(wd)).cuda(), 0, hb.make_format(8, 32, 1))
+    dx = hb.gemm_conv2d(img, conv, flt)
+    torch.cuda.synchronize()
+    dyq = ref.decode(ref.encode(dy.reshape(n * h * w, f), 1, 32, 8)).reshape(n, h, w, f).astype(np.float64)
+    wq = ref.decode(ref.encode(np.ascontiguousarray(wd), 32, 1, 8)).astype(np.float64).reshape(3, 3, f, c)   # mirrored, [fr][fs][f][c]
+    # adjoint, written out: dx[img, y, x, ch] = sum_{fr, fs, f} dy[img, y + 1 - fr, x + 1 - fs, f] * w4[fr, fs, ch, f]
+    # where wq[2 - fr, 2 - fs, f, ch] is the quantised w4[fr, fs, ch, f]
+    want = np.zeros((n, h, w, c))
+    dyp = np.zeros((n, h + 2, w + 2, f))
+    dyp[:, 1:-1, 1:-1] = dyq
+    for fr in range(3):
+        for fs in range(3):
+            want += dyp[:, 2 - fr:2 - fr + h, 2 - fs:2 - fs + w, :] @ wq[2 - fr, 2 - fs]
+    assert rel_fro(dx.cpu().numpy(), want.reshape(n * h * w, c)) <= TOL
+
+
+def test_conv_rejects_what_it_does_not_cover(hb):
+    import ctypes
+    x = torch.zeros((2 * 8 * 8, 64), device="cuda")
+    img = hb.encode(x, 1, hb.make_format(8, 1, 32))
+    flt = hb.encode(torch.zeros((9 * 64, 16), device="cuda"), 0, hb.make_format(8, 32, 1))
+    conv = hb.Conv2d(2, 8, 8, 64, 3, 3, 1, 1, 1, 1, 0, 0)
+    y = torch.empty((128, 16), device="cuda")
+    ws = torch.empty(hb.gemm_conv2d_workspace(img.desc, conv, flt.desc), dtype=torch.uint8, device="cuda")
+    call = lambda i, c, f_, ldy=16, beta=0.0, w=ws: hb._lib.hbfp_gemm_conv2d(
+        ctypes.byref(i.desc), ctypes.byref(c), ctypes.byref(f_.desc), y.data_ptr(), ldy, beta, w.data_ptr(), w.numel(), None)
+    assert call(img, conv, flt) == hb.OK
+    assert call(img, conv, flt, ldy=8) == hb.ERR_ARG
+    assert call(img, conv, flt, beta=0.5) == hb.ERR_ARG
+    assert call(img, hb.Conv2d(2, 8, 8, 64, 3, 3, 1, 1, 1, 1, 32, 0), flt) == hb.ERR_FORMAT            # channel-block order
+    assert call(img, hb.Conv2d(2, 8, 9, 64, 3, 3, 1, 1, 1, 1, 0, 0), flt) == hb.ERR_LAYOUT             # not this image
+    img24 = hb.encode(x, 1, hb.make_format(8, 1, 24))
+    assert call(img24, conv, flt) == hb.ERR_FORMAT                                                       # blocks of 24
+    flt5 = hb.encode(torch.zeros((25 * 64, 16), device="cuda"), 0, hb.make_format(8, 32, 1))
+    assert call(img, conv, flt5) == hb.ERR_LAYOUT
+    assert hb._lib.hbfp_gemm_conv2d(ctypes.byref(img.desc), ctypes.byref(conv), ctypes.byref(flt.desc), y.data_ptr(), 16, 0.0,
+                                    None, 0, None) == hb.ERR_WORKSPACE
+    torch.cuda.synchronize()
