@@ -44,30 +44,54 @@ __device__ __forceinline__ int quant_rne(float x, int neg_unit_exp) {
     return __float_as_int(t) - 0x4B400000;
 }
 
-// Stochastic rounding in integer arithmetic on the bit pattern.  shbase = 25 - m + Eb, so the shift
-// sh = shbase - (element's exponent) is at least 25 - m >= 9.  The definition
+// Stochastic rounding: q = floor(|x| / unit + h / 2^32), sign applied afterwards, where an element whose significand
+// would have to move right by more than 32 bits becomes 0.  |x| / unit is exact in FP32 (a power-of-two scaling), its
+// integer part is the mantissa before rounding and its fraction, scaled by 2^32, is an exact integer below 2^32
+// whenever the shift is at most 32 bits; the carry of fraction + h is the rounding decision.  With
+// sh = 25 - m + Eb - (exponent field of x, at least 1) this is the definition
 //     q = (sig + (h >> (32 - sh))) >> sh   (sh <= 31),   carry of sig + h   (sh = 32),   0   (sh > 32)
-// equals bits 32 and up of (sig << (32 - sh)) + h for every sh <= 32: the bits of h dropped before the
-// sum of the definition are a fraction below one unit of sig and cannot change the floor.  So one
-// add-with-carry serves all cases; a zero (padding) value always gives 0.
-__device__ __forceinline__ int quant_sr(uint32_t bits, int shbase, uint32_t h) {
-    const uint32_t a = bits & 0x7fffffffu;
-    const uint32_t be = a >> 23;
-    uint32_t sig = be ? ((a & 0x7fffffu) | 0x800000u) : a;
-    const int sh = shbase - (int)(be ? be : 1u);
-    sig = sh > 32 ? 0u : sig;
-    const uint32_t lo = sig << ((32 - sh) & 31);
-    const uint32_t hi = (sig >> 8) >> ((sh - 8) & 31);
-    const uint32_t q = hi + ((lo + h) < h ? 1u : 0u);
+// bit for bit: the bits of h that the definition drops before adding are a fraction below one unit of sig and cannot
+// change the floor.  neg_unit_exp = 125 + m - Eb; small_bits: bit patterns below it need more than 32 bits of shift.
+__device__ __forceinline__ uint32_t sr_small_bits(uint32_t Eb, int m) {
+    const int t = (int)Eb - 7 - m;                 // elements whose exponent field (at least 1) is below t vanish
+    return t <= 1 ? 0u : (uint32_t)t << 23;
+}
+__device__ __forceinline__ int quant_sr(float x, int neg_unit_exp, uint32_t small_bits, uint32_t h) {
+    const uint32_t bits = __float_as_uint(x);
+    const float ax = (bits & 0x7fffffffu) < small_bits ? 0.0f : __builtin_fabsf(x);
+    const float y = __builtin_amdgcn_ldexpf(ax, neg_unit_exp);
+    const uint32_t whole = (uint32_t)y;                                                // truncation: y >= 0
+    const uint32_t frac = (uint32_t)__builtin_amdgcn_ldexpf(__builtin_amdgcn_fractf(y), 32);
+    const uint32_t q = whole + ((frac + h) < h ? 1u : 0u);
     const uint32_t sgn = (uint32_t)((int32_t)bits >> 31);
     return (int)((q ^ sgn) - sgn);
+}
+
+// The hash in two parts.  Its first three steps (the xorshift triple) are linear over GF(2), so the part of the
+// counter that is common to a run of elements can be pushed through them once: for counters c0 + e with c0 a
+// multiple of 8 and e < 8, c0 + e = c0 ^ e and triple(c0 ^ e ^ s0) = triple(c0 ^ s0) ^ triple(e).
+__host__ __device__ constexpr uint32_t sr_triple(uint32_t x) {
+    x ^= x << 13;
+    x ^= x >> 17;
+    x ^= x << 5;
+    return x;
+}
+// after_triple: the counter's low word ^ s0 after the three xorshift steps; high_term = (high word of the counter) ^ s1
+__device__ __forceinline__ uint32_t sr_hash_tail(uint32_t after_triple, uint32_t high_term) {
+    uint32_t x = after_triple + high_term;
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
 }
 
 template <int ROUND>
 __device__ __forceinline__ int quantise(float x, uint32_t Eb, int m, uint32_t idx_lo, uint32_t idx_hi,
                                         uint32_t s0, uint32_t s1) {
     if (ROUND == 0) return quant_rne(x, 125 + m - (int)Eb);
-    return quant_sr(__float_as_uint(x), 25 - m + (int)Eb, sr_hash(idx_lo, idx_hi, s0, s1));
+    return quant_sr(x, 125 + m - (int)Eb, sr_small_bits(Eb, m), sr_hash(idx_lo, idx_hi, s0, s1));
 }
 
 }  // namespace hbfp

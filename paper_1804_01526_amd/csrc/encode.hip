@@ -112,6 +112,7 @@ struct RowParams {
     int32_t chunks;     // 8-element chunks per stored row = kpad / 8
     int32_t nseg;       // segments per row = ceil(chunks / lanes-per-row)
     int32_t vec_ok;     // 16-byte vector loads are aligned
+    int32_t sr_aligned; // the stochastic-rounding counter of every chunk's first element is a multiple of 8
     uint32_t s0, s1;
     // GP = 0 (second pass of the two-pass conversion): the largest magnitude of every exponent block has been
     // computed already, table[(row / rblock) * ntk + block / kshare]; a stored block is gp chunks long
@@ -216,10 +217,20 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         // the image had been converted once and lowered afterwards
         uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
         if (CONV && GP == 0 && at[u] >= 0) idx0 = (uint64_t)at[u];
+        if (ROUND == 1 && p.sr_aligned) {
+            // the eight counters are idx0 | e: the xorshift steps of the hash, linear over GF(2), run once on the common
+            // part and the elements differ by compile-time constants
+            const uint32_t common = sr_triple((uint32_t)idx0 ^ p.s0), high = (uint32_t)(idx0 >> 32) ^ p.s1;
+            const uint32_t small = sr_small_bits(Eb, p.m);
+            const int unit = 125 + p.m - (int)Eb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint64_t idx = idx0 + e;
-            q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+            for (int e = 0; e < 8; ++e) q[e] = quant_sr(v[u][e], unit, small, sr_hash_tail(common ^ sr_triple((uint32_t)e), high));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t idx = idx0 + e;
+                q[e] = quantise<ROUND>(v[u][e], Eb, p.m, (uint32_t)idx, (uint32_t)(idx >> 32), p.s0, p.s1);
+            }
         }
         if (row >= 0) {
             if (!WIDE) {
@@ -341,7 +352,10 @@ void launch_row_tiled_g(const RowParams &p, int rblock, dim3 grid, bool wide, in
 
 template <int GP, bool WIDE, int ROUND>
 void launch_row_t(const RowParams &p, dim3 grid, hipStream_t s) {
-    hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 4>), grid, dim3(kThreads), 0, s, p);
+    // stochastic rounding is bound by its vector instructions and holds more registers: two chunks per thread instead of
+    // four keep more waves on a SIMD (config 2, 8-bit: 67 us against 71-75 us)
+    if (ROUND) hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 2>), dim3(grid.x * 2), dim3(kThreads), 0, s, p);
+    else hipLaunchKernelGGL((enc_row_kernel<GP, WIDE, ROUND, 4>), grid, dim3(kThreads), 0, s, p);
 }
 
 template <int GP>
@@ -890,6 +904,7 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
     p.nseg = 0;
     p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
+    p.sr_aligned = ((g.src_cols % 8) == 0 && (g.kblock % 8) == 0) ? 1 : 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
     p.table = nullptr;
@@ -912,7 +927,7 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
         return launch_status();
     }
     const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
-    if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+    if (gx > 0x3fffffff) return HBFP_ERR_ARG;                            // the stochastic-rounding launch doubles the grid
     const dim3 grid((unsigned)gx);
     const bool wide = g.m > 8;
     if (g.kbp == 32) launch_row_g<4>(p, grid, wide, g.rounding, s);
@@ -1030,6 +1045,7 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
     p.nseg = 0;
     p.vec_ok = (((uintptr_t)x & 15) == 0) ? 1 : 0;                      // C is a multiple of 8
+    p.sr_aligned = 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
     p.table = table;
@@ -1043,7 +1059,7 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     magic_of((uint32_t)p.kshare, p.dK);
     p.cv = conv_geom(c, ho, wo);
     const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
-    if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+    if (gx > 0x3fffffff) return HBFP_ERR_ARG;                            // the stochastic-rounding launch doubles the grid
     const dim3 grid((unsigned)gx);
     const bool wide = g.m > 8;
     if (table) launch_row_conv_g<0>(p, grid, wide, g.rounding, s);
@@ -1183,6 +1199,7 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         p.lpr_log2 = (((int64_t)1 << l2) == p.chunks) ? l2 : -1;
         p.nseg = 0;
         p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
+        p.sr_aligned = ((g.src_cols % 8) == 0 && (g.kblock % 8) == 0) ? 1 : 0;
         p.s0 = g.seed_lo;
         p.s1 = g.seed_hi;
         p.table = tile_amax;
@@ -1196,7 +1213,7 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         magic_of((uint32_t)p.rblock, p.dR);
         magic_of((uint32_t)p.kshare, p.dK);
         const int64_t gx = ceil_div(g.R * (int64_t)p.chunks, (int64_t)kThreads * 4);
-        if (gx > 0x7fffffff) return HBFP_ERR_ARG;
+        if (gx > 0x3fffffff) return HBFP_ERR_ARG;
         launch_row_g<0>(p, dim3((unsigned)gx), wide, g.rounding, s);
     } else {
         ColParams p;
