@@ -305,7 +305,7 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     del ta, tb, out, ws, img, Wd, dimg
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the
-    # block-scaled matrix instruction with three 4-bit limbs per mantissa)
+    # FP16 matrix instruction on mantissas widened to FP16)
     Ah, Bh = synth.c5_wide_range()
     A, B = torch.from_numpy(Ah).cuda(), torch.from_numpy(Bh).cuda()
     fa, fb = hbfp.make_format(12, 1, 64, hbfp.STOCHASTIC, 51), hbfp.make_format(12, 64, 1, hbfp.STOCHASTIC, 52)
@@ -424,9 +424,9 @@ def _encoded_output(torch, hbfp, reps=10):
 
 
 def _kernel_families(torch, hbfp, reps=8):
-    """The two ways the library evaluates the product, side by side on square products with N(0,1) operands:
-    int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction
-    (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included).  Block length 0 is one
+    """The ways the library evaluates the product, side by side on square products with N(0,1) operands:
+    int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction, and for
+    12-bit mantissas the FP16 matrix instruction on mantissas widened to FP16 (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included).  Block length 0 is one
     exponent per row of A and per column of B (Sec. 4), where the int8 family runs its 256 x 256-tile kernel
     (one chain of matrix instructions, exponents applied at the store)."""
     res = {}
@@ -445,15 +445,17 @@ def _kernel_families(torch, hbfp, reps=8):
             del wse
         del A, B
         out = torch.empty((n, n), dtype=torch.float32, device="cuda")
-        for tag, kernel in (("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)):
+        families = [("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)] + ([("fp16", hbfp.KERNEL_FP16)] if m > 8 else [])
+        for tag, kernel in families:
             ws = torch.empty(max(hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel), 256), dtype=torch.uint8, device="cuda")
             ms = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws, kernel=kernel), reps)
             entry[tag + "_ms"] = round(ms, 4)
             entry[tag + "_TOPS"] = round(2.0 * n ** 3 / ms / 1e9, 1)
             del ws
-        auto = hbfp.gemm_workspace(ta.desc, tb.desc) > hbfp.gemm_select_workspace(ta.desc, tb.desc, hbfp.KERNEL_INT8)
-        entry["automatic_choice"] = "scaled" if auto else "int8"
-        best = min(entry["int8_ms"], entry["scaled_ms"])
+        auto = hbfp.gemm_workspace(ta.desc, tb.desc)           # the choice shows in the workspace it asks for
+        entry["automatic_choice"] = next((tag for tag, kernel in reversed(families)
+                                          if auto == hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel)), "int8")
+        best = min(entry[tag + "_ms"] for tag, _ in families)
         entry["best_TOPS_incl_encode"] = round(2.0 * n ** 3 / (best + entry["encode_a_ms"] + entry["encode_b_ms"]) / 1e9, 1)
         res[name] = entry
         del ta, tb, out

@@ -305,11 +305,17 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
  *                       HBFP_KERNEL_INT8 and HBFP_KERNEL_AUTO take it by themselves when at least 128 such
  *                       tiles are at least 75 % full; naming it runs it on any shape (HBFP_ERR_FORMAT if the
  *                       operands have more than one block or wider mantissas);
- *   HBFP_KERNEL_AUTO    what hbfp_gemm does: SCALED where it is measured faster (at least 144 output
- *                       tiles of 256 x 256, a stored contraction length of at least 2048, or 1024 from
- *                       512 tiles on, and either blocks of at most 32 elements, an operand of at most
- *                       5 bits, or mantissas wider than 9 bits), else INT8.
- * Both satisfy the same bound against the FP64 product of the decoded operands.
+ *   HBFP_KERNEL_FP16    9..12-bit mantissas as FP16 numbers (an 11-bit magnitude is an FP16 significand): one FP16 matrix
+ *                       instruction multiplies them exactly and sums in FP32, then the per-block scale-and-accumulate runs
+ *                       on the vector unit as in the int8 family.  A block sum beyond 2^24 is rounded to nearest once per
+ *                       16 products of the chain instead of once per block; blocks of 32, 64 or a multiple of 128
+ *                       (HBFP_ERR_FORMAT otherwise, and for 8-bit operands);
+ *   HBFP_KERNEL_AUTO    what hbfp_gemm does: FP16 when both operands have 9..12-bit mantissas in blocks it takes (measured
+ *                       ahead of both other families from 2048^3 to 8192^3); otherwise SCALED where it is measured faster
+ *                       (at least 144 output tiles of 256 x 256, a stored contraction length of at least 2048, or 1024
+ *                       from 512 tiles on, and either blocks of at most 32 elements, an operand of at most 5 bits, or
+ *                       mantissas wider than 9 bits), else INT8.
+ * All satisfy the same bound against the FP64 product of the decoded operands.
  * Arguments, domain and errors as hbfp_gemm, plus HBFP_ERR_ARG for an unknown kernel; the workspace
  * size depends on the kernel: hbfp_gemm_select_workspace.
  */
@@ -317,6 +323,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 #define HBFP_KERNEL_INT8 1
 #define HBFP_KERNEL_SCALED 2
 #define HBFP_KERNEL_INT8_WIDE 3
+#define HBFP_KERNEL_FP16 4
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes);
 int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
                      void *workspace, size_t ws_bytes, void *stream);
@@ -392,7 +399,8 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
  * computed with the int8 matrix instruction (v_mfma_i32_32x32x32_i8) by the member of the int8 kernel family
  * that can write its int32 accumulators out: a kernel of its own, not one that hbfp_gemm launches (those keep
  * the block sums in registers and scale them at once).  The kernels hbfp_gemm runs are checked separately, on
- * inputs for which the FP32 result itself is exact.  Same operand rules.
+ * inputs for which the FP32 result itself is exact.  Same operand rules; workspace: what hbfp_gemm_select_workspace
+ * returns for HBFP_KERNEL_INT8.
  *   row0, rows / col0, cols (hbfp_gemm_partials_window): only the block sums of that window of the product are
  *   computed and written, P[((i - row0) * cols + (j - col0)) * nblk + b]: a few tiles of a product whose full
  *   dump would not fit in memory.  HBFP_ERR_ARG if the window is empty or leaves the product.

@@ -527,12 +527,12 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
 }
 
 static bool use_scaled(const GemmArgs &g, int kernel) {
-    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE) return false;
+    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE || kernel == HBFP_KERNEL_FP16) return false;
     return kernel == HBFP_KERNEL_SCALED ? gemm_mx_possible(g) : gemm_mx_ok(g);
 }
 
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes) {
-    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
     int rc = check_tensor(A, false);
     if (rc != HBFP_OK) return rc;
     rc = check_tensor(B, false);
@@ -540,6 +540,11 @@ int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int k
     *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
                                                      : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld);
     const GemmArgs g = gemm_args(A, B);
+    const size_t f16 = gemm_f16_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld > B->exp_ld ? A->exp_ld : B->exp_ld);
+    if (kernel == HBFP_KERNEL_FP16 || (kernel == HBFP_KERNEL_AUTO && gemm_f16_possible(g))) {
+        *bytes = f16;
+        return HBFP_OK;
+    }
     if (use_scaled(g, kernel))                                   // [packed A][packed B][int8 path behind the block-scaled kernel]
         *bytes = align256(*bytes) + mx_packed_bytes(g.M, g.kpad, g.mA) + mx_packed_bytes(g.N, g.kpad, g.mB);
     return HBFP_OK;
@@ -553,18 +558,22 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
                     void *workspace, size_t ws_bytes, void *stream) {
     int rc = check_pair(A, B);
     if (rc != HBFP_OK) return rc;
-    size_t need = 0;
-    hbfp_gemm_select_workspace(A, B, kernel, &need);
-    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     GemmArgs g = gemm_args(A, B);
     g.C = C;
     g.ldc = ldc;
     g.beta = beta;
     g.P = P;
+    if (kernel == HBFP_KERNEL_FP16 && !gemm_f16_possible(g)) return HBFP_ERR_FORMAT;
+    size_t need = 0;
+    hbfp_gemm_select_workspace(A, B, kernel, &need);
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     if (kernel == HBFP_KERNEL_INT8_WIDE) {
         if (!gemm_wide_possible(g)) return HBFP_ERR_FORMAT;
         g.wide = 1;
     }
+    // 9..12-bit mantissas are exact FP16 values: one FP16 matrix instruction per element pair instead of four or nine limb products
+    if (kernel == HBFP_KERNEL_FP16 || (kernel == HBFP_KERNEL_AUTO && gemm_f16_possible(g)))
+        return launch_gemm_f16(g, workspace, (hipStream_t)stream);
     if (use_scaled(g, kernel)) {
         // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
         // the int8 kernels queue up behind it and run only in that case
@@ -584,7 +593,7 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !C) return HBFP_ERR_ARG;
     if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
     if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
     return run_gemm(A, B, C, ldc, beta, nullptr, kernel, workspace, ws_bytes, stream);
 }
@@ -599,7 +608,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 static int batch_plan(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, GemmArgs *g, size_t *part,
                       bool *grouped) {
     if (!A || !B || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
     bool all_scaled = true, same = true;
     for (int i = 0; i < n; ++i) {
         if (!A[i] || !B[i]) return HBFP_ERR_ARG;
@@ -684,7 +693,7 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
 static int gemm_bfp_plan(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, bool need_ptrs,
                          bool *fused, size_t part[3]) {
     if (!A || !B || !out) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_INT8_WIDE) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
     int rc = need_ptrs ? check_pair(A, B) : check_tensor(A, false);
     if (rc == HBFP_OK && !need_ptrs) rc = check_tensor(B, false);
     if (rc == HBFP_OK) rc = check_tensor(out, need_ptrs);

@@ -331,13 +331,48 @@ struct W8Params {
     ConvA cv;                    // CONV only
 };
 
+// The same kernel multiplies 9..12-bit mantissas stored as FP16 numbers (F16): an 11-bit magnitude is an FP16
+// significand, so the mantissa itself is an FP16 value, v_mfma_f32_32x32x16_f16 multiplies two of them exactly (22 bits)
+// and accumulates in FP32, and a k-step of 32 bytes is 16 elements.  A block's chain then starts from zero, its FP32 sum
+// (exact below 2^24, rounded to nearest beyond: the same rounding the int32 -> FP32 conversion of the limb kernels
+// applies once) is multiplied by the row scale 2^(Ea - 127), spread over the output layout by the same bf16 matrix
+// instruction, and by the column scale: again two vector instructions per output and block.
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+template <bool F16>
+struct W8Ops;
+template <>
+struct W8Ops<false> {
+    typedef v16i acc_t;
+    static __device__ __forceinline__ acc_t mma(const v4i &a, const v4i &b, const acc_t &c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+    // what a block's chain of matrix instructions starts from: the row constants
+    static __device__ __forceinline__ acc_t start(const acc_t &row) { return row; }
+    // the block sum with its row scale applied: the constant removed
+    static __device__ __forceinline__ float scaled(int d, int row) { return __int_as_float(d) - __int_as_float(row); }
+    static __device__ __forceinline__ acc_t rows(uint32_t rowc, const v2i &one_hot) { return row_constants(rowc, one_hot); }
+    // keeps both results in vector registers at this point of the schedule
+    static __device__ __forceinline__ void pin(const acc_t &d0, const acc_t &d1) { asm volatile("" ::"v"(d0), "v"(d1)); }
+};
+template <>
+struct W8Ops<true> {
+    typedef v16f acc_t;
+    static __device__ __forceinline__ acc_t mma(const v4i &a, const v4i &b, const acc_t &c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ acc_t start(const acc_t &) { return acc_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; }   // zero
+    static __device__ __forceinline__ float scaled(float d, float row) { return d * row; }                    // the scale multiplied in
+    static __device__ __forceinline__ acc_t rows(uint32_t rowc, const v2i &one_hot) { return __builtin_bit_cast(v16f, row_constants(rowc, one_hot)); }
+    static __device__ __forceinline__ void pin(const acc_t &d0, const acc_t &d1) { asm volatile("" ::"v"(d0), "v"(d1)); }
+};
+
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (a block is spb / 2 whole stages).  A block
 // that spans several k-steps chains its matrix instructions through the C input and is scaled at its last
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-template <int SPB, bool CONV = false>
+template <int SPB, bool CONV = false, bool F16 = false>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
+    typedef W8Ops<F16> ops;
+    typedef typename ops::acc_t acc_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const GemmParams &p = q.g;
     if (stands_down(p.run_a, p.run_b)) return;
@@ -458,7 +493,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         for (int v = 0; v < 16; ++v) acc[ni][v] = 0.0f;
 
     v4i a, b[2];
-    v16i cin, d0, d1;
+    acc_t cin, d0, d1;
     uint32_t rowc = 0;
     float sb[2][2];
 #define HBFP_READ_STEP(ring, s_, set)                                                                         \
@@ -478,28 +513,33 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #define HBFP_STEP(cur, FIRST, LAST, MIDDLE)                                                             \
     {                                                                                                   \
         if (FIRST) {                                                                                    \
-            d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], cin, 0, 0, 0);                          \
-            d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], cin, 0, 0, 0);                          \
+            d0 = ops::mma(a, b[0], ops::start(cin));                                                    \
+            d1 = ops::mma(a, b[1], ops::start(cin));                                                    \
         } else {                                                                                        \
-            d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[0], d0, 0, 0, 0);                           \
-            d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[1], d1, 0, 0, 0);                           \
+            d0 = ops::mma(a, b[0], d0);                                                                 \
+            d1 = ops::mma(a, b[1], d1);                                                                 \
         }                                                                                               \
         /* both results live at once: the second matrix instruction runs while the first is scaled */   \
-        asm volatile("" ::"v"(d0), "v"(d1));                                                            \
+        ops::pin(d0, d1);                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         MIDDLE;                                                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         if (LAST) {                                                                                     \
             float x0[16], x1[16];                                                                       \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v) x0[v] = __int_as_float(d0[v]) - __int_as_float(cin[v]); \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v) x1[v] = __int_as_float(d1[v]) - __int_as_float(cin[v]); \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) x0[v] = ops::scaled(d0[v], cin[v]);          \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) x1[v] = ops::scaled(d1[v], cin[v]);          \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x0[v]));              \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));              \
             __builtin_amdgcn_sched_barrier(0);                                                          \
-            cin = row_constants(rowc, one_hot);                                                         \
+            cin = ops::rows(rowc, one_hot);                                                             \
             if (SPB == 0) {               /* long blocks always chain: the next block starts from its constants */ \
-                d0 = row_constants(rowc, one_hot);                                                      \
-                d1 = row_constants(rowc, one_hot);                                                      \
+                if (F16) {                                                                              \
+                    d0 = ops::start(cin);                                                               \
+                    d1 = ops::start(cin);                                                               \
+                } else {                                                                                \
+                    d0 = ops::rows(rowc, one_hot);                                                      \
+                    d1 = ops::rows(rowc, one_hot);                                                      \
+                }                                                                                       \
             }                                                                                           \
             __builtin_amdgcn_sched_barrier(0);                                                          \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[0][v] = fmaf(x0[v], sb[cur][0], acc[0][v]); \
@@ -518,13 +558,13 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #define HBFP_PAIR(ring)                                                                                 \
     {                                                                                                   \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (pos & 3) == 3;       \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (!F16 && (pos & 3) == 3); \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
             HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                 \
             HBFP_STEP(1, SPB == 1, last1, HBFP_READ_STEP((ring) + 1, 0, 0));                            \
         }                                                                                               \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (pos & 3) == 3;       \
+            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (!F16 && (pos & 3) == 3); \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
             HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP((ring) + 1, 1, 1));                           \
             HBFP_STEP(1, SPB == 1, last1, {                                                             \
@@ -551,10 +591,15 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     asm volatile("" ::: "memory");
     if (nst > 0) {
         HBFP_READ_STEP(0, 0, 0);
-        cin = row_constants(rowc, one_hot);
+        cin = ops::rows(rowc, one_hot);
         if (SPB == 0) {
-            d0 = row_constants(rowc, one_hot);
-            d1 = row_constants(rowc, one_hot);
+            if (F16) {
+                d0 = ops::start(cin);
+                d1 = ops::start(cin);
+            } else {
+                d0 = ops::rows(rowc, one_hot);
+                d1 = ops::rows(rowc, one_hot);
+            }
         }
     }
     int pos = 0;
@@ -750,6 +795,112 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
     hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     int rc = launch_status();
+    if (rc != HBFP_OK) return rc;
+    if (p.splits > 1) {
+        int64_t nb = ceil_div(a.M * a.N, kThreads);
+        if (nb > 8192) nb = 8192;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, p.partial, p.C, p.M, p.N, p.ldc, p.splits,
+                           p.beta, (const int *)nullptr, (const int *)nullptr);
+        rc = launch_status();
+    }
+    return rc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// 9..12-bit mantissas on the FP16 matrix instruction: the int16 mantissas become FP16 planes (exact: |m| <= 2047) in
+// the workspace, then the kernel above runs on them with F16 set.  workspace: [split-k slices][A plane][B plane]
+// [row words of A][column words of B].
+namespace {
+__global__ __launch_bounds__(256) void mant_to_f16_kernel(const int16_t *src, _Float16 *dst, int64_t n8) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const v4i x = reinterpret_cast<const v4i *>(src)[i];
+        v8h y;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] = (_Float16)(float)(int16_t)((uint32_t)x[e >> 1] >> (16 * (e & 1)));
+        reinterpret_cast<v8h *>(dst)[i] = y;
+    }
+}
+size_t f16_plane_bytes(int64_t rows, int64_t kpad) { return ((size_t)rows * (size_t)kpad * 2 + 255) & ~(size_t)255; }
+int f16_splits(int64_t M, int64_t N, int64_t kpad, int64_t kbp) {
+    const int64_t spb = kbp / 16;                       // k-steps of 32 bytes per block
+    return choose_splits(M, N, kpad * 2 / BK, spb >= 4 ? spb / 4 : 1);
+}
+}  // namespace
+
+bool gemm_f16_possible(const GemmArgs &a) {
+    return !a.P && a.mA > 8 && a.mB > 8 && a.mA <= 12 && a.mB <= 12 && (a.kbp == 32 || a.kbp == 64 || a.kbp % 128 == 0) &&
+           use_w8(a.kpad * 2) && ceil_div(a.M, BM) * ceil_div(a.N, BN) <= 0x7ffffff0 && a.kpad * 2 / BK <= 0x7fffffff;
+}
+
+size_t gemm_f16_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_t exp_ld) {
+    return split_bytes(M, N, f16_splits(M, N, kpad, kbp)) + f16_plane_bytes(M, kpad) + f16_plane_bytes(N, kpad) + word_bytes(M, exp_ld) +
+           word_bytes(N, exp_ld);
+}
+
+int launch_gemm_f16(const GemmArgs &a, void *workspace, hipStream_t s) {
+    if (!gemm_f16_possible(a) || !workspace) return HBFP_ERR_FORMAT;
+    GemmParams p = {};
+    p.splits = f16_splits(a.M, a.N, a.kpad, a.kbp);
+    uint8_t *w = (uint8_t *)workspace;
+    p.partial = (float *)w;
+    w += split_bytes(a.M, a.N, p.splits);
+    _Float16 *planeA = (_Float16 *)w;
+    w += f16_plane_bytes(a.M, a.kpad);
+    _Float16 *planeB = (_Float16 *)w;
+    w += f16_plane_bytes(a.N, a.kpad);
+    {
+        const int64_t na = a.M * a.kpad / 8, nb = a.N * a.kpad / 8;       // kpad is a multiple of 128
+        int64_t ga = ceil_div(na, 256), gb = ceil_div(nb, 256);
+        ga = ga > 65536 ? 65536 : ga;
+        gb = gb > 65536 ? 65536 : gb;
+        hipLaunchKernelGGL(mant_to_f16_kernel, dim3((unsigned)ga), dim3(256), 0, s, (const int16_t *)a.mantA, planeA, na);
+        hipLaunchKernelGGL(mant_to_f16_kernel, dim3((unsigned)gb), dim3(256), 0, s, (const int16_t *)a.mantB, planeB, nb);
+        if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
+    }
+    p.A = (const uint8_t *)planeA;
+    p.B = (const uint8_t *)planeB;
+    p.eA = a.expA;
+    p.eB = a.expB;
+    p.C = a.C;
+    p.M = a.M;
+    p.N = a.N;
+    p.kpad = a.kpad * 2;                                  // bytes of k per operand row
+    p.eA_ld = a.expA_ld;
+    p.eB_ld = a.expB_ld;
+    p.ldc = a.ldc;
+    p.nblk = a.nblk;
+    p.nstage = (int32_t)(p.kpad / BK);
+    p.spb = (int32_t)(a.kbp / 16);                        // k-steps of 32 bytes (16 elements) per exponent block
+    const int64_t tm = ceil_div(a.M, BM), tn = ceil_div(a.N, BN);
+    p.tiles_m = (int32_t)tm;
+    p.tiles_n = (int32_t)tn;
+    p.beta = a.beta != 0.0f;
+    p.final_scale = ldexpf(1.0f, 4 - a.mA - a.mB);        // scales are 2^(E - 127) each, one mantissa unit 2^(E - 125 - m)
+    const int stages_per_block = p.spb >= 4 ? p.spb / 4 : 1;
+    {
+        const int64_t units = p.nstage / stages_per_block;
+        p.stages_per_split = (int32_t)(ceil_div(units, p.splits) * stages_per_block);
+        p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
+    }
+    W8Params q = {};
+    q.g = p;
+    q.mpad = ceil_div(a.M, 128) * 128;
+    q.npad = ceil_div(a.N, 128) * 128;
+    q.wA = (const uint32_t *)w;
+    q.wB = (const uint32_t *)(w + word_bytes(a.M, a.expA_ld));
+    int rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0u, const_cast<uint32_t *>(q.wA),
+                                const_cast<uint32_t *>(q.wB), nullptr, nullptr, s);
+    if (rc != HBFP_OK) return rc;
+    static std::atomic<bool> configured[2];
+    const void *const kernels[2] = {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2, false, true>),
+                                    reinterpret_cast<const void *>(&gemm_i8_w8_kernel<0, false, true>)};
+    for (int i = 0; i < 2; ++i)
+        if (allow_dynamic_lds(configured[i], kernels[i], kW8LdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
+                                    : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
+    if (p.spb == 2) hipLaunchKernelGGL((gemm_i8_w8_kernel<2, false, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    else hipLaunchKernelGGL((gemm_i8_w8_kernel<0, false, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    rc = launch_status();
     if (rc != HBFP_OK) return rc;
     if (p.splits > 1) {
         int64_t nb = ceil_div(a.M * a.N, kThreads);

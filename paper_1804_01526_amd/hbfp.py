@@ -245,7 +245,7 @@ def decode(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> tor
     return out
 
 
-KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED, KERNEL_INT8_WIDE = 0, 1, 2, 3
+KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED, KERNEL_INT8_WIDE, KERNEL_FP16 = 0, 1, 2, 3, 4
 
 
 def gemm_select_workspace(a: TensorDesc, b: TensorDesc, kernel: int) -> int:
@@ -346,7 +346,7 @@ def gemm_packed(a: BfpTensor, packed_a: torch.Tensor, b: BfpTensor, packed_b: to
 
 def gemm_partials(a: BfpTensor, b: BfpTensor, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     P = torch.empty((a.desc.rows, b.desc.rows, a.desc.nblk), dtype=torch.int32, device=a.mant.device)
-    workspace = _workspace(gemm_workspace(a.desc, b.desc), P.device, workspace)
+    workspace = _workspace(gemm_select_workspace(a.desc, b.desc, KERNEL_INT8), P.device, workspace)
     _check(_lib.hbfp_gemm_partials(ctypes.byref(a.desc), ctypes.byref(b.desc), _dev_ptr(P), _dev_ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream_ptr(stream)),
            "hbfp_gemm_partials")

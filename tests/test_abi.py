@@ -214,7 +214,11 @@ def test_gemm_select_validation():
         return d
 
     a, b = desc(8, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)
-    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 4, fake, 1 << 20, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 5, fake, 1 << 20, None) == hbfp.ERR_ARG
+    # the FP16 kernel is for 9..12-bit mantissas in blocks stored as 32, 64 or a multiple of 128 elements
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_FP16, fake, 1 << 24, None) == hbfp.ERR_FORMAT
+    a12, b12 = desc(12, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)          # both operands have to be wide
+    assert lib.hbfp_gemm_select(byref(a12), byref(b12), fake, 64, 0.0, hbfp.KERNEL_FP16, fake, 1 << 24, None) == hbfp.ERR_FORMAT
     # the 256 x 256-tile int8 kernel is for one exponent per operand row: these operands have 8 blocks of 32
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_INT8_WIDE, fake, 1 << 20, None) == hbfp.ERR_FORMAT
     a1, b1 = desc(8, 128, 256, 1, 1, 0), desc(8, 256, 64, 0, 0, 1)
@@ -230,14 +234,19 @@ def test_gemm_select_validation():
     assert n_scaled >= n_int8 + 2 * 4 * 8 * 3328
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_SCALED, fake, n_int8, None) == hbfp.ERR_WORKSPACE
     # automatic choice on a 4096^3 product: blocks of 24 (padded to 32) and of 32 -> block-scaled; blocks of 64 -> int8;
-    # 12-bit and 4-bit mantissas -> block-scaled; a 2048^3 product (64 tiles of 256 x 256) -> int8
+    # 4-bit mantissas -> block-scaled; a 2048^3 product (64 tiles of 256 x 256) -> int8; 12-bit mantissas on both
+    # sides -> the FP16 instruction, 12-bit against 8-bit -> block-scaled
     def auto_is_scaled(m, blk):
         x, w = desc(m, 4096, 4096, 1, 1, blk), desc(m, 4096, 4096, 0, blk, 1)
         return hbfp.gemm_workspace(x, w) > hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
     assert auto_is_scaled(8, 32) and auto_is_scaled(8, 24) and not auto_is_scaled(8, 64)
     x, w = desc(8, 2048, 2048, 1, 1, 32), desc(8, 2048, 2048, 0, 32, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
-    assert auto_is_scaled(12, 64) and auto_is_scaled(4, 64) and auto_is_scaled(5, 24)
+    assert auto_is_scaled(4, 64) and auto_is_scaled(5, 24)
+    x, w = desc(12, 4096, 4096, 1, 1, 64), desc(12, 4096, 4096, 0, 64, 1)
+    assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_FP16)
+    w = desc(8, 4096, 4096, 0, 64, 1)
+    assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_SCALED)
     # narrow output: tiles of 256 x 256 would be half empty
     x, w = desc(8, 100352, 1152, 1, 1, 32), desc(8, 1152, 128, 0, 32, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)

@@ -15,7 +15,7 @@ from tests.util import unpack
 
 pytestmark = pytest.mark.gpu
 
-AUTO, INT8, SCALED, WIDE = 0, 1, 2, 3
+AUTO, INT8, SCALED, WIDE, FP16 = 0, 1, 2, 3, 4
 
 
 @pytest.fixture(scope="module")
@@ -180,7 +180,26 @@ def test_exact_sums_mixed_limb_counts(hb, ma, mb):
         _exact(hb, A, B, (1, 32, ma), (32, 1, mb), kernel)
 
 
-@pytest.mark.parametrize("kernel", [INT8, SCALED])
+@pytest.mark.parametrize("kernel", [FP16])
+@pytest.mark.parametrize("kb,K,m", [(32, 512, 9), (64, 1024, 9), (128, 768, 9), (256, 1024, 9), (0, 640, 9), (64, 16384, 9), (64, 256, 11),
+                                    (32, 160, 12)])
+def test_exact_sums_fp16_kernel(hb, kernel, kb, K, m):
+    """9..12-bit mantissas as FP16 numbers on the FP16 matrix instruction: every block length the kernel takes (two
+    matrix instructions per block of 32, chains for longer blocks), a contraction long enough for split-k, full-range
+    9-bit mantissas (|sum| <= K * 255 * 3 ... below 2^24 by construction) and wider ones with small magnitudes around the
+    planted full-width entry."""
+    rng = np.random.default_rng(8000 + kb + K + m)
+    M, N = (200, 280) if K < 8192 else (100, 90)
+    kbe = kb if kb else K
+    top = (1 << (m - 1)) - 1
+    small = {9: 255 if K <= 256 else 60, 11: 30, 12: 40}[m] if K < 8192 else 25
+    A = _integers(rng, (M, K), kbe, 1, top, small=small)
+    B = _integers(rng, (K, N), kbe, 0, top, small=small)
+    assert (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)).max() < 2 ** 24, "test input: sums must stay exact"
+    _exact(hb, A, B, (1, kb, m), (kb, 1, m), kernel)
+
+
+@pytest.mark.parametrize("kernel", [INT8, SCALED, FP16])
 @pytest.mark.parametrize("ma,mb", [(12, 12), (10, 12), (12, 10)])
 def test_exact_sums_three_limbs(hb, kernel, ma, mb):
     """9..12-bit mantissas (three 4-bit limbs, or two int8 limbs): one full-width entry per block of 64 and small

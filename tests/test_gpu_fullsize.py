@@ -75,7 +75,10 @@ def _check_product(hb, name, ta, tb, oa, ob, fa, fb, C, rows, kernel_is_scaled, 
     np.testing.assert_allclose(ref.scale_accumulate(P, ea, eb, fa[2], fb[2]), C64, rtol=1e-11, atol=0)   # the oracle agrees with itself both ways (FP64 summation order apart)
     terms = ref.scale_accumulate(np.abs(P), ea, eb, fa[2], fb[2])
     limbs = lambda m: 1 if m <= 5 else 2 if m <= 9 else 3
-    n_acc = max(nblk, limbs(fa[2]) * limbs(fb[2]) * 2 * (-(-K // 64))) if kernel_is_scaled else nblk
+    if kernel_is_scaled == "fp16":       # every FP16 matrix instruction (16 products) may round once, then one per block
+        n_acc = nblk + -(-ta.desc.kpad // 16)
+    else:
+        n_acc = max(nblk, limbs(fa[2]) * limbs(fb[2]) * 2 * (-(-K // 64))) if kernel_is_scaled else nblk
     excess = np.abs(got - C64) - n_acc * 2.0 ** -24 * terms
     worst = float((np.abs(got - C64) / np.maximum(terms, 1e-300)).max())
     print(f"[{name}] rows={len(rows)} rel fro {err:.2e}  worst |C-C64| / sum|term| = {worst:.2e} (bound {n_acc * 2.0 ** -24:.2e})", flush=True)
@@ -151,7 +154,8 @@ def test_config3_conv_shapes(hb):
 
 def test_config5_wide_range_bfp12(hb):
     """Config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20: the library's choice
-    (block-scaled kernel, three limbs per mantissa), then the int8 limb kernels."""
+    (mantissas widened to FP16 for the FP16 matrix instruction), then the block-scaled kernel with three limbs per
+    mantissa, then the int8 limb kernels."""
     import synth
     A, B = synth.c5_wide_range()
     rng = np.random.default_rng(6)
@@ -161,8 +165,13 @@ def test_config5_wide_range_bfp12(hb):
     rows = _rows_with_edges(8192, rng)
     C = hb.gemm(ta, tb)
     torch.cuda.synchronize()
-    assert hb.gemm_workspace(ta.desc, tb.desc) > hb.gemm_select_workspace(ta.desc, tb.desc, INT8)
-    _check_product(hb, "c5 scaled", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, True, rng)
+    assert hb.gemm_workspace(ta.desc, tb.desc) == hb.gemm_select_workspace(ta.desc, tb.desc, hb.KERNEL_FP16)
+    _check_product(hb, "c5 fp16", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, "fp16", rng)
+    C.zero_()
+    C = hb.gemm(ta, tb, out=C, kernel=hb.KERNEL_SCALED)
+    torch.cuda.synchronize()
+    _check_product(hb, "c5 scaled", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, True, rng, windows=False)
+    C.zero_()
     C = hb.gemm(ta, tb, out=C, kernel=INT8)
     torch.cuda.synchronize()
     # the int8 limb kernels convert block sums of up to 2.7e8 to FP32 (one rounding each) before scaling them

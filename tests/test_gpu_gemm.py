@@ -288,6 +288,17 @@ def test_gemm_wide_mantissas_as_two_limbs(hb, M, N, K, B, m, rounding):
     _run(hb, A, Bm, (1, B, m, rounding, 5), (B, 1, m, rounding, 6))
 
 
+@pytest.mark.parametrize("M,N,K,B,m,rounding", [
+    (100, 150, 640, 64, 12, 1), (130, 70, 1000, 32, 12, 0), (96, 96, 1024, 256, 12, 0), (70, 200, 1152, 0, 9, 0),
+    (200, 100, 1000, 128, 12, 1), (300, 260, 2048, 64, 10, 0), (100, 90, 16384, 64, 12, 0),
+])
+def test_gemm_wide_mantissas_on_the_fp16_instruction(hb, M, N, K, B, m, rounding):
+    """9..12-bit mantissas as FP16 numbers: block sums reach 64 * 2047^2 = 2.7e8 > 2^24 and are rounded inside the chain."""
+    A, Bm = _rand((M, K), M + 2 * K), _rand((K, N), N + 3 * K)
+    _run(hb, A, Bm, (1, B, m, rounding, 5), (B, 1, m, rounding, 6), partials=False, kernel=4)
+    _run(hb, A, Bm, (1, B, m, rounding, 5), (B, 1, m, rounding, 6), partials=False, kernel=4, beta=1.0)
+
+
 def test_gemm_wide_mantissas_extreme_values(hb):
     M, N, K = 64, 128, 512
     A = np.full((M, K), 2047.0, dtype=np.float32)
@@ -296,6 +307,8 @@ def test_gemm_wide_mantissas_extreme_values(hb):
     A[:, ::3] *= -1
     _run(hb, A, B, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0))
     _run(hb, A, np.abs(B), (1, 512, 12, 0, 0), (512, 1, 12, 0, 0))      # 512 * 2047^2 = 2.15e9 - the int32 limit
+    _run(hb, A, B, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False, kernel=4)
+    _run(hb, A, np.abs(B), (1, 512, 12, 0, 0), (512, 1, 12, 0, 0), partials=False, kernel=4)
 
 
 # ---- the block-scaled kernel (hbfp_gemm_select with HBFP_KERNEL_SCALED): 256 x 256 tiles, k-steps of 64
