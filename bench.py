@@ -50,10 +50,12 @@ ALG_BYTES_GEMM_C4 = 2 * 16 * 64 * 26624 + 4096 * 4096 * 4
 def _parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--preheat", type=int, default=60,
+                    help="untimed steps before the warm-up steps: the shader clock takes some 40 steps to come up from idle")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph instead of 12 separate launches")
+    ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph instead of 8 separate launches")
     ap.add_argument("--no-extra", action="store_true", help="skip the config 2 / 3 / 5 side measurements")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only matrix-instruction loops")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -102,26 +104,34 @@ def _linear_layer(torch, hbfp, synth):
     # each source matrix is converted into both of its operand layouts, stored and packed for the block-scaled kernel,
     # by one call that reads it once (hbfp_encode_packed)
     packed = {k: torch.empty(hbfp.pack_bytes(t.desc), dtype=torch.uint8, device="cuda") for k, t in enc.items()}
-    groups = [("encode_act", X, ["x_fwd", "x_wgrad"]), ("encode_act", dY, ["dy_dgrad", "dy_wgrad"]), ("encode_w", W, ["w_fwd", "w_dgrad"])]
-    assert all(hbfp.encode_packed_workspace([enc[k] for k in names]) == 0 for _, _, names in groups)
-    ws_packed = [torch.empty(max(hbfp.gemm_packed_workspace(enc[a].desc, enc[b].desc), 256), dtype=torch.uint8, device="cuda")
-                 for a, b in prods]
+    groups = {"x": ("encode_act", X, ["x_fwd", "x_wgrad"]), "dy": ("encode_act", dY, ["dy_dgrad", "dy_wgrad"]),
+              "w": ("encode_w", W, ["w_fwd", "w_dgrad"])}
+    assert all(hbfp.encode_packed_workspace([enc[k] for k in names]) == 0 for _, _, names in groups.values())
+    product = lambda i: (enc[prods[i][0]], packed[prods[i][0]], enc[prods[i][1]], packed[prods[i][1]])
+    ws_fwd = torch.empty(max(hbfp.gemm_packed_workspace(enc["x_fwd"].desc, enc["w_fwd"].desc), 256), dtype=torch.uint8, device="cuda")
+    ws_bwd = torch.empty(max(hbfp.gemm_packed_batch_workspace([(product(i)[0], product(i)[2]) for i in (1, 2)]), 256),
+                         dtype=torch.uint8, device="cuda")
+
+    def bracket(timer, name, fn):
+        if timer:
+            a, b = timer.region(name)
+            a.record()
+        fn()
+        if timer:
+            b.record()
+
+    def convert(timer, key):
+        name, src, names = groups[key]
+        bracket(timer, name, lambda: hbfp.encode_packed(src, [enc[k] for k in names], [packed[k] for k in names]))
 
     def step(timer=None):
-        for name, src, names in groups:
-            if timer:
-                a, b = timer.region(name)
-                a.record()
-            hbfp.encode_packed(src, [enc[k] for k in names], [packed[k] for k in names])
-            if timer:
-                b.record()
-        for i, (pa, pb) in enumerate(prods):
-            if timer:
-                a, b = timer.region("gemm")
-                a.record()
-            hbfp.gemm_packed(enc[pa], packed[pa], enc[pb], packed[pb], out=outs[i], workspace=ws_packed[i])
-            if timer:
-                b.record()
+        # the order of a training step: inputs and weights, the forward product, then the gradient that arrives from
+        # the layer above and the two backward products that wait for it, which share one launch
+        convert(timer, "x")
+        convert(timer, "w")
+        bracket(timer, "gemm", lambda: hbfp.gemm_packed(*product(0), out=outs[0], workspace=ws_fwd))
+        convert(timer, "dy")
+        bracket(timer, "gemm_pair", lambda: hbfp.gemm_packed_batch([product(1), product(2)], outs[1:], workspace=ws_bwd))
 
     flops_per_product = 2.0 * M * N * K
     return step, 3 * flops_per_product, flops_per_product, dict(M=M, N=N, K=K), outs
@@ -532,7 +542,7 @@ def main():
     torch.cuda.set_device(0)
 
     step, flops_step, flops_product, shape, outs = _linear_layer(torch, hbfp, synth)
-    for _ in range(args.warmup):
+    for _ in range(args.preheat + args.warmup):
         step()
     torch.cuda.synchronize()
     run_step = step
@@ -564,7 +574,8 @@ def main():
     torch.cuda.synchronize()
     # the same steps again with HIP events around every call, for the per-kernel figures
     timer = Timer(torch)
-    for _ in range(args.steps):
+    n_bracketed = min(args.steps, 100)
+    for _ in range(n_bracketed):
         step(timer)
     torch.cuda.synchronize()
     ms_step = t_begin.elapsed_time(t_end) / args.steps
@@ -576,9 +587,10 @@ def main():
     product_tops = flops_product / product_ms / 1e9
     # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
     limb_tflops = 4.0 * product_tops
-    enc_act_ms = timer.total_ms("encode_act") / args.steps
-    enc_w_ms = timer.total_ms("encode_w") / args.steps
-    gemm_step_ms = timer.total_ms("gemm") / args.steps
+    enc_act_ms = timer.total_ms("encode_act") / n_bracketed
+    enc_w_ms = timer.total_ms("encode_w") / n_bracketed
+    pair_ms = timer.total_ms("gemm_pair") / timer.count("gemm_pair")
+    gemm_step_ms = (timer.total_ms("gemm") + timer.total_ms("gemm_pair")) / n_bracketed
 
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
@@ -594,7 +606,8 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 mantissas as 4-bit limbs in FP6 (E2M3), block-scaled matrix instruction, FP32 accumulate", "data": "synthetic",
         "config": {"workload": "config 4: dense layer M=K=N=4096, BFP8, 1x24 activation blocks, 24x24 weight tiles, "
-                               "forward + data gradient + weight gradient, all six operand encodes included (3 conversion calls, 3 products)", **shape},
+                               "forward + data gradient + weight gradient, all six operand encodes included (3 conversion calls, 3 products: "
+                               "the forward one alone, the two backward ones in one launch)", "preheat_steps": args.preheat, **shape},
         "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
         "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_activations_x4": round(enc_act_ms, 4),
                                   "encode_weights_x2": round(enc_w_ms, 4)},
@@ -608,13 +621,15 @@ def main():
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(product_tops / INT8_PEAK_TOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
                      "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
-                     "algorithmic_ops_per_launch": flops_product,
+                     "algorithmic_ops_per_launch": flops_product, "backward_pair_launch_ms": round(pair_ms, 4),
                      "limb_products": {"achieved": round(limb_tflops, 1), "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s",
                                        "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
                                        "note": "4 exact limb products per 8-bit mantissa product, every one of them matrix-core work"},
-                     "note": "avg_launch_ms is the HIP-event time of one hbfp_gemm_packed call of the timed step on the launch stream: "
-                             "the product kernel plus the int8 stand-by kernel behind it (exits at once when every exponent is in "
-                             "range); the operands were packed by the conversion calls; the rocprofv3 summary lists each kernel"},
+                     "note": "avg_launch_ms is the HIP-event time of the hbfp_gemm_packed call of the step (the forward product) on the "
+                             "launch stream: the product kernel (grid 131072) plus the int8 stand-by kernel behind it (exits at once "
+                             "when every exponent is in range); backward_pair_launch_ms is the hbfp_gemm_packed_batch call: the same "
+                             "kernel over both backward products (grid 262144) plus two stand-by launches; the operands were packed "
+                             "by the conversion calls; the rocprofv3 summary lists each kernel"},
     }
     if not args.no_probe:
         out["roofline"]["matrix_probe"] = _matrix_probe(torch, hbfp)

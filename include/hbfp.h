@@ -394,6 +394,22 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
                      int64_t ldc, float beta, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_gemm_packed_batch: hbfp_gemm_batch for operands packed beforehand: up to HBFP_BATCH_MAX independent products
+ * (the data-gradient and weight-gradient products of a layer, Sec. 5.1, which both wait for the same gradient) in one
+ * launch of the block-scaled kernel, so that the output tiles of one product are stored while the next product's
+ * tiles are being multiplied.  Every product is bit for bit what hbfp_gemm_packed computes for it.
+ *   A, packed_a, B, packed_b, C, ldc   host arrays of n entries, each as the arguments of hbfp_gemm_packed
+ *   workspace                          hbfp_gemm_packed_batch_workspace bytes, 256-byte aligned
+ * Errors: as hbfp_gemm_packed for the first product that fails a check (nothing has been launched then);
+ * HBFP_ERR_FORMAT if the products do not all have the same limb counts (mantissas of up to 5, 6..9 or 10..12 bits,
+ * operand by operand).
+ */
+int hbfp_gemm_packed_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, size_t *bytes);
+int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const *packed_a, const hbfp_tensor *const *B,
+                           const void *const *packed_b, float *const *C, const int64_t *ldc, float beta, void *workspace,
+                           size_t ws_bytes, void *stream);
+
+/*
  * hbfp_gemm_partials: the fixed-point half of Eq. (2) alone, for checking:
  *     P[(i*N + j)*nblk + b] = sum_{k in block b} mA[i][k] * mB[j][k]     (int32, exact)
  * computed with the int8 matrix instruction (v_mfma_i32_32x32x32_i8) by the member of the int8 kernel family

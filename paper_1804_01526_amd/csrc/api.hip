@@ -803,6 +803,57 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
     return launch_gemm_i8(g, workspace, (hipStream_t)stream);
 }
 
+int hbfp_gemm_packed_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, size_t *bytes) {
+    if (!bytes || !A || !B || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
+    *bytes = 0;
+    for (int i = 0; i < n; ++i) {
+        size_t part = 0;
+        const int rc = hbfp_gemm_packed_workspace(A[i], B[i], &part);
+        if (rc != HBFP_OK) return rc;
+        *bytes += align256(part);
+    }
+    return HBFP_OK;
+}
+
+int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const *packed_a, const hbfp_tensor *const *B,
+                           const void *const *packed_b, float *const *C, const int64_t *ldc, float beta, void *workspace,
+                           size_t ws_bytes, void *stream) {
+    if (!A || !B || !C || !ldc || !packed_a || !packed_b || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
+    if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
+    GemmArgs g[HBFP_BATCH_MAX];
+    size_t part[HBFP_BATCH_MAX], need = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!A[i] || !B[i] || !C[i] || !packed_a[i] || !packed_b[i]) return HBFP_ERR_ARG;
+        if (((uintptr_t)packed_a[i] & 255) || ((uintptr_t)packed_b[i] & 255) || ((uintptr_t)C[i] & 3)) return HBFP_ERR_ARG;
+        int rc = check_pair(A[i], B[i]);
+        if (rc != HBFP_OK) return rc;
+        if (ldc[i] < B[i]->rows) return HBFP_ERR_ARG;
+        rc = hbfp_gemm_packed_workspace(A[i], B[i], &part[i]);
+        if (rc != HBFP_OK) return rc;
+        part[i] = align256(part[i]);
+        need += part[i];
+        g[i] = gemm_args(A[i], B[i]);
+        g[i].C = C[i];
+        g[i].ldc = ldc[i];
+        g[i].beta = beta;
+        if (!gemm_mx_possible(g[i])) return HBFP_ERR_ARG;
+        if ((A[i]->mant_bits > 8) != (A[0]->mant_bits > 8) || !mx_same_limbs(g[i], g[0])) return HBFP_ERR_FORMAT;
+    }
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int rc = launch_mx_products(n, g, packed_a, packed_b, s);
+    if (rc != HBFP_OK) return rc;
+    char *ws = (char *)workspace;
+    for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
+        g[i].run_a = (const int *)packed_a[i];
+        g[i].run_b = (const int *)packed_b[i];
+        rc = A[i]->mant_bits > 8 ? launch_gemm_limb(g[i], ws, s) : launch_gemm_i8(g[i], ws, s);
+        if (rc != HBFP_OK) return rc;
+        ws += part[i];
+    }
+    return HBFP_OK;
+}
+
 int hbfp_gemm_partials(const hbfp_tensor *A, const hbfp_tensor *B, int32_t *P,
                        void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !P || ((uintptr_t)P & 3)) return HBFP_ERR_ARG;

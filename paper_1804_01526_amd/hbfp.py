@@ -94,6 +94,9 @@ def _load():
     lib.hbfp_pack.argtypes = [T, vp, sz, vp]
     lib.hbfp_gemm_packed_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm_packed.argtypes = [T, vp, T, vp, vp, i64, ctypes.c_float, vp, sz, vp]
+    lib.hbfp_gemm_packed_batch_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(T), ctypes.POINTER(sz)]
+    lib.hbfp_gemm_packed_batch.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(vp), ctypes.POINTER(T), ctypes.POINTER(vp),
+                                           ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_partials.argtypes = [T, T, vp, vp, sz, vp]
     lib.hbfp_gemm_partials_window.argtypes = [T, T, i64, i64, i64, i64, vp, vp, sz, vp]
     lib.hbfp_gemm_f32_workspace.argtypes = [i32, i32, i64, i64, i64, F, F, ctypes.POINTER(sz)]
@@ -108,7 +111,7 @@ def _load():
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
     for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_encode_packed_workspace", "hbfp_encode_packed", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
-                 "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
+                 "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_packed_batch_workspace", "hbfp_gemm_packed_batch", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
         getattr(lib, name).restype = i32
     return lib
@@ -342,6 +345,30 @@ def gemm_packed(a: BfpTensor, packed_a: torch.Tensor, b: BfpTensor, packed_b: to
                                  _dev_ptr(out), out.stride(0), beta, _dev_ptr(workspace),
                                  0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_gemm_packed")
     return out
+
+
+def gemm_packed_batch_workspace(pairs) -> int:
+    """pairs: sequence of (A, B), each a BfpTensor or a TensorDesc."""
+    n = ctypes.c_size_t(0)
+    a, b = _desc_array([p[0] for p in pairs]), _desc_array([p[1] for p in pairs])
+    _check(_lib.hbfp_gemm_packed_batch_workspace(len(pairs), a, b, ctypes.byref(n)), "hbfp_gemm_packed_batch_workspace")
+    return int(n.value)
+
+
+def gemm_packed_batch(products, outs, beta: float = 0.0, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_gemm_packed_batch: outs[i] (+)= A[i] . B[i]^T; products: sequence of (A, packed A, B, packed B)."""
+    n = len(products)
+    a, b = _desc_array([p[0] for p in products]), _desc_array([p[2] for p in products])
+    pa = (ctypes.c_void_p * n)(*[p[1].data_ptr() for p in products])
+    pb = (ctypes.c_void_p * n)(*[p[3].data_ptr() for p in products])
+    for o in outs:
+        assert o.is_cuda and o.dtype == torch.float32 and o.stride(1) == 1
+    c = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+    ld = (ctypes.c_int64 * n)(*[o.stride(0) for o in outs])
+    workspace = _workspace(gemm_packed_batch_workspace([(p[0], p[2]) for p in products]), outs[0].device, workspace)
+    _check(_lib.hbfp_gemm_packed_batch(n, a, pa, b, pb, c, ld, beta, _dev_ptr(workspace),
+                                       0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_gemm_packed_batch")
+    return outs
 
 
 def gemm_partials(a: BfpTensor, b: BfpTensor, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

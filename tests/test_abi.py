@@ -295,6 +295,40 @@ def test_gemm_batch_validation():
     assert hbfp.gemm_batch_workspace([q, q, q12, q12]) == 2 * alone + 2 * hbfp.gemm_workspace(q12[0], q12[1])
 
 
+def test_gemm_packed_batch_validation():
+    """hbfp_gemm_packed_batch: every check happens before the launch."""
+    lib = hbfp._lib
+    fake = ctypes.c_void_p(0x1000)
+
+    def desc(m, rows, cols, axis, br, bc):
+        d = hbfp.plan(hbfp.make_format(m, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    def call(pairs, n=None, packed=0x4000, c=0x3000, ldc=None, beta=0.0, ws=fake, ws_bytes=1 << 30):
+        k = len(pairs)
+        n = k if n is None else n
+        a, b = hbfp._desc_array([p[0] for p in pairs]), hbfp._desc_array([p[1] for p in pairs])
+        pa, pb = (ctypes.c_void_p * k)(*[packed] * k), (ctypes.c_void_p * k)(*[0x8000] * k)
+        cs = (ctypes.c_void_p * k)(*[c] * k)
+        ld = (ctypes.c_int64 * k)(*(ldc or [p[1].rows for p in pairs]))
+        return lib.hbfp_gemm_packed_batch(n, a, pa, b, pb, cs, ld, beta, ws, ws_bytes, None)
+
+    p8 = (desc(8, 128, 256, 1, 1, 24), desc(8, 256, 64, 0, 24, 1))
+    p4 = (desc(4, 128, 256, 1, 1, 24), desc(4, 256, 64, 0, 24, 1))
+    assert call([p8] * 5) == hbfp.ERR_ARG and call([p8], n=0) == hbfp.ERR_ARG
+    assert call([p8, p8], packed=0x4010) == hbfp.ERR_ARG and call([p8, p8], packed=0) == hbfp.ERR_ARG
+    assert call([p8, p8], c=0x3001) == hbfp.ERR_ARG and call([p8, p8], ldc=[64, 63]) == hbfp.ERR_ARG
+    assert call([p8, p8], beta=0.5) == hbfp.ERR_ARG
+    assert call([p8, p4]) == hbfp.ERR_FORMAT
+    assert call([p8, (p8[0], desc(8, 256, 64, 0, 32, 1))]) != hbfp.OK            # blocks disagree
+    need = hbfp.gemm_packed_batch_workspace([p8, p8])
+    assert need == 2 * ((hbfp.gemm_packed_workspace(*p8) + 255) // 256 * 256)
+    if need:
+        assert call([p8, p8], ws_bytes=need - 256) == hbfp.ERR_WORKSPACE
+        assert call([p8, p8], ws=None) == hbfp.ERR_WORKSPACE
+
+
 def test_gemm_bfp_validation():
     """hbfp_gemm_bfp: the output plan must be that of an A->rows x B->rows matrix; the workspace always holds the FP32
     product (for the int8 kernels that stand by, or as the route to the conversion kernels) plus the product's own

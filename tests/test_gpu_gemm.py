@@ -621,6 +621,47 @@ def test_packed_operands_outside_the_scale_range_and_repacking(hb):
         assert rel_fro(C.cpu().numpy(), _oracle_product(A, W, fa, fb)) <= TOL
 
 
+def test_packed_batch_equals_the_products_one_by_one(hb):
+    """hbfp_gemm_packed_batch: products of different shapes in one launch, one of them with an operand outside the
+    scale range (its int8 stand-by computes it), bit for bit what hbfp_gemm_packed returns for each; beta = 1 too;
+    products whose limb counts differ are refused."""
+    m, blk = 8, 24
+    shapes = [(300, 270, 700), (130, 520, 330), (512, 256, 1024), (70, 90, 240)]
+    prods, want, srcs = [], [], []
+    for i, (M, N, K) in enumerate(shapes):
+        A, B = _rand((M, K), 40 + i), (_rand((K, N), 50 + i, 1) * 0.1).astype(np.float32)
+        if i == 1:
+            B[24:48, 5] = (B[24:48, 5].astype(np.float64) * 2.0 ** -126).astype(np.float32)
+        ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(m, 1, blk))
+        tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(m, blk, 1))
+        prods.append((ta, hb.pack(ta), tb, hb.pack(tb)))
+        want.append(hb.gemm_packed(*prods[-1]))
+        srcs.append((A, B))
+    torch.cuda.synchronize()
+    for n in (1, 2, 4):
+        print(f"[case] packed batch of {n}", flush=True)
+        outs = [torch.full_like(w, float("nan")) for w in want[:n]]
+        hb.gemm_packed_batch(prods[:n], outs)
+        torch.cuda.synchronize()
+        for o, w in zip(outs, want):
+            assert torch.equal(o, w)
+    for (A, B), w in zip(srcs, want):
+        assert rel_fro(w.cpu().numpy(), _oracle_product(A, B, (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
+    base = [torch.from_numpy(_rand(tuple(w.shape), 60 + i, 1)).cuda() for i, w in enumerate(want)]
+    outs = [b.clone() for b in base]
+    hb.gemm_packed_batch(prods, outs, beta=1.0)
+    one = [hb.gemm_packed(*p, out=b.clone(), beta=1.0) for p, b in zip(prods, base)]
+    torch.cuda.synchronize()
+    for o, w in zip(outs, one):
+        assert torch.equal(o, w)
+    # a 4-bit product has one limb per mantissa, these have two
+    t4a = hb.encode(torch.from_numpy(srcs[0][0]).cuda(), 1, hb.make_format(4, 1, blk))
+    t4b = hb.encode(torch.from_numpy(srcs[0][1]).cuda(), 0, hb.make_format(4, blk, 1))
+    with pytest.raises(hb.HbfpError) as e:
+        hb.gemm_packed_batch([prods[0], (t4a, hb.pack(t4a), t4b, hb.pack(t4b))], [torch.empty_like(want[0]), torch.empty_like(want[0])])
+    assert e.value.status == hb.ERR_FORMAT
+
+
 def test_packed_product_in_a_replayed_graph(hb):
     """Weights packed outside, activations encoded and packed inside a captured graph; every replay (new activations
     in the same buffers, eager work and synchronisation between replays) must equal the eager result.  One replay
