@@ -56,15 +56,30 @@ __device__ __forceinline__ uint32_t sr_small_bits(uint32_t Eb, int m) {
     const int t = (int)Eb - 7 - m;                 // elements whose exponent field (at least 1) is below t vanish
     return t <= 1 ? 0u : (uint32_t)t << 23;
 }
-__device__ __forceinline__ int quant_sr(float x, int neg_unit_exp, uint32_t small_bits, uint32_t h) {
+// the rounded magnitude, at most 2^(m-1) - 1
+__device__ __forceinline__ uint32_t quant_sr_magnitude(float x, int neg_unit_exp, uint32_t small_bits, uint32_t h) {
     const uint32_t bits = __float_as_uint(x);
     const float ax = (bits & 0x7fffffffu) < small_bits ? 0.0f : __builtin_fabsf(x);
     const float y = __builtin_amdgcn_ldexpf(ax, neg_unit_exp);
     const uint32_t whole = (uint32_t)y;                                                // truncation: y >= 0
     const uint32_t frac = (uint32_t)__builtin_amdgcn_ldexpf(__builtin_amdgcn_fractf(y), 32);
-    const uint32_t q = whole + ((frac + h) < h ? 1u : 0u);
-    const uint32_t sgn = (uint32_t)((int32_t)bits >> 31);
+    return whole + ((frac + h) < h ? 1u : 0u);
+}
+__device__ __forceinline__ int quant_sr(float x, int neg_unit_exp, uint32_t small_bits, uint32_t h) {
+    const uint32_t q = quant_sr_magnitude(x, neg_unit_exp, small_bits, h);
+    const uint32_t sgn = (uint32_t)((int32_t)__float_as_uint(x) >> 31);
     return (int)((q ^ sgn) - sgn);
+}
+// Two magnitudes (each below 2^15) with the signs of two floats, as two 16-bit two's-complement halves of one word:
+// the sign words come from the floats' upper halves with one byte permute and one packed shift, and the conditional
+// negation (m ^ s) - s runs on both halves at once.
+typedef short v2s16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t signed_pair16(uint32_t mag0, uint32_t mag1, float x0, float x1) {
+    const uint32_t mags = __builtin_amdgcn_perm(mag1, mag0, 0x05040100u);                                       // mag0.lo16, mag1.lo16
+    const uint32_t tops = __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);        // x0.hi16, x1.hi16
+    const v2s16 s = __builtin_bit_cast(v2s16, tops) >> (short)15;
+    const v2s16 r = __builtin_bit_cast(v2s16, mags ^ __builtin_bit_cast(uint32_t, s)) - s;
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // The hash in two parts.  Its first three steps (the xorshift triple) are linear over GF(2), so the part of the

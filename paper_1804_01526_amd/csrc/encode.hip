@@ -33,8 +33,12 @@ __device__ __forceinline__ uint32_t group_max(uint32_t v) {
     return v;
 }
 
+// low bytes of four values into one word: two byte permutes gather pairs, the third joins them (the mask-shift-or
+// form takes seven instructions)
 __device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
-    return (uint32_t)(a & 0xff) | ((uint32_t)(b & 0xff) << 8) | ((uint32_t)(c & 0xff) << 16) | ((uint32_t)d << 24);
+    const uint32_t ab = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);    // bytes: a.0, b.0, 0, 0
+    const uint32_t cd = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(cd, ab, 0x05040100u);                                    // ab.0, ab.1, cd.0, cd.1
 }
 __device__ __forceinline__ uint32_t pack2_i16(int a, int b) {
     return (uint32_t)(a & 0xffff) | ((uint32_t)b << 16);
@@ -113,6 +117,7 @@ struct RowParams {
     int32_t nseg;       // segments per row = ceil(chunks / lanes-per-row)
     int32_t vec_ok;     // 16-byte vector loads are aligned
     int32_t sr_aligned; // the stochastic-rounding counter of every chunk's first element is a multiple of 8
+    int32_t one_row;    // every workgroup's chunks lie in one row and 32-bit offsets reach anywhere inside a row
     uint32_t s0, s1;
     // GP = 0 (second pass of the two-pass conversion): the largest magnitude of every exponent block has been
     // computed already, table[(row / rblock) * ntk + block / kshare]; a stored block is gp chunks long
@@ -134,6 +139,20 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     // straddle rows; rows need not be a power of two long.
     const uint64_t total = (uint64_t)p.R * (uint64_t)p.chunks;
     const uint64_t g0 = (uint64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    // Long rows (a workgroup's chunks inside one row, the usual case): the row and everything that is a multiple of it
+    // stay on the scalar unit and a lane adds 32-bit offsets; the flat 64-bit index space is for the general case.
+    // Only stochastic rounding, which is bound by its vector instructions, takes this path (nearest-even rounding
+    // waits for memory, and its short workgroups lose more to the longer scalar prologue than they gain: 60 against 57 us
+    // on 2^26 elements).
+    const bool one_row = !CONV && GP != 0 && ROUND == 1 && p.one_row;
+    uint64_t wg_row = 0;
+    uint32_t wg_cl = 0;
+    if (one_row) {
+        const uint64_t gw = (uint64_t)blockIdx.x * (kThreads * U);
+        wg_row = p.lpr_log2 >= 0 ? gw >> p.lpr_log2 : gw / (uint64_t)(uint32_t)p.chunks;
+        wg_cl = (uint32_t)(gw - wg_row * (uint64_t)(uint32_t)p.chunks);
+        if (wg_row >= (uint64_t)p.R) return;         // the grid is rounded up to whole workgroups of four chunks per thread
+    }
 
     float v[U][8];
     int n[U], cl[U];
@@ -141,6 +160,29 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
     int64_t at[U];        // CONV with one exponent per image: index of the chunk's first value in the image tensor, else -1
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        if (one_row) {
+            cl[u] = (int)(wg_cl + threadIdx.x + u * kThreads);
+            rows[u] = (int64_t)wg_row;
+            const uint32_t blk = (uint32_t)cl[u] / (uint32_t)(GP ? GP : 1), j = (uint32_t)cl[u] % (uint32_t)(GP ? GP : 1);
+            const uint32_t kb = blk * (uint32_t)p.kblock, k0 = kb + 8u * j;     // K < 2^30 here
+            uint32_t cnt = 0;
+            if (blk < (uint32_t)p.nblk) {
+                const uint32_t K = (uint32_t)p.K, blen = K - kb < (uint32_t)p.kblock ? K - kb : (uint32_t)p.kblock;
+                cnt = blen > 8u * j ? (blen - 8u * j < 8u ? blen - 8u * j : 8u) : 0u;
+            }
+            n[u] = (int)cnt;
+            const char *s = reinterpret_cast<const char *>(p.src + wg_row * (uint64_t)p.ld) + (cnt ? k0 * 4u : 0u);
+            if (cnt == 8) {
+                const float4 a = *reinterpret_cast<const float4 *>(s);
+                const float4 b = *reinterpret_cast<const float4 *>(s + 16);
+                v[u][0] = a.x; v[u][1] = a.y; v[u][2] = a.z; v[u][3] = a.w;
+                v[u][4] = b.x; v[u][5] = b.y; v[u][6] = b.z; v[u][7] = b.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = ((uint32_t)e < cnt) ? reinterpret_cast<const float *>(s)[e] : 0.0f;
+            }
+            continue;
+        }
         const uint64_t g = g0 + (uint64_t)u * kThreads;
         const bool in = g < total;
         int64_t row;
@@ -197,11 +239,11 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             for (int e = 0; e < 8; ++e) v[u][e] = (e < cnt) ? s[e] : 0.0f;
         }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
+    // Second half, per chunk: exponent, rounding, stores.  It is expanded twice, once with the row as the workgroup's
+    // (scalar) value and once with the lane's, so that in the long-row case every multiple of the row stays scalar.
+    auto finish = [&](const int u, const int64_t row, const bool row_is_uniform) {
         const int blk = GP ? cl[u] / (GP ? GP : 1) : (int)div_magic((uint32_t)cl[u], p.dGp);
         const int j = cl[u] - blk * (GP ? GP : p.gp);
-        const int64_t row = rows[u];
         uint32_t amax = 0;
         if (GP) {
 #pragma unroll
@@ -212,10 +254,14 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
         }
         const uint32_t Eb = block_exponent<ROUND>(amax, p.m);
         int q[8];
+        uint32_t pairs[4];            // the same mantissas as 16-bit halves, where the rounding step produces them that way
+        bool have_pairs = false;
         // stochastic rounding draws by logical index: of the (lowered) source matrix, or, when a whole image shares one
         // exponent, of the image tensor: a pixel is then rounded the same way in every window it appears in, as if
         // the image had been converted once and lowered afterwards
-        uint64_t idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
+        uint64_t idx0;
+        if (row_is_uniform) idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint32_t)(blk * p.kblock + 8 * j);
+        else idx0 = (uint64_t)row * (uint64_t)p.src_cols + (uint64_t)((int64_t)blk * p.kblock + 8 * j);
         if (CONV && GP == 0 && at[u] >= 0) idx0 = (uint64_t)at[u];
         if (ROUND == 1 && p.sr_aligned) {
             // the eight counters are idx0 | e: the xorshift steps of the hash, linear over GF(2), run once on the common
@@ -223,8 +269,13 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             const uint32_t common = sr_triple((uint32_t)idx0 ^ p.s0), high = (uint32_t)(idx0 >> 32) ^ p.s1;
             const uint32_t small = sr_small_bits(Eb, p.m);
             const int unit = 125 + p.m - (int)Eb;
+            uint32_t mag[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) q[e] = quant_sr(v[u][e], unit, small, sr_hash_tail(common ^ sr_triple((uint32_t)e), high));
+            for (int e = 0; e < 8; ++e) mag[e] = quant_sr_magnitude(v[u][e], unit, small, sr_hash_tail(common ^ sr_triple((uint32_t)e), high));
+            // signs two at a time; the pairs are the stored 16-bit mantissas, or give their low bytes to the 8-bit ones
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) pairs[e / 2] = signed_pair16(mag[e], mag[e + 1], v[u][e], v[u][e + 1]);
+            have_pairs = true;
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -233,31 +284,49 @@ __global__ __launch_bounds__(kThreads) void enc_row_kernel(const RowParams p) {
             }
         }
         if (row >= 0) {
+            // destination of this chunk's mantissas: row base (uniform in the long-row case) plus the lane's chunk
+            uint8_t *mrow = p.mant + row * p.kpad * (WIDE ? 2 : 1), *erow = p.exps + row * p.exp_ld;
             if (!WIDE) {
                 uint2 o;
-                o.x = pack4_i8(q[0], q[1], q[2], q[3]);
-                o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                if (have_pairs) {
+                    o.x = __builtin_amdgcn_perm(pairs[1], pairs[0], 0x06040200u);     // the low byte of each half
+                    o.y = __builtin_amdgcn_perm(pairs[3], pairs[2], 0x06040200u);
+                } else {
+                    o.x = pack4_i8(q[0], q[1], q[2], q[3]);
+                    o.y = pack4_i8(q[4], q[5], q[6], q[7]);
+                }
                 // streaming stores: the mantissas are not read again by this kernel (about 1 % on a 2^26-element encode)
                 typedef unsigned v2u __attribute__((ext_vector_type(2)));
                 const v2u o2 = {o.x, o.y};
-                __builtin_nontemporal_store(o2, reinterpret_cast<v2u *>(p.mant + row * p.kpad + (int64_t)cl[u] * 8));
+                __builtin_nontemporal_store(o2, reinterpret_cast<v2u *>(mrow + (uint32_t)cl[u] * 8u));
             } else {
                 uint4 o;
-                o.x = pack2_i16(q[0], q[1]);
-                o.y = pack2_i16(q[2], q[3]);
-                o.z = pack2_i16(q[4], q[5]);
-                o.w = pack2_i16(q[6], q[7]);
+                if (have_pairs) {
+                    o.x = pairs[0]; o.y = pairs[1]; o.z = pairs[2]; o.w = pairs[3];
+                } else {
+                    o.x = pack2_i16(q[0], q[1]);
+                    o.y = pack2_i16(q[2], q[3]);
+                    o.z = pack2_i16(q[4], q[5]);
+                    o.w = pack2_i16(q[6], q[7]);
+                }
                 typedef unsigned v4u __attribute__((ext_vector_type(4)));
                 const v4u o4 = {o.x, o.y, o.z, o.w};
-                __builtin_nontemporal_store(o4, reinterpret_cast<v4u *>(p.mant + (row * p.kpad + (int64_t)cl[u] * 8) * 2));
+                __builtin_nontemporal_store(o4, reinterpret_cast<v4u *>(mrow + (uint32_t)cl[u] * 16u));
             }
             if (j == 0) {
-                uint8_t *e = p.exps + row * p.exp_ld;
+                uint8_t *e = erow;
                 e[blk] = blk < p.nblk ? (uint8_t)Eb : (uint8_t)1;
                 if (blk == p.nb_stored - 1)
                     for (int64_t b = p.nb_stored; b < p.exp_ld; ++b) e[b] = 1;
             }
         }
+    };
+    if (one_row) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) finish(u, (int64_t)wg_row, true);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) finish(u, rows[u], false);
     }
 }
 
@@ -905,6 +974,11 @@ int launch_encode_row_fused(const float *src, const EncodeGeom &g, void *mant, u
     p.nseg = 0;
     p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
     p.sr_aligned = ((g.src_cols % 8) == 0 && (g.kblock % 8) == 0) ? 1 : 0;
+    {
+        const int per_wg = kThreads * 2;                                 // chunks of a stochastic-rounding workgroup (launch_row_t)
+        p.one_row = (g.rounding && p.vec_ok && g.rblock <= 1 && p.chunks % per_wg == 0 && g.K < ((int64_t)1 << 30) && g.kpad < ((int64_t)1 << 30) &&
+                     g.exp_ld < ((int64_t)1 << 31)) ? 1 : 0;
+    }
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
     p.table = nullptr;
@@ -1046,6 +1120,7 @@ int launch_encode_im2col(const float *x, const hbfp_conv2d &c, int64_t ho, int64
     p.nseg = 0;
     p.vec_ok = (((uintptr_t)x & 15) == 0) ? 1 : 0;                      // C is a multiple of 8
     p.sr_aligned = 0;
+    p.one_row = 0;
     p.s0 = g.seed_lo;
     p.s1 = g.seed_hi;
     p.table = table;
@@ -1200,6 +1275,7 @@ int launch_encode_generic(const float *src, const EncodeGeom &g, void *mant, uin
         p.nseg = 0;
         p.vec_ok = (((uintptr_t)src & 15) == 0 && (g.ld % 4) == 0 && (g.kblock % 4) == 0) ? 1 : 0;
         p.sr_aligned = ((g.src_cols % 8) == 0 && (g.kblock % 8) == 0) ? 1 : 0;
+        p.one_row = 0;
         p.s0 = g.seed_lo;
         p.s1 = g.seed_hi;
         p.table = tile_amax;

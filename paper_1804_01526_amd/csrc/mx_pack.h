@@ -64,8 +64,8 @@ __device__ __forceinline__ uint32_t dense_block_of(uint32_t j, int ob) {
 }
 // the code of twice the value of each byte's code: normal codes (>= 8) gain one in their exponent field (+ 8),
 // subnormal codes (< 8) double as integers (7 -> 14 is the normal code of 14 / 8)
-// 0xff in every byte whose bit 0 is set in `ones` (a value of 0 or 1 per byte), without the 32-bit multiplication by
-// 255 (a quarter-rate instruction, and what the compiler makes of (ones << 8) - ones)
+// 0xff in every byte whose bit 0 is set in `ones` (a value of 0 or 1 per byte) in two instructions; written as
+// (ones << 8) - ones the compiler turns it back into a 32-bit multiplication by 255 with its constant in a register
 __device__ __forceinline__ uint32_t byte_mask(uint32_t ones) { return (0x80808080u - ones) ^ 0x80808080u; }
 __device__ __forceinline__ uint32_t e2m3_double_bytes(uint32_t c) {
     const uint32_t normal = ((c + 0x78787878u) >> 7) & 0x01010101u;   // 1 in the bytes that hold a code >= 8
