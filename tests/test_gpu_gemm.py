@@ -299,6 +299,28 @@ def test_gemm_wide_mantissas_on_the_fp16_instruction(hb, M, N, K, B, m, rounding
     _run(hb, A, Bm, (1, B, m, rounding, 5), (B, 1, m, rounding, 6), partials=False, kernel=4, beta=1.0)
 
 
+def test_fp16_instruction_wide_exponent_range_and_few_stages(hb):
+    """The FP16 route with rows 2^+-20 apart, products near the ends of the FP32 range (results that underflow gradually,
+    R15), every start-up and drain path of the LDS ring, blocks of 32 / 64 / 128 / 512, split-K with beta = 1."""
+    rng = np.random.default_rng(18)
+    M, N, K = 96, 80, 512
+    A = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * np.exp2(rng.integers(-20, 21, size=(K, 1)))).astype(np.float32)
+    for blk in (32, 64, 128, 512):
+        _run(hb, A, B, (1, blk, 12, 0, 0), (blk, 1, 12, 0, 0), partials=False, kernel=4)
+    A2 = (A.astype(np.float64) * 2.0 ** -60).astype(np.float32)
+    B2 = (B.astype(np.float64) * 2.0 ** 55).astype(np.float32)
+    _run(hb, A2, B2, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False, kernel=4)
+    A3 = (A.astype(np.float64) * 2.0 ** -70).astype(np.float32)
+    B3 = (B.astype(np.float64) * 2.0 ** -60).astype(np.float32)          # products around 2^-130: subnormal results
+    _run(hb, A3, B3, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False, kernel=4)
+    for K2 in (64, 128, 192, 320, 576):
+        _run(hb, _rand((70, K2), K2 + 12), _rand((K2, 150), K2 + 64), (1, 64, 10, 1, 9), (64, 1, 10, 1, 10), partials=False, kernel=4)
+    A4, B4 = _rand((100, 16384), 91, 2), _rand((16384, 90), 92, 2)
+    _run(hb, A4, B4, (1, 64, 12, 0, 0), (64, 1, 12, 0, 0), partials=False, kernel=4, beta=1.0)
+    _run(hb, A4, B4, (1, 1024, 9, 0, 0), (1024, 1, 9, 0, 0), partials=False, kernel=4)
+
+
 def test_gemm_wide_mantissas_extreme_values(hb):
     M, N, K = 64, 128, 512
     A = np.full((M, K), 2047.0, dtype=np.float32)
