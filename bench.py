@@ -312,7 +312,24 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                                            "TOPS_kernel": round(flops / ms_k / 1e9, 1),
                                            "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1),
                                            "note": "dX directly (51 MB), no lowered gradient and no scatter-add"}
-    del ta, tb, out, ws, img, Wd, dimg
+    del ta, tb, out, ws
+    # ... and the same data gradient with the gather in the product: the gradient image converted once (12.8 MB)
+    d2 = dY.view(-1, 128)
+    ti, tf = hbfp.alloc(row, 100352, 128, 1), hbfp.encode(Wd, 0, col)
+    out = torch.empty((100352, 128), dtype=torch.float32, device="cuda")
+    wsc = torch.empty(hbfp.gemm_conv2d_workspace(ti.desc, conv, tf.desc), dtype=torch.uint8, device="cuda")
+
+    def conv_dgrad():
+        hbfp.encode(d2, 1, row, out=ti)
+        hbfp.encode(Wd, 0, col, out=tf)
+        hbfp.gemm_conv2d(ti, conv, tf, out=out, workspace=wsc)
+
+    ms_all = _time_call(torch, conv_dgrad, reps)
+    ms_k = _time_call(torch, lambda: hbfp.gemm_conv2d(ti, conv, tf, out=out, workspace=wsc), reps)
+    res["c3_dgrad_conv2d_gather_in_the_product"] = {"gemm_ms": round(ms_k, 4), "whole_data_gradient_ms": round(ms_all, 4),
+                                                    "TOPS_kernel": round(flops / ms_k / 1e9, 1),
+                                                    "TOPS_incl_encode": round(flops / ms_all / 1e9, 1)}
+    del ti, tf, out, wsc, img, Wd, dimg
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the
     # FP16 matrix instruction on mantissas widened to FP16)
