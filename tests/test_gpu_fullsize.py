@@ -96,7 +96,8 @@ def _check_product(hb, name, ta, tb, oa, ob, fa, fb, C, rows, kernel_is_scaled, 
 
 def test_config4_step_as_the_benchmark_runs_it(hb):
     """The three products of config 4 from operands converted and packed by hbfp_encode_packed (one call per FP32
-    matrix) and multiplied by hbfp_gemm_packed; then the forward product once more on the int8 kernels."""
+    matrix) and multiplied by hbfp_gemm_packed (forward) and hbfp_gemm_packed_batch (both backward products in one launch);
+    then the forward product once more on the int8 kernels."""
     import synth
     X, W, dY = synth.c4_linear()
     rng = np.random.default_rng(5)
@@ -124,11 +125,17 @@ def test_config4_step_as_the_benchmark_runs_it(hb):
     cases = (("c4 fwd", x_f, px_f, w_f, pw_f, oX_r, oW, act_r, tile, None, None),
              ("c4 dgrad", d_d, pd_d, w_d, pw_d, oD_r, T(oW), act_r, tile, None, oW),
              ("c4 wgrad", x_w, px_w, d_w, pd_w, T(oX_c), oD_c, act_r, act_c, oX_c, None))
-    for name, a, pa, b, pb, oa, ob, fa, fb, sa, sb in cases:
-        C = hb.gemm_packed(a, pa, b, pb)
-        torch.cuda.synchronize()
+    # as in the benchmark's step: the forward product alone, both backward products in one launch
+    outs = [hb.gemm_packed(x_f, px_f, w_f, pw_f)]
+    outs += hb.gemm_packed_batch([(d_d, pd_d, w_d, pw_d), (x_w, px_w, d_w, pd_w)],
+                                 [torch.full((4096, 4096), float("nan"), device="cuda") for _ in range(2)])
+    torch.cuda.synchronize()
+    for (name, a, pa, b, pb, oa, ob, fa, fb, sa, sb), C in zip(cases, outs):
         _check_product(hb, name, a, b, oa, ob, fa, fb, C, rows, True, rng, src_a=sa, src_b=sb)
-        del C
+    one = hb.gemm_packed(d_d, pd_d, w_d, pw_d)
+    torch.cuda.synchronize()
+    assert torch.equal(one, outs[1])                       # the shared launch changes no bit
+    del outs, one
     C = hb.gemm(x_f, w_f, kernel=INT8)
     torch.cuda.synchronize()
     _check_product(hb, "c4 fwd int8", x_f, w_f, oX_r, oW, act_r, tile, C, rows, False, rng, windows=False)
