@@ -559,9 +559,21 @@ def main():
     torch.cuda.set_device(0)
 
     step, flops_step, flops_product, shape, outs = _linear_layer(torch, hbfp, synth)
-    for _ in range(args.preheat + args.warmup):
+    # the first steps after idle, timed for the record (the shader clock is still coming up), then the rest of the
+    # untimed steps
+    for _ in range(3):
         step()
     torch.cuda.synchronize()
+    c_begin, c_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_from_idle = max(0, min(20, args.preheat - 3))
+    c_begin.record()
+    for _ in range(n_from_idle):
+        step()
+    c_end.record()
+    for _ in range(max(0, args.preheat - 3 - n_from_idle) + args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ms_from_idle = c_begin.elapsed_time(c_end) / n_from_idle if n_from_idle else None
     run_step = step
     if args.graph:
         # one HIP graph of the launches of a step (no memset nodes: the library clears nothing with
@@ -626,6 +638,7 @@ def main():
                                "forward + data gradient + weight gradient, all six operand encodes included (3 conversion calls, 3 products: "
                                "the forward one alone, the two backward ones in one launch)", "preheat_steps": args.preheat, **shape},
         "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
+        "ms_per_step_first_steps_after_idle": None if ms_from_idle is None else round(ms_from_idle, 4),
         "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_activations_x4": round(enc_act_ms, 4),
                                   "encode_weights_x2": round(enc_w_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
