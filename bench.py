@@ -53,7 +53,7 @@ def _parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--preheat", type=int, default=60,
-                    help="untimed steps before the warm-up steps: the shader clock takes some 40 steps to come up from idle")
+                    help="untimed steps before the warm-up steps: after idle the chip's power management needs some 50 steps to settle")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--graph", action="store_true", help="replay each step as one HIP graph instead of 8 separate launches")
     ap.add_argument("--no-extra", action="store_true", help="skip the config 2 / 3 / 5 side measurements")
@@ -559,7 +559,8 @@ def main():
     torch.cuda.set_device(0)
 
     step, flops_step, flops_product, shape, outs = _linear_layer(torch, hbfp, synth)
-    # the first steps after idle, timed for the record (the shader clock is still coming up), then the rest of the
+    # the first steps after idle, timed for the record (the power management has not settled: by the kernel trace the
+    # product kernel takes 126 us at first, 141-146 us for a few steps, then falls to 122 us), then the rest of the
     # untimed steps
     for _ in range(3):
         step()
