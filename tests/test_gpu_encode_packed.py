@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from oracle import ref
-from tests.util import rel_fro, unpack
+from tests.util import random_cases, rel_fro, unpack
 
 pytestmark = pytest.mark.gpu
 
@@ -91,6 +91,26 @@ def test_single_outputs_stochastic_rounding_and_narrow_mantissas(hb):
                  [(24, 24, 4, 1, 9, 1)]):
         print(f"[encode_packed] {spec}", flush=True)
         _check_against_separate_calls(hb, x, spec)
+
+
+@pytest.mark.parametrize("case", random_cases(12))
+def test_random_shapes_formats_and_value_ranges(hb, case):
+    """Random sizes (ragged in both directions, down to a single tile), one or two outputs, 1-D blocks or tiles in either
+    orientation, 4..8-bit mantissas, either rounding, values spread over 1 to 9 binades: stored operand, limb planes and
+    mark equal to the separate conversion and pack calls, and the stored operand equal to the oracle's."""
+    rng = np.random.default_rng(1000 + case)
+    rows, cols = int(rng.integers(1, 700)), 4 * int(rng.integers(1, 175))
+    x = _rand((rows, cols), 2000 + case, spread=int(rng.integers(0, 5)))
+    if rng.integers(0, 3) == 0:
+        x[:, : cols // 3] = 0.0                                     # whole zero blocks
+    rounding = int(rng.integers(0, 2))
+    m = int(rng.choice([8, 8, 8, 7, 6, 5, 4]))
+    m2 = m if m > 5 else int(rng.choice([4, 5]))                   # both outputs need the same limb count
+    kinds = [(1, 24, 1), (24, 1, 0), (24, 24, 0), (24, 24, 1)]
+    picks = rng.choice(len(kinds), size=int(rng.integers(1, 3)), replace=False)
+    specs = [(kinds[k][0], kinds[k][1], m if i == 0 else m2, rounding, 50 + i, kinds[k][2]) for i, k in enumerate(picks)]
+    print(f"[encode_packed] case {case}: {rows}x{cols} {specs}", flush=True)
+    _check_against_separate_calls(hb, x, specs)
 
 
 def test_heavy_tails_and_zero_blocks_mark_the_same_operands(hb):
