@@ -146,6 +146,7 @@ GemmArgs gemm_args(const hbfp_tensor *A, const hbfp_tensor *B) {
     g.nblk = A->nblk;
     g.kbp = A->kblock_pad;
     g.kblock = A->kblock;
+    g.kdim = A->kdim;
     g.mA = A->mant_bits;
     g.mB = B->mant_bits;
     return g;
@@ -338,6 +339,7 @@ static int pack_one(const hbfp_tensor *t, void *packed, hipStream_t s) {
     g.kbp = t->kblock_pad;
     g.kblock = t->kblock;
     g.nblk = t->nblk;
+    g.kdim = t->kdim;
     g.mA = g.mB = t->mant_bits;
     return launch_mx_pack(g, packed, nullptr, s);
 }

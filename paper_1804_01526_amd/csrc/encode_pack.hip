@@ -300,7 +300,10 @@ int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *c
         o.axis = t->contract_axis;
         o.tiled = t->rblock == 24;
         o.nb_stored = (int32_t)(t->kpad / 32);
-        o.ksteps = (int32_t)(round_up(t->nblk * 24, 128) / 64);
+        {   // the packed k axis ends with the last octet that holds an element (as mx_ksteps counts it)
+            const int64_t all = t->nblk * 3, used = ceil_div(t->kdim, 8);
+            o.ksteps = (int32_t)(round_up((used < all ? used : all) * 8, 128) / 64);
+        }
         o.row_tiles = (int32_t)(ceil_div(t->rows, 256) * 8);
         o.s0 = (uint32_t)t->seed;
         o.s1 = (uint32_t)(t->seed >> 32);

@@ -783,8 +783,14 @@ int32_t next_mark() {
 int dense_octets(const GemmArgs &a) {
     return (a.kbp == 32 && a.kblock < 32 && a.kblock % 8 == 0 && a.mA <= 8 && a.mB <= 8) ? (int)(a.kblock / 8) : 0;
 }
+// octets of a densely packed row: those of all exponent blocks, less the ones of the last block that lie wholly behind
+// the end of the contraction (a last block of 16 elements in blocks of 24 has two, not three)
+static int64_t dense_row_octets(const GemmArgs &a) {
+    const int64_t all = a.nblk * dense_octets(a), used = ceil_div(a.kdim, 8);
+    return a.kdim > 0 && used < all ? used : all;
+}
 // k-steps of 64 that the product kernel walks: the stored length, or the unpadded one for the dense layout
-int64_t mx_ksteps(const GemmArgs &a) { return (dense_octets(a) ? round_up(a.nblk * a.kblock, 128) : a.kpad) / 64; }
+int64_t mx_ksteps(const GemmArgs &a) { return (dense_octets(a) ? round_up(dense_row_octets(a) * 8, 128) : a.kpad) / 64; }
 
 PackParams pack_params(const GemmArgs &a, const void *mant, const uint8_t *exps, int64_t R, int64_t exp_ld, int m, void *packed) {
     const int64_t kpad = a.kpad, kbp = a.kbp;
@@ -802,7 +808,7 @@ PackParams pack_params(const GemmArgs &a, const void *mant, const uint8_t *exps,
     q.chunks32_per_block = (int32_t)(kbp / 32);
     q.m = m;
     q.ob = dense_octets(a);
-    q.noct = (int32_t)(a.nblk * q.ob);
+    q.noct = (int32_t)dense_row_octets(a);
     return q;
 }
 

@@ -58,6 +58,7 @@ struct GemmArgs {
     const void *mantA, *mantB;        // int8 [rows][kpad] (or limb planes)
     const uint8_t *expA, *expB;       // [rows][exp_ld]
     int64_t M, N, kpad, expA_ld, expB_ld, nblk, kbp, kblock;
+    int64_t kdim;                     // contraction length without any padding (0: unknown, take nblk * kblock)
     int32_t mA, mB;                   // mantissa bits
     float *C;
     int64_t ldc;

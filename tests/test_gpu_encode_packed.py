@@ -31,10 +31,10 @@ def _flagged(buf):
 def _planes_end(d):
     """First byte past the limb planes a pack writes: 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
     bytes behind the 256-byte header; blocks of 8, 16 and 24 are packed without their padding (buffers are sized for
-    the padded length, the rest is never written)."""
+    the padded length, the rest is never written), and octets of the last block that hold no element are not packed."""
     limbs = 1 if d.mant_bits <= 5 else 2 if d.mant_bits <= 9 else 3
     dense = d.mant_bits <= 8 and d.kblock < 32 and d.kblock % 8 == 0
-    klen = -(-(d.nblk * d.kblock) // 128) * 128 if dense else d.kpad
+    klen = -(-min(d.nblk * d.kblock, -(-d.kdim // 8) * 8) // 128) * 128 if dense else d.kpad
     return 256 + -(-d.rows // 256) * (klen // 64) * 8 * (limbs * 1536 + 256)
 
 
