@@ -38,9 +38,9 @@ HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_config4_hbm_traffic_counters.txt for the
 # product kernel of config 4 alone, profiles/bench_default_hbm_traffic_counters.txt for the encode), scaled by what the same
 # counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 product kernel (gemm_mx_kernel<2, 2, false>, 64 k-steps): 82544 KiB x 2.0 + 65536 KiB = 236.2 MB
+#   config 4 product kernel (gemm_mx_kernel<2, 2, false>, 64 k-steps): 80048 KiB x 2.0 + 65536 KiB = 231.0 MB
 #   config 2 encode m=8 RNE launch: 131552 KiB x 2.0 + 67588 KiB = 338.6 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 236.2e6
+TRAFFIC_GEMM_C4_BYTES = 231.0e6
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.6e6
 # algorithmic bytes of the config 4 product kernel: both operands as densely packed limb planes read once (16 panels of
 # 256 rows x 64 k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
