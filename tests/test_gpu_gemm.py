@@ -724,6 +724,58 @@ def test_packed_product_in_a_replayed_graph(hb):
         assert rel_fro(got.cpu().numpy(), _oracle_product(X, W, (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
 
 
+def test_training_step_route_in_a_replayed_graph(hb):
+    """The route the benchmark times, captured once and replayed: conversions that write stored and packed operands
+    (blocks of 24), the forward product, both backward products in one launch.  Every replay (new inputs in the same
+    buffers, eager work and synchronisation in between) must equal the eager calls bit for bit; one replay has
+    heavy-tailed gradients, whose operands are marked and computed by the int8 kernels inside the same calls."""
+    M, K, N = 300, 520, 280
+    rng = np.random.default_rng(14)
+    f_row, f_col, f_tile = hb.make_format(8, 1, 24), hb.make_format(8, 24, 1), hb.make_format(8, 24, 24)
+    X, W, dY = (torch.zeros(s, device="cuda") for s in ((M, K), (K, N), (M, N)))
+    x = [hb.alloc(f_row, M, K, 1), hb.alloc(f_col, M, K, 0)]
+    w = [hb.alloc(f_tile, K, N, 0), hb.alloc(f_tile, K, N, 1)]
+    g = [hb.alloc(f_row, M, N, 1), hb.alloc(f_col, M, N, 0)]
+    px, pw, pg = ([torch.empty(hb.pack_bytes(t.desc), dtype=torch.uint8, device="cuda") for t in ts] for ts in (x, w, g))
+    Y, dX, dW = torch.empty((M, N), device="cuda"), torch.empty((M, K), device="cuda"), torch.empty((K, N), device="cuda")
+    ws1 = torch.empty(max(hb.gemm_packed_workspace(x[0].desc, w[0].desc), 256), dtype=torch.uint8, device="cuda")
+    pair = lambda: [(g[0], pg[0], w[1], pw[1]), (x[1], px[1], g[1], pg[1])]
+    ws2 = torch.empty(max(hb.gemm_packed_batch_workspace([(p[0], p[2]) for p in pair()]), 256), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def step(s):
+        hb.encode_packed(X, x, px, stream=s)
+        hb.encode_packed(W, w, pw, stream=s)
+        hb.gemm_packed(x[0], px[0], w[0], pw[0], out=Y, workspace=ws1, stream=s)
+        hb.encode_packed(dY, g, pg, stream=s)
+        hb.gemm_packed_batch(pair(), [dX, dW], workspace=ws2, stream=s)
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        step(stream)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            step(stream)
+    for i, tails in enumerate([False, True, False, False]):
+        X.copy_(torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)))
+        W.copy_(torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)))
+        grad = rng.standard_t(2, size=(M, N)) if tails else rng.standard_normal((M, N))
+        dY.copy_(torch.from_numpy((grad * 1e-3).astype(np.float32)))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (Y, dX, dW)]
+        marked = [bool(p[:8].view(torch.int32)[0] == p[:8].view(torch.int32)[1]) for p in pg]
+        step(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        print(f"[case] step graph replay {i} heavy tails={tails} gradient operands marked={marked}", flush=True)
+        assert all(marked) == tails
+        for a, b in zip(got, (Y, dX, dW)):
+            assert torch.equal(a, b)
+        oa, ob = ref.encode(X.cpu().numpy(), 1, 24, 8), ref.encode(W.cpu().numpy(), 24, 24, 8)
+        assert rel_fro(Y.cpu().numpy(), ref.gemm(ref.decode(oa), ref.decode(ob))) <= TOL
+
+
 def test_pack_argument_checks(hb):
     import ctypes
     t = hb.encode(torch.randn((64, 128), device="cuda"), 1, hb.make_format(8, 1, 32))
