@@ -208,6 +208,22 @@ def _weight_update_config4(torch, hbfp, synth, reps=10):
 def _gemm_side_configs(torch, hbfp, synth, reps=10):
     """Config 3 (conv lowered to GEMM; forward, dgrad, wgrad), kernel-only and including encodes."""
     res = {}
+    # config 1 (256^3, blocks of 32): the parity configuration, bound by launch latency; conversions and product as three calls
+    Ah, Bh = synth.c1_gemm_small()
+    A1, B1 = torch.from_numpy(Ah).cuda(), torch.from_numpy(Bh).cuda()
+    f1a, f1b = hbfp.make_format(8, 1, 32), hbfp.make_format(8, 32, 1)
+    t1a, t1b = hbfp.alloc(f1a, 256, 256, 1), hbfp.alloc(f1b, 256, 256, 0)
+    out1 = torch.empty((256, 256), dtype=torch.float32, device="cuda")
+    ws1 = torch.empty(max(hbfp.gemm_workspace(t1a.desc, t1b.desc), 256), dtype=torch.uint8, device="cuda")
+
+    def c1_call():
+        hbfp.encode(A1, 1, f1a, out=t1a)
+        hbfp.encode(B1, 0, f1b, out=t1b)
+        hbfp.gemm(t1a, t1b, out=out1, workspace=ws1)
+
+    ms1 = _time_call(torch, c1_call, 50)
+    res["c1_256_cubed_incl_encodes"] = {"ms": round(ms1, 4), "TOPS": round(2.0 * 256 ** 3 / ms1 / 1e9, 2)}
+    del A1, B1, t1a, t1b, out1, ws1
     Xh, Wh, dYh = synth.c3_conv_as_gemm()
     X, W, dY = (torch.from_numpy(a).cuda() for a in (Xh, Wh, dYh))
     row, col = hbfp.make_format(8, 1, 32), hbfp.make_format(8, 32, 1)
