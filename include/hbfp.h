@@ -375,7 +375,12 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
  *           opaque and stay valid until the operand is encoded again (then pack it again).  The first 256 bytes
  *           hold a mark that differs from pack to pack (it lets a pack signal "exponent out of range" without
  *           anything having to be cleared first), so two packs of the same operand agree from byte 256 on, not
- *           before: the rule "same inputs, same bytes" holds for every result except this header.  The buffer is
+ *           before: the rule "same inputs, same bytes" holds for every result except this header.  Its first two
+ *           32-bit words are equal exactly when the operand is marked (an exponent out of range, or neighbouring
+ *           blocks of a densely packed group more than 3 binades apart, as heavy-tailed values produce them); a
+ *           caller may read them once the pack has completed: products on a marked operand are computed by the
+ *           older int8 kernel inside the same call, and hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored
+ *           operands is the faster way to the same product.  The buffer is
  *           sized for blocks stored padded to 32; blocks of 8, 16 and 24 elements are packed without their
  *           padding and leave its tail unwritten.
  * hbfp_gemm_packed is hbfp_gemm_select with HBFP_KERNEL_SCALED on operands packed beforehand: C and beta as in
