@@ -506,6 +506,34 @@ def _kernel_families(torch, hbfp, reps=8):
     return {"kernel_families": res}
 
 
+def _heavy_tails(torch, hbfp, reps=10):
+    """A 4096^3 product of config 4's formats whose activation operand is heavy-tailed (Student-t, 3 degrees of freedom):
+    its packed form is marked, so hbfp_gemm_packed hands over to its int8 stand-by: the 4-wave kernel by default, the
+    8-wave kernel when the operand carries HBFP_HINT_HEAVY_TAILS; hbfp_gemm_select with HBFP_KERNEL_INT8 for comparison."""
+    n = 4096
+    g = torch.Generator(device="cuda").manual_seed(11)
+    z = torch.randn((n, n), device="cuda", generator=g)
+    chi = (torch.randn((3, n, n), device="cuda", generator=g) ** 2).sum(0) / 3.0
+    X = z / chi.sqrt()
+    W = torch.randn((n, n), device="cuda", generator=g) * 0.02
+    del z, chi
+    x, w = hbfp.alloc(hbfp.make_format(8, 1, 24), n, n, 1), hbfp.alloc(hbfp.make_format(8, 24, 24), n, n, 0)
+    px, pw = (torch.empty(hbfp.pack_bytes(t.desc), dtype=torch.uint8, device="cuda") for t in (x, w))
+    hbfp.encode_packed(X, [x], [px])
+    hbfp.encode_packed(W, [w], [pw])
+    out = torch.empty((n, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_packed_workspace(x.desc, w.desc), 256), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    mark = px[:8].view(torch.int32).tolist()
+    res = {"operand_marked": mark[0] == mark[1]}
+    res["gemm_packed_ms"] = round(_time_call(torch, lambda: hbfp.gemm_packed(x, px, w, pw, out=out, workspace=ws), reps), 4)
+    x.desc.hints = hbfp.HINT_HEAVY_TAILS
+    res["gemm_packed_with_hint_ms"] = round(_time_call(torch, lambda: hbfp.gemm_packed(x, px, w, pw, out=out, workspace=ws), reps), 4)
+    x.desc.hints = 0
+    res["gemm_select_int8_ms"] = round(_time_call(torch, lambda: hbfp.gemm(x, w, out=out, workspace=ws, kernel=hbfp.KERNEL_INT8), reps), 4)
+    return {"c4_product_with_heavy_tailed_activations": res}
+
+
 def _matrix_probe(torch, hbfp, iters=3000):
     """What the matrix core sustains on this machine: register-only loops (hbfp_probe_matrix_rate) of the int8 and of the
     block-scaled FP6 matrix instruction at 1 and 2 workgroups of 4 waves per compute unit, with constant and with
@@ -695,6 +723,7 @@ def main():
         extra.update(_paper_formats(torch, hbfp))
         extra.update(_batched_products(torch, hbfp))
         extra.update(_encoded_output(torch, hbfp))
+        extra.update(_heavy_tails(torch, hbfp))
         out["extra"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)

@@ -118,10 +118,14 @@ typedef struct hbfp_tensor {
     int32_t contract_axis; /* 0: k runs down the source rows, 1: along the source columns */
     int32_t mant_bits;
     int32_t rounding;
-    int32_t reserved;
+    int32_t hints;         /* HBFP_HINT_*: set by the caller after hbfp_plan (which leaves 0); results never depend on it */
     uint64_t seed;
     uint64_t mant_bytes, exp_bytes;
 } hbfp_tensor;
+/* The values of this operand are heavy-tailed (gradients often are): its packed form will usually be marked (see hbfp_pack),
+ * so products on packed operands prepare the faster of the int8 kernels as their stand-by.  That costs about 2 us per
+ * product when the stand-by turns out not to be needed and saves a quarter of the time of a product when it is. */
+#define HBFP_HINT_HEAVY_TAILS 1
 
 /* Library version and a short text for a status code (host, never NULL). */
 int hbfp_version(void);

@@ -154,6 +154,9 @@ GemmArgs gemm_args(const hbfp_tensor *A, const hbfp_tensor *B) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// the caller expects marked operands: prepare the 8-wave int8 kernel as the stand-by of the block-scaled product
+bool fast_standby(const hbfp_tensor *A, const hbfp_tensor *B) { return ((A->hints | B->hints) & HBFP_HINT_HEAVY_TAILS) != 0; }
+
 }  // namespace
 
 extern "C" {
@@ -580,12 +583,12 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
         // the block-scaled matrix instruction computes the product unless some exponent is out of its range;
         // the int8 kernels queue up behind it and run only in that case
         void *pa = workspace, *pb = (char *)workspace + mx_packed_bytes(g.M, g.kpad, g.mA);
+        workspace = (char *)pb + mx_packed_bytes(g.N, g.kpad, g.mB);                  // what is left is the stand-by's
         rc = launch_mx_pack(g, pa, pb, (hipStream_t)stream);
-        if (rc == HBFP_OK) rc = launch_mx_product(g, pa, pb, (hipStream_t)stream);
+        if (rc == HBFP_OK) rc = launch_mx_product(g, pa, pb, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
         if (rc != HBFP_OK) return rc;
         g.run_a = (const int *)pa;
         g.run_b = (const int *)pb;
-        workspace = (char *)pb + mx_packed_bytes(g.N, g.kpad, g.mB);
     }
     if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
     return launch_gemm_i8(g, workspace, (hipStream_t)stream);
@@ -680,7 +683,9 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
         pb[i] = b;
         ws += part[i];
     }
-    rc = launch_mx_products(n, g, pa, pb, s);
+    void *fast[HBFP_BATCH_MAX];
+    for (int i = 0; i < n; ++i) fast[i] = fast_standby(A[i], B[i]) ? standby[i] : nullptr;
+    rc = launch_mx_products(n, g, pa, pb, fast, s);
     if (rc != HBFP_OK) return rc;
     for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
         g[i].run_a = (const int *)pa[i];
@@ -797,7 +802,7 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
     g.ldc = ldc;
     g.beta = beta;
     if (!gemm_mx_possible(g)) return HBFP_ERR_ARG;
-    rc = launch_mx_product(g, packed_a, packed_b, (hipStream_t)stream);
+    rc = launch_mx_product(g, packed_a, packed_b, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
     if (rc != HBFP_OK) return rc;
     g.run_a = (const int *)packed_a;
     g.run_b = (const int *)packed_b;
@@ -843,7 +848,15 @@ int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const
     }
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    int rc = launch_mx_products(n, g, packed_a, packed_b, s);
+    void *standby[HBFP_BATCH_MAX];
+    {
+        char *w = (char *)workspace;
+        for (int i = 0; i < n; ++i) {
+            standby[i] = part[i] && fast_standby(A[i], B[i]) ? w : nullptr;
+            w += part[i];
+        }
+    }
+    int rc = launch_mx_products(n, g, packed_a, packed_b, standby, s);
     if (rc != HBFP_OK) return rc;
     char *ws = (char *)workspace;
     for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product

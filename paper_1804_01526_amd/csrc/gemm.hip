@@ -912,6 +912,33 @@ int launch_gemm_f16(const GemmArgs &a, void *workspace, hipStream_t s) {
     return rc;
 }
 
+// split-K plan of the int8 kernels for product `a`
+static void split_plan(const GemmArgs &a, int32_t *splits, int32_t *stages_per_split) {
+    const int32_t nstage = (int32_t)(a.kpad / BK), spb = (int32_t)(a.kbp / 32);
+    const int stages_per_block = spb >= 4 ? spb / 4 : 1;
+    int32_t sp = a.P ? 1 : choose_splits(a.M, a.N, nstage, stages_per_block);
+    const int64_t units = nstage / stages_per_block;
+    *stages_per_split = (int32_t)(ceil_div(units, sp) * stages_per_block);
+    *splits = (int32_t)ceil_div(nstage, *stages_per_split);
+}
+
+bool gemm_i8_standby_words(const GemmArgs &a, void *workspace, StandbyWords *w) {
+    if (!workspace || a.P || a.mA > 8 || a.mB > 8 || !use_w8(a.kpad)) return false;
+    if (a.wide ? gemm_wide_possible(a) : gemm_wide_ok(a)) return false;                  // that kernel reads exponent bytes itself
+    if (ceil_div(a.M, BM) * ceil_div(a.N, BN) > 0x7ffffff0 || a.kpad / BK > 0x7fffffff) return false;
+    int32_t splits, sps;
+    split_plan(a, &splits, &sps);
+    uint8_t *base = (uint8_t *)workspace + split_bytes(a.M, a.N, splits);
+    w->eA = a.expA; w->eB = a.expB;
+    w->ldA = a.expA_ld; w->ldB = a.expB_ld;
+    w->M = a.M; w->N = a.N;
+    w->slots = (int32_t)a.expA_ld;
+    w->a_or = 0x40u;
+    w->wA = (uint32_t *)base;
+    w->wB = (uint32_t *)(base + word_bytes(a.M, a.expA_ld));
+    return true;
+}
+
 int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     if (a.wide ? gemm_wide_possible(a) : gemm_wide_ok(a)) return launch_gemm_wide(a, s);
     GemmParams p;
@@ -939,21 +966,16 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
     p.final_scale = ldexpf(1.0f, 27 - a.mA - a.mB);
     p.run_a = a.run_a;
     p.run_b = a.run_b;
-    const int stages_per_block = p.spb >= 4 ? p.spb / 4 : 1;
-    p.splits = a.P ? 1 : choose_splits(a.M, a.N, p.nstage, stages_per_block);
-    {
-        const int64_t units = p.nstage / stages_per_block;
-        p.stages_per_split = (int32_t)(ceil_div(units, p.splits) * stages_per_block);
-        p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
-    }
+    split_plan(a, &p.splits, &p.stages_per_split);
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
     int rc;
     if (a.P) {
         rc = p.spb == 1 ? launch_t<1, true>(p, grid, s) : p.spb == 2 ? launch_t<2, true>(p, grid, s) : launch_t<0, true>(p, grid, s);
     } else {
-        // behind the block-scaled kernel the product almost never runs: one launch, no scale-word kernel
-        if (use_w8(a.kpad) && !a.run_a) {
+        // behind the block-scaled kernel the product almost never runs: one launch, no scale-word kernel in front of it;
+        // it is the 8-wave kernel when the product kernel has prepared its scale words (words_ready), else the 4-wave one
+        if (use_w8(a.kpad) && (!a.run_a || a.words_ready)) {
             static std::atomic<bool> configured[3];
             const void *const kernels[3] = {reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1>), reinterpret_cast<const void *>(&gemm_i8_w8_kernel<2>),
                                             reinterpret_cast<const void *>(&gemm_i8_w8_kernel<0>)};
@@ -967,9 +989,11 @@ int launch_gemm_i8(const GemmArgs &a, void *workspace, hipStream_t s) {
             uint8_t *w = (uint8_t *)workspace + split_bytes(a.M, a.N, p.splits);
             q.wA = (const uint32_t *)w;
             q.wB = (const uint32_t *)(w + word_bytes(a.M, a.expA_ld));
-            rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0x40u,
-                                    const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_a, a.run_b, s);
-            if (rc != HBFP_OK) return rc;
+            if (!a.words_ready) {
+                rc = launch_scale_words(a.expA, a.expA_ld, a.M, a.expB, a.expB_ld, a.N, (int)a.expA_ld, 0x40u,
+                                        const_cast<uint32_t *>(q.wA), const_cast<uint32_t *>(q.wB), a.run_a, a.run_b, s);
+                if (rc != HBFP_OK) return rc;
+            }
             if (p.spb == 1) hipLaunchKernelGGL(gemm_i8_w8_kernel<1>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             else if (p.spb == 2) hipLaunchKernelGGL(gemm_i8_w8_kernel<2>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);
             else hipLaunchKernelGGL(gemm_i8_w8_kernel<0>, grid, dim3(kW8Threads), kW8LdsBytes, s, q);

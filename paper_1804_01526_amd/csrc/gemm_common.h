@@ -88,12 +88,11 @@ struct WordParams {
     uint32_t a_or;               // 0x40: row words are 1.5 * 2^(E - 127) as bf16; 0: 2^(E - 127) as bf16
     const int *run_a, *run_b;
 };
-__global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
-    if (stands_down(w.run_a, w.run_b)) return;
-    const int z = blockIdx.z;
-    const int64_t row = (int64_t)(blockIdx.x % w.row_blocks) * 256 + threadIdx.x;
+// one block of 256 threads of that job: block index, operand, thread
+__device__ __forceinline__ void scale_words_block(const WordParams &w, uint32_t block, int z, int thread) {
+    const int64_t row = (int64_t)(block % (uint32_t)w.row_blocks) * 256 + thread;
     if (row >= w.rows_pad[z]) return;
-    const int s0 = (blockIdx.x / w.row_blocks) * 4;
+    const int s0 = (int)(block / (uint32_t)w.row_blocks) * 4;
     const uint32_t e4 = row < w.rows[z] ? *reinterpret_cast<const uint32_t *>(w.exps[z] + row * w.ld[z] + s0) : 0x01010101u;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -102,14 +101,17 @@ __global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) 
         w.words[z][(int64_t)(s0 + i) * w.rows_pad[z] + row] = z == 0 ? ((e << 7) | w.a_or) : (e << 23);
     }
 }
+__global__ __launch_bounds__(256) void scale_words_t_kernel(const WordParams w) {
+    if (stands_down(w.run_a, w.run_b)) return;
+    scale_words_block(w, blockIdx.x, (int)blockIdx.z, (int)threadIdx.x);
+}
 
 // bytes of one operand's scale words: [slots][rows rounded up to 128]
 inline size_t word_bytes(int64_t rows, int64_t slots) { return (size_t)slots * (size_t)(ceil_div(rows, 128) * 128) * 4; }
 
 // slots must be a multiple of 4 and at most the exponent row pitch of either operand
-inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const uint8_t *eB, int64_t ldB, int64_t N, int slots,
-                              uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_a, const int *run_b,
-                              hipStream_t s) {
+inline WordParams scale_word_params(const uint8_t *eA, int64_t ldA, int64_t M, const uint8_t *eB, int64_t ldB, int64_t N, int slots,
+                                    uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_a, const int *run_b) {
     WordParams wp;
     wp.exps[0] = eA; wp.exps[1] = eB;
     wp.words[0] = wA; wp.words[1] = wB;
@@ -122,8 +124,16 @@ inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const u
     wp.run_b = run_b;
     const int64_t maxpad = wp.rows_pad[0] > wp.rows_pad[1] ? wp.rows_pad[0] : wp.rows_pad[1];
     wp.row_blocks = (int)ceil_div(maxpad, 256);
-    if ((int64_t)wp.row_blocks * (slots / 4) > 0x7fffffff) return HBFP_ERR_ARG;
-    hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)(wp.row_blocks * (slots / 4)), 1, 2), dim3(256), 0, s, wp);
+    return wp;
+}
+// blocks of 256 threads per operand that the job consists of
+inline int64_t scale_word_blocks(const WordParams &wp) { return (int64_t)wp.row_blocks * (wp.slots / 4); }
+inline int launch_scale_words(const uint8_t *eA, int64_t ldA, int64_t M, const uint8_t *eB, int64_t ldB, int64_t N, int slots,
+                              uint32_t a_or, uint32_t *wA, uint32_t *wB, const int *run_a, const int *run_b,
+                              hipStream_t s) {
+    const WordParams wp = scale_word_params(eA, ldA, M, eB, ldB, N, slots, a_or, wA, wB, run_a, run_b);
+    if (scale_word_blocks(wp) > 0x7fffffff) return HBFP_ERR_ARG;
+    hipLaunchKernelGGL(scale_words_t_kernel, dim3((unsigned)scale_word_blocks(wp), 1, 2), dim3(256), 0, s, wp);
     return launch_status();
 }
 

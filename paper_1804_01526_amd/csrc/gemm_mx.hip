@@ -251,11 +251,18 @@ struct MxOut {
     uint32_t s0, s1;
 };
 
+// Workgroups behind the tiles (kMxWordWgs per product that has a job): they prepare the scale words of the 8-wave int8
+// kernel that stands by behind this launch, and only if that kernel is going to run (an operand is marked); otherwise
+// they are gone at once.  This keeps the stand-by path at one launch without tying it to the slower kernel that
+// reads exponent bytes itself.
+constexpr int kMxWordWgs = 64;
 struct MxGroup {
     MxParams p[kMxGroup];
     int32_t first[kMxGroup + 1];
     int32_t n;
+    int32_t word_jobs;           // bit i: product i has a scale-word job
     MxOut out;                   // of product 0 of a launch with a single product
+    WordParams words[kMxGroup];
 };
 
 template <int CTRL>
@@ -494,6 +501,24 @@ __global__ __launch_bounds__(kMxThreads, 2) void gemm_mx_kernel(const MxGroup g)
 
     // which product this workgroup belongs to: selected with constant indices, so that the parameters stay in
     // scalar registers (the copy instructions take their base addresses from there)
+    if ((int)blockIdx.x >= g.first[kMxGroup]) {
+        // behind the tiles: scale words for the int8 stand-by of product i, 256 threads per operand
+        const int extra = (int)blockIdx.x - g.first[kMxGroup], i = extra / kMxWordWgs;
+        WordParams w = g.words[0];
+#pragma unroll
+        for (int j = 1; j < kMxGroup; ++j)
+            if (j == i) w = g.words[j];
+        if (!((g.word_jobs >> i) & 1) || stands_down(w.run_a, w.run_b)) return;
+        const uint32_t blocks = (uint32_t)w.row_blocks * (uint32_t)(w.slots / 4);
+        // few workgroups (each costs launch time when there is nothing to do), so several blocks at a time: their loads
+        // are independent
+        for (uint32_t b = (uint32_t)(extra - i * kMxWordWgs); b < blocks; b += 4 * kMxWordWgs) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (b + u * kMxWordWgs < blocks) scale_words_block(w, b + u * kMxWordWgs, (int)(threadIdx.x >> 8), (int)(threadIdx.x & 255));
+        }
+        return;
+    }
     MxParams p = g.p[0];
     int first_wg = 0;
 #pragma unroll
@@ -885,7 +910,8 @@ int launch_mx_tr(const MxGroup &g, hipStream_t s) {
     constexpr int bytes = mx_lds_bytes(LA, LB);
     static std::atomic<bool> configured{false};
     if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_mx_kernel<LA, LB, TR>), bytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
-    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB, TR>), dim3((unsigned)g.first[g.n]), dim3(kMxThreads), bytes, s, g);
+    const unsigned grid = (unsigned)g.first[g.n] + (g.word_jobs ? (unsigned)(g.n * kMxWordWgs) : 0u);
+    hipLaunchKernelGGL((gemm_mx_kernel<LA, LB, TR>), dim3(grid), dim3(kMxThreads), bytes, s, g);
     return launch_status();
 }
 
@@ -999,8 +1025,8 @@ int launch_mx_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
 }
 
 // n <= kMxGroup products with the same limb counts in one launch
-static int launch_mx_group(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, const MxOut *out,
-                           hipStream_t s) {
+static int launch_mx_group(int n, GemmArgs *args, const void *const *packed_a, const void *const *packed_b, const MxOut *out,
+                           void *const *standby_ws, hipStream_t s) {
     if (n < 1 || n > kMxGroup || (out && n != 1)) return HBFP_ERR_ARG;
     const int LA = limbs_of(args[0].mA), LB = limbs_of(args[0].mB);
     MxGroup g = {};
@@ -1028,6 +1054,15 @@ static int launch_mx_group(int n, const GemmArgs *args, const void *const *packe
         if (first > 0x7ffffff0) return HBFP_ERR_ARG;
     }
     for (int i = n; i <= kMxGroup; ++i) g.first[i] = (int32_t)first;
+    for (int i = 0; i < n && standby_ws; ++i) {
+        StandbyWords w;
+        if (!standby_ws[i] || !gemm_i8_standby_words(args[i], standby_ws[i], &w)) continue;
+        g.words[i] = scale_word_params(w.eA, w.ldA, w.M, w.eB, w.ldB, w.N, w.slots, w.a_or, w.wA, w.wB, (const int *)packed_a[i],
+                                       (const int *)packed_b[i]);
+        if (scale_word_blocks(g.words[i]) > 0x7fffffff) continue;
+        g.word_jobs |= 1 << i;
+        args[i].words_ready = 1;
+    }
     switch (LA * 4 + LB) {
         case 1 * 4 + 1: return launch_mx_t<1, 1>(g, s);
         case 1 * 4 + 2: return launch_mx_t<1, 2>(g, s);
@@ -1040,12 +1075,13 @@ static int launch_mx_group(int n, const GemmArgs *args, const void *const *packe
     }
 }
 
-int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
-    return launch_mx_group(n, args, packed_a, packed_b, nullptr, s);
+int launch_mx_products(int n, GemmArgs *args, const void *const *packed_a, const void *const *packed_b, void *const *standby_ws,
+                       hipStream_t s) {
+    return launch_mx_group(n, args, packed_a, packed_b, nullptr, standby_ws, s);
 }
 
-int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s) {
-    return launch_mx_group(1, &a, &packed_a, &packed_b, nullptr, s);
+int launch_mx_product(GemmArgs &a, const void *packed_a, const void *packed_b, void *standby_ws, hipStream_t s) {
+    return launch_mx_group(1, &a, &packed_a, &packed_b, nullptr, &standby_ws, s);
 }
 
 // The block-scaled kernel can write its accumulators as an encoded operand when the output's exponent blocks are
@@ -1059,7 +1095,8 @@ int launch_mx_product_encoded(const GemmArgs &a, const void *packed_a, const voi
                               hipStream_t s) {
     if (!mx_encoded_output_ok(out)) return HBFP_ERR_FORMAT;
     const MxOut o = mx_out_of(out, relu);
-    return launch_mx_group(1, &a, &packed_a, &packed_b, &o, s);
+    GemmArgs copy = a;
+    return launch_mx_group(1, &copy, &packed_a, &packed_b, &o, nullptr, s);
 }
 
 // behind the int8 kernels that stood by for launch_mx_product_encoded and wrote the FP32 product to C

@@ -68,7 +68,19 @@ struct GemmArgs {
     // every kernel of the launch does nothing unless one of them is marked out of range (word 0 == word 1)
     const int *run_a, *run_b;
     int32_t wide;                     // 1: the caller asked for the 256 x 256-tile int8 kernel whatever the shape
+    int32_t words_ready;              // stand-by launches: the scale words of the 8-wave int8 kernel are in the workspace already
 };
+// What the block-scaled product kernel needs in order to prepare the scale words of the int8 stand-by launch behind it
+// (extra workgroups of its own grid that do nothing unless an operand is marked)
+struct StandbyWords {
+    const uint8_t *eA, *eB;
+    uint32_t *wA, *wB;
+    int64_t ldA, ldB, M, N;
+    int32_t slots;
+    uint32_t a_or;
+};
+// true if the int8 stand-by of product `a` is the 8-wave kernel, whose scale words then lie at w->wA / w->wB in `workspace`
+bool gemm_i8_standby_words(const GemmArgs &a, void *workspace, StandbyWords *w);
 // 2-D tiles of at most 32 x 32 held in registers: one input (FP32 matrix, or stored wide weights + alpha * step),
 // up to three outputs of the same tile shape in any orientation
 bool tile_path_ok(const hbfp_tensor *const *outs, int n, const hbfp_tensor *wide_in, const float *src, int64_t ld);
@@ -111,7 +123,10 @@ int launch_mx_product_encoded(const GemmArgs &a, const void *packed_a, const voi
 int launch_mx_encode_standby(const float *C, int64_t ldc, const hbfp_tensor &out, int relu, const int *run_a, const int *run_b,
                              hipStream_t s);
 int launch_relu(float *x, int64_t n, hipStream_t s);
-int launch_mx_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
-int launch_mx_product(const GemmArgs &a, const void *packed_a, const void *packed_b, hipStream_t s);
+// standby_ws: per product, the workspace its int8 stand-by launch will be given, or null; where that stand-by is the
+// 8-wave int8 kernel the launch also prepares its scale words (args[i].words_ready is set then)
+int launch_mx_products(int n, GemmArgs *args, const void *const *packed_a, const void *const *packed_b, void *const *standby_ws,
+                       hipStream_t s);
+int launch_mx_product(GemmArgs &a, const void *packed_a, const void *packed_b, void *standby_ws, hipStream_t s);
 
 }  // namespace hbfp

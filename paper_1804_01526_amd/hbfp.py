@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libhbfp.so")
 
 OK, ERR_ARG, ERR_FORMAT, ERR_LAYOUT, ERR_RANGE, ERR_LAUNCH, ERR_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
 RNE, STOCHASTIC = 0, 1
+HINT_HEAVY_TAILS = 1
 
 
 class HbfpError(RuntimeError):
@@ -52,7 +53,7 @@ class TensorDesc(ctypes.Structure):
                 ("exp_ld", ctypes.c_int64), ("rblock", ctypes.c_int64), ("kshare", ctypes.c_int64),
                 ("src_rows", ctypes.c_int64), ("src_cols", ctypes.c_int64),
                 ("contract_axis", ctypes.c_int32), ("mant_bits", ctypes.c_int32),
-                ("rounding", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("rounding", ctypes.c_int32), ("hints", ctypes.c_int32),
                 ("seed", ctypes.c_uint64), ("mant_bytes", ctypes.c_uint64), ("exp_bytes", ctypes.c_uint64)]
 
 

@@ -724,6 +724,45 @@ def test_packed_product_in_a_replayed_graph(hb):
         assert rel_fro(got.cpu().numpy(), _oracle_product(X, W, (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
 
 
+def test_heavy_tail_hint_changes_the_stand_by_kernel_not_the_result(hb):
+    """HBFP_HINT_HEAVY_TAILS on an operand: products on packed operands prepare the 8-wave int8 kernel as their stand-by
+    (its scale words written by extra workgroups of the product kernel).  Marked operands (Student-t values) then give
+    exactly what hbfp_gemm_select computes with HBFP_KERNEL_INT8; unmarked ones exactly what they give without the
+    hint; the same through hbfp_gemm_packed_batch, hbfp_gemm_select (packing inside the call) and with beta = 1."""
+    rng = np.random.default_rng(21)
+    M, K, N = 300, 1000, 280
+    f_row, f_col = hb.make_format(8, 1, 24), hb.make_format(8, 24, 1)
+    W = torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)).cuda()
+    w = hb.encode(W, 0, f_col)
+    pw = hb.pack(w)
+    for tails in (True, False):
+        data = rng.standard_t(2, size=(M, K)) if tails else rng.standard_normal((M, K))
+        X = torch.from_numpy(data.astype(np.float32)).cuda()
+        x = hb.encode(X, 1, f_row)
+        px = hb.pack(x)
+        torch.cuda.synchronize()
+        marked = bool(px[:8].view(torch.int32)[0] == px[:8].view(torch.int32)[1])
+        assert marked == tails
+        plain = hb.gemm_packed(x, px, w, pw)
+        x.desc.hints = hb.HINT_HEAVY_TAILS
+        hinted = hb.gemm_packed(x, px, w, pw)
+        base = torch.from_numpy(_rand((M, N), 5, 1)).cuda()
+        hinted_acc = hb.gemm_packed(x, px, w, pw, out=base.clone(), beta=1.0)
+        both = hb.gemm_packed_batch([(x, px, w, pw), (x, px, w, pw)], [torch.empty_like(plain), torch.empty_like(plain)])
+        inside = hb.gemm(x, w, kernel=SCALED)
+        int8 = hb.gemm(x, w, kernel=1)
+        int8_acc = hb.gemm(x, w, out=base.clone(), beta=1.0, kernel=1)
+        x.desc.hints = 0
+        plain_acc = hb.gemm_packed(x, px, w, pw, out=base.clone(), beta=1.0)
+        torch.cuda.synchronize()
+        print(f"[case] heavy-tail hint, operand marked={marked}", flush=True)
+        for got in (hinted, both[0], both[1], inside):
+            assert torch.equal(got, int8 if tails else plain)
+        assert torch.equal(hinted_acc, int8_acc if tails else plain_acc)
+        oa, ob = ref.encode(data.astype(np.float32), 1, 24, 8), ref.encode(W.cpu().numpy(), 24, 1, 8)
+        assert rel_fro(hinted.cpu().numpy(), ref.gemm(ref.decode(oa), ref.decode(ob))) <= TOL
+
+
 def test_training_step_route_in_a_replayed_graph(hb):
     """The route the benchmark times, captured once and replayed: conversions that write stored and packed operands
     (blocks of 24), the forward product, both backward products in one launch.  Every replay (new inputs in the same
