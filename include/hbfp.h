@@ -383,8 +383,9 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
  *           32-bit words are equal exactly when the operand is marked (an exponent out of range, or neighbouring
  *           blocks of a densely packed group more than 3 binades apart, as heavy-tailed values produce them); a
  *           caller may read them once the pack has completed: products on a marked operand are computed by the
- *           older int8 kernel inside the same call, and hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored
- *           operands is the faster way to that product.  The buffer is
+ *           older int8 kernel inside the same call (by the faster one if the operand carries HBFP_HINT_HEAVY_TAILS),
+ *           and hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored operands is the fastest way to that product.
+ *           The buffer is
  *           sized for blocks stored padded to 32; blocks of 8, 16 and 24 elements are packed without their
  *           padding and leave its tail unwritten.
  * hbfp_gemm_packed is hbfp_gemm_select with HBFP_KERNEL_SCALED on operands packed beforehand: C and beta as in
