@@ -495,6 +495,30 @@ int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *c
                        const size_t *packed_bytes, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_encode_packed_batch: hbfp_encode_packed of up to HBFP_BATCH_MAX independent sources in one call (the input and
+ * the weights of a layer before its forward product, Sec. 5.1: neither conversion waits for the other).  Sources that
+ * the one-kernel case of hbfp_encode_packed takes, with equal rounding and limb counts, share one launch, so that the
+ * conversion of one source fills the compute units that the tail of another leaves idle; the remaining ones are
+ * converted one after the other.  Every output is bit for bit what hbfp_encode_packed writes for it.
+ *   jobs[j]     the arguments of hbfp_encode_packed for source j (host struct, host arrays; read during the call only)
+ *   workspace   hbfp_encode_packed_batch_workspace bytes, 256-byte aligned
+ * The outputs of different jobs must not overlap.
+ * Errors: as hbfp_encode_packed for the first job that fails a check (nothing has been launched then); HBFP_ERR_ARG
+ * if njobs is outside 1..HBFP_BATCH_MAX.
+ */
+typedef struct hbfp_encode_job {
+    const float *src;                  /* device, FP32, row-major                     */
+    int64_t ld;                        /* elements between its rows                    */
+    int32_t n;                         /* outputs of this source                       */
+    int32_t reserved;                  /* 0                                            */
+    const hbfp_tensor *const *outs;    /* host array of n planned tensors              */
+    void *const *packed;               /* host array of n device buffers (or NULL)     */
+    const size_t *packed_bytes;        /* host array of their sizes                    */
+} hbfp_encode_job;
+int hbfp_encode_packed_batch_workspace(int njobs, const hbfp_encode_job *jobs, size_t *bytes);
+int hbfp_encode_packed_batch(int njobs, const hbfp_encode_job *jobs, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_weight_update: one step on weights kept in BFP with wide mantissas
  * (Sec. 4.2 "Wide weight storage"; Sec. 5.1, the optimizer shell: the update is
  * computed in FP32 and the result is converted to two BFP formats, the wide one

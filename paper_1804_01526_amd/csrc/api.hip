@@ -347,10 +347,10 @@ static int pack_one(const hbfp_tensor *t, void *packed, hipStream_t s) {
     return launch_mx_pack(g, packed, nullptr, s);
 }
 
-int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed,
-                       const size_t *packed_bytes, void *workspace, size_t ws_bytes, void *stream) {
-    size_t need = 0;
-    int rc = encode_multi_check(n, outs, &need);
+// argument checks of hbfp_encode_packed for one source; *need: bytes of its conversion's scratch
+static int encode_packed_check(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed,
+                               const size_t *packed_bytes, size_t *need) {
+    int rc = encode_multi_check(n, outs, need);
     if (rc != HBFP_OK) return rc;
     if (!packed || !packed_bytes || !src || ((uintptr_t)src & 3) || ld < outs[0]->src_cols) return HBFP_ERR_ARG;
     for (int i = 0; i < n; ++i) {
@@ -360,6 +360,14 @@ int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *c
         if (packed_bytes[i] < mx_packed_bytes(outs[i]->rows, outs[i]->kpad, outs[i]->mant_bits)) return HBFP_ERR_WORKSPACE;
         if (ceil_div(outs[i]->rows, 256) * 8 * ceil_div(outs[i]->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
     }
+    return HBFP_OK;
+}
+
+int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed,
+                       const size_t *packed_bytes, void *workspace, size_t ws_bytes, void *stream) {
+    size_t need = 0;
+    int rc = encode_packed_check(src, ld, n, outs, packed, packed_bytes, &need);
+    if (rc != HBFP_OK) return rc;
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     if (encode_pack_ok(src, ld, n, outs, packed)) return launch_encode_pack(src, ld, n, outs, packed, s);
@@ -367,6 +375,58 @@ int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *c
     for (int i = 0; i < n && rc == HBFP_OK; ++i)
         if (packed[i]) rc = pack_one(outs[i], packed[i], s);
     return rc;
+}
+
+int hbfp_encode_packed_batch_workspace(int njobs, const hbfp_encode_job *jobs, size_t *bytes) {
+    if (!bytes || !jobs || njobs < 1 || njobs > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
+    *bytes = 0;
+    for (int j = 0; j < njobs; ++j) {
+        size_t b = 0;
+        int rc = encode_multi_check(jobs[j].n, jobs[j].outs, &b);
+        if (rc != HBFP_OK) return rc;
+        *bytes = b > *bytes ? b : *bytes;       // the sources are converted one after the other when they need it
+    }
+    return HBFP_OK;
+}
+
+int hbfp_encode_packed_batch(int njobs, const hbfp_encode_job *jobs, void *workspace, size_t ws_bytes, void *stream) {
+    if (!jobs || njobs < 1 || njobs > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
+    size_t need = 0;
+    for (int j = 0; j < njobs; ++j) {
+        size_t b = 0;
+        int rc = encode_packed_check(jobs[j].src, jobs[j].ld, jobs[j].n, jobs[j].outs, jobs[j].packed, jobs[j].packed_bytes, &b);
+        if (rc != HBFP_OK) return rc;
+        need = b > need ? b : need;
+    }
+    if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    // sources that the fused kernel takes, with equal rounding and limb counts, share launches; the others go one by one
+    const float *src[HBFP_BATCH_MAX];
+    int64_t ld[HBFP_BATCH_MAX];
+    int n[HBFP_BATCH_MAX];
+    const hbfp_tensor *const *outs[HBFP_BATCH_MAX];
+    void *const *packed[HBFP_BATCH_MAX];
+    bool done[HBFP_BATCH_MAX] = {};
+    for (int j = 0; j < njobs; ++j) {
+        if (done[j] || !encode_pack_ok(jobs[j].src, jobs[j].ld, jobs[j].n, jobs[j].outs, jobs[j].packed)) continue;
+        int m = 0;
+        for (int k = j; k < njobs; ++k) {
+            if (done[k] || !encode_pack_ok(jobs[k].src, jobs[k].ld, jobs[k].n, jobs[k].outs, jobs[k].packed)) continue;
+            src[m] = jobs[k].src, ld[m] = jobs[k].ld, n[m] = jobs[k].n, outs[m] = jobs[k].outs, packed[m] = jobs[k].packed;
+            if (!encode_pack_batch_ok(m + 1, outs)) continue;
+            done[k] = true;
+            ++m;
+        }
+        int rc = launch_encode_pack_batch(m, src, ld, n, outs, packed, s);
+        if (rc != HBFP_OK) return rc;
+    }
+    for (int j = 0; j < njobs; ++j) {
+        if (done[j]) continue;
+        int rc = hbfp_encode_packed(jobs[j].src, jobs[j].ld, jobs[j].n, jobs[j].outs, jobs[j].packed, jobs[j].packed_bytes, workspace,
+                                    ws_bytes, stream);
+        if (rc != HBFP_OK) return rc;
+    }
+    return HBFP_OK;
 }
 
 int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,

@@ -40,7 +40,14 @@ struct EpOut {
 struct EpParams {
     const float *src;
     int64_t ld, rows, cols;
+    int32_t gx, gy;              // regions along the columns and the rows that this source needs
     EpOut o[2];
+};
+// several source matrices in one launch (blockIdx.z picks the source): the workgroups of the second start as those of the
+// first retire, which a kernel boundary would not allow
+constexpr int kEpBatch = 4;
+struct EpBatch {
+    EpParams p[kEpBatch];
 };
 
 template <int CTRL>
@@ -55,8 +62,10 @@ __device__ __forceinline__ uint32_t ep_pack4(int a, int b, int c, int d) {
 }
 
 template <int ROUND, int L>
-__global__ __launch_bounds__(kEpThreads, 4) void encode_pack_kernel(const EpParams p) {
+__global__ __launch_bounds__(kEpThreads, 4) void encode_pack_kernel(const EpBatch batch) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const EpParams &p = batch.p[blockIdx.z];
+    if ((int)blockIdx.x >= p.gx || (int)blockIdx.y >= p.gy) return;       // the grid is that of the largest source
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int j = lane & 7, h = (lane >> 3) & 1, tw = lane >> 4;
     const int tcl = (wave & 1) * 4 + tw;                                  // tile column of the region
@@ -277,7 +286,9 @@ bool encode_pack_ok(const float *src, int64_t ld, int n, const hbfp_tensor *cons
     return true;
 }
 
-int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed, hipStream_t s) {
+// fills the parameters of one source; marks its packed buffers
+static int ep_params_of(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed, hipStream_t s,
+                        EpParams *out) {
     const hbfp_tensor *f = outs[0];
     EpParams p = {};
     p.src = src;
@@ -320,20 +331,50 @@ int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *c
             ext_cols = rext > ext_cols ? rext : ext_cols;
         }
     }
-    const dim3 grid((unsigned)ceil_div(ext_cols, kEpRegion), (unsigned)ceil_div(ext_rows, kEpRegion));
-    const int L = limbs_of(f->mant_bits);
+    p.gx = (int32_t)ceil_div(ext_cols, kEpRegion);
+    p.gy = (int32_t)ceil_div(ext_rows, kEpRegion);
+    *out = p;
+    return HBFP_OK;
+}
+
+// the instantiation that a source's outputs need: rounding and limb count
+static int ep_which(const hbfp_tensor *f) { return (f->rounding ? 2 : 0) + (limbs_of(f->mant_bits) - 1); }
+
+bool encode_pack_batch_ok(int nsrc, const hbfp_tensor *const *const *outs) {
+    if (nsrc < 1 || nsrc > kEpBatch) return false;
+    for (int i = 1; i < nsrc; ++i)
+        if (ep_which(outs[i][0]) != ep_which(outs[0][0])) return false;
+    return true;
+}
+
+// nsrc sources, each of which encode_pack_ok accepts, with equal rounding and limb counts (encode_pack_batch_ok)
+int launch_encode_pack_batch(int nsrc, const float *const *src, const int64_t *ld, const int *n, const hbfp_tensor *const *const *outs,
+                             void *const *const *packed, hipStream_t s) {
+    EpBatch b = {};
+    int gx = 0, gy = 0;
+    for (int i = 0; i < nsrc; ++i) {
+        const int rc = ep_params_of(src[i], ld[i], n[i], outs[i], packed[i], s, &b.p[i]);
+        if (rc != HBFP_OK) return rc;
+        gx = b.p[i].gx > gx ? b.p[i].gx : gx;
+        gy = b.p[i].gy > gy ? b.p[i].gy : gy;
+    }
+    const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)nsrc);
     static std::atomic<bool> configured[4];
     const void *const kernels[4] = {reinterpret_cast<const void *>(&encode_pack_kernel<0, 1>), reinterpret_cast<const void *>(&encode_pack_kernel<0, 2>),
                                     reinterpret_cast<const void *>(&encode_pack_kernel<1, 1>), reinterpret_cast<const void *>(&encode_pack_kernel<1, 2>)};
-    const int which = (f->rounding ? 2 : 0) + (L - 1);
+    const int which = ep_which(outs[0][0]);
     if (allow_dynamic_lds(configured[which], kernels[which], kEpLds) != HBFP_OK) return HBFP_ERR_LAUNCH;
     switch (which) {
-        case 0: hipLaunchKernelGGL((encode_pack_kernel<0, 1>), grid, dim3(kEpThreads), kEpLds, s, p); break;
-        case 1: hipLaunchKernelGGL((encode_pack_kernel<0, 2>), grid, dim3(kEpThreads), kEpLds, s, p); break;
-        case 2: hipLaunchKernelGGL((encode_pack_kernel<1, 1>), grid, dim3(kEpThreads), kEpLds, s, p); break;
-        default: hipLaunchKernelGGL((encode_pack_kernel<1, 2>), grid, dim3(kEpThreads), kEpLds, s, p); break;
+        case 0: hipLaunchKernelGGL((encode_pack_kernel<0, 1>), grid, dim3(kEpThreads), kEpLds, s, b); break;
+        case 1: hipLaunchKernelGGL((encode_pack_kernel<0, 2>), grid, dim3(kEpThreads), kEpLds, s, b); break;
+        case 2: hipLaunchKernelGGL((encode_pack_kernel<1, 1>), grid, dim3(kEpThreads), kEpLds, s, b); break;
+        default: hipLaunchKernelGGL((encode_pack_kernel<1, 2>), grid, dim3(kEpThreads), kEpLds, s, b); break;
     }
     return launch_status();
+}
+
+int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed, hipStream_t s) {
+    return launch_encode_pack_batch(1, &src, &ld, &n, &outs, &packed, s);
 }
 
 }  // namespace hbfp

@@ -115,6 +115,9 @@ int mx_pack_begin(void *packed, hipStream_t s, int32_t *mark);
 // encode_pack.hip: conversion and packing in one kernel (blocks of 24 along k, up to two outputs from one read)
 bool encode_pack_ok(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed);
 int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *const *outs, void *const *packed, hipStream_t s);
+bool encode_pack_batch_ok(int nsrc, const hbfp_tensor *const *const *outs);
+int launch_encode_pack_batch(int nsrc, const float *const *src, const int64_t *ld, const int *n, const hbfp_tensor *const *const *outs,
+                             void *const *const *packed, hipStream_t s);
 bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);
 bool gemm_mx_group_ok(int n, const GemmArgs *args);
 bool mx_encoded_output_ok(const hbfp_tensor &out);

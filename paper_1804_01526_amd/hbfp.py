@@ -45,6 +45,12 @@ class Conv2d(ctypes.Structure):
         return ((self.h + 2 * self.pad_h - self.r) // self.stride_h + 1, (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1)
 
 
+class EncodeJob(ctypes.Structure):
+    """hbfp_encode_job: one source of hbfp_encode_packed_batch."""
+    _fields_ = [("src", ctypes.c_void_p), ("ld", ctypes.c_int64), ("n", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("outs", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("packed_bytes", ctypes.c_void_p)]
+
+
 class TensorDesc(ctypes.Structure):
     """hbfp_tensor: an encoded operand (layout in include/hbfp.h)."""
     _fields_ = [("mant", ctypes.c_void_p), ("exps", ctypes.c_void_p),
@@ -106,11 +112,13 @@ def _load():
     lib.hbfp_encode_multi.argtypes = [vp, i64, i32, ctypes.POINTER(T), vp, sz, vp]
     lib.hbfp_encode_packed_workspace.argtypes = [i32, ctypes.POINTER(T), ctypes.POINTER(sz)]
     lib.hbfp_encode_packed.argtypes = [vp, i64, i32, ctypes.POINTER(T), ctypes.POINTER(vp), ctypes.POINTER(sz), vp, sz, vp]
+    lib.hbfp_encode_packed_batch_workspace.argtypes = [i32, ctypes.POINTER(EncodeJob), ctypes.POINTER(sz)]
+    lib.hbfp_encode_packed_batch.argtypes = [i32, ctypes.POINTER(EncodeJob), vp, sz, vp]
     lib.hbfp_probe_matrix_rate.argtypes = [i32, vp, i32, i32, vp, vp, vp]
     lib.hbfp_probe_matrix_rate.restype = i32
     lib.hbfp_weight_update_workspace.argtypes = [T, T, T, ctypes.POINTER(sz)]
     lib.hbfp_weight_update.argtypes = [T, vp, i64, ctypes.c_float, T, T, vp, sz, vp]
-    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_encode_packed_workspace", "hbfp_encode_packed", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
+    for name in ("hbfp_gemm_batch_workspace", "hbfp_gemm_batch", "hbfp_gemm_bfp_workspace", "hbfp_gemm_bfp", "hbfp_encode_im2col", "hbfp_encode_multi_workspace", "hbfp_encode_multi", "hbfp_encode_packed_workspace", "hbfp_encode_packed", "hbfp_encode_packed_batch_workspace", "hbfp_encode_packed_batch", "hbfp_weight_update_workspace", "hbfp_weight_update", "hbfp_plan", "hbfp_encode_workspace", "hbfp_encode", "hbfp_encode_static", "hbfp_decode", "hbfp_gemm_workspace",
                  "hbfp_gemm", "hbfp_gemm_select_workspace", "hbfp_gemm_select", "hbfp_pack_bytes", "hbfp_pack",
                  "hbfp_gemm_packed_workspace", "hbfp_gemm_packed", "hbfp_gemm_packed_batch_workspace", "hbfp_gemm_packed_batch", "hbfp_gemm_partials", "hbfp_gemm_partials_window", "hbfp_gemm_f32_workspace",
                  "hbfp_gemm_f32"):
@@ -492,6 +500,42 @@ def encode_packed(src: torch.Tensor, outs, packed, workspace: Optional[torch.Ten
     _check(_lib.hbfp_encode_packed(_dev_ptr(src), ld, n, _desc_array(outs), ptrs, sizes, _dev_ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_packed")
     return outs
+
+
+def _encode_jobs(sources):
+    """sources: sequence of (src, outs, packed); returns the job array and the objects that its pointers refer to."""
+    jobs, keep = (EncodeJob * len(sources))(), []
+    for j, (src, outs, packed) in enumerate(sources):
+        assert src.is_cuda and src.dtype == torch.float32 and src.dim() == 2 and src.stride(1) == 1
+        rows, cols = src.shape
+        n = len(outs)
+        descs = _desc_array(outs)
+        ptrs = (ctypes.c_void_p * n)(*[None if b is None else b.data_ptr() for b in packed])
+        sizes = (ctypes.c_size_t * n)(*[0 if b is None else b.numel() for b in packed])
+        keep += [descs, ptrs, sizes]
+        jobs[j].src, jobs[j].ld, jobs[j].n = src.data_ptr(), (src.stride(0) if rows > 1 else max(src.stride(0), cols)), n
+        jobs[j].outs = ctypes.cast(descs, ctypes.c_void_p)
+        jobs[j].packed = ctypes.cast(ptrs, ctypes.c_void_p)
+        jobs[j].packed_bytes = ctypes.cast(sizes, ctypes.c_void_p)
+    return jobs, keep
+
+
+def encode_packed_batch_workspace(sources) -> int:
+    jobs, keep = _encode_jobs(sources)
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_packed_batch_workspace(len(sources), jobs, ctypes.byref(n)), "hbfp_encode_packed_batch_workspace")
+    return int(n.value)
+
+
+def encode_packed_batch(sources, workspace: Optional[torch.Tensor] = None, stream=None):
+    """hbfp_encode_packed_batch: sources is a sequence of (src, outs, packed), each as the arguments of encode_packed."""
+    jobs, keep = _encode_jobs(sources)
+    need = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_packed_batch_workspace(len(sources), jobs, ctypes.byref(need)), "hbfp_encode_packed_batch_workspace")
+    workspace = _workspace(int(need.value), sources[0][0].device, workspace)
+    _check(_lib.hbfp_encode_packed_batch(len(sources), jobs, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                         _stream_ptr(stream)), "hbfp_encode_packed_batch")
+    return [s[1] for s in sources]
 
 
 def probe_matrix_rate(instruction: int, words: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor,

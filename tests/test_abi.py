@@ -329,6 +329,48 @@ def test_gemm_packed_batch_validation():
         assert call([p8, p8], ws=None) == hbfp.ERR_WORKSPACE
 
 
+def test_encode_packed_batch_validation():
+    """hbfp_encode_packed_batch: the checks of hbfp_encode_packed for every job, all before the first launch."""
+    lib = hbfp._lib
+
+    def desc(m, rows, cols, axis, br, bc):
+        d = hbfp.plan(hbfp.make_format(m, br, bc), rows, cols, axis)
+        d.mant, d.exps = 0x10000, 0x20000
+        return d
+
+    def job(outs, src=0x100000, ld=None, packed=0x4000, size=1 << 40):
+        n = len(outs)
+        descs = hbfp._desc_array(outs)
+        ptrs, sizes = (ctypes.c_void_p * n)(*[packed] * n), (ctypes.c_size_t * n)(*[size] * n)
+        j = hbfp.EncodeJob(src, outs[0].src_cols if ld is None else ld, n, 0, ctypes.cast(descs, ctypes.c_void_p),
+                           ctypes.cast(ptrs, ctypes.c_void_p), ctypes.cast(sizes, ctypes.c_void_p))
+        return j, (descs, ptrs, sizes)
+
+    def call(jobs, n=None):
+        arr = (hbfp.EncodeJob * len(jobs))(*[j[0] for j in jobs])
+        return lib.hbfp_encode_packed_batch(len(jobs) if n is None else n, arr, None, 0, None)
+
+    x = [desc(8, 96, 240, 1, 1, 24), desc(8, 96, 240, 0, 24, 1)]
+    w = [desc(8, 240, 48, 0, 24, 24)]
+    good = job(x)
+    assert call([good] * 5) == hbfp.ERR_ARG and call([good], n=0) == hbfp.ERR_ARG
+    assert lib.hbfp_encode_packed_batch(1, None, None, 0, None) == hbfp.ERR_ARG
+    assert call([good, job(w, src=0)]) == hbfp.ERR_ARG and call([good, job(w, src=0x100002)]) == hbfp.ERR_ARG
+    assert call([good, job(w, ld=47)]) == hbfp.ERR_ARG
+    assert call([good, job(w, packed=0x4010)]) == hbfp.ERR_ARG
+    assert call([good, job(w, size=1024)]) == hbfp.ERR_WORKSPACE
+    assert call([good, job([desc(16, 240, 48, 0, 24, 24)])]) == hbfp.ERR_FORMAT          # too wide for the packed form
+    assert call([good, job([x[0], w[0]])]) == hbfp.ERR_LAYOUT                             # outputs of different source shapes
+    # a job whose conversion needs scratch (one exponent per matrix) makes the batch need it
+    whole = [desc(8, 96, 240, 1, 96, 240)]
+    scratch_job = job(whole)                                                              # holds the arrays the job points to
+    arr = (hbfp.EncodeJob * 2)(good[0], scratch_job[0])
+    need = ctypes.c_size_t(0)
+    assert lib.hbfp_encode_packed_batch_workspace(2, arr, ctypes.byref(need)) == hbfp.OK
+    assert need.value == hbfp.encode_packed_workspace(whole) and need.value > 0
+    assert call([good, scratch_job]) == hbfp.ERR_WORKSPACE
+
+
 def test_gemm_bfp_validation():
     """hbfp_gemm_bfp: the output plan must be that of an A->rows x B->rows matrix; the workspace always holds the FP32
     product (for the int8 kernels that stand by, or as the route to the conversion kernels) plus the product's own

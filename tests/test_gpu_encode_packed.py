@@ -157,3 +157,63 @@ def test_product_of_operands_packed_by_the_conversion(hb, M, K, N):
         err = rel_fro(C.cpu().numpy(), want)
         print(f"        rel fro err = {err:.3e}", flush=True)
         assert err <= 1e-5
+
+
+def _alloc_outputs(hb, shape, specs):
+    fmts = [hb.make_format(m, br, bc, rnd, seed) for br, bc, m, rnd, seed, _ in specs]
+    outs = [hb.alloc(f, shape[0], shape[1], s[5]) for f, s in zip(fmts, specs)]
+    packed = [torch.full((hb.pack_bytes(o.desc),), 0x5a, dtype=torch.uint8, device="cuda") for o in outs]
+    for o in outs:
+        o.mant.fill_(0x33)
+        o.exps.fill_(0x33)
+    return outs, packed
+
+
+BATCHES = [
+    # sources of different sizes in one launch (the grid is that of the largest): activations and weight tiles
+    [((300, 520), [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)]), ((520, 280), [(24, 24, 8, 0, 0, 0), (24, 24, 8, 0, 0, 1)])],
+    # four sources, one output or two, ragged, down to a single tile
+    [((24, 24), [(24, 24, 7, 0, 0, 1)]), ((1000, 1004), [(1, 24, 8, 0, 0, 1)]), ((97, 388), [(24, 1, 6, 0, 0, 0), (1, 24, 6, 0, 0, 1)]),
+     ((1, 4), [(1, 24, 8, 0, 0, 1)])],
+    # stochastic rounding; one-limb mantissas
+    [((260, 300), [(1, 24, 8, 1, 77, 1), (24, 1, 8, 1, 78, 0)]), ((200, 196), [(24, 24, 8, 1, 5, 0)])],
+    [((260, 300), [(24, 24, 4, 0, 0, 0), (1, 24, 5, 0, 0, 1)]), ((500, 100), [(24, 1, 5, 0, 0, 0)])],
+    # sources that cannot share a launch: different rounding, different limb counts, a format of the separate kernels
+    [((260, 300), [(1, 24, 8, 0, 0, 1)]), ((200, 196), [(24, 24, 8, 1, 5, 0)]), ((192, 192), [(1, 24, 4, 0, 0, 1)]),
+     ((200, 320), [(1, 32, 8, 0, 0, 1), (32, 1, 8, 0, 0, 0)])],
+]
+
+
+@pytest.mark.parametrize("batch", range(len(BATCHES)))
+def test_batch_of_sources_equals_the_conversions_one_by_one(hb, batch):
+    """hbfp_encode_packed_batch: every stored operand, limb plane and mark equal to what hbfp_encode_packed writes for
+    that source alone (which the tests above hold against the oracle)."""
+    jobs = BATCHES[batch]
+    print(f"[encode_packed_batch] {jobs}", flush=True)
+    srcs = [torch.from_numpy(_rand(shape, 31 * i + batch, spread=1 + i)).cuda() for i, (shape, _) in enumerate(jobs)]
+    got = [_alloc_outputs(hb, shape, specs) for shape, specs in jobs]
+    hb.encode_packed_batch([(s, o, p) for s, (o, p) in zip(srcs, got)])
+    torch.cuda.synchronize()
+    for s, (shape, specs), (outs, packed) in zip(srcs, jobs, got):
+        w_outs, w_packed = _alloc_outputs(hb, shape, specs)
+        hb.encode_packed(s, w_outs, w_packed)
+        torch.cuda.synchronize()
+        for o, pk, wo, wpk in zip(outs, packed, w_outs, w_packed):
+            assert torch.equal(o.mant, wo.mant) and torch.equal(o.exps, wo.exps), f"stored operand differs: {shape} {specs}"
+            end = _planes_end(o.desc)
+            assert torch.equal(pk[256:end], wpk[256:end]), f"limb planes differ: {shape} {specs}"
+            assert torch.equal(pk[end:], wpk[end:]), "bytes past the planes were written"
+            assert _flagged(pk) == _flagged(wpk)
+
+
+def test_batch_marks_each_source_on_its_own(hb):
+    """A heavy-tailed source next to a plain one: only the first is marked."""
+    rng = np.random.default_rng(3)
+    heavy = torch.from_numpy((rng.standard_t(1.5, size=(300, 400)) * 1e-3).astype(np.float32)).cuda()
+    plain = torch.from_numpy(_rand((400, 300), 4, 0)).cuda()
+    specs = [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)]
+    a, b = _alloc_outputs(hb, (300, 400), specs), _alloc_outputs(hb, (400, 300), specs)
+    for first, second in (((heavy,) + a, (plain,) + b), ((plain,) + b, (heavy,) + a)):
+        hb.encode_packed_batch([first, second])
+        torch.cuda.synchronize()
+        assert all(_flagged(p) for p in a[1]) and not any(_flagged(p) for p in b[1])

@@ -95,22 +95,25 @@ def _check_product(hb, name, ta, tb, oa, ob, fa, fb, C, rows, kernel_is_scaled, 
 
 
 def test_config4_step_as_the_benchmark_runs_it(hb):
-    """The three products of config 4 from operands converted and packed by hbfp_encode_packed (one call per FP32
-    matrix) and multiplied by hbfp_gemm_packed (forward) and hbfp_gemm_packed_batch (both backward products in one launch);
+    """The three products of config 4 from operands converted and packed by hbfp_encode_packed_batch (input and
+    weights) and hbfp_encode_packed (gradient) and multiplied by hbfp_gemm_packed (forward) and hbfp_gemm_packed_batch (both backward products in one launch);
     then the forward product once more on the int8 kernels."""
     import synth
     X, W, dY = synth.c4_linear()
     rng = np.random.default_rng(5)
     act_r, act_c, tile = (1, 24, 8), (24, 1, 8), (24, 24, 8)
-    enc = {}
+    enc, jobs = {}, {}
     for name, src, specs in (("x", X, [(act_r, 1), (act_c, 0)]), ("w", W, [(tile, 0), (tile, 1)]), ("dy", dY, [(act_r, 1), (act_c, 0)])):
         g = torch.from_numpy(src).cuda()
         outs = [hb.alloc(hb.make_format(f[2], f[0], f[1]), 4096, 4096, ax) for f, ax in specs]
         packs = [torch.empty(hb.pack_bytes(o.desc), dtype=torch.uint8, device="cuda") for o in outs]
-        hb.encode_packed(g, outs, packs)
+        jobs[name] = (g, outs, packs)
         enc[name] = list(zip(outs, packs))
-        del g
+    # as in the benchmark's step: input and weights in one launch, the gradient on its own
+    hb.encode_packed_batch([jobs["x"], jobs["w"]])
+    hb.encode_packed(*jobs["dy"])
     torch.cuda.synchronize()
+    del jobs
     for _, (o, pk) in ((k, v) for k, vs in enc.items() for v in vs):
         w = pk[:8].view(torch.int32).cpu().numpy()
         assert w[0] != w[1], "config 4's operands are expected to pack densely (no fallback)"

@@ -783,8 +783,7 @@ def test_training_step_route_in_a_replayed_graph(hb):
     stream = torch.cuda.Stream()
 
     def step(s):
-        hb.encode_packed(X, x, px, stream=s)
-        hb.encode_packed(W, w, pw, stream=s)
+        hb.encode_packed_batch([(X, x, px), (W, w, pw)], stream=s)
         hb.gemm_packed(x[0], px[0], w[0], pw[0], out=Y, workspace=ws1, stream=s)
         hb.encode_packed(dY, g, pg, stream=s)
         hb.gemm_packed_batch(pair(), [dX, dW], workspace=ws2, stream=s)
