@@ -21,6 +21,7 @@ events on the launch stream, and the CPU oracle timed on a bounded sample.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -120,15 +121,16 @@ def _linear_layer(torch, hbfp, synth):
         if timer:
             b.record()
 
+    source = lambda key: (groups[key][1], [enc[k] for k in groups[key][2]], [packed[k] for k in groups[key][2]])
+
     def convert(timer, key):
-        name, src, names = groups[key]
-        bracket(timer, name, lambda: hbfp.encode_packed(src, [enc[k] for k in names], [packed[k] for k in names]))
+        bracket(timer, groups[key][0], lambda: hbfp.encode_packed(*source(key)))
 
     def step(timer=None):
         # the order of a training step: inputs and weights, the forward product, then the gradient that arrives from
         # the layer above and the two backward products that wait for it, which share one launch
-        convert(timer, "x")
-        convert(timer, "w")
+        # (input and weights do not wait for each other: one call, one launch)
+        bracket(timer, "encode_x_w", lambda: hbfp.encode_packed_batch([source("x"), source("w")]))
         bracket(timer, "gemm", lambda: hbfp.gemm_packed(*product(0), out=outs[0], workspace=ws_fwd))
         convert(timer, "dy")
         bracket(timer, "gemm_pair", lambda: hbfp.gemm_packed_batch([product(1), product(2)], outs[1:], workspace=ws_bwd))
@@ -604,6 +606,11 @@ def main():
     torch.cuda.set_device(0)
 
     step, flops_step, flops_product, shape, outs = _linear_layer(torch, hbfp, synth)
+    # No cyclic garbage collection while launches are being timed (what timeit does): with torch and numpy loaded a
+    # full collection stops the launching thread for 35-50 ms, 70 steps' worth, at a moment that depends on how many
+    # objects the interpreter happened to allocate before.  Reference counting still frees everything the steps create.
+    gc.collect()
+    gc.disable()
     # the first steps after idle, timed for the record (the power management has not settled: by the kernel trace the
     # product kernel takes 126 us at first, 141-146 us for a few steps, then falls to 122 us), then the rest of the
     # untimed steps
@@ -662,8 +669,8 @@ def main():
     product_tops = flops_product / product_ms / 1e9
     # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
     limb_tflops = 4.0 * product_tops
-    enc_act_ms = timer.total_ms("encode_act") / n_bracketed
-    enc_w_ms = timer.total_ms("encode_w") / n_bracketed
+    enc_xw_ms = timer.total_ms("encode_x_w") / n_bracketed
+    enc_dy_ms = timer.total_ms("encode_act") / n_bracketed
     pair_ms = timer.total_ms("gemm_pair") / timer.count("gemm_pair")
     gemm_step_ms = (timer.total_ms("gemm") + timer.total_ms("gemm_pair")) / n_bracketed
 
@@ -681,14 +688,14 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 mantissas as 4-bit limbs in FP6 (E2M3), block-scaled matrix instruction, FP32 accumulate", "data": "synthetic",
         "config": {"workload": "config 4: dense layer M=K=N=4096, BFP8, 1x24 activation blocks, 24x24 weight tiles, "
-                               "forward + data gradient + weight gradient, all six operand encodes included (3 conversion calls, 3 products: "
+                               "forward + data gradient + weight gradient, all six operand encodes included (2 conversion calls: input and weights in one launch, then the "
+                               "output gradient; 3 products: "
                                "the forward one alone, the two backward ones in one launch)", "preheat_steps": args.preheat, **shape},
         "pct_int8_peak": round(100.0 * tops / INT8_PEAK_TOPS, 2),
         "ms_per_step_first_steps_after_idle": None if ms_from_idle is None else round(ms_from_idle, 4),
-        "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_activations_x4": round(enc_act_ms, 4),
-                                  "encode_weights_x2": round(enc_w_ms, 4)},
+        "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_input_and_weights_x4": round(enc_xw_ms, 4),
+                                  "encode_output_gradient_x2": round(enc_dy_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
-        "TOPS_incl_activation_encode": round(flops_step / (gemm_step_ms + enc_act_ms) / 1e9, 2),
         # Roofline of the dominant kernel against the peak the metric names: effective operations 2*M*N*K, counted once
         # per mantissa product, over the product kernel's launch time, against the published dense int8 matrix peak.
         # The kernel reaches them with 4 limb products per mantissa product on the FP6 rate of the block-scaled
@@ -717,14 +724,14 @@ def main():
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(e["GBps"] / HBM_PEAK_GBPS, 4),
                                   "traffic": TRAFFIC_ENCODE_C2_M8_BYTES, "traffic_unit": "bytes per launch (HBM, measured)",
                                   "algorithmic_bytes": e["bytes"], "avg_launch_ms": e["ms"]}
-        extra.update(_gemm_side_configs(torch, hbfp, synth))
-        extra.update(_weight_update_config4(torch, hbfp, synth))
-        extra.update(_kernel_families(torch, hbfp))
-        extra.update(_paper_formats(torch, hbfp))
-        extra.update(_batched_products(torch, hbfp))
-        extra.update(_encoded_output(torch, hbfp))
-        extra.update(_heavy_tails(torch, hbfp))
+        for section in (lambda: _gemm_side_configs(torch, hbfp, synth), lambda: _weight_update_config4(torch, hbfp, synth),
+                        lambda: _kernel_families(torch, hbfp), lambda: _paper_formats(torch, hbfp),
+                        lambda: _batched_products(torch, hbfp), lambda: _encoded_output(torch, hbfp),
+                        lambda: _heavy_tails(torch, hbfp)):
+            gc.collect()                     # between the sections, not inside their timed loops
+            extra.update(section())
         out["extra"] = extra
+    gc.enable()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(synth)
     print(json.dumps(out))
