@@ -344,7 +344,7 @@ static int pack_one(const hbfp_tensor *t, void *packed, hipStream_t s) {
     g.nblk = t->nblk;
     g.kdim = t->kdim;
     g.mA = g.mB = t->mant_bits;
-    return launch_mx_pack(g, packed, nullptr, s);
+    return bf_operand(t->mant_bits) ? launch_bf_pack(g, packed, nullptr, s) : launch_mx_pack(g, packed, nullptr, s);
 }
 
 // argument checks of hbfp_encode_packed for one source; *need: bytes of its conversion's scratch
@@ -357,7 +357,7 @@ static int encode_packed_check(const float *src, int64_t ld, int n, const hbfp_t
         if (!packed[i]) continue;
         if ((uintptr_t)packed[i] & 255) return HBFP_ERR_ARG;
         if (outs[i]->mant_bits > 12) return HBFP_ERR_FORMAT;
-        if (packed_bytes[i] < mx_packed_bytes(outs[i]->rows, outs[i]->kpad, outs[i]->mant_bits)) return HBFP_ERR_WORKSPACE;
+        if (packed_bytes[i] < packed_operand_bytes(outs[i]->rows, outs[i]->kpad, outs[i]->mant_bits)) return HBFP_ERR_WORKSPACE;
         if (ceil_div(outs[i]->rows, 256) * 8 * ceil_div(outs[i]->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
     }
     return HBFP_OK;
@@ -828,7 +828,7 @@ int hbfp_pack_bytes(const hbfp_tensor *t, size_t *bytes) {
     const int rc = check_tensor(t, false);
     if (rc != HBFP_OK) return rc;
     if (t->mant_bits > 12) return HBFP_ERR_FORMAT;
-    *bytes = mx_packed_bytes(t->rows, t->kpad, t->mant_bits);
+    *bytes = packed_operand_bytes(t->rows, t->kpad, t->mant_bits);
     return HBFP_OK;
 }
 
@@ -837,9 +837,18 @@ int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream) {
     if (rc != HBFP_OK) return rc;
     if (t->mant_bits > 12) return HBFP_ERR_FORMAT;
     if (!packed || ((uintptr_t)packed & 255)) return HBFP_ERR_ARG;
-    if (bytes < mx_packed_bytes(t->rows, t->kpad, t->mant_bits)) return HBFP_ERR_WORKSPACE;
+    if (bytes < packed_operand_bytes(t->rows, t->kpad, t->mant_bits)) return HBFP_ERR_WORKSPACE;
     if (ceil_div(t->rows, 256) * 8 * ceil_div(t->kpad / 64, 4) > 0x7fffffff) return HBFP_ERR_ARG;
     return pack_one(t, packed, (hipStream_t)stream);
+}
+
+// The packed form of an operand depends on its mantissa width alone (6..9 bits: bf16 planes, otherwise limb planes), so
+// a product of packed operands runs on the bf16 kernel, on the block-scaled kernel, or, when the two forms meet, on the
+// int8 kernels from the stored operands.
+enum { kPackedMx = 0, kPackedBf = 1, kPackedMixed = 2 };
+static int packed_kind(const hbfp_tensor *A, const hbfp_tensor *B) {
+    const bool a = bf_operand(A->mant_bits), b = bf_operand(B->mant_bits);
+    return a && b ? kPackedBf : a == b ? kPackedMx : kPackedMixed;
 }
 
 int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
@@ -862,10 +871,14 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
     g.ldc = ldc;
     g.beta = beta;
     if (!gemm_mx_possible(g)) return HBFP_ERR_ARG;
-    rc = launch_mx_product(g, packed_a, packed_b, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
+    const int kind = packed_kind(A, B);
+    if (kind == kPackedBf) rc = launch_bf_products(1, &g, &packed_a, &packed_b, (hipStream_t)stream);
+    else if (kind == kPackedMx) rc = launch_mx_product(g, packed_a, packed_b, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
     if (rc != HBFP_OK) return rc;
-    g.run_a = (const int *)packed_a;
-    g.run_b = (const int *)packed_b;
+    if (kind != kPackedMixed) {      // the int8 kernels stand by; for a mixed pair they are the product
+        g.run_a = (const int *)packed_a;
+        g.run_b = (const int *)packed_b;
+    }
     if (A->mant_bits > 8) return launch_gemm_limb(g, workspace, (hipStream_t)stream);
     return launch_gemm_i8(g, workspace, (hipStream_t)stream);
 }
@@ -905,7 +918,9 @@ int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const
         g[i].beta = beta;
         if (!gemm_mx_possible(g[i])) return HBFP_ERR_ARG;
         if ((A[i]->mant_bits > 8) != (A[0]->mant_bits > 8) || !mx_same_limbs(g[i], g[0])) return HBFP_ERR_FORMAT;
+        if (packed_kind(A[i], B[i]) != packed_kind(A[0], B[0])) return HBFP_ERR_FORMAT;
     }
+    const int kind = packed_kind(A[0], B[0]);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     void *standby[HBFP_BATCH_MAX];
@@ -916,12 +931,15 @@ int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const
             w += part[i];
         }
     }
-    int rc = launch_mx_products(n, g, packed_a, packed_b, standby, s);
+    int rc = kind == kPackedBf ? launch_bf_products(n, g, packed_a, packed_b, s)
+             : kind == kPackedMx ? launch_mx_products(n, g, packed_a, packed_b, standby, s) : HBFP_OK;
     if (rc != HBFP_OK) return rc;
     char *ws = (char *)workspace;
     for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
-        g[i].run_a = (const int *)packed_a[i];
-        g[i].run_b = (const int *)packed_b[i];
+        if (kind != kPackedMixed) {
+            g[i].run_a = (const int *)packed_a[i];
+            g[i].run_b = (const int *)packed_b[i];
+        }
         rc = A[i]->mant_bits > 8 ? launch_gemm_limb(g[i], ws, s) : launch_gemm_i8(g[i], ws, s);
         if (rc != HBFP_OK) return rc;
         ws += part[i];

@@ -14,6 +14,7 @@
 // padding; after one barrier the workgroup streams the stored operand out in 16-byte pieces and packs the limb planes
 // from the same tile with the arithmetic of the pack kernel (mx_pack.h).  Two workgroups share a compute unit (2 x 78 KB
 // of LDS, 128 registers), so one converts while the other loads or stores.
+#include "bf_pack.h"
 #include "bfp_device.h"
 #include "mx_pack.h"
 
@@ -260,8 +261,20 @@ __global__ __launch_bounds__(kEpThreads, 4) void encode_pack_kernel(const EpBatc
                 const int e = el[r16 * 128 + (jl * 43 >> 7)];    // jl / 3 for jl < 24
                 ex[oc] = (raw[oc][0] | raw[oc][1]) ? (e > 254 ? 254 : e) : 255;
             }
-            uint8_t *chunk = o.planes + (((rt >> 3) * o.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
-            bad |= pack_half_group_dense<L>(raw, ex, o.m, chunk, (r16 & 1) * 16 + r4 + 32 * (q >> 1), q);
+            if constexpr (L == 2) {
+                // 6..8-bit mantissas: bf16 planes (bf_pack.h), an octet of one row is 16 bytes of one half k-step of 32
+#pragma unroll
+                for (int oc = 0; oc < 2; ++oc) {
+                    const int jl = ksl * 8 + q * 2 + oc;
+                    const int e = el[r16 * 128 + (jl * 43 >> 7)];
+                    bad |= ex[oc] != 255 && !bf_exponent_ok(e);
+                    *reinterpret_cast<v4u *>(o.planes + bf_piece_offset(rt, 2 * ks + (q >> 1), 2 * (int64_t)o.ksteps, q & 1, oc,
+                                                                        (r16 & 1) * 16 + r4)) = bf_octet_i8(raw[oc], e, o.m);
+                }
+            } else {
+                uint8_t *chunk = o.planes + (((rt >> 3) * o.ksteps + ks) * kRowTiles + (rt & 7)) * (int64_t)chunk_bytes(L);
+                bad |= pack_half_group_dense<L>(raw, ex, o.m, chunk, (r16 & 1) * 16 + r4 + 32 * (q >> 1), q);
+            }
         }
         if (bad) o.header[0] = o.mark;
     }

@@ -1,0 +1,371 @@
+// BFP matrix product for mantissas of 6 to 9 bits on the bf16 matrix instruction of gfx950 (Eq. (2) of Sec. 4):
+//     C[i][j] = sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k] * mB[j][k]
+//
+// A mantissa of at most 9 bits times its block's power of two is a bf16 number (8 significant bits, the exponent
+// range of the stored exponent byte), so the decode of Eq. (1) is exact in bf16 and v_mfma_f32_32x32x16_bf16 is the
+// arithmetic of Eq. (2) in hardware: it multiplies the 8-bit significands as integers, adds the exponents, and
+// accumulates in FP32 (Sec. 4: accumulation across blocks is in floating point).  One matrix instruction per 16 k
+// does what the block-scaled instruction needs four 4-bit limb products for, at the same instruction rate and at
+// a lower power per product, which is what bounds both kernels on this chip; and blocks whose exponents lie far apart
+// (heavy-tailed gradients) need no other path.
+//
+// pack kernel:    stored operand (int8 / int16 mantissas [rows][kpad], exponent bytes) -> bf16 planes in the register
+//                 order of the matrix instruction (bf_pack.h), blocks of 8, 16 and 24 without their padding.
+// gemm_bf_kernel: 256 x 256 tile of C per workgroup, 8 waves of 64 x 128, four-stage LDS ring of k-steps of 32 filled
+//                 by asynchronous copies of whole stages, one barrier per k-step, operand registers of the next half
+//                 k-step read while the matrix instructions of this one run.
+// Only a non-zero block with an exponent byte above 253 (values from 2^127 on) cannot be packed safely; the pack then
+// marks the header of the packed operand as the block-scaled path does, the product kernel does nothing when either
+// header is marked and the int8 kernels, launched behind it with the opposite condition, compute the product.  Small
+// values need no such care: the instruction takes subnormal bf16 operands and keeps subnormal FP32 sums.
+#include <atomic>
+
+#include "bf_pack.h"
+#include "hbfp_internal.h"
+
+namespace hbfp {
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+
+constexpr int kBfThreads = 512;
+constexpr int kBfStage = 2 * kBfStageBytes;      // A's panel and B's panel of one k-step: 32 KB
+constexpr int kBfRing = 4;
+constexpr int kBfCopies = kBfStage / 1024 / 8;   // copy instructions (1 KB each) per wave and stage
+constexpr int kBfGroup = HBFP_BATCH_MAX;
+
+// ------------------------------------------------------------------------------------------------
+struct BfPackParams {
+    const void *mant;
+    const uint8_t *exps;
+    uint8_t *out;
+    int *header;                 // word 1 = this pack's mark, word 0 = the mark of the last pack that found an exponent out of range
+    int64_t R, kpad, exp_ld;
+    int32_t ksteps;              // k-steps of 32 of the packed operand (a multiple of 4)
+    int32_t chunks32_per_block, m, mark;
+    int32_t ob, noct;            // dense layout: octets per exponent block and in the whole row; ob = 0: as stored
+};
+struct BfPackPair {
+    BfPackParams op[2];
+    uint32_t blocks_a;
+};
+
+// A workgroup of 4 waves packs one row tile of 32 rows over 4 x 64 k; a lane converts 16 consecutive k of one row (two
+// octets) of rows r and r + 16.
+template <typename MT>
+__device__ __forceinline__ void bf_pack_block(const BfPackParams &p, uint32_t block) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
+    const int nk4 = (p.ksteps / 2 + 3) / 4;
+    const int64_t rt = block / nk4;
+    const int ks64 = (int)(block % nk4) * 4 + wave;
+    if (2 * ks64 >= p.ksteps) return;
+    const int q = lane & 3, r4 = lane >> 2;
+    const int ks = 2 * ks64 + (q >> 1), h = q & 1;
+    bool bad = false;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int r32 = hh * 16 + r4;
+        const int64_t row = rt * 32 + r32;
+        const bool live = row < p.R;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            const uint32_t j = (uint32_t)ks64 * 8u + (uint32_t)q * 2u + (uint32_t)o;          // octet of the packed k axis
+            bool there = live;
+            int64_t pos;                                                                       // its first element in the stored row
+            uint32_t b;                                                                        // its exponent block
+            if (p.ob) {
+                there = there && j < (uint32_t)p.noct;
+                b = there ? bf_dense_block_of(j, p.ob) : 0u;
+                pos = there ? (int64_t)b * 32 + 8 * (int)(j - b * (uint32_t)p.ob) : 0;
+            } else {
+                pos = (int64_t)j * 8;
+                b = (j >> 2) / (uint32_t)p.chunks32_per_block;
+            }
+            const int64_t rs = there ? row : 0;                                                // what does not exist reads row 0 and stores zeros
+            const int E = p.exps[rs * p.exp_ld + b];
+            v4u out = {0u, 0u, 0u, 0u};
+            bool any;
+            if constexpr (sizeof(MT) == 1) {
+                const v2i raw = *reinterpret_cast<const v2i *>(reinterpret_cast<const int8_t *>(p.mant) + rs * p.kpad + pos);
+                any = (raw[0] | raw[1]) != 0;
+                if (there) out = bf_octet_i8(raw, E, p.m);
+            } else {
+                const v4i_t raw = *reinterpret_cast<const v4i_t *>(reinterpret_cast<const int16_t *>(p.mant) + rs * p.kpad + pos);
+                any = (raw[0] | raw[1] | raw[2] | raw[3]) != 0;
+                if (there) out = bf_octet_i16(raw, E, p.m);
+            }
+            bad = bad || (there && any && !bf_exponent_ok(E));
+            *reinterpret_cast<v4u *>(p.out + bf_piece_offset(rt, ks, p.ksteps, h, o, r32)) = out;
+        }
+    }
+    if (bad) p.header[0] = p.mark;
+}
+
+template <typename MT>
+__global__ __launch_bounds__(256) void bf_pack_kernel(const BfPackPair q) {
+    if (blockIdx.x < q.blocks_a) bf_pack_block<MT>(q.op[0], blockIdx.x);
+    else bf_pack_block<MT>(q.op[1], blockIdx.x - q.blocks_a);
+}
+
+// ------------------------------------------------------------------------------------------------
+struct BfParams {
+    const uint8_t *pa, *pb;      // bf16 planes of the packed operands
+    const int *ha, *hb;          // their headers: words 0 and 1 equal = marked
+    float *C;
+    int64_t M, N, ldc;
+    int32_t ksteps, tiles_m, tiles_n, beta;
+};
+// Up to kBfGroup independent products in one launch: workgroups first[i] .. first[i + 1] - 1 belong to product i, so the
+// stores of one product's tiles drain under the matrix instructions of the next.
+struct BfGroup {
+    BfParams p[kBfGroup];
+    int32_t first[kBfGroup + 1];
+    int32_t n;
+};
+
+__global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    // which product this workgroup belongs to: selected with constant indices, so that the parameters stay in scalar
+    // registers (the copy instructions take their base addresses from there)
+    BfParams p = g.p[0];
+    int first_wg = 0;
+#pragma unroll
+    for (int i = 1; i < kBfGroup; ++i)
+        if (i < g.n && (int)blockIdx.x >= g.first[i]) {
+            p = g.p[i];
+            first_wg = g.first[i];
+        }
+    if (p.ha[0] == p.ha[1] || p.hb[0] == p.hb[1]) return;      // uniform: the int8 kernels take over
+    int tm, tn;
+    if (!tile_of_workgroup((int)blockIdx.x - first_wg, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave & 3, wn = wave >> 2;
+
+    // ---- copies: a stage is 32 pieces of 1 KB, A's 16 first; wave w moves pieces w, w + 8, w + 16, w + 24.  The source
+    // of a piece advances by one stage of its operand per k-step.
+    const uint32_t voff = lane * 16;
+    const uint8_t *cptr[kBfCopies];
+    uint32_t coff[kBfCopies];
+#pragma unroll
+    for (int i = 0; i < kBfCopies; ++i) {
+        const int byte = (wave + 8 * i) * 1024;
+        coff[i] = byte;
+        cptr[i] = byte < kBfStageBytes ? p.pa + (int64_t)tm * p.ksteps * kBfStageBytes + byte
+                                       : p.pb + (int64_t)tn * p.ksteps * kBfStageBytes + (byte - kBfStageBytes);
+    }
+#define HBFP_BF_COPY_STAGE(ring_)                                                                  \
+    {                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < kBfCopies; ++i) {                                    \
+            async_copy16(cptr[i], voff, (uint32_t)((ring_) * kBfStage) + coff[i]);                 \
+            cptr[i] += kBfStageBytes;                                                              \
+        }                                                                                          \
+    }
+    // ---- operand registers: row tiles 2 wm, 2 wm + 1 of A's panel, column tiles 4 wn .. 4 wn + 3 of B's
+    int abase = lane * 16 + 2 * wm * kBfTileBytes, bbase = lane * 16 + kBfStageBytes + 4 * wn * kBfTileBytes;
+    asm volatile("" : "+v"(abase), "+v"(bbase));
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    v4i_t af[2][2], bf[2][4];
+#define HBFP_BF_READ(buf, base_, h)                                                                                                             \
+    {                                                                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i) af[buf][i] = *reinterpret_cast<const v4i_t *>((base_) + abase + i * kBfTileBytes + (h) * 1024); \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) bf[buf][j] = *reinterpret_cast<const v4i_t *>((base_) + bbase + j * kBfTileBytes + (h) * 1024); \
+    }
+#define HBFP_BF_MFMA(buf, i, j)                                                                                                    \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, af[buf][i]), __builtin_bit_cast(v8bf, bf[buf][j]), \
+                                                        acc[i][j], 0, 0, 0)
+#define HBFP_BF_ROW(buf, i)        \
+    {                              \
+        HBFP_BF_MFMA(buf, i, 0);   \
+        HBFP_BF_MFMA(buf, i, 1);   \
+        HBFP_BF_MFMA(buf, i, 2);   \
+        HBFP_BF_MFMA(buf, i, 3);   \
+    }
+    // Neither the optimiser (memory clobber) nor the instruction scheduler moves LDS reads or matrix instructions
+    // across a fence: the order below is the schedule.
+#define HBFP_BF_FENCE                   \
+    asm volatile("" ::: "memory");      \
+    __builtin_amdgcn_sched_barrier(0)
+    // One k-step.  The registers of its second half are requested first and arrive under the matrix instructions of
+    // the first half.  The hand-over sits before the last row of matrix instructions: wait for this wave's copies of
+    // stage ks + 1, barrier (now every wave's copies of it have landed and every wave has read all of stage ks),
+    // request the first half of stage ks + 1, and hand the buffer of stage ks to the copy of stage ks + 4.
+    // MODE 0: stages ks + 1 .. ks + 3 in flight and a copy to issue; 1: the same, nothing left to copy; 2: two stages
+    // in flight; 3: one; 4: last k-step
+#define HBFP_BF_KSTEP(MODE)                                                                                \
+    {                                                                                                      \
+        const uint8_t *base = lds + ring * kBfStage;                                                       \
+        const int copy_ring = ring;                                                                        \
+        const int next = ring + 1 == kBfRing ? 0 : ring + 1;                                               \
+        const uint8_t *nbase = lds + next * kBfStage;                                                      \
+        HBFP_BF_READ(1, base, 1);                                                                          \
+        HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_ROW(0, 0);                                                                                 \
+        HBFP_BF_ROW(0, 1);                                                                                 \
+        HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_ROW(1, 0);                                                                                 \
+        HBFP_BF_FENCE;                                                                                     \
+        if (MODE != 4) {                                                                                   \
+            if (MODE <= 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kBfCopies) : "memory");            \
+            else if (MODE == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kBfCopies) : "memory");           \
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                          \
+            __builtin_amdgcn_s_barrier();                                                                  \
+            asm volatile("" ::: "memory");                                                                 \
+            HBFP_BF_READ(0, nbase, 0);                                                                     \
+            if (MODE == 0) HBFP_BF_COPY_STAGE(copy_ring);                                                  \
+        }                                                                                                  \
+        HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_ROW(1, 1);                                                                                 \
+        HBFP_BF_FENCE;                                                                                     \
+        ring = next;                                                                                       \
+    }
+    // the number of k-steps is a multiple of 4 (the packed k axis is a multiple of 128)
+    HBFP_BF_COPY_STAGE(0);
+    HBFP_BF_COPY_STAGE(1);
+    HBFP_BF_COPY_STAGE(2);
+    HBFP_BF_COPY_STAGE(3);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * kBfCopies) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    HBFP_BF_READ(0, lds, 0);
+    int ring = 0;
+    for (int ks = 0; ks + kBfRing < p.ksteps; ++ks) HBFP_BF_KSTEP(0);
+    HBFP_BF_KSTEP(1);
+    HBFP_BF_KSTEP(2);
+    HBFP_BF_KSTEP(3);
+    HBFP_BF_KSTEP(4);
+#undef HBFP_BF_KSTEP
+#undef HBFP_BF_FENCE
+#undef HBFP_BF_ROW
+#undef HBFP_BF_MFMA
+#undef HBFP_BF_READ
+#undef HBFP_BF_COPY_STAGE
+
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int64_t row0 = (int64_t)tm * 256 + wm * 64, col0 = (int64_t)tn * 256 + wn * 128;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = col0 + j * 32 + l32;
+            if (col >= p.N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row < p.M) {
+                    float *dst = p.C + row * p.ldc + col;
+                    // C is written once and not read again here: streaming stores leave the operand panels in the caches
+                    if (p.beta) *dst = *dst + acc[i][j][v];
+                    else __builtin_nontemporal_store(acc[i][j][v], dst);
+                }
+            }
+        }
+}
+
+int64_t klen_of(const GemmArgs &a, int m) { return bf_klen(a.kpad, a.kbp, a.kblock, a.nblk, a.kdim, m); }
+
+BfPackParams bf_pack_params(const GemmArgs &a, const void *mant, const uint8_t *exps, int64_t R, int64_t exp_ld, int m, void *packed,
+                            int32_t mark) {
+    BfPackParams q;
+    q.mant = mant;
+    q.exps = exps;
+    q.header = (int *)packed;
+    q.out = (uint8_t *)packed + 256;
+    q.mark = mark;
+    q.R = R;
+    q.kpad = a.kpad;
+    q.exp_ld = exp_ld;
+    q.ksteps = (int32_t)(klen_of(a, m) / 32);
+    q.chunks32_per_block = (int32_t)(a.kbp / 32);
+    q.m = m;
+    q.ob = bf_dense_octets(a.kbp, a.kblock, m);
+    q.noct = (int32_t)bf_dense_row_octets(q.ob, a.nblk, a.kdim);
+    return q;
+}
+
+}  // namespace
+
+bool bf_operand(int mant_bits) { return bf_class(mant_bits); }
+
+size_t packed_operand_bytes(int64_t rows, int64_t kpad, int mant_bits) {
+    return bf_class(mant_bits) ? bf_packed_bytes(rows, kpad) : mx_packed_bytes(rows, kpad, mant_bits);
+}
+
+bool gemm_bf_possible(const GemmArgs &a) {
+    return !a.P && bf_class(a.mA) && bf_class(a.mB) && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 32 <= 0x7fffffff &&
+           a.nblk * 4 <= 0x7fffffff;
+}
+
+// packs operand A (rows a.M) and / or operand B (rows a.N) of `a` in one launch; a null buffer skips that operand
+int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s) {
+    if (!packed_a && !packed_b) return HBFP_OK;
+    BfPackPair q = {};
+    int64_t ba = 0, bb = 0;
+    if (packed_a) {
+        int32_t mark;
+        const int rc = mx_pack_begin(packed_a, s, &mark);
+        if (rc != HBFP_OK) return rc;
+        q.op[0] = bf_pack_params(a, a.mantA, a.expA, a.M, a.expA_ld, a.mA, packed_a, mark);
+    }
+    if (packed_b) {
+        int32_t mark;
+        const int rc = mx_pack_begin(packed_b, s, &mark);
+        if (rc != HBFP_OK) return rc;
+        q.op[1] = bf_pack_params(a, a.mantB, a.expB, a.N, a.expB_ld, a.mB, packed_b, mark);
+    }
+    // whole panels are written: the row tiles behind the last row hold zeros
+    if (packed_a) ba = ceil_div(a.M, 256) * 8 * ceil_div(q.op[0].ksteps / 2, 4);
+    if (packed_b) bb = ceil_div(a.N, 256) * 8 * ceil_div(q.op[1].ksteps / 2, 4);
+    if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
+    q.blocks_a = (uint32_t)ba;
+    const bool wide = (packed_a ? a.mA : a.mB) > 8;             // both operands of a product are of the same storage class
+    if (wide) hipLaunchKernelGGL(bf_pack_kernel<int16_t>, dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
+    else hipLaunchKernelGGL(bf_pack_kernel<int8_t>, dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
+    return launch_status();
+}
+
+// n <= HBFP_BATCH_MAX products of operands packed as bf16 planes, in one launch
+int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
+    if (n < 1 || n > kBfGroup) return HBFP_ERR_ARG;
+    BfGroup g = {};
+    g.n = n;
+    int64_t first = 0;
+    for (int i = 0; i < n; ++i) {
+        const GemmArgs &a = args[i];
+        if (!gemm_bf_possible(a) || klen_of(a, a.mA) != klen_of(a, a.mB)) return HBFP_ERR_FORMAT;
+        BfParams &p = g.p[i];
+        p.ha = (const int *)packed_a[i];
+        p.hb = (const int *)packed_b[i];
+        p.pa = (const uint8_t *)packed_a[i] + 256;
+        p.pb = (const uint8_t *)packed_b[i] + 256;
+        p.C = a.C;
+        p.M = a.M;
+        p.N = a.N;
+        p.ldc = a.ldc;
+        p.ksteps = (int32_t)(klen_of(a, a.mA) / 32);
+        p.tiles_m = (int32_t)ceil_div(a.M, 256);
+        p.tiles_n = (int32_t)ceil_div(a.N, 256);
+        p.beta = a.beta != 0.0f;
+        if (p.ksteps < kBfRing || p.ksteps % 4) return HBFP_ERR_ARG;    // the stored length is a multiple of 128
+        g.first[i] = (int32_t)first;
+        first += ceil_div((int64_t)p.tiles_m * p.tiles_n, 8) * 8;      // a multiple of 8: the XCD of a tile does not depend on the group
+        if (first > 0x7ffffff0) return HBFP_ERR_ARG;
+    }
+    for (int i = n; i <= kBfGroup; ++i) g.first[i] = (int32_t)first;
+    static std::atomic<bool> configured{false};
+    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_bf_kernel), kBfRing * kBfStage) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    hipLaunchKernelGGL(gemm_bf_kernel, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    return launch_status();
+}
+
+}  // namespace hbfp

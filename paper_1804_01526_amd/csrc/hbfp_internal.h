@@ -118,6 +118,13 @@ int launch_encode_pack(const float *src, int64_t ld, int n, const hbfp_tensor *c
 bool encode_pack_batch_ok(int nsrc, const hbfp_tensor *const *const *outs);
 int launch_encode_pack_batch(int nsrc, const float *const *src, const int64_t *ld, const int *n, const hbfp_tensor *const *const *outs,
                              void *const *const *packed, hipStream_t s);
+// gemm_bf.hip: mantissas of 6 to 9 bits as bf16 numbers on the bf16 matrix instruction.  A packed operand of that class
+// is the same 256-byte header followed by bf16 planes.
+bool bf_operand(int mant_bits);
+size_t packed_operand_bytes(int64_t rows, int64_t kpad, int mant_bits);   // of either kind of packed operand
+bool gemm_bf_possible(const GemmArgs &a);
+int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
+int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
 bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);
 bool gemm_mx_group_ok(int n, const GemmArgs *args);
 bool mx_encoded_output_ok(const hbfp_tensor &out);

@@ -29,12 +29,15 @@ def _flagged(buf):
 
 
 def _planes_end(d):
-    """First byte past the limb planes a pack writes: 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
-    bytes behind the 256-byte header; blocks of 8, 16 and 24 are packed without their padding (buffers are sized for
-    the padded length, the rest is never written), and octets of the last block that hold no element are not packed."""
+    """First byte past the planes a pack writes, behind the 256-byte header.  Mantissas of 6..9 bits: bf16 planes, 256-row
+    panels x packed k x 2 bytes; others: limb planes, 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
+    bytes.  Blocks of 8, 16 and 24 are packed without their padding (buffers are sized for the padded length, the rest is
+    never written), and octets of the last block that hold no element are not packed."""
     limbs = 1 if d.mant_bits <= 5 else 2 if d.mant_bits <= 9 else 3
     dense = d.mant_bits <= 8 and d.kblock < 32 and d.kblock % 8 == 0
     klen = -(-min(d.nblk * d.kblock, -(-d.kdim // 8) * 8) // 128) * 128 if dense else d.kpad
+    if 6 <= d.mant_bits <= 9:
+        return 256 + -(-d.rows // 256) * 256 * klen * 2
     return 256 + -(-d.rows // 256) * (klen // 64) * 8 * (limbs * 1536 + 256)
 
 
@@ -114,18 +117,26 @@ def test_random_shapes_formats_and_value_ranges(hb, case):
 
 
 def test_heavy_tails_and_zero_blocks_mark_the_same_operands(hb):
-    """Student-t values put neighbouring blocks more than 2 binades apart (the operand must be marked, as hbfp_pack marks
-    it); all-zero rows, columns and blocks take any exponent."""
+    """Student-t values put neighbouring blocks more than 2 binades apart.  4-bit mantissas are packed as one limb
+    with a group exponent, so the operand must be marked (as hbfp_pack marks it); 8-bit mantissas are packed as bf16
+    numbers, which take any spread, and stay unmarked.  All-zero rows, columns and blocks take any exponent; values
+    above 2^127 (exponent bytes of 254) mark an 8-bit operand."""
     rng = np.random.default_rng(3)
     x = (rng.standard_t(1.5, size=(300, 400)) * 1e-3).astype(np.float32)
-    outs, packed = _check_against_separate_calls(hb, x, [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
+    outs, packed = _check_against_separate_calls(hb, x, [(1, 24, 4, 0, 0, 1), (24, 1, 4, 0, 0, 0)])
     assert _flagged(packed[0]) and _flagged(packed[1]), "test input: these operands were meant to need the fallback"
+    outs, packed = _check_against_separate_calls(hb, x, [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
+    assert not _flagged(packed[0]) and not _flagged(packed[1])
     y = _rand((300, 400), 4, 0)
     y[:, 48:72] = 0.0
     y[96:120] = 0.0
     y[7] = 0.0
+    for m in (4, 8):
+        outs, packed = _check_against_separate_calls(hb, y, [(1, 24, m, 0, 0, 1), (24, 1, m, 0, 0, 0)])
+        assert not _flagged(packed[0]) and not _flagged(packed[1])
+    y[200, 100] = 2.0 ** 127
     outs, packed = _check_against_separate_calls(hb, y, [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)])
-    assert not _flagged(packed[0]) and not _flagged(packed[1])
+    assert _flagged(packed[0]) and _flagged(packed[1])
 
 
 def test_other_formats_take_the_separate_kernels(hb):
@@ -207,13 +218,18 @@ def test_batch_of_sources_equals_the_conversions_one_by_one(hb, batch):
 
 
 def test_batch_marks_each_source_on_its_own(hb):
-    """A heavy-tailed source next to a plain one: only the first is marked."""
+    """A source that needs the fallback next to a plain one: only the first is marked (4-bit mantissas: heavy tails;
+    8-bit mantissas: a value above 2^127)."""
     rng = np.random.default_rng(3)
-    heavy = torch.from_numpy((rng.standard_t(1.5, size=(300, 400)) * 1e-3).astype(np.float32)).cuda()
+    heavy = (rng.standard_t(1.5, size=(300, 400)) * 1e-3).astype(np.float32)
+    huge = _rand((300, 400), 5, 0)
+    huge[17, 33] = -(2.0 ** 127)
     plain = torch.from_numpy(_rand((400, 300), 4, 0)).cuda()
-    specs = [(1, 24, 8, 0, 0, 1), (24, 1, 8, 0, 0, 0)]
-    a, b = _alloc_outputs(hb, (300, 400), specs), _alloc_outputs(hb, (400, 300), specs)
-    for first, second in (((heavy,) + a, (plain,) + b), ((plain,) + b, (heavy,) + a)):
-        hb.encode_packed_batch([first, second])
-        torch.cuda.synchronize()
-        assert all(_flagged(p) for p in a[1]) and not any(_flagged(p) for p in b[1])
+    for m, bad in ((4, heavy), (8, huge)):
+        bad = torch.from_numpy(bad).cuda()
+        specs = [(1, 24, m, 0, 0, 1), (24, 1, m, 0, 0, 0)]
+        a, b = _alloc_outputs(hb, (300, 400), specs), _alloc_outputs(hb, (400, 300), specs)
+        for first, second in (((bad,) + a, (plain,) + b), ((plain,) + b, (bad,) + a)):
+            hb.encode_packed_batch([first, second])
+            torch.cuda.synchronize()
+            assert all(_flagged(p) for p in a[1]) and not any(_flagged(p) for p in b[1])

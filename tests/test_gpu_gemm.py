@@ -687,7 +687,8 @@ def test_packed_batch_equals_the_products_one_by_one(hb):
 def test_packed_product_in_a_replayed_graph(hb):
     """Weights packed outside, activations encoded and packed inside a captured graph; every replay (new activations
     in the same buffers, eager work and synchronisation between replays) must equal the eager result.  One replay
-    has activations outside the scale range, the next is in range again."""
+    has activations above 2^127, which mark the packed operand (the int8 kernels queued in the graph compute that
+    product), the next is in range again; one has activations so small that the products are FP32 subnormals."""
     m, blk, M, N, K = 8, 32, 260, 300, 640
     rng = np.random.default_rng(4)
     W = (rng.standard_normal((K, N)) * 0.05).astype(np.float32)
@@ -710,13 +711,16 @@ def test_packed_product_in_a_replayed_graph(hb):
             hb.encode(x, 1, fmt, out=tx, stream=stream)
             hb.pack(tx, out=px, stream=stream)
             hb.gemm_packed(tx, px, tw, pw, out=out, workspace=ws, stream=stream)
-    for i, scale in enumerate([1.0, 2.0 ** -124, 1.0, 3.0]):
+    for i, scale in enumerate([1.0, 2.0 ** 125, 1.0, 2.0 ** -124, 3.0]):
         X = (rng.standard_normal((M, K)) * scale).astype(np.float32)
+        assert np.isfinite(X).all()
         x.copy_(torch.from_numpy(X).cuda())
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         got = out.clone()
+        marked = bool(px[:8].view(torch.int32)[0] == px[:8].view(torch.int32)[1])
+        assert marked == (scale == 2.0 ** 125)
         eager = hb.gemm(hb.encode(x, 1, fmt), tw, kernel=SCALED)
         torch.cuda.synchronize()
         print(f"[case] packed graph replay {i} scale={scale}", flush=True)
@@ -724,14 +728,17 @@ def test_packed_product_in_a_replayed_graph(hb):
         assert rel_fro(got.cpu().numpy(), _oracle_product(X, W, (1, blk, m, 0, 0), (blk, 1, m, 0, 0))) <= TOL
 
 
-def test_heavy_tail_hint_changes_the_stand_by_kernel_not_the_result(hb):
+@pytest.mark.parametrize("m", [4, 8])
+def test_heavy_tail_hint_changes_the_stand_by_kernel_not_the_result(hb, m):
     """HBFP_HINT_HEAVY_TAILS on an operand: products on packed operands prepare the 8-wave int8 kernel as their stand-by
-    (its scale words written by extra workgroups of the product kernel).  Marked operands (Student-t values) then give
-    exactly what hbfp_gemm_select computes with HBFP_KERNEL_INT8; unmarked ones exactly what they give without the
-    hint; the same through hbfp_gemm_packed_batch, hbfp_gemm_select (packing inside the call) and with beta = 1."""
+    (its scale words written by extra workgroups of the block-scaled product kernel).  Marked operands (Student-t values
+    in 4-bit mantissas, which are packed as limbs with group exponents) then give exactly what hbfp_gemm_select computes
+    with HBFP_KERNEL_INT8; unmarked ones exactly what they give without the hint; the same through
+    hbfp_gemm_packed_batch and with beta = 1.  8-bit mantissas are packed as bf16 numbers: heavy tails do not mark them
+    and the hint changes nothing."""
     rng = np.random.default_rng(21)
     M, K, N = 300, 1000, 280
-    f_row, f_col = hb.make_format(8, 1, 24), hb.make_format(8, 24, 1)
+    f_row, f_col = hb.make_format(m, 1, 24), hb.make_format(m, 24, 1)
     W = torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)).cuda()
     w = hb.encode(W, 0, f_col)
     pw = hb.pack(w)
@@ -742,7 +749,7 @@ def test_heavy_tail_hint_changes_the_stand_by_kernel_not_the_result(hb):
         px = hb.pack(x)
         torch.cuda.synchronize()
         marked = bool(px[:8].view(torch.int32)[0] == px[:8].view(torch.int32)[1])
-        assert marked == tails
+        assert marked == (tails and m == 4)
         plain = hb.gemm_packed(x, px, w, pw)
         x.desc.hints = hb.HINT_HEAVY_TAILS
         hinted = hb.gemm_packed(x, px, w, pw)
@@ -756,18 +763,20 @@ def test_heavy_tail_hint_changes_the_stand_by_kernel_not_the_result(hb):
         plain_acc = hb.gemm_packed(x, px, w, pw, out=base.clone(), beta=1.0)
         torch.cuda.synchronize()
         print(f"[case] heavy-tail hint, operand marked={marked}", flush=True)
-        for got in (hinted, both[0], both[1], inside):
-            assert torch.equal(got, int8 if tails else plain)
-        assert torch.equal(hinted_acc, int8_acc if tails else plain_acc)
-        oa, ob = ref.encode(data.astype(np.float32), 1, 24, 8), ref.encode(W.cpu().numpy(), 24, 1, 8)
-        assert rel_fro(hinted.cpu().numpy(), ref.gemm(ref.decode(oa), ref.decode(ob))) <= TOL
+        for got in (hinted, both[0], both[1]) + ((inside,) if m == 4 else ()):       # (packing inside the call keeps limb planes)
+            assert torch.equal(got, int8 if marked else plain)
+        assert torch.equal(hinted_acc, int8_acc if marked else plain_acc)
+        oa, ob = ref.encode(data.astype(np.float32), 1, 24, m), ref.encode(W.cpu().numpy(), 24, 1, m)
+        want = ref.gemm(ref.decode(oa), ref.decode(ob))
+        assert rel_fro(hinted.cpu().numpy(), want) <= TOL and rel_fro(inside.cpu().numpy(), want) <= TOL
 
 
 def test_training_step_route_in_a_replayed_graph(hb):
     """The route the benchmark times, captured once and replayed: conversions that write stored and packed operands
     (blocks of 24), the forward product, both backward products in one launch.  Every replay (new inputs in the same
     buffers, eager work and synchronisation in between) must equal the eager calls bit for bit; one replay has
-    heavy-tailed gradients, whose operands are marked and computed by the int8 kernels inside the same calls."""
+    heavy-tailed gradients (8-bit mantissas are packed as bf16 numbers, which take them as they are), one has gradients
+    above 2^127, whose operands are marked and computed by the int8 kernels inside the same calls."""
     M, K, N = 300, 520, 280
     rng = np.random.default_rng(14)
     f_row, f_col, f_tile = hb.make_format(8, 1, 24), hb.make_format(8, 24, 1), hb.make_format(8, 24, 24)
@@ -794,11 +803,14 @@ def test_training_step_route_in_a_replayed_graph(hb):
         stream.synchronize()
         with torch.cuda.graph(graph, stream=stream):
             step(stream)
-    for i, tails in enumerate([False, True, False, False]):
+    for i, kind in enumerate(["normal", "heavy tails", "huge", "normal", "normal"]):
         X.copy_(torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)))
         W.copy_(torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)))
-        grad = rng.standard_t(2, size=(M, N)) if tails else rng.standard_normal((M, N))
-        dY.copy_(torch.from_numpy((grad * 1e-3).astype(np.float32)))
+        grad = rng.standard_t(2, size=(M, N)) if kind == "heavy tails" else rng.standard_normal((M, N))
+        grad = (grad * 1e-3).astype(np.float32)
+        if kind == "huge":
+            grad[5, 7] = 2.0 ** 127
+        dY.copy_(torch.from_numpy(grad))
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
@@ -806,8 +818,8 @@ def test_training_step_route_in_a_replayed_graph(hb):
         marked = [bool(p[:8].view(torch.int32)[0] == p[:8].view(torch.int32)[1]) for p in pg]
         step(torch.cuda.current_stream())
         torch.cuda.synchronize()
-        print(f"[case] step graph replay {i} heavy tails={tails} gradient operands marked={marked}", flush=True)
-        assert all(marked) == tails
+        print(f"[case] step graph replay {i} gradients: {kind}, gradient operands marked={marked}", flush=True)
+        assert all(marked) == (kind == "huge") and any(marked) == (kind == "huge")
         for a, b in zip(got, (Y, dX, dW)):
             assert torch.equal(a, b)
         oa, ob = ref.encode(X.cpu().numpy(), 1, 24, 8), ref.encode(W.cpu().numpy(), 24, 24, 8)
