@@ -874,7 +874,7 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
     const int kind = packed_kind(A, B);
     if (kind == kPackedBf) rc = launch_bf_products(1, &g, &packed_a, &packed_b, (hipStream_t)stream);
     else if (kind == kPackedMx) rc = launch_mx_product(g, packed_a, packed_b, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
-    if (rc != HBFP_OK) return rc;
+    if (rc != HBFP_OK || kind == kPackedBf) return rc;      // the bf16 kernel deals with marked operands itself
     if (kind != kPackedMixed) {      // the int8 kernels stand by; for a mixed pair they are the product
         g.run_a = (const int *)packed_a;
         g.run_b = (const int *)packed_b;
@@ -933,7 +933,7 @@ int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const
     }
     int rc = kind == kPackedBf ? launch_bf_products(n, g, packed_a, packed_b, s)
              : kind == kPackedMx ? launch_mx_products(n, g, packed_a, packed_b, standby, s) : HBFP_OK;
-    if (rc != HBFP_OK) return rc;
+    if (rc != HBFP_OK || kind == kPackedBf) return rc;      // the bf16 kernel deals with marked operands itself
     char *ws = (char *)workspace;
     for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
         if (kind != kPackedMixed) {

@@ -15,9 +15,9 @@
 //                 by asynchronous copies of whole stages, one barrier per k-step, operand registers of the next half
 //                 k-step read while the matrix instructions of this one run.
 // Only a non-zero block with an exponent byte above 253 (values from 2^127 on) cannot be packed safely; the pack then
-// marks the header of the packed operand as the block-scaled path does, the product kernel does nothing when either
-// header is marked and the int8 kernels, launched behind it with the opposite condition, compute the product.  Small
-// values need no such care: the instruction takes subnormal bf16 operands and keeps subnormal FP32 sums.
+// marks the header of the packed operand as the block-scaled path does, and the product kernel computes such a product
+// from the stored operands with plain integer and FP32 arithmetic (bf_marked_tile).  Small values need no such care:
+// the instruction takes subnormal bf16 operands and keeps subnormal FP32 sums.
 #include <atomic>
 
 #include "bf_pack.h"
@@ -116,7 +116,37 @@ struct BfParams {
     float *C;
     int64_t M, N, ldc;
     int32_t ksteps, tiles_m, tiles_n, beta;
+    // the stored operands, read only when a packed operand is marked
+    const void *mantA, *mantB;
+    const uint8_t *expA, *expB;
+    int64_t kpad, expA_ld, expB_ld;
+    int32_t chunks32_per_block, shift, wide;   // shift: -(2 * 125 + mA + mB)
 };
+
+// A tile of a product with a marked operand (an exponent byte above 253: values next to the largest finite FP32 number),
+// from the stored operands with the arithmetic of Eq. (2) as written: an integer sum per stored chunk of 32, scaled by
+// 2^(eA + eB) and accumulated in FP32.  Thread t owns column t % 256 of the tile and every second row.  Slow, and
+// expected never to run on training data; it spares every product the launch of a stand-by kernel.
+template <typename MT>
+__device__ void bf_marked_tile(const BfParams &p, int tm, int tn) {
+    const int64_t col = (int64_t)tn * 256 + (threadIdx.x & 255);
+    if (col >= p.N) return;
+    const MT *b = reinterpret_cast<const MT *>(p.mantB) + col * p.kpad;
+    for (int i = 0; i < 128; ++i) {
+        const int64_t row = (int64_t)tm * 256 + (threadIdx.x >> 8) + 2 * i;
+        if (row >= p.M) break;
+        const MT *a = reinterpret_cast<const MT *>(p.mantA) + row * p.kpad;
+        float sum = 0.0f;
+        for (int64_t c = 0; c < p.kpad / 32; ++c) {
+            int P = 0;
+            for (int k = 0; k < 32; ++k) P += (int)a[c * 32 + k] * (int)b[c * 32 + k];
+            const int64_t blk = c / p.chunks32_per_block;
+            sum += __builtin_ldexpf((float)P, (int)p.expA[row * p.expA_ld + blk] + (int)p.expB[col * p.expB_ld + blk] + p.shift);
+        }
+        float *dst = p.C + row * p.ldc + col;
+        *dst = p.beta ? *dst + sum : sum;
+    }
+}
 // Up to kBfGroup independent products in one launch: workgroups first[i] .. first[i + 1] - 1 belong to product i, so the
 // stores of one product's tiles drain under the matrix instructions of the next.
 struct BfGroup {
@@ -137,9 +167,13 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
             p = g.p[i];
             first_wg = g.first[i];
         }
-    if (p.ha[0] == p.ha[1] || p.hb[0] == p.hb[1]) return;      // uniform: the int8 kernels take over
     int tm, tn;
     if (!tile_of_workgroup((int)blockIdx.x - first_wg, p.tiles_m, p.tiles_n, tm, tn)) return;   // whole workgroup, before any barrier
+    if (p.ha[0] == p.ha[1] || p.hb[0] == p.hb[1]) {            // uniform
+        if (p.wide) bf_marked_tile<int16_t>(p, tm, tn);
+        else bf_marked_tile<int8_t>(p, tm, tn);
+        return;
+    }
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -196,10 +230,19 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
 #define HBFP_BF_FENCE                   \
     asm volatile("" ::: "memory");      \
     __builtin_amdgcn_sched_barrier(0)
+    // Matrix instructions touch no memory, so a fence alone does not keep them on their side of the hand-over: an empty
+    // statement that reads and writes one register of every accumulator does (the next instruction on that
+    // accumulator depends on it).
+#define HBFP_BF_PIN                                                                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                                       \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) asm volatile("" : "+v"(acc[i_][j_][0]))
     // One k-step.  The registers of its second half are requested first and arrive under the matrix instructions of
-    // the first half.  The hand-over sits before the last row of matrix instructions: wait for this wave's copies of
-    // stage ks + 1, barrier (now every wave's copies of it have landed and every wave has read all of stage ks),
-    // request the first half of stage ks + 1, and hand the buffer of stage ks to the copy of stage ks + 4.
+    // the first half.  The hand-over sits between the two rows of the first half, so that matrix instructions are in
+    // flight when a wave reaches the barrier and ready to issue when it leaves: wait for the second-half registers and
+    // for this wave's copies of stage ks + 1, barrier (now every wave's copies of it have landed and every wave has
+    // read all of stage ks).  After the first half the wave requests the first-half registers of stage ks + 1 and
+    // hands the buffer of stage ks to the copy of stage ks + 4; both land under the second half.  (Measured: the
+    // barrier after the whole first half, or inside the second, costs 1 to 5 % of the product.)
     // MODE 0: stages ks + 1 .. ks + 3 in flight and a copy to issue; 1: the same, nothing left to copy; 2: two stages
     // in flight; 3: one; 4: last k-step
 #define HBFP_BF_KSTEP(MODE)                                                                                \
@@ -211,22 +254,27 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
         HBFP_BF_READ(1, base, 1);                                                                          \
         HBFP_BF_FENCE;                                                                                     \
         HBFP_BF_ROW(0, 0);                                                                                 \
-        HBFP_BF_ROW(0, 1);                                                                                 \
-        HBFP_BF_FENCE;                                                                                     \
-        HBFP_BF_ROW(1, 0);                                                                                 \
-        HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_PIN;                                                                                       \
         if (MODE != 4) {                                                                                   \
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                             \
             if (MODE <= 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kBfCopies) : "memory");            \
             else if (MODE == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kBfCopies) : "memory");           \
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                          \
             __builtin_amdgcn_s_barrier();                                                                  \
             asm volatile("" ::: "memory");                                                                 \
+        }                                                                                                  \
+        HBFP_BF_PIN;                                                                                       \
+        HBFP_BF_ROW(0, 1);                                                                                 \
+        HBFP_BF_PIN;                                                                                       \
+        HBFP_BF_FENCE;                                                                                     \
+        if (MODE != 4) {                                                                                   \
             HBFP_BF_READ(0, nbase, 0);                                                                     \
             if (MODE == 0) HBFP_BF_COPY_STAGE(copy_ring);                                                  \
         }                                                                                                  \
         HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_ROW(1, 0);                                                                                 \
         HBFP_BF_ROW(1, 1);                                                                                 \
-        HBFP_BF_FENCE;                                                                                     \
+        HBFP_BF_PIN;                                                                                       \
         ring = next;                                                                                       \
     }
     // the number of k-steps is a multiple of 4 (the packed k axis is a multiple of 128)
@@ -246,6 +294,7 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
     HBFP_BF_KSTEP(4);
 #undef HBFP_BF_KSTEP
 #undef HBFP_BF_FENCE
+#undef HBFP_BF_PIN
 #undef HBFP_BF_ROW
 #undef HBFP_BF_MFMA
 #undef HBFP_BF_READ
@@ -356,6 +405,16 @@ int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a,
         p.tiles_m = (int32_t)ceil_div(a.M, 256);
         p.tiles_n = (int32_t)ceil_div(a.N, 256);
         p.beta = a.beta != 0.0f;
+        p.mantA = a.mantA;
+        p.mantB = a.mantB;
+        p.expA = a.expA;
+        p.expB = a.expB;
+        p.kpad = a.kpad;
+        p.expA_ld = a.expA_ld;
+        p.expB_ld = a.expB_ld;
+        p.chunks32_per_block = (int32_t)(a.kbp / 32);
+        p.shift = -(250 + a.mA + a.mB);
+        p.wide = a.mA > 8;
         if (p.ksteps < kBfRing || p.ksteps % 4) return HBFP_ERR_ARG;    // the stored length is a multiple of 128
         g.first[i] = (int32_t)first;
         first += ceil_div((int64_t)p.tiles_m * p.tiles_n, 8) * 8;      // a multiple of 8: the XCD of a tile does not depend on the group
