@@ -314,11 +314,18 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
  *                       on the vector unit as in the int8 family.  A block sum beyond 2^24 is rounded to nearest once per
  *                       16 products of the chain instead of once per block; blocks of 32, 64 or a multiple of 128
  *                       (HBFP_ERR_FORMAT otherwise, and for 8-bit operands);
- *   HBFP_KERNEL_AUTO    what hbfp_gemm does: FP16 when both operands have 9..12-bit mantissas in blocks it takes (measured
- *                       ahead of both other families from 2048^3 to 8192^3); otherwise SCALED where it is measured faster
- *                       (at least 144 output tiles of 256 x 256, a stored contraction length of at least 2048, or 1024
- *                       from 512 tiles on, and either blocks of at most 32 elements, an operand of at most 5 bits, or
- *                       mantissas wider than 9 bits), else INT8.
+ *   HBFP_KERNEL_BF16    6..9-bit mantissas as bf16 numbers: such a mantissa times its block's power of two has at most
+ *                       8 significant bits and the exponent range of the exponent byte, so Eq. (1) is exact in bf16; one
+ *                       bf16 matrix instruction per 16 k multiplies the significands, adds the exponents and accumulates in
+ *                       FP32, and nothing is scaled per block (any block length, any spread of exponents; a non-zero block
+ *                       with an exponent byte above 253 is computed with plain arithmetic inside the same kernel).  The
+ *                       operands are packed into bf16 planes in the workspace first.  HBFP_ERR_FORMAT for other widths;
+ *   HBFP_KERNEL_AUTO    what hbfp_gemm does, in this order: BF16 when both operands have 6..9-bit mantissas and the shape is
+ *                       one where 256 x 256 tiles pay (at least 144 output tiles, a stored contraction length of at least
+ *                       2048, or 1024 from 512 tiles on, blocks of at most 32 elements); FP16 when both operands have
+ *                       9..12-bit mantissas in blocks it takes (measured ahead of the int8 and block-scaled families from
+ *                       2048^3 to 8192^3); SCALED for the same shapes as BF16 when an operand has at most 5 bits or both
+ *                       have more than 9; else INT8.
  * All satisfy the same bound against the FP64 product of the decoded operands.
  * Arguments, domain and errors as hbfp_gemm, plus HBFP_ERR_ARG for an unknown kernel; the workspace
  * size depends on the kernel: hbfp_gemm_select_workspace.
@@ -328,6 +335,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 #define HBFP_KERNEL_SCALED 2
 #define HBFP_KERNEL_INT8_WIDE 3
 #define HBFP_KERNEL_FP16 4
+#define HBFP_KERNEL_BF16 5
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes);
 int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
                      void *workspace, size_t ws_bytes, void *stream);

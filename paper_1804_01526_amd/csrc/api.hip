@@ -591,13 +591,22 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
     return HBFP_OK;
 }
 
+// 6..9-bit mantissas as bf16 numbers: asked for by name, or chosen where the 256 x 256 tiles pay (the shapes and block
+// lengths for which the block-scaled kernel was measured ahead of the int8 kernels; the bf16 kernel is ahead of both there)
+static bool use_bf(const GemmArgs &g, int kernel) {
+    if (g.P || !gemm_bf_possible(g)) return false;
+    return kernel == HBFP_KERNEL_BF16 || (kernel == HBFP_KERNEL_AUTO && gemm_mx_ok(g));
+}
+
 static bool use_scaled(const GemmArgs &g, int kernel) {
-    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE || kernel == HBFP_KERNEL_FP16) return false;
+    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE || kernel == HBFP_KERNEL_FP16 || kernel == HBFP_KERNEL_BF16)
+        return false;
+    if (use_bf(g, kernel)) return false;
     return kernel == HBFP_KERNEL_SCALED ? gemm_mx_possible(g) : gemm_mx_ok(g);
 }
 
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes) {
-    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
+    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
     int rc = check_tensor(A, false);
     if (rc != HBFP_OK) return rc;
     rc = check_tensor(B, false);
@@ -605,6 +614,10 @@ int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int k
     *bytes = (A->mant_bits > 8 || B->mant_bits > 8) ? gemm_limb_workspace(A, B)
                                                      : gemm_i8_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld);
     const GemmArgs g = gemm_args(A, B);
+    if (use_bf(g, kernel)) {                                     // [packed A][packed B]
+        *bytes = packed_operand_bytes(g.M, g.kpad, g.mA) + packed_operand_bytes(g.N, g.kpad, g.mB);
+        return HBFP_OK;
+    }
     const size_t f16 = gemm_f16_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld > B->exp_ld ? A->exp_ld : B->exp_ld);
     if (kernel == HBFP_KERNEL_FP16 || (kernel == HBFP_KERNEL_AUTO && gemm_f16_possible(g))) {
         *bytes = f16;
@@ -629,12 +642,19 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
     g.beta = beta;
     g.P = P;
     if (kernel == HBFP_KERNEL_FP16 && !gemm_f16_possible(g)) return HBFP_ERR_FORMAT;
+    if (kernel == HBFP_KERNEL_BF16 && !P && !gemm_bf_possible(g)) return HBFP_ERR_FORMAT;
     size_t need = 0;
     hbfp_gemm_select_workspace(A, B, kernel, &need);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
     if (kernel == HBFP_KERNEL_INT8_WIDE) {
         if (!gemm_wide_possible(g)) return HBFP_ERR_FORMAT;
         g.wide = 1;
+    }
+    if (use_bf(g, kernel)) {
+        void *pa = workspace, *pb = (char *)workspace + packed_operand_bytes(g.M, g.kpad, g.mA);
+        rc = launch_bf_pack(g, pa, pb, (hipStream_t)stream);
+        const void *cpa = pa, *cpb = pb;
+        return rc == HBFP_OK ? launch_bf_products(1, &g, &cpa, &cpb, (hipStream_t)stream) : rc;
     }
     // 9..12-bit mantissas are exact FP16 values: one FP16 matrix instruction per element pair instead of four or nine limb products
     if (kernel == HBFP_KERNEL_FP16 || (kernel == HBFP_KERNEL_AUTO && gemm_f16_possible(g)))
@@ -658,7 +678,7 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !C) return HBFP_ERR_ARG;
     if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
     if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
     return run_gemm(A, B, C, ldc, beta, nullptr, kernel, workspace, ws_bytes, stream);
 }
@@ -671,22 +691,27 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 // Checks the products of a batch and decides whether they share one launch of the block-scaled kernel; part[i] is
 // product i's share of the workspace.
 static int batch_plan(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, GemmArgs *g, size_t *part,
-                      bool *grouped) {
+                      bool *grouped, int *group_kernel) {
     if (!A || !B || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
-    bool all_scaled = true, same = true;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
+    bool all_scaled = true, all_bf = true, bf_class = true, same = true;
     for (int i = 0; i < n; ++i) {
         if (!A[i] || !B[i]) return HBFP_ERR_ARG;
         const int rc = check_pair(A[i], B[i]);
         if (rc != HBFP_OK) return rc;
         g[i] = gemm_args(A[i], B[i]);
         all_scaled = all_scaled && use_scaled(g[i], kernel);
+        all_bf = all_bf && use_bf(g[i], kernel);
+        bf_class = bf_class && gemm_bf_possible(g[i]);
         same = same && (A[i]->mant_bits > 8) == (A[0]->mant_bits > 8) && mx_same_limbs(g[i], g[0]);
     }
-    // products that would each take the block-scaled kernel anyway, or (automatic choice) that fill the chip only together
-    *grouped = n > 1 && same && (all_scaled || (kernel == HBFP_KERNEL_AUTO && gemm_mx_group_ok(n, g)));
+    // products that would each take the bf16 or the block-scaled kernel anyway, or (automatic choice) that fill the chip
+    // only together
+    const bool together = kernel == HBFP_KERNEL_AUTO && gemm_mx_group_ok(n, g);
+    *grouped = n > 1 && same && (all_scaled || all_bf || together);
+    *group_kernel = !*grouped ? kernel : (all_bf || (together && bf_class)) ? HBFP_KERNEL_BF16 : HBFP_KERNEL_SCALED;
     for (int i = 0; i < n; ++i) {
-        hbfp_gemm_select_workspace(A[i], B[i], *grouped ? HBFP_KERNEL_SCALED : kernel, &part[i]);
+        hbfp_gemm_select_workspace(A[i], B[i], *group_kernel, &part[i]);
         part[i] = align256(part[i]);
     }
     return HBFP_OK;
@@ -697,7 +722,8 @@ int hbfp_gemm_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_ten
     GemmArgs g[HBFP_BATCH_MAX];
     size_t part[HBFP_BATCH_MAX];
     bool grouped = false;
-    const int rc = batch_plan(n, A, B, kernel, g, part, &grouped);
+    int group_kernel = kernel;
+    const int rc = batch_plan(n, A, B, kernel, g, part, &grouped, &group_kernel);
     if (rc != HBFP_OK) return rc;
     *bytes = 0;
     for (int i = 0; i < n; ++i) *bytes += part[i];
@@ -711,7 +737,8 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
     GemmArgs g[HBFP_BATCH_MAX];
     size_t part[HBFP_BATCH_MAX], need = 0;
     bool grouped = false;
-    int rc = batch_plan(n, A, B, kernel, g, part, &grouped);
+    int group_kernel = kernel;
+    int rc = batch_plan(n, A, B, kernel, g, part, &grouped, &group_kernel);
     if (rc != HBFP_OK) return rc;
     for (int i = 0; i < n; ++i) {
         if (!C[i] || ldc[i] < B[i]->rows || ((uintptr_t)C[i] & 3)) return HBFP_ERR_ARG;
@@ -733,6 +760,17 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
         return HBFP_OK;
     }
     const void *pa[HBFP_BATCH_MAX], *pb[HBFP_BATCH_MAX];
+    if (group_kernel == HBFP_KERNEL_BF16) {
+        for (int i = 0; i < n; ++i) {                                // product i: [packed A][packed B]
+            char *a = ws, *b = a + packed_operand_bytes(g[i].M, g[i].kpad, g[i].mA);
+            rc = launch_bf_pack(g[i], a, b, s);
+            if (rc != HBFP_OK) return rc;
+            pa[i] = a;
+            pb[i] = b;
+            ws += part[i];
+        }
+        return launch_bf_products(n, g, pa, pb, s);
+    }
     void *standby[HBFP_BATCH_MAX];
     for (int i = 0; i < n; ++i) {                                    // product i: [packed A][packed B][int8 workspace]
         char *a = ws, *b = a + mx_packed_bytes(g[i].M, g[i].kpad, g[i].mA);
@@ -758,15 +796,19 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
 
 // Workspace of hbfp_gemm_bfp: [FP32 product M x N][workspace of the product][workspace of the conversion]
 static int gemm_bfp_plan(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, bool need_ptrs,
-                         bool *fused, size_t part[3]) {
+                         bool *fused, size_t part[3], int *kernel_used) {
     if (!A || !B || !out) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
     int rc = need_ptrs ? check_pair(A, B) : check_tensor(A, false);
     if (rc == HBFP_OK && !need_ptrs) rc = check_tensor(B, false);
     if (rc == HBFP_OK) rc = check_tensor(out, need_ptrs);
     if (rc != HBFP_OK) return rc;
     if (out->src_rows != A->rows || out->src_cols != B->rows) return HBFP_ERR_LAYOUT;
     const GemmArgs g = gemm_args(A, B);
+    // the automatic choice keeps the block-scaled kernel where that one can convert its accumulators itself: the bf16
+    // kernel would be faster as a product (it is the choice for FP32 outputs) but not by the separate conversion pass
+    if (kernel == HBFP_KERNEL_AUTO && use_bf(g, kernel) && mx_encoded_output_ok(*out)) kernel = HBFP_KERNEL_SCALED;
+    *kernel_used = kernel;
     *fused = use_scaled(g, kernel) && mx_encoded_output_ok(*out);
     part[0] = align256((size_t)A->rows * (size_t)B->rows * sizeof(float));
     hbfp_gemm_select_workspace(A, B, kernel, &part[1]);
@@ -781,7 +823,7 @@ int hbfp_gemm_bfp_workspace(const hbfp_tensor *A, const hbfp_tensor *B, const hb
     if (!bytes) return HBFP_ERR_ARG;
     bool fused = false;
     size_t part[3];
-    const int rc = gemm_bfp_plan(A, B, out, kernel, false, &fused, part);
+    const int rc = gemm_bfp_plan(A, B, out, kernel, false, &fused, part, &kernel);
     if (rc != HBFP_OK) return rc;
     *bytes = part[0] + part[1] + part[2];
     return HBFP_OK;
@@ -791,7 +833,7 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
                   size_t ws_bytes, void *stream) {
     bool fused = false;
     size_t part[3];
-    int rc = gemm_bfp_plan(A, B, out, kernel, true, &fused, part);
+    int rc = gemm_bfp_plan(A, B, out, kernel, true, &fused, part, &kernel);
     if (rc != HBFP_OK) return rc;
     if (relu != 0 && relu != 1) return HBFP_ERR_ARG;
     if (!workspace || ws_bytes < part[0] + part[1] + part[2] || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;

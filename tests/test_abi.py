@@ -214,7 +214,19 @@ def test_gemm_select_validation():
         return d
 
     a, b = desc(8, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)
-    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 5, fake, 1 << 20, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 6, fake, 1 << 20, None) == hbfp.ERR_ARG
+    # the bf16 kernel is for 6..9-bit mantissas on both sides; its workspace holds the bf16 planes of both operands
+    # (whole panels of 256 rows, 2 bytes per stored element, a 256-byte header each)
+    for m in (4, 5, 10, 12):
+        am, bm = desc(m, 128, 256, 1, 1, 32), desc(m, 256, 64, 0, 32, 1)
+        assert lib.hbfp_gemm_select(byref(am), byref(bm), fake, 64, 0.0, hbfp.KERNEL_BF16, fake, 1 << 24, None) == hbfp.ERR_FORMAT
+    a4 = desc(4, 128, 256, 1, 1, 32)
+    assert lib.hbfp_gemm_select(byref(a4), byref(b), fake, 64, 0.0, hbfp.KERNEL_BF16, fake, 1 << 24, None) == hbfp.ERR_FORMAT
+    for m in (6, 8, 9):
+        am, bm = desc(m, 128, 256, 1, 1, 32), desc(m, 256, 64, 0, 32, 1)
+        n_bf = hbfp.gemm_select_workspace(am, bm, hbfp.KERNEL_BF16)
+        assert n_bf == 2 * (256 + 256 * 256 * 2) == hbfp.pack_bytes(am) + hbfp.pack_bytes(bm)
+        assert lib.hbfp_gemm_select(byref(am), byref(bm), fake, 64, 0.0, hbfp.KERNEL_BF16, fake, n_bf - 256, None) == hbfp.ERR_WORKSPACE
     # the FP16 kernel is for 9..12-bit mantissas in blocks stored as 32, 64 or a multiple of 128 elements
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_FP16, fake, 1 << 24, None) == hbfp.ERR_FORMAT
     a12, b12 = desc(12, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)          # both operands have to be wide
@@ -233,13 +245,17 @@ def test_gemm_select_validation():
     # one 256-row panel per operand, 4 k-steps of 64, two limbs: 8 row tiles x (2 x 1536 + 256) bytes per k-step
     assert n_scaled >= n_int8 + 2 * 4 * 8 * 3328
     assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, hbfp.KERNEL_SCALED, fake, n_int8, None) == hbfp.ERR_WORKSPACE
-    # automatic choice on a 4096^3 product: blocks of 24 (padded to 32) and of 32 -> block-scaled; blocks of 64 -> int8;
-    # 4-bit mantissas -> block-scaled; a 2048^3 product (64 tiles of 256 x 256) -> int8; 12-bit mantissas on both
-    # sides -> the FP16 instruction, 12-bit against 8-bit -> block-scaled
-    def auto_is_scaled(m, blk):
+    # automatic choice on a 4096^3 product: 6..9-bit mantissas in blocks of 24 (padded to 32) and of 32 -> bf16; blocks of
+    # 64 -> int8; 4-bit mantissas -> block-scaled; a 2048^3 product (64 tiles of 256 x 256) -> int8; 12-bit mantissas on
+    # both sides -> the FP16 instruction, 12-bit against 8-bit -> block-scaled
+    def auto_is(m, blk, kernel):
         x, w = desc(m, 4096, 4096, 1, 1, blk), desc(m, 4096, 4096, 0, blk, 1)
-        return hbfp.gemm_workspace(x, w) > hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
-    assert auto_is_scaled(8, 32) and auto_is_scaled(8, 24) and not auto_is_scaled(8, 64)
+        n = hbfp.gemm_workspace(x, w)
+        return n == hbfp.gemm_select_workspace(x, w, kernel) and (kernel == hbfp.KERNEL_INT8 or n != hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8))
+    def auto_is_scaled(m, blk):
+        return auto_is(m, blk, hbfp.KERNEL_SCALED)
+    assert auto_is(8, 32, hbfp.KERNEL_BF16) and auto_is(8, 24, hbfp.KERNEL_BF16) and auto_is(6, 16, hbfp.KERNEL_BF16)
+    assert auto_is(9, 32, hbfp.KERNEL_BF16) and auto_is(8, 64, hbfp.KERNEL_INT8)
     x, w = desc(8, 2048, 2048, 1, 1, 32), desc(8, 2048, 2048, 0, 32, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
     assert auto_is_scaled(4, 64) and auto_is_scaled(5, 24)
@@ -254,7 +270,7 @@ def test_gemm_select_validation():
 
 def test_gemm_batch_validation():
     """hbfp_gemm_batch: argument checks happen before any launch; products that fill the chip only together are
-    grouped by the automatic choice (seen through the workspace, which then holds limb planes)."""
+    grouped by the automatic choice (seen through the workspace, which then holds the packed operands)."""
     lib = hbfp._lib
     fake = ctypes.c_void_p(0x1000)
 
@@ -282,11 +298,16 @@ def test_gemm_batch_validation():
     assert need == 2 * hbfp.gemm_select_workspace(small[0], small[1], hbfp.KERNEL_SCALED)
     assert call([small, small], kernel=hbfp.KERNEL_SCALED, ws_bytes=need - 256) == hbfp.ERR_WORKSPACE
     assert hbfp.gemm_batch_workspace([small, small]) == 2 * hbfp.gemm_workspace(small[0], small[1])
-    # four products of 64 tiles each: alone each takes the int8 kernels, together the block-scaled kernel
+    # four products of 64 tiles each: alone each takes the int8 kernels, together the bf16 kernel (8-bit mantissas) or
+    # the block-scaled kernel (4-bit mantissas)
     q = pair(8, 2048, 2048, 2048, 32)
     alone, scaled = hbfp.gemm_workspace(q[0], q[1]), hbfp.gemm_select_workspace(q[0], q[1], hbfp.KERNEL_SCALED)
-    assert alone < scaled
-    assert hbfp.gemm_batch_workspace([q] * 4) == 4 * scaled
+    bf = hbfp.gemm_select_workspace(q[0], q[1], hbfp.KERNEL_BF16)
+    assert alone < scaled and bf != scaled and bf != alone
+    assert hbfp.gemm_batch_workspace([q] * 4) == 4 * bf == hbfp.gemm_batch_workspace([q] * 4, hbfp.KERNEL_BF16)
+    assert hbfp.gemm_batch_workspace([q] * 4, hbfp.KERNEL_SCALED) == 4 * scaled
+    q4 = pair(4, 2048, 2048, 2048, 32)
+    assert hbfp.gemm_batch_workspace([q4] * 4) == 4 * hbfp.gemm_select_workspace(q4[0], q4[1], hbfp.KERNEL_SCALED)
     assert hbfp.gemm_batch_workspace([q] * 2) == 2 * alone                         # 128 tiles: not together either
     assert hbfp.gemm_batch_workspace([q] * 4, hbfp.KERNEL_INT8) == 4 * alone
     q64 = pair(8, 2048, 2048, 2048, 64)                                            # blocks of 64: the int8 kernels are ahead
@@ -394,7 +415,7 @@ def test_gemm_bfp_validation():
         hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED) + -(-hbfp.encode_workspace(row_exp) // 256) * 256
     assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 128, 65, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
     assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 64, 128, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
-    assert _status(hbfp.gemm_bfp_workspace, a, b, out, 5) == hbfp.ERR_ARG
+    assert _status(hbfp.gemm_bfp_workspace, a, b, out, 6) == hbfp.ERR_ARG
     need = hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED)
     call = lib.hbfp_gemm_bfp
     assert call(byref(a), byref(b), byref(out), 0, hbfp.KERNEL_SCALED, fake, need - 1, None) == hbfp.ERR_WORKSPACE

@@ -863,6 +863,79 @@ def test_scaled_kernel_random_shapes(hb, case):
          beta=float(rng.integers(2)))
 
 
+# ---- 6..9-bit mantissas as bf16 numbers (HBFP_KERNEL_BF16)
+
+BF16 = 5
+
+
+@pytest.mark.parametrize("case", random_cases(24))
+def test_bf16_kernel_random_shapes(hb, case):
+    """Seeded random shapes (down to a single row, column or contraction element), block lengths (packed without their
+    padding or as stored), 6..9-bit mantissas (int8 and int16 storage), rounding modes and beta, through the bf16 kernel."""
+    rng = np.random.default_rng(5000 + case)
+    M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+    K = int(rng.choice([1, 7, 31, 32, 33, 63, 64, 65, 127, 129, 500, 1023, 1500]))
+    blk = int(rng.choice([8, 16, 24, 32, 48, 64, 100, 0]))
+    if rng.integers(3):
+        ma, mb = int(rng.integers(6, 9)), int(rng.integers(6, 9))
+    else:
+        ma, mb = 9, 9
+    ra, rb = int(rng.integers(2)), int(rng.integers(2))
+    A, B = _rand((M, K), 6000 + case), _rand((K, N), 7000 + case)
+    _run(hb, A, B, (1, blk, ma, ra, 17 + case), (blk, 1, mb, rb, 29 + case), partials=False, kernel=BF16,
+         beta=float(rng.integers(2)))
+
+
+@pytest.mark.parametrize("K", [32, 128, 160, 256, 384, 512, 640, 4100])
+def test_bf16_kernel_every_pipeline_length(hb, K):
+    """4 to 132 k-steps of 32: start-up, steady state and the drain of the four-stage ring; 2 x 3 tiles with ragged edges."""
+    A, B = _rand((300, K), K + 25), _rand((K, 520), K + 26)
+    _run(hb, A, B, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=BF16)
+    _run(hb, A, B, (1, 24, 7, 1, 5), (24, 1, 8, 1, 6), partials=False, kernel=BF16, beta=1.0)
+
+
+def test_bf16_kernel_extreme_mantissas_and_exponents(hb):
+    """Every mantissa +-127 (9-bit: +-255) over K = 4096; rows and columns spread over 2^+-20; values pushed towards both
+    ends of the FP32 range: products that are FP32 subnormals, and a block whose exponent byte is 254 (computed inside the
+    same kernel from the stored operands)."""
+    M, N, K = 64, 96, 4096
+    rng = np.random.default_rng(0)
+    for m, top in ((8, 127.0), (9, 255.0)):
+        A = (rng.choice([-1.0, 1.0], size=(M, K)) * top).astype(np.float32)
+        B = (np.ones((K, N)) * top).astype(np.float32)
+        B[:, ::2] *= -1
+        _run(hb, A, B, (1, 32, m, 0, 0), (32, 1, m, 0, 0), partials=False, kernel=BF16)
+    A = (rng.standard_normal((M, 512)) * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)
+    B = (rng.standard_normal((512, N)) * np.exp2(rng.integers(-20, 21, size=(1, N)))).astype(np.float32)
+    _run(hb, A, B, (1, 24, 8, 0, 0), (24, 1, 8, 0, 0), partials=False, kernel=BF16)
+    tiny = (rng.standard_normal((M, 512)) * 2.0 ** -124).astype(np.float32)
+    _run(hb, tiny, B * np.float32(2.0 ** -20), (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=BF16)
+    _run(hb, (tiny * np.float32(0.25)).astype(np.float32), rng.standard_normal((512, N)).astype(np.float32), (1, 32, 8, 0, 0),
+         (32, 1, 8, 0, 0), partials=False, kernel=BF16)
+    huge = rng.standard_normal((M, 512)).astype(np.float32)
+    huge[3, 40] = 2.0 ** 127
+    small = (rng.standard_normal((512, N)) * 2.0 ** -30).astype(np.float32)
+    _run(hb, huge, small, (1, 32, 8, 0, 0), (32, 1, 8, 0, 0), partials=False, kernel=BF16)
+    _run(hb, huge, small, (1, 24, 9, 0, 0), (24, 1, 9, 0, 0), partials=False, kernel=BF16, beta=1.0)
+
+
+def test_bf16_kernel_is_the_automatic_choice_and_equals_the_packed_route(hb):
+    """hbfp_gemm on a shape where 256 x 256 tiles pay gives, bit for bit, what HBFP_KERNEL_BF16 and hbfp_gemm_packed on
+    operands packed beforehand give; a batch of such products in one launch likewise."""
+    M, K, N = 3072, 2048, 3072
+    rng = np.random.default_rng(12)
+    X = torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)).cuda()
+    W = torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)).cuda()
+    x, w = hb.encode(X, 1, hb.make_format(8, 1, 24)), hb.encode(W, 0, hb.make_format(8, 24, 1))
+    assert hb.gemm_workspace(x.desc, w.desc) == hb.gemm_select_workspace(x.desc, w.desc, BF16)
+    auto, named, packed = hb.gemm(x, w), hb.gemm(x, w, kernel=BF16), hb.gemm_packed(x, hb.pack(x), w, hb.pack(w))
+    both = hb.gemm_batch([(x, w), (x, w)], [torch.empty_like(auto), torch.empty_like(auto)])
+    int8 = hb.gemm(x, w, kernel=1)
+    torch.cuda.synchronize()
+    assert torch.equal(auto, named) and torch.equal(auto, packed) and torch.equal(both[0], auto) and torch.equal(both[1], auto)
+    assert rel_fro(auto.cpu().numpy(), int8.cpu().numpy().astype(np.float64)) <= 2e-6
+
+
 # ---- the 256 x 256-tile int8 kernel for one exponent per operand row (HBFP_KERNEL_INT8_WIDE)
 
 WIDE = 3
@@ -1007,8 +1080,8 @@ def test_batch_mixed_formats_and_argument_checks(hb):
 
 def test_batch_that_fills_the_chip_only_together_sampled(hb):
     """Four products of 64 output tiles each: alone the library gives each to the int8 kernels, in one batch they
-    share a launch of the block-scaled kernel.  Sampled rows against the oracle; every product bit for bit what
-    the block-scaled kernel returns for it alone."""
+    share a launch of the bf16 kernel (8-bit mantissas).  Sampled rows against the oracle; every product bit for bit
+    what that kernel returns for it alone."""
     M = N = 2048
     K = 1024
     fa, fb = (1, 32, 8, 0, 0), (32, 1, 8, 0, 0)
@@ -1020,14 +1093,14 @@ def test_batch_that_fills_the_chip_only_together_sampled(hb):
                       hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(8, 32, 1))))
         want.append(ref.gemm(ref.decode(ref.encode(A, *fa)), ref.decode(ref.encode(B, *fb)), rows=rows))
     assert hb.gemm_workspace(pairs[0][0].desc, pairs[0][1].desc) == hb.gemm_select_workspace(pairs[0][0].desc, pairs[0][1].desc, 1)
-    assert hb.gemm_batch_workspace(pairs) == 4 * hb.gemm_select_workspace(pairs[0][0].desc, pairs[0][1].desc, SCALED)
+    assert hb.gemm_batch_workspace(pairs) == 4 * hb.gemm_select_workspace(pairs[0][0].desc, pairs[0][1].desc, BF16)
     outs = [torch.full((M, N), 5.0, device="cuda") for _ in range(4)]
     hb.gemm_batch(pairs, outs)
     torch.cuda.synchronize()
     for i in range(4):
         print(f"[case] grouped batch, product {i}", flush=True)
         assert rel_fro(outs[i].cpu().numpy()[rows], want[i]) <= TOL
-        alone = hb.gemm(pairs[i][0], pairs[i][1], kernel=SCALED)
+        alone = hb.gemm(pairs[i][0], pairs[i][1], kernel=BF16)
         torch.cuda.synchronize()
         assert torch.equal(outs[i], alone)
 
