@@ -3,16 +3,17 @@
 
 A step is one pass of the whole path over one batch of config 4 (dense layer,
 M = K = N = 4096, 8-bit mantissas, 1 x 24 activation/gradient blocks, 24 x 24 weight
-tiles): for each of the forward, data-gradient and weight-gradient products, both
-operands are converted FP32 -> BFP and multiplied (hbfp_gemm: for this shape the
-library picks the block-scaled matrix instruction, 8-bit mantissas as two 4-bit limbs,
-exponent bytes applied in the instruction, FP32 accumulation).  Each of the three FP32 matrices (input, weights,
-output gradient) is converted into both operand layouts it is needed in by one
-hbfp_encode_multi call (the weight tiles from a single read; the 1-D activation blocks
-by one kernel per layout); the cpu_baseline leg does the same six conversions one by
-one.  Inputs are resident in HBM before the timed
-region.  One JSON line is printed; `value` is effective TOP/s (2*M*N*K per product,
-padding not counted) including every conversion.
+tiles): the three FP32 matrices (input, weights, output gradient) are converted
+FP32 -> BFP, each into both operand layouts it is needed in, stored and packed, by
+one kernel that reads it once (hbfp_encode_packed_batch for input and weights,
+hbfp_encode_packed for the gradient), and the forward, data-gradient and
+weight-gradient products are multiplied from the packed operands (hbfp_gemm_packed,
+hbfp_gemm_packed_batch: 8-bit mantissas times their block's power of two are exact
+bf16 numbers, so the products run on the bf16 matrix instruction with FP32
+accumulation).  The cpu_baseline leg does the same six conversions one by one and the
+three products in FP64.  Inputs are resident in HBM before the timed region.  One JSON
+line is printed; `value` is effective TOP/s (2*M*N*K per product, padding not counted)
+including every conversion.
 
 The same line carries: the roofline of the dominant kernel (the GEMM) and of the
 encode kernel on config 2 (64M log-normal values, blocks of 32), both timed with HIP
@@ -36,16 +37,19 @@ FP6_PEAK_TFLOPS = 10100.0  # MI355X dense FP6 / FP4 matrix peak, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X FP32 vector peak, published (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 HBM_PEAK_GBPS = 8000.0    # MI355X HBM3E peak, published
 
+BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_config4_hbm_traffic_counters.txt for the
 # product kernel of config 4 alone, profiles/bench_default_hbm_traffic_counters.txt for the encode), scaled by what the same
 # counters read for a plain 1 GiB device copy (fetch x2.0, write x1.0):
-#   config 4 product kernel (gemm_mx_kernel<2, 2, false>, 64 k-steps): 80048 KiB x 2.0 + 65536 KiB = 231.0 MB
+#   config 4 product kernel (gemm_bf_kernel, 128 k-steps of 32): 98454 KiB x 2.0 + 65536 KiB = 268.7 MB
 #   config 2 encode m=8 RNE launch: 131552 KiB x 2.0 + 67588 KiB = 338.6 MB   (algorithmic 337.6 MB)
-TRAFFIC_GEMM_C4_BYTES = 231.0e6
+TRAFFIC_GEMM_C4_BYTES = 268.7e6
 TRAFFIC_ENCODE_C2_M8_BYTES = 338.6e6
-# algorithmic bytes of the config 4 product kernel: both operands as densely packed limb planes read once (16 panels of
-# 256 rows x 64 k-steps x 26624 bytes each) and C written once; operand panels are re-read by the workgroups of different XCDs
-ALG_BYTES_GEMM_C4 = 2 * 16 * 64 * 26624 + 4096 * 4096 * 4
+# algorithmic bytes of the config 4 product kernel: both operands as bf16 planes read once (4096 rows x 4096 k x 2 bytes
+# each: blocks of 24 are packed without their padding) and C written once; operand panels are re-read by the workgroups
+# of different XCDs
+ALG_BYTES_GEMM_C4 = 2 * 4096 * 4096 * 2 + 4096 * 4096 * 4
 
 
 def _parse():
@@ -491,7 +495,8 @@ def _kernel_families(torch, hbfp, reps=8):
             del wse
         del A, B
         out = torch.empty((n, n), dtype=torch.float32, device="cuda")
-        families = [("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)] + ([("fp16", hbfp.KERNEL_FP16)] if m > 8 else [])
+        families = [("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)] + ([("fp16", hbfp.KERNEL_FP16)] if m > 8 else []) + \
+                   ([("bf16", hbfp.KERNEL_BF16)] if 6 <= m <= 9 else [])
         for tag, kernel in families:
             ws = torch.empty(max(hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel), 256), dtype=torch.uint8, device="cuda")
             ms = _time_call(torch, lambda: hbfp.gemm(ta, tb, out=out, workspace=ws, kernel=kernel), reps)
@@ -509,9 +514,11 @@ def _kernel_families(torch, hbfp, reps=8):
 
 
 def _heavy_tails(torch, hbfp, reps=10):
-    """A 4096^3 product of config 4's formats whose activation operand is heavy-tailed (Student-t, 3 degrees of freedom):
-    its packed form is marked, so hbfp_gemm_packed hands over to its int8 stand-by: the 4-wave kernel by default, the
-    8-wave kernel when the operand carries HBFP_HINT_HEAVY_TAILS; hbfp_gemm_select with HBFP_KERNEL_INT8 for comparison."""
+    """A 4096^3 product of config 4's formats whose activation operand is heavy-tailed (Student-t, 3 degrees of freedom).
+    8-bit mantissas are packed as bf16 numbers, which take any spread of block exponents: the operand is not marked and
+    the product runs as fast as any other (the block-scaled limb packing used to hand such operands to the int8 kernels;
+    HBFP_HINT_HEAVY_TAILS, which chooses the faster of those as the stand-by, matters for 4-bit mantissas only);
+    hbfp_gemm_select with HBFP_KERNEL_INT8 for comparison."""
     n = 4096
     g = torch.Generator(device="cuda").manual_seed(11)
     z = torch.randn((n, n), device="cuda", generator=g)
@@ -546,8 +553,12 @@ def _matrix_probe(torch, hbfp, iters=3000):
     g = torch.Generator(device="cuda").manual_seed(1)
     operands = {"constant_bits": torch.full((64 * 64,), 0x01010101, dtype=torch.int32, device="cuda"),
                 "random_bits": torch.randint(-2 ** 31, 2 ** 31 - 1, (64 * 64,), dtype=torch.int64, device="cuda", generator=g).to(torch.int32)}
-    for name, instr, flop in (("int8_32x32x32", 0, 2.0 * 32 * 32 * 32), ("scaled_fp6_32x32x64", 1, 2.0 * 32 * 32 * 64)):
-        for tag, words in operands.items():
+    # bf16 operands: integers -127..127 times a power of two from 8 binades, as the packed operands of the product hold them
+    vals = torch.randint(-127, 128, (2 * 64 * 64,), device="cuda", generator=g).float() * torch.exp2(torch.randint(-4, 4, (2 * 64 * 64,), device="cuda", generator=g).float())
+    bf_words = vals.to(torch.bfloat16).view(torch.int32)
+    for name, instr, flop in (("int8_32x32x32", 0, 2.0 * 32 * 32 * 32), ("scaled_fp6_32x32x64", 1, 2.0 * 32 * 32 * 64),
+                              ("bf16_32x32x16", 2, 2.0 * 32 * 32 * 16)):
+        for tag, words in (operands.items() if instr != 2 else (("mantissas_times_powers_of_two", bf_words),)):
             best = None
             for wgs in (512, 1024):
                 hbfp.probe_matrix_rate(instr, words, wgs, 100, sink, clocks)
@@ -564,8 +575,8 @@ def _matrix_probe(torch, hbfp, iters=3000):
                     best = {"T_per_s": round(rate, 1), "shader_clock_GHz": round(c[0] / max(c[1], 1) * 0.1, 3), "waves_per_simd": wgs // 512,
                             "ms": round(ms, 3)}
             res[f"{name}_{tag}"] = best
-    res["note"] = ("T_per_s: tera-operations per second of the loop (int8: TOP/s, FP6: TFLOP/s), best of 1 and 2 waves per SIMD; "
-                   "the published peaks are 5000 and 10100")
+    res["note"] = ("T_per_s: tera-operations per second of the loop (int8: TOP/s, FP6 and bf16: TFLOP/s), best of 1 and 2 waves per SIMD; "
+                   "the published peaks are 5000, 10100 and 2500")
     return res
 
 
@@ -663,12 +674,9 @@ def main():
     ms_step = t_begin.elapsed_time(t_end) / args.steps
     tops = flops_step / ms_step / 1e9
 
-    # one hbfp_gemm_packed call = the product kernel plus the int8 stand-by launch behind it, which exits at once
-    # when every exponent is in range (4 us of the bracket; the rocprofv3 summary lists the two separately)
+    # one hbfp_gemm_packed call = one launch of the bf16 product kernel
     product_ms = timer.total_ms("gemm") / timer.count("gemm")
     product_tops = flops_product / product_ms / 1e9
-    # the block-scaled kernel multiplies every pair of 4-bit limbs: 2 x 2 limb products per mantissa product
-    limb_tflops = 4.0 * product_tops
     enc_xw_ms = timer.total_ms("encode_x_w") / n_bracketed
     enc_dy_ms = timer.total_ms("encode_act") / n_bracketed
     pair_ms = timer.total_ms("gemm_pair") / timer.count("gemm_pair")
@@ -686,7 +694,7 @@ def main():
         "metric": "BFP8 GEMM effective TOPS incl. encode (% int8 MFMA peak); encode GB/s",
         "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 mantissas as 4-bit limbs in FP6 (E2M3), block-scaled matrix instruction, FP32 accumulate", "data": "synthetic",
+        "dtype": "int8 mantissas x 2^exponent as bf16 numbers (exact), bf16 matrix instruction, FP32 accumulate", "data": "synthetic",
         "config": {"workload": "config 4: dense layer M=K=N=4096, BFP8, 1x24 activation blocks, 24x24 weight tiles, "
                                "forward + data gradient + weight gradient, all six operand encodes included (2 conversion calls: input and weights in one launch, then the "
                                "output gradient; 3 products: "
@@ -696,23 +704,20 @@ def main():
         "breakdown_ms_per_step": {"gemm_x3": round(gemm_step_ms, 4), "encode_input_and_weights_x4": round(enc_xw_ms, 4),
                                   "encode_output_gradient_x2": round(enc_dy_ms, 4)},
         "TOPS_kernel_only": round(flops_step / gemm_step_ms / 1e9, 2),
-        # Roofline of the dominant kernel against the peak the metric names: effective operations 2*M*N*K, counted once
-        # per mantissa product, over the product kernel's launch time, against the published dense int8 matrix peak.
-        # The kernel reaches them with 4 limb products per mantissa product on the FP6 rate of the block-scaled
-        # instruction (limb_products: the same time against the published FP6 peak).
-        "roofline": {"bound": "mfma", "kernel": "gemm_mx_kernel<2, 2, false>", "achieved": round(product_tops, 1),
-                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(product_tops / INT8_PEAK_TOPS, 4),
+        # Roofline of the dominant kernel: a dense contraction on the bf16 matrix instruction, so its operations
+        # (2*M*N*K, one multiply-add per mantissa pair) over the kernel's launch time against the published dense bf16
+        # peak; vs_int8_peak is the same rate against the int8 peak that the metric names.
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf_kernel", "achieved": round(product_tops, 1),
+                     "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(product_tops / BF16_PEAK_TFLOPS, 4),
+                     "vs_int8_peak": round(product_tops / INT8_PEAK_TOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
                      "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
                      "algorithmic_ops_per_launch": flops_product, "backward_pair_launch_ms": round(pair_ms, 4),
-                     "limb_products": {"achieved": round(limb_tflops, 1), "peak": FP6_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                       "frac": round(limb_tflops / FP6_PEAK_TFLOPS, 4),
-                                       "note": "4 exact limb products per 8-bit mantissa product, every one of them matrix-core work"},
                      "note": "avg_launch_ms is the HIP-event time of the hbfp_gemm_packed call of the step (the forward product) on the "
-                             "launch stream: the product kernel (grid 131072) plus the int8 stand-by kernel behind it (exits at once "
-                             "when every exponent is in range); backward_pair_launch_ms is the hbfp_gemm_packed_batch call: the same "
-                             "kernel over both backward products (grid 262144) plus two stand-by launches; the operands were packed "
-                             "by the conversion calls; the rocprofv3 summary lists each kernel"},
+                             "launch stream: one launch of the product kernel (grid 256 workgroups of 512 threads); "
+                             "backward_pair_launch_ms is the hbfp_gemm_packed_batch call: the same kernel over both backward "
+                             "products (grid 512); the operands were packed by the conversion calls; the rocprofv3 summary lists "
+                             "each kernel"},
     }
     if not args.no_probe:
         out["roofline"]["matrix_probe"] = _matrix_probe(torch, hbfp)

@@ -560,13 +560,14 @@ int hbfp_weight_update(const hbfp_tensor *wide, const float *delta, int64_t ld, 
  * hbfp_probe_matrix_rate: measurement aid, not part of the path.  Runs a register-only loop of one matrix instruction
  * (no memory traffic inside the loop) on every compute unit, so that a caller can time what the matrix core sustains
  * for given operand bits: the chip lowers its clock under its power limit, and how far depends on the bits.
- *   instruction  0: v_mfma_i32_32x32x32_i8;  1: v_mfma_scale_f32_32x32x64_f8f6f4 with FP6 (E2M3) operands
+ *   instruction  0: v_mfma_i32_32x32x32_i8;  1: v_mfma_scale_f32_32x32x64_f8f6f4 with FP6 (E2M3) operands;
+ *                2: v_mfma_f32_32x32x16_bf16 (four registers per operand: every half word a finite bf16 number)
  *   words        device, 64 x 64 ints: register r of lane l at words[r * 64 + l]; registers 0..31 feed the first
  *                operands of the 4 x 4 independent chains of a wave, 32..63 the second operands
  *   workgroups   workgroups of 4 waves (8 .. 65536); iters: loop trips, 16 matrix instructions per wave each
  *   sink         device, workgroups * 256 floats (written, so that the loop is not removed)
  *   clocks       device, 2 x int64: shader cycles and 100 MHz wall-clock ticks of the loop of workgroup 7
- * One trip is 16 instructions of 2 * 32 * 32 * 32 (int8) or 2 * 32 * 32 * 64 (FP6) operations per wave.
+ * One trip is 16 instructions of 2 * 32 * 32 * 32 (int8), 2 * 32 * 32 * 64 (FP6) or 2 * 32 * 32 * 16 (bf16) operations per wave.
  * Errors: HBFP_ERR_ARG, HBFP_ERR_LAUNCH.
  */
 int hbfp_probe_matrix_rate(int instruction, const int *words, int workgroups, int iters, float *sink, long long *clocks,
