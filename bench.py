@@ -714,7 +714,8 @@ def main():
                      "algorithmic_bytes": ALG_BYTES_GEMM_C4, "avg_launch_ms": round(product_ms, 4),
                      "algorithmic_ops_per_launch": flops_product, "backward_pair_launch_ms": round(pair_ms, 4),
                      "note": "avg_launch_ms is the HIP-event time of the hbfp_gemm_packed call of the step (the forward product) on the "
-                             "launch stream: one launch of the product kernel (grid 256 workgroups of 512 threads); "
+                             "launch stream: one launch of the product kernel (grid 256 workgroups of 512 threads; the bracket holds 3 to 4 us of "
+                             "dispatch latency on top of the kernel duration that rocprofv3 lists); "
                              "backward_pair_launch_ms is the hbfp_gemm_packed_batch call: the same kernel over both backward "
                              "products (grid 512); the operands were packed by the conversion calls; the rocprofv3 summary lists "
                              "each kernel"},

@@ -122,9 +122,11 @@ typedef struct hbfp_tensor {
     uint64_t seed;
     uint64_t mant_bytes, exp_bytes;
 } hbfp_tensor;
-/* The values of this operand are heavy-tailed (gradients often are): its packed form will usually be marked (see hbfp_pack),
- * so products on packed operands prepare the faster of the int8 kernels as their stand-by.  That costs about 2 us per
- * product when the stand-by turns out not to be needed and saves a quarter of the time of a product when it is. */
+/* The values of this operand are heavy-tailed (gradients often are).  It matters for mantissas of at most 5 bits, whose
+ * packed form (limb planes with group exponents) will then usually be marked (see hbfp_pack): products on packed operands
+ * prepare the faster of the int8 kernels as their stand-by.  That costs about 2 us per product when the stand-by turns out
+ * not to be needed and saves a quarter of the time of a product when it is.  Mantissas of 6..9 bits are packed as bf16
+ * numbers, which heavy tails do not mark; the hint changes nothing for them. */
 #define HBFP_HINT_HEAVY_TAILS 1
 
 /* Library version and a short text for a status code (host, never NULL). */
@@ -380,27 +382,33 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
                   size_t ws_bytes, void *stream);
 
 /*
- * hbfp_pack / hbfp_gemm_packed: the block-scaled kernel in two steps, for operands that take part in many
- * products (weights between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders
- * an encoded operand (mantissas of at most 12 bits) into the limb planes that kernel reads:
+ * hbfp_pack / hbfp_gemm_packed: the product in two steps, for operands that take part in many products (weights
+ * between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders an encoded operand
+ * (mantissas of at most 12 bits) into the form the product kernels read.  The form depends on the operand's mantissa
+ * width alone: 6..9 bits -> the bf16 values of its elements (Eq. (1), exact: at most 8 significant bits) in the
+ * register order of the bf16 matrix instruction; otherwise -> planes of 4-bit limbs with scale bytes for the
+ * block-scaled matrix instruction.
  *   packed  device buffer of hbfp_pack_bytes bytes, 256-byte aligned, owned by the caller; its contents are
  *           opaque and stay valid until the operand is encoded again (then pack it again).  The first 256 bytes
- *           hold a mark that differs from pack to pack (it lets a pack signal "exponent out of range" without
+ *           hold a mark that differs from pack to pack (it lets a pack signal "cannot be expressed" without
  *           anything having to be cleared first), so two packs of the same operand agree from byte 256 on, not
  *           before: the rule "same inputs, same bytes" holds for every result except this header.  Its first two
- *           32-bit words are equal exactly when the operand is marked (an exponent out of range, or neighbouring
- *           blocks of a densely packed group more than 3 binades apart, as heavy-tailed values produce them); a
- *           caller may read them once the pack has completed: products on a marked operand are computed by the
- *           older int8 kernel inside the same call (by the faster one if the operand carries HBFP_HINT_HEAVY_TAILS),
- *           and hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored operands is the fastest way to that product.
+ *           32-bit words are equal exactly when the operand is marked: bf16 planes, a non-zero block with an exponent
+ *           byte above 253 (values from 2^127 on); limb planes, an exponent byte outside the range of the scale bytes,
+ *           or neighbouring blocks of a densely packed group more than 3 binades apart, as heavy-tailed values produce
+ *           them.  A caller may read the words once the pack has completed.  Products on a marked operand are still
+ *           computed inside the same call: from the stored operands by the bf16 kernel itself (slowly; such values do
+ *           not occur in training data), or by the older int8 kernel behind the block-scaled kernel (by the faster one
+ *           if the operand carries HBFP_HINT_HEAVY_TAILS; hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored operands
+ *           is the fastest way to that product).
  *           The buffer is
  *           sized for blocks stored padded to 32; blocks of 8, 16 and 24 elements are packed without their
  *           padding and leave its tail unwritten.
- * hbfp_gemm_packed is hbfp_gemm_select with HBFP_KERNEL_SCALED on operands packed beforehand: C and beta as in
- * hbfp_gemm; A and B are the descriptors the buffers were packed from (their mantissas and exponents are read
- * only when an operand holds a non-zero block outside the range of the scale bytes, in which case the int8
- * kernels compute the product inside the same call); workspace: hbfp_gemm_packed_workspace bytes (what the int8
- * kernels need).
+ * hbfp_gemm_packed is hbfp_gemm_select on operands packed beforehand, with HBFP_KERNEL_BF16 when both are bf16 planes
+ * and HBFP_KERNEL_SCALED when both are limb planes (a pair of the two forms is multiplied by the int8 kernels from the
+ * stored operands): C and beta as in hbfp_gemm; A and B are the descriptors the buffers were packed from (their
+ * mantissas and exponents are read only in the cases just named); workspace: hbfp_gemm_packed_workspace bytes (what the
+ * int8 kernels need).
  * Errors: HBFP_ERR_ARG (null or misaligned pointers, beta, ldc), HBFP_ERR_FORMAT (mantissas wider than 12 bits,
  * mixed classes), HBFP_ERR_LAYOUT, HBFP_ERR_RANGE as hbfp_gemm, HBFP_ERR_WORKSPACE (packed buffer or workspace too
  * small), HBFP_ERR_LAUNCH.
@@ -414,13 +422,13 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
 /*
  * hbfp_gemm_packed_batch: hbfp_gemm_batch for operands packed beforehand: up to HBFP_BATCH_MAX independent products
  * (the data-gradient and weight-gradient products of a layer, Sec. 5.1, which both wait for the same gradient) in one
- * launch of the block-scaled kernel, so that the output tiles of one product are stored while the next product's
+ * launch of the bf16 or the block-scaled kernel, so that the output tiles of one product are stored while the next product's
  * tiles are being multiplied.  Every product is bit for bit what hbfp_gemm_packed computes for it.
  *   A, packed_a, B, packed_b, C, ldc   host arrays of n entries, each as the arguments of hbfp_gemm_packed
  *   workspace                          hbfp_gemm_packed_batch_workspace bytes, 256-byte aligned
  * Errors: as hbfp_gemm_packed for the first product that fails a check (nothing has been launched then);
- * HBFP_ERR_FORMAT if the products do not all have the same limb counts (mantissas of up to 5, 6..9 or 10..12 bits,
- * operand by operand).
+ * HBFP_ERR_FORMAT if the products do not all have the same packed forms and limb counts (mantissas of up to 5, 6..9 or
+ * 10..12 bits, operand by operand).
  */
 int hbfp_gemm_packed_batch_workspace(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, size_t *bytes);
 int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const *packed_a, const hbfp_tensor *const *B,

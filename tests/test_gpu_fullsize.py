@@ -6,7 +6,9 @@ half drawn at random.  Three checks per product:
     bound: |C - C64| <= n_acc * 2^-24 * sum_b |term_b|, term_b the scaled integer sum of block b (Eq. (2)) taken
     from the oracle's block sums, n_acc the number of FP32 accumulations an output receives (one per block on
     the int8 kernels; limb pairs x groups of 32 on the block-scaled kernel, where every limb product of a group is
-    accumulated by an instruction of its own);
+    accumulated by an instruction of its own).  On the bf16 kernel the sums inside a block are FP32 sums too, so there
+    the bound is taken against the sum of |a_k b_k| over all k, with two roundings allowed per matrix instruction
+    (16 products);
   * the integer block sums of four random 32 x 32 windows of the product (hbfp_gemm_partials_window) equal the
     oracle's bit for bit."""
 import numpy as np
@@ -75,7 +77,10 @@ def _check_product(hb, name, ta, tb, oa, ob, fa, fb, C, rows, kernel_is_scaled, 
     np.testing.assert_allclose(ref.scale_accumulate(P, ea, eb, fa[2], fb[2]), C64, rtol=1e-11, atol=0)   # the oracle agrees with itself both ways (FP64 summation order apart)
     terms = ref.scale_accumulate(np.abs(P), ea, eb, fa[2], fb[2])
     limbs = lambda m: 1 if m <= 5 else 2 if m <= 9 else 3
-    if kernel_is_scaled == "fp16":       # every FP16 matrix instruction (16 products) may round once, then one per block
+    if kernel_is_scaled == "bf16":
+        terms = np.abs(A_dec[rows]) @ np.abs(B_dec)
+        n_acc = 2 * -(-K // 16)
+    elif kernel_is_scaled == "fp16":     # every FP16 matrix instruction (16 products) may round once, then one per block
         n_acc = nblk + -(-ta.desc.kpad // 16)
     else:
         n_acc = max(nblk, limbs(fa[2]) * limbs(fb[2]) * 2 * (-(-K // 64))) if kernel_is_scaled else nblk
@@ -134,7 +139,7 @@ def test_config4_step_as_the_benchmark_runs_it(hb):
                                  [torch.full((4096, 4096), float("nan"), device="cuda") for _ in range(2)])
     torch.cuda.synchronize()
     for (name, a, pa, b, pb, oa, ob, fa, fb, sa, sb), C in zip(cases, outs):
-        _check_product(hb, name, a, b, oa, ob, fa, fb, C, rows, True, rng, src_a=sa, src_b=sb)
+        _check_product(hb, name, a, b, oa, ob, fa, fb, C, rows, "bf16", rng, src_a=sa, src_b=sb)
     one = hb.gemm_packed(d_d, pd_d, w_d, pw_d)
     torch.cuda.synchronize()
     assert torch.equal(one, outs[1])                       # the shared launch changes no bit
