@@ -15,7 +15,7 @@ from tests.util import unpack
 
 pytestmark = pytest.mark.gpu
 
-AUTO, INT8, SCALED, WIDE, FP16 = 0, 1, 2, 3, 4
+AUTO, INT8, SCALED, WIDE, FP16, BF16 = 0, 1, 2, 3, 4, 5
 
 
 @pytest.fixture(scope="module")
@@ -72,12 +72,12 @@ def _exact(hb, A, B, fa, fb, kernel, check_integers=True):
 
 
 # ------------------------------------------------------------------ 8-bit mantissas: every product kernel
-@pytest.mark.parametrize("kernel", [INT8, SCALED])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, BF16])
 @pytest.mark.parametrize("kb,K", [(32, 1024), (24, 1000), (64, 1024), (16, 400), (8, 264)])
 def test_exact_sums_8_bit_blocks(hb, kernel, kb, K):
     """Random mantissas in [-127, 127], one +-127 planted per block: equal exponent bytes, |sum| <= 1024 * 127^2 < 2^24.
     Blocks of 32 / 24 / 16 / 8 (one matrix instruction per block), 64 (two, chained): the int8 kernels' three block
-    modes and the two-limb block-scaled kernel, several 256 x 256 tiles with ragged edges."""
+    modes, the two-limb block-scaled kernel and the bf16 kernel, several 256 x 256 tiles with ragged edges."""
     rng = np.random.default_rng(1000 + kb + K + kernel)
     M, N = 300, 530
     A = _integers(rng, (M, K), kb, 1, 127)
@@ -85,7 +85,7 @@ def test_exact_sums_8_bit_blocks(hb, kernel, kb, K):
     _exact(hb, A, B, (1, kb, 8), (kb, 1, 8), kernel)
 
 
-@pytest.mark.parametrize("kernel", [INT8, SCALED, AUTO])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, AUTO, BF16])
 @pytest.mark.parametrize("kb,K", [(128, 1024), (256, 768), (512, 1024), (0, 896)])
 def test_exact_sums_8_bit_long_blocks(hb, kernel, kb, K):
     """Blocks of 128 and more, and one exponent per row / column (Sec. 4): chains of matrix instructions."""
@@ -113,7 +113,7 @@ def test_long_blocks_of_equal_signs_stay_exact(hb, kernel, kb, K):
     _exact(hb, A, B, (1, kb, 8), (kb, 1, 8), kernel)
 
 
-@pytest.mark.parametrize("kernel", [INT8, SCALED])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, BF16])
 def test_exact_sums_config4_formats(hb, kernel):
     """1 x 24 activation blocks against 24 x 24 weight tiles, ragged last block (1000 = 41 * 24 + 16)."""
     rng = np.random.default_rng(77 + kernel)
@@ -124,7 +124,7 @@ def test_exact_sums_config4_formats(hb, kernel):
 
 
 # ------------------------------------------------------------------ one block, unequal exponents
-@pytest.mark.parametrize("kernel", [INT8, SCALED])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, BF16])
 @pytest.mark.parametrize("kb", [32, 24, 64])
 def test_single_block_with_unequal_exponents(hb, kernel, kb):
     """One block along k (K = kb): C[i][j] = P[i][j] * 2^(eA[i] + eB[j]) with |P| < 2^24 is exact for any exponents.
@@ -136,7 +136,7 @@ def test_single_block_with_unequal_exponents(hb, kernel, kb):
     _exact(hb, A.astype(np.float32), B.astype(np.float32), (1, kb, 8), (kb, 1, 8), kernel)
 
 
-@pytest.mark.parametrize("kernel", [INT8, SCALED])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, BF16])
 def test_blocks_with_unequal_exponents_and_disjoint_support(hb, kernel):
     """Several blocks with different exponents each: row i of A is non-zero only in block i % nblk, so each output is a
     single block product and stays exact, while the kernel still walks all blocks with their own scale words."""
@@ -171,7 +171,7 @@ def test_exact_sums_mixed_limb_counts(hb, ma, mb):
     """Operands with different limb counts (2 x 1, 1 x 2) and 9-bit mantissas (two limbs, |m| up to 255)."""
     ta_, tb_ = (1 << (ma - 1)) - 1, (1 << (mb - 1)) - 1
     K = 1024 if ma * mb <= 32 else 256
-    for kernel in (INT8, SCALED):
+    for kernel in (INT8, SCALED) + ((BF16,) if ma == mb == 9 else ()):        # 9-bit mantissas (int16 storage) are bf16 numbers too
         rng = np.random.default_rng(4100 + ma * 16 + mb + kernel)
         M, N = 260, 300
         A = _integers(rng, (M, K), 32, 1, ta_)
