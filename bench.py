@@ -531,7 +531,8 @@ def _heavy_tails(torch, hbfp, reps=10):
     hbfp.encode_packed(X, [x], [px])
     hbfp.encode_packed(W, [w], [pw])
     out = torch.empty((n, n), dtype=torch.float32, device="cuda")
-    ws = torch.empty(max(hbfp.gemm_packed_workspace(x.desc, w.desc), 256), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(hbfp.gemm_packed_workspace(x.desc, w.desc), hbfp.gemm_select_workspace(x.desc, w.desc, hbfp.KERNEL_INT8), 256),
+                     dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     mark = px[:8].view(torch.int32).tolist()
     res = {"operand_marked": mark[0] == mark[1]}

@@ -408,7 +408,7 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
  * and HBFP_KERNEL_SCALED when both are limb planes (a pair of the two forms is multiplied by the int8 kernels from the
  * stored operands): C and beta as in hbfp_gemm; A and B are the descriptors the buffers were packed from (their
  * mantissas and exponents are read only in the cases just named); workspace: hbfp_gemm_packed_workspace bytes (what the
- * int8 kernels need).
+ * int8 kernels need; nothing for a pair of bf16 planes).
  * Errors: HBFP_ERR_ARG (null or misaligned pointers, beta, ldc), HBFP_ERR_FORMAT (mantissas wider than 12 bits,
  * mixed classes), HBFP_ERR_LAYOUT, HBFP_ERR_RANGE as hbfp_gemm, HBFP_ERR_WORKSPACE (packed buffer or workspace too
  * small), HBFP_ERR_LAUNCH.

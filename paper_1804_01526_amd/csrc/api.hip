@@ -805,11 +805,8 @@ static int gemm_bfp_plan(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_
     if (rc != HBFP_OK) return rc;
     if (out->src_rows != A->rows || out->src_cols != B->rows) return HBFP_ERR_LAYOUT;
     const GemmArgs g = gemm_args(A, B);
-    // the automatic choice keeps the block-scaled kernel where that one can convert its accumulators itself: the bf16
-    // kernel would be faster as a product (it is the choice for FP32 outputs) but not by the separate conversion pass
-    if (kernel == HBFP_KERNEL_AUTO && use_bf(g, kernel) && mx_encoded_output_ok(*out)) kernel = HBFP_KERNEL_SCALED;
     *kernel_used = kernel;
-    *fused = use_scaled(g, kernel) && mx_encoded_output_ok(*out);
+    *fused = (use_scaled(g, kernel) || use_bf(g, kernel)) && mx_encoded_output_ok(*out);
     part[0] = align256((size_t)A->rows * (size_t)B->rows * sizeof(float));
     hbfp_gemm_select_workspace(A, B, kernel, &part[1]);
     part[1] = align256(part[1]);
@@ -847,12 +844,21 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
         if (rc != HBFP_OK) return rc;
         return encode_planned(C, N, out, part[2] != 0, ws_enc, s);
     }
-    // the block-scaled kernel converts its accumulators; should an exponent be outside its range, the int8 kernels behind
-    // it write the FP32 product to the workspace and a conversion behind them produces the same output
     GemmArgs g = gemm_args(A, B);
     g.C = C;
     g.ldc = N;
     g.beta = 0.0f;
+    if (use_bf(g, kernel)) {
+        // the bf16 kernel converts its accumulators; for a marked operand it writes the FP32 product to the workspace
+        // instead and the conversion behind it, which runs in that case only, produces the same output
+        void *pa = ws_gemm, *pb = ws_gemm + packed_operand_bytes(g.M, g.kpad, g.mA);
+        rc = launch_bf_pack(g, pa, pb, s);
+        if (rc == HBFP_OK) rc = launch_bf_product_encoded(g, pa, pb, *out, relu, s);
+        if (rc != HBFP_OK) return rc;
+        return launch_mx_encode_standby(C, N, *out, relu, (const int *)pa, (const int *)pb, s);
+    }
+    // the block-scaled kernel converts its accumulators; should an exponent be outside its range, the int8 kernels behind
+    // it write the FP32 product to the workspace and a conversion behind them produces the same output
     void *pa = ws_gemm, *pb = ws_gemm + mx_packed_bytes(g.M, g.kpad, g.mA);
     rc = launch_mx_pack(g, pa, pb, s);
     if (rc == HBFP_OK) rc = launch_mx_product_encoded(g, pa, pb, *out, relu, s);
@@ -894,7 +900,9 @@ static int packed_kind(const hbfp_tensor *A, const hbfp_tensor *B) {
 }
 
 int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
-    return hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_INT8, bytes);
+    const int rc = hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_INT8, bytes);
+    if (rc == HBFP_OK && packed_kind(A, B) == kPackedBf) *bytes = 0;      // no stand-by kernels behind the bf16 kernel
+    return rc;
 }
 
 int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tensor *B, const void *packed_b, float *C,

@@ -22,6 +22,7 @@
 
 #include "bf_pack.h"
 #include "hbfp_internal.h"
+#include "mx_out.h"
 
 namespace hbfp {
 namespace {
@@ -153,8 +154,12 @@ struct BfGroup {
     BfParams p[kBfGroup];
     int32_t first[kBfGroup + 1];
     int32_t n;
+    MxOut out;                   // of product 0 of a launch with a single product (TR)
 };
 
+// TR: the variant whose output is an encoded operand (g.out): the operands of the matrix instruction exchanged, so
+// that every 32 x 32 result arrives transposed (same products, same sums) as mx_store_encoded wants them
+template <bool TR>
 __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // which product this workgroup belongs to: selected with constant indices, so that the parameters stay in scalar
@@ -216,8 +221,8 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
         _Pragma("unroll") for (int j = 0; j < 4; ++j) bf[buf][j] = *reinterpret_cast<const v4i_t *>((base_) + bbase + j * kBfTileBytes + (h) * 1024); \
     }
 #define HBFP_BF_MFMA(buf, i, j)                                                                                                    \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, af[buf][i]), __builtin_bit_cast(v8bf, bf[buf][j]), \
-                                                        acc[i][j], 0, 0, 0)
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, TR ? bf[buf][j] : af[buf][i]),                    \
+                                                        __builtin_bit_cast(v8bf, TR ? af[buf][i] : bf[buf][j]), acc[i][j], 0, 0, 0)
 #define HBFP_BF_ROW(buf, i)        \
     {                              \
         HBFP_BF_MFMA(buf, i, 0);   \
@@ -302,6 +307,11 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
 
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t row0 = (int64_t)tm * 256 + wm * 64, col0 = (int64_t)tn * 256 + wn * 128;
+    if (TR) {
+        if (g.out.rounding) mx_store_encoded<1>(g.out, acc, row0, col0, p.M, p.N, lane);
+        else mx_store_encoded<0>(g.out, acc, row0, col0, p.M, p.N, lane);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -383,11 +393,14 @@ int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
     return launch_status();
 }
 
-// n <= HBFP_BATCH_MAX products of operands packed as bf16 planes, in one launch
-int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
-    if (n < 1 || n > kBfGroup) return HBFP_ERR_ARG;
+// n <= HBFP_BATCH_MAX products of operands packed as bf16 planes, in one launch; out: product 0 of a single-product
+// launch is delivered as this encoded operand (a marked operand: the FP32 product goes to args[0].C instead)
+static int launch_bf_group(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, const MxOut *out,
+                           hipStream_t s) {
+    if (n < 1 || n > kBfGroup || (out && n != 1)) return HBFP_ERR_ARG;
     BfGroup g = {};
     g.n = n;
+    if (out) g.out = *out;
     int64_t first = 0;
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
@@ -421,10 +434,26 @@ int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a,
         if (first > 0x7ffffff0) return HBFP_ERR_ARG;
     }
     for (int i = n; i <= kBfGroup; ++i) g.first[i] = (int32_t)first;
-    static std::atomic<bool> configured{false};
-    if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_bf_kernel), kBfRing * kBfStage) != HBFP_OK) return HBFP_ERR_LAUNCH;
-    hipLaunchKernelGGL(gemm_bf_kernel, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    static std::atomic<bool> configured[2];
+    const void *kernel = out ? reinterpret_cast<const void *>(&gemm_bf_kernel<true>) : reinterpret_cast<const void *>(&gemm_bf_kernel<false>);
+    if (allow_dynamic_lds(configured[out ? 1 : 0], kernel, kBfRing * kBfStage) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    if (out) hipLaunchKernelGGL(gemm_bf_kernel<true>, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    else hipLaunchKernelGGL(gemm_bf_kernel<false>, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
     return launch_status();
+}
+
+int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
+    return launch_bf_group(n, args, packed_a, packed_b, nullptr, s);
+}
+
+// The product as an encoded operand (output blocks of 32 or 64 along the columns of the product: mx_encoded_output_ok).
+// a.C / a.ldc: FP32 scratch of M x N that receives the product when an operand is marked; the caller then queues
+// launch_mx_encode_standby behind this launch, which converts it in that case only.
+int launch_bf_product_encoded(const GemmArgs &a, const void *packed_a, const void *packed_b, const hbfp_tensor &out, int relu,
+                              hipStream_t s) {
+    if (!mx_encoded_output_ok(out)) return HBFP_ERR_FORMAT;
+    const MxOut o = mx_out_of(out, relu);
+    return launch_bf_group(1, &a, &packed_a, &packed_b, &o, s);
 }
 
 }  // namespace hbfp

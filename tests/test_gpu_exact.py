@@ -218,7 +218,7 @@ def test_exact_sums_three_limbs(hb, kernel, ma, mb):
 
 
 # ------------------------------------------------------------------ the product delivered as an encoded operand
-@pytest.mark.parametrize("kernel", [SCALED, INT8])
+@pytest.mark.parametrize("kernel", [SCALED, INT8, BF16])
 @pytest.mark.parametrize("out_kb,out_m,relu", [(32, 8, False), (64, 8, True), (32, 12, True), (24, 8, False)])
 def test_encoded_output_of_an_exact_product(hb, kernel, out_kb, out_m, relu):
     """hbfp_gemm_bfp on a product whose FP32 value is exact: the encoded output must equal the ORACLE's conversion of

@@ -1174,12 +1174,16 @@ def _check_bfp_output(hb, A, B, fa, fb, fo, axis, relu, kernel, fused):
 @pytest.mark.parametrize("fo,relu", [((1, 32, 8, 0, 0), False), ((1, 32, 8, 1, 77), True), ((1, 64, 8, 0, 0), True),
                                      ((1, 64, 12, 1, 5), False), ((1, 32, 4, 0, 0), False), ((1, 32, 16, 0, 0), True)])
 @pytest.mark.parametrize("M,N,K", [(300, 270, 704), (256, 512, 128), (70, 33, 200)])
-def test_product_delivered_as_an_encoded_operand(hb, fo, relu, M, N, K):
-    """The block-scaled kernel converting its own accumulators: blocks of 32 and 64 along the columns of the product,
-    8-, 12-, 4- and 16-bit outputs, both roundings, with and without ReLU, ragged edges in every direction."""
-    print(f"[case] encoded output fo={fo} relu={relu} M={M} N={N} K={K}", flush=True)
+@pytest.mark.parametrize("kernel", [2, 5])
+def test_product_delivered_as_an_encoded_operand(hb, fo, relu, M, N, K, kernel):
+    """The block-scaled kernel and the bf16 kernel converting their own accumulators: blocks of 32 and 64 along the
+    columns of the product, 8-, 12-, 4- and 16-bit outputs, both roundings, with and without ReLU, ragged edges in every
+    direction."""
+    print(f"[case] encoded output fo={fo} relu={relu} M={M} N={N} K={K} kernel={kernel}", flush=True)
     A, B = _rand((M, K), 3 + M), (_rand((K, N), 4 + N, 2) * 0.05).astype(np.float32)
-    _check_bfp_output(hb, A, B, (1, 32, 8), (32, 1, 8), fo, 1, relu, SCALED, True)
+    _check_bfp_output(hb, A, B, (1, 32, 8), (32, 1, 8), fo, 1, relu, kernel, True)
+    if kernel == 5 and (M, N, K) == (300, 270, 704):
+        _check_bfp_output(hb, A, B, (1, 24, 7), (24, 1, 7), fo, 1, relu, kernel, True)      # blocks of 24, packed without padding
 
 
 @pytest.mark.parametrize("fo,axis,kernel", [((1, 24, 8, 0, 0), 1, SCALED), ((1, 0, 8, 1, 3), 1, SCALED), ((32, 1, 8, 0, 0), 0, SCALED),
@@ -1205,6 +1209,14 @@ def test_encoded_product_with_wide_operands_and_outside_the_scale_range(hb):
     for fo in [(1, 32, 8, 0, 0), (1, 64, 12, 1, 4)]:
         print(f"[case] encoded output, operands outside the scale range, fo={fo}", flush=True)
         _check_bfp_output(hb, A2, B2, (1, 32, 8), (32, 1, 8), fo, 1, True, SCALED, True)
+    # the bf16 kernel: an operand with an exponent byte of 254 is marked; the kernel then writes the FP32 product to the
+    # workspace and the conversion queued behind it produces the output
+    A3 = A.copy()
+    A3[7, 100] = 2.0 ** 127
+    B3 = (B.astype(np.float64) * 2.0 ** -40).astype(np.float32)
+    for fo in [(1, 32, 8, 0, 0), (1, 64, 12, 1, 4)]:
+        print(f"[case] encoded output of the bf16 kernel, marked operand, fo={fo}", flush=True)
+        _check_bfp_output(hb, A3, B3, (1, 32, 8), (32, 1, 8), fo, 1, True, 5, True)
 
 
 def test_encoded_product_feeds_the_next_product_full_size(hb):
