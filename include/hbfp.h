@@ -345,13 +345,14 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
 /*
  * hbfp_gemm_batch: up to HBFP_BATCH_MAX independent products C[i] (+)= A[i] . B[i]^T in one call (the data-gradient
  * and weight-gradient products of a layer, Sec. 5.1; the products of several layers or micro-batches).  Every
- * product is what hbfp_gemm_select computes for it (bit for bit with HBFP_KERNEL_SCALED and HBFP_KERNEL_INT8; with
- * HBFP_KERNEL_AUTO within the same bound, because the choice of kernel may differ, see below).  Products whose limb
- * counts agree can share one launch of the block-scaled kernel (workgroup ranges of one grid), so that products
- * too small to fill the chip alone fill it together.  They do with HBFP_KERNEL_SCALED, and with HBFP_KERNEL_AUTO
- * when every product would take that kernel anyway or when the group has at least 256 output tiles of 256 x 256,
- * contraction lengths of at least 1024 within a factor of two of each other, and a format the block-scaled kernel
- * is ahead in; otherwise the products run one after the other, each as hbfp_gemm_select runs it.
+ * product is what hbfp_gemm_select computes for it (bit for bit with HBFP_KERNEL_BF16, HBFP_KERNEL_SCALED and
+ * HBFP_KERNEL_INT8; with HBFP_KERNEL_AUTO within the same bound, because the choice of kernel may differ, see below).
+ * Products whose mantissa classes agree can share one launch of the bf16 kernel (6..9-bit mantissas) or of the
+ * block-scaled kernel (workgroup ranges of one grid), so that products too small to fill the chip alone fill it
+ * together.  They do with HBFP_KERNEL_BF16 and HBFP_KERNEL_SCALED, and with HBFP_KERNEL_AUTO when every product would
+ * take that kernel anyway or when the group has at least 256 output tiles of 256 x 256, contraction lengths of at
+ * least 1024 within a factor of two of each other, and a format these kernels are ahead in; otherwise the products
+ * run one after the other, each as hbfp_gemm_select runs it.
  *   A, B, C, ldc   host arrays of n descriptors / device pointers / leading dimensions
  *   kernel         HBFP_KERNEL_* as for hbfp_gemm_select, applied to every product
  *   workspace      hbfp_gemm_batch_workspace bytes (the sum of the products' own workspaces)
@@ -371,8 +372,8 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
  *   relu     0 or 1: max(x, 0) on the FP32 values before the conversion (the one floating-point operation between two
  *            products that needs no other operand)
  *   kernel   HBFP_KERNEL_* as for hbfp_gemm_select
- * The result equals hbfp_gemm_select followed by hbfp_encode of its output, bit for bit.  When the block-scaled kernel
- * computes the product and out has k along the columns of the product in blocks of 32 or 64 (one exponent per block
+ * The result equals hbfp_gemm_select followed by hbfp_encode of its output, bit for bit.  When the bf16 or the block-scaled
+ * kernel computes the product and out has k along the columns of the product in blocks of 32 or 64 (one exponent per block
  * and row), the kernel converts its accumulators itself; otherwise the FP32 product goes through the workspace.
  *   workspace  hbfp_gemm_bfp_workspace bytes (includes A->rows * B->rows floats), 256-byte aligned
  * Errors: as hbfp_gemm_select; HBFP_ERR_LAYOUT if out is not the plan of an A->rows x B->rows matrix.
