@@ -19,6 +19,7 @@
 // from the stored operands with plain integer and FP32 arithmetic (bf_marked_tile).  Small values need no such care:
 // the instruction takes subnormal bf16 operands and keeps subnormal FP32 sums.
 #include <atomic>
+#include <type_traits>
 
 #include "bf_pack.h"
 #include "hbfp_internal.h"
@@ -65,40 +66,52 @@ __device__ __forceinline__ void bf_pack_block(const BfPackParams &p, uint32_t bl
     const int q = lane & 3, r4 = lane >> 2;
     const int ks = 2 * ks64 + (q >> 1), h = q & 1;
     bool bad = false;
+    // all loads first (mantissas and exponent bytes of both rows and both octets), then the conversions and the stores:
+    // the compiler cannot move a load above a store through another pointer
+    typedef typename std::conditional<sizeof(MT) == 1, v2i, v4i_t>::type raw_t;
+    raw_t raw[2][2];
+    int E[2][2];
+    bool there[2][2];
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-        const int r32 = hh * 16 + r4;
-        const int64_t row = rt * 32 + r32;
+        const int64_t row = rt * 32 + hh * 16 + r4;
         const bool live = row < p.R;
 #pragma unroll
         for (int o = 0; o < 2; ++o) {
             const uint32_t j = (uint32_t)ks64 * 8u + (uint32_t)q * 2u + (uint32_t)o;          // octet of the packed k axis
-            bool there = live;
+            bool t = live;
             int64_t pos;                                                                       // its first element in the stored row
             uint32_t b;                                                                        // its exponent block
             if (p.ob) {
-                there = there && j < (uint32_t)p.noct;
-                b = there ? bf_dense_block_of(j, p.ob) : 0u;
-                pos = there ? (int64_t)b * 32 + 8 * (int)(j - b * (uint32_t)p.ob) : 0;
+                t = t && j < (uint32_t)p.noct;
+                b = t ? bf_dense_block_of(j, p.ob) : 0u;
+                pos = t ? (int64_t)b * 32 + 8 * (int)(j - b * (uint32_t)p.ob) : 0;
             } else {
                 pos = (int64_t)j * 8;
                 b = (j >> 2) / (uint32_t)p.chunks32_per_block;
             }
-            const int64_t rs = there ? row : 0;                                                // what does not exist reads row 0 and stores zeros
-            const int E = p.exps[rs * p.exp_ld + b];
+            const int64_t rs = t ? row : 0;                                                    // what does not exist reads row 0 and stores zeros
+            there[hh][o] = t;
+            E[hh][o] = p.exps[rs * p.exp_ld + b];
+            raw[hh][o] = *reinterpret_cast<const raw_t *>(reinterpret_cast<const MT *>(p.mant) + rs * p.kpad + pos);
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int r32 = hh * 16 + r4;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
             v4u out = {0u, 0u, 0u, 0u};
             bool any;
             if constexpr (sizeof(MT) == 1) {
-                const v2i raw = *reinterpret_cast<const v2i *>(reinterpret_cast<const int8_t *>(p.mant) + rs * p.kpad + pos);
-                any = (raw[0] | raw[1]) != 0;
-                if (there) out = bf_octet_i8(raw, E, p.m);
+                any = (raw[hh][o][0] | raw[hh][o][1]) != 0;
+                if (there[hh][o]) out = bf_octet_i8(raw[hh][o], E[hh][o], p.m);
             } else {
-                const v4i_t raw = *reinterpret_cast<const v4i_t *>(reinterpret_cast<const int16_t *>(p.mant) + rs * p.kpad + pos);
-                any = (raw[0] | raw[1] | raw[2] | raw[3]) != 0;
-                if (there) out = bf_octet_i16(raw, E, p.m);
+                any = (raw[hh][o][0] | raw[hh][o][1] | raw[hh][o][2] | raw[hh][o][3]) != 0;
+                if (there[hh][o]) out = bf_octet_i16(raw[hh][o], E[hh][o], p.m);
             }
-            bad = bad || (there && any && !bf_exponent_ok(E));
-            *reinterpret_cast<v4u *>(p.out + bf_piece_offset(rt, ks, p.ksteps, h, o, r32)) = out;
+            bad = bad || (there[hh][o] && any && !bf_exponent_ok(E[hh][o]));
+            __builtin_nontemporal_store(out, reinterpret_cast<v4u *>(p.out + bf_piece_offset(rt, ks, p.ksteps, h, o, r32)));
         }
     }
     if (bad) p.header[0] = p.mark;
