@@ -521,7 +521,7 @@ int hbfp_encode_packed(const float *src, int64_t ld, int n, const hbfp_tensor *c
  *   workspace   hbfp_encode_packed_batch_workspace bytes, 256-byte aligned
  * The outputs of different jobs must not overlap.
  * Errors: as hbfp_encode_packed for the first job that fails a check (nothing has been launched then); HBFP_ERR_ARG
- * if njobs is outside 1..HBFP_BATCH_MAX.
+ * if njobs is outside 1..HBFP_BATCH_MAX or a job's reserved field is not 0.
  */
 typedef struct hbfp_encode_job {
     const float *src;                  /* device, FP32, row-major                     */

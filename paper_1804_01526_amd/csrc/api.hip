@@ -394,6 +394,7 @@ int hbfp_encode_packed_batch(int njobs, const hbfp_encode_job *jobs, void *works
     size_t need = 0;
     for (int j = 0; j < njobs; ++j) {
         size_t b = 0;
+        if (jobs[j].reserved != 0) return HBFP_ERR_ARG;
         int rc = encode_packed_check(jobs[j].src, jobs[j].ld, jobs[j].n, jobs[j].outs, jobs[j].packed, jobs[j].packed_bytes, &b);
         if (rc != HBFP_OK) return rc;
         need = b > need ? b : need;

@@ -378,6 +378,9 @@ def test_encode_packed_batch_validation():
     assert lib.hbfp_encode_packed_batch(1, None, None, 0, None) == hbfp.ERR_ARG
     assert call([good, job(w, src=0)]) == hbfp.ERR_ARG and call([good, job(w, src=0x100002)]) == hbfp.ERR_ARG
     assert call([good, job(w, ld=47)]) == hbfp.ERR_ARG
+    odd = job(w)
+    odd[0].reserved = 1
+    assert call([good, odd]) == hbfp.ERR_ARG
     assert call([good, job(w, packed=0x4010)]) == hbfp.ERR_ARG
     assert call([good, job(w, size=1024)]) == hbfp.ERR_WORKSPACE
     assert call([good, job([desc(16, 240, 48, 0, 24, 24)])]) == hbfp.ERR_FORMAT          # too wide for the packed form
