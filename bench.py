@@ -708,7 +708,7 @@ def main():
         # Roofline of the dominant kernel: a dense contraction on the bf16 matrix instruction, so its operations
         # (2*M*N*K, one multiply-add per mantissa pair) over the kernel's launch time against the published dense bf16
         # peak; vs_int8_peak is the same rate against the int8 peak that the metric names.
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf_kernel", "achieved": round(product_tops, 1),
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf_kernel<false>", "achieved": round(product_tops, 1),
                      "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(product_tops / BF16_PEAK_TFLOPS, 4),
                      "vs_int8_peak": round(product_tops / INT8_PEAK_TOPS, 4),
                      "traffic": TRAFFIC_GEMM_C4_BYTES, "traffic_unit": "bytes per launch (HBM, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
