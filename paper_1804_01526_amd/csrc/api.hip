@@ -689,7 +689,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
     return hbfp_gemm_select(A, B, C, ldc, beta, HBFP_KERNEL_AUTO, workspace, ws_bytes, stream);
 }
 
-// Checks the products of a batch and decides whether they share one launch of the block-scaled kernel; part[i] is
+// Checks the products of a batch and decides whether they share one launch of the bf16 or the block-scaled kernel; part[i] is
 // product i's share of the workspace.
 static int batch_plan(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, GemmArgs *g, size_t *part,
                       bool *grouped, int *group_kernel) {

@@ -1,9 +1,10 @@
-// FP32 -> BFP conversion that also writes the limb planes of the block-scaled product kernel (Sec. 4.1: operands are
+// FP32 -> BFP conversion that also writes the packed form that the product kernels read (Sec. 4.1: operands are
 // converted right before every dot product; Sec. 5.1: forward and backward products both take converted inputs, so an
 // activation or weight matrix is needed in two operand layouts).  One read of the FP32 matrix produces, for up to two
 // outputs with exponent blocks of 24 along their contraction axes (1 x 24 / 24 x 1 blocks, or 24 x 24 tiles, the
 // paper's tile size, Sec. 4.2), the stored operand (int8 mantissas, exponent bytes: what hbfp_encode writes) and its
-// densely packed limb planes (what hbfp_pack writes), so that a product can start without a pack pass.
+// packed form (what hbfp_pack writes: bf16 planes for mantissas of 6 to 8 bits, densely packed limb planes for
+// narrower ones), so that a product can start without a pack pass.  Several source matrices can share a launch.
 //
 // A workgroup of 8 waves owns a 192 x 192 region of the source: 8 x 8 tiles of 24 x 24, which is 3 k-steps of 64 and
 // 6 row tiles of 32 in either orientation, the smallest region whose packed output consists of whole chunks.  It
@@ -11,9 +12,9 @@
 // lane (h, j) owns columns 4 j .. 4 j + 3 of rows 12 h .. 12 h + 11, all loads of a half issued before the first
 // use); block maxima are DPP reductions over the lanes of a tile (tiles), of a tile's row (1 x 24 blocks) or a register
 // maximum and one exchange (24 x 1 blocks).  The mantissas of each output go to an LDS tile [operand row][k] without
-// padding; after one barrier the workgroup streams the stored operand out in 16-byte pieces and packs the limb planes
-// from the same tile with the arithmetic of the pack kernel (mx_pack.h).  Two workgroups share a compute unit (2 x 78 KB
-// of LDS, 128 registers), so one converts while the other loads or stores.
+// padding; after one barrier the workgroup streams the stored operand out in 16-byte pieces and writes the packed
+// planes from the same tile with the arithmetic of the pack kernels (bf_pack.h, mx_pack.h).  Two workgroups share a
+// compute unit (2 x 78 KB of LDS, 128 registers), so one converts while the other loads or stores.
 #include "bf_pack.h"
 #include "bfp_device.h"
 #include "mx_pack.h"
@@ -30,7 +31,7 @@ constexpr int kEpLds = 2 * (kEpTileBytes + kEpExpBytes);
 
 struct EpOut {
     uint8_t *mant, *exps;        // stored operand
-    uint8_t *planes;             // limb planes of the packed operand (behind its 256-byte header)
+    uint8_t *planes;             // planes of the packed operand (behind its 256-byte header)
     int *header;
     int64_t kpad, exp_ld, R;
     int32_t m, axis, tiled, present, mark;
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(kEpThreads, 4) void encode_pack_kernel(const EpBatc
                 *reinterpret_cast<uint32_t *>(o.exps + orow0 * o.exp_ld + kreg * 8 + ((uint32_t)rl * (uint32_t)o.exp_ld + 4u * half)) =
                     *reinterpret_cast<const uint32_t *>(E + rl * 8 + 4 * half);
         }
-        // ---- limb planes: a wave takes 16 operand rows of one k-step at a time (lane = row, quarter of the k-step)
+        // ---- packed planes: a wave takes 16 operand rows of one k-step of 64 at a time (lane = row, quarter of the k-step)
         bool bad = false;
         const int q = lane & 3, r4 = lane >> 2;
         const uint8_t *tl = T + r4 * kEpStride + q * 16;     // this lane's 16 mantissas of k-step 0 of rows 0..15
