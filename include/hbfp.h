@@ -322,12 +322,20 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
  *                       FP32, and nothing is scaled per block (any block length, any spread of exponents; a non-zero block
  *                       with an exponent byte above 253 is computed with plain arithmetic inside the same kernel).  The
  *                       operands are packed into bf16 planes in the workspace first.  HBFP_ERR_FORMAT for other widths;
+ *   HBFP_KERNEL_FP16_PLANES  9..12-bit mantissas as FP16 numbers on the kernel of HBFP_KERNEL_BF16: FP16 has the 11-bit
+ *                       significand but not the exponent range, so every operand row is taken relative to the largest
+ *                       exponent byte Eref of its blocks: an element becomes mant * 2^(E - Eref + 4), exact in FP16
+ *                       (subnormals included) when its block lies at most 28 binades below the row's largest, the FP16
+ *                       matrix instruction multiplies and accumulates in FP32 with nothing scaled per block, and the
+ *                       factors 2^(Eref ...) of the row of A and the row of B are applied once, at the store.  A non-zero
+ *                       block further down is computed with plain arithmetic inside the same kernel, as for BF16.  The
+ *                       operands are packed in the workspace first.  HBFP_ERR_FORMAT for other widths;
  *   HBFP_KERNEL_AUTO    what hbfp_gemm does, in this order: BF16 when both operands have 6..9-bit mantissas and the shape is
  *                       one where 256 x 256 tiles pay (at least 144 output tiles, a stored contraction length of at least
- *                       2048, or 1024 from 512 tiles on, blocks of at most 32 elements); FP16 when both operands have
+ *                       2048, or 1024 from 512 tiles on, blocks of at most 32 elements); FP16_PLANES when both have 9..12-bit
+ *                       mantissas and the shape is such a one (any block length); FP16 when both operands have
  *                       9..12-bit mantissas in blocks it takes (measured ahead of the int8 and block-scaled families from
- *                       2048^3 to 8192^3); SCALED for the same shapes as BF16 when an operand has at most 5 bits or both
- *                       have more than 9; else INT8.
+ *                       2048^3 to 8192^3); SCALED for the same shapes as BF16 when an operand has at most 5 bits; else INT8.
  * All satisfy the same bound against the FP64 product of the decoded operands.
  * Arguments, domain and errors as hbfp_gemm, plus HBFP_ERR_ARG for an unknown kernel; the workspace
  * size depends on the kernel: hbfp_gemm_select_workspace.
@@ -338,6 +346,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 #define HBFP_KERNEL_INT8_WIDE 3
 #define HBFP_KERNEL_FP16 4
 #define HBFP_KERNEL_BF16 5
+#define HBFP_KERNEL_FP16_PLANES 6
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes);
 int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc, float beta, int kernel,
                      void *workspace, size_t ws_bytes, void *stream);

@@ -599,15 +599,23 @@ static bool use_bf(const GemmArgs &g, int kernel) {
     return kernel == HBFP_KERNEL_BF16 || (kernel == HBFP_KERNEL_AUTO && gemm_mx_ok(g));
 }
 
+// 9..12-bit mantissas as FP16 numbers relative to their rows' largest exponents, on the same 256 x 256-tile kernel:
+// asked for by name, or chosen for the shapes where those tiles pay when the bf16 kernel does not apply
+static bool use_f16_planes(const GemmArgs &g, int kernel) {
+    if (g.P || !gemm_f16_planes_possible(g)) return false;
+    return kernel == HBFP_KERNEL_FP16_PLANES || (kernel == HBFP_KERNEL_AUTO && !use_bf(g, kernel) && gemm_mx_ok(g));
+}
+
 static bool use_scaled(const GemmArgs &g, int kernel) {
-    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE || kernel == HBFP_KERNEL_FP16 || kernel == HBFP_KERNEL_BF16)
+    if (g.P || kernel == HBFP_KERNEL_INT8 || kernel == HBFP_KERNEL_INT8_WIDE || kernel == HBFP_KERNEL_FP16 || kernel == HBFP_KERNEL_BF16 ||
+        kernel == HBFP_KERNEL_FP16_PLANES)
         return false;
-    if (use_bf(g, kernel)) return false;
+    if (use_bf(g, kernel) || use_f16_planes(g, kernel)) return false;
     return kernel == HBFP_KERNEL_SCALED ? gemm_mx_possible(g) : gemm_mx_ok(g);
 }
 
 int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int kernel, size_t *bytes) {
-    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
+    if (!bytes || kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16_PLANES) return HBFP_ERR_ARG;
     int rc = check_tensor(A, false);
     if (rc != HBFP_OK) return rc;
     rc = check_tensor(B, false);
@@ -617,6 +625,10 @@ int hbfp_gemm_select_workspace(const hbfp_tensor *A, const hbfp_tensor *B, int k
     const GemmArgs g = gemm_args(A, B);
     if (use_bf(g, kernel)) {                                     // [packed A][packed B]
         *bytes = packed_operand_bytes(g.M, g.kpad, g.mA) + packed_operand_bytes(g.N, g.kpad, g.mB);
+        return HBFP_OK;
+    }
+    if (use_f16_planes(g, kernel)) {                             // [packed A][packed B]
+        *bytes = f16_planes_bytes(g.M, g.kpad) + f16_planes_bytes(g.N, g.kpad);
         return HBFP_OK;
     }
     const size_t f16 = gemm_f16_workspace(A->rows, B->rows, A->kpad, A->kblock_pad, A->exp_ld > B->exp_ld ? A->exp_ld : B->exp_ld);
@@ -644,6 +656,7 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
     g.P = P;
     if (kernel == HBFP_KERNEL_FP16 && !gemm_f16_possible(g)) return HBFP_ERR_FORMAT;
     if (kernel == HBFP_KERNEL_BF16 && !P && !gemm_bf_possible(g)) return HBFP_ERR_FORMAT;
+    if (kernel == HBFP_KERNEL_FP16_PLANES && !P && !gemm_f16_planes_possible(g)) return HBFP_ERR_FORMAT;
     size_t need = 0;
     hbfp_gemm_select_workspace(A, B, kernel, &need);
     if (need && (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255))) return HBFP_ERR_WORKSPACE;
@@ -656,6 +669,12 @@ static int run_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_
         rc = launch_bf_pack(g, pa, pb, (hipStream_t)stream);
         const void *cpa = pa, *cpb = pb;
         return rc == HBFP_OK ? launch_bf_products(1, &g, &cpa, &cpb, (hipStream_t)stream) : rc;
+    }
+    if (use_f16_planes(g, kernel)) {
+        void *pa = workspace, *pb = (char *)workspace + f16_planes_bytes(g.M, g.kpad);
+        rc = launch_f16_planes_pack(g, pa, pb, (hipStream_t)stream);
+        const void *cpa = pa, *cpb = pb;
+        return rc == HBFP_OK ? launch_f16_planes_products(1, &g, &cpa, &cpb, (hipStream_t)stream) : rc;
     }
     // 9..12-bit mantissas are exact FP16 values: one FP16 matrix instruction per element pair instead of four or nine limb products
     if (kernel == HBFP_KERNEL_FP16 || (kernel == HBFP_KERNEL_AUTO && gemm_f16_possible(g)))
@@ -679,7 +698,7 @@ int hbfp_gemm_select(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64
                      void *workspace, size_t ws_bytes, void *stream) {
     if (!A || !B || !C) return HBFP_ERR_ARG;
     if (beta != 0.0f && beta != 1.0f) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16_PLANES) return HBFP_ERR_ARG;
     if (ldc < B->rows || ((uintptr_t)C & 3)) return HBFP_ERR_ARG;
     return run_gemm(A, B, C, ldc, beta, nullptr, kernel, workspace, ws_bytes, stream);
 }
@@ -694,7 +713,7 @@ int hbfp_gemm(const hbfp_tensor *A, const hbfp_tensor *B, float *C, int64_t ldc,
 static int batch_plan(int n, const hbfp_tensor *const *A, const hbfp_tensor *const *B, int kernel, GemmArgs *g, size_t *part,
                       bool *grouped, int *group_kernel) {
     if (!A || !B || n < 1 || n > HBFP_BATCH_MAX) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16_PLANES) return HBFP_ERR_ARG;
     bool all_scaled = true, all_bf = true, bf_class = true, same = true;
     for (int i = 0; i < n; ++i) {
         if (!A[i] || !B[i]) return HBFP_ERR_ARG;
@@ -799,7 +818,7 @@ int hbfp_gemm_batch(int n, const hbfp_tensor *const *A, const hbfp_tensor *const
 static int gemm_bfp_plan(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor *out, int kernel, bool need_ptrs,
                          bool *fused, size_t part[3], int *kernel_used) {
     if (!A || !B || !out) return HBFP_ERR_ARG;
-    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_BF16) return HBFP_ERR_ARG;
+    if (kernel < HBFP_KERNEL_AUTO || kernel > HBFP_KERNEL_FP16_PLANES) return HBFP_ERR_ARG;
     int rc = need_ptrs ? check_pair(A, B) : check_tensor(A, false);
     if (rc == HBFP_OK && !need_ptrs) rc = check_tensor(B, false);
     if (rc == HBFP_OK) rc = check_tensor(out, need_ptrs);

@@ -84,5 +84,27 @@ __device__ __forceinline__ v4u bf_octet_i16(const v4i &raw, int E, int m) {
     return out;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Mantissas of 10 to 12 bits do not fit a bf16 significand, but they fit an FP16 one (11 bits), and FP16's narrow
+// exponent range is enough once every operand row is taken relative to its own largest block exponent Eref: an element
+// becomes mant * 2^(E - Eref + 4), at most 2^15 in magnitude, exact in FP16 (subnormals included) as long as its block
+// lies no more than 28 binades below the row's largest, and the row's factor 2^(Eref - 4 - 125 - m) is applied to the
+// FP32 sums when they are stored.  Same planes as above with FP16 elements, preceded by one scale word per row:
+// [256-byte header][rows padded to 256: int32 Eref - 129 - m][planes].  A non-zero block further down marks the operand.
+constexpr int kF16Lift = 4;
+constexpr int kF16MinShift = -24;                 // weight of the last bit of an FP16 subnormal
+inline size_t f16_scale_bytes(int64_t rows) { return (size_t)((rows + 255) / 256) * 256 * 4; }
+inline size_t f16_packed_bytes(int64_t rows, int64_t kpad) { return 256 + f16_scale_bytes(rows) + (size_t)((rows + 255) / 256) * 256 * (size_t)kpad * 2; }
+// an octet of int16 mantissas times 2^shift as FP16 numbers (exact for shift >= kF16MinShift)
+__device__ __forceinline__ v4u f16_octet_i16(const v4i &raw, int shift) {
+    v4u out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = __builtin_ldexpf((float)(int)(int16_t)raw[i], shift), b = __builtin_ldexpf((float)(raw[i] >> 16), shift);
+        out[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+    }
+    return out;
+}
+
 }  // namespace
 }  // namespace hbfp

@@ -29,6 +29,7 @@ namespace hbfp {
 namespace {
 
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBfThreads = 512;
@@ -47,6 +48,8 @@ struct BfPackParams {
     int32_t ksteps;              // k-steps of 32 of the packed operand (a multiple of 4)
     int32_t chunks32_per_block, m, mark;
     int32_t ob, noct;            // dense layout: octets per exponent block and in the whole row; ob = 0: as stored
+    int32_t *scale;              // FP16 planes: one word per row (rows padded to 256), Eref - 129 - m; else null
+    int32_t nblk;
 };
 struct BfPackPair {
     BfPackParams op[2];
@@ -55,7 +58,7 @@ struct BfPackPair {
 
 // A workgroup of 4 waves packs one row tile of 32 rows over 4 x 64 k; a lane converts 16 consecutive k of one row (two
 // octets) of rows r and r + 16.
-template <typename MT>
+template <typename MT, bool F16>
 __device__ __forceinline__ void bf_pack_block(const BfPackParams &p, uint32_t block) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (block == 0 && threadIdx.x == 0) p.header[1] = p.mark;
@@ -70,12 +73,13 @@ __device__ __forceinline__ void bf_pack_block(const BfPackParams &p, uint32_t bl
     // the compiler cannot move a load above a store through another pointer
     typedef typename std::conditional<sizeof(MT) == 1, v2i, v4i_t>::type raw_t;
     raw_t raw[2][2];
-    int E[2][2];
+    int E[2][2], Eref[2] = {0, 0};
     bool there[2][2];
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
         const int64_t row = rt * 32 + hh * 16 + r4;
         const bool live = row < p.R;
+        if (F16) Eref[hh] = p.scale[rt * 32 + hh * 16 + r4] + 129 + p.m;      // written by f16_row_scale_kernel before this launch
 #pragma unroll
         for (int o = 0; o < 2; ++o) {
             const uint32_t j = (uint32_t)ks64 * 8u + (uint32_t)q * 2u + (uint32_t)o;          // octet of the packed k axis
@@ -108,19 +112,41 @@ __device__ __forceinline__ void bf_pack_block(const BfPackParams &p, uint32_t bl
                 if (there[hh][o]) out = bf_octet_i8(raw[hh][o], E[hh][o], p.m);
             } else {
                 any = (raw[hh][o][0] | raw[hh][o][1] | raw[hh][o][2] | raw[hh][o][3]) != 0;
-                if (there[hh][o]) out = bf_octet_i16(raw[hh][o], E[hh][o], p.m);
+                if (F16) {
+                    const int shift = E[hh][o] - Eref[hh] + kF16Lift;
+                    if (there[hh][o]) out = f16_octet_i16(raw[hh][o], shift);
+                    bad = bad || (there[hh][o] && any && shift < kF16MinShift);
+                } else if (there[hh][o]) {
+                    out = bf_octet_i16(raw[hh][o], E[hh][o], p.m);
+                }
             }
-            bad = bad || (there[hh][o] && any && !bf_exponent_ok(E[hh][o]));
+            if (!F16) bad = bad || (there[hh][o] && any && !bf_exponent_ok(E[hh][o]));
             __builtin_nontemporal_store(out, reinterpret_cast<v4u *>(p.out + bf_piece_offset(rt, ks, p.ksteps, h, o, r32)));
         }
     }
     if (bad) p.header[0] = p.mark;
 }
 
-template <typename MT>
+template <typename MT, bool F16>
 __global__ __launch_bounds__(256) void bf_pack_kernel(const BfPackPair q) {
-    if (blockIdx.x < q.blocks_a) bf_pack_block<MT>(q.op[0], blockIdx.x);
-    else bf_pack_block<MT>(q.op[1], blockIdx.x - q.blocks_a);
+    if (blockIdx.x < q.blocks_a) bf_pack_block<MT, F16>(q.op[0], blockIdx.x);
+    else bf_pack_block<MT, F16>(q.op[1], blockIdx.x - q.blocks_a);
+}
+
+// FP16 planes: the scale word of every row, from the largest exponent byte of its blocks; one thread per row of either
+// operand (rows behind the last: 0).  Runs before the pack kernel, which reads the words.
+__global__ __launch_bounds__(256) void f16_row_scale_kernel(const BfPackPair q, uint32_t rows_a, uint32_t rows_b) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows_a + rows_b) return;
+    const BfPackParams &p = i < rows_a ? q.op[0] : q.op[1];
+    const int64_t row = i < rows_a ? i : i - rows_a;
+    int word = 0;
+    if (row < p.R) {
+        int emax = 1;
+        for (int b = 0; b < p.nblk; ++b) emax = max(emax, (int)p.exps[row * p.exp_ld + b]);
+        word = emax - 129 - p.m;
+    }
+    p.scale[row] = word;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -135,6 +161,7 @@ struct BfParams {
     const uint8_t *expA, *expB;
     int64_t kpad, expA_ld, expB_ld;
     int32_t chunks32_per_block, shift, wide;   // shift: -(2 * 125 + mA + mB)
+    const int32_t *sa, *sb;                    // FP16 planes: the scale words of the rows of A and of B
 };
 
 // A tile of a product with a marked operand (an exponent byte above 253: values next to the largest finite FP32 number),
@@ -172,7 +199,9 @@ struct BfGroup {
 
 // TR: the variant whose output is an encoded operand (g.out): the operands of the matrix instruction exchanged, so
 // that every 32 x 32 result arrives transposed (same products, same sums) as mx_store_encoded wants them
-template <bool TR>
+// F16: FP16 planes (10..12-bit mantissas relative to their rows' largest exponents): the FP16 matrix instruction, and the
+// rows' and columns' factors applied at the store
+template <bool TR, bool F16>
 __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // which product this workgroup belongs to: selected with constant indices, so that the parameters stay in scalar
@@ -234,8 +263,12 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
         _Pragma("unroll") for (int j = 0; j < 4; ++j) bf[buf][j] = *reinterpret_cast<const v4i_t *>((base_) + bbase + j * kBfTileBytes + (h) * 1024); \
     }
 #define HBFP_BF_MFMA(buf, i, j)                                                                                                    \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, TR ? bf[buf][j] : af[buf][i]),                    \
-                                                        __builtin_bit_cast(v8bf, TR ? af[buf][i] : bf[buf][j]), acc[i][j], 0, 0, 0)
+    if (F16)                                                                                                                       \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, af[buf][i]), __builtin_bit_cast(v8h, bf[buf][j]), \
+                                                           acc[i][j], 0, 0, 0);                                                    \
+    else                                                                                                                           \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, TR ? bf[buf][j] : af[buf][i]),                \
+                                                            __builtin_bit_cast(v8bf, TR ? af[buf][i] : bf[buf][j]), acc[i][j], 0, 0, 0)
 #define HBFP_BF_ROW(buf, i)        \
     {                              \
         HBFP_BF_MFMA(buf, i, 0);   \
@@ -320,39 +353,49 @@ __global__ __launch_bounds__(kBfThreads, 2) void gemm_bf_kernel(const BfGroup g)
 
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t row0 = (int64_t)tm * 256 + wm * 64, col0 = (int64_t)tn * 256 + wn * 128;
-    if (TR) {
+    if (TR && !F16) {
         if (g.out.rounding) mx_store_encoded<1>(g.out, acc, row0, col0, p.M, p.N, lane);
         else mx_store_encoded<0>(g.out, acc, row0, col0, p.M, p.N, lane);
         return;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+        int sa[16];
+        if (F16) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sa[v] = p.sa[row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3)];      // padded to whole panels
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t col = col0 + j * 32 + l32;
             if (col >= p.N) continue;
+            const int sb = F16 ? p.sb[col] : 0;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = row0 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (row < p.M) {
                     float *dst = p.C + row * p.ldc + col;
+                    const float x = F16 ? __builtin_ldexpf(acc[i][j][v], sa[v] + sb) : acc[i][j][v];
                     // C is written once and not read again here: streaming stores leave the operand panels in the caches
-                    if (p.beta) *dst = *dst + acc[i][j][v];
-                    else __builtin_nontemporal_store(acc[i][j][v], dst);
+                    if (p.beta) *dst = *dst + x;
+                    else __builtin_nontemporal_store(x, dst);
                 }
             }
         }
+    }
 }
 
 int64_t klen_of(const GemmArgs &a, int m) { return bf_klen(a.kpad, a.kbp, a.kblock, a.nblk, a.kdim, m); }
 
 BfPackParams bf_pack_params(const GemmArgs &a, const void *mant, const uint8_t *exps, int64_t R, int64_t exp_ld, int m, void *packed,
-                            int32_t mark) {
+                            int32_t mark, bool f16) {
     BfPackParams q;
     q.mant = mant;
     q.exps = exps;
     q.header = (int *)packed;
-    q.out = (uint8_t *)packed + 256;
+    q.scale = f16 ? (int32_t *)((uint8_t *)packed + 256) : nullptr;
+    q.out = (uint8_t *)packed + 256 + (f16 ? f16_scale_bytes(R) : 0);
+    q.nblk = (int32_t)a.nblk;
     q.mark = mark;
     q.R = R;
     q.kpad = a.kpad;
@@ -373,13 +416,18 @@ size_t packed_operand_bytes(int64_t rows, int64_t kpad, int mant_bits) {
     return bf_class(mant_bits) ? bf_packed_bytes(rows, kpad) : mx_packed_bytes(rows, kpad, mant_bits);
 }
 
-bool gemm_bf_possible(const GemmArgs &a) {
-    return !a.P && bf_class(a.mA) && bf_class(a.mB) && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 32 <= 0x7fffffff &&
-           a.nblk * 4 <= 0x7fffffff;
+static bool shape_ok(const GemmArgs &a) {
+    return !a.P && ceil_div(a.M, 256) * ceil_div(a.N, 256) <= 0x7ffffff0 && a.kpad / 32 <= 0x7fffffff && a.nblk * 4 <= 0x7fffffff;
 }
+bool gemm_bf_possible(const GemmArgs &a) { return shape_ok(a) && bf_class(a.mA) && bf_class(a.mB); }
+// 9..12-bit mantissas (int16 storage) as FP16 numbers relative to their rows' largest exponents
+bool gemm_f16_planes_possible(const GemmArgs &a) {
+    return shape_ok(a) && a.mA >= 9 && a.mA <= 12 && a.mB >= 9 && a.mB <= 12 && a.M <= 0x7fffff00 && a.N <= 0x7fffff00 && a.nblk <= 0x7fffffff;
+}
+size_t f16_planes_bytes(int64_t rows, int64_t kpad) { return f16_packed_bytes(rows, kpad); }
 
 // packs operand A (rows a.M) and / or operand B (rows a.N) of `a` in one launch; a null buffer skips that operand
-int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s) {
+static int launch_pack(const GemmArgs &a, void *packed_a, void *packed_b, bool f16, hipStream_t s) {
     if (!packed_a && !packed_b) return HBFP_OK;
     BfPackPair q = {};
     int64_t ba = 0, bb = 0;
@@ -387,13 +435,18 @@ int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
         int32_t mark;
         const int rc = mx_pack_begin(packed_a, s, &mark);
         if (rc != HBFP_OK) return rc;
-        q.op[0] = bf_pack_params(a, a.mantA, a.expA, a.M, a.expA_ld, a.mA, packed_a, mark);
+        q.op[0] = bf_pack_params(a, a.mantA, a.expA, a.M, a.expA_ld, a.mA, packed_a, mark, f16);
     }
     if (packed_b) {
         int32_t mark;
         const int rc = mx_pack_begin(packed_b, s, &mark);
         if (rc != HBFP_OK) return rc;
-        q.op[1] = bf_pack_params(a, a.mantB, a.expB, a.N, a.expB_ld, a.mB, packed_b, mark);
+        q.op[1] = bf_pack_params(a, a.mantB, a.expB, a.N, a.expB_ld, a.mB, packed_b, mark, f16);
+    }
+    if (f16) {      // the scale words of whole panels first: the pack kernel reads them
+        const uint32_t ra = packed_a ? (uint32_t)(ceil_div(a.M, 256) * 256) : 0u, rb = packed_b ? (uint32_t)(ceil_div(a.N, 256) * 256) : 0u;
+        hipLaunchKernelGGL(f16_row_scale_kernel, dim3((ra + rb + 255) / 256), dim3(256), 0, s, q, ra, rb);
+        if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
     }
     // whole panels are written: the row tiles behind the last row hold zeros
     if (packed_a) ba = ceil_div(a.M, 256) * 8 * ceil_div(q.op[0].ksteps / 2, 4);
@@ -401,28 +454,35 @@ int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_
     if (ba + bb > 0x7fffffff) return HBFP_ERR_ARG;
     q.blocks_a = (uint32_t)ba;
     const bool wide = (packed_a ? a.mA : a.mB) > 8;             // both operands of a product are of the same storage class
-    if (wide) hipLaunchKernelGGL(bf_pack_kernel<int16_t>, dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
-    else hipLaunchKernelGGL(bf_pack_kernel<int8_t>, dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
+    if (f16) hipLaunchKernelGGL((bf_pack_kernel<int16_t, true>), dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
+    else if (wide) hipLaunchKernelGGL((bf_pack_kernel<int16_t, false>), dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
+    else hipLaunchKernelGGL((bf_pack_kernel<int8_t, false>), dim3((unsigned)(ba + bb)), dim3(256), 0, s, q);
     return launch_status();
+}
+int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s) { return launch_pack(a, packed_a, packed_b, false, s); }
+int launch_f16_planes_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s) {
+    return launch_pack(a, packed_a, packed_b, true, s);
 }
 
 // n <= HBFP_BATCH_MAX products of operands packed as bf16 planes, in one launch; out: product 0 of a single-product
 // launch is delivered as this encoded operand (a marked operand: the FP32 product goes to args[0].C instead)
 static int launch_bf_group(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, const MxOut *out,
-                           hipStream_t s) {
-    if (n < 1 || n > kBfGroup || (out && n != 1)) return HBFP_ERR_ARG;
+                           bool f16, hipStream_t s) {
+    if (n < 1 || n > kBfGroup || (out && (n != 1 || f16))) return HBFP_ERR_ARG;
     BfGroup g = {};
     g.n = n;
     if (out) g.out = *out;
     int64_t first = 0;
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
-        if (!gemm_bf_possible(a) || klen_of(a, a.mA) != klen_of(a, a.mB)) return HBFP_ERR_FORMAT;
+        if (!(f16 ? gemm_f16_planes_possible(a) : gemm_bf_possible(a)) || klen_of(a, a.mA) != klen_of(a, a.mB)) return HBFP_ERR_FORMAT;
         BfParams &p = g.p[i];
         p.ha = (const int *)packed_a[i];
         p.hb = (const int *)packed_b[i];
-        p.pa = (const uint8_t *)packed_a[i] + 256;
-        p.pb = (const uint8_t *)packed_b[i] + 256;
+        p.pa = (const uint8_t *)packed_a[i] + 256 + (f16 ? f16_scale_bytes(a.M) : 0);
+        p.pb = (const uint8_t *)packed_b[i] + 256 + (f16 ? f16_scale_bytes(a.N) : 0);
+        p.sa = f16 ? (const int32_t *)((const uint8_t *)packed_a[i] + 256) : nullptr;
+        p.sb = f16 ? (const int32_t *)((const uint8_t *)packed_b[i] + 256) : nullptr;
         p.C = a.C;
         p.M = a.M;
         p.N = a.N;
@@ -447,16 +507,24 @@ static int launch_bf_group(int n, const GemmArgs *args, const void *const *packe
         if (first > 0x7ffffff0) return HBFP_ERR_ARG;
     }
     for (int i = n; i <= kBfGroup; ++i) g.first[i] = (int32_t)first;
-    static std::atomic<bool> configured[2];
-    const void *kernel = out ? reinterpret_cast<const void *>(&gemm_bf_kernel<true>) : reinterpret_cast<const void *>(&gemm_bf_kernel<false>);
-    if (allow_dynamic_lds(configured[out ? 1 : 0], kernel, kBfRing * kBfStage) != HBFP_OK) return HBFP_ERR_LAUNCH;
-    if (out) hipLaunchKernelGGL(gemm_bf_kernel<true>, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
-    else hipLaunchKernelGGL(gemm_bf_kernel<false>, dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    static std::atomic<bool> configured[3];
+    const int which = f16 ? 2 : out ? 1 : 0;
+    const void *kernel = f16   ? reinterpret_cast<const void *>(&gemm_bf_kernel<false, true>)
+                         : out ? reinterpret_cast<const void *>(&gemm_bf_kernel<true, false>)
+                               : reinterpret_cast<const void *>(&gemm_bf_kernel<false, false>);
+    if (allow_dynamic_lds(configured[which], kernel, kBfRing * kBfStage) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    if (f16) hipLaunchKernelGGL((gemm_bf_kernel<false, true>), dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    else if (out) hipLaunchKernelGGL((gemm_bf_kernel<true, false>), dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
+    else hipLaunchKernelGGL((gemm_bf_kernel<false, false>), dim3((unsigned)first), dim3(kBfThreads), kBfRing * kBfStage, s, g);
     return launch_status();
 }
 
 int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
-    return launch_bf_group(n, args, packed_a, packed_b, nullptr, s);
+    return launch_bf_group(n, args, packed_a, packed_b, nullptr, false, s);
+}
+// the same on FP16 planes (launch_f16_planes_pack)
+int launch_f16_planes_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s) {
+    return launch_bf_group(n, args, packed_a, packed_b, nullptr, true, s);
 }
 
 // The product as an encoded operand (output blocks of 32 or 64 along the columns of the product: mx_encoded_output_ok).
@@ -466,7 +534,7 @@ int launch_bf_product_encoded(const GemmArgs &a, const void *packed_a, const voi
                               hipStream_t s) {
     if (!mx_encoded_output_ok(out)) return HBFP_ERR_FORMAT;
     const MxOut o = mx_out_of(out, relu);
-    return launch_bf_group(1, &a, &packed_a, &packed_b, &o, s);
+    return launch_bf_group(1, &a, &packed_a, &packed_b, &o, false, s);
 }
 
 }  // namespace hbfp

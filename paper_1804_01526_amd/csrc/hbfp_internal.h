@@ -125,6 +125,12 @@ size_t packed_operand_bytes(int64_t rows, int64_t kpad, int mant_bits);   // of 
 bool gemm_bf_possible(const GemmArgs &a);
 int launch_bf_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
 int launch_bf_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
+// 9..12-bit mantissas as FP16 numbers relative to their rows' largest exponents, on the same kernel with the FP16
+// matrix instruction; packed operand: header, one scale word per row, FP16 planes
+bool gemm_f16_planes_possible(const GemmArgs &a);
+size_t f16_planes_bytes(int64_t rows, int64_t kpad);
+int launch_f16_planes_pack(const GemmArgs &a, void *packed_a, void *packed_b, hipStream_t s);
+int launch_f16_planes_products(int n, const GemmArgs *args, const void *const *packed_a, const void *const *packed_b, hipStream_t s);
 int launch_bf_product_encoded(const GemmArgs &a, const void *packed_a, const void *packed_b, const hbfp_tensor &out, int relu,
                               hipStream_t s);
 bool mx_same_limbs(const GemmArgs &a, const GemmArgs &b);

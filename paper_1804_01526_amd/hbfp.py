@@ -257,7 +257,7 @@ def decode(t: BfpTensor, out: Optional[torch.Tensor] = None, stream=None) -> tor
     return out
 
 
-KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED, KERNEL_INT8_WIDE, KERNEL_FP16, KERNEL_BF16 = 0, 1, 2, 3, 4, 5
+KERNEL_AUTO, KERNEL_INT8, KERNEL_SCALED, KERNEL_INT8_WIDE, KERNEL_FP16, KERNEL_BF16, KERNEL_FP16_PLANES = 0, 1, 2, 3, 4, 5, 6
 
 
 def gemm_select_workspace(a: TensorDesc, b: TensorDesc, kernel: int) -> int:

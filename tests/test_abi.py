@@ -214,7 +214,7 @@ def test_gemm_select_validation():
         return d
 
     a, b = desc(8, 128, 256, 1, 1, 32), desc(8, 256, 64, 0, 32, 1)
-    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 6, fake, 1 << 20, None) == hbfp.ERR_ARG
+    assert lib.hbfp_gemm_select(byref(a), byref(b), fake, 64, 0.0, 7, fake, 1 << 20, None) == hbfp.ERR_ARG
     # the bf16 kernel is for 6..9-bit mantissas on both sides; its workspace holds the bf16 planes of both operands
     # (whole panels of 256 rows, 2 bytes per stored element, a 256-byte header each)
     for m in (4, 5, 10, 12):
@@ -259,8 +259,18 @@ def test_gemm_select_validation():
     x, w = desc(8, 2048, 2048, 1, 1, 32), desc(8, 2048, 2048, 0, 32, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_INT8)
     assert auto_is_scaled(4, 64) and auto_is_scaled(5, 24)
+    # 12-bit mantissas on both sides: FP16 planes on the 256 x 256-tile kernel where those tiles pay (header, a scale
+    # word per row and 2 bytes per stored element for each operand), the FP16 instruction on 128 x 128 tiles elsewhere
     x, w = desc(12, 4096, 4096, 1, 1, 64), desc(12, 4096, 4096, 0, 64, 1)
+    planes = hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_FP16_PLANES)
+    assert hbfp.gemm_workspace(x, w) == planes == 2 * (256 + 4096 * 4 + 4096 * 4096 * 2)
+    assert planes != hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_FP16)
+    x, w = desc(12, 1024, 4096, 1, 1, 64), desc(12, 4096, 1024, 0, 64, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_FP16)
+    for m in (4, 8):
+        am, bm = desc(m, 128, 256, 1, 1, 32), desc(m, 256, 64, 0, 32, 1)
+        assert lib.hbfp_gemm_select(byref(am), byref(bm), fake, 64, 0.0, hbfp.KERNEL_FP16_PLANES, fake, 1 << 24, None) == hbfp.ERR_FORMAT
+    x, w = desc(12, 4096, 4096, 1, 1, 64), desc(12, 4096, 4096, 0, 64, 1)
     w = desc(8, 4096, 4096, 0, 64, 1)
     assert hbfp.gemm_workspace(x, w) == hbfp.gemm_select_workspace(x, w, hbfp.KERNEL_SCALED)
     # narrow output: tiles of 256 x 256 would be half empty
@@ -418,7 +428,7 @@ def test_gemm_bfp_validation():
         hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED) + -(-hbfp.encode_workspace(row_exp) // 256) * 256
     assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 128, 65, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
     assert _status(hbfp.gemm_bfp_workspace, a, b, desc(8, 64, 128, 1, 1, 32), 0) == hbfp.ERR_LAYOUT
-    assert _status(hbfp.gemm_bfp_workspace, a, b, out, 6) == hbfp.ERR_ARG
+    assert _status(hbfp.gemm_bfp_workspace, a, b, out, 7) == hbfp.ERR_ARG
     need = hbfp.gemm_bfp_workspace(a, b, out, hbfp.KERNEL_SCALED)
     call = lib.hbfp_gemm_bfp
     assert call(byref(a), byref(b), byref(out), 0, hbfp.KERNEL_SCALED, fake, need - 1, None) == hbfp.ERR_WORKSPACE

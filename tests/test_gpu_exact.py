@@ -15,7 +15,7 @@ from tests.util import unpack
 
 pytestmark = pytest.mark.gpu
 
-AUTO, INT8, SCALED, WIDE, FP16, BF16 = 0, 1, 2, 3, 4, 5
+AUTO, INT8, SCALED, WIDE, FP16, BF16, F16P = 0, 1, 2, 3, 4, 5, 6
 
 
 @pytest.fixture(scope="module")
@@ -180,7 +180,7 @@ def test_exact_sums_mixed_limb_counts(hb, ma, mb):
         _exact(hb, A, B, (1, 32, ma), (32, 1, mb), kernel)
 
 
-@pytest.mark.parametrize("kernel", [FP16])
+@pytest.mark.parametrize("kernel", [FP16, F16P])
 @pytest.mark.parametrize("kb,K,m", [(32, 512, 9), (64, 1024, 9), (128, 768, 9), (256, 1024, 9), (0, 640, 9), (64, 16384, 9), (64, 256, 11),
                                     (32, 160, 12)])
 def test_exact_sums_fp16_kernel(hb, kernel, kb, K, m):
@@ -199,7 +199,7 @@ def test_exact_sums_fp16_kernel(hb, kernel, kb, K, m):
     _exact(hb, A, B, (1, kb, m), (kb, 1, m), kernel)
 
 
-@pytest.mark.parametrize("kernel", [INT8, SCALED, FP16])
+@pytest.mark.parametrize("kernel", [INT8, SCALED, FP16, F16P])
 @pytest.mark.parametrize("ma,mb", [(12, 12), (10, 12), (12, 10)])
 def test_exact_sums_three_limbs(hb, kernel, ma, mb):
     """9..12-bit mantissas (three 4-bit limbs, or two int8 limbs): one full-width entry per block of 64 and small

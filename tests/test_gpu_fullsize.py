@@ -6,8 +6,8 @@ half drawn at random.  Three checks per product:
     bound: |C - C64| <= n_acc * 2^-24 * sum_b |term_b|, term_b the scaled integer sum of block b (Eq. (2)) taken
     from the oracle's block sums, n_acc the number of FP32 accumulations an output receives (one per block on
     the int8 kernels; limb pairs x groups of 32 on the block-scaled kernel, where every limb product of a group is
-    accumulated by an instruction of its own).  On the bf16 kernel the sums inside a block are FP32 sums too, so there
-    the bound is taken against the sum of |a_k b_k| over all k, with two roundings allowed per matrix instruction
+    accumulated by an instruction of its own).  On the bf16 kernel and on FP16 planes the sums inside a block are FP32 sums
+    too, so there the bound is taken against the sum of |a_k b_k| over all k, with two roundings allowed per matrix instruction
     (16 products);
   * the integer block sums of four random 32 x 32 windows of the product (hbfp_gemm_partials_window) equal the
     oracle's bit for bit."""
@@ -169,8 +169,8 @@ def test_config3_conv_shapes(hb):
 
 def test_config5_wide_range_bfp12(hb):
     """Config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20: the library's choice
-    (mantissas widened to FP16 for the FP16 matrix instruction), then the block-scaled kernel with three limbs per
-    mantissa, then the int8 limb kernels."""
+    (FP16 planes relative to the rows' largest exponents on the 256 x 256-tile kernel), then the FP16 matrix instruction
+    with per-block scaling, then the block-scaled kernel with three limbs per mantissa, then the int8 limb kernels."""
     import synth
     A, B = synth.c5_wide_range()
     rng = np.random.default_rng(6)
@@ -180,8 +180,12 @@ def test_config5_wide_range_bfp12(hb):
     rows = _rows_with_edges(8192, rng)
     C = hb.gemm(ta, tb)
     torch.cuda.synchronize()
-    assert hb.gemm_workspace(ta.desc, tb.desc) == hb.gemm_select_workspace(ta.desc, tb.desc, hb.KERNEL_FP16)
-    _check_product(hb, "c5 fp16", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, "fp16", rng)
+    assert hb.gemm_workspace(ta.desc, tb.desc) == hb.gemm_select_workspace(ta.desc, tb.desc, hb.KERNEL_FP16_PLANES)
+    _check_product(hb, "c5 fp16 planes", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, "bf16", rng)
+    C.zero_()
+    C = hb.gemm(ta, tb, out=C, kernel=hb.KERNEL_FP16)
+    torch.cuda.synchronize()
+    _check_product(hb, "c5 fp16", ta, tb, oa, ob, (1, 64, 12), (64, 1, 12), C, rows, "fp16", rng, windows=False)
     C.zero_()
     C = hb.gemm(ta, tb, out=C, kernel=hb.KERNEL_SCALED)
     torch.cuda.synchronize()

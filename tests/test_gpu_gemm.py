@@ -936,6 +936,57 @@ def test_bf16_kernel_is_the_automatic_choice_and_equals_the_packed_route(hb):
     assert rel_fro(auto.cpu().numpy(), int8.cpu().numpy().astype(np.float64)) <= 2e-6
 
 
+# ---- 9..12-bit mantissas as FP16 numbers relative to their rows' largest exponents (HBFP_KERNEL_FP16_PLANES)
+
+F16P = 6
+
+
+@pytest.mark.parametrize("case", random_cases(24))
+def test_fp16_planes_kernel_random_shapes(hb, case):
+    """Seeded random shapes, block lengths, 9..12-bit mantissas (equal or not), rounding modes and beta; values spread over
+    2 to 9 binades element by element and, in a third of the cases, over 2^+-20 row by row (the rows' own factors)."""
+    rng = np.random.default_rng(9000 + case)
+    M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+    K = int(rng.choice([1, 7, 31, 32, 33, 63, 64, 65, 127, 129, 500, 1023, 1500]))
+    blk = int(rng.choice([8, 16, 24, 32, 48, 64, 100, 256]))
+    ma, mb = int(rng.integers(9, 13)), int(rng.integers(9, 13))
+    ra, rb = int(rng.integers(2)), int(rng.integers(2))
+    A, B = _rand((M, K), 6100 + case, int(rng.integers(1, 5))), _rand((K, N), 7100 + case)
+    if case % 3 == 0:
+        A = (A * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)
+        B = (B * np.exp2(rng.integers(-20, 21, size=(1, N)))).astype(np.float32)
+    _run(hb, A, B, (1, blk, ma, ra, 17 + case), (blk, 1, mb, rb, 29 + case), partials=False, kernel=F16P,
+         beta=float(rng.integers(2)))
+
+
+def test_fp16_planes_kernel_block_exponents_far_apart_in_a_row(hb):
+    """Blocks of one row up to 28 binades below the row's largest are exact FP16 numbers (subnormals from 14 on); one block
+    further down marks the operand and the product is computed from the stored operands inside the same kernel."""
+    rng = np.random.default_rng(3)
+    M, N, K, blk = 300, 270, 1024, 64
+    B = _rand((K, N), 5)
+    for spread, expect_marked in ((12, False), (20, False), (27, False), (36, True)):
+        A = rng.standard_normal((M, K)).astype(np.float32)
+        for b in range(K // blk):
+            A[:, b * blk:(b + 1) * blk] *= np.float32(2.0 ** -(spread * b // (K // blk - 1)))
+        print(f"[case] FP16 planes, blocks of a row {spread} binades apart", flush=True)
+        _run(hb, A, B, (1, blk, 12, 0, 0), (blk, 1, 12, 0, 0), partials=False, kernel=F16P)
+        _run(hb, A, B, (1, blk, 10, 1, 3), (blk, 1, 11, 0, 0), partials=False, kernel=F16P, beta=1.0)
+
+
+def test_fp16_planes_is_the_automatic_choice_for_large_wide_products(hb):
+    M, K, N = 3072, 2048, 3072
+    rng = np.random.default_rng(13)
+    X = torch.from_numpy((rng.standard_normal((M, K)) * np.exp2(rng.integers(-20, 21, size=(M, 1)))).astype(np.float32)).cuda()
+    W = torch.from_numpy((rng.standard_normal((K, N)) * 0.05).astype(np.float32)).cuda()
+    x, w = hb.encode(X, 1, hb.make_format(12, 1, 64, 1, 5)), hb.encode(W, 0, hb.make_format(12, 64, 1, 1, 6))
+    assert hb.gemm_workspace(x.desc, w.desc) == hb.gemm_select_workspace(x.desc, w.desc, F16P)
+    auto, named, fp16 = hb.gemm(x, w), hb.gemm(x, w, kernel=F16P), hb.gemm(x, w, kernel=4)
+    torch.cuda.synchronize()
+    assert torch.equal(auto, named)
+    assert rel_fro(auto.cpu().numpy(), fp16.cpu().numpy().astype(np.float64)) <= 2e-6
+
+
 # ---- the 256 x 256-tile int8 kernel for one exponent per operand row (HBFP_KERNEL_INT8_WIDE)
 
 WIDE = 3
