@@ -354,8 +354,8 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
                                                     "TOPS_incl_encode": round(flops / ms_all / 1e9, 1)}
     del ti, tf, out, wsc, img, Wd, dimg
     del X, W, dY
-    # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: the
-    # FP16 matrix instruction on mantissas widened to FP16)
+    # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: FP16 planes
+    # relative to the rows' largest exponents, packed inside the call, on the 256 x 256-tile kernel)
     Ah, Bh = synth.c5_wide_range()
     A, B = torch.from_numpy(Ah).cuda(), torch.from_numpy(Bh).cuda()
     fa, fb = hbfp.make_format(12, 1, 64, hbfp.STOCHASTIC, 51), hbfp.make_format(12, 64, 1, hbfp.STOCHASTIC, 52)
@@ -475,8 +475,9 @@ def _encoded_output(torch, hbfp, reps=10):
 
 def _kernel_families(torch, hbfp, reps=8):
     """The ways the library evaluates the product, side by side on square products with N(0,1) operands:
-    int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction, and for
-    12-bit mantissas the FP16 matrix instruction on mantissas widened to FP16 (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included).  Block length 0 is one
+    int8 matrix instructions + FP32 scaling on the vector unit against the block-scaled matrix instruction, for 6..9-bit
+    mantissas the bf16 matrix instruction on bf16 planes, and for 12-bit mantissas the FP16 matrix instruction on mantissas
+    widened to FP16, with per-block scaling or on planes relative to the rows' largest exponents (hbfp_gemm_select).  Times are whole calls (packing / scale-word kernels included).  Block length 0 is one
     exponent per row of A and per column of B (Sec. 4), where the int8 family runs its 256 x 256-tile kernel
     (one chain of matrix instructions, exponents applied at the store)."""
     res = {}
@@ -495,7 +496,8 @@ def _kernel_families(torch, hbfp, reps=8):
             del wse
         del A, B
         out = torch.empty((n, n), dtype=torch.float32, device="cuda")
-        families = [("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)] + ([("fp16", hbfp.KERNEL_FP16)] if m > 8 else []) + \
+        families = [("int8", hbfp.KERNEL_INT8), ("scaled", hbfp.KERNEL_SCALED)] + \
+                   ([("fp16", hbfp.KERNEL_FP16), ("fp16_planes", hbfp.KERNEL_FP16_PLANES)] if m > 8 else []) + \
                    ([("bf16", hbfp.KERNEL_BF16)] if 6 <= m <= 9 else [])
         for tag, kernel in families:
             ws = torch.empty(max(hbfp.gemm_select_workspace(ta.desc, tb.desc, kernel), 256), dtype=torch.uint8, device="cuda")
