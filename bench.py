@@ -714,7 +714,7 @@ def main():
         # per mantissa product, over the product kernel's launch time, against the published dense int8 matrix peak.
         # The kernel reaches them on the bf16 matrix instruction (one multiply-add per mantissa pair), whose own
         # published peak is half the int8 one: own_dtype holds the same rate against that.
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf_kernel<false>", "achieved": round(product_tops, 1),
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf_kernel<false, false>", "achieved": round(product_tops, 1),
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(product_tops / INT8_PEAK_TOPS, 4),
                      "own_dtype": {"dtype": "bf16", "achieved": round(product_tops, 1), "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": round(product_tops / BF16_PEAK_TFLOPS, 4),
