@@ -396,29 +396,31 @@ int hbfp_gemm_bfp(const hbfp_tensor *A, const hbfp_tensor *B, const hbfp_tensor 
  * between two optimizer steps: Sec. 5.1 converts them once per update).  hbfp_pack reorders an encoded operand
  * (mantissas of at most 12 bits) into the form the product kernels read.  The form depends on the operand's mantissa
  * width alone: 6..9 bits -> the bf16 values of its elements (Eq. (1), exact: at most 8 significant bits) in the
- * register order of the bf16 matrix instruction; otherwise -> planes of 4-bit limbs with scale bytes for the
- * block-scaled matrix instruction.
+ * register order of the bf16 matrix instruction; 10..12 bits -> FP16 elements relative to the largest exponent byte of
+ * their row, behind one scale word per row (HBFP_KERNEL_FP16_PLANES); at most 5 bits -> planes of 4-bit limbs with scale
+ * bytes for the block-scaled matrix instruction.
  *   packed  device buffer of hbfp_pack_bytes bytes, 256-byte aligned, owned by the caller; its contents are
  *           opaque and stay valid until the operand is encoded again (then pack it again).  The first 256 bytes
  *           hold a mark that differs from pack to pack (it lets a pack signal "cannot be expressed" without
  *           anything having to be cleared first), so two packs of the same operand agree from byte 256 on, not
  *           before: the rule "same inputs, same bytes" holds for every result except this header.  Its first two
  *           32-bit words are equal exactly when the operand is marked: bf16 planes, a non-zero block with an exponent
- *           byte above 253 (values from 2^127 on); limb planes, an exponent byte outside the range of the scale bytes,
+ *           byte above 253 (values from 2^127 on); FP16 planes, a non-zero block more than 28 binades below the largest
+ *           of its row; limb planes, an exponent byte outside the range of the scale bytes,
  *           or neighbouring blocks of a densely packed group more than 3 binades apart, as heavy-tailed values produce
  *           them.  A caller may read the words once the pack has completed.  Products on a marked operand are still
- *           computed inside the same call: from the stored operands by the bf16 kernel itself (slowly; such values do
- *           not occur in training data), or by the older int8 kernel behind the block-scaled kernel (by the faster one
+ *           computed inside the same call: from the stored operands by the bf16 / FP16 kernel itself (slowly; such values
+ *           do not occur in training data), or by the older int8 kernel behind the block-scaled kernel (by the faster one
  *           if the operand carries HBFP_HINT_HEAVY_TAILS; hbfp_gemm_select with HBFP_KERNEL_INT8 on the stored operands
  *           is the fastest way to that product).
  *           The buffer is
  *           sized for blocks stored padded to 32; blocks of 8, 16 and 24 elements are packed without their
  *           padding and leave its tail unwritten.
- * hbfp_gemm_packed is hbfp_gemm_select on operands packed beforehand, with HBFP_KERNEL_BF16 when both are bf16 planes
- * and HBFP_KERNEL_SCALED when both are limb planes (a pair of the two forms is multiplied by the int8 kernels from the
- * stored operands): C and beta as in hbfp_gemm; A and B are the descriptors the buffers were packed from (their
+ * hbfp_gemm_packed is hbfp_gemm_select on operands packed beforehand, with HBFP_KERNEL_BF16 when both are bf16 planes,
+ * HBFP_KERNEL_FP16_PLANES when both are FP16 planes and HBFP_KERNEL_SCALED when both are limb planes (a pair of different
+ * forms is multiplied by the int8 kernels from the stored operands): C and beta as in hbfp_gemm; A and B are the descriptors the buffers were packed from (their
  * mantissas and exponents are read only in the cases just named); workspace: hbfp_gemm_packed_workspace bytes (what the
- * int8 kernels need; nothing for a pair of bf16 planes).
+ * int8 kernels need; nothing for a pair of bf16 planes or of FP16 planes).
  * Errors: HBFP_ERR_ARG (null or misaligned pointers, beta, ldc), HBFP_ERR_FORMAT (mantissas wider than 12 bits,
  * mixed classes), HBFP_ERR_LAYOUT, HBFP_ERR_RANGE as hbfp_gemm, HBFP_ERR_WORKSPACE (packed buffer or workspace too
  * small), HBFP_ERR_LAUNCH.

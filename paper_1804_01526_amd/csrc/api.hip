@@ -344,7 +344,9 @@ static int pack_one(const hbfp_tensor *t, void *packed, hipStream_t s) {
     g.nblk = t->nblk;
     g.kdim = t->kdim;
     g.mA = g.mB = t->mant_bits;
-    return bf_operand(t->mant_bits) ? launch_bf_pack(g, packed, nullptr, s) : launch_mx_pack(g, packed, nullptr, s);
+    return bf_operand(t->mant_bits) ? launch_bf_pack(g, packed, nullptr, s)
+           : t->mant_bits >= 10     ? launch_f16_planes_pack(g, packed, nullptr, s)
+                                    : launch_mx_pack(g, packed, nullptr, s);
 }
 
 // argument checks of hbfp_encode_packed for one source; *need: bytes of its conversion's scratch
@@ -913,15 +915,16 @@ int hbfp_pack(const hbfp_tensor *t, void *packed, size_t bytes, void *stream) {
 // The packed form of an operand depends on its mantissa width alone (6..9 bits: bf16 planes, otherwise limb planes), so
 // a product of packed operands runs on the bf16 kernel, on the block-scaled kernel, or, when the two forms meet, on the
 // int8 kernels from the stored operands.
-enum { kPackedMx = 0, kPackedBf = 1, kPackedMixed = 2 };
+enum { kPackedMx = 0, kPackedBf = 1, kPackedMixed = 2, kPackedF16 = 3 };
+static int packed_form(int mant_bits) { return bf_operand(mant_bits) ? 1 : mant_bits >= 10 ? 2 : 0; }
 static int packed_kind(const hbfp_tensor *A, const hbfp_tensor *B) {
-    const bool a = bf_operand(A->mant_bits), b = bf_operand(B->mant_bits);
-    return a && b ? kPackedBf : a == b ? kPackedMx : kPackedMixed;
+    const int a = packed_form(A->mant_bits), b = packed_form(B->mant_bits);
+    return a != b ? kPackedMixed : a == 1 ? kPackedBf : a == 2 ? kPackedF16 : kPackedMx;
 }
 
 int hbfp_gemm_packed_workspace(const hbfp_tensor *A, const hbfp_tensor *B, size_t *bytes) {
     const int rc = hbfp_gemm_select_workspace(A, B, HBFP_KERNEL_INT8, bytes);
-    if (rc == HBFP_OK && packed_kind(A, B) == kPackedBf) *bytes = 0;      // no stand-by kernels behind the bf16 kernel
+    if (rc == HBFP_OK && (packed_kind(A, B) == kPackedBf || packed_kind(A, B) == kPackedF16)) *bytes = 0;      // no stand-by kernels behind the bf16 / FP16 kernel
     return rc;
 }
 
@@ -943,8 +946,9 @@ int hbfp_gemm_packed(const hbfp_tensor *A, const void *packed_a, const hbfp_tens
     if (!gemm_mx_possible(g)) return HBFP_ERR_ARG;
     const int kind = packed_kind(A, B);
     if (kind == kPackedBf) rc = launch_bf_products(1, &g, &packed_a, &packed_b, (hipStream_t)stream);
+    else if (kind == kPackedF16) rc = launch_f16_planes_products(1, &g, &packed_a, &packed_b, (hipStream_t)stream);
     else if (kind == kPackedMx) rc = launch_mx_product(g, packed_a, packed_b, fast_standby(A, B) ? workspace : nullptr, (hipStream_t)stream);
-    if (rc != HBFP_OK || kind == kPackedBf) return rc;      // the bf16 kernel deals with marked operands itself
+    if (rc != HBFP_OK || kind == kPackedBf || kind == kPackedF16) return rc;      // that kernel deals with marked operands itself
     if (kind != kPackedMixed) {      // the int8 kernels stand by; for a mixed pair they are the product
         g.run_a = (const int *)packed_a;
         g.run_b = (const int *)packed_b;
@@ -1001,9 +1005,11 @@ int hbfp_gemm_packed_batch(int n, const hbfp_tensor *const *A, const void *const
             w += part[i];
         }
     }
-    int rc = kind == kPackedBf ? launch_bf_products(n, g, packed_a, packed_b, s)
-             : kind == kPackedMx ? launch_mx_products(n, g, packed_a, packed_b, standby, s) : HBFP_OK;
-    if (rc != HBFP_OK || kind == kPackedBf) return rc;      // the bf16 kernel deals with marked operands itself
+    int rc = kind == kPackedBf    ? launch_bf_products(n, g, packed_a, packed_b, s)
+             : kind == kPackedF16 ? launch_f16_planes_products(n, g, packed_a, packed_b, s)
+             : kind == kPackedMx  ? launch_mx_products(n, g, packed_a, packed_b, standby, s)
+                                  : HBFP_OK;
+    if (rc != HBFP_OK || kind == kPackedBf || kind == kPackedF16) return rc;      // that kernel deals with marked operands itself
     char *ws = (char *)workspace;
     for (int i = 0; i < n; ++i) {      // the int8 kernels stand by behind the group, one launch per product
         if (kind != kPackedMixed) {

@@ -413,7 +413,7 @@ BfPackParams bf_pack_params(const GemmArgs &a, const void *mant, const uint8_t *
 bool bf_operand(int mant_bits) { return bf_class(mant_bits); }
 
 size_t packed_operand_bytes(int64_t rows, int64_t kpad, int mant_bits) {
-    return bf_class(mant_bits) ? bf_packed_bytes(rows, kpad) : mx_packed_bytes(rows, kpad, mant_bits);
+    return bf_class(mant_bits) ? bf_packed_bytes(rows, kpad) : mant_bits >= 10 ? f16_packed_bytes(rows, kpad) : mx_packed_bytes(rows, kpad, mant_bits);
 }
 
 static bool shape_ok(const GemmArgs &a) {

@@ -30,7 +30,7 @@ def _flagged(buf):
 
 def _planes_end(d):
     """First byte past the planes a pack writes, behind the 256-byte header.  Mantissas of 6..9 bits: bf16 planes, 256-row
-    panels x packed k x 2 bytes; others: limb planes, 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
+    panels x packed k x 2 bytes; 10..12 bits: the same with FP16 elements behind a scale word per row; others: limb planes, 256-row panels x k-steps of 64 x 8 row tiles x (limbs x 1536 + 256)
     bytes.  Blocks of 8, 16 and 24 are packed without their padding (buffers are sized for the padded length, the rest is
     never written), and octets of the last block that hold no element are not packed."""
     limbs = 1 if d.mant_bits <= 5 else 2 if d.mant_bits <= 9 else 3
@@ -38,6 +38,8 @@ def _planes_end(d):
     klen = -(-min(d.nblk * d.kblock, -(-d.kdim // 8) * 8) // 128) * 128 if dense else d.kpad
     if 6 <= d.mant_bits <= 9:
         return 256 + -(-d.rows // 256) * 256 * klen * 2
+    if d.mant_bits >= 10:            # FP16 planes behind one scale word per row
+        return 256 + -(-d.rows // 256) * 256 * (4 + klen * 2)
     return 256 + -(-d.rows // 256) * (klen // 64) * 8 * (limbs * 1536 + 256)
 
 

@@ -583,7 +583,8 @@ def _oracle_product(A, B, fa, fb):
 @pytest.mark.parametrize("m,blk,M,N,K", [(8, 32, 300, 270, 700), (4, 24, 130, 520, 330), (12, 64, 260, 140, 512), (9, 0, 70, 90, 200)])
 def test_packed_operands_two_step_product(hb, m, blk, M, N, K):
     """hbfp_pack once, hbfp_gemm_packed many times: the weights' planes serve several activations, results
-    within the bound of the oracle and identical to the one-call block-scaled product."""
+    within the bound of the oracle and identical to the one-call product on the kernel that reads that packed form
+    (limb planes: block-scaled; bf16 planes: bf16; FP16 planes: FP16 planes)."""
     print(f"[case] packed m={m} blk={blk} M={M} N={N} K={K}", flush=True)
     fa, fb = (1, blk, m, 0, 0), (blk, 1, m, 0, 0)
     W = (_rand((K, N), 31 + m, 1) * 0.05).astype(np.float32)
@@ -595,7 +596,7 @@ def test_packed_operands_two_step_product(hb, m, blk, M, N, K):
         tx = hb.encode(torch.from_numpy(X).cuda(), 1, hb.make_format(m, 1, blk))
         px = hb.pack(tx)
         C = hb.gemm_packed(tx, px, tw, pw)
-        C1 = hb.gemm(tx, tw, kernel=SCALED)
+        C1 = hb.gemm(tx, tw, kernel=5 if 6 <= m <= 9 else 6 if m >= 10 else SCALED)
         torch.cuda.synchronize()
         assert torch.equal(C, C1)
         err = rel_fro(C.cpu().numpy(), _oracle_product(X, W, fa, fb))
@@ -972,6 +973,38 @@ def test_fp16_planes_kernel_block_exponents_far_apart_in_a_row(hb):
         print(f"[case] FP16 planes, blocks of a row {spread} binades apart", flush=True)
         _run(hb, A, B, (1, blk, 12, 0, 0), (blk, 1, 12, 0, 0), partials=False, kernel=F16P)
         _run(hb, A, B, (1, blk, 10, 1, 3), (blk, 1, 11, 0, 0), partials=False, kernel=F16P, beta=1.0)
+
+
+def test_fp16_planes_as_the_packed_form_of_wide_operands(hb):
+    """hbfp_pack of 10..12-bit operands writes FP16 planes; hbfp_gemm_packed and hbfp_gemm_packed_batch on them equal the
+    one-call product bit for bit; an operand with blocks of a row more than 28 binades apart is marked and still
+    multiplied correctly; 12-bit planes against 9-bit ones (bf16 planes) go to the int8 limb kernels."""
+    rng = np.random.default_rng(8)
+    M, N, K, blk = 300, 270, 1024, 64
+    B = _rand((K, N), 5)
+    tb = hb.encode(torch.from_numpy(B).cuda(), 0, hb.make_format(12, blk, 1))
+    pb = hb.pack(tb)
+    for spread in (20, 36):
+        A = rng.standard_normal((M, K)).astype(np.float32)
+        for b in range(K // blk):
+            A[:, b * blk:(b + 1) * blk] *= np.float32(2.0 ** -(spread * b // (K // blk - 1)))
+        ta = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(11, 1, blk))
+        pa = hb.pack(ta)
+        torch.cuda.synchronize()
+        marked = bool(pa[:8].view(torch.int32)[0] == pa[:8].view(torch.int32)[1])
+        print(f"[case] packed FP16 planes, spread {spread}, marked={marked}", flush=True)
+        assert marked == (spread > 28)
+        assert hb.gemm_packed_workspace(ta.desc, tb.desc) == 0
+        C = hb.gemm_packed(ta, pa, tb, pb)
+        both = hb.gemm_packed_batch([(ta, pa, tb, pb), (ta, pa, tb, pb)], [torch.empty_like(C), torch.empty_like(C)])
+        one = hb.gemm(ta, tb, kernel=F16P)
+        torch.cuda.synchronize()
+        assert torch.equal(C, one) and torch.equal(both[0], C) and torch.equal(both[1], C)
+        assert rel_fro(C.cpu().numpy(), _oracle_product(A, B, (1, blk, 11, 0, 0), (blk, 1, 12, 0, 0))) <= TOL
+    t9 = hb.encode(torch.from_numpy(A).cuda(), 1, hb.make_format(9, 1, blk))
+    C = hb.gemm_packed(t9, hb.pack(t9), tb, pb)
+    torch.cuda.synchronize()
+    assert rel_fro(C.cpu().numpy(), _oracle_product(A, B, (1, blk, 9, 0, 0), (blk, 1, 12, 0, 0))) <= TOL
 
 
 def test_fp16_planes_is_the_automatic_choice_for_large_wide_products(hb):
