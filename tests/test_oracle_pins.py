@@ -241,6 +241,47 @@ def test_block_of_one_is_a_float_cast():
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("m,kb", [(6, 24), (8, 24), (8, 32), (9, 64)])
+def test_decoded_values_of_narrow_mantissas_are_bfloat16_numbers(m, kb):
+    """What the bf16 product route rests on: a mantissa of at most 9 bits times its block's power of two (Eq. (1)) is a
+    bfloat16 number for every exponent byte up to 253, subnormal blocks included; the library cast is the check."""
+    rng = np.random.default_rng(40 + m)
+    x = (rng.standard_normal((64, 960)) * np.exp2(rng.integers(-126, 126, size=(64, 1)))).astype(np.float32)
+    x[:4] = (rng.standard_normal((4, 960)) * 2.0 ** -132).astype(np.float32)   # FP32 subnormals: exponent byte 1
+    x[4:8, ::7] = 0.0
+    t = ref.encode(x, 1, kb, m)
+    assert int(t.exps.max()) <= 253 and int(t.exps.min()) == 1
+    d = ref.decode(t)
+    assert np.isfinite(d).all()
+    np.testing.assert_array_equal(torch.from_numpy(d).to(torch.bfloat16).to(torch.float32).numpy(), d)
+
+
+@pytest.mark.parametrize("m", [10, 11, 12])
+def test_wide_mantissas_relative_to_the_row_maximum_are_half_precision_numbers(m):
+    """What the FP16-planes route rests on: mant * 2^(E - Eref + 4), Eref the largest exponent byte of the operand row, is an
+    IEEE half-precision number (subnormals included) whenever the block lies at most 28 binades below the row's largest,
+    its magnitude stays below 2^15, and decode = that number times 2^(Eref - 4 - 125 - m) exactly."""
+    rng = np.random.default_rng(50 + m)
+    kb, nb = 64, 16
+    x = rng.standard_normal((48, kb * nb)).astype(np.float32)
+    for b in range(nb):                                                       # blocks of a row 0..28 binades apart
+        x[:, b * kb:(b + 1) * kb] *= np.float32(2.0 ** -(28 * b // (nb - 1)))
+    x *= np.exp2(rng.integers(-60, 60, size=(48, 1))).astype(np.float32)
+    t = ref.encode(x, 1, kb, m)
+    e = t.exps.astype(np.int64)                                               # [rows, blocks]
+    eref = e.max(axis=1, keepdims=True)
+    assert int((eref - e).max()) >= 27
+    shift = np.repeat(e - eref + 4, kb, axis=1)
+    rel = np.ldexp(t.mant.astype(np.float64), shift)
+    ok = np.repeat(eref - e <= 28, kb, axis=1)
+    assert np.abs(rel).max() < 2.0 ** 15
+    half = rel.astype(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(half[ok], rel[ok])
+    np.testing.assert_array_equal(np.ldexp(rel, np.broadcast_to(eref - 4 - 125 - m, rel.shape)).astype(np.float32), ref.decode(t))
+    # one binade further and the last bit of an odd mantissa is lost
+    assert np.float64(np.float16(np.ldexp(1.0, -25))) == 0.0
+
+
 def test_zero_subnormal_and_signed_zero():
     x = np.zeros((2, 32), dtype=np.float32)
     x[1, 3] = -0.0
