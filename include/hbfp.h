@@ -269,6 +269,34 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
                      void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_gemm_conv2d_dgrad: the data gradient of a convolution of any stride, executed like the forward pass (Sec. 5.1
+ * treats the backward pass of a convolution as it treats the forward pass: as a BFP matrix product).  With
+ *     y[img][oy][ox][f] = sum over (fr, fs, ch) of x[img][oy*stride_h - pad_h + fr][ox*stride_w - pad_w + fs][ch] * w[fr][fs][ch][f]
+ * the gradient is the adjoint sum
+ *     dX[(img, iy, ix)][ch] = beta * dX + sum over (fr, fs, f) and the (oy, ox) with oy*stride_h - pad_h + fr = iy,
+ *                             ox*stride_w - pad_w + fs = ix of dy[img][oy][ox][f] * w[fr][fs][ch][f],
+ * which is a stride-1 convolution, with padding (r - 1 - pad_h, s - 1 - pad_w), of dy with stride - 1 rows and columns of
+ * zeros put between its pixels, against the filter mirrored in both window axes with its channel axes exchanged.  The
+ * zeros are never stored: the product kernel gathers each tap from dy as converted once ([n*ho*wo][filters], blocks of 32
+ * filters) and reads a page of zeros for the positions in between; all h x w input positions are computed, also those
+ * that only part of a window reaches.  Both factors count as their BFP values and the sum is taken as Eq. (2) takes it.
+ * With stride 1 this is hbfp_gemm_conv2d on dy with that padding.
+ *   dy       encoded [n*ho*wo][filters], contraction axis 1, blocks of 32 along the filters, filters a multiple of 64,
+ *            <= 8 bits (ho, wo: the output extents of conv)
+ *   conv     geometry of the FORWARD convolution (n, h, w, c describe x; c_block must be 0)
+ *   filters  encoded matrix [r*s*filters][c] with row ((r-1-fr) * s + (s-1-fs)) * filters + f, column ch = w[fr][fs][ch][f],
+ *            contraction axis 0, blocks of 32 down its rows, <= 8 bits
+ *   dX       device FP32 [n*h*w][ldx], ldx >= c; beta 0 or 1
+ *   workspace  hbfp_gemm_conv2d_dgrad_workspace bytes, 256-byte aligned
+ * Cost: every tap of the dilated image is multiplied, zeros included, so the matrix cores do stride_h * stride_w times
+ * the work the sum needs.
+ * Errors: as hbfp_gemm_conv2d; HBFP_ERR_ARG also for extents from 2^21 on.
+ */
+int hbfp_gemm_conv2d_dgrad_workspace(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes);
+int hbfp_gemm_conv2d_dgrad(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *dX, int64_t ldx, float beta,
+                           void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_gemm: the BFP matrix product, Eq. (2) with per-block FP accumulation
  * (Sec. 4, tiled matrix multiplication):
  *     C[i][j] = beta*C[i][j] + sum_b 2^(eA[i][b] + eB[j][b]) * sum_{k in b} mA[i][k]*mB[j][k]

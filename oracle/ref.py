@@ -158,6 +158,29 @@ def filter_matrix_dgrad(w4: np.ndarray, c_block: int = 0) -> np.ndarray:
     return filter_matrix(np.ascontiguousarray(mirrored), c_block)
 
 
+def im2col_dgrad(dy: np.ndarray, h: int, w: int, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1,
+                 stride_w: int = 1) -> np.ndarray:
+    """Activation operand of the data gradient of a convolution of any stride (Sec. 5.1: the backward pass is executed
+    like the forward pass).  dy [n, ho, wo, f] is the gradient of y[oy, ox] = sum x[oy*stride - pad + fr, ...] w4[fr, ...];
+    x has h x w positions.  dx[iy, ix] collects dy[oy, ox] * w4[fr, fs] over all oy*stride_h - pad_h + fr = iy (same in
+    x), i.e. it is a stride-1 convolution of dy spread out with stride - 1 zeros between its pixels: dy[oy, ox] sits at
+    position (r - 1 - pad_h + oy*stride_h, s - 1 - pad_w + ox*stride_w) of a zero canvas of (h + r - 1) x (w + s - 1), and
+    row (img, iy, ix) of the result holds the canvas under the window whose corner is (iy, ix), column
+    (fr' * s + fs') * f + ch: [n*h*w, r*s*f], to be multiplied by filter_matrix_dgrad."""
+    n, ho, wo, f = dy.shape
+    canvas = np.zeros((n, h + r - 1, w + s - 1, f), dtype=dy.dtype)
+    for oy in range(ho):
+        for ox in range(wo):
+            cy, cx = r - 1 - pad_h + oy * stride_h, s - 1 - pad_w + ox * stride_w
+            if 0 <= cy < h + r - 1 and 0 <= cx < w + s - 1:            # beyond: a window that lies wholly in the padding
+                canvas[:, cy, cx, :] = dy[:, oy, ox, :]
+    out = np.empty((n, h, w, r, s, f), dtype=dy.dtype)
+    for fr in range(r):
+        for fs in range(s):
+            out[:, :, :, fr, fs, :] = canvas[:, fr:fr + h, fs:fs + w, :]
+    return out.reshape(n * h * w, r * s * f)
+
+
 def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:
     """Integer block partials P[i, j, b] of Eq. (2); mA [M, K], mB [K, N]."""
     mA = np.ascontiguousarray(mA, dtype=np.int32)

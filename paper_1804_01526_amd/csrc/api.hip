@@ -528,6 +528,81 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
     return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream);
 }
 
+// The data gradient of a convolution of any stride: a stride-1 convolution of the zero-dilated output gradient with
+// padding r - 1 - pad and the mirrored filter, computed for all h x w positions of the input.  The synthesized geometry
+// describes that convolution: its image is dY as stored.
+static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, hbfp_conv2d *as_forward) {
+    if (!dy || !conv || !filters) return HBFP_ERR_ARG;
+    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
+        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
+        return HBFP_ERR_ARG;
+    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    if (conv->c_block > 0 && conv->c_block < conv->c) return HBFP_ERR_FORMAT;
+    int rc = check_tensor(dy, need_ptrs);
+    if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
+    if (rc != HBFP_OK) return rc;
+    const int64_t ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
+    const int64_t wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
+    const int64_t f = dy->src_cols;
+    if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || f > 0x7fffffff || conv->n * conv->h * conv->w > 0x7fffffff ||
+        conv->n * ho * wo > 0x7fffffff || conv->pad_h > 0xffff || conv->pad_w > 0xffff || conv->stride_h > 0xffff || conv->stride_w > 0xffff)
+        return HBFP_ERR_ARG;
+    if (dy->contract_axis != 1 || dy->src_rows != conv->n * ho * wo) return HBFP_ERR_LAYOUT;
+    if (filters->contract_axis != 0 || filters->src_rows != (int64_t)conv->r * conv->s * f || filters->src_cols != conv->c) return HBFP_ERR_LAYOUT;
+    if (dy->mant_bits > 8 || filters->mant_bits > 8) return HBFP_ERR_FORMAT;
+    if (dy->kblock != 32 || dy->rblock != 1 || dy->kshare != 1 || filters->kblock != 32 || filters->rblock != 1 || filters->kshare != 1 ||
+        (f & 63))
+        return HBFP_ERR_FORMAT;
+    *as_forward = *conv;
+    as_forward->h = ho;
+    as_forward->w = wo;
+    as_forward->c = f;
+    as_forward->pad_h = conv->r - 1 - conv->pad_h;
+    as_forward->pad_w = conv->s - 1 - conv->pad_w;
+    as_forward->stride_h = as_forward->stride_w = 1;
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d_dgrad_workspace(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    hbfp_conv2d fw;
+    const int rc = conv_dgrad_check(dy, conv, filters, false, &fw);
+    if (rc != HBFP_OK) return rc;
+    *bytes = align256(gemm_conv_workspace(conv->n * conv->h * conv->w, filters->rows, filters->kpad, dy->rows, (int)(fw.c / 32)));
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d_dgrad(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *dX, int64_t ldx, float beta,
+                           void *workspace, size_t ws_bytes, void *stream) {
+    hbfp_conv2d fw;
+    int rc = conv_dgrad_check(dy, conv, filters, true, &fw);
+    if (rc != HBFP_OK) return rc;
+    if (!dX || ((uintptr_t)dX & 3) || ldx < filters->rows || (beta != 0.0f && beta != 1.0f)) return HBFP_ERR_ARG;
+    size_t need = 0;
+    hbfp_gemm_conv2d_dgrad_workspace(dy, conv, filters, &need);
+    if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = dy->mant;
+    g.expA = dy->exps;
+    g.expA_ld = dy->exp_ld;
+    g.mantB = filters->mant;
+    g.expB = filters->exps;
+    g.expB_ld = filters->exp_ld;
+    g.M = conv->n * conv->h * conv->w;
+    g.N = filters->rows;
+    g.kpad = filters->kpad;
+    g.nblk = filters->nblk;
+    g.kbp = 32;
+    g.kblock = 32;
+    g.mA = dy->mant_bits;
+    g.mB = filters->mant_bits;
+    g.C = dX;
+    g.ldc = ldx;
+    g.beta = beta;
+    return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w);
+}
+
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {
     if (!dst) return HBFP_ERR_ARG;
     int rc = check_tensor(t, true);

@@ -315,6 +315,10 @@ constexpr int kW8LdsBytes = kW8Ring * kHalfStage;           // 72 KB: two workgr
 // image is an operand of its own, [pixels][channels] with blocks of 32 channels; a stage of 64 bytes of k is 64
 // channels of one filter tap, i.e. of one pixel, so the gather is one address per lane and stage.  Taps that fall
 // outside the image read a page of zeros.
+// DIL: the image stands for one with dil - 1 rows and columns of zeros between its pixels (the output gradient of a
+// strided convolution, whose data gradient is a stride-1 convolution of exactly that, Sec. 5.1); positions of the
+// dilated image that are not a multiple of dil read the page of zeros as well, and the others divide by dil (in FP32:
+// exact while coordinates stay below 2^21, which the host checks).
 struct ConvA {
     const uint8_t *zeros;        // at least 64 zero bytes; behind them, at +64, one row-constant word for them
     const uint32_t *words;       // row constants of the image [channel block][pixel pitch]
@@ -322,7 +326,12 @@ struct ConvA {
     int32_t H, W, Ho, Wo, S, ntaps, spt;   // image, output, filter columns, taps, stages (64 channels) per tap
     int32_t pad_h, pad_w, str_h, str_w;
     int32_t pix_bytes;           // bytes between pixels of the encoded image
+    int32_t dil_h, dil_w;        // DIL only
+    float inv_dh, inv_dw;
 };
+
+// floor(i / d) for a coordinate i of the dilated image (may be negative), inv = 1 / d rounded
+__device__ __forceinline__ int conv_undilate(int i, float inv) { return (int)__builtin_floorf(((float)i + 0.5f) * inv); }
 
 struct W8Params {
     GemmParams g;
@@ -369,7 +378,7 @@ struct W8Ops<true> {
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-template <int SPB, bool CONV = false, bool F16 = false>
+template <int SPB, bool CONV = false, bool F16 = false, bool DIL = false>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     typedef W8Ops<F16> ops;
     typedef typename ops::acc_t acc_t;
@@ -426,6 +435,10 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         cchunk = ((lane & 3) ^ ((rm >> 2) & 3)) * 16;
         cpix = ((im * q.cv.H + cy) * q.cv.W + cx) * q.cv.pix_bytes + cchunk;     // byte offset of that corner's chunk in the image
         wpix = (iw * q.cv.H + wy) * q.cv.W + wx;
+        if (DIL) {                                                               // corners are in dilated coordinates: keep the image only
+            cpix = im * q.cv.H * q.cv.W * q.cv.pix_bytes + cchunk;
+            wpix = iw * q.cv.H * q.cv.W;
+        }
     }
     const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
     const int wc = wave_u & 3;                                                   // word copy: block wc >> 1, rows 64 (wc & 1) ..
@@ -449,9 +462,16 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         if (CONV) {                                                                                     \
             const bool tap_ok = ctap < q.cv.ntaps;                                                      \
             const uint8_t *tapA = p.A + ((int64_t)cfr * q.cv.W + cfs) * q.cv.pix_bytes + csub * kHalfK;  /* uniform */ \
-            const bool in_m = tap_ok && (unsigned)(cy + cfr) < (unsigned)q.cv.H && (unsigned)(cx + cfs) < (unsigned)q.cv.W; \
-            const uint8_t *srcA = in_m ? tapA + cpix : q.cv.zeros;                                      \
-            async_copy16_at(srcA, lb + ldsM);                                                           \
+            bool in_m = tap_ok && (unsigned)(cy + cfr) < (unsigned)q.cv.H && (unsigned)(cx + cfs) < (unsigned)q.cv.W; \
+            const uint8_t *srcA = tapA + cpix;                                                          \
+            if (DIL) {                                                                                  \
+                const int iy = cy + cfr, ix = cx + cfs;                                                 \
+                const int qy = conv_undilate(iy, q.cv.inv_dh), qx = conv_undilate(ix, q.cv.inv_dw);     \
+                in_m = tap_ok && qy * q.cv.dil_h == iy && qx * q.cv.dil_w == ix && (unsigned)qy < (unsigned)q.cv.H && \
+                       (unsigned)qx < (unsigned)q.cv.W;                                                 \
+                srcA = p.A + cpix + (int64_t)(qy * q.cv.W + qx) * q.cv.pix_bytes + csub * kHalfK;       \
+            }                                                                                           \
+            async_copy16_at(in_m ? srcA : q.cv.zeros, lb + ldsM);                                       \
         } else {                                                                                        \
             async_copy16(nextA, voffA, lb + ldsM);                                                      \
         }                                                                                               \
@@ -459,9 +479,16 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         if (CONV && wave_u < 4) {                                                                       \
             const bool tap_ok = ctap < q.cv.ntaps;                                                      \
             const uint32_t *tapW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + ((int64_t)cfr * q.cv.W + cfs);  /* uniform */ \
-            const bool in_w = tap_ok && (unsigned)(wy + cfr) < (unsigned)q.cv.H && (unsigned)(wx + cfs) < (unsigned)q.cv.W; \
-            const uint32_t *srcW = in_w ? tapW + wpix : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64); \
-            async_copy4_at(srcW, lb + ldsW);                                                            \
+            bool in_w = tap_ok && (unsigned)(wy + cfr) < (unsigned)q.cv.H && (unsigned)(wx + cfs) < (unsigned)q.cv.W; \
+            const uint32_t *srcW = tapW + wpix;                                                         \
+            if (DIL) {                                                                                  \
+                const int iy = wy + cfr, ix = wx + cfs;                                                 \
+                const int qy = conv_undilate(iy, q.cv.inv_dh), qx = conv_undilate(ix, q.cv.inv_dw);     \
+                in_w = tap_ok && qy * q.cv.dil_h == iy && qx * q.cv.dil_w == ix && (unsigned)qy < (unsigned)q.cv.H && \
+                       (unsigned)qx < (unsigned)q.cv.W;                                                 \
+                srcW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + (wpix + (qy * q.cv.W + qx)); \
+            }                                                                                           \
+            async_copy4_at(in_w ? srcW : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64), lb + ldsW); \
         } else {                                                                                        \
             async_copy4(nextW, voffW, lb + ldsW);                                                       \
         }                                                                                               \
@@ -727,8 +754,10 @@ size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, i
 
 // a: M = output positions, N = filters, mantB/expB = the filter matrix, kpad = its stored k extent (r * s * c rounded up to
 // 128); mantA/expA = the encoded image [pixels][pix_bytes], expA_ld its exponent pitch.
+// dil_h, dil_w > 1: the image stands for its zero-dilated form (c.h, c.w are the stored extents; c.pad_* and the taps
+// count in dilated positions); ho x wo is then whatever the caller wants computed.
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
-                        hipStream_t s) {
+                        hipStream_t s, int dil_h, int dil_w) {
     GemmParams p = {};
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;
@@ -782,6 +811,16 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     q.cv.str_h = c.stride_h;
     q.cv.str_w = c.stride_w;
     q.cv.pix_bytes = (int32_t)pix_bytes;
+    q.cv.dil_h = dil_h;
+    q.cv.dil_w = dil_w;
+    q.cv.inv_dh = 1.0f / (float)dil_h;
+    q.cv.inv_dw = 1.0f / (float)dil_w;
+    const bool dilated = dil_h > 1 || dil_w > 1;
+    if (dil_h < 1 || dil_w < 1) return HBFP_ERR_ARG;
+    // the kernel divides dilated coordinates in FP32
+    if (dilated && (ho * c.stride_h + c.r + (c.pad_h < 0 ? -c.pad_h : c.pad_h) >= (1 << 21) ||
+                    wo * c.stride_w + c.s + (c.pad_w < 0 ? -c.pad_w : c.pad_w) >= (1 << 21)))
+        return HBFP_ERR_ARG;
     {
         const int64_t most = pixels > q.npad ? pixels : q.npad;
         if (ceil_div(most, 256) > 0x7fffffff) return HBFP_ERR_ARG;
@@ -789,11 +828,14 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
                            pitch, wimg, a.expB, a.expB_ld, a.N, (int)(a.kpad / 32), q.npad, wflt, zeros);
         if (launch_status() != HBFP_OK) return HBFP_ERR_LAUNCH;
     }
-    static std::atomic<bool> configured{false};
+    static std::atomic<bool> configured{false}, configured_dil{false};
     if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true>), kW8LdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
+    if (allow_dynamic_lds(configured_dil, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, true>), kW8LdsBytes) != HBFP_OK)
+        return HBFP_ERR_LAUNCH;
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
-    hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     int rc = launch_status();
     if (rc != HBFP_OK) return rc;
     if (p.splits > 1) {

@@ -88,6 +88,10 @@ def _load():
     lib.hbfp_gemm_conv2d_workspace.restype = i32
     lib.hbfp_gemm_conv2d.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_conv2d.restype = i32
+    lib.hbfp_gemm_conv2d_dgrad_workspace.argtypes = [T, ctypes.POINTER(Conv2d), T, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_conv2d_dgrad_workspace.restype = i32
+    lib.hbfp_gemm_conv2d_dgrad.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
+    lib.hbfp_gemm_conv2d_dgrad.restype = i32
     lib.hbfp_gemm_workspace.argtypes = [T, T, ctypes.POINTER(sz)]
     lib.hbfp_gemm.argtypes = [T, T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_select_workspace.argtypes = [T, T, i32, ctypes.POINTER(sz)]
@@ -566,4 +570,25 @@ def gemm_conv2d(image: BfpTensor, conv: Conv2d, filters: BfpTensor, out: Optiona
     _check(_lib.hbfp_gemm_conv2d(ctypes.byref(image.desc), ctypes.byref(conv), ctypes.byref(filters.desc), _dev_ptr(out),
                                  out.stride(0), beta, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                                  _stream_ptr(stream)), "hbfp_gemm_conv2d")
+    return out
+
+
+def gemm_conv2d_dgrad_workspace(dy: TensorDesc, conv: Conv2d, filters: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_conv2d_dgrad_workspace(ctypes.byref(dy), ctypes.byref(conv), ctypes.byref(filters), ctypes.byref(n)),
+           "hbfp_gemm_conv2d_dgrad_workspace")
+    return int(n.value)
+
+
+def gemm_conv2d_dgrad(dy: BfpTensor, conv: Conv2d, filters: BfpTensor, out: Optional[torch.Tensor] = None, beta: float = 0.0,
+                      workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hbfp_gemm_conv2d_dgrad: dX[n*h*w, c] of the convolution `conv` (any stride) from its output gradient encoded once
+    as [n*ho*wo, filters] (blocks of 32 filters) and the mirrored filter matrix [r*s*filters, c]."""
+    if out is None:
+        out = torch.empty((conv.n * conv.h * conv.w, filters.desc.rows), dtype=torch.float32, device=dy.mant.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1
+    workspace = _workspace(gemm_conv2d_dgrad_workspace(dy.desc, conv, filters.desc), out.device, workspace)
+    _check(_lib.hbfp_gemm_conv2d_dgrad(ctypes.byref(dy.desc), ctypes.byref(conv), ctypes.byref(filters.desc), _dev_ptr(out),
+                                       out.stride(0), beta, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                       _stream_ptr(stream)), "hbfp_gemm_conv2d_dgrad")
     return out

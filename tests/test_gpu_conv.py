@@ -1,7 +1,8 @@
 """hbfp_gemm_conv2d: the convolution whose activation operand is gathered from the image converted once (Sec. 5.1:
 convolutions are executed like matrix products), against the oracle - which lowers the image explicitly - and against
 the library's own product on the lowered operand of hbfp_encode_im2col (bit for bit: a block of 32 channels of a pixel
-is the same block in the image and in every window that contains the pixel)."""
+is the same block in the image and in every window that contains the pixel).  hbfp_gemm_conv2d_dgrad: the data gradient
+of a convolution of any stride, gathered from the output gradient converted once."""
 import numpy as np
 import pytest
 import torch
@@ -110,6 +111,100 @@ def test_conv_data_gradient_of_a_stride_one_convolution(hb):
         for fs in range(3):
             want += dyp[:, 2 - fr:2 - fr + h, 2 - fs:2 - fs + w, :] @ wq[2 - fr, 2 - fs]
     assert rel_fro(dx.cpu().numpy(), want.reshape(n * h * w, c)) <= TOL
+
+
+def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
+    """hbfp_gemm_conv2d_dgrad against the oracle (dY converted, spread out and lowered explicitly, FP64 product with the
+    converted mirrored filter) and, bit for bit, against hbfp_gemm_conv2d on a dY whose zeros are really stored."""
+    rng = np.random.default_rng(seed)
+    ho, wo = (h + 2 * pad_h - r) // sh + 1, (w + 2 * pad_w - s) // sw + 1
+    print(f"[dgrad] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad=({pad_h},{pad_w}) stride=({sh},{sw}) dy {ho}x{wo}", flush=True)
+    dy = (rng.standard_normal((n, ho, wo, f)) * 1e-2 * np.exp2(rng.integers(-3, 4, size=(n, ho, wo, 1)))).astype(np.float32)
+    w4 = (rng.standard_normal((r, s, c, f)) * 0.1).astype(np.float32)
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4))                 # [r*s*f, c]
+    conv = hb.Conv2d(n, h, w, c, r, s, pad_h, pad_w, sh, sw, 0, 0)
+    assert conv.out_hw() == (ho, wo)
+    img = hb.encode(torch.from_numpy(dy.reshape(n * ho * wo, f)).cuda(), 1, hb.make_format(8, 1, 32))
+    flt = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, 32, 1))
+    x0 = None
+    if beta:
+        x0 = rng.standard_normal((n * h * w, c)).astype(np.float32)
+        dx = hb.gemm_conv2d_dgrad(img, conv, flt, out=torch.from_numpy(x0).cuda(), beta=1.0)
+    else:
+        dx = hb.gemm_conv2d_dgrad(img, conv, flt)
+    torch.cuda.synchronize()
+    dx = dx.cpu().numpy()
+    dyq = ref.decode(ref.encode(dy.reshape(n * ho * wo, f), 1, 32, 8)).reshape(n, ho, wo, f)
+    want = ref.gemm(ref.im2col_dgrad(dyq, h, w, r, s, pad_h, pad_w, sh, sw), ref.decode(ref.encode(wd, 32, 1, 8)))
+    if x0 is not None:
+        want = want + x0.astype(np.float64)
+    err = rel_fro(dx, want)
+    print(f"        rel fro err = {err:.3e}", flush=True)
+    assert err <= TOL
+    ph, pw = r - 1 - pad_h, s - 1 - pad_w
+    if ph >= 0 and pw >= 0 and not beta:
+        hc, wc = h + r - 1 - 2 * ph, w + s - 1 - 2 * pw                 # the spread-out dY, with the rows no window reaches
+        spread = np.zeros((n, hc, wc, f), dtype=np.float32)
+        spread[:, 0:(ho - 1) * sh + 1:sh, 0:(wo - 1) * sw + 1:sw, :] = dy
+        simg = hb.encode(torch.from_numpy(spread.reshape(n * hc * wc, f)).cuda(), 1, hb.make_format(8, 1, 32))
+        sconv = hb.Conv2d(n, hc, wc, f, r, s, ph, pw, 1, 1, 0, 0)
+        assert sconv.out_hw() == (h, w)
+        ds = hb.gemm_conv2d(simg, sconv, flt)
+        torch.cuda.synchronize()
+        assert np.array_equal(dx, ds.cpu().numpy()), "differs from the convolution of the stored spread-out gradient"
+
+
+@pytest.mark.parametrize("geom", [
+    # n, h, w, c, f, r, s, pad_h, pad_w, stride_h, stride_w   (of the forward convolution)
+    (2, 12, 12, 40, 64, 3, 3, 1, 1, 2, 2),           # the last row and column of x are reached by part of a window only
+    (2, 13, 11, 128, 128, 3, 3, 1, 1, 2, 2),
+    (3, 9, 10, 64, 64, 3, 3, 1, 1, 1, 1),            # stride 1: the plain gather
+    (2, 14, 14, 130, 64, 1, 1, 0, 0, 2, 2),          # a strided 1 x 1 convolution: three quarters of dx are zero
+    (1, 17, 15, 24, 192, 5, 3, 2, 1, 3, 2),
+    (2, 10, 9, 64, 64, 2, 2, 0, 0, 2, 2),            # windows that tile the image
+    (2, 9, 9, 33, 64, 3, 3, 0, 0, 4, 4),             # stride beyond the window: rows of x that no window touches
+    (2, 6, 7, 20, 64, 2, 2, 3, 2, 2, 2),             # padding wider than the window
+])
+def test_conv_data_gradient_geometries(hb, geom):
+    _dgrad_case(hb, *geom, seed=sum(geom) + 1)
+
+
+def test_conv_data_gradient_accumulates_and_splits_k(hb):
+    _dgrad_case(hb, 2, 12, 12, 40, 64, 3, 3, 1, 1, 2, 2, seed=15, beta=1.0)
+    _dgrad_case(hb, 1, 8, 8, 100, 1024, 3, 3, 1, 1, 2, 2, seed=16)         # few tiles, k = 9216: split along k
+    _dgrad_case(hb, 1, 8, 8, 100, 1024, 3, 3, 1, 1, 2, 2, seed=17, beta=1.0)
+
+
+def test_conv_data_gradient_random_geometries(hb):
+    for seed in random_cases(12):
+        rng = np.random.default_rng(9500 + seed)
+        r, s = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        h, w = int(rng.integers(r, 16)), int(rng.integers(s, 16))
+        geom = (int(rng.integers(1, 4)), h, w, int(rng.integers(1, 150)), 64 * int(rng.integers(1, 4)), r, s,
+                int(rng.integers(0, r + 1)), int(rng.integers(0, s + 1)), int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        _dgrad_case(hb, *geom, seed=seed)
+
+
+def test_conv_data_gradient_rejects_what_it_does_not_cover(hb):
+    import ctypes
+    conv = hb.Conv2d(2, 8, 8, 48, 3, 3, 1, 1, 2, 2, 0, 0)                  # dy 4 x 4
+    dy = hb.encode(torch.zeros((2 * 4 * 4, 64), device="cuda"), 1, hb.make_format(8, 1, 32))
+    flt = hb.encode(torch.zeros((9 * 64, 48), device="cuda"), 0, hb.make_format(8, 32, 1))
+    dx = torch.empty((128, 48), device="cuda")
+    ws = torch.empty(hb.gemm_conv2d_dgrad_workspace(dy.desc, conv, flt.desc), dtype=torch.uint8, device="cuda")
+    call = lambda d, c, f_, ldx=48, beta=0.0, w=ws: hb._lib.hbfp_gemm_conv2d_dgrad(
+        ctypes.byref(d.desc), ctypes.byref(c), ctypes.byref(f_.desc), dx.data_ptr(), ldx, beta, w.data_ptr(), w.numel(), None)
+    assert call(dy, conv, flt) == hb.OK
+    assert call(dy, conv, flt, ldx=40) == hb.ERR_ARG
+    assert call(dy, conv, flt, beta=2.0) == hb.ERR_ARG
+    assert call(dy, hb.Conv2d(2, 8, 8, 48, 3, 3, 1, 1, 1, 1, 0, 0), flt) == hb.ERR_LAYOUT              # dy of another stride
+    assert call(dy, hb.Conv2d(2, 8, 8, 40, 3, 3, 1, 1, 2, 2, 0, 0), flt) == hb.ERR_LAYOUT              # filter of other channels
+    assert call(dy, hb.Conv2d(2, 8, 8, 48, 3, 3, 1, 1, 2, 2, 16, 0), flt) == hb.ERR_FORMAT             # channel-block order
+    dy24 = hb.encode(torch.zeros((2 * 4 * 4, 64), device="cuda"), 1, hb.make_format(8, 1, 16))
+    assert call(dy24, conv, flt) == hb.ERR_FORMAT                                                      # blocks of 16 filters
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    assert call(dy, conv, flt, w=small) == hb.ERR_WORKSPACE
+    torch.cuda.synchronize()
 
 
 def test_conv_rejects_what_it_does_not_cover(hb):

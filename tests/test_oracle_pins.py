@@ -444,6 +444,37 @@ def test_data_gradient_of_a_convolution_as_a_forward_product(h, w, c, f, r, s, p
     assert np.sum(y * dy) == np.sum(x * want)
 
 
+@pytest.mark.parametrize("h,w,c,f,r,s,pad_h,pad_w,sh,sw", [(7, 8, 3, 4, 3, 3, 1, 1, 2, 2), (8, 8, 2, 3, 3, 3, 1, 1, 2, 2), (9, 7, 2, 3, 3, 2, 0, 1, 3, 2),
+                                                           (6, 9, 3, 2, 1, 1, 0, 0, 2, 3), (10, 10, 2, 2, 5, 5, 2, 2, 4, 1), (5, 6, 2, 3, 2, 2, 3, 2, 2, 2),
+                                                           (6, 6, 3, 2, 3, 3, 1, 1, 1, 1)])
+def test_data_gradient_of_a_strided_convolution_as_a_forward_product(h, w, c, f, r, s, pad_h, pad_w, sh, sw):
+    """Any stride: the adjoint of the convolution sum, written out from its definition, equals the lowered, spread-out dy
+    times the mirrored, channel-exchanged filter, at every position of x (also those that only some windows reach, and
+    with padding wider than the window); and <y, dy> = <x, dx>."""
+    rng = np.random.default_rng(h * 100 + w * 10 + r + sh)
+    n = 2
+    ho, wo = (h + 2 * pad_h - r) // sh + 1, (w + 2 * pad_w - s) // sw + 1
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float64)
+    wgt = rng.integers(-3, 4, size=(r, s, c, f)).astype(np.float64)
+    dy = rng.integers(-5, 6, size=(n, ho, wo, f)).astype(np.float64)
+    want = np.zeros((n, h, w, c))
+    for img in range(n):
+        for oy in range(ho):
+            for ox in range(wo):
+                for fr in range(r):
+                    for fs in range(s):
+                        iy, ix = oy * sh - pad_h + fr, ox * sw - pad_w + fs
+                        if 0 <= iy < h and 0 <= ix < w:
+                            want[img, iy, ix, :] += wgt[fr, fs, :, :] @ dy[img, oy, ox, :]
+    got = ref.im2col_dgrad(dy, h, w, r, s, pad_h, pad_w, sh, sw) @ ref.filter_matrix_dgrad(wgt)
+    assert got.shape == (n * h * w, c)
+    np.testing.assert_array_equal(got.reshape(n, h, w, c), want)
+    y = (ref.im2col(x, r, s, pad_h, pad_w, sh, sw) @ ref.filter_matrix(wgt)).reshape(n, ho, wo, f)
+    assert np.sum(y * dy) == np.sum(x * want)
+    if sh == 1 and sw == 1 and pad_h < r and pad_w < s:
+        np.testing.assert_array_equal(ref.im2col_dgrad(dy, h, w, r, s, pad_h, pad_w), ref.im2col(dy, r, s, r - 1 - pad_h, s - 1 - pad_w))
+
+
 def test_filter_matrix_tiles_in_channel_block_order_are_the_outer_dimension_tiles():
     """Sec. 5.1 tiles the two outer dimensions of a convolution's filter.  With the window entries in channel-block order
     a tile of (r*s*cb) x fb of the filter matrix holds exactly one (channel block, filter block) pair with the whole
