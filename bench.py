@@ -352,7 +352,29 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     res["c3_dgrad_conv2d_gather_in_the_product"] = {"gemm_ms": round(ms_k, 4), "whole_data_gradient_ms": round(ms_all, 4),
                                                     "TOPS_kernel": round(flops / ms_k / 1e9, 1),
                                                     "TOPS_incl_encode": round(flops / ms_all / 1e9, 1)}
-    del ti, tf, out, wsc, img, Wd, dimg
+    del ti, tf, out, wsc
+    # ... and the data gradient of the strided convolution that would produce config 3's activations (128 x 56 x 56 x 64,
+    # 3 x 3, stride 2 -> 128 x 28 x 28 x 128): the same gradient image, no zeros stored or multiplied between its pixels,
+    # one launch that walks the four output phases (hbfp_gemm_conv2d_dgrad)
+    sconv = hbfp.Conv2d(128, 56, 56, 64, 3, 3, 1, 1, 2, 2, 0, 0)
+    Ws = Wd[:, :64].contiguous()
+    ti, tf = hbfp.alloc(row, 100352, 128, 1), hbfp.encode(Ws, 0, col)
+    out = torch.empty((128 * 56 * 56, 64), dtype=torch.float32, device="cuda")
+    wsc = torch.empty(hbfp.gemm_conv2d_dgrad_workspace(ti.desc, sconv, tf.desc), dtype=torch.uint8, device="cuda")
+
+    def strided_dgrad():
+        hbfp.encode(d2, 1, row, out=ti)
+        hbfp.encode(Ws, 0, col, out=tf)
+        hbfp.gemm_conv2d_dgrad(ti, sconv, tf, out=out, workspace=wsc)
+
+    ms_all = _time_call(torch, strided_dgrad, reps)
+    ms_k = _time_call(torch, lambda: hbfp.gemm_conv2d_dgrad(ti, sconv, tf, out=out, workspace=wsc), reps)
+    sflops = 2.0 * 100352 * 9 * 64 * 128
+    res["strided_dgrad_conv2d_gather_in_the_product"] = {
+        "gemm_ms": round(ms_k, 4), "whole_data_gradient_ms": round(ms_all, 4), "TOPS_kernel": round(sflops / ms_k / 1e9, 1),
+        "TOPS_incl_encode": round(sflops / ms_all / 1e9, 1),
+        "note": "dX 401408 x 64 (103 MB) from the 51 MB gradient tensor; 64 output channels fill half of a 128-column tile"}
+    del ti, tf, out, wsc, img, Wd, Ws, dimg
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: FP16 planes
     # relative to the rows' largest exponents, packed inside the call, on the 256 x 256-tile kernel)

@@ -255,7 +255,7 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
  * the image, the result equals hbfp_gemm_select(HBFP_KERNEL_INT8) on hbfp_encode_im2col's operand bit for bit (with
  * round to nearest; stochastic rounding draws by position in the image here, by position in the lowered matrix there).
  * The data gradient of a stride-1 convolution is the same call on the output gradient (as the image, with padding
- * r - 1 - pad) and the mirrored filter with its channel axes exchanged.
+ * r - 1 - pad) and the mirrored filter with its channel axes exchanged; hbfp_gemm_conv2d_dgrad does that for any stride.
  *   image    encoded [n*h*w][c], contraction axis 1, blocks of 32 along the channels, c a multiple of 64, <= 8 bits
  *   conv     geometry (c_block must be 0: window entries in the order (fr, fs, ch))
  *   filters  encoded filter matrix [r*s*c][filters], contraction axis 0, blocks of 32 down its rows, <= 8 bits
@@ -288,8 +288,12 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
  *            contraction axis 0, blocks of 32 down its rows, <= 8 bits
  *   dX       device FP32 [n*h*w][ldx], ldx >= c; beta 0 or 1
  *   workspace  hbfp_gemm_conv2d_dgrad_workspace bytes, 256-byte aligned
- * Cost: every tap of the dilated image is multiplied, zeros included, so the matrix cores do stride_h * stride_w times
- * the work the sum needs.
+ * Where the window is at least as large as the stride in both directions (and stride_h * stride_w <= 16) the zeros are
+ * not multiplied either: the input positions fall into stride_h * stride_w phases (iy mod stride_h, ix mod stride_w), a
+ * phase meets only every stride-th filter tap and reads dy without gaps, and one launch walks all phases, each storing
+ * to the rows of its input positions.  The taps that do contribute are accumulated in the same order both ways, so the
+ * result is bit for bit that of hbfp_gemm_conv2d on a dy whose zeros are stored.  Otherwise (a window smaller than the
+ * stride) every tap of the spread-out dy is multiplied, zeros included: stride_h * stride_w times the work the sum needs.
  * Errors: as hbfp_gemm_conv2d; HBFP_ERR_ARG also for extents from 2^21 on.
  */
 int hbfp_gemm_conv2d_dgrad_workspace(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes);

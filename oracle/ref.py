@@ -181,6 +181,41 @@ def im2col_dgrad(dy: np.ndarray, h: int, w: int, r: int, s: int, pad_h: int, pad
     return out.reshape(n * h * w, r * s * f)
 
 
+def im2col_rows(x: np.ndarray, rows, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1, stride_w: int = 1) -> np.ndarray:
+    """The rows `rows` of im2col(x, ...) (plain window order), each written out from the definition: for checks at sizes
+    where the whole lowered matrix is too large to hold."""
+    n, h, w, c = x.shape
+    ho = (h + 2 * pad_h - r) // stride_h + 1
+    wo = (w + 2 * pad_w - s) // stride_w + 1
+    out = np.zeros((len(rows), r, s, c), dtype=x.dtype)
+    for i, row in enumerate(rows):
+        img, rem = divmod(int(row), ho * wo)
+        oy, ox = divmod(rem, wo)
+        for fr in range(r):
+            for fs in range(s):
+                iy, ix = oy * stride_h - pad_h + fr, ox * stride_w - pad_w + fs
+                if 0 <= iy < h and 0 <= ix < w:
+                    out[i, fr, fs, :] = x[img, iy, ix, :]
+    return out.reshape(len(rows), r * s * c)
+
+
+def im2col_dgrad_rows(dy: np.ndarray, rows, h: int, w: int, r: int, s: int, pad_h: int, pad_w: int, stride_h: int = 1,
+                      stride_w: int = 1) -> np.ndarray:
+    """The rows `rows` of im2col_dgrad(dy, ...), each written out from the definition: entry (fr', fs') of input position
+    (iy, ix) is dy[oy, ox] for the output position with oy*stride_h - pad_h + (r - 1 - fr') = iy (same in x), if there is one."""
+    n, ho, wo, f = dy.shape
+    out = np.zeros((len(rows), r, s, f), dtype=dy.dtype)
+    for i, row in enumerate(rows):
+        img, rem = divmod(int(row), h * w)
+        iy, ix = divmod(rem, w)
+        for fr in range(r):
+            for fs in range(s):
+                ny, nx = iy + pad_h - fr, ix + pad_w - fs
+                if ny % stride_h == 0 and nx % stride_w == 0 and 0 <= ny // stride_h < ho and 0 <= nx // stride_w < wo:
+                    out[i, r - 1 - fr, s - 1 - fs, :] = dy[img, ny // stride_h, nx // stride_w, :]
+    return out.reshape(len(rows), r * s * f)
+
+
 def block_dots(mA: np.ndarray, mB: np.ndarray, kb: int) -> np.ndarray:
     """Integer block partials P[i, j, b] of Eq. (2); mA [M, K], mB [K, N]."""
     mA = np.ascontiguousarray(mA, dtype=np.int32)

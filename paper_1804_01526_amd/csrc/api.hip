@@ -600,7 +600,8 @@ int hbfp_gemm_conv2d_dgrad(const hbfp_tensor *dy, const hbfp_conv2d *conv, const
     g.C = dX;
     g.ldc = ldx;
     g.beta = beta;
-    return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w);
+    return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w,
+                               conv_dgrad_by_phase(conv->r, conv->s, conv->stride_h, conv->stride_w));
 }
 
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {

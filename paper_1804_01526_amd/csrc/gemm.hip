@@ -330,6 +330,29 @@ struct ConvA {
     float inv_dh, inv_dw;
 };
 
+// PHASE: the data gradient of a strided convolution, output phase by output phase.  The input positions
+// (yy * sh + py, xx * sw + px) of one phase (py, px) meet only the filter taps fr0 + j * sh, fs0 + i * sw, and under tap
+// (j, i) they read the stored gradient at (yy + oy0 + j, xx + ox0 + i): a stride-1 gather without any zeros in between.
+// Operand B stays the whole mirrored filter; the kernel steps through the taps of its phase in it.  blockIdx.y names the
+// phase, and a row of the phase is stored to the row of its input position.
+struct ConvPhase {
+    int32_t Hp, Wp;              // input positions of the phase
+    int32_t py, px;
+    int32_t oy0, ox0;            // may be negative
+    int32_t fr0, fs0;
+    int32_t Rp, Sp;              // taps of the phase
+    int32_t tiles_m;
+    int32_t nst;                 // stages of 64 bytes of k: Rp * Sp * stages per tap, rounded up to an even number
+};
+constexpr int kConvPhases = 16;
+struct ConvPhases {
+    ConvPhase p[kConvPhases];
+    int32_t sh, sw;              // strides of the forward convolution
+    int32_t h, w;                // input extents: where the rows of a phase are stored
+    int32_t s_full;              // filter columns of the whole filter
+    int32_t n;                   // images
+};
+
 // floor(i / d) for a coordinate i of the dilated image (may be negative), inv = 1 / d rounded
 __device__ __forceinline__ int conv_undilate(int i, float inv) { return (int)__builtin_floorf(((float)i + 0.5f) * inv); }
 
@@ -338,6 +361,7 @@ struct W8Params {
     const uint32_t *wA, *wB;     // scale words [kpad / 32][rows_pad]
     int64_t mpad, npad;
     ConvA cv;                    // CONV only
+    ConvPhases ph;               // PHASE only
 };
 
 // The same kernel multiplies 9..12-bit mantissas stored as FP16 numbers (F16): an 11-bit magnitude is an FP16
@@ -378,8 +402,10 @@ struct W8Ops<true> {
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-template <int SPB, bool CONV = false, bool F16 = false, bool DIL = false>
+// GATHER (CONV only): 0 the image as it is, 1 = DIL, 2 = PHASE
+template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
+    constexpr bool DIL = GATHER == 1, PHASE = GATHER == 2;
     typedef W8Ops<F16> ops;
     typedef typename ops::acc_t acc_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -392,14 +418,27 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 
     // 8 and more k ranges are dealt to the XCDs (few tiles, very long k); fewer ride in blockIdx.y while the tiles are
     // dealt to the XCDs as in an unsplit product
-    int tm, tn, split = blockIdx.y;
-    if (p.splits >= 8 ? !tile_and_split_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, tm, tn, split)
-                      : !tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn))
+    int tm, tn, split = PHASE ? 0 : blockIdx.y;
+    // geometry of the gather: the convolution's own, or that of this workgroup's phase (uniform)
+    int64_t M = p.M;
+    int gHo = q.cv.Ho, gWo = q.cv.Wo, gS = q.cv.S, gtaps = q.cv.ntaps;
+    int gstr_h = q.cv.str_h, gstr_w = q.cv.str_w, gpad_h = q.cv.pad_h, gpad_w = q.cv.pad_w;
+    int tiles_m = p.tiles_m, ph_nst = 0, ph_py = 0, ph_px = 0, ph_fr0 = 0, ph_fs0 = 0;
+    if (PHASE) {
+        const ConvPhase &f = q.ph.p[blockIdx.y];
+        gHo = f.Hp, gWo = f.Wp, gS = f.Sp, gtaps = f.Rp * f.Sp;
+        gstr_h = gstr_w = 1, gpad_h = -f.oy0, gpad_w = -f.ox0;
+        tiles_m = f.tiles_m, ph_nst = f.nst, ph_py = f.py, ph_px = f.px, ph_fr0 = f.fr0, ph_fs0 = f.fs0;
+        M = (int64_t)q.ph.n * f.Hp * f.Wp;
+    }
+    if (p.splits >= 8 && !PHASE ? !tile_and_split_of_workgroup(blockIdx.x, tiles_m, p.tiles_n, p.splits, tm, tn, split)
+                                : !tile_of_workgroup(blockIdx.x, tiles_m, p.tiles_n, tm, tn))
         return;                                                                  // whole workgroup, before any barrier
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
     const int st_begin = 2 * split * p.stages_per_split;                         // in 64-byte stages
     int st_end = st_begin + 2 * p.stages_per_split;
     if (st_end > 2 * p.nstage) st_end = 2 * p.nstage;
+    if (PHASE) st_end = ph_nst;
     const int nst = st_end - st_begin;
 
     // ---- copy roles.  Mantissas: wave w moves rows 16 w .. 16 w + 15 of A and of B, lane -> (row, LDS chunk).
@@ -409,7 +448,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     {
         const int r = 16 * wave + (lane >> 2);
         const int chunk = (lane & 3) ^ ((r >> 2) & 3);
-        const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
+        const int rows_a = (int)((M - row0) < BM ? (M - row0) : BM), rows_b = (int)((p.N - col0) < BN ? (p.N - col0) : BN);
         const int ra = r < rows_a ? r : rows_a - 1;   // rows past the edge re-read the last row; never stored
         const int rb = r < rows_b ? r : rows_b - 1;
         voffA = (uint32_t)ra * (uint32_t)p.kpad + chunk * 16;
@@ -422,16 +461,16 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     int64_t cpix = 0, wpix = 0;                                                  // pixel index of that corner (may lie outside)
     int cchunk = 0;
     if (CONV) {
-        const int rows_a = (int)((p.M - row0) < BM ? (p.M - row0) : BM);
+        const int rows_a = (int)((M - row0) < BM ? (M - row0) : BM);
         const int rm = 16 * wave + (lane >> 2), rw = 64 * (wave & 1) + lane;
         const int64_t pm = row0 + (rm < rows_a ? rm : rows_a - 1), pw = row0 + (rw < rows_a ? rw : rows_a - 1);
-        const int64_t per_img = (int64_t)q.cv.Ho * q.cv.Wo;
+        const int64_t per_img = (int64_t)gHo * gWo;
         const int64_t im = pm / per_img, iw = pw / per_img;
         const int remm = (int)(pm - im * per_img), remw = (int)(pw - iw * per_img);
-        cy = remm / q.cv.Wo * q.cv.str_h - q.cv.pad_h;
-        cx = remm % q.cv.Wo * q.cv.str_w - q.cv.pad_w;
-        wy = remw / q.cv.Wo * q.cv.str_h - q.cv.pad_h;
-        wx = remw % q.cv.Wo * q.cv.str_w - q.cv.pad_w;
+        cy = remm / gWo * gstr_h - gpad_h;
+        cx = remm % gWo * gstr_w - gpad_w;
+        wy = remw / gWo * gstr_h - gpad_h;
+        wx = remw % gWo * gstr_w - gpad_w;
         cchunk = ((lane & 3) ^ ((rm >> 2) & 3)) * 16;
         cpix = ((im * q.cv.H + cy) * q.cv.W + cx) * q.cv.pix_bytes + cchunk;     // byte offset of that corner's chunk in the image
         wpix = (iw * q.cv.H + wy) * q.cv.W + wx;
@@ -455,12 +494,12 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     int req_pos = 0;                                                             // SPB == 0: stage within its block
     // CONV: filter tap and 64-channel piece of the stage requested next (uniform)
     int ctap = CONV ? st_begin / q.cv.spt : 0, csub = CONV ? st_begin % q.cv.spt : 0;
-    int cfr = CONV ? ctap / q.cv.S : 0, cfs = CONV ? ctap % q.cv.S : 0;
+    int cfr = CONV ? ctap / gS : 0, cfs = CONV ? ctap % gS : 0;
 #define HBFP_COPY_NEXT(ring)                                                                            \
     {                                                                                                   \
         const uint32_t lb = (ring) * kHalfStage;                                                        \
         if (CONV) {                                                                                     \
-            const bool tap_ok = ctap < q.cv.ntaps;                                                      \
+            const bool tap_ok = ctap < gtaps;                                                           \
             const uint8_t *tapA = p.A + ((int64_t)cfr * q.cv.W + cfs) * q.cv.pix_bytes + csub * kHalfK;  /* uniform */ \
             bool in_m = tap_ok && (unsigned)(cy + cfr) < (unsigned)q.cv.H && (unsigned)(cx + cfs) < (unsigned)q.cv.W; \
             const uint8_t *srcA = tapA + cpix;                                                          \
@@ -475,9 +514,11 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         } else {                                                                                        \
             async_copy16(nextA, voffA, lb + ldsM);                                                      \
         }                                                                                               \
-        async_copy16(nextB, voffB, lb + kHalfTile + ldsM);                                              \
+        /* PHASE: where this stage's tap lies along k in the whole filter (uniform); past the last tap A reads zeros */ \
+        const int64_t kphase = PHASE && ctap < gtaps ? ((int64_t)(ph_fr0 + cfr * q.ph.sh) * q.ph.s_full + (ph_fs0 + cfs * q.ph.sw)) * (q.cv.spt * kHalfK) + csub * kHalfK : 0; \
+        async_copy16(PHASE ? tileB + kphase : nextB, voffB, lb + kHalfTile + ldsM);                     \
         if (CONV && wave_u < 4) {                                                                       \
-            const bool tap_ok = ctap < q.cv.ntaps;                                                      \
+            const bool tap_ok = ctap < gtaps;                                                           \
             const uint32_t *tapW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + ((int64_t)cfr * q.cv.W + cfs);  /* uniform */ \
             bool in_w = tap_ok && (unsigned)(wy + cfr) < (unsigned)q.cv.H && (unsigned)(wx + cfs) < (unsigned)q.cv.W; \
             const uint32_t *srcW = tapW + wpix;                                                         \
@@ -490,7 +531,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             }                                                                                           \
             async_copy4_at(in_w ? srcW : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64), lb + ldsW); \
         } else {                                                                                        \
-            async_copy4(nextW, voffW, lb + ldsW);                                                       \
+            async_copy4(PHASE ? wordsrc + (kphase / 32 + (wc >> 1)) * wordpitch : nextW, voffW, lb + ldsW); \
         }                                                                                               \
         nextA += kHalfK;                                                                                \
         nextB += kHalfK;                                                                                \
@@ -499,7 +540,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         if (CONV && ++csub == q.cv.spt) {                                                               \
             csub = 0;                                                                                   \
             ++ctap;                                                                                     \
-            if (++cfs == q.cv.S) { cfs = 0; ++cfr; }                                                    \
+            if (++cfs == gS) { cfs = 0; ++cfr; }                                                        \
         }                                                                                               \
     }
 #define HBFP_WAIT_COPIES(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
@@ -643,6 +684,35 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #undef HBFP_COPY_NEXT
 #undef HBFP_WAIT_COPIES
 
+    if (PHASE) {
+        // a row of the phase goes to the row of its input position; the 16 rows of a lane are 4 runs of 4
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int64_t i0 = row0 + wm * 32 + 8 * g + 4 * lh;
+            const uint32_t per_img = (uint32_t)(gHo * gWo);
+            uint32_t img = (uint32_t)i0 / per_img, rem = (uint32_t)i0 % per_img;
+            uint32_t yy = rem / (uint32_t)gWo, xx = rem % (uint32_t)gWo;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int v = 4 * g + u;
+                const int64_t orow = ((int64_t)img * q.ph.h + (yy * q.ph.sh + ph_py)) * q.ph.w + (xx * q.ph.sw + ph_px);
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    const int64_t j = col0 + wn * 64 + ni * 32 + l32;
+                    if (i0 + u < M && j < p.N) {
+                        const float val = acc[ni][v] * p.final_scale;
+                        if (p.beta) p.C[orow * p.ldc + j] += val;
+                        else __builtin_nontemporal_store(val, p.C + orow * p.ldc + j);
+                    }
+                }
+                if (++xx == (uint32_t)gWo) {
+                    xx = 0;
+                    if (++yy == (uint32_t)gHo) yy = 0, ++img;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
@@ -754,10 +824,17 @@ size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, i
 
 // a: M = output positions, N = filters, mantB/expB = the filter matrix, kpad = its stored k extent (r * s * c rounded up to
 // 128); mantA/expA = the encoded image [pixels][pix_bytes], expA_ld its exponent pitch.
+// Whether the data gradient of a convolution with these strides and this window runs phase by phase: every phase must
+// meet at least one filter tap in each direction.
+bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w) {
+    return (stride_h > 1 || stride_w > 1) && stride_h * stride_w <= kConvPhases && r >= stride_h && s >= stride_w;
+}
+
 // dil_h, dil_w > 1: the image stands for its zero-dilated form (c.h, c.w are the stored extents; c.pad_* and the taps
-// count in dilated positions); ho x wo is then whatever the caller wants computed.
+// count in dilated positions); ho x wo is then whatever the caller wants computed.  by_phase: the same result computed
+// output phase by output phase (conv_dgrad_by_phase must hold), without multiplying the zeros.
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
-                        hipStream_t s, int dil_h, int dil_w) {
+                        hipStream_t s, int dil_h, int dil_w, bool by_phase) {
     GemmParams p = {};
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;
@@ -830,11 +907,38 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     }
     static std::atomic<bool> configured{false}, configured_dil{false};
     if (allow_dynamic_lds(configured, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true>), kW8LdsBytes) != HBFP_OK) return HBFP_ERR_LAUNCH;
-    if (allow_dynamic_lds(configured_dil, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, true>), kW8LdsBytes) != HBFP_OK)
+    if (allow_dynamic_lds(configured_dil, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 1>), kW8LdsBytes) != HBFP_OK)
         return HBFP_ERR_LAUNCH;
+    if (by_phase) {
+        if (!conv_dgrad_by_phase(c.r, c.s, dil_h, dil_w) || c.stride_h != 1 || c.stride_w != 1) return HBFP_ERR_ARG;
+        static std::atomic<bool> configured_phase{false};
+        if (allow_dynamic_lds(configured_phase, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 2>), kW8LdsBytes) != HBFP_OK)
+            return HBFP_ERR_LAUNCH;
+        q.g.splits = 1;
+        q.ph.sh = dil_h, q.ph.sw = dil_w, q.ph.h = (int32_t)ho, q.ph.w = (int32_t)wo, q.ph.s_full = c.s, q.ph.n = (int32_t)c.n;
+        const auto mod = [](int x, int m) { return ((x % m) + m) % m; };
+        int64_t most = 0;
+        for (int py = 0; py < dil_h; ++py)
+            for (int px = 0; px < dil_w; ++px) {
+                ConvPhase &f = q.ph.p[py * dil_w + px];
+                f.py = py, f.px = px;
+                f.Hp = ho > py ? (int32_t)((ho - py + dil_h - 1) / dil_h) : 0;
+                f.Wp = wo > px ? (int32_t)((wo - px + dil_w - 1) / dil_w) : 0;
+                f.fr0 = mod(c.pad_h - py, dil_h), f.fs0 = mod(c.pad_w - px, dil_w);
+                f.Rp = (c.r - f.fr0 + dil_h - 1) / dil_h, f.Sp = (c.s - f.fs0 + dil_w - 1) / dil_w;
+                f.oy0 = (py - c.pad_h + f.fr0) / dil_h, f.ox0 = (px - c.pad_w + f.fs0) / dil_w;   // exact divisions
+                const int64_t rows = c.n * f.Hp * f.Wp;
+                f.tiles_m = (int32_t)ceil_div(rows, BM);
+                f.nst = (int32_t)(ceil_div((int64_t)f.Rp * f.Sp * q.cv.spt, 2) * 2);
+                most = f.tiles_m > most ? f.tiles_m : most;
+            }
+        hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 2>), dim3((unsigned)(ceil_div(most * tn, 8) * 8), (unsigned)(dil_h * dil_w)),
+                           dim3(kW8Threads), kW8LdsBytes, s, q);
+        return launch_status();
+    }
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
-    if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 1>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     int rc = launch_status();
     if (rc != HBFP_OK) return rc;

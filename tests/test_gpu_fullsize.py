@@ -167,6 +167,64 @@ def test_config3_conv_shapes(hb):
         del ta, tb, C, oa, ob
 
 
+def _check_gathered(name, got, low, flt_dec, nblk):
+    """Sampled rows of a convolution product against the FP64 product of the oracle's lowered rows and decoded filter:
+    relative Frobenius error, and element-wise |C - C64| <= blocks * 2^-24 * sum_k |a_k b_k| (one FP32 accumulation per
+    block of 32; a block's integer sum is no larger than the sum of its products' magnitudes)."""
+    C64 = ref.gemm(low, flt_dec)
+    err = rel_fro(got, C64)
+    terms = np.abs(low).astype(np.float64) @ np.abs(flt_dec).astype(np.float64)
+    worst = float((np.abs(got - C64) / np.maximum(terms, 1e-300)).max())
+    print(f"[{name}] rows={len(low)} rel fro {err:.2e}  worst |C-C64| / sum|a b| = {worst:.2e} (bound {nblk * 2.0 ** -24:.2e})", flush=True)
+    assert np.linalg.norm(C64) > 0
+    assert err <= TOL
+    assert (np.abs(got - C64) <= nblk * 2.0 ** -24 * terms).all()
+
+
+def test_config3_convolution_gathered_by_the_product(hb):
+    """Config 3 as the convolution it is (hbfp_gemm_conv2d, as the benchmark runs it): the image converted once, bit for bit
+    against the oracle; the product on 64 output positions (panel edges and random) against the oracle's explicitly
+    lowered rows.  Then the data gradient of the strided convolution that would produce config 3's activations
+    (128 x 56 x 56 x 64 -> 3 x 3, stride 2 -> 128 x 28 x 28 x 128; hbfp_gemm_conv2d_dgrad, phase by phase), the same way."""
+    import synth
+    X, W, dY = synth.c3_conv_as_gemm()
+    rng = np.random.default_rng(33)
+    n, h, w, c, f = 128, 28, 28, 128, 128
+    img = np.maximum(synth.normal((n, h, w, c), 3, 7), 0.0)                      # activations after a ReLU, as config 3's X
+    conv = hb.Conv2d(n, h, w, c, 3, 3, 1, 1, 1, 1, 0, 0)
+    ti = hb.encode(torch.from_numpy(img.reshape(n * h * w, c)).cuda(), 1, hb.make_format(8, 1, 32))
+    tf = hb.encode(torch.from_numpy(W).cuda(), 0, hb.make_format(8, 32, 1))
+    y = hb.gemm_conv2d(ti, conv, tf)
+    torch.cuda.synchronize()
+    oi, of = ref.encode(img.reshape(n * h * w, c), 1, 32, 8), ref.encode(W, 32, 1, 8)
+    for t, o in ((ti, oi), (tf, of)):
+        m, e = unpack(t)
+        np.testing.assert_array_equal(m, o.mant)
+        np.testing.assert_array_equal(e, o.exps)
+    rows = _rows_with_edges(n * h * w, rng)
+    low = ref.im2col_rows(ref.decode(oi).reshape(n, h, w, c), rows, 3, 3, 1, 1)
+    _check_gathered("c3 conv2d fwd", y[rows].cpu().numpy().astype(np.float64), low, ref.decode(of), 36)
+    del ti, y, oi, low
+
+    hx, wx, cx = 56, 56, 64
+    w4 = np.ascontiguousarray(W.reshape(3, 3, 128, 128)[:, :, :cx, :])          # [r, s, c, f] of the strided convolution
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4))                         # [9 * 128, 64]
+    sconv = hb.Conv2d(n, hx, wx, cx, 3, 3, 1, 1, 2, 2, 0, 0)
+    assert sconv.out_hw() == (h, w)
+    td = hb.encode(torch.from_numpy(dY).cuda(), 1, hb.make_format(8, 1, 32))
+    tw = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, 32, 1))
+    dx = hb.gemm_conv2d_dgrad(td, sconv, tw)
+    torch.cuda.synchronize()
+    od, ow = ref.encode(dY, 1, 32, 8), ref.encode(wd, 32, 1, 8)
+    for t, o in ((td, od), (tw, ow)):
+        m, e = unpack(t)
+        np.testing.assert_array_equal(m, o.mant)
+        np.testing.assert_array_equal(e, o.exps)
+    rows = _rows_with_edges(n * hx * wx, rng)
+    low = ref.im2col_dgrad_rows(ref.decode(od).reshape(n, h, w, f), rows, hx, wx, 3, 3, 1, 1, 2, 2)
+    _check_gathered("strided dgrad into 128x56x56x64", dx[rows].cpu().numpy().astype(np.float64), low, ref.decode(ow), 36)
+
+
 def test_config5_wide_range_bfp12(hb):
     """Config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding, rows spanning 2^+-20: the library's choice
     (FP16 planes relative to the rows' largest exponents on the 256 x 256-tile kernel), then the FP16 matrix instruction

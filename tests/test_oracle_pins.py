@@ -475,6 +475,22 @@ def test_data_gradient_of_a_strided_convolution_as_a_forward_product(h, w, c, f,
         np.testing.assert_array_equal(ref.im2col_dgrad(dy, h, w, r, s, pad_h, pad_w), ref.im2col(dy, r, s, r - 1 - pad_h, s - 1 - pad_w))
 
 
+def test_sampled_rows_of_the_lowered_operands_equal_the_whole_matrices():
+    """im2col_rows / im2col_dgrad_rows (used where the lowered matrix is too large) against im2col / im2col_dgrad, which the
+    tests above pin to the convolution sum and its adjoint."""
+    rng = np.random.default_rng(77)
+    for (h, w, c, f, r, s, ph, pw, sh, sw) in [(7, 8, 3, 4, 3, 3, 1, 1, 2, 2), (9, 7, 2, 3, 3, 2, 0, 1, 3, 2), (6, 6, 3, 2, 3, 3, 1, 1, 1, 1),
+                                               (5, 6, 2, 3, 2, 2, 3, 2, 2, 2)]:
+        n = 2
+        ho, wo = (h + 2 * ph - r) // sh + 1, (w + 2 * pw - s) // sw + 1
+        x = rng.standard_normal((n, h, w, c))
+        dy = rng.standard_normal((n, ho, wo, f))
+        rows = np.arange(n * ho * wo)
+        np.testing.assert_array_equal(ref.im2col_rows(x, rows, r, s, ph, pw, sh, sw), ref.im2col(x, r, s, ph, pw, sh, sw))
+        rows = rng.permutation(n * h * w)
+        np.testing.assert_array_equal(ref.im2col_dgrad_rows(dy, rows, h, w, r, s, ph, pw, sh, sw), ref.im2col_dgrad(dy, h, w, r, s, ph, pw, sh, sw)[rows])
+
+
 def test_filter_matrix_tiles_in_channel_block_order_are_the_outer_dimension_tiles():
     """Sec. 5.1 tiles the two outer dimensions of a convolution's filter.  With the window entries in channel-block order
     a tile of (r*s*cb) x fb of the filter matrix holds exactly one (channel block, filter block) pair with the whole
