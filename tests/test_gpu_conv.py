@@ -185,6 +185,46 @@ def test_conv_data_gradient_random_geometries(hb):
         _dgrad_case(hb, *geom, seed=seed)
 
 
+def test_conv_data_gradient_under_graph_replay(hb):
+    """Conversion of dY + hbfp_gemm_conv2d_dgrad (phase by phase) captured in a HIP graph and replayed on new gradients in
+    the same buffers, with eager work in between; every replay against the eager result (bit for bit) and the oracle."""
+    n, h, w, c, f, r, s, pad, st = 2, 11, 12, 48, 64, 3, 3, 1, 2
+    conv = hb.Conv2d(n, h, w, c, r, s, pad, pad, st, st, 0, 0)
+    ho, wo = conv.out_hw()
+    rng = np.random.default_rng(71)
+    w4 = (rng.standard_normal((r, s, c, f)) * 0.1).astype(np.float32)
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4))
+    flt = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, 32, 1))
+    fmt = hb.make_format(8, 1, 32)
+    dy = torch.zeros((n * ho * wo, f), device="cuda")
+    td = hb.encode(dy, 1, fmt)
+    dx = torch.empty((n * h * w, c), device="cuda")
+    ws = torch.empty(hb.gemm_conv2d_dgrad_workspace(td.desc, conv, flt.desc), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        hb.encode(dy, 1, fmt, out=td, stream=stream)
+        hb.gemm_conv2d_dgrad(td, conv, flt, out=dx, workspace=ws, stream=stream)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            hb.encode(dy, 1, fmt, out=td, stream=stream)
+            hb.gemm_conv2d_dgrad(td, conv, flt, out=dx, workspace=ws, stream=stream)
+    for i, scale in enumerate([1e-2, 3.0, 2.0 ** -100, 1e-3]):
+        g = (rng.standard_normal((n, ho, wo, f)) * scale).astype(np.float32)
+        dy.copy_(torch.from_numpy(g.reshape(n * ho * wo, f)).cuda())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dx.cpu().numpy().copy()
+        eager = hb.gemm_conv2d_dgrad(hb.encode(dy, 1, fmt), conv, flt)
+        torch.cuda.synchronize()
+        print(f"[case] dgrad graph replay {i} scale={scale}", flush=True)
+        assert np.array_equal(got, eager.cpu().numpy())
+        gq = ref.decode(ref.encode(g.reshape(n * ho * wo, f), 1, 32, 8)).reshape(n, ho, wo, f)
+        want = ref.gemm(ref.im2col_dgrad(gq, h, w, r, s, pad, pad, st, st), ref.decode(ref.encode(wd, 32, 1, 8)))
+        assert np.linalg.norm(want) > 0 and rel_fro(got, want) <= TOL
+
+
 def test_conv_data_gradient_rejects_what_it_does_not_cover(hb):
     import ctypes
     conv = hb.Conv2d(2, 8, 8, 48, 3, 3, 1, 1, 2, 2, 0, 0)                  # dy 4 x 4
