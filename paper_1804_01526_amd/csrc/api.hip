@@ -462,15 +462,16 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, table, (hipStream_t)stream);
 }
 
-// geometry and operand checks shared by hbfp_gemm_conv2d and its workspace query
+// geometry and operand checks shared by hbfp_gemm_conv2d and its workspace query.  *slot_order: -1 for the gather of 64
+// channels of one tap per stage (blocks of 32, channels a multiple of 64, window entries tap by tap), else the order of k
+// (0 tap by tap, 1 channel block by channel block) for the gather slot by slot.
 static int conv_gemm_check(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, int64_t *ho,
-                           int64_t *wo) {
+                           int64_t *wo, int *slot_order) {
     if (!image || !conv || !filters) return HBFP_ERR_ARG;
     if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
         conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
         return HBFP_ERR_ARG;
     if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
-    if (conv->c_block > 0 && conv->c_block < conv->c) return HBFP_ERR_FORMAT;          // plain window order only
     int rc = check_tensor(image, need_ptrs);
     if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
     if (rc != HBFP_OK) return rc;
@@ -482,25 +483,32 @@ static int conv_gemm_check(const hbfp_tensor *image, const hbfp_conv2d *conv, co
     if (image->contract_axis != 1 || image->src_rows != pixels || image->src_cols != conv->c) return HBFP_ERR_LAYOUT;
     if (filters->contract_axis != 0 || filters->src_rows != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
     if (image->mant_bits > 8 || filters->mant_bits > 8) return HBFP_ERR_FORMAT;
-    if (image->kblock != 32 || image->rblock != 1 || image->kshare != 1 || filters->kblock != 32 || filters->rblock != 1 ||
-        filters->kshare != 1 || (conv->c & 63))
+    // Both operands in stored blocks of 32 bytes that hold the same kblock <= 32 channels; how exponents are shared
+    // beyond that (per pixel and block, per training input, filter tiles over the whole window) is the operands' business:
+    // the product reads one exponent byte per row and stored block.
+    const bool by_block = conv->c_block > 0 && conv->c_block < conv->c;
+    if (image->kblock_pad != 32 || filters->kblock_pad != 32 || image->kblock != filters->kblock || conv->c % image->kblock ||
+        (by_block && conv->c_block != image->kblock))
         return HBFP_ERR_FORMAT;
+    *slot_order = by_block ? 1 : (image->kblock == 32 && !(conv->c & 63)) ? -1 : 0;
     return HBFP_OK;
 }
 
 int hbfp_gemm_conv2d_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes) {
     if (!bytes) return HBFP_ERR_ARG;
     int64_t ho = 0, wo = 0;
-    const int rc = conv_gemm_check(image, conv, filters, false, &ho, &wo);
+    int slot_order = -1;
+    const int rc = conv_gemm_check(image, conv, filters, false, &ho, &wo, &slot_order);
     if (rc != HBFP_OK) return rc;
-    *bytes = align256(gemm_conv_workspace(conv->n * ho * wo, filters->rows, filters->kpad, image->rows, (int)(conv->c / 32)));
+    *bytes = align256(gemm_conv_workspace(conv->n * ho * wo, filters->rows, filters->kpad, image->rows, (int)(conv->c / image->kblock)));
     return HBFP_OK;
 }
 
 int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *Y, int64_t ldy, float beta,
                      void *workspace, size_t ws_bytes, void *stream) {
     int64_t ho = 0, wo = 0;
-    int rc = conv_gemm_check(image, conv, filters, true, &ho, &wo);
+    int slot_order = -1;
+    int rc = conv_gemm_check(image, conv, filters, true, &ho, &wo, &slot_order);
     if (rc != HBFP_OK) return rc;
     if (!Y || ((uintptr_t)Y & 3) || ldy < filters->rows || (beta != 0.0f && beta != 1.0f)) return HBFP_ERR_ARG;
     size_t need = 0;
@@ -519,13 +527,13 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
     g.kpad = filters->kpad;
     g.nblk = filters->nblk;
     g.kbp = 32;
-    g.kblock = 32;
+    g.kblock = image->kblock;
     g.mA = image->mant_bits;
     g.mB = filters->mant_bits;
     g.C = Y;
     g.ldc = ldy;
     g.beta = beta;
-    return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream);
+    return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream, 1, 1, false, slot_order, (int)image->kblock);
 }
 
 // The data gradient of a convolution of any stride: a stride-1 convolution of the zero-dilated output gradient with

@@ -921,9 +921,56 @@ __global__ __launch_bounds__(kThreads) void tile_amax_wide_kernel(const TilePara
     }
 }
 
+// The same pass once more for blocks that span all columns of a narrow matrix whose rows lie back to back in memory
+// (ld = columns; an image tensor seen as [pixels][channels] with one exponent per image, say): a block row is one
+// contiguous run of br * columns values.  The kernels above give a lane 4 columns and walk down the rows, which leaves
+// most lanes without a column and one load in flight per lane here; this one reduces the run flat, 8 vector loads per
+// lane in flight, one atomic per workgroup.  gridDim.x workgroups share a block row, gridDim.y strides over the block rows.
+constexpr int kFlatLoads = 8;
+
+__global__ __launch_bounds__(kThreads) void tile_amax_flat_kernel(const TileParams p) {
+    __shared__ uint32_t wave_max[kThreads / 64];
+    const int64_t per_tile = p.br * p.src_cols, total = p.src_rows * p.src_cols;
+    for (int64_t tr = blockIdx.y; tr < p.nbr; tr += gridDim.y) {
+        const int64_t begin = tr * per_tile, end = begin + per_tile < total ? begin + per_tile : total;
+        uint32_t a = 0;
+        for (int64_t base = begin + ((int64_t)blockIdx.x * kFlatLoads * kThreads + threadIdx.x) * 4; base < end;
+             base += (int64_t)gridDim.x * kFlatLoads * kThreads * 4) {
+            float4 d[kFlatLoads];
+#pragma unroll
+            for (int u = 0; u < kFlatLoads; ++u) {
+                const int64_t i = base + (int64_t)u * kThreads * 4;               // runs are multiples of 4 values long
+                d[u] = i < end ? *reinterpret_cast<const float4 *>(p.src + i) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int u = 0; u < kFlatLoads; ++u)
+                a = max(a, max(max(__float_as_uint(d[u].x) & 0x7fffffffu, __float_as_uint(d[u].y) & 0x7fffffffu),
+                               max(__float_as_uint(d[u].z) & 0x7fffffffu, __float_as_uint(d[u].w) & 0x7fffffffu)));
+        }
+        a = group_max<16>(a);
+        a = max(a, (uint32_t)__shfl_xor((int)a, 16));
+        a = max(a, (uint32_t)__shfl_xor((int)a, 32));
+        __syncthreads();                                       // the previous block row's maxima have been read
+        if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = a;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t v = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+            if (v) atomicMax(p.tile_amax + tr, v);
+        }
+    }
+}
+
 // launches the maximum pass (the table has been cleared)
 int launch_tile_amax(const TileParams &p, hipStream_t s) {
     const int vec_ok = (((uintptr_t)p.src & 15) == 0 && (p.ld % 4) == 0) ? 1 : 0;
+    if (p.nbc == 1 && vec_ok && p.ld == p.src_cols && p.src_cols < kThreads * 4 && p.br >= 8) {
+        const int64_t per_wg = (int64_t)kFlatLoads * kThreads * 4;
+        int64_t gx = ceil_div(p.br * p.src_cols, per_wg);
+        gx = gx > 64 ? 64 : gx;
+        const int64_t gy = p.nbr > 65535 ? 65535 : p.nbr;
+        hipLaunchKernelGGL(tile_amax_flat_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kThreads), 0, s, p);
+        return HBFP_OK;
+    }
     const int strip = amax_strip_rows(p.br);
     int64_t gy = ceil_div(p.src_rows, strip);
     gy = gy > 65535 ? 65535 : gy;

@@ -328,8 +328,14 @@ struct ConvA {
     int32_t pix_bytes;           // bytes between pixels of the encoded image
     int32_t dil_h, dil_w;        // DIL only
     float inv_dh, inv_dw;
+    int32_t ncb, R, cb_order, nslots;   // SLOT only: stored blocks per pixel, filter rows, order of k, r * s * ncb
 };
 
+// SLOT: the general gather.  The image is stored in blocks of at most 32 channels, each padded to 32 bytes (a slot), so
+// any channel count that is a multiple of the block length works, and k runs over slots either tap by tap
+// (k = (tap, channel block, channel): cb_order 0) or channel block by channel block (k = (channel block, tap, channel):
+// cb_order 1, the order in which a filter tile spans the whole window, Sec. 5.1).  A stage of 64 bytes is two consecutive
+// slots, in general of two different pixels: the lanes that copy its upper half take the second slot's tap and block.
 // PHASE: the data gradient of a strided convolution, output phase by output phase.  The input positions
 // (yy * sh + py, xx * sw + px) of one phase (py, px) meet only the filter taps fr0 + j * sh, fs0 + i * sw, and under tap
 // (j, i) they read the stored gradient at (yy + oy0 + j, xx + ox0 + i): a stride-1 gather without any zeros in between.
@@ -402,10 +408,10 @@ struct W8Ops<true> {
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-// GATHER (CONV only): 0 the image as it is, 1 = DIL, 2 = PHASE
+// GATHER (CONV only): 0 the image as it is (64 channels of one tap per stage), 1 = DIL, 2 = PHASE, 3 = SLOT
 template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
-    constexpr bool DIL = GATHER == 1, PHASE = GATHER == 2;
+    constexpr bool DIL = GATHER == 1, PHASE = GATHER == 2, SLOT = GATHER == 3;
     typedef W8Ops<F16> ops;
     typedef typename ops::acc_t acc_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -478,6 +484,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             cpix = im * q.cv.H * q.cv.W * q.cv.pix_bytes + cchunk;
             wpix = iw * q.cv.H * q.cv.W;
         }
+        if (SLOT) cpix -= cchunk & 32;                                           // the half of the stage selects the slot, not an offset
     }
     const uint8_t *tileA = p.A + row0 * p.kpad, *tileB = p.B + col0 * p.kpad;   // uniform
     const int wc = wave_u & 3;                                                   // word copy: block wc >> 1, rows 64 (wc & 1) ..
@@ -495,10 +502,36 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     // CONV: filter tap and 64-channel piece of the stage requested next (uniform)
     int ctap = CONV ? st_begin / q.cv.spt : 0, csub = CONV ? st_begin % q.cv.spt : 0;
     int cfr = CONV ? ctap / gS : 0, cfs = CONV ? ctap % gS : 0;
+    // SLOT: filter row, filter column and channel block of the first slot of the stage requested next, and its number
+    int sidx = 2 * st_begin, scb = 0;
+    if (SLOT) {
+        const int tap = q.cv.cb_order ? sidx % q.cv.ntaps : sidx / q.cv.ncb;
+        scb = q.cv.cb_order ? sidx / q.cv.ntaps : sidx % q.cv.ncb;
+        cfr = tap / gS, cfs = tap % gS;
+    }
+    // the slot after (fr, fs, cb) in the order of k
+#define HBFP_NEXT_SLOT(fr, fs, cb)                                                                      \
+    {                                                                                                   \
+        if (q.cv.cb_order) {                                                                            \
+            if (++fs == gS) { fs = 0; if (++fr == q.cv.R) { fr = 0; ++cb; } }                           \
+        } else if (++cb == q.cv.ncb) {                                                                  \
+            cb = 0;                                                                                     \
+            if (++fs == gS) { fs = 0; ++fr; }                                                           \
+        }                                                                                               \
+    }
 #define HBFP_COPY_NEXT(ring)                                                                            \
     {                                                                                                   \
         const uint32_t lb = (ring) * kHalfStage;                                                        \
-        if (CONV) {                                                                                     \
+        int fr1 = cfr, fs1 = cfs, cb1 = scb;                /* SLOT: the second slot of the stage (uniform) */ \
+        if (SLOT) HBFP_NEXT_SLOT(fr1, fs1, cb1);                                                        \
+        if (SLOT) {                                                                                     \
+            const bool upper = (cchunk & 32) != 0;                                                      \
+            const int fr = upper ? fr1 : cfr, fs = upper ? fs1 : cfs, cb = upper ? cb1 : scb;           \
+            const bool in_m = sidx + (upper ? 1 : 0) < q.cv.nslots && (unsigned)(cy + fr) < (unsigned)q.cv.H && \
+                              (unsigned)(cx + fs) < (unsigned)q.cv.W;                                   \
+            const uint8_t *srcA = p.A + cpix + (int64_t)(fr * q.cv.W + fs) * q.cv.pix_bytes + cb * 32;  \
+            async_copy16_at(in_m ? srcA : q.cv.zeros, lb + ldsM);                                       \
+        } else if (CONV) {                                                                              \
             const bool tap_ok = ctap < gtaps;                                                           \
             const uint8_t *tapA = p.A + ((int64_t)cfr * q.cv.W + cfs) * q.cv.pix_bytes + csub * kHalfK;  /* uniform */ \
             bool in_m = tap_ok && (unsigned)(cy + cfr) < (unsigned)q.cv.H && (unsigned)(cx + cfs) < (unsigned)q.cv.W; \
@@ -517,7 +550,14 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         /* PHASE: where this stage's tap lies along k in the whole filter (uniform); past the last tap A reads zeros */ \
         const int64_t kphase = PHASE && ctap < gtaps ? ((int64_t)(ph_fr0 + cfr * q.ph.sh) * q.ph.s_full + (ph_fs0 + cfs * q.ph.sw)) * (q.cv.spt * kHalfK) + csub * kHalfK : 0; \
         async_copy16(PHASE ? tileB + kphase : nextB, voffB, lb + kHalfTile + ldsM);                     \
-        if (CONV && wave_u < 4) {                                                                       \
+        if (SLOT && wave_u < 4) {                           /* the wave's slot of the stage: uniform */ \
+            const bool upper = (wc >> 1) != 0;                                                          \
+            const int fr = upper ? fr1 : cfr, fs = upper ? fs1 : cfs, cb = upper ? cb1 : scb;           \
+            const bool in_w = sidx + (upper ? 1 : 0) < q.cv.nslots && (unsigned)(wy + fr) < (unsigned)q.cv.H && \
+                              (unsigned)(wx + fs) < (unsigned)q.cv.W;                                   \
+            const uint32_t *srcW = q.cv.words + (int64_t)cb * q.cv.word_pitch + (wpix + (fr * q.cv.W + fs)); \
+            async_copy4_at(in_w ? srcW : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64), lb + ldsW); \
+        } else if (CONV && wave_u < 4) {                                                                \
             const bool tap_ok = ctap < gtaps;                                                           \
             const uint32_t *tapW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + ((int64_t)cfr * q.cv.W + cfs);  /* uniform */ \
             bool in_w = tap_ok && (unsigned)(wy + cfr) < (unsigned)q.cv.H && (unsigned)(wx + cfs) < (unsigned)q.cv.W; \
@@ -537,7 +577,11 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         nextB += kHalfK;                                                                                \
         if (SPB != 0) nextW += stepW;                                                                   \
         else if (++req_pos == spb64) { req_pos = 0; nextW += stepW; }                                   \
-        if (CONV && ++csub == q.cv.spt) {                                                               \
+        if (SLOT) {                                                                                     \
+            cfr = fr1, cfs = fs1, scb = cb1;                                                            \
+            HBFP_NEXT_SLOT(cfr, cfs, scb);                                                              \
+            sidx += 2;                                                                                  \
+        } else if (CONV && ++csub == q.cv.spt) {                                                        \
             csub = 0;                                                                                   \
             ++ctap;                                                                                     \
             if (++cfs == gS) { cfs = 0; ++cfr; }                                                        \
@@ -682,6 +726,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
 #undef HBFP_COPY_NEXT
+#undef HBFP_NEXT_SLOT
 #undef HBFP_WAIT_COPIES
 
     if (PHASE) {
@@ -832,9 +877,11 @@ bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w) {
 
 // dil_h, dil_w > 1: the image stands for its zero-dilated form (c.h, c.w are the stored extents; c.pad_* and the taps
 // count in dilated positions); ho x wo is then whatever the caller wants computed.  by_phase: the same result computed
-// output phase by output phase (conv_dgrad_by_phase must hold), without multiplying the zeros.
+// output phase by output phase (conv_dgrad_by_phase must hold), without multiplying the zeros.  slot_order >= 0: the
+// general gather from an image stored in blocks of kblock channels (c.c a multiple of it), k tap by tap (0) or channel
+// block by channel block (1).
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
-                        hipStream_t s, int dil_h, int dil_w, bool by_phase) {
+                        hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock) {
     GemmParams p = {};
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;
@@ -861,7 +908,9 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     p.splits = (int32_t)ceil_div(p.nstage, p.stages_per_split);
     p.partial = (float *)workspace;
     const int64_t pixels = c.n * c.h * c.w;
-    const int cblocks = (int)(c.c / 32);
+    const bool slots = slot_order >= 0;
+    if (slots && (kblock < 1 || kblock > 32 || c.c % kblock || dil_h != 1 || dil_w != 1 || by_phase)) return HBFP_ERR_ARG;
+    const int cblocks = (int)(slots ? c.c / kblock : c.c / 32);
     W8Params q = {};
     q.g = p;
     q.mpad = ceil_div(a.M, 128) * 128;
@@ -882,7 +931,11 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     q.cv.Wo = (int32_t)wo;
     q.cv.S = c.s;
     q.cv.ntaps = c.r * c.s;
-    q.cv.spt = (int32_t)(c.c / 64);
+    q.cv.spt = slots ? 1 : (int32_t)(c.c / 64);
+    q.cv.ncb = cblocks;
+    q.cv.R = c.r;
+    q.cv.cb_order = slot_order > 0;
+    q.cv.nslots = c.r * c.s * cblocks;
     q.cv.pad_h = c.pad_h;
     q.cv.pad_w = c.pad_w;
     q.cv.str_h = c.stride_h;
@@ -938,7 +991,12 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     }
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
-    if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 1>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    if (slots) {
+        static std::atomic<bool> configured_slot{false};
+        if (allow_dynamic_lds(configured_slot, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 3>), kW8LdsBytes) != HBFP_OK)
+            return HBFP_ERR_LAUNCH;
+        hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 3>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    } else if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 1>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     int rc = launch_status();
     if (rc != HBFP_OK) return rc;

@@ -113,6 +113,93 @@ def test_conv_data_gradient_of_a_stride_one_convolution(hb):
     assert rel_fro(dx.cpu().numpy(), want.reshape(n * h * w, c)) <= TOL
 
 
+def _slot_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, kb, by_block, per_image, tiles, seed, beta=0.0):
+    """The general gather: channels in blocks of kb (stored padded to 32), window entries tap by tap or channel block by
+    channel block (by_block), the image with one exponent per pixel and block or one per training input (per_image), the
+    filter with one exponent per column and block or in tiles (tiles: kb x kb tap by tap, the whole window x kb channels
+    x 24 filters by block - the tiling of the two outer filter dimensions of Sec. 5.1)."""
+    rng = np.random.default_rng(seed)
+    x = (np.maximum(rng.standard_normal((n, h, w, c)), -0.5) * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
+    w4 = (rng.standard_normal((r, s, c, f)) * np.exp2(rng.integers(-4, 5, size=(1, 1, c, 1))) * 0.1).astype(np.float32)
+    cb = kb if by_block else 0
+    wmat = np.ascontiguousarray(ref.filter_matrix(w4, cb))
+    conv = hb.Conv2d(n, h, w, c, r, s, pad_h, pad_w, sh, sw, cb, 0)
+    ho, wo = conv.out_hw()
+    print(f"[slots] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad=({pad_h},{pad_w}) stride=({sh},{sw}) blocks of {kb} "
+          f"{'by block' if by_block else 'by tap'} {'per image' if per_image else 'per pixel'} {'tiles' if tiles else 'columns'}", flush=True)
+    x2 = x.reshape(n * h * w, c)
+    if per_image:
+        img = hb.encode(torch.from_numpy(x2).cuda(), 1, hb.make_format(8, h * w, 0, k_slot=kb))
+        xq = ref.decode(ref.encode(x.reshape(n, -1), 1, 0, 8)).reshape(n, h, w, c)
+        low_fmt = hb.make_format(8, ho * wo, 0, k_slot=kb)
+    else:
+        img = hb.encode(torch.from_numpy(x2).cuda(), 1, hb.make_format(8, 1, kb))
+        xq = ref.decode(ref.encode(x2, 1, kb, 8)).reshape(n, h, w, c)
+        low_fmt = hb.make_format(8, 1, kb)
+    if tiles and by_block:
+        flt = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, r * s * kb, 24, k_slot=kb))
+        wq = ref.decode(ref.encode(wmat, r * s * kb, 24, 8))
+    elif tiles:
+        flt = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, kb, kb))
+        wq = ref.decode(ref.encode(wmat, kb, kb, 8))
+    else:
+        flt = hb.encode(torch.from_numpy(wmat).cuda(), 0, hb.make_format(8, kb, 1))
+        wq = ref.decode(ref.encode(wmat, kb, 1, 8))
+    y0 = None
+    if beta:
+        y0 = rng.standard_normal((n * ho * wo, f)).astype(np.float32)
+        y = hb.gemm_conv2d(img, conv, flt, out=torch.from_numpy(y0).cuda(), beta=1.0)
+    else:
+        y = hb.gemm_conv2d(img, conv, flt)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    want = ref.gemm(ref.im2col(xq, r, s, pad_h, pad_w, sh, sw, cb), wq)
+    if y0 is not None:
+        want = want + y0.astype(np.float64)
+    err = rel_fro(y, want)
+    print(f"        rel fro err = {err:.3e}", flush=True)
+    assert np.linalg.norm(want) > 0 and err <= TOL
+    if not beta:
+        ta = hb.encode_im2col(torch.from_numpy(x).cuda(), conv, low_fmt)
+        yl = hb.gemm(ta, flt, kernel=hb.KERNEL_INT8)
+        torch.cuda.synchronize()
+        assert np.array_equal(y, yl.cpu().numpy()), "differs from the product on the lowered operand"
+
+
+@pytest.mark.parametrize("geom", [
+    # n, h, w, c, f, r, s, pad_h, pad_w, stride_h, stride_w, block, by block, per image, filter tiles
+    (3, 9, 9, 48, 50, 3, 3, 1, 1, 1, 1, 24, True, True, True),          # the format of Sec. 5.1 in full
+    (2, 10, 8, 72, 30, 3, 3, 1, 1, 1, 1, 24, True, True, True),         # 27 slots: an odd number, the last stage half empty
+    (2, 10, 8, 72, 30, 3, 3, 1, 1, 2, 2, 24, True, False, False),
+    (2, 9, 11, 48, 70, 3, 3, 1, 1, 1, 1, 24, False, True, True),        # tap by tap, 24 x 24 filter tiles
+    (2, 9, 11, 96, 40, 3, 3, 1, 1, 1, 1, 32, False, False, False),      # blocks of 32 but 96 channels: three slots per tap
+    (2, 8, 8, 32, 20, 5, 3, 2, 1, 1, 1, 32, False, False, False),       # one slot per tap
+    (2, 8, 8, 32, 20, 3, 3, 1, 1, 1, 1, 16, True, False, False),        # blocks of 16
+    (3, 7, 9, 24, 24, 1, 1, 0, 0, 1, 1, 8, False, False, False),        # blocks of 8, a 1 x 1 convolution
+    (2, 12, 12, 24, 40, 2, 2, 0, 0, 2, 2, 24, True, True, True),        # a single channel block
+    (1, 6, 6, 960, 100, 3, 3, 1, 1, 1, 1, 24, True, True, True),        # few tiles, 360 slots: split along k
+])
+def test_conv_general_gather(hb, geom):
+    _slot_case(hb, *geom, seed=sum(int(g) for g in geom))
+
+
+def test_conv_general_gather_accumulates(hb):
+    _slot_case(hb, 3, 9, 9, 48, 50, 3, 3, 1, 1, 1, 1, 24, True, True, True, seed=3, beta=1.0)
+    _slot_case(hb, 1, 6, 6, 960, 100, 3, 3, 1, 1, 1, 1, 24, True, True, True, seed=4, beta=1.0)
+
+
+def test_conv_general_gather_random(hb):
+    for seed in random_cases(12):
+        rng = np.random.default_rng(9700 + seed)
+        r, s = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        h, w = int(rng.integers(r, 13)), int(rng.integers(s, 13))
+        kb = int(rng.choice([8, 16, 24, 32]))
+        geom = (int(rng.integers(1, 4)), h, w, kb * int(rng.integers(1, 6)), int(rng.integers(1, 150)), r, s,
+                int(rng.integers(0, r)), int(rng.integers(0, s)), int(rng.integers(1, 3)), int(rng.integers(1, 3)),
+                kb, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)))
+        _slot_case(hb, *geom, seed=seed)
+
+
 def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
     """hbfp_gemm_conv2d_dgrad against the oracle (dY converted, spread out and lowered explicitly, FP64 product with the
     converted mirrored filter) and, bit for bit, against hbfp_gemm_conv2d on a dY whose zeros are really stored."""
@@ -260,10 +347,12 @@ def test_conv_rejects_what_it_does_not_cover(hb):
     assert call(img, conv, flt) == hb.OK
     assert call(img, conv, flt, ldy=8) == hb.ERR_ARG
     assert call(img, conv, flt, beta=0.5) == hb.ERR_ARG
-    assert call(img, hb.Conv2d(2, 8, 8, 64, 3, 3, 1, 1, 1, 1, 32, 0), flt) == hb.ERR_FORMAT            # channel-block order
+    assert call(img, hb.Conv2d(2, 8, 8, 64, 3, 3, 1, 1, 1, 1, 16, 0), flt) == hb.ERR_FORMAT            # channel blocks that are not the stored blocks
     assert call(img, hb.Conv2d(2, 8, 9, 64, 3, 3, 1, 1, 1, 1, 0, 0), flt) == hb.ERR_LAYOUT             # not this image
     img24 = hb.encode(x, 1, hb.make_format(8, 1, 24))
-    assert call(img24, conv, flt) == hb.ERR_FORMAT                                                       # blocks of 24
+    assert call(img24, conv, flt) == hb.ERR_FORMAT                                                       # blocks of 24: 64 channels are no multiple, and the filter has 32
+    img16 = hb.encode(x, 1, hb.make_format(8, 1, 16))
+    assert call(img16, conv, flt) == hb.ERR_FORMAT                                                       # blocks of 16 against a filter in blocks of 32
     flt5 = hb.encode(torch.zeros((25 * 64, 16), device="cuda"), 0, hb.make_format(8, 32, 1))
     assert call(img, conv, flt5) == hb.ERR_LAYOUT
     assert hb._lib.hbfp_gemm_conv2d(ctypes.byref(img.desc), ctypes.byref(conv), ctypes.byref(flt.desc), y.data_ptr(), 16, 0.0,
