@@ -307,6 +307,31 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
         "gemm_ms": round(ms_k, 4), "encode_im2col_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
         "TOPS_kernel": round(flops / ms_k / 1e9, 1), "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1)}
     del ta, tb, out, ws, wse
+    # ... the same format in full (filter exponents shared by 24 channels x 24 filters x the whole window: window entries
+    # channel block by channel block) without any lowered operand: the image, its channels padded with zeros to 144 = 6 x 24,
+    # converted once with one exponent per training input, gathered slot by slot by the product (hbfp_gemm_conv2d)
+    img144 = torch.zeros((128, 28, 28, 144), device="cuda")
+    img144[..., :128] = img
+    W144 = torch.zeros((6, 9, 24, 128), device="cuda")                        # [channel block][tap][channel][filter]
+    W144.view(6, 9, 24, 128)[:5] = W.view(9, 128, 128)[:, :120].reshape(9, 5, 24, 128).permute(1, 0, 2, 3)
+    W144[5, :, :8] = W.view(9, 128, 128)[:, 120:]
+    W144 = W144.view(9 * 144, 128)
+    conv144 = hbfp.Conv2d(128, 28, 28, 144, 3, 3, 1, 1, 1, 1, 24, 0)
+    per_image, outer = hbfp.make_format(8, 28 * 28, 0, k_slot=24), hbfp.make_format(8, 9 * 24, 24, k_slot=24)
+    x144 = img144.view(-1, 144)
+    ti, tf = hbfp.alloc(per_image, 100352, 144, 1), hbfp.encode(W144, 0, outer)
+    out = torch.empty((100352, 128), dtype=torch.float32, device="cuda")
+    wsc = torch.empty(hbfp.gemm_conv2d_workspace(ti.desc, conv144, tf.desc), dtype=torch.uint8, device="cuda")
+    wse = torch.empty(max(hbfp.encode_workspace(ti.desc), 256), dtype=torch.uint8, device="cuda")
+    hbfp.encode(x144, 1, per_image, out=ti, workspace=wse)
+    ms_k = _time_call(torch, lambda: hbfp.gemm_conv2d(ti, conv144, tf, out=out, workspace=wsc), reps)
+    ms_ea = _time_call(torch, lambda: hbfp.encode(x144, 1, per_image, out=ti, workspace=wse), reps)
+    ms_eb = _time_call(torch, lambda: hbfp.encode(W144, 0, outer, out=tf), reps)
+    res["c3_fwd_conv2d_gather_exponent_per_input_x_outer_dimension_tiles"] = {
+        "gemm_ms": round(ms_k, 4), "encode_image_ms": round(ms_ea, 4), "encode_b_ms": round(ms_eb, 4),
+        "TOPS_kernel": round(flops / ms_k / 1e9, 1), "TOPS_incl_encode": round(flops / (ms_k + ms_ea + ms_eb) / 1e9, 1),
+        "note": "54 slots of 24 channels (stored as 32) instead of 36 blocks of 32; no 154 MB lowered operand"}
+    del img144, W144, x144, ti, tf, out, wsc, wse
     # ... and its weight gradient dW [1152, 128] = lowered(X)^T dY with the lowered operand gathered the same way
     ta, tb = hbfp.alloc(col, 100352, 1152, 0), hbfp.encode(dY, 0, col)
     out = torch.empty((ta.desc.rows, tb.desc.rows), dtype=torch.float32, device="cuda")

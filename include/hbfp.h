@@ -245,24 +245,34 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
 
 /*
  * hbfp_gemm_conv2d: a convolution executed as a BFP matrix product (Sec. 5.1) whose activation operand is never
- * lowered at all: the image is converted ONCE, as the matrix [n*h*w pixels][c channels] with blocks of 32 channels
+ * lowered at all: the image is converted ONCE, as the matrix [n*h*w pixels][c channels] with blocks along the channels
  * (hbfp_encode, contraction axis 1), and the product kernel gathers every filter tap from it while it stages its
- * operand (one address per operand row and 64 channels; taps outside the image read zeros).
+ * operand (one address per operand row and stage; taps outside the image read zeros).
  *     Y[(img, oy, ox)][f] = beta * Y + sum over (fr, fs, ch) of x[img][oy*stride_h - pad_h + fr][ox*stride_w - pad_w + fs][ch]
  *                                                             * w[(fr * s + fs) * c + ch][f]
- * with both factors as their BFP values and the sum taken as Eq. (2) takes it (integer sums over 32 channels of one
- * tap, scaled by the two block exponents, accumulated in FP32).  Because a block of the lowered matrix is a block of
+ * with both factors as their BFP values and the sum taken as Eq. (2) takes it (integer sums over the channels of one
+ * stored block of one tap, scaled by the two block exponents, accumulated in FP32).  Because a block of the lowered matrix is a block of
  * the image, the result equals hbfp_gemm_select(HBFP_KERNEL_INT8) on hbfp_encode_im2col's operand bit for bit (with
  * round to nearest; stochastic rounding draws by position in the image here, by position in the lowered matrix there).
  * The data gradient of a stride-1 convolution is the same call on the output gradient (as the image, with padding
  * r - 1 - pad) and the mirrored filter with its channel axes exchanged; hbfp_gemm_conv2d_dgrad does that for any stride.
- *   image    encoded [n*h*w][c], contraction axis 1, blocks of 32 along the channels, c a multiple of 64, <= 8 bits
- *   conv     geometry (c_block must be 0: window entries in the order (fr, fs, ch))
- *   filters  encoded filter matrix [r*s*c][filters], contraction axis 0, blocks of 32 down its rows, <= 8 bits
+ *   image    encoded [n*h*w][c], contraction axis 1, stored blocks of B <= 32 channels (block_cols = B, or k_slot = B
+ *            with exponents shared more widely: block_rows = h*w and block_cols = 0 is one exponent per training input,
+ *            Sec. 5.1), c a multiple of B, <= 8 bits
+ *   conv     geometry; c_block 0: window entries in the order (fr, fs, ch); c_block = B: channel block by channel
+ *            block (see hbfp_conv2d), the order in which a filter tile of (r*s*B) x (filter block) with k_slot = B
+ *            shares one exponent over B channels, a block of filters and the whole window (Sec. 5.1)
+ *   filters  encoded filter matrix [r*s*c][filters] in the same order, contraction axis 0, stored blocks of B down its
+ *            rows (block_rows = B or k_slot = B; any sharing of exponents), <= 8 bits
  *   Y        device FP32 [n*ho*wo][ldy], ldy >= filters; beta 0 or 1
  *   workspace  hbfp_gemm_conv2d_workspace bytes (scale words of both operands, split-k slices), 256-byte aligned
- * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (operands do not match the geometry), HBFP_ERR_FORMAT (other block shapes,
- * mantissas wider than 8 bits, c not a multiple of 64, c_block set), HBFP_ERR_WORKSPACE, HBFP_ERR_LAUNCH.
+ * With B = 32, c a multiple of 64 and c_block = 0 a stage of the product is 64 channels of one tap; otherwise it is two
+ * consecutive stored blocks, in general of two different pixels (5 % slower at equal sizes).  Blocks shorter than 32 are
+ * stored as 32 and cost as much.  A channel count that is no multiple of B is handled by the caller: zero channels
+ * appended to the image tensor and zero rows to the filter change neither exponents nor sums.
+ * Errors: HBFP_ERR_ARG, HBFP_ERR_LAYOUT (operands do not match the geometry), HBFP_ERR_FORMAT (stored blocks longer
+ * than 32 or different in the two operands, c no multiple of them, c_block neither 0 nor the block length, mantissas
+ * wider than 8 bits), HBFP_ERR_WORKSPACE, HBFP_ERR_LAUNCH.
  */
 int hbfp_gemm_conv2d_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes);
 int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *Y, int64_t ldy, float beta,
