@@ -221,8 +221,8 @@ int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream);
  * largest value of the whole image x[img] (also of
  * pixels no window reaches when the stride exceeds the filter), each value is converted as if the image had been
  * converted once and lowered afterwards (stochastic rounding draws by the index in x, so a pixel gets the same
- * mantissa in every window), and `workspace` must hold hbfp_encode_workspace(out) bytes (4 per image; HBFP_ERR_WORKSPACE);
- * the other formats need no workspace (NULL, 0).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
+ * mantissa in every window), and `workspace` must hold hbfp_encode_im2col_workspace bytes (4 per image, rounded up to 256;
+ * HBFP_ERR_WORKSPACE); the other formats need no workspace (NULL, 0).  Errors as hbfp_encode; HBFP_ERR_LAYOUT if the descriptor's shape is not the
  * convolution's.
  */
 typedef struct hbfp_conv2d {
@@ -240,6 +240,7 @@ typedef struct hbfp_conv2d {
                           of Sec. 5.1. */
     int32_t reserved;
 } hbfp_conv2d;
+int hbfp_encode_im2col_workspace(const hbfp_conv2d *conv, const hbfp_tensor *plan, size_t *bytes);   /* host only */
 int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
                        void *stream);
 

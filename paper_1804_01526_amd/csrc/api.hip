@@ -432,26 +432,46 @@ int hbfp_encode_packed_batch(int njobs, const hbfp_encode_job *jobs, void *works
     return HBFP_OK;
 }
 
-int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
-                       void *stream) {
-    if (!x || !conv || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
+// geometry and plan checks shared by hbfp_encode_im2col and its workspace query
+static int im2col_check(const hbfp_conv2d *conv, const hbfp_tensor *out, bool need_ptrs, int64_t *ho, int64_t *wo, bool *per_image) {
+    if (!conv) return HBFP_ERR_ARG;
     if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
         conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
         return HBFP_ERR_ARG;
     if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
-    int rc = check_tensor(out, true);
+    int rc = check_tensor(out, need_ptrs);
     if (rc != HBFP_OK) return rc;
-    const int64_t ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
-    const int64_t wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
-    if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || ho * wo > 0x7fffffff) return HBFP_ERR_ARG;
-    if (out->src_rows != conv->n * ho * wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
+    *ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
+    *wo = (conv->w + 2 * conv->pad_w - conv->s) / conv->stride_w + 1;
+    if (conv->h > 0x7fffffff || conv->w > 0x7fffffff || conv->c > 0x7fffffff || *ho * *wo > 0x7fffffff) return HBFP_ERR_ARG;
+    if (out->src_rows != conv->n * *ho * *wo || out->src_cols != (int64_t)conv->r * conv->s * conv->c) return HBFP_ERR_LAYOUT;
     if (out->src_rows > 0x7fffffff || out->src_cols > 0x7fffffff) return HBFP_ERR_ARG;
     // one exponent per training input (Sec. 5.1): the rows of one image and the whole window share it
-    const bool per_image = out->contract_axis == 1 && out->rblock == ho * wo && out->rblock > 1 && out->kshare >= out->nblk;
-    if (!per_image && (out->rblock != 1 || out->kshare != 1)) return HBFP_ERR_FORMAT;
+    *per_image = out->contract_axis == 1 && out->rblock == *ho * *wo && out->rblock > 1 && out->kshare >= out->nblk;
+    if (!*per_image && (out->rblock != 1 || out->kshare != 1)) return HBFP_ERR_FORMAT;
     if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7) || (conv->c_block & 7)) : out->kblock > 64)
         return HBFP_ERR_FORMAT;
     if ((int64_t)conv->r * conv->s * (conv->c_block > 0 && conv->c_block < conv->c ? conv->c_block : conv->c) > 0x7fffffff) return HBFP_ERR_ARG;
+    return HBFP_OK;
+}
+
+int hbfp_encode_im2col_workspace(const hbfp_conv2d *conv, const hbfp_tensor *plan, size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    int64_t ho = 0, wo = 0;
+    bool per_image = false;
+    const int rc = im2col_check(conv, plan, false, &ho, &wo, &per_image);
+    if (rc != HBFP_OK) return rc;
+    *bytes = per_image ? align256((size_t)conv->n * 4) : 0;
+    return HBFP_OK;
+}
+
+int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tensor *out, void *workspace, size_t ws_bytes,
+                       void *stream) {
+    if (!x || ((uintptr_t)x & 15)) return HBFP_ERR_ARG;
+    int64_t ho = 0, wo = 0;
+    bool per_image = false;
+    const int rc = im2col_check(conv, out, true, &ho, &wo, &per_image);
+    if (rc != HBFP_OK) return rc;
     uint32_t *table = nullptr;
     if (per_image) {
         const size_t need = align256((size_t)conv->n * 4);

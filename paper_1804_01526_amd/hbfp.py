@@ -84,6 +84,8 @@ def _load():
     lib.hbfp_encode_static_limit.argtypes = []
     lib.hbfp_decode.argtypes = [T, vp, i64, vp]
     lib.hbfp_encode_im2col.argtypes = [vp, ctypes.POINTER(Conv2d), T, vp, sz, vp]
+    lib.hbfp_encode_im2col_workspace.argtypes = [ctypes.POINTER(Conv2d), T, ctypes.POINTER(sz)]
+    lib.hbfp_encode_im2col_workspace.restype = i32
     lib.hbfp_gemm_conv2d_workspace.argtypes = [T, ctypes.POINTER(Conv2d), T, ctypes.POINTER(sz)]
     lib.hbfp_gemm_conv2d_workspace.restype = i32
     lib.hbfp_gemm_conv2d.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
@@ -452,6 +454,12 @@ def _desc_array(outs):
     return arr
 
 
+def encode_im2col_workspace(conv: Conv2d, desc: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_encode_im2col_workspace(ctypes.byref(conv), ctypes.byref(desc), ctypes.byref(n)), "hbfp_encode_im2col_workspace")
+    return int(n.value)
+
+
 def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, contract_axis: int = 1, out: Optional[BfpTensor] = None,
                   workspace: Optional[torch.Tensor] = None, stream=None) -> BfpTensor:
     """hbfp_encode_im2col on an NHWC FP32 device tensor: the lowered activation operand of a convolution
@@ -460,7 +468,7 @@ def encode_im2col(x: torch.Tensor, conv: Conv2d, fmt: Format, contract_axis: int
     ho, wo = conv.out_hw()
     if out is None:
         out = alloc(fmt, conv.n * ho * wo, conv.r * conv.s * conv.c, contract_axis, x.device)
-    workspace = _workspace(encode_workspace(out.desc), x.device, workspace)
+    workspace = _workspace(encode_im2col_workspace(conv, out.desc), x.device, workspace)
     _check(_lib.hbfp_encode_im2col(_dev_ptr(x), ctypes.byref(conv), ctypes.byref(out.desc), _dev_ptr(workspace),
                                    0 if workspace is None else workspace.numel(), _stream_ptr(stream)), "hbfp_encode_im2col")
     return out

@@ -107,6 +107,23 @@ def test_plan_rejects_bad_arguments():
     assert _status(hbfp.plan, hbfp.make_format(8, 1, 32, rounding=2), 10, 10, 1) == hbfp.ERR_FORMAT
 
 
+def test_encode_im2col_workspace_sizes():
+    """One exponent per training input needs 4 bytes per image at any image size (also where hbfp_encode converts the
+    same plan in one pass); blocks inside a pixel need nothing; a plan of another shape is refused."""
+    import ctypes
+    conv = hbfp.Conv2d(3, 2, 1, 8, 1, 1, 0, 0, 1, 1, 8, 0)                    # three images of 2 x 1 pixels
+    per_input = hbfp.plan(hbfp.make_format(8, 2, 0, k_slot=8), 6, 8, 1)
+    assert hbfp.encode_workspace(per_input) == 0
+    assert hbfp.encode_im2col_workspace(conv, per_input) == 256
+    assert hbfp.encode_im2col_workspace(conv, hbfp.plan(hbfp.make_format(8, 1, 8), 6, 8, 1)) == 0
+    big = hbfp.Conv2d(100, 28, 28, 24, 3, 3, 1, 1, 1, 1, 0, 0)
+    assert hbfp.encode_im2col_workspace(big, hbfp.plan(hbfp.make_format(8, 784, 0, k_slot=24), 78400, 216, 1)) == 512
+    n = ctypes.c_size_t(0)
+    other = hbfp.plan(hbfp.make_format(8, 1, 8), 7, 8, 1)
+    assert hbfp._lib.hbfp_encode_im2col_workspace(ctypes.byref(conv), ctypes.byref(other), ctypes.byref(n)) == hbfp.ERR_LAYOUT
+    assert hbfp._lib.hbfp_encode_im2col_workspace(ctypes.byref(conv), ctypes.byref(per_input), None) == hbfp.ERR_ARG
+
+
 def test_encode_workspace_sizes():
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 1, 32), 64, 256, 1)) == 0
     assert hbfp.encode_workspace(hbfp.plan(hbfp.make_format(8, 32, 1), 256, 64, 0)) == 0
