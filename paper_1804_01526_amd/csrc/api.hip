@@ -432,13 +432,18 @@ int hbfp_encode_packed_batch(int njobs, const hbfp_encode_job *jobs, void *works
     return HBFP_OK;
 }
 
+// a convolution with positive extents whose window fits the padded image at least once
+static bool conv_geometry_ok(const hbfp_conv2d &c) {
+    if (c.n <= 0 || c.h <= 0 || c.w <= 0 || c.c <= 0 || c.r <= 0 || c.s <= 0 || c.pad_h < 0 || c.pad_w < 0 || c.stride_h <= 0 ||
+        c.stride_w <= 0 || c.c_block < 0)
+        return false;
+    return c.h + 2 * c.pad_h >= c.r && c.w + 2 * c.pad_w >= c.s;
+}
+
 // geometry and plan checks shared by hbfp_encode_im2col and its workspace query
 static int im2col_check(const hbfp_conv2d *conv, const hbfp_tensor *out, bool need_ptrs, int64_t *ho, int64_t *wo, bool *per_image) {
     if (!conv) return HBFP_ERR_ARG;
-    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
-        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
-        return HBFP_ERR_ARG;
-    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    if (!conv_geometry_ok(*conv)) return HBFP_ERR_ARG;
     int rc = check_tensor(out, need_ptrs);
     if (rc != HBFP_OK) return rc;
     *ho = (conv->h + 2 * conv->pad_h - conv->r) / conv->stride_h + 1;
@@ -482,16 +487,37 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
     return launch_encode_im2col(x, *conv, ho, wo, g, out->mant, out->exps, table, (hipStream_t)stream);
 }
 
+// arguments of a product whose operand A is gathered from `image` for M output rows
+static GemmArgs conv_product_args(const hbfp_tensor *image, const hbfp_tensor *filters, int64_t M, float *C, int64_t ldc, float beta) {
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.mantA = image->mant;
+    g.expA = image->exps;
+    g.expA_ld = image->exp_ld;
+    g.mantB = filters->mant;
+    g.expB = filters->exps;
+    g.expB_ld = filters->exp_ld;
+    g.M = M;
+    g.N = filters->rows;
+    g.kpad = filters->kpad;
+    g.nblk = filters->nblk;
+    g.kbp = 32;
+    g.kblock = image->kblock;
+    g.mA = image->mant_bits;
+    g.mB = filters->mant_bits;
+    g.C = C;
+    g.ldc = ldc;
+    g.beta = beta;
+    return g;
+}
+
 // geometry and operand checks shared by hbfp_gemm_conv2d and its workspace query.  *slot_order: -1 for the gather of 64
 // channels of one tap per stage (blocks of 32, channels a multiple of 64, window entries tap by tap), else the order of k
 // (0 tap by tap, 1 channel block by channel block) for the gather slot by slot.
 static int conv_gemm_check(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, int64_t *ho,
                            int64_t *wo, int *slot_order) {
     if (!image || !conv || !filters) return HBFP_ERR_ARG;
-    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
-        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
-        return HBFP_ERR_ARG;
-    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    if (!conv_geometry_ok(*conv)) return HBFP_ERR_ARG;
     int rc = check_tensor(image, need_ptrs);
     if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
     if (rc != HBFP_OK) return rc;
@@ -534,25 +560,7 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
     size_t need = 0;
     hbfp_gemm_conv2d_workspace(image, conv, filters, &need);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
-    GemmArgs g;
-    memset(&g, 0, sizeof g);
-    g.mantA = image->mant;
-    g.expA = image->exps;
-    g.expA_ld = image->exp_ld;
-    g.mantB = filters->mant;
-    g.expB = filters->exps;
-    g.expB_ld = filters->exp_ld;
-    g.M = conv->n * ho * wo;
-    g.N = filters->rows;
-    g.kpad = filters->kpad;
-    g.nblk = filters->nblk;
-    g.kbp = 32;
-    g.kblock = image->kblock;
-    g.mA = image->mant_bits;
-    g.mB = filters->mant_bits;
-    g.C = Y;
-    g.ldc = ldy;
-    g.beta = beta;
+    const GemmArgs g = conv_product_args(image, filters, conv->n * ho * wo, Y, ldy, beta);
     return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream, 1, 1, false, slot_order, (int)image->kblock);
 }
 
@@ -561,10 +569,7 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
 // describes that convolution: its image is dY as stored.
 static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, hbfp_conv2d *as_forward) {
     if (!dy || !conv || !filters) return HBFP_ERR_ARG;
-    if (conv->n <= 0 || conv->h <= 0 || conv->w <= 0 || conv->c <= 0 || conv->r <= 0 || conv->s <= 0 || conv->pad_h < 0 ||
-        conv->pad_w < 0 || conv->stride_h <= 0 || conv->stride_w <= 0 || conv->c_block < 0)
-        return HBFP_ERR_ARG;
-    if (conv->h + 2 * conv->pad_h < conv->r || conv->w + 2 * conv->pad_w < conv->s) return HBFP_ERR_ARG;
+    if (!conv_geometry_ok(*conv)) return HBFP_ERR_ARG;
     if (conv->c_block > 0 && conv->c_block < conv->c) return HBFP_ERR_FORMAT;
     int rc = check_tensor(dy, need_ptrs);
     if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
@@ -609,25 +614,7 @@ int hbfp_gemm_conv2d_dgrad(const hbfp_tensor *dy, const hbfp_conv2d *conv, const
     size_t need = 0;
     hbfp_gemm_conv2d_dgrad_workspace(dy, conv, filters, &need);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
-    GemmArgs g;
-    memset(&g, 0, sizeof g);
-    g.mantA = dy->mant;
-    g.expA = dy->exps;
-    g.expA_ld = dy->exp_ld;
-    g.mantB = filters->mant;
-    g.expB = filters->exps;
-    g.expB_ld = filters->exp_ld;
-    g.M = conv->n * conv->h * conv->w;
-    g.N = filters->rows;
-    g.kpad = filters->kpad;
-    g.nblk = filters->nblk;
-    g.kbp = 32;
-    g.kblock = 32;
-    g.mA = dy->mant_bits;
-    g.mB = filters->mant_bits;
-    g.C = dX;
-    g.ldc = ldx;
-    g.beta = beta;
+    const GemmArgs g = conv_product_args(dy, filters, conv->n * conv->h * conv->w, dX, ldx, beta);
     return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w,
                                conv_dgrad_by_phase(conv->r, conv->s, conv->stride_h, conv->stride_w));
 }
