@@ -291,7 +291,8 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
  * zeros are never stored: the product kernel gathers each tap from dy as converted once ([n*ho*wo][filters], blocks of 32
  * filters) and reads a page of zeros for the positions in between; all h x w input positions are computed, also those
  * that only part of a window reaches.  Both factors count as their BFP values and the sum is taken as Eq. (2) takes it.
- * With stride 1 this is hbfp_gemm_conv2d on dy with that padding.
+ * With stride 1 this is hbfp_gemm_conv2d on dy with that padding (which, unlike this call, takes every format of its
+ * operands: other block lengths, one exponent per training input, filter tiles over the whole window).
  *   dy       encoded [n*ho*wo][filters], contraction axis 1, blocks of 32 along the filters, filters a multiple of 64,
  *            <= 8 bits (ho, wo: the output extents of conv)
  *   conv     geometry of the FORWARD convolution (n, h, w, c describe x; c_block must be 0)

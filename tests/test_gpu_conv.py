@@ -201,6 +201,27 @@ def test_conv_general_gather_random(hb):
         _slot_case(hb, *geom, seed=seed)
 
 
+def test_conv_data_gradient_of_a_stride_one_convolution_in_the_format_of_the_experiments(hb):
+    """Stride 1: the data gradient is hbfp_gemm_conv2d itself on dY (padding r - 1 - pad) in any format the gather takes;
+    here dY with one exponent per training input in blocks of 24 filters, the mirrored filter in tiles over the whole
+    window, 24 filters and 24 channels, against the oracle's lowered dY times its decoded filter."""
+    rng = np.random.default_rng(52)
+    n, h, w, c, f, r, s, pad = 3, 9, 10, 50, 72, 3, 3, 1
+    dy = (rng.standard_normal((n, h, w, f)) * 1e-2 * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
+    w4 = (rng.standard_normal((r, s, c, f)) * np.exp2(rng.integers(-3, 4, size=(1, 1, 1, f))) * 0.1).astype(np.float32)
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4, 24))                                  # [(f block, tap, f in block), c]
+    conv = hb.Conv2d(n, h, w, f, r, s, r - 1 - pad, s - 1 - pad, 1, 1, 24, 0)
+    img = hb.encode(torch.from_numpy(dy.reshape(n * h * w, f)).cuda(), 1, hb.make_format(8, h * w, 0, k_slot=24))
+    flt = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, r * s * 24, 24, k_slot=24))
+    dx = hb.gemm_conv2d(img, conv, flt)
+    torch.cuda.synchronize()
+    dyq = ref.decode(ref.encode(dy.reshape(n, -1), 1, 0, 8)).reshape(n, h, w, f)
+    low = ref.im2col_dgrad(dyq, h, w, r, s, pad, pad)                                             # columns (tap, f)
+    low = low.reshape(n * h * w, r * s, f // 24, 24).transpose(0, 2, 1, 3).reshape(n * h * w, -1)  # -> (f block, tap, f in block)
+    want = ref.gemm(low, ref.decode(ref.encode(wd, r * s * 24, 24, 8)))
+    assert np.linalg.norm(want) > 0 and rel_fro(dx.cpu().numpy(), want) <= TOL
+
+
 def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
     """hbfp_gemm_conv2d_dgrad against the oracle (dY converted, spread out and lowered explicitly, FP64 product with the
     converted mirrored filter) and, bit for bit, against hbfp_gemm_conv2d on a dY whose zeros are really stored."""
