@@ -291,21 +291,23 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
  * zeros are never stored: the product kernel gathers each tap from dy as converted once ([n*ho*wo][filters], blocks of 32
  * filters) and reads a page of zeros for the positions in between; all h x w input positions are computed, also those
  * that only part of a window reaches.  Both factors count as their BFP values and the sum is taken as Eq. (2) takes it.
- * With stride 1 this is hbfp_gemm_conv2d on dy with that padding (which, unlike this call, takes every format of its
- * operands: other block lengths, one exponent per training input, filter tiles over the whole window).
- *   dy       encoded [n*ho*wo][filters], contraction axis 1, blocks of 32 along the filters, filters a multiple of 64,
- *            <= 8 bits (ho, wo: the output extents of conv)
- *   conv     geometry of the FORWARD convolution (n, h, w, c describe x; c_block must be 0)
- *   filters  encoded matrix [r*s*filters][c] with row ((r-1-fr) * s + (s-1-fs)) * filters + f, column ch = w[fr][fs][ch][f],
- *            contraction axis 0, blocks of 32 down its rows, <= 8 bits
+ * With stride 1 this is hbfp_gemm_conv2d on dy with that padding.
+ *   dy       encoded [n*ho*wo][filters] (ho, wo: the output extents of conv), contraction axis 1, in any of the formats
+ *            hbfp_gemm_conv2d takes for its image, with the filters in the place of the channels: stored blocks of
+ *            B <= 32 filters, filters a multiple of B, any sharing of exponents beyond (one per training input), <= 8 bits
+ *   conv     geometry of the FORWARD convolution (n, h, w, c describe x).  c_block 0: k = (mirrored tap, filter);
+ *            c_block = B: filter block by filter block, k = (filter block, mirrored tap, filter in the block)
+ *   filters  encoded matrix [r*s*filters][c] in that order - with c_block 0, row ((r-1-fr) * s + (s-1-fs)) * filters + f,
+ *            column ch = w[fr][fs][ch][f] -, contraction axis 0, stored blocks of B down its rows, <= 8 bits
  *   dX       device FP32 [n*h*w][ldx], ldx >= c; beta 0 or 1
  *   workspace  hbfp_gemm_conv2d_dgrad_workspace bytes, 256-byte aligned
- * Where the window is at least as large as the stride in both directions (and stride_h * stride_w <= 16) the zeros are
- * not multiplied either: the input positions fall into stride_h * stride_w phases (iy mod stride_h, ix mod stride_w), a
+ * With blocks of 32 filters, a multiple of 64 filters and c_block 0, where the window is at least as large as the stride
+ * in both directions (and stride_h * stride_w <= 16), the zeros are not multiplied either: the input positions fall into stride_h * stride_w phases (iy mod stride_h, ix mod stride_w), a
  * phase meets only every stride-th filter tap and reads dy without gaps, and one launch walks all phases, each storing
  * to the rows of its input positions.  The taps that do contribute are accumulated in the same order both ways, so the
  * result is bit for bit that of hbfp_gemm_conv2d on a dy whose zeros are stored.  Otherwise (a window smaller than the
- * stride) every tap of the spread-out dy is multiplied, zeros included: stride_h * stride_w times the work the sum needs.
+ * stride, the other formats) every tap of the spread-out dy is multiplied, zeros included: stride_h * stride_w times the
+ * work the sum needs.
  * Errors: as hbfp_gemm_conv2d; HBFP_ERR_ARG also for extents from 2^21 on.
  */
 int hbfp_gemm_conv2d_dgrad_workspace(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes);

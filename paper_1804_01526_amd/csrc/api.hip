@@ -567,10 +567,10 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
 // The data gradient of a convolution of any stride: a stride-1 convolution of the zero-dilated output gradient with
 // padding r - 1 - pad and the mirrored filter, computed for all h x w positions of the input.  The synthesized geometry
 // describes that convolution: its image is dY as stored.
-static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, hbfp_conv2d *as_forward) {
+static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, bool need_ptrs, hbfp_conv2d *as_forward,
+                            int *slot_order) {
     if (!dy || !conv || !filters) return HBFP_ERR_ARG;
     if (!conv_geometry_ok(*conv)) return HBFP_ERR_ARG;
-    if (conv->c_block > 0 && conv->c_block < conv->c) return HBFP_ERR_FORMAT;
     int rc = check_tensor(dy, need_ptrs);
     if (rc == HBFP_OK) rc = check_tensor(filters, need_ptrs);
     if (rc != HBFP_OK) return rc;
@@ -583,9 +583,12 @@ static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, cons
     if (dy->contract_axis != 1 || dy->src_rows != conv->n * ho * wo) return HBFP_ERR_LAYOUT;
     if (filters->contract_axis != 0 || filters->src_rows != (int64_t)conv->r * conv->s * f || filters->src_cols != conv->c) return HBFP_ERR_LAYOUT;
     if (dy->mant_bits > 8 || filters->mant_bits > 8) return HBFP_ERR_FORMAT;
-    if (dy->kblock != 32 || dy->rblock != 1 || dy->kshare != 1 || filters->kblock != 32 || filters->rblock != 1 || filters->kshare != 1 ||
-        (f & 63))
+    // as for hbfp_gemm_conv2d, with the filters of dy in the place of the channels (c_block counts filters here)
+    const bool by_block = conv->c_block > 0 && conv->c_block < f;
+    if (dy->kblock_pad != 32 || filters->kblock_pad != 32 || dy->kblock != filters->kblock || f % dy->kblock ||
+        (by_block && conv->c_block != dy->kblock))
         return HBFP_ERR_FORMAT;
+    *slot_order = by_block ? 1 : (dy->kblock == 32 && !(f & 63)) ? -1 : 0;
     *as_forward = *conv;
     as_forward->h = ho;
     as_forward->w = wo;
@@ -599,24 +602,28 @@ static int conv_dgrad_check(const hbfp_tensor *dy, const hbfp_conv2d *conv, cons
 int hbfp_gemm_conv2d_dgrad_workspace(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes) {
     if (!bytes) return HBFP_ERR_ARG;
     hbfp_conv2d fw;
-    const int rc = conv_dgrad_check(dy, conv, filters, false, &fw);
+    int slot_order = -1;
+    const int rc = conv_dgrad_check(dy, conv, filters, false, &fw, &slot_order);
     if (rc != HBFP_OK) return rc;
-    *bytes = align256(gemm_conv_workspace(conv->n * conv->h * conv->w, filters->rows, filters->kpad, dy->rows, (int)(fw.c / 32)));
+    *bytes = align256(gemm_conv_workspace(conv->n * conv->h * conv->w, filters->rows, filters->kpad, dy->rows, (int)(fw.c / dy->kblock)));
     return HBFP_OK;
 }
 
 int hbfp_gemm_conv2d_dgrad(const hbfp_tensor *dy, const hbfp_conv2d *conv, const hbfp_tensor *filters, float *dX, int64_t ldx, float beta,
                            void *workspace, size_t ws_bytes, void *stream) {
     hbfp_conv2d fw;
-    int rc = conv_dgrad_check(dy, conv, filters, true, &fw);
+    int slot_order = -1;
+    int rc = conv_dgrad_check(dy, conv, filters, true, &fw, &slot_order);
     if (rc != HBFP_OK) return rc;
     if (!dX || ((uintptr_t)dX & 3) || ldx < filters->rows || (beta != 0.0f && beta != 1.0f)) return HBFP_ERR_ARG;
     size_t need = 0;
     hbfp_gemm_conv2d_dgrad_workspace(dy, conv, filters, &need);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     const GemmArgs g = conv_product_args(dy, filters, conv->n * conv->h * conv->w, dX, ldx, beta);
-    return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w,
-                               conv_dgrad_by_phase(conv->r, conv->s, conv->stride_h, conv->stride_w));
+    // the slot-by-slot gather spreads dy out (zeros multiplied); the others go phase by phase where the window allows
+    const bool by_phase = slot_order < 0 && conv_dgrad_by_phase(conv->r, conv->s, conv->stride_h, conv->stride_w);
+    return launch_gemm_conv_i8(g, fw, conv->h, conv->w, dy->kpad, workspace, (hipStream_t)stream, conv->stride_h, conv->stride_w, by_phase,
+                               slot_order, (int)dy->kblock);
 }
 
 int hbfp_decode(const hbfp_tensor *t, float *dst, int64_t ld, void *stream) {

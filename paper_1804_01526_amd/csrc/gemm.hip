@@ -408,10 +408,10 @@ struct W8Ops<true> {
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
-// GATHER (CONV only): 0 the image as it is (64 channels of one tap per stage), 1 = DIL, 2 = PHASE, 3 = SLOT
+// GATHER (CONV only): 0 the image as it is (64 channels of one tap per stage), 1 = DIL, 2 = PHASE, 3 = SLOT, 4 = SLOT + DIL
 template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
-    constexpr bool DIL = GATHER == 1, PHASE = GATHER == 2, SLOT = GATHER == 3;
+    constexpr bool DIL = GATHER == 1 || GATHER == 4, PHASE = GATHER == 2, SLOT = GATHER == 3 || GATHER == 4;
     typedef W8Ops<F16> ops;
     typedef typename ops::acc_t acc_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -527,9 +527,15 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         if (SLOT) {                                                                                     \
             const bool upper = (cchunk & 32) != 0;                                                      \
             const int fr = upper ? fr1 : cfr, fs = upper ? fs1 : cfs, cb = upper ? cb1 : scb;           \
-            const bool in_m = sidx + (upper ? 1 : 0) < q.cv.nslots && (unsigned)(cy + fr) < (unsigned)q.cv.H && \
-                              (unsigned)(cx + fs) < (unsigned)q.cv.W;                                   \
-            const uint8_t *srcA = p.A + cpix + (int64_t)(fr * q.cv.W + fs) * q.cv.pix_bytes + cb * 32;  \
+            bool in_m = sidx + (upper ? 1 : 0) < q.cv.nslots;                                           \
+            int py = cy + fr, px = cx + fs;                 /* DIL: in the spread-out image; cpix holds the image only */ \
+            if (DIL) {                                                                                  \
+                const int qy = conv_undilate(py, q.cv.inv_dh), qx = conv_undilate(px, q.cv.inv_dw);     \
+                in_m = in_m && qy * q.cv.dil_h == py && qx * q.cv.dil_w == px;                          \
+                py = qy, px = qx;                                                                       \
+            }                                                                                           \
+            in_m = in_m && (unsigned)py < (unsigned)q.cv.H && (unsigned)px < (unsigned)q.cv.W;          \
+            const uint8_t *srcA = p.A + cpix + (int64_t)((DIL ? py : fr) * q.cv.W + (DIL ? px : fs)) * q.cv.pix_bytes + cb * 32; \
             async_copy16_at(in_m ? srcA : q.cv.zeros, lb + ldsM);                                       \
         } else if (CONV) {                                                                              \
             const bool tap_ok = ctap < gtaps;                                                           \
@@ -553,9 +559,15 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         if (SLOT && wave_u < 4) {                           /* the wave's slot of the stage: uniform */ \
             const bool upper = (wc >> 1) != 0;                                                          \
             const int fr = upper ? fr1 : cfr, fs = upper ? fs1 : cfs, cb = upper ? cb1 : scb;           \
-            const bool in_w = sidx + (upper ? 1 : 0) < q.cv.nslots && (unsigned)(wy + fr) < (unsigned)q.cv.H && \
-                              (unsigned)(wx + fs) < (unsigned)q.cv.W;                                   \
-            const uint32_t *srcW = q.cv.words + (int64_t)cb * q.cv.word_pitch + (wpix + (fr * q.cv.W + fs)); \
+            bool in_w = sidx + (upper ? 1 : 0) < q.cv.nslots;                                           \
+            int py = wy + fr, px = wx + fs;                                                             \
+            if (DIL) {                                                                                  \
+                const int qy = conv_undilate(py, q.cv.inv_dh), qx = conv_undilate(px, q.cv.inv_dw);     \
+                in_w = in_w && qy * q.cv.dil_h == py && qx * q.cv.dil_w == px;                          \
+                py = qy, px = qx;                                                                       \
+            }                                                                                           \
+            in_w = in_w && (unsigned)py < (unsigned)q.cv.H && (unsigned)px < (unsigned)q.cv.W;          \
+            const uint32_t *srcW = q.cv.words + (int64_t)cb * q.cv.word_pitch + (wpix + ((DIL ? py : fr) * q.cv.W + (DIL ? px : fs))); \
             async_copy4_at(in_w ? srcW : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64), lb + ldsW); \
         } else if (CONV && wave_u < 4) {                                                                \
             const bool tap_ok = ctap < gtaps;                                                           \
@@ -879,7 +891,7 @@ bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w) {
 // count in dilated positions); ho x wo is then whatever the caller wants computed.  by_phase: the same result computed
 // output phase by output phase (conv_dgrad_by_phase must hold), without multiplying the zeros.  slot_order >= 0: the
 // general gather from an image stored in blocks of kblock channels (c.c a multiple of it), k tap by tap (0) or channel
-// block by channel block (1).
+// block by channel block (1); it combines with the dilation, not with the phases.
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
                         hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock) {
     GemmParams p = {};
@@ -909,7 +921,7 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     p.partial = (float *)workspace;
     const int64_t pixels = c.n * c.h * c.w;
     const bool slots = slot_order >= 0;
-    if (slots && (kblock < 1 || kblock > 32 || c.c % kblock || dil_h != 1 || dil_w != 1 || by_phase)) return HBFP_ERR_ARG;
+    if (slots && (kblock < 1 || kblock > 32 || c.c % kblock || by_phase)) return HBFP_ERR_ARG;
     const int cblocks = (int)(slots ? c.c / kblock : c.c / 32);
     W8Params q = {};
     q.g = p;
@@ -992,10 +1004,12 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
     if (slots) {
-        static std::atomic<bool> configured_slot{false};
-        if (allow_dynamic_lds(configured_slot, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 3>), kW8LdsBytes) != HBFP_OK)
+        static std::atomic<bool> configured_slot{false}, configured_slot_dil{false};
+        if (allow_dynamic_lds(configured_slot, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 3>), kW8LdsBytes) != HBFP_OK ||
+            allow_dynamic_lds(configured_slot_dil, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 4>), kW8LdsBytes) != HBFP_OK)
             return HBFP_ERR_LAUNCH;
-        hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 3>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+        if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 4>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+        else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 3>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     } else if (dilated) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 1>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
     int rc = launch_status();

@@ -222,19 +222,25 @@ def test_conv_data_gradient_of_a_stride_one_convolution_in_the_format_of_the_exp
     assert np.linalg.norm(want) > 0 and rel_fro(dx.cpu().numpy(), want) <= TOL
 
 
-def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
+def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0, kb=32, by_block=False, per_image=False, tiles=False):
     """hbfp_gemm_conv2d_dgrad against the oracle (dY converted, spread out and lowered explicitly, FP64 product with the
-    converted mirrored filter) and, bit for bit, against hbfp_gemm_conv2d on a dY whose zeros are really stored."""
+    converted mirrored filter) and, bit for bit, against hbfp_gemm_conv2d on a dY whose zeros are really stored.
+    kb / by_block / per_image / tiles: the formats of _slot_case, with the filters of dY in the place of the channels."""
     rng = np.random.default_rng(seed)
     ho, wo = (h + 2 * pad_h - r) // sh + 1, (w + 2 * pad_w - s) // sw + 1
-    print(f"[dgrad] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad=({pad_h},{pad_w}) stride=({sh},{sw}) dy {ho}x{wo}", flush=True)
-    dy = (rng.standard_normal((n, ho, wo, f)) * 1e-2 * np.exp2(rng.integers(-3, 4, size=(n, ho, wo, 1)))).astype(np.float32)
+    print(f"[dgrad] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad=({pad_h},{pad_w}) stride=({sh},{sw}) dy {ho}x{wo} blocks of {kb} "
+          f"{'by block' if by_block else 'by tap'} {'per image' if per_image else 'per pixel'} {'tiles' if tiles else 'columns'}", flush=True)
+    dy = (rng.standard_normal((n, ho, wo, f)) * 1e-2 * np.exp2(rng.integers(-3, 4, size=(n, 1 if per_image else ho, 1 if per_image else wo, 1)))).astype(np.float32)
     w4 = (rng.standard_normal((r, s, c, f)) * 0.1).astype(np.float32)
-    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4))                 # [r*s*f, c]
-    conv = hb.Conv2d(n, h, w, c, r, s, pad_h, pad_w, sh, sw, 0, 0)
+    cb = kb if by_block else 0
+    wd = np.ascontiguousarray(ref.filter_matrix_dgrad(w4, cb))             # [r*s*f, c]
+    conv = hb.Conv2d(n, h, w, c, r, s, pad_h, pad_w, sh, sw, cb, 0)
     assert conv.out_hw() == (ho, wo)
-    img = hb.encode(torch.from_numpy(dy.reshape(n * ho * wo, f)).cuda(), 1, hb.make_format(8, 1, 32))
-    flt = hb.encode(torch.from_numpy(wd).cuda(), 0, hb.make_format(8, 32, 1))
+    f_img = (lambda rows: hb.make_format(8, rows, 0, k_slot=kb)) if per_image else (lambda rows: hb.make_format(8, 1, kb))
+    f_flt = (hb.make_format(8, r * s * kb, 24, k_slot=kb) if by_block else hb.make_format(8, kb, kb)) if tiles else hb.make_format(8, kb, 1)
+    o_flt = ((r * s * kb, 24) if by_block else (kb, kb)) if tiles else (kb, 1)
+    img = hb.encode(torch.from_numpy(dy.reshape(n * ho * wo, f)).cuda(), 1, f_img(ho * wo))
+    flt = hb.encode(torch.from_numpy(wd).cuda(), 0, f_flt)
     x0 = None
     if beta:
         x0 = rng.standard_normal((n * h * w, c)).astype(np.float32)
@@ -243,8 +249,11 @@ def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
         dx = hb.gemm_conv2d_dgrad(img, conv, flt)
     torch.cuda.synchronize()
     dx = dx.cpu().numpy()
-    dyq = ref.decode(ref.encode(dy.reshape(n * ho * wo, f), 1, 32, 8)).reshape(n, ho, wo, f)
-    want = ref.gemm(ref.im2col_dgrad(dyq, h, w, r, s, pad_h, pad_w, sh, sw), ref.decode(ref.encode(wd, 32, 1, 8)))
+    dyq = (ref.decode(ref.encode(dy.reshape(n, -1), 1, 0, 8)) if per_image else ref.decode(ref.encode(dy.reshape(n * ho * wo, f), 1, kb, 8))).reshape(n, ho, wo, f)
+    low = ref.im2col_dgrad(dyq, h, w, r, s, pad_h, pad_w, sh, sw)          # columns (tap, filter)
+    if by_block:                                                           # -> (filter block, tap, filter in block)
+        low = low.reshape(n * h * w, r * s, f // kb, kb).transpose(0, 2, 1, 3).reshape(n * h * w, -1)
+    want = ref.gemm(low, ref.decode(ref.encode(wd, o_flt[0], o_flt[1], 8)))
     if x0 is not None:
         want = want + x0.astype(np.float64)
     err = rel_fro(dx, want)
@@ -255,8 +264,8 @@ def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
         hc, wc = h + r - 1 - 2 * ph, w + s - 1 - 2 * pw                 # the spread-out dY, with the rows no window reaches
         spread = np.zeros((n, hc, wc, f), dtype=np.float32)
         spread[:, 0:(ho - 1) * sh + 1:sh, 0:(wo - 1) * sw + 1:sw, :] = dy
-        simg = hb.encode(torch.from_numpy(spread.reshape(n * hc * wc, f)).cuda(), 1, hb.make_format(8, 1, 32))
-        sconv = hb.Conv2d(n, hc, wc, f, r, s, ph, pw, 1, 1, 0, 0)
+        simg = hb.encode(torch.from_numpy(spread.reshape(n * hc * wc, f)).cuda(), 1, f_img(hc * wc))
+        sconv = hb.Conv2d(n, hc, wc, f, r, s, ph, pw, 1, 1, cb, 0)
         assert sconv.out_hw() == (h, w)
         ds = hb.gemm_conv2d(simg, sconv, flt)
         torch.cuda.synchronize()
@@ -276,6 +285,31 @@ def _dgrad_case(hb, n, h, w, c, f, r, s, pad_h, pad_w, sh, sw, seed, beta=0.0):
 ])
 def test_conv_data_gradient_geometries(hb, geom):
     _dgrad_case(hb, *geom, seed=sum(geom) + 1)
+
+
+@pytest.mark.parametrize("geom", [
+    # n, h, w, c, f, r, s, pad_h, pad_w, stride_h, stride_w, block, by block, per image, filter tiles
+    (2, 12, 12, 40, 48, 3, 3, 1, 1, 2, 2, 24, True, True, True),       # the format of Sec. 5.1, strided
+    (2, 11, 9, 30, 72, 3, 3, 1, 1, 2, 1, 24, False, True, True),
+    (2, 10, 10, 50, 96, 3, 3, 1, 1, 2, 2, 32, False, False, False),    # 96 filters in blocks of 32: three slots per tap
+    (2, 9, 9, 20, 32, 2, 2, 0, 0, 3, 3, 16, True, False, False),
+    (3, 8, 8, 24, 48, 3, 3, 1, 1, 1, 1, 24, True, True, True),         # stride 1 in that format
+    (1, 7, 7, 100, 960, 3, 3, 1, 1, 2, 2, 24, True, True, True),       # few tiles, 360 slots: split along k
+])
+def test_conv_data_gradient_general_formats(hb, geom):
+    n, h, w, c, f, r, s, ph, pw, sh, sw, kb, by_block, per_image, tiles = geom
+    _dgrad_case(hb, n, h, w, c, f, r, s, ph, pw, sh, sw, seed=sum(int(g) for g in geom), kb=kb, by_block=by_block, per_image=per_image, tiles=tiles)
+
+
+def test_conv_data_gradient_general_formats_random(hb):
+    for seed in random_cases(12):
+        rng = np.random.default_rng(9900 + seed)
+        r, s = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        h, w = int(rng.integers(r, 14)), int(rng.integers(s, 14))
+        kb = int(rng.choice([8, 16, 24, 32]))
+        _dgrad_case(hb, int(rng.integers(1, 4)), h, w, int(rng.integers(1, 150)), kb * int(rng.integers(1, 6)), r, s,
+                    int(rng.integers(0, r + 1)), int(rng.integers(0, s + 1)), int(rng.integers(1, 4)), int(rng.integers(1, 4)), seed=seed,
+                    kb=kb, by_block=bool(rng.integers(0, 2)), per_image=bool(rng.integers(0, 2)), tiles=bool(rng.integers(0, 2)))
 
 
 def test_conv_data_gradient_accumulates_and_splits_k(hb):
