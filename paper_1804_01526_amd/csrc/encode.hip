@@ -97,12 +97,17 @@ __device__ __forceinline__ void conv_window_entry(const ConvGeom &c, uint32_t k,
 }
 
 // output position -> image, top-left corner of its window
-__device__ __forceinline__ void conv_position(const ConvGeom &c, uint32_t pos, uint32_t &img, int &y0, int &x0) {
+__device__ __forceinline__ void conv_position(const ConvGeom &c, uint32_t pos, uint32_t &img, int &y0, int &x0, int &oy, int &ox) {
     img = div_magic(pos, c.dP);
     const uint32_t rem = pos - img * (uint32_t)(c.Ho * c.Wo);
-    const uint32_t oy = div_magic(rem, c.dW), ox = rem - oy * (uint32_t)c.Wo;
-    y0 = (int)oy * c.str_h - c.pad_h;
-    x0 = (int)ox * c.str_w - c.pad_w;
+    oy = (int)div_magic(rem, c.dW);
+    ox = (int)rem - oy * c.Wo;
+    y0 = oy * c.str_h - c.pad_h;
+    x0 = ox * c.str_w - c.pad_w;
+}
+__device__ __forceinline__ void conv_position(const ConvGeom &c, uint32_t pos, uint32_t &img, int &y0, int &x0) {
+    int oy, ox;
+    conv_position(c, pos, img, y0, x0, oy, ox);
 }
 
 // row path
@@ -485,6 +490,7 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     const int group0 = (lane / p.rblock) * p.rblock;   // first lane of this lane's 2-D tile
     int conv_fr = 0, conv_fs = 0, conv_ch = 0;          // CONV: this lane's filter tap and channel
     if (CONV) conv_window_entry(p.cv, r_ok ? (uint32_t)r : 0u, conv_fr, conv_fs, conv_ch);
+    const int conv_off = CONV ? (conv_fr * p.cv.W + conv_fs) * p.cv.C + conv_ch : 0;    // of the lane's window entry from the corner
 
     for (int bi = wave; bi < NBT; bi += 4) {
         const int64_t piece = blk0 + bi;                                  // stored piece of KBP elements
@@ -503,15 +509,26 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
 #pragma unroll
             for (int kk = 0; kk < KBP; ++kk) v[kk] = (kk < blen && r_ok) ? s[(int64_t)kk * p.ld] : 0.0f;
         } else {
+            // The output position is the same for the whole wave and walks on by one per element: it is decoded once
+            // per piece and advanced on the scalar unit, and its corner pixel is a uniform base address; the lane adds
+            // the offset of its own window entry, so the vector unit only checks the two coordinates.
+            uint32_t img;
+            int y0, x0, oy, ox;
+            conv_position(p.cv, (uint32_t)kfirst, img, y0, x0, oy, ox);
+            const int64_t step = (int64_t)p.cv.str_w * p.cv.C;
+            const float *corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W + x0) * p.cv.C;         // may lie outside; uniform
 #pragma unroll
             for (int kk = 0; kk < KBP; ++kk) {
-                // the output position is the same for the whole wave; the window offset is the lane's
-                uint32_t img;
-                int y0, x0;
-                conv_position(p.cv, (uint32_t)kfirst + (uint32_t)(kk < blen ? kk : 0), img, y0, x0);
-                const int iy = y0 + conv_fr, ix = x0 + conv_fs;
-                const bool inside = kk < blen && r_ok && iy >= 0 && iy < p.cv.H && ix >= 0 && ix < p.cv.W;
-                v[kk] = inside ? p.src[(((int64_t)img * p.cv.H + iy) * p.cv.W + ix) * p.cv.C + conv_ch] : 0.0f;
+                const bool inside = kk < blen && r_ok && (unsigned)(y0 + conv_fr) < (unsigned)p.cv.H &&
+                                    (unsigned)(x0 + conv_fs) < (unsigned)p.cv.W;
+                v[kk] = inside ? corner[conv_off] : 0.0f;
+                x0 += p.cv.str_w;
+                corner += step;
+                if (++ox == p.cv.Wo) {                                        // next output row, or next image
+                    ox = 0, x0 = -p.cv.pad_w, y0 += p.cv.str_h;
+                    if (++oy == p.cv.Ho) oy = 0, y0 = -p.cv.pad_h, ++img;
+                    corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W + x0) * p.cv.C;
+                }
             }
         }
         uint32_t amax = 0;
