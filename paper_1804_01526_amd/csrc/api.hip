@@ -457,7 +457,8 @@ static int im2col_check(const hbfp_conv2d *conv, const hbfp_tensor *out, bool ne
     if (out->contract_axis == 1 ? (out->kblock > 128 || (out->kblock & 7) || (conv->c & 7) || (conv->c_block & 7)) : out->kblock > 64)
         return HBFP_ERR_FORMAT;
     if ((int64_t)conv->r * conv->s * (conv->c_block > 0 && conv->c_block < conv->c ? conv->c_block : conv->c) > 0x7fffffff) return HBFP_ERR_ARG;
-    if (((int64_t)conv->r * conv->w + conv->s) * conv->c > 0x7fffffff) return HBFP_ERR_ARG;   // a window entry's offset from its corner pixel
+    // the offset of a window entry from the corner pixel of the first window of its output row stays below 2^31 elements
+    if ((((int64_t)conv->r + 1) * conv->w + conv->s) * conv->c > 0x7fffffff) return HBFP_ERR_ARG;
     return HBFP_OK;
 }
 

@@ -474,6 +474,34 @@ struct ColParams {
 constexpr int kColRowBytes = 512;   // bytes of one operand row in an LDS tile
 constexpr int kColStride = 528;     // padded LDS row stride: 16-byte writes of 16 lanes hit 16 bank groups
 
+// CONV: the KBP values of one piece for the lane's window entry (fr, fs, channel; off = its offset from the corner pixel
+// of a window) at the consecutive output positions from (img, oy, ox) on.  The position is the wave's: it walks on the
+// scalar unit, and only the end of an output row costs more than a compare there - the row's corner pixel is then a new
+// uniform base address and the lane's row check a new mask.  Inside a row the lane steps its own column and offset.
+// FULL: all KBP positions exist.
+template <int KBP, bool FULL>
+__device__ __forceinline__ void conv_col_gather(const ColParams &p, uint32_t img, int y0, int x0, int oy, int ox, int blen, bool r_ok,
+                                                int fr, int fs, int off, float (&v)[KBP]) {
+    const int step = p.cv.str_w * p.cv.C;                                                 // elements per output column
+    const float *corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W + x0) * p.cv.C; // may lie outside the tensor; uniform
+    bool row_ok = r_ok && (unsigned)(y0 + fr) < (unsigned)p.cv.H;
+    int xl = x0 + fs, offl = off;                                                         // the lane's input column and offset
+#pragma unroll
+    for (int kk = 0; kk < KBP; ++kk) {
+        const bool inside = (FULL || kk < blen) && row_ok && (unsigned)xl < (unsigned)p.cv.W;
+        v[kk] = inside ? corner[offl] : 0.0f;
+        xl += p.cv.str_w;
+        offl += step;
+        if (++ox == p.cv.Wo) {                                                            // next output row, or next image
+            ox = 0, y0 += p.cv.str_h;
+            if (++oy == p.cv.Ho) oy = 0, y0 = -p.cv.pad_h, ++img;
+            corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W - p.cv.pad_w) * p.cv.C;
+            row_ok = r_ok && (unsigned)(y0 + fr) < (unsigned)p.cv.H;
+            xl = fs - p.cv.pad_w, offl = off;
+        }
+    }
+}
+
 template <int KBP, bool WIDE, int ROUND, bool TABLE, bool CONV = false>
 __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
     constexpr int ESZ = WIDE ? 2 : 1;
@@ -515,21 +543,8 @@ __global__ __launch_bounds__(kThreads) void enc_col_kernel(const ColParams p) {
             uint32_t img;
             int y0, x0, oy, ox;
             conv_position(p.cv, (uint32_t)kfirst, img, y0, x0, oy, ox);
-            const int64_t step = (int64_t)p.cv.str_w * p.cv.C;
-            const float *corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W + x0) * p.cv.C;         // may lie outside; uniform
-#pragma unroll
-            for (int kk = 0; kk < KBP; ++kk) {
-                const bool inside = kk < blen && r_ok && (unsigned)(y0 + conv_fr) < (unsigned)p.cv.H &&
-                                    (unsigned)(x0 + conv_fs) < (unsigned)p.cv.W;
-                v[kk] = inside ? corner[conv_off] : 0.0f;
-                x0 += p.cv.str_w;
-                corner += step;
-                if (++ox == p.cv.Wo) {                                        // next output row, or next image
-                    ox = 0, x0 = -p.cv.pad_w, y0 += p.cv.str_h;
-                    if (++oy == p.cv.Ho) oy = 0, y0 = -p.cv.pad_h, ++img;
-                    corner = p.src + (((int64_t)img * p.cv.H + y0) * p.cv.W + x0) * p.cv.C;
-                }
-            }
+            if (blen == KBP) conv_col_gather<KBP, true>(p, img, y0, x0, oy, ox, blen, r_ok, conv_fr, conv_fs, conv_off, v);
+            else conv_col_gather<KBP, false>(p, img, y0, x0, oy, ox, blen, r_ok, conv_fr, conv_fs, conv_off, v);
         }
         uint32_t amax = 0;
 #pragma unroll
