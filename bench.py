@@ -398,7 +398,7 @@ def _gemm_side_configs(torch, hbfp, synth, reps=10):
     res["strided_dgrad_conv2d_gather_in_the_product"] = {
         "gemm_ms": round(ms_k, 4), "whole_data_gradient_ms": round(ms_all, 4), "TOPS_kernel": round(sflops / ms_k / 1e9, 1),
         "TOPS_incl_encode": round(sflops / ms_all / 1e9, 1),
-        "note": "dX 401408 x 64 (103 MB) from the 51 MB gradient tensor; 64 output channels fill half of a 128-column tile"}
+        "note": "dX 401408 x 64 (103 MB) from the 51 MB gradient tensor; 64 output channels fill half of a 128-column tile (the waves of the other half only copy)"}
     del ti, tf, out, wsc, img, Wd, Ws, dimg
     del X, W, dY
     # config 5: 8192^3, 12-bit mantissas, blocks of 64, stochastic rounding (the library's choice of kernel: FP16 planes

@@ -713,6 +713,22 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    // A wave whose 64 columns lie past the last column of the product (the second column half of a tile over at most 64
+    // remaining columns) has nothing to multiply: it keeps its part of the copies and every hand-over of the loop below,
+    // and leaves its SIMD to the waves that compute (the kernel is bound by their vector instructions).
+    if (col0 + (wave_u >> 2) * 64 >= p.N) {
+        for (int st = st_begin; st < st_end; st += 2) {
+            const int ring = ((st - st_begin) & 2);
+            const int rem = st_end - 2 - st;
+            if (rem > 0) {
+                HBFP_WAIT_COPIES(0);
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (rem >= 4) { HBFP_COPY_NEXT(ring); HBFP_COPY_NEXT(ring + 1); }
+            }
+        }
+        return;
+    }
     if (nst > 0) {
         HBFP_READ_STEP(0, 0, 0);
         cin = ops::rows(rowc, one_hot);
