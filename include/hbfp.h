@@ -267,6 +267,11 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
  *            rows (block_rows = B or k_slot = B; any sharing of exponents), <= 8 bits
  *   Y        device FP32 [n*ho*wo][ldy], ldy >= filters; beta 0 or 1
  *   workspace  hbfp_gemm_conv2d_workspace bytes (scale words of both operands, split-k slices), 256-byte aligned
+ * Where both operands repeat their exponents over the r*s taps of a channel block (c_block = B, the image with one
+ * exponent per training input, filter tiles over the whole window), the integer sums of such a run of blocks are added
+ * up before they are scaled (as Sec. 4 has it: one FP operation per tile, not per block; at most as many blocks as keep
+ * the sum below 2^22): fewer FP32 roundings than block by block, so that case equals the product on the lowered operand
+ * to rounding, not bit for bit.
  * With B = 32, c a multiple of 64 and c_block = 0 a stage of the product is 64 channels of one tap; otherwise it is two
  * consecutive stored blocks, in general of two different pixels (5 % slower at equal sizes).  Blocks shorter than 32 are
  * stored as 32 and cost as much.  A channel count that is no multiple of B is handled by the caller: zero channels

@@ -563,7 +563,14 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
     hbfp_gemm_conv2d_workspace(image, conv, filters, &need);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     const GemmArgs g = conv_product_args(image, filters, conv->n * ho * wo, Y, ldy, beta);
-    return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream, 1, 1, false, slot_order, (int)image->kblock);
+    // One exponent per training input (and stored block) against filter tiles over the whole window, window entries
+    // channel block by channel block: both operands repeat their exponents over the r * s taps of a channel block, and
+    // the product scales each such run once (Sec. 4: the larger the tile, the fewer FP operations per fixed-point one).
+    const int64_t taps = (int64_t)conv->r * conv->s;
+    const bool runs = slot_order == 1 && taps > 1 && image->rblock == conv->h * conv->w &&
+                      (filters->kshare >= filters->nblk || filters->kshare % taps == 0);
+    return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream, 1, 1, false, slot_order, (int)image->kblock,
+                               runs ? (int)taps : 0);
 }
 
 // The data gradient of a convolution of any stride: a stride-1 convolution of the zero-dilated output gradient with

@@ -43,6 +43,7 @@ struct GemmParams {
     int64_t M, N, kpad, eA_ld, eB_ld, ldc, nblk;
     int32_t nstage;              // kpad / 128
     int32_t spb;                 // 32-byte k-steps per exponent block (kblock_pad / 32)
+    int32_t chain_limit;         // gemm_i8_w8_kernel<3>: most k-steps chained before their sum is scaled
     int32_t stages_per_split;
     int32_t splits;
     int32_t tiles_m, tiles_n;
@@ -409,8 +410,14 @@ struct W8Ops<true> {
 // chained sum then stays below 256 * 127 * 127 < 2^22, the range in which adding it to the bit pattern of the
 // row constant is exact.  The longer the block, the closer the kernel gets to the matrix core's own pace.
 // GATHER (CONV only): 0 the image as it is (64 channels of one tap per stage), 1 = DIL, 2 = PHASE, 3 = SLOT, 4 = SLOT + DIL
+// SPB = 3: stored blocks of one k-step whose exponents repeat over runs of p.spb consecutive blocks in BOTH operands
+// (an image with one exponent per training input against filter tiles that span the whole window, Sec. 5.1): the scale
+// words are staged per k-step as for SPB = 1, but a run is chained like a long block and scaled once, at its last
+// k-step, after p.chain_limit k-steps (the range in which the row constant trick is exact) and at the end of the k range.
 template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
+    constexpr bool STEPW = SPB == 1 || SPB == 3;     // scale words per k-step
+    constexpr bool CHAIN = SPB == 0 || SPB == 3;     // the matrix instructions of a block (run) chain through their C input
     constexpr bool DIL = GATHER == 1 || GATHER == 4, PHASE = GATHER == 2, SLOT = GATHER == 3 || GATHER == 4;
     typedef W8Ops<F16> ops;
     typedef typename ops::acc_t acc_t;
@@ -496,8 +503,8 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 
     // stages are requested in order, so the three source pointers of this wave just advance
     const uint8_t *nextA = tileA + (int64_t)st_begin * kHalfK, *nextB = tileB + (int64_t)st_begin * kHalfK;
-    const uint32_t *nextW = wordsrc + (SPB == 1 ? 2 * (int64_t)st_begin + (wc >> 1) : SPB == 2 ? (int64_t)st_begin : (int64_t)st_begin / spb64) * wordpitch;
-    const int64_t stepW = (SPB == 1 ? 2 : 1) * wordpitch;                        // words per stage (long blocks: per block)
+    const uint32_t *nextW = wordsrc + (STEPW ? 2 * (int64_t)st_begin + (wc >> 1) : SPB == 2 ? (int64_t)st_begin : (int64_t)st_begin / spb64) * wordpitch;
+    const int64_t stepW = (STEPW ? 2 : 1) * wordpitch;                           // words per stage (long blocks: per block)
     int req_pos = 0;                                                             // SPB == 0: stage within its block
     // CONV: filter tap and 64-channel piece of the stage requested next (uniform)
     int ctap = CONV ? st_begin / q.cv.spt : 0, csub = CONV ? st_begin % q.cv.spt : 0;
@@ -568,7 +575,12 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             }                                                                                           \
             in_w = in_w && (unsigned)py < (unsigned)q.cv.H && (unsigned)px < (unsigned)q.cv.W;          \
             const uint32_t *srcW = q.cv.words + (int64_t)cb * q.cv.word_pitch + (wpix + ((DIL ? py : fr) * q.cv.W + (DIL ? px : fs))); \
-            async_copy4_at(in_w ? srcW : reinterpret_cast<const uint32_t *>(q.cv.zeros + 64), lb + ldsW); \
+            const uint32_t *outW = reinterpret_cast<const uint32_t *>(q.cv.zeros + 64);                  \
+            if (SPB == 3) {                                 /* a chain has one exponent: a tap outside takes that of the nearest pixel of the image */ \
+                const int ny = py < 0 ? 0 : (py >= q.cv.H ? q.cv.H - 1 : py), nx = px < 0 ? 0 : (px >= q.cv.W ? q.cv.W - 1 : px); \
+                outW = q.cv.words + (int64_t)(cb < q.cv.ncb ? cb : 0) * q.cv.word_pitch + (wpix + ((ny - wy) * q.cv.W + (nx - wx))); \
+            }                                                                                           \
+            async_copy4_at(in_w ? srcW : outW, lb + ldsW);                                              \
         } else if (CONV && wave_u < 4) {                                                                \
             const bool tap_ok = ctap < gtaps;                                                           \
             const uint32_t *tapW = q.cv.words + (int64_t)(2 * csub + (wc >> 1)) * q.cv.word_pitch + ((int64_t)cfr * q.cv.W + cfs);  /* uniform */ \
@@ -622,7 +634,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     float sb[2][2];
 #define HBFP_READ_STEP(ring, s_, set)                                                                         \
     {                                                                                                         \
-        constexpr int s = SPB == 1 ? (s_) : 0;           /* slot of the words */                              \
+        constexpr int s = STEPW ? (s_) : 0;              /* slot of the words */                              \
         const uint8_t *base_ = lds + (ring) * kHalfStage;                                                     \
         rowc = *reinterpret_cast<const uint32_t *>(base_ + offW + (s) * 512);                                 \
         a = *reinterpret_cast<const v4i *>(base_ + ((s_) ? fragA1 : fragA0));                                 \
@@ -656,7 +668,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
             _Pragma("unroll") for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(x1[v]));              \
             __builtin_amdgcn_sched_barrier(0);                                                          \
             cin = ops::rows(rowc, one_hot);                                                             \
-            if (SPB == 0) {               /* long blocks always chain: the next block starts from its constants */ \
+            if (CHAIN) {                  /* long blocks always chain: the next block starts from its constants */ \
                 if (F16) {                                                                              \
                     d0 = ops::start(cin);                                                               \
                     d1 = ops::start(cin);                                                               \
@@ -679,19 +691,32 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     // wave has consumed every LDS read of the pair, so after the barrier both buffers are free for the pair
     // after next, and the next pair - requested a pair earlier - has landed for everyone.  One barrier per
     // four k-steps instead of two was worth 5 % although a copy now has two stages instead of three to land.
+    // SPB = 3: whether the k-step that comes now ends a chain; moves on to the next k-step
+#define HBFP_CHAIN_ENDS(flag)                                                                           \
+    bool flag = false;                                                                                  \
+    if (SPB == 3) {                                                                                     \
+        flag = cpos == p.spb - 1 || crun == p.chain_limit - 1 || cstep == 2 * nst - 1;                  \
+        cpos = cpos == p.spb - 1 ? 0 : cpos + 1;                                                        \
+        crun = flag ? 0 : crun + 1;                                                                     \
+        ++cstep;                                                                                        \
+    }
 #define HBFP_PAIR(ring)                                                                                 \
     {                                                                                                   \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (!F16 && (pos & 3) == 3); \
+            const bool first0 = !CHAIN, last1 = SPB == 1 || SPB == 2 || (SPB == 0 && (pos == spb64 - 1 || (!F16 && (pos & 3) == 3))); \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
-            HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP(ring, 1, 1));                                 \
-            HBFP_STEP(1, SPB == 1, last1, HBFP_READ_STEP((ring) + 1, 0, 0));                            \
+            HBFP_CHAIN_ENDS(end0);                                                                      \
+            HBFP_CHAIN_ENDS(end1);                                                                      \
+            HBFP_STEP(0, first0, SPB == 1 || end0, HBFP_READ_STEP(ring, 1, 1));                         \
+            HBFP_STEP(1, SPB == 1, last1 || end1, HBFP_READ_STEP((ring) + 1, 0, 0));                    \
         }                                                                                               \
         {                                                                                               \
-            const bool first0 = SPB != 0, last1 = SPB != 0 || pos == spb64 - 1 || (!F16 && (pos & 3) == 3); \
+            const bool first0 = !CHAIN, last1 = SPB == 1 || SPB == 2 || (SPB == 0 && (pos == spb64 - 1 || (!F16 && (pos & 3) == 3))); \
             pos = pos == spb64 - 1 ? 0 : pos + 1;                                                       \
-            HBFP_STEP(0, first0, SPB == 1, HBFP_READ_STEP((ring) + 1, 1, 1));                           \
-            HBFP_STEP(1, SPB == 1, last1, {                                                             \
+            HBFP_CHAIN_ENDS(end0);                                                                      \
+            HBFP_CHAIN_ENDS(end1);                                                                      \
+            HBFP_STEP(0, first0, SPB == 1 || end0, HBFP_READ_STEP((ring) + 1, 1, 1));                   \
+            HBFP_STEP(1, SPB == 1, last1 || end1, {                                                     \
                 const int rem = st_end - 2 - st;                 /* stages after this pair */           \
                 if (rem > 0) {                                                                          \
                     HBFP_WAIT_COPIES(0);                                                                \
@@ -732,7 +757,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
     if (nst > 0) {
         HBFP_READ_STEP(0, 0, 0);
         cin = ops::rows(rowc, one_hot);
-        if (SPB == 0) {
+        if (CHAIN) {
             if (F16) {
                 d0 = ops::start(cin);
                 d1 = ops::start(cin);
@@ -743,6 +768,8 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         }
     }
     int pos = 0;
+    // SPB = 3: k-step within its run of equal exponents, k-steps since the last scaling, k-step of this workgroup's range
+    int cpos = SPB == 3 ? (2 * st_begin) % p.spb : 0, crun = 0, cstep = 0;
     for (int st = st_begin; st < st_end;) {
         HBFP_PAIR(0);
         st += 2;
@@ -751,6 +778,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
         st += 2;
     }
 #undef HBFP_PAIR
+#undef HBFP_CHAIN_ENDS
 #undef HBFP_READ_STEP
 #undef HBFP_STEP
 #undef HBFP_COPY_NEXT
@@ -907,9 +935,10 @@ bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w) {
 // count in dilated positions); ho x wo is then whatever the caller wants computed.  by_phase: the same result computed
 // output phase by output phase (conv_dgrad_by_phase must hold), without multiplying the zeros.  slot_order >= 0: the
 // general gather from an image stored in blocks of kblock channels (c.c a multiple of it), k tap by tap (0) or channel
-// block by channel block (1); it combines with the dilation, not with the phases.
+// block by channel block (1); it combines with the dilation, not with the phases.  chain > 1 (slot_order 1, no dilation):
+// both operands repeat their exponents over runs of `chain` consecutive stored blocks, which are then scaled once.
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
-                        hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock) {
+                        hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock, int chain) {
     GemmParams p = {};
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;
@@ -1019,7 +1048,16 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     }
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
-    if (slots) {
+    // the sum of a chain must stay below 2^22 for the row constants to come off exactly
+    const int64_t chain_limit = (((int64_t)1 << 22) - 1) / ((int64_t)kblock * (((int64_t)1 << (a.mA - 1)) - 1) * (((int64_t)1 << (a.mB - 1)) - 1));
+    if (slots && !dilated && slot_order == 1 && chain > 1 && chain_limit > 1) {
+        static std::atomic<bool> configured_chain{false};
+        if (allow_dynamic_lds(configured_chain, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<3, true, false, 3>), kW8LdsBytes) != HBFP_OK)
+            return HBFP_ERR_LAUNCH;
+        q.g.spb = chain;
+        q.g.chain_limit = (int32_t)(chain_limit < chain ? chain_limit : chain);
+        hipLaunchKernelGGL((gemm_i8_w8_kernel<3, true, false, 3>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+    } else if (slots) {
         static std::atomic<bool> configured_slot{false}, configured_slot_dil{false};
         if (allow_dynamic_lds(configured_slot, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 3>), kW8LdsBytes) != HBFP_OK ||
             allow_dynamic_lds(configured_slot_dil, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 4>), kW8LdsBytes) != HBFP_OK)
