@@ -252,8 +252,8 @@ int hbfp_encode_im2col(const float *x, const hbfp_conv2d *conv, const hbfp_tenso
  *     Y[(img, oy, ox)][f] = beta * Y + sum over (fr, fs, ch) of x[img][oy*stride_h - pad_h + fr][ox*stride_w - pad_w + fs][ch]
  *                                                             * w[(fr * s + fs) * c + ch][f]
  * with both factors as their BFP values and the sum taken as Eq. (2) takes it (integer sums over the channels of one
- * stored block of one tap, scaled by the two block exponents, accumulated in FP32).  Because a block of the lowered matrix is a block of
- * the image, the result equals hbfp_gemm_select(HBFP_KERNEL_INT8) on hbfp_encode_im2col's operand bit for bit (with
+ * stored block of one tap, scaled by the two block exponents, accumulated in FP32).  Because a block of the lowered
+ * matrix is a block of the image, the result equals hbfp_gemm_select(HBFP_KERNEL_INT8) on hbfp_encode_im2col's operand bit for bit (with
  * round to nearest; stochastic rounding draws by position in the image here, by position in the lowered matrix there).
  * The data gradient of a stride-1 convolution is the same call on the output gradient (as the image, with padding
  * r - 1 - pad) and the mirrored filter with its channel axes exchanged; hbfp_gemm_conv2d_dgrad does that for any stride.
@@ -293,8 +293,8 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
  *                             ox*stride_w - pad_w + fs = ix of dy[img][oy][ox][f] * w[fr][fs][ch][f],
  * which is a stride-1 convolution, with padding (r - 1 - pad_h, s - 1 - pad_w), of dy with stride - 1 rows and columns of
  * zeros put between its pixels, against the filter mirrored in both window axes with its channel axes exchanged.  The
- * zeros are never stored: the product kernel gathers each tap from dy as converted once ([n*ho*wo][filters], blocks of 32
- * filters) and reads a page of zeros for the positions in between; all h x w input positions are computed, also those
+ * zeros are never stored: the product kernel gathers each tap from dy as converted once ([n*ho*wo][filters], blocks along
+ * the filters) and reads a page of zeros for the positions in between; all h x w input positions are computed, also those
  * that only part of a window reaches.  Both factors count as their BFP values and the sum is taken as Eq. (2) takes it.
  * With stride 1 this is hbfp_gemm_conv2d on dy with that padding.
  *   dy       encoded [n*ho*wo][filters] (ho, wo: the output extents of conv), contraction axis 1, in any of the formats
@@ -307,8 +307,8 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
  *   dX       device FP32 [n*h*w][ldx], ldx >= c; beta 0 or 1
  *   workspace  hbfp_gemm_conv2d_dgrad_workspace bytes, 256-byte aligned
  * With blocks of 32 filters, a multiple of 64 filters and c_block 0, where the window is at least as large as the stride
- * in both directions (and stride_h * stride_w <= 16), the zeros are not multiplied either: the input positions fall into stride_h * stride_w phases (iy mod stride_h, ix mod stride_w), a
- * phase meets only every stride-th filter tap and reads dy without gaps, and one launch walks all phases, each storing
+ * in both directions (and stride_h * stride_w <= 16), the zeros are not multiplied either: the input positions fall
+ * into stride_h * stride_w phases (iy mod stride_h, ix mod stride_w), a phase meets only every stride-th filter tap and reads dy without gaps, and one launch walks all phases, each storing
  * to the rows of its input positions.  The taps that do contribute are accumulated in the same order both ways, so the
  * result is bit for bit that of hbfp_gemm_conv2d on a dy whose zeros are stored.  Otherwise (a window smaller than the
  * stride, the other formats) every tap of the spread-out dy is multiplied, zeros included: stride_h * stride_w times the
