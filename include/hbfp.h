@@ -285,6 +285,26 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
                      void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * hbfp_gemm_conv2d_bfp: hbfp_gemm_conv2d whose result arrives as an encoded operand (Sec. 5.3: an FP-to-BFP unit converts
+ * what the MatMul unit produces for the next product; an activation unit sits in between): out = encode(relu ? max(Y, 0) : Y)
+ * with Y the convolution of hbfp_gemm_conv2d, as hbfp_gemm_bfp does it for a matrix product.  With `out` planned as the
+ * next layer's image - [n*ho*wo][filters], contraction axis 1, blocks of 32 filters, at most 8 bits, round to nearest or
+ * stochastic (drawn by the position in Y) - and a product that is not split along k, the product kernel converts its own
+ * accumulators (the tile passes through LDS to bring the 32 filters of a block side by side): the FP32 result, four
+ * times the bytes, is neither written nor read back, and the next layer needs no conversion call.  Any other output
+ * format: the FP32 product in the workspace, then the conversion kernels.  Either way the bytes are those of
+ * hbfp_encode on the FP32 result of hbfp_gemm_conv2d.
+ *   out    planned and allocated by the caller (hbfp_plan: rows n*ho*wo, columns filters)
+ *   relu   0 or 1
+ *   workspace  hbfp_gemm_conv2d_bfp_workspace bytes, 256-byte aligned
+ * Errors: as hbfp_gemm_conv2d; HBFP_ERR_LAYOUT if `out` has another shape.
+ */
+int hbfp_gemm_conv2d_bfp_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, const hbfp_tensor *out,
+                                   size_t *bytes);
+int hbfp_gemm_conv2d_bfp(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, const hbfp_tensor *out, int relu,
+                         void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * hbfp_gemm_conv2d_dgrad: the data gradient of a convolution of any stride, executed like the forward pass (Sec. 5.1
  * treats the backward pass of a convolution as it treats the forward pass: as a BFP matrix product).  With
  *     y[img][oy][ox][f] = sum over (fr, fs, ch) of x[img][oy*stride_h - pad_h + fr][ox*stride_w - pad_w + fs][ch] * w[fr][fs][ch][f]

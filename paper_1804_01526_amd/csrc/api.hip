@@ -542,6 +542,14 @@ static int conv_gemm_check(const hbfp_tensor *image, const hbfp_conv2d *conv, co
     return HBFP_OK;
 }
 
+// whether both operands of a convolution repeat their exponents over the r * s taps of a channel block (one exponent per
+// training input against filter tiles over the whole window, window entries channel block by channel block): the
+// product then scales each such run once (Sec. 4: the larger the tile, the fewer FP operations per fixed-point one)
+static bool conv_runs(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, int slot_order) {
+    const int64_t taps = (int64_t)conv->r * conv->s;
+    return slot_order == 1 && taps > 1 && image->rblock == conv->h * conv->w && (filters->kshare >= filters->nblk || filters->kshare % taps == 0);
+}
+
 int hbfp_gemm_conv2d_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, size_t *bytes) {
     if (!bytes) return HBFP_ERR_ARG;
     int64_t ho = 0, wo = 0;
@@ -563,14 +571,63 @@ int hbfp_gemm_conv2d(const hbfp_tensor *image, const hbfp_conv2d *conv, const hb
     hbfp_gemm_conv2d_workspace(image, conv, filters, &need);
     if (!workspace || ws_bytes < need || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
     const GemmArgs g = conv_product_args(image, filters, conv->n * ho * wo, Y, ldy, beta);
-    // One exponent per training input (and stored block) against filter tiles over the whole window, window entries
-    // channel block by channel block: both operands repeat their exponents over the r * s taps of a channel block, and
-    // the product scales each such run once (Sec. 4: the larger the tile, the fewer FP operations per fixed-point one).
-    const int64_t taps = (int64_t)conv->r * conv->s;
-    const bool runs = slot_order == 1 && taps > 1 && image->rblock == conv->h * conv->w &&
-                      (filters->kshare >= filters->nblk || filters->kshare % taps == 0);
     return launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, workspace, (hipStream_t)stream, 1, 1, false, slot_order, (int)image->kblock,
-                               runs ? (int)taps : 0);
+                               conv_runs(image, conv, filters, slot_order) ? conv->r * conv->s : 0);
+}
+
+// hbfp_gemm_conv2d_bfp: [FP32 product, unless the kernel converts its accumulators][workspace of the convolution]
+// [scratch of the conversion]
+static int conv_bfp_plan(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, const hbfp_tensor *out, bool need_ptrs,
+                         int64_t *ho, int64_t *wo, int *slot_order, bool *fused, size_t (&part)[3]) {
+    int rc = conv_gemm_check(image, conv, filters, need_ptrs, ho, wo, slot_order);
+    if (rc == HBFP_OK) rc = check_tensor(out, need_ptrs);
+    if (rc != HBFP_OK) return rc;
+    const int64_t M = conv->n * *ho * *wo, N = filters->rows;
+    if (out->src_rows != M || out->src_cols != N) return HBFP_ERR_LAYOUT;
+    *fused = conv_encoded_output_ok(M, N, filters->kpad, *out) && !conv_runs(image, conv, filters, *slot_order);
+    part[0] = *fused ? 0 : align256((size_t)M * (size_t)N * 4);
+    part[1] = align256(gemm_conv_workspace(M, N, filters->kpad, image->rows, (int)(conv->c / image->kblock)));
+    size_t enc = 0;
+    if (!*fused) hbfp_encode_workspace(out, &enc);
+    part[2] = enc;
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d_bfp_workspace(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, const hbfp_tensor *out,
+                                   size_t *bytes) {
+    if (!bytes) return HBFP_ERR_ARG;
+    int64_t ho = 0, wo = 0;
+    int slot_order = -1;
+    bool fused = false;
+    size_t part[3];
+    const int rc = conv_bfp_plan(image, conv, filters, out, false, &ho, &wo, &slot_order, &fused, part);
+    if (rc != HBFP_OK) return rc;
+    *bytes = part[0] + part[1] + part[2];
+    return HBFP_OK;
+}
+
+int hbfp_gemm_conv2d_bfp(const hbfp_tensor *image, const hbfp_conv2d *conv, const hbfp_tensor *filters, const hbfp_tensor *out, int relu,
+                         void *workspace, size_t ws_bytes, void *stream) {
+    int64_t ho = 0, wo = 0;
+    int slot_order = -1;
+    bool fused = false;
+    size_t part[3];
+    int rc = conv_bfp_plan(image, conv, filters, out, true, &ho, &wo, &slot_order, &fused, part);
+    if (rc != HBFP_OK) return rc;
+    if (relu != 0 && relu != 1) return HBFP_ERR_ARG;
+    if (!workspace || ws_bytes < part[0] + part[1] + part[2] || ((uintptr_t)workspace & 255)) return HBFP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t M = conv->n * ho * wo, N = filters->rows;
+    float *C = (float *)workspace;
+    char *ws_conv = (char *)workspace + part[0], *ws_enc = ws_conv + part[1];
+    const GemmArgs g = conv_product_args(image, filters, M, fused ? nullptr : C, N, 0.0f);
+    const int chain = conv_runs(image, conv, filters, slot_order) ? conv->r * conv->s : 0;
+    rc = launch_gemm_conv_i8(g, *conv, ho, wo, image->kpad, ws_conv, s, 1, 1, false, slot_order, (int)image->kblock, chain,
+                             fused ? out : nullptr, relu);
+    if (rc != HBFP_OK || fused) return rc;
+    if (relu) rc = launch_relu(C, M * N, s);
+    if (rc != HBFP_OK) return rc;
+    return encode_planned(C, N, out, part[2] != 0, ws_enc, s);
 }
 
 // The data gradient of a convolution of any stride: a stride-1 convolution of the zero-dilated output gradient with

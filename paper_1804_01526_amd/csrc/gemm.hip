@@ -21,6 +21,7 @@
 //   2. one subtraction removes the constant (exact), one FMA multiplies by the column
 //      scale 2^(Eb - 127) and accumulates.
 // The remaining constant 2^(27 - mA - mB) is applied once when C is stored.
+#include "bfp_device.h"
 #include "gemm_common.h"
 
 namespace hbfp {
@@ -363,12 +364,22 @@ struct ConvPhases {
 // floor(i / d) for a coordinate i of the dilated image (may be negative), inv = 1 / d rounded
 __device__ __forceinline__ int conv_undilate(int i, float inv) { return (int)__builtin_floorf(((float)i + 0.5f) * inv); }
 
+// ENC: the product leaves the kernel as an encoded operand (the FP->BFP conversion of Sec. 4.1 / Sec. 5.3 applied to the
+// accumulators): rows of C, blocks of 32 along its columns - for a convolution, the next layer's image.
+struct W8Enc {
+    uint8_t *mant, *exps;
+    int64_t kpad, exp_ld;
+    int32_t nblk, m, rounding, relu;
+    uint32_t s0, s1;
+};
+
 struct W8Params {
     GemmParams g;
     const uint32_t *wA, *wB;     // scale words [kpad / 32][rows_pad]
     int64_t mpad, npad;
     ConvA cv;                    // CONV only
     ConvPhases ph;               // PHASE only
+    W8Enc enc;                   // ENC only
 };
 
 // The same kernel multiplies 9..12-bit mantissas stored as FP16 numbers (F16): an 11-bit magnitude is an FP16
@@ -404,6 +415,70 @@ struct W8Ops<true> {
     static __device__ __forceinline__ void pin(const acc_t &d0, const acc_t &d1) { asm volatile("" ::"v"(d0), "v"(d1)); }
 };
 
+// ENC epilogue.  The accumulators hold a column per lane and rows across registers, the conversion wants the 32 columns
+// of a block side by side: the tile goes through LDS (the ring is free by then) as [128 rows][132 floats], and each of the
+// 512 threads converts one row's block of 32 - largest magnitude, shared exponent, rounding with the index of the
+// element in C, 32 mantissas in two 16-byte stores, one exponent byte - with the arithmetic of the conversion kernels,
+// so the result is what converting the FP32 product would give.  A wave that computed nothing writes nothing (its columns
+// lie past N and count as zeros) but keeps both barriers.
+constexpr int kEncStride = 132;
+template <int ROUND>
+__device__ __forceinline__ void w8_encode_block(const W8Enc &o, const float *row, int64_t grow, int64_t gcol0, int64_t N) {
+    float x[32];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float4 d = *reinterpret_cast<const float4 *>(row + 4 * j);
+        x[4 * j] = d.x, x[4 * j + 1] = d.y, x[4 * j + 2] = d.z, x[4 * j + 3] = d.w;
+    }
+    uint32_t amax = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        if (gcol0 + j >= N) x[j] = 0.0f;
+        amax = max(amax, __float_as_uint(x[j]) & 0x7fffffffu);
+    }
+    const uint32_t Eb = block_exponent<ROUND>(amax, o.m);
+    uint32_t w[8];
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        int qv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint64_t idx = (uint64_t)grow * (uint64_t)N + (uint64_t)(gcol0 + 4 * g + e);
+            qv[e] = quantise<ROUND>(x[4 * g + e], Eb, o.m, (uint32_t)idx, (uint32_t)(idx >> 32), o.s0, o.s1);
+        }
+        w[g] = (uint32_t)(qv[0] & 0xff) | ((uint32_t)(qv[1] & 0xff) << 8) | ((uint32_t)(qv[2] & 0xff) << 16) | ((uint32_t)qv[3] << 24);
+    }
+    uint4 *dst = reinterpret_cast<uint4 *>(o.mant + grow * o.kpad + gcol0);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    const int64_t b = gcol0 >> 5;
+    if (b < o.exp_ld) o.exps[grow * o.exp_ld + b] = b < o.nblk ? (uint8_t)Eb : (uint8_t)1;
+}
+
+// first half, for a wave that computed: its 32 x 64 results into the tile
+__device__ __forceinline__ void w8_tile_to_lds(const W8Enc &o, uint8_t *lds, const float (&acc)[2][16], float final_scale, int wm, int wn,
+                                               int l32, int lh) {
+    float *tile = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float val = acc[ni][v] * final_scale;
+            if (o.relu && val < 0.0f) val = 0.0f;
+            tile[(wm * 32 + 8 * (v >> 2) + 4 * lh + (v & 3)) * kEncStride + wn * 64 + ni * 32 + l32] = val;
+        }
+}
+// second half, for every thread: one row's block of 32
+__device__ __forceinline__ void w8_encode_from_lds(const W8Enc &o, const uint8_t *lds, int64_t row0, int64_t col0, int64_t M, int64_t N) {
+    const float *tile = reinterpret_cast<const float *>(lds);
+    const int r = threadIdx.x >> 2, qb = threadIdx.x & 3;
+    const int64_t grow = row0 + r, gcol0 = col0 + qb * 32;
+    if (grow < M && gcol0 < o.kpad) {
+        if (o.rounding) w8_encode_block<1>(o, tile + r * kEncStride + qb * 32, grow, gcol0, N);
+        else w8_encode_block<0>(o, tile + r * kEncStride + qb * 32, grow, gcol0, N);
+    }
+}
+
 // SPB: k-steps of 32 per exponent block: 1, 2, or 0 = a multiple of 4 (a block is spb / 2 whole stages).  A block
 // that spans several k-steps chains its matrix instructions through the C input and is scaled at its last
 // k-step, and, when it is longer than 256 elements, after every 256 (four stages) with the same scales: the
@@ -414,7 +489,7 @@ struct W8Ops<true> {
 // (an image with one exponent per training input against filter tiles that span the whole window, Sec. 5.1): the scale
 // words are staged per k-step as for SPB = 1, but a run is chained like a long block and scaled once, at its last
 // k-step, after p.chain_limit k-steps (the range in which the row constant trick is exact) and at the end of the k range.
-template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0>
+template <int SPB, bool CONV = false, bool F16 = false, int GATHER = 0, bool ENC = false>
 __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Params q) {
     constexpr bool STEPW = SPB == 1 || SPB == 3;     // scale words per k-step
     constexpr bool CHAIN = SPB == 0 || SPB == 3;     // the matrix instructions of a block (run) chain through their C input
@@ -752,6 +827,11 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
                 if (rem >= 4) { HBFP_COPY_NEXT(ring); HBFP_COPY_NEXT(ring + 1); }
             }
         }
+        if (ENC) {
+            __syncthreads();                                 // as below, without results of its own
+            __syncthreads();
+            w8_encode_from_lds(q.enc, lds, row0, col0, M, p.N);
+        }
         return;
     }
     if (nst > 0) {
@@ -785,6 +865,13 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 #undef HBFP_NEXT_SLOT
 #undef HBFP_WAIT_COPIES
 
+    if (ENC) {
+        __syncthreads();                                     // every wave has read the last stage of the ring
+        w8_tile_to_lds(q.enc, lds, acc, p.final_scale, wm, wn, l32, lh);
+        __syncthreads();
+        w8_encode_from_lds(q.enc, lds, row0, col0, M, p.N);
+        return;
+    }
     if (PHASE) {
         // a row of the phase goes to the row of its input position; the 16 rows of a lane are 4 runs of 4
 #pragma unroll
@@ -918,6 +1005,12 @@ __global__ __launch_bounds__(256) void conv_words_kernel(const uint8_t *eimg, in
 }
 }  // namespace
 
+// whether the gathering kernel can deliver this product as the encoded operand `out` (no split along k)
+bool conv_encoded_output_ok(int64_t M, int64_t N, int64_t kpad, const hbfp_tensor &out) {
+    return out.contract_axis == 1 && out.kblock == 32 && out.kblock_pad == 32 && out.rblock == 1 && out.kshare == 1 && out.mant_bits <= 8 &&
+           out.rows == M && out.kdim == N && choose_splits(M, N, kpad / BK, 1) == 1;
+}
+
 size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, int cblocks) {
     const int splits = choose_splits(M, N, kpad / BK, 1);
     return split_bytes(M, N, splits) + (size_t)cblocks * (size_t)(ceil_div(pixels, 128) * 128) * 4 + word_bytes(N, kpad / 32) + 256;
@@ -937,8 +1030,11 @@ bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w) {
 // general gather from an image stored in blocks of kblock channels (c.c a multiple of it), k tap by tap (0) or channel
 // block by channel block (1); it combines with the dilation, not with the phases.  chain > 1 (slot_order 1, no dilation):
 // both operands repeat their exponents over runs of `chain` consecutive stored blocks, which are then scaled once.
+// enc: the product leaves as this encoded operand (rows of C, blocks of 32 along its columns, at most 8 bits; the caller
+// has checked conv_encoded_output_ok), with ReLU first if asked for; a.C is then unused.
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
-                        hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock, int chain) {
+                        hipStream_t s, int dil_h, int dil_w, bool by_phase, int slot_order, int kblock, int chain, const hbfp_tensor *enc,
+                        int relu) {
     GemmParams p = {};
     p.A = (const uint8_t *)a.mantA;
     p.B = (const uint8_t *)a.mantB;
@@ -1048,7 +1144,28 @@ int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int
     }
     const dim3 grid = p.splits >= 8 ? dim3((unsigned)(8 * tm * tn * ceil_div(p.splits, 8)))
                                     : dim3((unsigned)(ceil_div(tm * tn, 8) * 8), (unsigned)p.splits);
-    // the sum of a chain must stay below 2^22 for the row constants to come off exactly
+    if (enc) {
+        if (dilated || p.splits != 1 || p.beta) return HBFP_ERR_ARG;
+        q.enc.mant = (uint8_t *)enc->mant;
+        q.enc.exps = enc->exps;
+        q.enc.kpad = enc->kpad;
+        q.enc.exp_ld = enc->exp_ld;
+        q.enc.nblk = (int32_t)enc->nblk;
+        q.enc.m = enc->mant_bits;
+        q.enc.rounding = enc->rounding;
+        q.enc.relu = relu;
+        q.enc.s0 = (uint32_t)enc->seed;
+        q.enc.s1 = (uint32_t)(enc->seed >> 32);
+        // (the variant that scales runs of blocks once has no registers left for this epilogue: the caller converts behind it)
+        if (chain > 1) return HBFP_ERR_ARG;
+        static std::atomic<bool> c0{false}, c1{false};
+        if (allow_dynamic_lds(c0, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 0, true>), kW8LdsBytes) != HBFP_OK ||
+            allow_dynamic_lds(c1, reinterpret_cast<const void *>(&gemm_i8_w8_kernel<1, true, false, 3, true>), kW8LdsBytes) != HBFP_OK)
+            return HBFP_ERR_LAUNCH;
+        if (slots) hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 3, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+        else hipLaunchKernelGGL((gemm_i8_w8_kernel<1, true, false, 0, true>), grid, dim3(kW8Threads), kW8LdsBytes, s, q);
+        return launch_status();
+    }
     const int64_t chain_limit = (((int64_t)1 << 22) - 1) / ((int64_t)kblock * (((int64_t)1 << (a.mA - 1)) - 1) * (((int64_t)1 << (a.mB - 1)) - 1));
     if (slots && !dilated && slot_order == 1 && chain > 1 && chain_limit > 1) {
         static std::atomic<bool> configured_chain{false};

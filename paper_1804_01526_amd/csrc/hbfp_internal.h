@@ -91,7 +91,8 @@ size_t gemm_i8_workspace(int64_t M, int64_t N, int64_t kpad, int64_t kbp, int64_
 size_t gemm_conv_workspace(int64_t M, int64_t N, int64_t kpad, int64_t pixels, int cblocks);
 int launch_gemm_conv_i8(const GemmArgs &a, const hbfp_conv2d &c, int64_t ho, int64_t wo, int64_t pix_bytes, void *workspace,
                         hipStream_t s, int dil_h = 1, int dil_w = 1, bool by_phase = false, int slot_order = -1,
-                        int kblock = 32, int chain = 0);
+                        int kblock = 32, int chain = 0, const hbfp_tensor *enc = nullptr, int relu = 0);
+bool conv_encoded_output_ok(int64_t M, int64_t N, int64_t kpad, const hbfp_tensor &out);
 bool conv_dgrad_by_phase(int r, int s, int stride_h, int stride_w);
 // 9..12-bit mantissas as FP16 numbers on the FP16 matrix instruction (blocks of 32, 64 or multiples of 128)
 bool gemm_f16_possible(const GemmArgs &a);

@@ -90,6 +90,10 @@ def _load():
     lib.hbfp_gemm_conv2d_workspace.restype = i32
     lib.hbfp_gemm_conv2d.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
     lib.hbfp_gemm_conv2d.restype = i32
+    lib.hbfp_gemm_conv2d_bfp_workspace.argtypes = [T, ctypes.POINTER(Conv2d), T, T, ctypes.POINTER(sz)]
+    lib.hbfp_gemm_conv2d_bfp_workspace.restype = i32
+    lib.hbfp_gemm_conv2d_bfp.argtypes = [T, ctypes.POINTER(Conv2d), T, T, i32, vp, sz, vp]
+    lib.hbfp_gemm_conv2d_bfp.restype = i32
     lib.hbfp_gemm_conv2d_dgrad_workspace.argtypes = [T, ctypes.POINTER(Conv2d), T, ctypes.POINTER(sz)]
     lib.hbfp_gemm_conv2d_dgrad_workspace.restype = i32
     lib.hbfp_gemm_conv2d_dgrad.argtypes = [T, ctypes.POINTER(Conv2d), T, vp, i64, ctypes.c_float, vp, sz, vp]
@@ -578,6 +582,27 @@ def gemm_conv2d(image: BfpTensor, conv: Conv2d, filters: BfpTensor, out: Optiona
     _check(_lib.hbfp_gemm_conv2d(ctypes.byref(image.desc), ctypes.byref(conv), ctypes.byref(filters.desc), _dev_ptr(out),
                                  out.stride(0), beta, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
                                  _stream_ptr(stream)), "hbfp_gemm_conv2d")
+    return out
+
+
+def gemm_conv2d_bfp_workspace(image: TensorDesc, conv: Conv2d, filters: TensorDesc, out: TensorDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.hbfp_gemm_conv2d_bfp_workspace(ctypes.byref(image), ctypes.byref(conv), ctypes.byref(filters), ctypes.byref(out),
+                                               ctypes.byref(n)), "hbfp_gemm_conv2d_bfp_workspace")
+    return int(n.value)
+
+
+def gemm_conv2d_bfp(image: BfpTensor, conv: Conv2d, filters: BfpTensor, fmt: Format, relu: bool = False, out: Optional[BfpTensor] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> BfpTensor:
+    """hbfp_gemm_conv2d_bfp: the convolution delivered as an encoded operand [n*ho*wo, filters] (contraction along the
+    filters): the next layer's image."""
+    ho, wo = conv.out_hw()
+    if out is None:
+        out = alloc(fmt, conv.n * ho * wo, filters.desc.rows, 1, image.mant.device)
+    workspace = _workspace(gemm_conv2d_bfp_workspace(image.desc, conv, filters.desc, out.desc), image.mant.device, workspace)
+    _check(_lib.hbfp_gemm_conv2d_bfp(ctypes.byref(image.desc), ctypes.byref(conv), ctypes.byref(filters.desc), ctypes.byref(out.desc),
+                                     1 if relu else 0, _dev_ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                     _stream_ptr(stream)), "hbfp_gemm_conv2d_bfp")
     return out
 
 

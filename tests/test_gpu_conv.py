@@ -209,6 +209,66 @@ def test_conv_general_gather_random(hb):
         _slot_case(hb, *geom, seed=seed)
 
 
+def _conv_bfp_case(hb, n, h, w, c, f, r, s, pad, st, kb, by_block, per_image, tiles, out_fmt, relu, seed):
+    """hbfp_gemm_conv2d_bfp against the oracle's conversion of the library's own FP32 convolution (bit for bit: the same
+    product, converted in the kernel or behind it), whose parity with the oracle the tests above establish."""
+    from tests.util import unpack
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((n, h, w, c)) * np.exp2(rng.integers(-3, 4, size=(n, 1, 1, 1)))).astype(np.float32)
+    w4 = (rng.standard_normal((r, s, c, f)) * 0.1).astype(np.float32)
+    cb = kb if by_block else 0
+    wmat = np.ascontiguousarray(ref.filter_matrix(w4, cb))
+    conv = hb.Conv2d(n, h, w, c, r, s, pad, pad, st, st, cb, 0)
+    ho, wo = conv.out_hw()
+    f_img = hb.make_format(8, h * w, 0, k_slot=kb) if per_image else hb.make_format(8, 1, kb)
+    f_flt = (hb.make_format(8, r * s * kb, 24, k_slot=kb) if by_block else hb.make_format(8, kb, kb)) if tiles else hb.make_format(8, kb, 1)
+    img = hb.encode(torch.from_numpy(x.reshape(n * h * w, c)).cuda(), 1, f_img)
+    flt = hb.encode(torch.from_numpy(wmat).cuda(), 0, f_flt)
+    print(f"[conv bfp] n={n} h={h} w={w} c={c} f={f} r={r} s={s} pad={pad} stride={st} blocks of {kb} by_block={by_block} "
+          f"per_image={per_image} tiles={tiles} out={out_fmt} relu={relu}", flush=True)
+    m, br, bc, rounding, sd = out_fmt
+    out = hb.gemm_conv2d_bfp(img, conv, flt, hb.make_format(m, br, bc, rounding, sd), relu=relu)
+    y = hb.gemm_conv2d(img, conv, flt)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    if relu:
+        y = np.maximum(y, 0.0)
+    want = ref.encode(y, br, bc, m, rounding, sd)
+    mant, exps = unpack(out)
+    np.testing.assert_array_equal(exps, want.exps)
+    np.testing.assert_array_equal(mant, want.mant)
+    assert np.abs(mant).max() > 0
+
+
+@pytest.mark.parametrize("case", [
+    # n, h, w, c, f, r, s, pad, stride, block, by block, per image, tiles, (m, block rows, block cols, rounding, seed), relu
+    (2, 12, 13, 64, 40, 3, 3, 1, 1, 32, False, False, False, (8, 1, 32, 0, 0), True),       # 64 channels per stage; 40 filters: a ragged block
+    (3, 9, 9, 128, 130, 3, 3, 1, 1, 32, False, False, False, (8, 1, 32, 1, 77), False),      # stochastic rounding, two column tiles
+    (2, 15, 16, 128, 64, 3, 3, 1, 2, 32, False, False, False, (6, 1, 32, 0, 0), True),       # strided, 6-bit output
+    (3, 9, 9, 48, 50, 3, 3, 1, 1, 24, True, True, True, (8, 1, 32, 0, 0), True),             # Sec. 5.1's pairing, runs scaled once
+    (2, 10, 8, 72, 96, 3, 3, 1, 1, 24, False, False, False, (8, 1, 32, 1, 5), True),         # slot by slot
+    (2, 12, 13, 64, 40, 3, 3, 1, 1, 32, False, False, False, (8, 1, 24, 0, 0), True),        # blocks of 24: converted behind the product
+    (2, 12, 13, 64, 40, 3, 3, 1, 1, 32, False, False, False, (12, 1, 32, 0, 0), False),      # 12 bits: behind the product
+    (1, 6, 6, 1024, 100, 3, 3, 1, 1, 32, False, False, False, (8, 1, 32, 0, 0), True),       # split along k: behind the product
+    (2, 12, 12, 24, 40, 2, 2, 0, 2, 24, True, True, True, (8, 144 // 4, 0, 0, 0), False),    # one exponent per training input out: behind
+])
+def test_conv_delivered_as_an_encoded_operand(hb, case):
+    _conv_bfp_case(hb, *case, seed=sum(int(v) for v in case[:9]))
+
+
+def test_conv_delivered_as_an_encoded_operand_random(hb):
+    for seed in random_cases(10):
+        rng = np.random.default_rng(9800 + seed)
+        r, s = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        h, w = int(rng.integers(max(r, s), 14)), int(rng.integers(max(r, s), 14))
+        kb = int(rng.choice([8, 16, 24, 32]))
+        by_block = bool(rng.integers(0, 2))
+        per_image = bool(rng.integers(0, 2))
+        _conv_bfp_case(hb, int(rng.integers(1, 4)), h, w, kb * int(rng.integers(1, 6)), int(rng.integers(1, 200)), r, s,
+                       int(rng.integers(0, min(r, s))), int(rng.integers(1, 3)), kb, by_block, per_image, by_block and per_image,
+                       (int(rng.integers(4, 9)), 1, 32, int(rng.integers(0, 2)), seed), bool(rng.integers(0, 2)), seed)
+
+
 def test_conv_data_gradient_of_a_stride_one_convolution_in_the_format_of_the_experiments(hb):
     """Stride 1: the data gradient is hbfp_gemm_conv2d itself on dY (padding r - 1 - pad) in any format the gather takes;
     here dY with one exponent per training input in blocks of 24 filters, the mirrored filter in tiles over the whole
