@@ -456,8 +456,10 @@ __device__ __forceinline__ void w8_encode_block(const W8Enc &o, const float *row
 }
 
 // first half, for a wave that computed: its 32 x 64 results into the tile
-__device__ __forceinline__ void w8_tile_to_lds(const W8Enc &o, uint8_t *lds, const float (&acc)[2][16], float final_scale, int wm, int wn,
-                                               int l32, int lh) {
+__device__ __forceinline__ void w8_tile_to_lds(const W8Enc &o, uint8_t *lds, const float (&acc)[2][16], float final_scale) {
+    // (its place in the tile recomputed from the thread index: the kernels that call this have no register to keep it in)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave & 3, wn = wave >> 2, l32 = lane & 31, lh = lane >> 5;
     float *tile = reinterpret_cast<float *>(lds);
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
@@ -867,7 +869,7 @@ __global__ __launch_bounds__(kW8Threads, 4) void gemm_i8_w8_kernel(const W8Param
 
     if (ENC) {
         __syncthreads();                                     // every wave has read the last stage of the ring
-        w8_tile_to_lds(q.enc, lds, acc, p.final_scale, wm, wn, l32, lh);
+        w8_tile_to_lds(q.enc, lds, acc, p.final_scale);
         __syncthreads();
         w8_encode_from_lds(q.enc, lds, row0, col0, M, p.N);
         return;
